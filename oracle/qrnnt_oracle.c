@@ -1,0 +1,698 @@
+/*
+ * qrnnt_oracle.c -- TEST INFRASTRUCTURE ONLY.
+ *
+ * A plain, slow, single-pass CPU statement of what the INT4 RNN-T hot path
+ * computes (arXiv 2206.07882: Sec. 3.1 quantizers, Sec. 3.2 placement of the
+ * quantizers, Sec. 3.4 "Outer" quantization, Sec. 2 network and Eq. 1 fusion).
+ * It exists so that the GPU library can be checked against something that was
+ * written from the paper and not from the GPU code.  Nothing in the product
+ * path may call it; it shares no source, header, table or helper with the HIP
+ * library.
+ *
+ * Arithmetic conventions (each is a reading of the paper, which prints no
+ * bit-level definition):
+ *   - symmetric b=4 grid: signed codes in [-8,7], step s = alpha/7 (Sec. 3.1,
+ *     symmetric LQ has one boundary alpha and no zero point);
+ *   - the rounding operator of Eq. 2 is round-half-to-even;
+ *   - a value is quantized as clamp(rne(x * inv_s)) with the product taken in
+ *     fp32, because that product decides an integer and the GPU path takes the
+ *     same decision in fp32;
+ *   - every other floating-point quantity (gate pre-activations, sigmoid,
+ *     tanh, log-softmax, Eq. 1) is evaluated in fp64 and rounded to fp32 only
+ *     where the method stores fp32 (cell state, projections, scores);
+ *   - LSTM: gate rows ordered i,f,g,o; one fp32 bias per gate row; weights and
+ *     activations integer, bias and cell state not quantized (Sec. 3.2).
+ *
+ * Parity status of each function is stated next to it: "pinned by" names the
+ * independent check in tests/test_oracle_pins.py.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+#define OQ_MAX_LAYERS 4
+
+/* Counters of activation-quantizer invocations (one per tensor handed to the
+ * quantizer), for the Outer-vs-Inner call-count check of Sec. 3.4. */
+static long g_quant_tensor_calls = 0;
+long oq_quant_calls_get(void) { return g_quant_tensor_calls; }
+void oq_quant_calls_reset(void) { g_quant_tensor_calls = 0; }
+
+/* ------------------------------------------------------------------ */
+/* Sec. 3.1: linear quantizers                                         */
+/* ------------------------------------------------------------------ */
+
+/* Symmetric 4-bit code of one value.  Pinned by: clip range, Q(deq(q))=q on
+ * all 16 codes, Q(0)=0, residual <= s/2 in range, monotonicity. */
+int8_t oq_quant_sym4(float x, float inv_s)
+{
+    float t = x * inv_s;
+    float r = nearbyintf(t); /* default rounding mode: ties to even */
+    if (r < -8.0f) r = -8.0f;
+    if (r > 7.0f) r = 7.0f;
+    return (int8_t)r;
+}
+
+void oq_quantize_sym4(const float *x, int64_t n, float inv_s, int8_t *q)
+{
+    g_quant_tensor_calls += 1;
+    for (int64_t i = 0; i < n; ++i) q[i] = oq_quant_sym4(x[i], inv_s);
+}
+
+/* Asymmetric LQ, Eq. 2 and Eq. 3, for b bits and boundaries alpha_-/alpha_+.
+ * Not on the integer path (weights are symmetric and every activation range
+ * used is +-alpha); carried as a utility.  Pinned by: alpha_- maps to 0,
+ * alpha_+ to 2^b-1, residual <= s/2 inside the range. */
+void oq_quantize_asym(const float *x, int64_t n, int bits, double a_lo, double a_hi,
+                      int32_t *x_int, double *x_q)
+{
+    double levels = (double)((1 << bits) - 1);
+    double s = (a_hi - a_lo) / levels;
+    double z = -a_lo / s;
+    for (int64_t i = 0; i < n; ++i) {
+        double v = nearbyint((double)x[i] / s) + z;
+        if (v < 0.0) v = 0.0;
+        if (v > levels) v = levels;
+        if (x_int) x_int[i] = (int32_t)nearbyint(v);
+        if (x_q) x_q[i] = s * (v - z);
+    }
+}
+
+/* MAX range picker applied per output row, then the symmetric quantizer
+ * (Sec. 3.1 MAX; per-row granularity is the measured configuration's choice).
+ * scale[r] = alpha_r/7 and the code uses inv = 7/alpha_r, both fp32 divisions.
+ * An all-zero row gets scale 1 and codes 0.  Pinned by: |code| reaches 7 on
+ * the max-abs element, codes on a hand-made row. */
+void oq_quantize_weight_rows(const float *w, int rows, int cols, int8_t *codes, float *scale)
+{
+    for (int r = 0; r < rows; ++r) {
+        const float *wr = w + (int64_t)r * cols;
+        float alpha = 0.0f;
+        for (int k = 0; k < cols; ++k) {
+            float a = fabsf(wr[k]);
+            if (a > alpha) alpha = a;
+        }
+        if (alpha == 0.0f) {
+            scale[r] = 1.0f;
+            for (int k = 0; k < cols; ++k) codes[(int64_t)r * cols + k] = 0;
+            continue;
+        }
+        float s = alpha / 7.0f;
+        float inv = 7.0f / alpha;
+        scale[r] = s;
+        for (int k = 0; k < cols; ++k) codes[(int64_t)r * cols + k] = oq_quant_sym4(wr[k], inv);
+    }
+}
+
+/* Canonical nibble packing: byte j of row r holds element (r,2j) in bits 0-3
+ * and (r,2j+1) in bits 4-7, two's complement; columns >= cols up to
+ * cols_padded are zero.  Pinned by: hand-written bytes, unpack(pack)=id over
+ * all 256 byte values. */
+void oq_pack_rows(const int8_t *codes, int rows, int cols, int cols_padded, uint8_t *packed)
+{
+    int bpr = cols_padded / 2;
+    for (int r = 0; r < rows; ++r)
+        for (int j = 0; j < bpr; ++j) {
+            int k0 = 2 * j, k1 = 2 * j + 1;
+            int lo = k0 < cols ? codes[(int64_t)r * cols + k0] : 0;
+            int hi = k1 < cols ? codes[(int64_t)r * cols + k1] : 0;
+            packed[(int64_t)r * bpr + j] = (uint8_t)((lo & 0xF) | ((hi & 0xF) << 4));
+        }
+}
+
+void oq_unpack_rows(const uint8_t *packed, int rows, int cols, int cols_padded, int8_t *codes)
+{
+    int bpr = cols_padded / 2;
+    for (int r = 0; r < rows; ++r)
+        for (int k = 0; k < cols; ++k) {
+            uint8_t byte = packed[(int64_t)r * bpr + k / 2];
+            int nib = (k & 1) ? (byte >> 4) : (byte & 0xF);
+            codes[(int64_t)r * cols + k] = (int8_t)(nib >= 8 ? nib - 16 : nib);
+        }
+}
+
+/* ------------------------------------------------------------------ */
+/* Integer contraction (the MAC of Sec. 3.1/3.2)                        */
+/* ------------------------------------------------------------------ */
+
+/* acc[n,r] = sum_k w[r,k]*a[n,k], int32.  Pinned by: Python triple loop on
+ * tiny shapes, extreme-code closed forms, permutation of k. */
+void oq_matmul_i32(const int8_t *w, int rows, int K, const int8_t *a, int N, int32_t *acc)
+{
+#pragma omp parallel for schedule(static)
+    for (int n = 0; n < N; ++n) {
+        const int8_t *an = a + (int64_t)n * K;
+        for (int r = 0; r < rows; ++r) {
+            const int8_t *wr = w + (int64_t)r * K;
+            int32_t s = 0;
+            for (int k = 0; k < K; ++k) s += (int32_t)wr[k] * (int32_t)an[k];
+            acc[(int64_t)n * rows + r] = s;
+        }
+    }
+}
+
+/* ------------------------------------------------------------------ */
+/* Quantized LSTM cell (Sec. 3.2, Sec. 3.4)                             */
+/* ------------------------------------------------------------------ */
+
+typedef struct {
+    const int8_t *w_ih;   /* [4H, I] codes, gate rows i,f,g,o */
+    const int8_t *w_hh;   /* [4H, H] codes */
+    const float *s_wih;   /* [4H] row scales */
+    const float *s_whh;   /* [4H] */
+    const float *bias;    /* [4H] fp32, not quantized */
+    int32_t I, H;
+    float s_x;            /* step of the input codes  */
+    float s_h;            /* step of the hidden codes (FIX +-1: 1/7) */
+    float inv_s_h;        /* 7/alpha_h (FIX +-1: 7) */
+} oq_lstm_t;
+
+static double sigm(double v) { return 1.0 / (1.0 + exp(-v)); }
+
+/* One time step for N rows.  Row n reads its previous state from slot
+ * parent[n] (n itself when parent is NULL).  Rows with active[n]==0 copy the
+ * parent's state through unchanged.  The hidden state leaves the cell as a
+ * 4-bit code (one quantizer call per cell output: Outer quantization,
+ * Sec. 3.4); that code is what the next step and the next layer consume.
+ * Optional outputs: accx/acch int32 [N,4H], gates fp64 [N,4H] (activated
+ * i,f,g,o), h_real fp64 [N,H] (h before the quantizer).
+ * Pinned by: zero-weight closed form, |code|<=7, hand-rolled numpy cell on
+ * random small inputs, pass-through of inactive rows. */
+void oq_lstm_step(const oq_lstm_t *L, const int8_t *x, const int32_t *parent,
+                  const int8_t *h_prev, const float *c_prev, const uint8_t *active, int N,
+                  int8_t *h_next, float *c_next,
+                  int32_t *accx_out, int32_t *acch_out, double *gates_out, double *h_real_out)
+{
+    const int H = L->H, I = L->I, R = 4 * L->H;
+    g_quant_tensor_calls += 1; /* the one quantizer at the cell output */
+#pragma omp parallel for schedule(static)
+    for (int n = 0; n < N; ++n) {
+        int src = parent ? parent[n] : n;
+        const int8_t *hp = h_prev + (int64_t)src * H;
+        const float *cp = c_prev + (int64_t)src * H;
+        if (active && !active[n]) {
+            memcpy(h_next + (int64_t)n * H, hp, (size_t)H);
+            memcpy(c_next + (int64_t)n * H, cp, (size_t)H * sizeof(float));
+            continue;
+        }
+        const int8_t *xn = x + (int64_t)n * I;
+        double *pre = (double *)malloc(sizeof(double) * (size_t)R);
+        for (int r = 0; r < R; ++r) {
+            int32_t ax = 0, ah = 0;
+            const int8_t *wi = L->w_ih + (int64_t)r * I;
+            const int8_t *wh = L->w_hh + (int64_t)r * H;
+            for (int k = 0; k < I; ++k) ax += (int32_t)wi[k] * (int32_t)xn[k];
+            for (int k = 0; k < H; ++k) ah += (int32_t)wh[k] * (int32_t)hp[k];
+            if (accx_out) accx_out[(int64_t)n * R + r] = ax;
+            if (acch_out) acch_out[(int64_t)n * R + r] = ah;
+            pre[r] = (double)L->s_x * (double)L->s_wih[r] * (double)ax +
+                     (double)L->s_h * (double)L->s_whh[r] * (double)ah + (double)L->bias[r];
+        }
+        for (int j = 0; j < H; ++j) {
+            double gi = sigm(pre[j]);
+            double gf = sigm(pre[H + j]);
+            double gg = tanh(pre[2 * H + j]);
+            double go = sigm(pre[3 * H + j]);
+            double c = gf * (double)cp[j] + gi * gg;
+            double h = go * tanh(c);
+            c_next[(int64_t)n * H + j] = (float)c;
+            h_next[(int64_t)n * H + j] = oq_quant_sym4((float)h, L->inv_s_h);
+            if (gates_out) {
+                double *g = gates_out + (int64_t)n * R;
+                g[j] = gi; g[H + j] = gf; g[2 * H + j] = gg; g[3 * H + j] = go;
+            }
+            if (h_real_out) h_real_out[(int64_t)n * H + j] = h;
+        }
+        free(pre);
+    }
+}
+
+/* One layer-direction over a whole batch of equal-length utterances.
+ * x [T,B,I] codes; output codes written to h_out[t,b,col_off + j] with row
+ * pitch ld_out, so that a bidirectional layer is two calls that fill the two
+ * halves of [T,B,2H] (both directions share the FIX +-1 step, Sec. 3.2).
+ * reverse!=0 walks t = T-1..0.  h0/c0 NULL mean zero (Sec. 3.4 assumes a zero
+ * state before the first step).  c_all (optional) receives c_t for every t.
+ * Pinned by: reverse == time-flip of forward on flipped input; T=1 == step. */
+void oq_lstm_layer(const oq_lstm_t *L, const int8_t *x, int T, int B, int reverse,
+                   const int8_t *h0, const float *c0,
+                   int8_t *h_out, int ld_out, int col_off,
+                   int8_t *h_last, float *c_last, float *c_all)
+{
+    const int H = L->H, I = L->I;
+    int8_t *h = (int8_t *)calloc((size_t)B * H, 1), *hn = (int8_t *)calloc((size_t)B * H, 1);
+    float *c = (float *)calloc((size_t)B * H, sizeof(float)), *cn = (float *)calloc((size_t)B * H, sizeof(float));
+    if (h0) memcpy(h, h0, (size_t)B * H);
+    if (c0) memcpy(c, c0, (size_t)B * H * sizeof(float));
+    for (int s = 0; s < T; ++s) {
+        int t = reverse ? T - 1 - s : s;
+        oq_lstm_step(L, x + (int64_t)t * B * I, NULL, h, c, NULL, B, hn, cn, NULL, NULL, NULL, NULL);
+        for (int b = 0; b < B; ++b)
+            memcpy(h_out + ((int64_t)t * B + b) * ld_out + col_off, hn + (int64_t)b * H, (size_t)H);
+        if (c_all) memcpy(c_all + (int64_t)t * B * H, cn, (size_t)B * H * sizeof(float));
+        int8_t *th = h; h = hn; hn = th;
+        float *tc = c; c = cn; cn = tc;
+    }
+    if (h_last) memcpy(h_last, h, (size_t)B * H);
+    if (c_last) memcpy(c_last, c, (size_t)B * H * sizeof(float));
+    free(h); free(hn); free(c); free(cn);
+}
+
+/* ------------------------------------------------------------------ */
+/* Quantized linear layer, log-softmax, joint, fusion (Sec. 2, Eq. 1)   */
+/* ------------------------------------------------------------------ */
+
+typedef struct {
+    const int8_t *w;      /* [rows, cols] codes */
+    const float *s_w;     /* [rows] */
+    const float *bias;    /* [rows] or NULL */
+    int32_t rows, cols;
+    float s_a;            /* step of the input codes */
+} oq_linear_t;
+
+/* y[n,r] = s_a*s_w[r]*acc[n,r] + b[r], fp64, stored fp32.
+ * Pinned by: dequantize-then-float-matmul in numpy. */
+void oq_linear(const oq_linear_t *P, const int8_t *a, int N, float *y, int32_t *acc_out)
+{
+#pragma omp parallel for schedule(static)
+    for (int n = 0; n < N; ++n)
+        for (int r = 0; r < P->rows; ++r) {
+            int32_t s = 0;
+            const int8_t *wr = P->w + (int64_t)r * P->cols, *an = a + (int64_t)n * P->cols;
+            for (int k = 0; k < P->cols; ++k) s += (int32_t)wr[k] * (int32_t)an[k];
+            if (acc_out) acc_out[(int64_t)n * P->rows + r] = s;
+            double v = (double)P->s_a * (double)P->s_w[r] * (double)s + (P->bias ? (double)P->bias[r] : 0.0);
+            y[(int64_t)n * P->rows + r] = (float)v;
+        }
+}
+
+/* lp = x - max - log sum exp(x - max) over V entries, fp64.
+ * Pinned by: sum exp(lp) = 1, shift invariance, uniform input -> -log V. */
+static void log_softmax_d(const double *x, int V, double *lp)
+{
+    double m = x[0];
+    for (int k = 1; k < V; ++k) if (x[k] > m) m = x[k];
+    double s = 0.0;
+    for (int k = 0; k < V; ++k) s += exp(x[k] - m);
+    double ls = log(s);
+    for (int k = 0; k < V; ++k) lp[k] = x[k] - m - ls;
+}
+
+void oq_log_softmax(const float *x, int N, int V, float *lp)
+{
+    double *xd = (double *)malloc(sizeof(double) * 2 * (size_t)V);
+    for (int n = 0; n < N; ++n) {
+        for (int k = 0; k < V; ++k) xd[k] = x[(int64_t)n * V + k];
+        log_softmax_d(xd, V, xd + V);
+        for (int k = 0; k < V; ++k) lp[(int64_t)n * V + k] = (float)xd[V + k];
+    }
+    free(xd);
+}
+
+/* Joint, first half: z = tanh(e .* p) (multiplicative combination, Sec. 2;
+ * the tanh is the measured configuration's), then the 4-bit code of z since z
+ * is the input of a quantized linear layer (Sec. 3.2).  Row n uses encoder row
+ * frame_row[n].  Pinned by: numpy restatement, |code| <= 7. */
+void oq_joint_z(const float *enc_proj, const int32_t *frame_row, const float *pred_proj,
+                int N, int J, float inv_s_z, int8_t *zq, double *z_real)
+{
+    for (int n = 0; n < N; ++n) {
+        const float *e = enc_proj + (int64_t)frame_row[n] * J, *p = pred_proj + (int64_t)n * J;
+        for (int j = 0; j < J; ++j) {
+            double z = tanh((double)e[j] * (double)p[j]);
+            if (z_real) z_real[(int64_t)n * J + j] = z;
+            zq[(int64_t)n * J + j] = oq_quant_sym4((float)z, inv_s_z);
+        }
+    }
+}
+
+/* Joint, second half + Eq. 1.  logits = Linear_out(zq); lp = log_softmax;
+ * fused[blank] = lp[blank]; fused[k] = lp[k] - lambda_src*lp_src[k]
+ * + lambda_ext*lp_ext[k] + rho for k != blank (the LMs score label sequences,
+ * which hold no blank; rho is the per-label insertion reward of Eq. 1).
+ * lp_src/lp_ext may be NULL (term dropped).
+ * Pinned by: sum exp(lp)=1, lambda=rho=0 gives lp, affinity in lambda. */
+void oq_joint_out(const oq_linear_t *out, const int8_t *zq, const float *lp_src, const float *lp_ext,
+                  float lambda_src, float lambda_ext, float rho, int N, int blank,
+                  float *lp_rnnt, float *fused)
+{
+    const int V = out->rows, J = out->cols;
+    double *buf = (double *)malloc(sizeof(double) * 2 * (size_t)V);
+    for (int n = 0; n < N; ++n) {
+        for (int k = 0; k < V; ++k) {
+            int32_t s = 0;
+            for (int j = 0; j < J; ++j) s += (int32_t)out->w[(int64_t)k * J + j] * (int32_t)zq[(int64_t)n * J + j];
+            buf[k] = (double)out->s_a * (double)out->s_w[k] * (double)s + (out->bias ? (double)out->bias[k] : 0.0);
+        }
+        log_softmax_d(buf, V, buf + V);
+        for (int k = 0; k < V; ++k) {
+            double lp = buf[V + k], f = lp;
+            if (k != blank) {
+                if (lp_src) f -= (double)lambda_src * (double)lp_src[(int64_t)n * V + k];
+                if (lp_ext) f += (double)lambda_ext * (double)lp_ext[(int64_t)n * V + k];
+                f += (double)rho;
+            }
+            if (lp_rnnt) lp_rnnt[(int64_t)n * V + k] = (float)lp;
+            fused[(int64_t)n * V + k] = (float)f;
+        }
+    }
+    free(buf);
+}
+
+void oq_joint_fuse(const float *enc_proj, const int32_t *frame_row, const float *pred_proj,
+                   const oq_linear_t *out, float inv_s_z, const float *lp_src, const float *lp_ext,
+                   float lambda_src, float lambda_ext, float rho, int N, int blank,
+                   int8_t *zq_out, float *lp_rnnt, float *fused)
+{
+    int8_t *zq = zq_out ? zq_out : (int8_t *)malloc((size_t)N * out->cols);
+    oq_joint_z(enc_proj, frame_row, pred_proj, N, out->cols, inv_s_z, zq, NULL);
+    oq_joint_out(out, zq, lp_src, lp_ext, lambda_src, lambda_ext, rho, N, blank, lp_rnnt, fused);
+    if (!zq_out) free(zq);
+}
+
+/* ------------------------------------------------------------------ */
+/* Beam selection and the time-synchronous search                       */
+/* ------------------------------------------------------------------ */
+
+/* Per utterance: candidates (w,k) with value score[w] + fused[w,k] (fp32 add:
+ * this sum decides a ranking, taken in the GPU path's precision); keep the W
+ * best by (value descending, flat index w*V+k ascending); -inf is never kept.
+ * force_blank != 0 restricts the candidates to k == blank.  Unfilled ranks get
+ * parent = token = -1, score = -inf.
+ * Pinned by: numpy lexsort restatement, tie case, -inf case. */
+void oq_beam_step(const float *score, const float *fused, int B, int W, int V, int blank,
+                  int force_blank, int32_t *parent_out, int32_t *token_out, float *score_out)
+{
+    for (int b = 0; b < B; ++b) {
+        int nc = W * V;
+        float *val = (float *)malloc(sizeof(float) * (size_t)nc);
+        uint8_t *taken = (uint8_t *)calloc((size_t)nc, 1);
+        for (int w = 0; w < W; ++w)
+            for (int k = 0; k < V; ++k) {
+                float v = score[b * W + w] + fused[((int64_t)b * W + w) * V + k];
+                if (force_blank && k != blank) v = -INFINITY;
+                val[w * V + k] = v;
+            }
+        for (int r = 0; r < W; ++r) {
+            int best = -1;
+            for (int c = 0; c < nc; ++c) {
+                if (taken[c] || !(val[c] > -INFINITY)) continue;
+                if (best < 0 || val[c] > val[best]) best = c; /* first index wins a tie */
+            }
+            if (best < 0) {
+                parent_out[b * W + r] = -1; token_out[b * W + r] = -1; score_out[b * W + r] = -INFINITY;
+            } else {
+                taken[best] = 1;
+                parent_out[b * W + r] = best / V; token_out[b * W + r] = best % V; score_out[b * W + r] = val[best];
+            }
+        }
+        free(val); free(taken);
+    }
+}
+
+/* A language model or the prediction network: embedding lookup, the symmetric
+ * quantizer on the embedding (FIX boundary, Sec. 3.2), L stacked quantized
+ * LSTM steps, one quantized linear layer.  The LM applies log-softmax to the
+ * linear output, the prediction network does not. */
+typedef struct {
+    const float *embed;   /* [V, E] fp32 */
+    int32_t E, L;
+    float inv_s_e;        /* 7/alpha of the embedding quantizer */
+    oq_lstm_t layer[OQ_MAX_LAYERS];
+    oq_linear_t out;
+    int32_t log_softmax;  /* 1: LM, 0: prediction network */
+} oq_net_t;
+
+typedef struct {
+    oq_net_t pred, lm_src, lm_ext;
+    oq_linear_t joint_out;
+    float inv_s_z;
+    float lambda_src, lambda_ext, rho;
+    int32_t V, blank, use_src, use_ext;
+} oq_model_t;
+
+typedef struct {
+    int8_t *h[OQ_MAX_LAYERS];
+    float *c[OQ_MAX_LAYERS];
+    float *y; /* cached output: p [J] or log-probs [V] */
+} net_state;
+
+static void ns_alloc(const oq_net_t *net, net_state *s)
+{
+    for (int l = 0; l < net->L; ++l) {
+        s->h[l] = (int8_t *)calloc((size_t)net->layer[l].H, 1);
+        s->c[l] = (float *)calloc((size_t)net->layer[l].H, sizeof(float));
+    }
+    s->y = (float *)calloc((size_t)net->out.rows, sizeof(float));
+}
+static void ns_free(const oq_net_t *net, net_state *s)
+{
+    for (int l = 0; l < net->L; ++l) { free(s->h[l]); free(s->c[l]); }
+    free(s->y);
+}
+static void ns_copy(const oq_net_t *net, net_state *d, const net_state *s)
+{
+    for (int l = 0; l < net->L; ++l) {
+        memcpy(d->h[l], s->h[l], (size_t)net->layer[l].H);
+        memcpy(d->c[l], s->c[l], (size_t)net->layer[l].H * sizeof(float));
+    }
+    memcpy(d->y, s->y, (size_t)net->out.rows * sizeof(float));
+}
+
+/* Feed one symbol: dst = advance(src, token).  dst and src must differ. */
+static void net_advance(const oq_net_t *net, const net_state *src, int token, net_state *dst)
+{
+    int maxw = net->E;
+    for (int l = 0; l < net->L; ++l) if (net->layer[l].H > maxw) maxw = net->layer[l].H;
+    int8_t *xin = (int8_t *)malloc((size_t)maxw);
+    oq_quantize_sym4(net->embed + (int64_t)token * net->E, net->E, net->inv_s_e, xin);
+    for (int l = 0; l < net->L; ++l) {
+        oq_lstm_step(&net->layer[l], xin, NULL, src->h[l], src->c[l], NULL, 1,
+                     dst->h[l], dst->c[l], NULL, NULL, NULL, NULL);
+        memcpy(xin, dst->h[l], (size_t)net->layer[l].H);
+    }
+    oq_linear(&net->out, xin, 1, dst->y, NULL);
+    if (net->log_softmax) oq_log_softmax(dst->y, 1, net->out.rows, dst->y);
+    free(xin);
+}
+
+/* Exposed for tests: run `n_tok` symbols through a net from the zero state and
+ * return the cached output after each one ([n_tok, out.rows]). */
+void oq_net_run(const oq_net_t *net, const int32_t *tokens, int n_tok, float *y_all)
+{
+    net_state a, b;
+    ns_alloc(net, &a); ns_alloc(net, &b);
+    for (int i = 0; i < n_tok; ++i) {
+        net_advance(net, &a, tokens[i], &b);
+        memcpy(y_all + (int64_t)i * net->out.rows, b.y, (size_t)net->out.rows * sizeof(float));
+        net_state t = a; a = b; b = t;
+    }
+    ns_free(net, &a); ns_free(net, &b);
+}
+
+typedef struct {
+    int32_t *tok; int len, cap;
+    float score;
+    net_state pred, src, ext;
+} hyp_t;
+
+static void hyp_alloc(const oq_model_t *M, hyp_t *h)
+{
+    h->tok = NULL; h->len = 0; h->cap = 0; h->score = -INFINITY;
+    ns_alloc(&M->pred, &h->pred);
+    if (M->use_src) ns_alloc(&M->lm_src, &h->src);
+    if (M->use_ext) ns_alloc(&M->lm_ext, &h->ext);
+}
+static void hyp_free(const oq_model_t *M, hyp_t *h)
+{
+    free(h->tok);
+    ns_free(&M->pred, &h->pred);
+    if (M->use_src) ns_free(&M->lm_src, &h->src);
+    if (M->use_ext) ns_free(&M->lm_ext, &h->ext);
+}
+static void hyp_copy(const oq_model_t *M, hyp_t *d, const hyp_t *s)
+{
+    if (d->cap < s->len + 1) { d->cap = s->len + 16; d->tok = (int32_t *)realloc(d->tok, sizeof(int32_t) * (size_t)d->cap); }
+    if (s->len) memcpy(d->tok, s->tok, sizeof(int32_t) * (size_t)s->len);
+    d->len = s->len; d->score = s->score;
+    ns_copy(&M->pred, &d->pred, &s->pred);
+    if (M->use_src) ns_copy(&M->lm_src, &d->src, &s->src);
+    if (M->use_ext) ns_copy(&M->lm_ext, &d->ext, &s->ext);
+}
+/* d = s extended by `token` (all three networks advance from s's state). */
+static void hyp_extend(const oq_model_t *M, hyp_t *d, const hyp_t *s, int token, float score)
+{
+    if (d->cap < s->len + 1) { d->cap = s->len + 16; d->tok = (int32_t *)realloc(d->tok, sizeof(int32_t) * (size_t)d->cap); }
+    if (s->len) memcpy(d->tok, s->tok, sizeof(int32_t) * (size_t)s->len);
+    d->tok[s->len] = token; d->len = s->len + 1; d->score = score;
+    net_advance(&M->pred, &s->pred, token, &d->pred);
+    if (M->use_src) net_advance(&M->lm_src, &s->src, token, &d->src);
+    if (M->use_ext) net_advance(&M->lm_ext, &s->ext, token, &d->ext);
+}
+
+/* Time-synchronous beam search with at most max_sym labels per frame, one
+ * utterance at a time (Sec. 2 describes a beam of up to 16 hypotheses kept per
+ * iteration of the decoding loop; the frame-synchronous variant with an
+ * emission cap is the measured configuration's).
+ *
+ *   beam: up to W hypotheses.  Start: the empty sequence, score 0, networks
+ *   advanced once on symbol 0 from the zero state.
+ *   for each frame t:  A <- beam, Nx <- empty
+ *     for round v = 0..max_sym:
+ *       F[w,:] = joint_fuse(e[t], hypothesis w of A)           (Eq. 1)
+ *       pick the W best (w,k) by oq_beam_step (blank only when v == max_sym)
+ *       picked blank   -> copy of hypothesis w with the new score joins Nx
+ *       picked label k -> hypothesis w extended by k joins the next A
+ *       stop the frame when the next A is empty
+ *     beam <- the W best of Nx by (score descending, insertion order)
+ *   No recombination of equal label sequences.
+ *
+ * enc_proj [T,B,J] fp32.  Outputs per utterance, best first: tokens
+ * [B,W,max_len] (padded with -1), lengths [B,W] (-1 for an unused rank),
+ * scores [B,W].
+ * Pinned by: W=1 vs an independent greedy loop, exhaustive enumeration on a
+ * tiny case, permutation of utterances, monotone scores. */
+void oq_decode(const oq_model_t *M, const float *enc_proj, int T, int B, int W, int max_sym,
+               int max_len, int32_t *tokens_out, int32_t *len_out, float *score_out)
+{
+    const int V = M->V, J = M->joint_out.cols;
+#pragma omp parallel for schedule(dynamic)
+    for (int b = 0; b < B; ++b) {
+        int nx_cap = W * (max_sym + 1);
+        hyp_t *beam = (hyp_t *)malloc(sizeof(hyp_t) * (size_t)W);
+        hyp_t *A = (hyp_t *)malloc(sizeof(hyp_t) * (size_t)W);
+        hyp_t *A2 = (hyp_t *)malloc(sizeof(hyp_t) * (size_t)W);
+        hyp_t *Nx = (hyp_t *)malloc(sizeof(hyp_t) * (size_t)nx_cap);
+        for (int w = 0; w < W; ++w) { hyp_alloc(M, &beam[w]); hyp_alloc(M, &A[w]); hyp_alloc(M, &A2[w]); }
+        for (int i = 0; i < nx_cap; ++i) hyp_alloc(M, &Nx[i]);
+        float *S = (float *)malloc(sizeof(float) * (size_t)W);
+        float *F = (float *)malloc(sizeof(float) * (size_t)W * V);
+        float *P = (float *)malloc(sizeof(float) * (size_t)W * J);
+        float *Ls = (float *)malloc(sizeof(float) * (size_t)W * V);
+        float *Le = (float *)malloc(sizeof(float) * (size_t)W * V);
+        int32_t *frow = (int32_t *)malloc(sizeof(int32_t) * (size_t)W);
+        int32_t *par = (int32_t *)malloc(sizeof(int32_t) * (size_t)W);
+        int32_t *tk = (int32_t *)malloc(sizeof(int32_t) * (size_t)W);
+        float *ns = (float *)malloc(sizeof(float) * (size_t)W);
+
+        /* start hypothesis: zero state advanced on symbol 0 */
+        {
+            hyp_t zero; hyp_alloc(M, &zero);
+            hyp_extend(M, &beam[0], &zero, 0, 0.0f);
+            beam[0].len = 0; /* the start symbol is not part of the label sequence */
+            hyp_free(M, &zero);
+        }
+        int n_beam = 1;
+
+        for (int t = 0; t < T; ++t) {
+            int nA = n_beam, nNx = 0;
+            for (int w = 0; w < nA; ++w) hyp_copy(M, &A[w], &beam[w]);
+            for (int v = 0; v <= max_sym && nA > 0; ++v) {
+                for (int w = 0; w < W; ++w) {
+                    frow[w] = t * B + b;
+                    S[w] = w < nA ? A[w].score : -INFINITY;
+                    const hyp_t *h = &A[w < nA ? w : 0];
+                    memcpy(P + (int64_t)w * J, h->pred.y, sizeof(float) * (size_t)J);
+                    if (M->use_src) memcpy(Ls + (int64_t)w * V, h->src.y, sizeof(float) * (size_t)V);
+                    if (M->use_ext) memcpy(Le + (int64_t)w * V, h->ext.y, sizeof(float) * (size_t)V);
+                }
+                oq_joint_fuse(enc_proj, frow, P, &M->joint_out, M->inv_s_z,
+                              M->use_src ? Ls : NULL, M->use_ext ? Le : NULL,
+                              M->lambda_src, M->lambda_ext, M->rho, W, M->blank, NULL, NULL, F);
+                oq_beam_step(S, F, 1, W, V, M->blank, v == max_sym, par, tk, ns);
+                int nA2 = 0;
+                for (int r = 0; r < W; ++r) {
+                    if (par[r] < 0) break;
+                    if (tk[r] == M->blank) {
+                        hyp_copy(M, &Nx[nNx], &A[par[r]]);
+                        Nx[nNx].score = ns[r];
+                        ++nNx;
+                    } else {
+                        hyp_extend(M, &A2[nA2], &A[par[r]], tk[r], ns[r]);
+                        ++nA2;
+                    }
+                }
+                hyp_t *tmp = A; A = A2; A2 = tmp;
+                nA = nA2;
+            }
+            /* beam <- W best of Nx, ties by insertion order */
+            uint8_t *used = (uint8_t *)calloc((size_t)nx_cap, 1);
+            n_beam = 0;
+            for (int r = 0; r < W; ++r) {
+                int best = -1;
+                for (int i = 0; i < nNx; ++i) {
+                    if (used[i]) continue;
+                    if (best < 0 || Nx[i].score > Nx[best].score) best = i;
+                }
+                if (best < 0) break;
+                used[best] = 1;
+                hyp_copy(M, &beam[n_beam++], &Nx[best]);
+            }
+            free(used);
+        }
+        for (int w = 0; w < W; ++w) {
+            int32_t *dst = tokens_out + ((int64_t)b * W + w) * max_len;
+            for (int i = 0; i < max_len; ++i) dst[i] = -1;
+            if (w < n_beam) {
+                int len = beam[w].len < max_len ? beam[w].len : max_len;
+                memcpy(dst, beam[w].tok, sizeof(int32_t) * (size_t)len);
+                len_out[b * W + w] = beam[w].len;
+                score_out[b * W + w] = beam[w].score;
+            } else {
+                len_out[b * W + w] = -1;
+                score_out[b * W + w] = -INFINITY;
+            }
+        }
+        for (int w = 0; w < W; ++w) { hyp_free(M, &beam[w]); hyp_free(M, &A[w]); hyp_free(M, &A2[w]); }
+        for (int i = 0; i < nx_cap; ++i) hyp_free(M, &Nx[i]);
+        free(beam); free(A); free(A2); free(Nx);
+        free(S); free(F); free(P); free(Ls); free(Le); free(frow); free(par); free(tk); free(ns);
+    }
+}
+
+/* Score of one fixed alignment, for the exhaustive-search pin: `actions` is a
+ * sequence of symbols (blank advances the frame, a label extends the
+ * hypothesis) consumed from frame 0; returns the sum of fused scores along it
+ * (fp32 accumulation, as the search does).  The caller guarantees exactly T
+ * blanks. */
+float oq_score_alignment(const oq_model_t *M, const float *enc_proj, int B, int b,
+                         const int32_t *actions, int n_act)
+{
+    const int V = M->V, J = M->joint_out.cols;
+    hyp_t cur, nxt, zero;
+    hyp_alloc(M, &cur); hyp_alloc(M, &nxt); hyp_alloc(M, &zero);
+    hyp_extend(M, &cur, &zero, 0, 0.0f);
+    cur.len = 0;
+    float *F = (float *)malloc(sizeof(float) * (size_t)V);
+    (void)J;
+    int t = 0;
+    float S = 0.0f;
+    for (int a = 0; a < n_act; ++a) {
+        int32_t frow = t * B + b;
+        oq_joint_fuse(enc_proj, &frow, cur.pred.y, &M->joint_out, M->inv_s_z,
+                      M->use_src ? cur.src.y : NULL, M->use_ext ? cur.ext.y : NULL,
+                      M->lambda_src, M->lambda_ext, M->rho, 1, M->blank, NULL, NULL, F);
+        S = S + F[actions[a]];
+        if (actions[a] == M->blank) {
+            ++t;
+        } else {
+            hyp_extend(M, &nxt, &cur, actions[a], S);
+            hyp_t tmp = cur; cur = nxt; nxt = tmp;
+        }
+    }
+    free(F);
+    hyp_free(M, &cur); hyp_free(M, &nxt); hyp_free(M, &zero);
+    return S;
+}
+
+int oq_struct_sizes(int which)
+{
+    switch (which) {
+    case 0: return (int)sizeof(oq_lstm_t);
+    case 1: return (int)sizeof(oq_linear_t);
+    case 2: return (int)sizeof(oq_net_t);
+    case 3: return (int)sizeof(oq_model_t);
+    default: return -1;
+    }
+}

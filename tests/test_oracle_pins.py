@@ -1,0 +1,514 @@
+"""Pins of the CPU oracle against things other than itself.
+
+Each test fixes one part of ``oracle/`` with a closed form, an invariant, a
+hand-computed value, brute force in plain Python, or a special case that
+reduces to a numpy routine, chosen so that a plausible slip (dropped term,
+wrong sign, swapped gate, transposed operand) fails at least one of them.
+Citations: Sec. 3.1 (quantizers, Eq. 2-3), Sec. 3.2 (what is quantized),
+Sec. 3.4 (Outer quantization and its call counts), Sec. 2 (network, Eq. 1).
+"""
+import itertools
+import math
+import os
+
+import numpy as np
+import pytest
+
+import oracle
+from oracle import models
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden")
+
+
+# ------------------------------------------------------------------ Sec. 3.1
+
+def test_sym4_clip_range_and_grid_identity():
+    # codes never leave [-8, 7]; every grid value is a fixed point of Q o deq
+    x = np.linspace(-10, 10, 4001, dtype=np.float32)
+    q = oracle.quant_sym4(x, 7.0)
+    assert q.min() == -8 and q.max() == 7
+    for alpha in (1.0, 1.25, 4.0, 0.37):
+        s = np.float32(alpha) / np.float32(7)
+        inv = np.float32(7) / np.float32(alpha)
+        codes = np.arange(-8, 8, dtype=np.int8)
+        back = oracle.quant_sym4(codes.astype(np.float32) * s, inv)
+        assert np.array_equal(back, codes)
+
+
+def test_sym4_zero_maps_to_zero_exactly():
+    # symmetric LQ maps a zero input exactly to integer zero (Sec. 3.1)
+    assert oracle.quant_sym4(np.array([0.0, -0.0], np.float32), 7.0).tolist() == [0, 0]
+
+
+def test_sym4_round_half_even_hand_values():
+    # x*7 = .5, 1.5, 2.5, -0.5, -1.5, 6.5, 7.5(clipped), -7.5, -8.5(clipped)
+    t = np.array([0.5, 1.5, 2.5, -0.5, -1.5, 6.5, 7.5, -7.5, -8.5, 3.49, 3.51], np.float32)
+    q = oracle.quant_sym4(t, 1.0)
+    assert q.tolist() == [0, 2, 2, 0, -2, 6, 7, -8, -8, 3, 4]
+
+
+def test_sym4_residual_bound_and_monotone():
+    # inside the clipping range the residual is at most s/2 (Sec. 3.1)
+    rng = np.random.default_rng(1)
+    alpha = 1.25
+    s = np.float32(alpha) / np.float32(7)
+    inv = np.float32(7) / np.float32(alpha)
+    x = rng.uniform(-alpha, alpha, 20000).astype(np.float32)
+    q = oracle.quant_sym4(x, inv)
+    assert np.all(np.abs(x.astype(np.float64) - q * float(s)) <= float(s) / 2 * (1 + 1e-5))
+    xs = np.sort(x)
+    assert np.all(np.diff(oracle.quant_sym4(xs, inv).astype(int)) >= 0)
+
+
+def test_asym_eq2_eq3_worked_example():
+    # b=4, alpha=+-1: s = 2/15, z = 7.5 (the worked numbers that follow from Eq. 2-3)
+    xi, xq = oracle.quantize_asym(np.array([-1.0, 1.0, 0.0, 5.0, -5.0], np.float32), 4, -1.0, 1.0)
+    assert xi[0] == 0 and xi[1] == 15        # alpha_- -> 0, alpha_+ -> 2^b - 1
+    assert xi[3] == 15 and xi[4] == 0        # clamp
+    assert abs(xq[0] + 1.0) < 1e-12 and abs(xq[1] - 1.0) < 1e-12
+    # b=8, asymmetric range with an integer zero point: s=0.01, z=100
+    xi, xq = oracle.quantize_asym(np.array([-1.0, 0.0, 0.5, 1.55], np.float32), 8, -1.0, 1.55)
+    assert xi.tolist() == [0, 100, 150, 255]
+    rng = np.random.default_rng(2)
+    x = rng.uniform(-1.0, 1.55, 5000).astype(np.float32)
+    _, xq = oracle.quantize_asym(x, 8, -1.0, 1.55)
+    assert np.all(np.abs(xq - x) <= 0.005 * (1 + 1e-6))
+
+
+def test_weight_rows_max_abs_scale_hand_row():
+    w = np.array([[0.7, -0.35, 0.05, 0.0, -0.7, 0.1499],
+                  [0.0, 0.0, 0.0, 0.0, 0.0, 0.0],
+                  [-3.5, 1.0, 0.25, 0.26, 3.0, 0.75]], np.float32)
+    q, s = oracle.quantize_weight_rows(w)
+    # row 0: alpha=.7, step .1 -> 7, -3.5->-4 (tie to even), .5->0 (tie to even), 0, -7, 1.499->1
+    assert q[0].tolist() == [7, -4, 0, 0, -7, 1]
+    assert abs(s[0] - 0.1) < 1e-7
+    assert q[1].tolist() == [0] * 6 and s[1] == 1.0
+    # row 2: alpha=3.5, step .5 -> -7, 2, .5->0, .52->1, 6, 1.5->2
+    assert q[2].tolist() == [-7, 2, 0, 1, 6, 2]
+    rng = np.random.default_rng(3)
+    w = rng.standard_normal((50, 33)).astype(np.float32)
+    q, s = oracle.quantize_weight_rows(w)
+    assert np.all(np.abs(q).max(axis=1) == 7) and q.min() >= -7
+    assert np.allclose(s, np.abs(w).max(axis=1) / 7, rtol=1e-6)
+
+
+def test_pack_hand_bytes_and_roundtrip_all_bytes():
+    codes = np.array([[1, -1, 7, -8, 0, 3]], np.int8)
+    p = oracle.pack_rows(codes, 8)
+    assert p.tolist() == [[0xF1, 0x87, 0x30, 0x00]]
+    # all 256 byte values: every (lo, hi) nibble pair
+    lo, hi = np.meshgrid(np.arange(-8, 8), np.arange(-8, 8))
+    allc = np.stack([lo.ravel(), hi.ravel()], axis=1).astype(np.int8).reshape(1, -1)
+    p = oracle.pack_rows(allc, allc.shape[1])
+    assert sorted(p.ravel().tolist()) == list(range(256))
+    assert np.array_equal(oracle.unpack_rows(p, allc.shape[1]), allc)
+    # ragged: cols 5 padded to 8
+    c5 = np.array([[1, 2, 3, 4, 5], [-1, -2, -3, -4, -5]], np.int8)
+    p = oracle.pack_rows(c5, 8)
+    assert p.shape == (2, 4) and p[0].tolist() == [0x21, 0x43, 0x05, 0x00]
+    assert np.array_equal(oracle.unpack_rows(p, 5), c5)
+
+
+# ------------------------------------------------------------------ integer MAC
+
+def test_matmul_bruteforce_and_extremes():
+    rng = np.random.default_rng(4)
+    w = rng.integers(-8, 8, (5, 7)).astype(np.int8)
+    a = rng.integers(-8, 8, (3, 7)).astype(np.int8)
+    ref = [[sum(int(w[r, k]) * int(a[n, k]) for k in range(7)) for r in range(5)] for n in range(3)]
+    assert oracle.matmul_i32(w, a).tolist() == ref
+    K = 2048
+    assert oracle.matmul_i32(np.full((2, K), -8, np.int8), np.full((1, K), -8, np.int8)).tolist() == [[64 * K] * 2]
+    assert oracle.matmul_i32(np.full((2, K), 7, np.int8), np.full((1, K), -8, np.int8)).tolist() == [[-56 * K] * 2]
+    w = rng.integers(-8, 8, (9, 300)).astype(np.int8)
+    a = rng.integers(-8, 8, (4, 300)).astype(np.int8)
+    perm = rng.permutation(300)
+    assert np.array_equal(oracle.matmul_i32(w, a), oracle.matmul_i32(w[:, perm], a[:, perm]))
+    assert np.array_equal(oracle.matmul_i32(w, a), a.astype(np.int64) @ w.astype(np.int64).T)
+
+
+# ------------------------------------------------------------------ LSTM cell
+
+def _rand_lstm(rng, I, H, s_x=0.2):
+    return oracle.Lstm(rng.integers(-7, 8, (4 * H, I)), rng.uniform(0.005, 0.03, 4 * H),
+                       rng.integers(-7, 8, (4 * H, H)), rng.uniform(0.005, 0.03, 4 * H),
+                       rng.standard_normal(4 * H) * 0.3, s_x)
+
+
+def test_lstm_zero_weights_closed_form():
+    # zero weights: i,f,o = sigma(b), g = tanh(b); c_t = i g (1 - f^t)/(1 - f); h_t = o tanh(c_t)
+    H, I, T, B = 6, 5, 25, 2
+    rng = np.random.default_rng(5)
+    b = rng.standard_normal(4 * H)
+    L = oracle.Lstm(np.zeros((4 * H, I)), np.ones(4 * H), np.zeros((4 * H, H)), np.ones(4 * H), b, 0.3)
+    x = rng.integers(-7, 8, (T, B, I)).astype(np.int8)
+    h_out, h_last, c_last, c_all = oracle.lstm_layer(L, x, want_c_all=True)
+    b32 = b.astype(np.float32).astype(np.float64)
+    sg = lambda v: 1 / (1 + np.exp(-v))
+    i, f, g, o = sg(b32[:H]), sg(b32[H:2 * H]), np.tanh(b32[2 * H:3 * H]), sg(b32[3 * H:])
+    for t in range(1, T + 1):
+        c = i * g * (1 - f ** t) / (1 - f)
+        assert np.allclose(c_all[t - 1, 0], c, rtol=2e-6, atol=1e-7)   # fp32 storage of c each step
+        h = o * np.tanh(c)
+        code = np.rint(h * 7)
+        near_tie = np.abs(h * 7 - np.floor(h * 7) - 0.5) < 1e-4
+        assert np.all((h_out[t - 1, 1] == code) | near_tie)
+
+
+def test_lstm_step_against_numpy_cell():
+    # an independent restatement with numpy: dequantize, float matmul, textbook LSTM
+    rng = np.random.default_rng(6)
+    I, H, N = 24, 16, 9
+    L = _rand_lstm(rng, I, H)
+    x = rng.integers(-8, 8, (N, I)).astype(np.int8)
+    hp = rng.integers(-7, 8, (N, H)).astype(np.int8)
+    cp = rng.standard_normal((N, H)).astype(np.float32)
+    hn, cn, dbg = oracle.lstm_step(L, x, hp, cp, debug=True)
+    Wih = L.w_ih.astype(np.float64) * L.s_wih.astype(np.float64)[:, None]
+    Whh = L.w_hh.astype(np.float64) * L.s_whh.astype(np.float64)[:, None]
+    pre = (x.astype(np.float64) * float(L.s_x)) @ Wih.T + (hp.astype(np.float64) * float(L.s_h)) @ Whh.T + L.bias
+    sg = lambda v: 1 / (1 + np.exp(-v))
+    gi, gf, gg, go = sg(pre[:, :H]), sg(pre[:, H:2 * H]), np.tanh(pre[:, 2 * H:3 * H]), sg(pre[:, 3 * H:])
+    c = gf * cp + gi * gg
+    h = go * np.tanh(c)
+    assert np.allclose(dbg["gates"], np.concatenate([gi, gf, gg, go], 1), rtol=1e-12, atol=1e-13)
+    assert np.allclose(cn, c, rtol=1e-6, atol=1e-7)
+    assert np.allclose(dbg["h_real"], h, rtol=1e-9, atol=1e-12)
+    tie = np.abs(h * 7 - np.floor(h * 7) - 0.5) < 1e-5
+    assert np.all((hn == np.rint(h * 7)) | tie)
+    assert np.array_equal(dbg["accx"], x.astype(np.int64) @ L.w_ih.astype(np.int64).T)
+    assert np.array_equal(dbg["acch"], hp.astype(np.int64) @ L.w_hh.astype(np.int64).T)
+    assert np.abs(hn).max() <= 7    # h = tanh * sigma is in [-1,1]: FIX +-1 never clips (Sec. 3.2)
+
+
+def test_lstm_gate_roles_by_saturation():
+    # saturating one gate at a time shows each block of rows plays its textbook role
+    H, I = 4, 3
+    big = 40.0
+    x = np.zeros((1, I), np.int8); hp = np.zeros((1, H), np.int8)
+    cp = np.full((1, H), 0.5, np.float32)
+
+    def run(bi, bf, bg, bo):
+        b = np.concatenate([np.full(H, bi), np.full(H, bf), np.full(H, bg), np.full(H, bo)])
+        L = oracle.Lstm(np.zeros((4 * H, I)), np.ones(4 * H), np.zeros((4 * H, H)), np.ones(4 * H), b, 1.0)
+        return oracle.lstm_step(L, x, hp, cp)
+
+    hn, cn = run(-big, big, big, big)      # input gate closed, forget open: c stays
+    assert np.allclose(cn, 0.5)
+    hn, cn = run(big, -big, big, big)      # forget closed, input open, g=+1: c = 1
+    assert np.allclose(cn, 1.0)
+    hn, cn = run(big, -big, -big, big)     # g = -1
+    assert np.allclose(cn, -1.0)
+    assert hn.tolist() == [[int(np.rint(math.tanh(-1.0) * 7))] * H]
+    hn, cn = run(big, -big, big, -big)     # output gate closed: h = 0
+    assert hn.tolist() == [[0] * H]
+
+
+def test_lstm_parent_gather_and_inactive_passthrough():
+    rng = np.random.default_rng(7)
+    I, H, N = 8, 8, 6
+    L = _rand_lstm(rng, I, H)
+    x = rng.integers(-7, 8, (N, I)).astype(np.int8)
+    hp = rng.integers(-7, 8, (N, H)).astype(np.int8)
+    cp = rng.standard_normal((N, H)).astype(np.float32)
+    parent = np.array([3, 3, 0, 5, 1, 1], np.int32)
+    active = np.array([1, 0, 1, 1, 0, 1], np.uint8)
+    hn, cn = oracle.lstm_step(L, x, hp, cp, parent=parent, active=active)
+    hn2, cn2 = oracle.lstm_step(L, x, hp[parent], cp[parent])
+    for n in range(N):
+        if active[n]:
+            assert np.array_equal(hn[n], hn2[n]) and np.array_equal(cn[n], cn2[n])
+        else:
+            assert np.array_equal(hn[n], hp[parent[n]]) and np.array_equal(cn[n], cp[parent[n]])
+
+
+def test_lstm_layer_reverse_is_time_flip_and_offsets():
+    rng = np.random.default_rng(8)
+    I, H, T, B = 10, 8, 7, 3
+    L = _rand_lstm(rng, I, H)
+    x = rng.integers(-7, 8, (T, B, I)).astype(np.int8)
+    fwd_on_flipped, _, _, _ = oracle.lstm_layer(L, x[::-1].copy())
+    out = np.full((T, B, 2 * H + 3), 99, np.int8)
+    oracle.lstm_layer(L, x, reverse=True, h_out=out, col_off=H)
+    assert np.array_equal(out[:, :, H:2 * H], fwd_on_flipped[::-1])
+    assert np.all(out[:, :, :H] == 99) and np.all(out[:, :, 2 * H:] == 99)
+    # T = 1 equals one step from the zero state
+    h1, hl, cl, _ = oracle.lstm_layer(L, x[:1])
+    hs, cs = oracle.lstm_step(L, x[0], np.zeros((B, H), np.int8), np.zeros((B, H), np.float32))
+    assert np.array_equal(h1[0], hs) and np.array_equal(cl, cs) and np.array_equal(hl, hs)
+
+
+def test_outer_quantization_call_counts():
+    # Sec. 3.4: Outer needs T + T*L quantizer calls, Inner 2*T*L; ratio (L+1)/(2L);
+    # L = 12 (6 bidirectional layers counted twice) gives 13/24, i.e. about 45 % fewer calls.
+    rng = np.random.default_rng(9)
+    T, B, D, H, layers = 5, 2, 6, 4, 3
+    L_dirs = 2 * layers
+    feats = rng.standard_normal((T, B, D)).astype(np.float32)
+    oracle.quant_calls_reset()
+    x = np.stack([oracle.quant_sym4(feats[t], 7 / 4) for t in range(T)])    # one call per time step
+    for l in range(layers):
+        I = D if l == 0 else 2 * H
+        out = np.zeros((T, B, 2 * H), np.int8)
+        for d in range(2):
+            oracle.lstm_layer(_rand_lstm(rng, I, H), x, reverse=bool(d), h_out=out, col_off=d * H)
+        x = out        # the stored codes feed the next layer: no second quantizer
+    assert oracle.quant_calls() == T + T * L_dirs
+    assert (T + T * L_dirs) / (2 * T * L_dirs) == (L_dirs + 1) / (2 * L_dirs)
+    assert abs((1 - 13 / 24) - 0.458) < 1e-3
+
+
+# ------------------------------------------------------------------ linear, joint, Eq. 1
+
+def test_linear_against_dequantized_float_matmul():
+    rng = np.random.default_rng(10)
+    w = rng.integers(-8, 8, (11, 40)).astype(np.int8)
+    sw = rng.uniform(0.01, 0.05, 11).astype(np.float32)
+    b = rng.standard_normal(11).astype(np.float32)
+    P = oracle.Linear(w, sw, b, 1 / 7)
+    a = rng.integers(-8, 8, (6, 40)).astype(np.int8)
+    y, acc = oracle.linear(P, a, want_acc=True)
+    ref = (a.astype(np.float64) * float(np.float32(1 / 7))) @ (w.astype(np.float64) * sw.astype(np.float64)[:, None]).T + b
+    assert np.allclose(y, ref, rtol=1e-6, atol=1e-6)
+    assert np.array_equal(acc, a.astype(np.int64) @ w.astype(np.int64).T)
+
+
+def test_log_softmax_properties():
+    rng = np.random.default_rng(11)
+    x = (rng.standard_normal((7, 46)) * 5).astype(np.float32)
+    lp = oracle.log_softmax(x)
+    assert np.allclose(np.exp(lp.astype(np.float64)).sum(1), 1.0, atol=1e-6)
+    assert np.allclose(oracle.log_softmax(x + np.float32(100.0)), lp, atol=2e-5)
+    assert np.allclose(oracle.log_softmax(np.full((1, 46), 3.0, np.float32)), -math.log(46), atol=1e-6)
+    assert np.allclose(lp[:, 1:] - lp[:, :1], (x[:, 1:] - x[:, :1]), atol=1e-5)   # differences preserved
+    big = np.array([[1000.0, 0.0, -1000.0]], np.float32)                        # no overflow
+    assert np.allclose(oracle.log_softmax(big), [[0.0, -1000.0, -2000.0]])
+
+
+def _joint_setup(rng, N=5, J=16, V=7, TB=4):
+    e = rng.standard_normal((TB, J)).astype(np.float32)
+    p = rng.standard_normal((N, J)).astype(np.float32)
+    fr = rng.integers(0, TB, N).astype(np.int32)
+    out = oracle.Linear(rng.integers(-7, 8, (V, J)), rng.uniform(0.05, 0.2, V), rng.standard_normal(V) * 0.2, 1 / 7)
+    ls = np.log(rng.dirichlet(np.ones(V), N)).astype(np.float32)
+    le = np.log(rng.dirichlet(np.ones(V), N)).astype(np.float32)
+    return e, p, fr, out, ls, le
+
+
+def test_joint_against_numpy_restatement():
+    rng = np.random.default_rng(12)
+    e, p, fr, out, ls, le = _joint_setup(rng)
+    zq, lp, fused = oracle.joint_fuse(e, fr, p, out, ls, le, 0.3, 0.5, rho=0.2, blank=0)
+    z = np.tanh(e[fr].astype(np.float64) * p.astype(np.float64))      # multiplicative combination (Sec. 2)
+    tie = np.abs(z * 7 - np.floor(z * 7) - 0.5) < 1e-5
+    assert np.all((zq == np.rint(z * 7)) | tie) and np.abs(zq).max() <= 7
+    logits = (zq.astype(np.float64) * float(np.float32(1 / 7))) @ (out.w * out.s_w.astype(np.float64)[:, None]).T + out.bias
+    ref_lp = logits - np.log(np.exp(logits).sum(1, keepdims=True))
+    assert np.allclose(lp, ref_lp, atol=1e-5)
+    ref_f = ref_lp.copy()
+    ref_f[:, 1:] += -0.3 * ls[:, 1:].astype(np.float64) + 0.5 * le[:, 1:].astype(np.float64) + 0.2
+    assert np.allclose(fused, ref_f, atol=1e-5)
+    assert np.allclose(fused[:, 0], lp[:, 0])        # blank is not an LM event
+
+
+def test_fusion_special_cases_of_eq1():
+    rng = np.random.default_rng(13)
+    e, p, fr, out, ls, le = _joint_setup(rng)
+    _, lp, f0 = oracle.joint_fuse(e, fr, p, out, ls, le, 0.0, 0.0, rho=0.0)
+    assert np.array_equal(f0, lp)                                     # lambda = mu = rho = 0: plain RNN-T
+    _, _, fn = oracle.joint_fuse(e, fr, p, out, None, None, 0.3, 0.5)
+    assert np.array_equal(fn, lp)                                     # no LMs
+    _, _, f1 = oracle.joint_fuse(e, fr, p, out, ls, le, 0.4, 0.0)
+    _, _, f2 = oracle.joint_fuse(e, fr, p, out, ls, le, 0.8, 0.0)
+    assert np.allclose(f2 - f1, f1 - f0, atol=2e-6)                   # affine in lambda_src
+    assert np.all((f1 - f0)[:, 1:] > 0)                               # source LM enters with a minus sign (lp<0)
+    _, _, g1 = oracle.joint_fuse(e, fr, p, out, ls, le, 0.0, 0.7)
+    assert np.allclose((g1 - f0)[:, 1:], 0.7 * le[:, 1:], atol=2e-6)  # external LM enters with a plus sign
+    _, _, r1 = oracle.joint_fuse(e, fr, p, out, ls, le, 0.0, 0.0, rho=0.2)
+    assert np.allclose((r1 - f0)[:, 1:], 0.2, atol=1e-6) and np.array_equal(r1[:, 0], f0[:, 0])
+
+
+# ------------------------------------------------------------------ beam selection
+
+def _beam_ref(score, fused, blank, force):
+    B, W = score.shape
+    V = fused.shape[-1]
+    par = np.full((B, W), -1, np.int32); tok = np.full((B, W), -1, np.int32)
+    ns = np.full((B, W), -np.inf, np.float32)
+    for b in range(B):
+        val = (score[b][:, None] + fused.reshape(B, W, V)[b]).astype(np.float32).ravel()
+        if force:
+            mask = np.ones(W * V, bool); mask[blank::V] = False
+            val[mask] = -np.inf
+        order = np.lexsort((np.arange(W * V), -val.astype(np.float64)))
+        r = 0
+        for c in order:
+            if r == W or not np.isfinite(val[c]):
+                break
+            par[b, r], tok[b, r], ns[b, r] = c // V, c % V, val[c]
+            r += 1
+    return par, tok, ns
+
+
+def test_beam_step_against_lexsort_with_ties_and_dead_slots():
+    rng = np.random.default_rng(14)
+    B, W, V = 3, 4, 6
+    score = rng.standard_normal((B, W)).astype(np.float32)
+    score[1, 2:] = -np.inf                    # dead slots
+    score[2, 1:] = -np.inf                    # a single live slot: fewer finite candidates than ... V=6 >= W
+    fused = rng.standard_normal((B * W, V)).astype(np.float32)
+    fused[0, 1] = fused[0, 3] = 9.0           # exact tie inside one parent -> lower token first
+    score[0, 1] = score[0, 0]; fused[1, :] = fused[0, :]    # ties across parents -> lower parent first
+    for force in (False, True):
+        got = oracle.beam_step(score, fused, blank=0, force_blank=force)
+        ref = _beam_ref(score, fused, 0, force)
+        for g, r in zip(got, ref):
+            assert np.array_equal(g, r)
+    par, tok, ns = oracle.beam_step(score, fused)
+    assert (par[0, 0], tok[0, 0], par[0, 1], tok[0, 1]) == (0, 1, 0, 3)
+    assert (par[0, 2], tok[0, 2], par[0, 3], tok[0, 3]) == (1, 1, 1, 3)
+    par, tok, ns = oracle.beam_step(score, fused, force_blank=True)
+    assert np.all(tok[np.isfinite(ns)] == 0) and np.sum(np.isfinite(ns[1])) == 2 and np.sum(np.isfinite(ns[2])) == 1
+    assert np.all(par[~np.isfinite(ns)] == -1)
+
+
+# ------------------------------------------------------------------ networks and search
+
+def _tiny_model(seed, V=3, E=6, H=6, J=5, with_lms=True, lam=(0.3, 0.5), rho=0.0, std=0.8):
+    rng = np.random.default_rng(seed)
+
+    def net(out_rows, ls):
+        L = oracle.Lstm.from_float(rng.standard_normal((4 * H, E)) * std, rng.standard_normal((4 * H, H)) * std,
+                                   rng.standard_normal(4 * H) * 0.2, np.float32(1.25) / np.float32(7))
+        out = oracle.Linear.from_float(rng.standard_normal((out_rows, H)) * std, rng.standard_normal(out_rows) * 0.2,
+                                       np.float32(1) / np.float32(7))
+        return oracle.Net(rng.standard_normal((V, E)) * 0.5, 1.25, [L], out, ls)
+
+    pred = net(J, False)
+    src = net(V, True) if with_lms else None
+    ext = net(V, True) if with_lms else None
+    jout = oracle.Linear.from_float(rng.standard_normal((V, J)) * 1.5, rng.standard_normal(V) * 0.3,
+                                    np.float32(1) / np.float32(7))
+    return oracle.Model(pred, src, ext, jout, lam[0], lam[1], rho)
+
+
+def _state_outputs(model, tokens):
+    """Network outputs after feeding [start symbol 0] + tokens from the zero
+    state, recomputed from scratch (independent of the search's state copies)."""
+    seq = np.array([0] + list(tokens), np.int32)
+    p = oracle.net_run(model.pred, seq)[-1]
+    ls = oracle.net_run(model.lm_src, seq)[-1] if model.lm_src is not None else None
+    le = oracle.net_run(model.lm_ext, seq)[-1] if model.lm_ext is not None else None
+    return p, ls, le
+
+
+def _fused_row(model, e, T_B_row, tokens):
+    p, ls, le = _state_outputs(model, tokens)
+    _, _, f = oracle.joint_fuse(e.reshape(-1, e.shape[-1]), np.array([T_B_row], np.int32), p[None], model.joint_out,
+                                None if ls is None else ls[None], None if le is None else le[None],
+                                model.lambda_src, model.lambda_ext, model.rho, model.blank, model.inv_s_z)
+    return f[0]
+
+
+def test_net_run_matches_manual_steps():
+    m = _tiny_model(20)
+    net = m.lm_ext
+    toks = [0, 2, 1, 1]
+    y = oracle.net_run(net, np.array(toks, np.int32))
+    h = np.zeros((1, net.layers[0].H), np.int8); c = np.zeros((1, net.layers[0].H), np.float32)
+    for i, t in enumerate(toks):
+        xq = oracle.quant_sym4(net.embed[t][None], net.inv_s_e)
+        h, c = oracle.lstm_step(net.layers[0], xq, h, c)
+        ref = oracle.log_softmax(oracle.linear(net.out, h))
+        assert np.array_equal(y[i], ref[0])
+    assert np.allclose(np.exp(y.astype(np.float64)).sum(1), 1, atol=1e-6)
+
+
+def test_beam1_equals_independent_greedy():
+    # W = 1 is greedy decoding with a cap on labels per frame
+    for seed, lms in ((21, True), (22, False)):
+        m = _tiny_model(seed, V=5, with_lms=lms)
+        rng = np.random.default_rng(seed)
+        T, B, max_sym = 6, 2, 3
+        e = rng.standard_normal((T, B, m.joint_out.cols)).astype(np.float32)
+        tok, ln, sc = oracle.decode(m, e, 1, max_sym)
+        for b in range(B):
+            seq, S = [], np.float32(0)
+            for t in range(T):
+                for v in range(max_sym + 1):
+                    f = _fused_row(m, e, t * B + b, seq)
+                    k = 0 if v == max_sym else int(np.argmax(f))
+                    S = np.float32(S + f[k])
+                    if k == 0:
+                        break
+                    seq.append(k)
+            assert ln[b, 0] == len(seq) and tok[b, 0, :len(seq)].tolist() == seq
+            assert abs(sc[b, 0] - S) < 1e-4
+        assert any(ln[:, 0] > 0)
+
+
+def test_beam_search_equals_exhaustive_enumeration_when_nothing_is_pruned():
+    # T=2 frames, V=3, at most 2 labels per frame: 7 label strings per frame, 49 alignments.
+    # With W=64 no candidate is ever dropped, so the search must return every alignment's
+    # score, best first; an independent Python enumeration provides them.
+    m = _tiny_model(23, V=3)
+    rng = np.random.default_rng(23)
+    T, B, max_sym, W = 2, 1, 2, 64
+    e = rng.standard_normal((T, B, m.joint_out.cols)).astype(np.float32)
+    per_frame = [()] + [s for n in (1, 2) for s in itertools.product((1, 2), repeat=n)]
+    scores = []
+    for f0 in per_frame:
+        for f1 in per_frame:
+            seq, S = [], np.float32(0)
+            for t, labs in enumerate((f0, f1)):
+                for k in list(labs) + [0]:
+                    S = np.float32(S + _fused_row(m, e, t * B, seq)[k])
+                    if k:
+                        seq.append(k)
+            scores.append((float(S), tuple(seq)))
+            acts = list(f0) + [0] + list(f1) + [0]
+            assert abs(oracle.score_alignment(m, e, 0, acts) - float(S)) < 1e-5
+    scores.sort(key=lambda s: -s[0])
+    tok, ln, sc = oracle.decode(m, e, W, max_sym)
+    n = int((ln[0] >= 0).sum())
+    assert n == len(scores) == 49
+    assert np.allclose(sc[0, :n], [s for s, _ in scores], atol=1e-5)
+    assert np.all(np.diff(sc[0, :n]) <= 0)
+    assert tuple(tok[0, 0, :ln[0, 0]].tolist()) == scores[0][1]
+    # a narrow beam can only do worse or equal, never better, than the exhaustive optimum
+    tok2, ln2, sc2 = oracle.decode(m, e, 2, max_sym)
+    assert sc2[0, 0] <= sc[0, 0] + 1e-6
+
+
+def test_decode_permuting_utterances_permutes_outputs():
+    m = _tiny_model(24, V=5)
+    rng = np.random.default_rng(24)
+    T, B = 5, 3
+    e = rng.standard_normal((T, B, m.joint_out.cols)).astype(np.float32)
+    tok, ln, sc = oracle.decode(m, e, 3, 2)
+    perm = [2, 0, 1]
+    tok2, ln2, sc2 = oracle.decode(m, e[:, perm].copy(), 3, 2)
+    assert np.array_equal(tok2, tok[perm]) and np.array_equal(ln2, ln[perm]) and np.array_equal(sc2, sc[perm])
+    assert np.all(np.diff(sc, axis=1) <= 0)
+
+
+def test_decode_lm_weights_zero_equals_no_lms():
+    m = _tiny_model(25, V=5, lam=(0.0, 0.0))
+    m2 = oracle.Model(m.pred, None, None, m.joint_out, 0.0, 0.0)
+    rng = np.random.default_rng(25)
+    e = rng.standard_normal((5, 2, m.joint_out.cols)).astype(np.float32)
+    a = oracle.decode(m, e, 3, 2)
+    b = oracle.decode(m2, e, 3, 2)
+    for x, y in zip(a, b):
+        assert np.array_equal(x, y)
+
+
+def test_golden_config0_decode_is_reproducible():
+    """The stored config-0 beams (written by tests/golden/make_golden.py, which
+    calls only the oracle) are what the GPU path is compared with."""
+    path = os.path.join(GOLD, "cfg0_decode.txt")
+    if not os.path.exists(path):
+        pytest.skip("golden file not generated")
+    from tests.golden import make_golden
+    assert open(path).read() == make_golden.render()
