@@ -1,0 +1,188 @@
+/*
+ * qrnnt.h -- C ABI of libqrnnt: INT4 RNN-T inference with density-ratio LM
+ * fusion on one AMD MI355X (gfx950).
+ *
+ * The calls follow the statement of the method in arXiv 2206.07882: weights
+ * are quantized once (Sec. 3.2), activations at every step; LSTM cells take
+ * integer inputs and hidden states, keep an unquantized cell state and emit
+ * the hidden state as a 4-bit code at the cell output ("Outer" quantization,
+ * Sec. 3.4); the joint network combines encoder and prediction outputs
+ * multiplicatively and ends in a log-softmax (Sec. 2); scores are fused by
+ * Eq. 1; a beam of up to 16 hypotheses is kept per utterance (Sec. 2).
+ *
+ * Conventions that hold for every entry point
+ *   - Pointers marked [device] must be device memory reachable from the GPU
+ *     that is current on the calling thread; pointers marked [host] are host
+ *     memory.  The caller owns every buffer, including workspaces; the library
+ *     allocates nothing and keeps no state between calls.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     All work is enqueued asynchronously; nothing synchronises.
+ *   - Every call validates its arguments on the host before launching
+ *     anything and returns a qrnnt_status; nothing throws across the boundary.
+ *     Validation needs no GPU.
+ *   - Activation codes travel as int8 containers holding values in [-8, 7].
+ *     Weights only exist as nibble-packed blobs written by qrnnt_pack_int4.
+ *   - Quantizer: q = clamp(rne(x * inv_step), -8, 7), product in fp32, ties to
+ *     even; step = alpha/7 (symmetric LQ of Sec. 3.1 on a signed 4-bit grid).
+ *   - LSTM gate rows are ordered i, f, g, o (rows [0,H), [H,2H), ...).
+ */
+#ifndef QRNNT_H
+#define QRNNT_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    QRNNT_OK = 0,
+    QRNNT_ERR_NULL = 1,        /* a required pointer is NULL */
+    QRNNT_ERR_SHAPE = 2,       /* a dimension is non-positive or violates a stated multiple */
+    QRNNT_ERR_ALIGN = 3,       /* a pointer violates its stated alignment */
+    QRNNT_ERR_RANGE = 4,       /* a scalar argument is outside its domain */
+    QRNNT_ERR_WORKSPACE = 5,   /* workspace too small */
+    QRNNT_ERR_LAYOUT = 6,      /* unknown or unsuitable weight layout */
+    QRNNT_ERR_UNSUPPORTED = 7, /* valid but not implemented for this size */
+    QRNNT_ERR_HIP = 8          /* the HIP runtime reported an error at launch */
+} qrnnt_status;
+
+const char *qrnnt_status_str(qrnnt_status s);
+uint32_t qrnnt_abi_version(void);
+
+/* Weight layouts.
+ * ROWMAJOR: byte j of row r holds element (r,2j) in bits 0-3 and (r,2j+1) in
+ *   bits 4-7 (two's complement); columns are zero-padded to cols_padded.
+ *   Exchange/test format; compute kernels do not read it.
+ * TILED: rows padded to a multiple of 16 and columns to a multiple of 128,
+ *   stored as 1 KiB blocks [row_tile][k_chunk]; inside a block, lane l of a
+ *   wavefront owns 16 bytes at offset 16*l whose dword d, byte b holds, in its
+ *   low nibble, W[16*row_tile + l%16][128*k_chunk + 16*(l/16) + 4*d + b] and,
+ *   in its high nibble, the element 64 columns further.  One 128-bit load per
+ *   lane thus yields two int8 MFMA operands after two mask/shift operations.
+ * TILED_GATES: TILED applied after permuting the 4H gate rows so that tiled
+ *   row 4*j + g is source row g*H + j: the four gates of a cell land in one
+ *   lane's accumulator quartet.  Row scales and biases stay in source order. */
+enum { QRNNT_LAYOUT_ROWMAJOR = 0, QRNNT_LAYOUT_TILED = 1, QRNNT_LAYOUT_TILED_GATES = 2 };
+enum { QRNNT_SRC_INT8_CODES = 0, QRNNT_SRC_FP32 = 1 };
+
+/* One quantized matrix: value[r,k] = row_scale[r] * code[r,k]. */
+typedef struct {
+    const void *packed;     /* [device] written by qrnnt_pack_int4, 16-byte aligned */
+    const float *row_scale; /* [device] [rows] fp32 */
+    int32_t rows, cols;     /* logical size */
+    int32_t layout;         /* QRNNT_LAYOUT_* */
+} qrnnt_qmat;
+
+/* One LSTM layer-direction (Sec. 3.2): both matrices in TILED_GATES layout,
+ * rows = 4*hidden_size. */
+typedef struct {
+    qrnnt_qmat w_ih;        /* [4H, I] */
+    qrnnt_qmat w_hh;        /* [4H, H] */
+    const float *bias;      /* [device] [4H] fp32, b_ih + b_hh, not quantized */
+    float x_scale;          /* step of the input codes */
+    float h_scale;          /* step of the hidden codes (FIX +-1: 1/7) */
+    float h_inv_scale;      /* 7/alpha of the hidden quantizer (FIX +-1: 7) */
+    int32_t input_size, hidden_size; /* both multiples of 16 */
+} qrnnt_lstm;
+
+/* ---- weights: quantize once, pack (Sec. 3.1 MAX per row + symmetric LQ; Sec. 3.2) ---- */
+
+/* Bytes of the packed blob for a rows x cols matrix in `layout`; 0 on bad arguments. */
+size_t qrnnt_pack_int4_bytes(int32_t rows, int32_t cols, int32_t layout);
+
+/* src [device]: rows x cols row-major, either int8 codes in [-8,7]
+ * (QRNNT_SRC_INT8_CODES; row_scale_out untouched, may be NULL) or fp32 weights
+ * (QRNNT_SRC_FP32; each row gets alpha = max|w|, row_scale_out[r] = alpha/7,
+ * code = clamp(rne(w * (7/alpha))); an all-zero row gets scale 1, codes 0).
+ * packed_out [device]: qrnnt_pack_int4_bytes bytes, 16-byte aligned, fully
+ * written (padding included).  TILED_GATES needs rows % 4 == 0. */
+qrnnt_status qrnnt_pack_int4(const void *src, int32_t src_dtype, int32_t rows, int32_t cols, int32_t layout,
+                             void *packed_out, float *row_scale_out, void *stream);
+
+/* Inverse of the packing, for tests: codes_out [device] rows x cols int8 in
+ * source row order. */
+qrnnt_status qrnnt_unpack_int4(const qrnnt_qmat *m, int8_t *codes_out, void *stream);
+
+/* ---- activations (Sec. 3.1 symmetric LQ with a FIX boundary, Sec. 3.2) ---- */
+
+/* q[i] = clamp(rne(x[i] * inv_scale), -8, 7); x, q [device], n elements. */
+qrnnt_status qrnnt_quantize_act(const float *x, int64_t n, float inv_scale, int8_t *q, void *stream);
+
+/* ---- quantized linear layer (Sec. 3.2: weights and inputs quantized) ---- */
+
+/* y[n,r] = a_scale * row_scale[r] * sum_k w[r,k]*a[n,k] + bias[r]; with
+ * log_softmax != 0 each row of y is replaced by its log-softmax (LM output
+ * layer, Sec. 2).  w: TILED layout.  a [device] [N, cols] int8, 16-byte aligned,
+ * cols % 16 == 0.  bias [device] [rows] or NULL.  y [device] [N, rows] fp32.
+ * dbg_acc [device] [N, rows] int32 or NULL.  log_softmax needs rows <= 64. */
+qrnnt_status qrnnt_linear(const qrnnt_qmat *w, const float *bias, float a_scale, const int8_t *a, int32_t N,
+                          int32_t log_softmax, float *y, int32_t *dbg_acc, void *stream);
+
+/* ---- LSTM: one step for a set of hypotheses (Sec. 3.2, Sec. 3.4) ---- */
+
+/* For n in [0,N): input row x_codes[x_row ? x_row[n] : n] (length I), previous
+ * state from slot s = parent ? parent[n] : n of h_prev/c_prev ([n_slots, H]);
+ *   pre = x_scale*s_wih[r]*accx + h_scale*s_whh[r]*acch + bias[r]   (fp32)
+ *   i,f,o = sigmoid, g = tanh, c' = f*c + i*g, h' = o*tanh(c'),
+ *   h_next[n] = Q(h'; h_inv_scale), c_next[n] = c'.
+ * Rows with active[n] == 0 copy slot s through unchanged.  h_next/c_next must
+ * not overlap h_prev/c_prev.  Optional debug outputs [device]: dbg_accx,
+ * dbg_acch int32 [N,4H], dbg_gates fp32 [N,4H] (activated i,f,g,o), all in
+ * source row order.  parent values are clamped to [0, n_slots). */
+qrnnt_status qrnnt_lstm_step(const qrnnt_lstm *L, const int8_t *x_codes, const int32_t *x_row, int32_t n_x_rows,
+                             const int32_t *parent, const int8_t *h_prev, const float *c_prev, int32_t n_slots,
+                             const uint8_t *active, int32_t N, int8_t *h_next, float *c_next,
+                             int32_t *dbg_accx, int32_t *dbg_acch, float *dbg_gates, void *stream);
+
+/* ---- LSTM: one layer-direction over whole utterances (Sec. 2 encoder, Sec. 3.4) ---- */
+
+size_t qrnnt_lstm_layer_workspace(const qrnnt_lstm *L, int32_t T, int32_t B);
+
+/* x_codes [device] [T,B,I] int8.  The input projection of all T*B frames is
+ * one integer GEMM; the recurrence then runs t = 0..T-1 (T-1..0 if reverse).
+ * Output codes go to h_out[(t*B + b)*ld_out + col_off + j], so the two
+ * directions of a bidirectional layer fill the two halves of [T,B,2H] (both
+ * use the FIX +-1 grid, Sec. 3.2).  h0/c0 [device] [B,H] or NULL (zero state,
+ * as Sec. 3.4 assumes).  h_last/c_last [device] [B,H] or NULL.  Debug
+ * [device] or NULL: dbg_accx int32 [T,B,4H] (source row order), dbg_c_all fp32
+ * [T,B,H].  All utterances have length T. */
+qrnnt_status qrnnt_lstm_layer(const qrnnt_lstm *L, const int8_t *x_codes, int32_t T, int32_t B, int32_t reverse,
+                              const int8_t *h0, const float *c0, int8_t *h_out, int32_t ld_out, int32_t col_off,
+                              int8_t *h_last, float *c_last, int32_t *dbg_accx, float *dbg_c_all,
+                              void *workspace, size_t workspace_bytes, void *stream);
+
+/* ---- joint network + log-softmax + Eq. 1 ---- */
+
+/* For n in [0,N): e = enc_proj[frame_row[n]], p = pred_proj[n] (length J);
+ *   z = tanh(e .* p); zq = Q(z; z_inv_scale);
+ *   logit[k] = z_scale*row_scale[k]*sum_j w_out[k,j]*zq[j] + b_out[k];
+ *   lp = log_softmax(logit);
+ *   fused[n,blank] = lp[blank];
+ *   fused[n,k] = lp[k] - lambda_src*lp_src[n,k] + lambda_ext*lp_ext[n,k] + rho  (k != blank).
+ * w_out: TILED layout, rows = V <= 64, cols = J (multiple of 64).  lp_src /
+ * lp_ext [device] [N,V] or NULL (term dropped).  Optional outputs [device]:
+ * lp_rnnt_out fp32 [N,V], dbg_zq int8 [N,J].  frame_row values are clamped to
+ * [0, n_enc_rows). */
+qrnnt_status qrnnt_joint_fuse(const float *enc_proj, int32_t n_enc_rows, const int32_t *frame_row,
+                              const float *pred_proj, const qrnnt_qmat *w_out, const float *b_out,
+                              float z_scale, float z_inv_scale, const float *lp_src, const float *lp_ext,
+                              float lambda_src, float lambda_ext, float rho, int32_t N, int32_t blank,
+                              float *lp_rnnt_out, int8_t *dbg_zq, float *fused_out, void *stream);
+
+/* ---- beam selection (Sec. 2: up to W hypotheses kept per iteration) ---- */
+
+/* Per utterance b: candidates (w,k) valued score[b,w] + fused[b*W+w,k] (fp32);
+ * the W best by (value descending, w*V+k ascending) are written best first to
+ * parent_out/token_out/score_out [B,W]; -inf candidates are never taken and
+ * unfilled ranks get parent = token = -1, score = -inf.  force_blank != 0
+ * restricts the candidates to k == blank.  W <= 64. */
+qrnnt_status qrnnt_beam_step(const float *score, const float *fused, int32_t B, int32_t W, int32_t V,
+                             int32_t blank, int32_t force_blank, int32_t *parent_out, int32_t *token_out,
+                             float *score_out, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* QRNNT_H */

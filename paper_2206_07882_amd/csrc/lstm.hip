@@ -1,0 +1,364 @@
+// Quantized LSTM cell: INT4 weights x INT4 activations on the int8 MFMA units
+// with the whole cell fused behind the contraction (Sec. 3.2: integer MACs for
+// W_ih and W_hh, fp bias and cell state; Sec. 3.4: the hidden state is
+// quantized once, at the cell output).
+#include "mma_core.h"
+
+namespace {
+
+struct StepArgs {
+    const v4i *wih, *whh;             // TILED_GATES blobs
+    const float *s_wih, *s_whh, *bias;
+    const int8_t *x;  int64_t ld_x;   // input codes, row pitch in bytes
+    const int32_t *x_row;  int n_x_rows;
+    const int32_t *gx;  int64_t ld_gx; // precomputed input projection [rows, 4H] in tiled-row order (or null)
+    const int32_t *parent;  int n_slots;
+    const int8_t *h_prev;  int64_t ld_hp;
+    const float *c_prev;
+    const uint8_t *active;
+    int8_t *h_next;  int64_t ld_hn;    // row pitch of the output codes
+    float *c_next;
+    int8_t *h_copy;                    // optional second copy of the output codes [N, H]
+    int32_t *dbg_accx, *dbg_acch;
+    float *dbg_gates;
+    int I, H, N, nkc_x, nkc_h;
+    float x_scale, h_scale, h_inv;
+};
+
+// Grid: x = groups of 4*MT row tiles (a wave owns MT tiles = 4*MT cells),
+//       y = groups of NT*16 hypotheses.  No LDS, no barriers.
+template <int MT, int NT, bool USE_GX>
+__global__ __launch_bounds__(256) void lstm_step_kernel(const StepArgs a)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int col = lane & 15, grp = lane >> 4;
+    const int n_row_tiles = a.H >> 2;   // 4H / 16
+    const int rt0 = (blockIdx.x * 4 + wave) * MT;
+    if (rt0 >= n_row_tiles) return;
+
+    int n_of[NT], src_of[NT];
+    const int8_t *xptr[NT], *hptr[NT];
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+        int n = (blockIdx.y * NT + nt) * 16 + col;
+        n_of[nt] = n;
+        int nn = n < a.N ? n : a.N - 1;
+        int s = a.parent ? a.parent[nn] : nn;
+        s = s < 0 ? 0 : (s >= a.n_slots ? a.n_slots - 1 : s);
+        src_of[nt] = s;
+        hptr[nt] = a.h_prev + (int64_t)s * a.ld_hp + grp * 16;
+        if (!USE_GX) {
+            int xr = a.x_row ? a.x_row[nn] : nn;
+            xr = xr < 0 ? 0 : (xr >= a.n_x_rows ? a.n_x_rows - 1 : xr);
+            xptr[nt] = a.x + (int64_t)xr * a.ld_x + grp * 16;
+        } else {
+            xptr[nt] = nullptr;
+        }
+    }
+
+    v4i acc[MT][NT];
+    float pre[MT][NT][4];
+    const v4i zero = {0, 0, 0, 0};
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) acc[mt][nt] = zero;
+
+    // ---- input part: s_x * s_wih[r] * accx
+    if (!USE_GX) qr_mma_range<MT, NT>(a.wih, a.nkc_x, n_row_tiles, rt0, lane, xptr, a.I, acc);
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+        const int j = (rt0 + mt) * 4 + grp;     // cell index; the lane's 4 accumulators are its gates i,f,g,o
+        const bool jv = j < a.H;
+        float sx[4];
+#pragma unroll
+        for (int g = 0; g < 4; ++g) sx[g] = jv ? a.x_scale * a.s_wih[g * a.H + j] : 0.0f;
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) {
+            v4i ax;
+            if (USE_GX) {
+                const int n = n_of[nt] < a.N ? n_of[nt] : a.N - 1;
+                ax = jv ? *(const v4i *)(a.gx + (int64_t)n * a.ld_gx + 4 * j) : zero;
+            } else {
+                ax = acc[mt][nt] >> 4;
+            }
+            if (a.dbg_accx && jv && n_of[nt] < a.N)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) a.dbg_accx[(int64_t)n_of[nt] * 4 * a.H + g * a.H + j] = ax[g];
+#pragma unroll
+            for (int g = 0; g < 4; ++g) pre[mt][nt][g] = sx[g] * (float)ax[g];
+            acc[mt][nt] = zero;
+        }
+    }
+
+    // ---- recurrent part: s_h * s_whh[r] * acch
+    qr_mma_range<MT, NT>(a.whh, a.nkc_h, n_row_tiles, rt0, lane, hptr, a.H, acc);
+
+    // ---- fused cell
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+        const int j = (rt0 + mt) * 4 + grp;
+        if (j >= a.H) continue;
+        float sh[4], bb[4];
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            sh[g] = a.h_scale * a.s_whh[g * a.H + j];
+            bb[g] = a.bias[g * a.H + j];
+        }
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) {
+            const int n = n_of[nt];
+            if (n >= a.N) continue;
+            const v4i ah = acc[mt][nt] >> 4;
+            const int s = src_of[nt];
+            const float cp = a.c_prev[(int64_t)s * a.H + j];
+            if (a.dbg_acch)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) a.dbg_acch[(int64_t)n * 4 * a.H + g * a.H + j] = ah[g];
+            int8_t code;
+            float cn;
+            if (a.active && !a.active[n]) {
+                code = a.h_prev[(int64_t)s * a.ld_hp + j];
+                cn = cp;
+            } else {
+                float p[4];
+#pragma unroll
+                for (int g = 0; g < 4; ++g) p[g] = pre[mt][nt][g] + (sh[g] * (float)ah[g] + bb[g]);
+                const float gi = qr_sigmoid(p[0]), gf = qr_sigmoid(p[1]), gg = tanhf(p[2]), go = qr_sigmoid(p[3]);
+                cn = gf * cp + gi * gg;
+                const float h = go * tanhf(cn);
+                code = (int8_t)qr_quant4(h, a.h_inv);
+                if (a.dbg_gates) {
+                    float *dg = a.dbg_gates + (int64_t)n * 4 * a.H + j;
+                    dg[0] = gi; dg[a.H] = gf; dg[2 * a.H] = gg; dg[3 * a.H] = go;
+                }
+            }
+            a.c_next[(int64_t)n * a.H + j] = cn;
+            a.h_next[(int64_t)n * a.ld_hn + j] = code;
+            if (a.h_copy) a.h_copy[(int64_t)n * a.H + j] = code;
+        }
+    }
+}
+
+template <bool USE_GX>
+void launch_step(const StepArgs &a, hipStream_t st)
+{
+    const int n_row_tiles = a.H >> 2;
+    if (a.N <= 16) {
+        dim3 grid((n_row_tiles + 3) / 4, 1);
+        lstm_step_kernel<1, 1, USE_GX><<<grid, 256, 0, st>>>(a);
+    } else if (a.N <= 32) {
+        dim3 grid((n_row_tiles + 3) / 4, 1);
+        lstm_step_kernel<1, 2, USE_GX><<<grid, 256, 0, st>>>(a);
+    } else {
+        dim3 grid((n_row_tiles + 7) / 8, (a.N + 63) / 64);
+        lstm_step_kernel<2, 4, USE_GX><<<grid, 256, 0, st>>>(a);
+    }
+}
+
+// Input projection of all frames: gx[m, 4j+g] = sum_k Wih[g*H+j, k] * x[m, k].
+// Output columns stay in tiled-row (gate-interleaved) order so that the step
+// kernel fetches a cell's four gate sums with one 128-bit load.
+template <int MT, int NT>
+__global__ __launch_bounds__(256) void gx_gemm_kernel(const v4i *__restrict__ wih, int nkc, int n_row_tiles,
+                                                       const int8_t *__restrict__ x, int64_t ld_x, int M, int K,
+                                                       int32_t *__restrict__ gx, int H, int32_t *__restrict__ dbg_accx)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int col = lane & 15, grp = lane >> 4;
+    // 2 x 2 waves: wave&1 along weight rows, wave>>1 along frames
+    const int rt0 = (blockIdx.x * 2 + (wave & 1)) * MT;
+    const int m0 = (blockIdx.y * 2 + (wave >> 1)) * NT * 16;
+    if (rt0 >= n_row_tiles || m0 >= M) return;
+    const int8_t *xptr[NT];
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+        int m = m0 + nt * 16 + col;
+        m = m < M ? m : M - 1;
+        xptr[nt] = x + (int64_t)m * ld_x + grp * 16;
+    }
+    v4i acc[MT][NT];
+    const v4i zero = {0, 0, 0, 0};
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) acc[mt][nt] = zero;
+    qr_mma_range<MT, NT>(wih, nkc, n_row_tiles, rt0, lane, xptr, K, acc);
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+        const int j = (rt0 + mt) * 4 + grp;
+        if (j >= H) continue;
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) {
+            const int m = m0 + nt * 16 + col;
+            if (m >= M) continue;
+            const v4i v = acc[mt][nt] >> 4;
+            *(v4i *)(gx + (int64_t)m * 4 * H + 4 * j) = v;
+            if (dbg_accx)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) dbg_accx[(int64_t)m * 4 * H + g * H + j] = v[g];
+        }
+    }
+}
+
+__global__ void fill_zero_kernel(uint32_t *p, size_t n_words)
+{
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n_words) p[i] = 0u;
+}
+
+qrnnt_status check_lstm(const qrnnt_lstm *L)
+{
+    QR_REQUIRE(L != nullptr, QRNNT_ERR_NULL);
+    qrnnt_status s = qr_check_qmat(&L->w_ih, QRNNT_LAYOUT_TILED_GATES);
+    if (s != QRNNT_OK) return s;
+    s = qr_check_qmat(&L->w_hh, QRNNT_LAYOUT_TILED_GATES);
+    if (s != QRNNT_OK) return s;
+    QR_REQUIRE(L->bias != nullptr, QRNNT_ERR_NULL);
+    QR_REQUIRE(L->input_size > 0 && L->hidden_size > 0, QRNNT_ERR_SHAPE);
+    QR_REQUIRE(L->input_size % 16 == 0 && L->hidden_size % 16 == 0, QRNNT_ERR_SHAPE);
+    QR_REQUIRE(L->w_ih.rows == 4 * L->hidden_size && L->w_hh.rows == 4 * L->hidden_size, QRNNT_ERR_SHAPE);
+    QR_REQUIRE(L->w_ih.cols == L->input_size && L->w_hh.cols == L->hidden_size, QRNNT_ERR_SHAPE);
+    QR_REQUIRE(L->x_scale > 0.0f && L->h_scale > 0.0f && L->h_inv_scale > 0.0f, QRNNT_ERR_RANGE);
+    return QRNNT_OK;
+}
+
+void fill_weights(StepArgs &a, const qrnnt_lstm *L)
+{
+    a.wih = (const v4i *)L->w_ih.packed;
+    a.whh = (const v4i *)L->w_hh.packed;
+    a.s_wih = L->w_ih.row_scale;
+    a.s_whh = L->w_hh.row_scale;
+    a.bias = L->bias;
+    a.I = L->input_size;
+    a.H = L->hidden_size;
+    a.nkc_x = qr_round_up(L->input_size, QRNNT_KCHUNK) / QRNNT_KCHUNK;
+    a.nkc_h = qr_round_up(L->hidden_size, QRNNT_KCHUNK) / QRNNT_KCHUNK;
+    a.x_scale = L->x_scale;
+    a.h_scale = L->h_scale;
+    a.h_inv = L->h_inv_scale;
+}
+
+}  // namespace
+
+extern "C" qrnnt_status qrnnt_lstm_step(const qrnnt_lstm *L, const int8_t *x_codes, const int32_t *x_row,
+                                        int32_t n_x_rows, const int32_t *parent, const int8_t *h_prev,
+                                        const float *c_prev, int32_t n_slots, const uint8_t *active, int32_t N,
+                                        int8_t *h_next, float *c_next, int32_t *dbg_accx, int32_t *dbg_acch,
+                                        float *dbg_gates, void *stream)
+{
+    qrnnt_status s = check_lstm(L);
+    if (s != QRNNT_OK) return s;
+    QR_REQUIRE(x_codes && h_prev && c_prev && h_next && c_next, QRNNT_ERR_NULL);
+    QR_REQUIRE(N > 0 && n_slots > 0 && n_x_rows > 0, QRNNT_ERR_SHAPE);
+    QR_REQUIRE(parent != nullptr || n_slots >= N, QRNNT_ERR_SHAPE);
+    QR_REQUIRE(x_row != nullptr || n_x_rows >= N, QRNNT_ERR_SHAPE);
+    QR_REQUIRE(qr_aligned(x_codes, 16) && qr_aligned(h_prev, 16), QRNNT_ERR_ALIGN);
+    QR_REQUIRE(qr_aligned(c_prev, 4) && qr_aligned(c_next, 4), QRNNT_ERR_ALIGN);
+    QR_REQUIRE((const void *)h_next != (const void *)h_prev && c_next != c_prev, QRNNT_ERR_RANGE);
+    StepArgs a = {};
+    fill_weights(a, L);
+    a.x = x_codes;  a.ld_x = L->input_size;  a.x_row = x_row;  a.n_x_rows = n_x_rows;
+    a.parent = parent;  a.n_slots = n_slots;
+    a.h_prev = h_prev;  a.ld_hp = L->hidden_size;  a.c_prev = c_prev;  a.active = active;
+    a.h_next = h_next;  a.ld_hn = L->hidden_size;  a.c_next = c_next;
+    a.dbg_accx = dbg_accx;  a.dbg_acch = dbg_acch;  a.dbg_gates = dbg_gates;
+    a.N = N;
+    launch_step<false>(a, (hipStream_t)stream);
+    return qr_launch_status();
+}
+
+// Workspace layout of qrnnt_lstm_layer:
+//   [0, gx_bytes)                int32 gx [T*B, 4H]
+//   then h state 2 x [B, H] int8 (rounded up to 256 B), c state 2 x [B, H] fp32.
+static size_t layer_ws_parts(const qrnnt_lstm *L, int T, int B, size_t *gx_b, size_t *h_b, size_t *c_b)
+{
+    const size_t H = (size_t)L->hidden_size;
+    *gx_b = ((size_t)T * B * 4 * H * sizeof(int32_t) + 255) / 256 * 256;
+    *h_b = ((size_t)B * H + 255) / 256 * 256;
+    *c_b = ((size_t)B * H * sizeof(float) + 255) / 256 * 256;
+    return *gx_b + 2 * *h_b + 2 * *c_b;
+}
+
+extern "C" size_t qrnnt_lstm_layer_workspace(const qrnnt_lstm *L, int32_t T, int32_t B)
+{
+    if (L == nullptr || T <= 0 || B <= 0 || L->hidden_size <= 0) return 0;
+    size_t g, h, c;
+    return layer_ws_parts(L, T, B, &g, &h, &c);
+}
+
+extern "C" qrnnt_status qrnnt_lstm_layer(const qrnnt_lstm *L, const int8_t *x_codes, int32_t T, int32_t B,
+                                         int32_t reverse, const int8_t *h0, const float *c0, int8_t *h_out,
+                                         int32_t ld_out, int32_t col_off, int8_t *h_last, float *c_last,
+                                         int32_t *dbg_accx, float *dbg_c_all, void *workspace, size_t workspace_bytes,
+                                         void *stream)
+{
+    qrnnt_status s = check_lstm(L);
+    if (s != QRNNT_OK) return s;
+    QR_REQUIRE(x_codes && h_out && workspace, QRNNT_ERR_NULL);
+    QR_REQUIRE(T > 0 && B > 0, QRNNT_ERR_SHAPE);
+    const int H = L->hidden_size, I = L->input_size;
+    QR_REQUIRE(col_off >= 0 && ld_out >= col_off + H, QRNNT_ERR_SHAPE);
+    QR_REQUIRE(ld_out % 16 == 0 && col_off % 16 == 0, QRNNT_ERR_SHAPE);
+    QR_REQUIRE(qr_aligned(x_codes, 16) && qr_aligned(h_out, 16) && qr_aligned(workspace, 256), QRNNT_ERR_ALIGN);
+    QR_REQUIRE(h0 == nullptr || qr_aligned(h0, 16), QRNNT_ERR_ALIGN);
+    size_t gx_b, h_b, c_b;
+    const size_t need = layer_ws_parts(L, T, B, &gx_b, &h_b, &c_b);
+    QR_REQUIRE(workspace_bytes >= need, QRNNT_ERR_WORKSPACE);
+    hipStream_t st = (hipStream_t)stream;
+
+    char *ws = (char *)workspace;
+    int32_t *gx = (int32_t *)ws;
+    int8_t *hbuf = (int8_t *)(ws + gx_b);           // [0]: zero / h0 staging is not needed: h0 is read in place
+    float *cbuf[2] = {(float *)(ws + gx_b + 2 * h_b), (float *)(ws + gx_b + 2 * h_b + c_b)};
+
+    // 1) input projection for all T*B frames
+    {
+        const int n_row_tiles = H >> 2;
+        const int nkc = qr_round_up(I, QRNNT_KCHUNK) / QRNNT_KCHUNK;
+        const int M = T * B;
+        dim3 grid((n_row_tiles + 7) / 8, (M + 127) / 128);
+        gx_gemm_kernel<4, 4><<<grid, 256, 0, st>>>((const v4i *)L->w_ih.packed, nkc, n_row_tiles, x_codes, I, M, I, gx,
+                                                   H, dbg_accx);
+    }
+    // 2) zero initial state where none is given
+    if (h0 == nullptr) {
+        const size_t nw = h_b / 4;
+        fill_zero_kernel<<<(unsigned)((nw + 255) / 256), 256, 0, st>>>((uint32_t *)hbuf, nw);
+    }
+    if (c0 == nullptr) {
+        const size_t nw = c_b / 4;
+        fill_zero_kernel<<<(unsigned)((nw + 255) / 256), 256, 0, st>>>((uint32_t *)cbuf[0], nw);
+    }
+    // 3) the recurrence, one fused launch per time step
+    StepArgs a = {};
+    fill_weights(a, L);
+    a.ld_gx = 4 * (int64_t)H;
+    a.n_slots = B;
+    a.N = B;
+    a.ld_hn = ld_out;
+    const float *c_prev = c0 ? c0 : cbuf[0];
+    int cur = c0 ? 0 : 1;   // next c buffer to write
+    for (int step = 0; step < T; ++step) {
+        const int t = reverse ? T - 1 - step : step;
+        a.gx = gx + (int64_t)t * B * 4 * H;
+        if (step == 0) {
+            a.h_prev = h0 ? h0 : hbuf;
+            a.ld_hp = H;
+        } else {
+            const int tp = reverse ? t + 1 : t - 1;
+            a.h_prev = h_out + (int64_t)tp * B * ld_out + col_off;
+            a.ld_hp = ld_out;
+        }
+        a.c_prev = c_prev;
+        a.c_next = dbg_c_all ? dbg_c_all + (int64_t)t * B * H : cbuf[cur];
+        a.h_next = h_out + (int64_t)t * B * ld_out + col_off;
+        a.h_copy = (step == T - 1) ? h_last : nullptr;
+        launch_step<true>(a, st);
+        c_prev = a.c_next;
+        cur ^= 1;
+    }
+    if (c_last)
+        (void)hipMemcpyAsync(c_last, c_prev, (size_t)B * H * sizeof(float), hipMemcpyDeviceToDevice, st);
+    return qr_launch_status();
+}

@@ -1,0 +1,68 @@
+// Internal helpers shared by the HIP translation units of libqrnnt (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "qrnnt.h"
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef float v4f __attribute__((ext_vector_type(4)));
+
+#define QRNNT_WAVE 64
+#define QRNNT_KCHUNK 128        // columns covered by one 1 KiB tiled block
+#define QRNNT_BLOCK_BYTES 1024  // 16 rows x 128 nibbles
+
+__host__ __device__ static inline int qr_round_up(int a, int b) { return (a + b - 1) / b * b; }
+static inline bool qr_aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+
+#define QR_REQUIRE(cond, err) \
+    do {                      \
+        if (!(cond)) return (err); \
+    } while (0)
+
+static inline qrnnt_status qr_launch_status() { return hipGetLastError() == hipSuccess ? QRNNT_OK : QRNNT_ERR_HIP; }
+
+// Host-side validation of a packed-matrix descriptor used by a compute kernel.
+static inline qrnnt_status qr_check_qmat(const qrnnt_qmat *m, int want_layout)
+{
+    QR_REQUIRE(m != nullptr && m->packed != nullptr && m->row_scale != nullptr, QRNNT_ERR_NULL);
+    QR_REQUIRE(m->rows > 0 && m->cols > 0, QRNNT_ERR_SHAPE);
+    QR_REQUIRE(m->layout == want_layout, QRNNT_ERR_LAYOUT);
+    QR_REQUIRE(qr_aligned(m->packed, 16), QRNNT_ERR_ALIGN);
+    return QRNNT_OK;
+}
+
+#ifdef __HIPCC__
+
+// Splits one 128-bit packed fragment into two int8x16 MFMA operands.  Each
+// nibble is moved to the top half of its byte, i.e. the operand holds 16*w as a
+// signed int8 with no sign-extension work; accumulators therefore hold 16*acc
+// and are shifted right by 4 (exact) once per tile.
+__device__ __forceinline__ void qr_unpack(v4i p, v4i &lo, v4i &hi)
+{
+    const int m = (int)0xF0F0F0F0u;
+    hi = p & m;
+    lo = (p << 4) & m;
+}
+
+// D[16 x 16] += A[16 x 64] * B[64 x 16], int8 in, int32 out.  Lane l supplies
+// row l%16 of A and column l%16 of B for the 16-wide K slice l/16, and receives
+// D[4*(l/16) + i][l%16] in element i of the result.
+__device__ __forceinline__ v4i qr_mfma(v4i a, v4i b, v4i c)
+{
+    return __builtin_amdgcn_mfma_i32_16x16x64_i8(a, b, c, 0, 0, 0);
+}
+
+__device__ __forceinline__ float qr_sigmoid(float v) { return 1.0f / (1.0f + expf(-v)); }
+
+// Symmetric 4-bit quantizer: clamp(rne(x * inv_step)), product in fp32.
+__device__ __forceinline__ int qr_quant4(float x, float inv_step)
+{
+    float t = x * inv_step;
+    float r = __builtin_rintf(t);
+    r = fminf(fmaxf(r, -8.0f), 7.0f);
+    return (int)r;
+}
+
+#endif  // __HIPCC__

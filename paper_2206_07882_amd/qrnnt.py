@@ -1,0 +1,246 @@
+"""ctypes binding of libqrnnt.so: argument marshalling only.
+
+Every function takes torch tensors that already live on the GPU (torch is used
+for device memory and streams, nothing else), checks dtype/contiguity, passes
+raw pointers across the C ABI and raises :class:`QrnntError` on a non-zero
+status.  There is no fallback: if the library is not built, :func:`load`
+raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libqrnnt.so")
+
+LAYOUT_ROWMAJOR, LAYOUT_TILED, LAYOUT_TILED_GATES = 0, 1, 2
+SRC_INT8_CODES, SRC_FP32 = 0, 1
+
+_lib = None
+
+
+class QrnntError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        msg = load().qrnnt_status_str(status).decode()
+        super().__init__(f"{where}: {msg} (status {status})")
+
+
+class CQMat(C.Structure):
+    _fields_ = [("packed", C.c_void_p), ("row_scale", C.c_void_p), ("rows", C.c_int32), ("cols", C.c_int32),
+                ("layout", C.c_int32)]
+
+
+class CLstm(C.Structure):
+    _fields_ = [("w_ih", CQMat), ("w_hh", CQMat), ("bias", C.c_void_p), ("x_scale", C.c_float),
+                ("h_scale", C.c_float), ("h_inv_scale", C.c_float), ("input_size", C.c_int32),
+                ("hidden_size", C.c_int32)]
+
+
+EXPORTS = ["qrnnt_status_str", "qrnnt_abi_version", "qrnnt_pack_int4_bytes", "qrnnt_pack_int4", "qrnnt_unpack_int4",
+           "qrnnt_quantize_act", "qrnnt_linear", "qrnnt_lstm_step", "qrnnt_lstm_layer_workspace", "qrnnt_lstm_layer",
+           "qrnnt_joint_fuse", "qrnnt_beam_step"]
+
+
+def load():
+    """Loads the built library; raises if it is missing (no CPU fallback exists)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is not built: run `python -m paper_2206_07882_amd.build`")
+        lib = C.CDLL(LIB_PATH)
+        lib.qrnnt_status_str.restype = C.c_char_p
+        lib.qrnnt_status_str.argtypes = [C.c_int]
+        lib.qrnnt_abi_version.restype = C.c_uint32
+        lib.qrnnt_pack_int4_bytes.restype = C.c_size_t
+        lib.qrnnt_pack_int4_bytes.argtypes = [C.c_int32, C.c_int32, C.c_int32]
+        lib.qrnnt_lstm_layer_workspace.restype = C.c_size_t
+        lib.qrnnt_lstm_layer_workspace.argtypes = [C.c_void_p, C.c_int32, C.c_int32]
+        _lib = lib
+    return _lib
+
+
+def _ptr(t: Optional[torch.Tensor], dtype=None):
+    if t is None:
+        return None
+    if dtype is not None and t.dtype != dtype:
+        raise TypeError(f"expected {dtype}, got {t.dtype}")
+    if not t.is_contiguous():
+        raise ValueError("tensor must be contiguous")
+    return C.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _check(status: int, where: str):
+    if status != 0:
+        raise QrnntError(status, where)
+
+
+def pack_bytes(rows: int, cols: int, layout: int) -> int:
+    return int(load().qrnnt_pack_int4_bytes(rows, cols, layout))
+
+
+class QMat:
+    """A packed INT4 matrix on the device plus its per-row scales."""
+
+    def __init__(self, packed: torch.Tensor, row_scale: torch.Tensor, rows: int, cols: int, layout: int):
+        self.packed, self.row_scale, self.rows, self.cols, self.layout = packed, row_scale, rows, cols, layout
+
+    def c(self) -> CQMat:
+        return CQMat(self.packed.data_ptr(), self.row_scale.data_ptr(), self.rows, self.cols, self.layout)
+
+
+def pack_int4(src: torch.Tensor, layout: int, row_scale: Optional[torch.Tensor] = None) -> QMat:
+    """fp32 weights (quantized per row) or int8 codes (row_scale given by the caller) -> QMat."""
+    assert src.dim() == 2 and src.is_cuda
+    rows, cols = src.shape
+    nbytes = pack_bytes(rows, cols, layout)
+    if nbytes == 0:
+        _check(2, "qrnnt_pack_int4_bytes")
+    packed = torch.empty(nbytes, dtype=torch.uint8, device=src.device)
+    if src.dtype == torch.float32:
+        scale = torch.empty(rows, dtype=torch.float32, device=src.device)
+        st = load().qrnnt_pack_int4(_ptr(src), SRC_FP32, rows, cols, layout, _ptr(packed), _ptr(scale), _stream())
+    elif src.dtype == torch.int8:
+        scale = row_scale if row_scale is not None else torch.ones(rows, dtype=torch.float32, device=src.device)
+        st = load().qrnnt_pack_int4(_ptr(src), SRC_INT8_CODES, rows, cols, layout, _ptr(packed), None, _stream())
+    else:
+        raise TypeError("src must be float32 or int8")
+    _check(st, "qrnnt_pack_int4")
+    return QMat(packed, scale, rows, cols, layout)
+
+
+def unpack_int4(m: QMat) -> torch.Tensor:
+    out = torch.empty((m.rows, m.cols), dtype=torch.int8, device=m.packed.device)
+    cm = m.c()
+    _check(load().qrnnt_unpack_int4(C.byref(cm), _ptr(out), _stream()), "qrnnt_unpack_int4")
+    return out
+
+
+def quantize_act(x: torch.Tensor, inv_scale: float) -> torch.Tensor:
+    q = torch.empty(x.shape, dtype=torch.int8, device=x.device)
+    _check(load().qrnnt_quantize_act(_ptr(x, torch.float32), C.c_int64(x.numel()), C.c_float(inv_scale), _ptr(q),
+                                     _stream()), "qrnnt_quantize_act")
+    return q
+
+
+def linear(w: QMat, bias: Optional[torch.Tensor], a_scale: float, a: torch.Tensor, log_softmax: bool = False,
+           want_acc: bool = False):
+    N = a.shape[0]
+    y = torch.empty((N, w.rows), dtype=torch.float32, device=a.device)
+    acc = torch.empty((N, w.rows), dtype=torch.int32, device=a.device) if want_acc else None
+    cw = w.c()
+    _check(load().qrnnt_linear(C.byref(cw), _ptr(bias, torch.float32), C.c_float(a_scale), _ptr(a, torch.int8),
+                               C.c_int32(N), C.c_int32(1 if log_softmax else 0), _ptr(y), _ptr(acc), _stream()),
+           "qrnnt_linear")
+    return (y, acc) if want_acc else y
+
+
+class Lstm:
+    """One LSTM layer-direction on the device (TILED_GATES weights, fp32 bias)."""
+
+    def __init__(self, w_ih: QMat, w_hh: QMat, bias: torch.Tensor, x_scale: float, h_scale: float = 1.0 / 7.0,
+                 h_inv_scale: float = 7.0):
+        self.w_ih, self.w_hh, self.bias = w_ih, w_hh, bias
+        self.I, self.H = w_ih.cols, w_hh.cols
+        self.x_scale, self.h_scale, self.h_inv_scale = float(x_scale), float(h_scale), float(h_inv_scale)
+
+    def c(self) -> CLstm:
+        return CLstm(self.w_ih.c(), self.w_hh.c(), self.bias.data_ptr(), self.x_scale, self.h_scale,
+                     self.h_inv_scale, self.I, self.H)
+
+
+def lstm_step(L: Lstm, x_codes, h_prev, c_prev, N: Optional[int] = None, x_row=None, parent=None, active=None,
+              debug: bool = False):
+    dev = h_prev.device
+    if N is None:
+        N = x_row.shape[0] if x_row is not None else x_codes.shape[0]
+    H = L.H
+    h_next = torch.empty((N, H), dtype=torch.int8, device=dev)
+    c_next = torch.empty((N, H), dtype=torch.float32, device=dev)
+    accx = acch = gates = None
+    if debug:
+        accx = torch.zeros((N, 4 * H), dtype=torch.int32, device=dev)
+        acch = torch.zeros((N, 4 * H), dtype=torch.int32, device=dev)
+        gates = torch.zeros((N, 4 * H), dtype=torch.float32, device=dev)
+    cl = L.c()
+    st = load().qrnnt_lstm_step(C.byref(cl), _ptr(x_codes, torch.int8), _ptr(x_row, torch.int32),
+                                C.c_int32(x_codes.shape[0]), _ptr(parent, torch.int32), _ptr(h_prev, torch.int8),
+                                _ptr(c_prev, torch.float32), C.c_int32(h_prev.shape[0]), _ptr(active, torch.uint8),
+                                C.c_int32(N), _ptr(h_next), _ptr(c_next), _ptr(accx), _ptr(acch), _ptr(gates), _stream())
+    _check(st, "qrnnt_lstm_step")
+    if debug:
+        return h_next, c_next, dict(accx=accx, acch=acch, gates=gates)
+    return h_next, c_next
+
+
+def lstm_layer_workspace(L: Lstm, T: int, B: int) -> int:
+    cl = L.c()
+    return int(load().qrnnt_lstm_layer_workspace(C.byref(cl), T, B))
+
+
+def lstm_layer(L: Lstm, x_codes: torch.Tensor, reverse: bool = False, h0=None, c0=None, h_out=None, col_off: int = 0,
+               want_last: bool = False, debug: bool = False, workspace: Optional[torch.Tensor] = None):
+    T, B, I = x_codes.shape
+    dev = x_codes.device
+    H = L.H
+    if h_out is None:
+        h_out = torch.zeros((T, B, H), dtype=torch.int8, device=dev)
+        col_off = 0
+    ld = h_out.shape[2]
+    need = lstm_layer_workspace(L, T, B)
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=dev)
+    h_last = torch.empty((B, H), dtype=torch.int8, device=dev) if want_last else None
+    c_last = torch.empty((B, H), dtype=torch.float32, device=dev) if want_last else None
+    accx = torch.zeros((T, B, 4 * H), dtype=torch.int32, device=dev) if debug else None
+    c_all = torch.zeros((T, B, H), dtype=torch.float32, device=dev) if debug else None
+    cl = L.c()
+    st = load().qrnnt_lstm_layer(C.byref(cl), _ptr(x_codes, torch.int8), C.c_int32(T), C.c_int32(B),
+                                 C.c_int32(1 if reverse else 0), _ptr(h0, torch.int8), _ptr(c0, torch.float32),
+                                 _ptr(h_out, torch.int8), C.c_int32(ld), C.c_int32(col_off), _ptr(h_last), _ptr(c_last),
+                                 _ptr(accx), _ptr(c_all), _ptr(workspace), C.c_size_t(workspace.numel()), _stream())
+    _check(st, "qrnnt_lstm_layer")
+    return dict(h_out=h_out, h_last=h_last, c_last=c_last, accx=accx, c_all=c_all)
+
+
+def joint_fuse(enc_proj, frame_row, pred_proj, w_out: QMat, b_out, lp_src, lp_ext, lambda_src: float,
+               lambda_ext: float, rho: float = 0.0, blank: int = 0, z_scale: float = 1.0 / 7.0,
+               z_inv_scale: float = 7.0, want_lp: bool = False, want_zq: bool = False):
+    N, J = pred_proj.shape
+    V = w_out.rows
+    dev = pred_proj.device
+    enc2 = enc_proj.reshape(-1, J)
+    fused = torch.empty((N, V), dtype=torch.float32, device=dev)
+    lp = torch.empty((N, V), dtype=torch.float32, device=dev) if want_lp else None
+    zq = torch.zeros((N, J), dtype=torch.int8, device=dev) if want_zq else None
+    cw = w_out.c()
+    st = load().qrnnt_joint_fuse(_ptr(enc2, torch.float32), C.c_int32(enc2.shape[0]), _ptr(frame_row, torch.int32),
+                                 _ptr(pred_proj, torch.float32), C.byref(cw), _ptr(b_out, torch.float32),
+                                 C.c_float(z_scale), C.c_float(z_inv_scale), _ptr(lp_src, torch.float32),
+                                 _ptr(lp_ext, torch.float32), C.c_float(lambda_src), C.c_float(lambda_ext),
+                                 C.c_float(rho), C.c_int32(N), C.c_int32(blank), _ptr(lp), _ptr(zq), _ptr(fused),
+                                 _stream())
+    _check(st, "qrnnt_joint_fuse")
+    return fused, lp, zq
+
+
+def beam_step(score: torch.Tensor, fused: torch.Tensor, blank: int = 0, force_blank: bool = False):
+    B, W = score.shape
+    V = fused.shape[-1]
+    dev = score.device
+    par = torch.empty((B, W), dtype=torch.int32, device=dev)
+    tok = torch.empty((B, W), dtype=torch.int32, device=dev)
+    ns = torch.empty((B, W), dtype=torch.float32, device=dev)
+    st = load().qrnnt_beam_step(_ptr(score, torch.float32), _ptr(fused, torch.float32), C.c_int32(B), C.c_int32(W),
+                                C.c_int32(V), C.c_int32(blank), C.c_int32(1 if force_blank else 0), _ptr(par),
+                                _ptr(tok), _ptr(ns), _stream())
+    _check(st, "qrnnt_beam_step")
+    return par, tok, ns

@@ -1,0 +1,276 @@
+"""Parity of the HIP path with the CPU oracle, call by call through the C ABI.
+
+Every kernel is fed the same seeded inputs as the oracle (teacher forcing: a
+rounding tie in one step cannot leak into the next comparison).  Bars:
+int32 accumulators, packed bytes, codes of weights/inputs and beam selections
+are bit-exact; fp32 gates and cell states within 1e-5 relative (+1e-6 absolute
+at zero crossings); requantised hidden codes agree on >= 99.99 % of entries and
+differ by one code only where the real value sits on a rounding tie; log-probs
+and fused scores within 1e-3 absolute (observed ~1e-6).
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from oracle import models
+from paper_2206_07882_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+S_H = float(np.float32(1) / np.float32(7))
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).to(DEV)
+
+
+def host(t):
+    return t.detach().cpu().numpy()
+
+
+def assert_codes_close(got, ref, real, what, min_agree=0.9999):
+    """Codes equal except at rounding ties of `real` (= value * inv_step, fp64)."""
+    got = got.astype(np.int32); ref = ref.astype(np.int32)
+    bad = got != ref
+    frac = 1.0 - bad.mean()
+    assert frac >= min_agree, f"{what}: only {frac:.6f} of codes agree"
+    if bad.any():
+        assert np.abs(got - ref)[bad].max() == 1, f"{what}: code differs by more than 1"
+        dist = np.abs(real[bad] - np.floor(real[bad]) - 0.5)
+        assert dist.max() < 1e-4, f"{what}: mismatch away from a rounding tie ({dist.max()})"
+
+
+def assert_rel(got, ref, what, rtol=1e-5, atol=1e-6):
+    err = np.abs(got.astype(np.float64) - ref.astype(np.float64))
+    lim = rtol * np.abs(ref.astype(np.float64)) + atol
+    assert np.all(err <= lim), f"{what}: max excess {np.max(err - lim):.3e}"
+
+
+# ------------------------------------------------------------------ pack / quantize
+
+@pytest.mark.parametrize("rows,cols", [(64, 32), (256, 64), (2560, 240), (48, 256), (46, 256), (16, 32), (4, 16)])
+def test_pack_roundtrip_and_canonical_bytes(gpu_lib, rows, cols):
+    q = gpu_lib
+    codes = synth.codes(11 + rows + cols, (rows, cols), -8, 7)
+    for layout in (q.LAYOUT_ROWMAJOR, q.LAYOUT_TILED, q.LAYOUT_TILED_GATES):
+        m = q.pack_int4(dev(codes), layout)
+        assert np.array_equal(host(q.unpack_int4(m)), codes), f"layout {layout}"
+        if layout == q.LAYOUT_ROWMAJOR:
+            cp = (cols + 63) // 64 * 64
+            assert np.array_equal(host(m.packed).reshape(rows, cp // 2), oracle.pack_rows(codes, cp))
+
+
+@pytest.mark.parametrize("rows,cols", [(64, 32), (3072, 768), (46, 256)])
+def test_pack_from_fp32_matches_oracle_quantizer(gpu_lib, rows, cols):
+    q = gpu_lib
+    w = synth.normal(21 + rows, (rows, cols), 1.0 / np.sqrt(cols))
+    w[1, :] = 0.0                      # an all-zero row
+    w[2, 3] = np.abs(w[2]).max() * 0.5  # an exact tie at 3.5 steps
+    ref_codes, ref_scale = oracle.quantize_weight_rows(w)
+    for layout in (q.LAYOUT_TILED, q.LAYOUT_ROWMAJOR) + ((q.LAYOUT_TILED_GATES,) if rows % 4 == 0 else ()):
+        m = q.pack_int4(dev(w), layout)
+        assert np.array_equal(host(q.unpack_int4(m)), ref_codes)
+        assert np.array_equal(host(m.row_scale), ref_scale)
+
+
+def test_quantize_act_bit_exact_including_ties(gpu_lib):
+    q = gpu_lib
+    x = synth.normal(31, (500 * 3 * 240 + 3,), 1.0)
+    x[:9] = np.array([0.5, 1.5, 2.5, -0.5, -1.5, 100.0, -100.0, 0.0, 6.5], np.float32) * np.float32(4.0 / 7.0)
+    inv = float(np.float32(7) / np.float32(4))
+    n = x.size - 3
+    # aligned body and a ragged tail
+    assert np.array_equal(host(q.quantize_act(dev(x[:n]), inv)), oracle.quant_sym4(x[:n], inv))
+    assert np.array_equal(host(q.quantize_act(dev(x[:n - 1]), inv)), oracle.quant_sym4(x[:n - 1], inv))
+    assert np.array_equal(host(q.quantize_act(dev(x[:5]), 1.0)), oracle.quant_sym4(x[:5], 1.0))
+
+
+# ------------------------------------------------------------------ linear
+
+@pytest.mark.parametrize("rows,cols,N,lsm", [(256, 1280, 300, False), (256, 768, 16, False), (32, 64, 5, False),
+                                             (46, 1024, 1024, True), (46, 1024, 16, True), (16, 64, 4, True),
+                                             (46, 256, 37, False)])
+def test_linear_parity(gpu_lib, rows, cols, N, lsm):
+    q = gpu_lib
+    w = synth.normal(41 + rows, (rows, cols), 1.0 / np.sqrt(cols))
+    b = synth.normal(42 + rows, (rows,), 0.1)
+    a = synth.codes(43 + N, (N, cols), -8, 7)
+    P = oracle.Linear.from_float(w, b, S_H)
+    m = q.pack_int4(dev(w), q.LAYOUT_TILED)
+    y, acc = q.linear(m, dev(b), S_H, dev(a), log_softmax=lsm, want_acc=True)
+    ry, racc = oracle.linear(P, a, want_acc=True)
+    assert np.array_equal(host(acc), racc)
+    if lsm:
+        assert np.abs(host(y) - oracle.log_softmax(ry)).max() < 2e-5
+    else:
+        assert_rel(host(y), ry, "linear y")
+
+
+# ------------------------------------------------------------------ LSTM step
+
+def _lstm_pair(q, seed, I, H, s_x, std=None):
+    sd_i = std if std is not None else 1.0 / np.sqrt(I)
+    sd_h = std if std is not None else 1.0 / np.sqrt(H)
+    w_ih = synth.normal(seed, (4 * H, I), sd_i)
+    w_hh = synth.normal(seed + 1, (4 * H, H), sd_h)
+    bias = synth.normal(seed + 2, (4 * H,), 0.1)
+    L = oracle.Lstm.from_float(w_ih, w_hh, bias, s_x, S_H, 7.0)
+    G = q.Lstm(q.pack_int4(dev(w_ih), q.LAYOUT_TILED_GATES), q.pack_int4(dev(w_hh), q.LAYOUT_TILED_GATES), dev(bias),
+               float(np.float32(s_x)), S_H, 7.0)
+    return L, G
+
+
+def _check_step(dbg_g, hn_g, cn_g, ref, what):
+    hn_r, cn_r, dbg_r = ref
+    assert np.array_equal(host(dbg_g["accx"]), dbg_r["accx"]), what + " accx"
+    assert np.array_equal(host(dbg_g["acch"]), dbg_r["acch"]), what + " acch"
+    assert_rel(host(dbg_g["gates"]), dbg_r["gates"], what + " gates")
+    assert_rel(host(cn_g), cn_r, what + " c")
+    assert_codes_close(host(hn_g), hn_r, dbg_r["h_real"] * 7.0, what + " h codes")
+
+
+@pytest.mark.parametrize("I,H,N", [(64, 64, 4), (32, 64, 2), (768, 768, 16), (256, 1024, 16), (1024, 1024, 37),
+                                   (240, 640, 32), (1280, 640, 1)])
+def test_lstm_step_parity_plain(gpu_lib, I, H, N):
+    q = gpu_lib
+    s_x = float(np.float32(1.25) / np.float32(7))
+    L, G = _lstm_pair(q, 51 + I + H, I, H, s_x)
+    x = synth.codes(52 + N, (N, I), -8, 7)
+    hp = synth.codes(53 + N, (N, H), -7, 7)
+    cp = synth.normal(54 + N, (N, H), 0.7)
+    hn, cn, dbg = q.lstm_step(G, dev(x), dev(hp), dev(cp), debug=True)
+    _check_step(dbg, hn, cn, oracle.lstm_step(L, x, hp, cp, debug=True), f"step {I}x{H}x{N}")
+
+
+def test_lstm_step_parity_beam_shape_with_gather_and_mask(gpu_lib):
+    """Prediction-network shape at 64 utterances x beam 16: embedding rows picked
+    by token id, previous state picked by parent slot, blank-extended rows masked."""
+    q = gpu_lib
+    I = H = 768
+    B, W, V = 64, 16, 46
+    N = B * W
+    s_x = float(np.float32(1.25) / np.float32(7))
+    L, G = _lstm_pair(q, 61, I, H, s_x)
+    emb = synth.codes(62, (V, I), -7, 7)
+    tok = synth.token_ids(63, (N,), V)
+    parent = synth.parent_perm(64, B, W)
+    active = (np.random.default_rng(65).random(N) < 0.6).astype(np.uint8)
+    hp = synth.codes(66, (N, H), -7, 7)
+    cp = synth.normal(67, (N, H), 0.7)
+    hn, cn, dbg = q.lstm_step(G, dev(emb), dev(hp), dev(cp), x_row=dev(tok), parent=dev(parent), active=dev(active),
+                              debug=True)
+    hn, cn = host(hn), host(cn)
+    # the oracle checks a sample of rows one by one (rows are independent given their parent)
+    rows = np.random.default_rng(68).choice(N, 96, replace=False)
+    ref = oracle.lstm_step(L, emb[tok[rows]], hp[parent[rows]], cp[parent[rows]], active=active[rows], debug=True)
+    act = active[rows].astype(bool)
+    assert np.array_equal(host(dbg["accx"])[rows][act], ref[2]["accx"][act])
+    assert np.array_equal(host(dbg["acch"])[rows][act], ref[2]["acch"][act])
+    assert_rel(host(dbg["gates"])[rows][act], ref[2]["gates"][act], "gates")
+    assert_rel(cn[rows], ref[1], "c")
+    assert_codes_close(hn[rows][act], ref[0][act], (ref[2]["h_real"] * 7.0)[act], "h codes")
+    # masked rows are exact copies of the parent slot, over the whole batch
+    ina = active == 0
+    assert np.array_equal(hn[ina], hp[parent[ina]]) and np.array_equal(cn[ina], cp[parent[ina]])
+
+
+def test_lstm_step_extreme_codes_no_overflow(gpu_lib):
+    """All weights at code 7/-7 against all activations at -8: the largest |sum|."""
+    q = gpu_lib
+    I, H, N = 2048, 64, 16
+    w_ih = np.full((4 * H, I), -8, np.int8); w_ih[::2] = 7
+    w_hh = np.full((4 * H, H), -8, np.int8)
+    ones = np.ones(4 * H, np.float32) * np.float32(1e-3)
+    bias = np.zeros(4 * H, np.float32)
+    L = oracle.Lstm(w_ih, ones, w_hh, ones, bias, 0.01, S_H, 7.0)
+    G = q.Lstm(q.pack_int4(dev(w_ih), q.LAYOUT_TILED_GATES, dev(ones)),
+               q.pack_int4(dev(w_hh), q.LAYOUT_TILED_GATES, dev(ones)), dev(bias), 0.01, S_H, 7.0)
+    x = np.full((N, I), -8, np.int8)
+    hp = np.full((N, H), -8, np.int8)
+    cp = np.zeros((N, H), np.float32)
+    hn, cn, dbg = q.lstm_step(G, dev(x), dev(hp), dev(cp), debug=True)
+    ref = oracle.lstm_step(L, x, hp, cp, debug=True)
+    assert np.array_equal(host(dbg["accx"]), ref[2]["accx"]) and host(dbg["accx"]).max() == 64 * I
+    assert host(dbg["accx"]).min() == -56 * I
+    assert np.array_equal(host(dbg["acch"]), ref[2]["acch"])
+
+
+# ------------------------------------------------------------------ LSTM layer
+
+@pytest.mark.parametrize("T,B,I,H,reverse", [(20, 2, 32, 64, False), (7, 3, 32, 64, True), (12, 32, 240, 640, False),
+                                             (9, 32, 1280, 640, True), (16, 1, 240, 640, False)])
+def test_lstm_layer_parity(gpu_lib, T, B, I, H, reverse):
+    """Whole-utterance layer: input-projection GEMM bit-exact; then every time step
+    is checked against one oracle step fed the GPU's own previous state, so a tie
+    flip cannot cascade; the free-running oracle layer is compared as well."""
+    q = gpu_lib
+    s_x = float(np.float32(4) / np.float32(7)) if I in (32, 240) else S_H
+    L, G = _lstm_pair(q, 71 + I + H, I, H, s_x)
+    x = synth.codes(72 + T, (T, B, I), -8, 7)
+    ld, off = 2 * H + 16, 16
+    h_out = torch.full((T, B, ld), 55, dtype=torch.int8, device=DEV)
+    out = q.lstm_layer(G, dev(x), reverse=reverse, h_out=h_out, col_off=off, want_last=True, debug=True)
+    hg = host(out["h_out"]); cg = host(out["c_all"])
+    assert np.all(hg[:, :, :off] == 55) and np.all(hg[:, :, off + H:] == 55)
+    hg = hg[:, :, off:off + H]
+    assert np.array_equal(host(out["accx"]).reshape(T * B, 4 * H), oracle.matmul_i32(L.w_ih, x.reshape(T * B, I)))
+    order = range(T - 1, -1, -1) if reverse else range(T)
+    hp = np.zeros((B, H), np.int8); cp = np.zeros((B, H), np.float32)
+    for t in order:
+        hr, cr, dbg = oracle.lstm_step(L, x[t], hp, cp, debug=True)
+        assert_rel(cg[t], cr, f"c t={t}")
+        assert_codes_close(hg[t], hr, dbg["h_real"] * 7.0, f"h t={t}")
+        hp, cp = hg[t], cg[t]
+    assert np.array_equal(host(out["h_last"]), hp) and np.array_equal(host(out["c_last"]), cp)
+    free, _, _, _ = oracle.lstm_layer(L, x, reverse=reverse)
+    agree = (free == hg).mean()
+    assert agree >= (1.0 if T * B * H < 5000 else 0.999), f"free-running agreement {agree}"
+
+
+# ------------------------------------------------------------------ joint + fusion, beam
+
+@pytest.mark.parametrize("N,J,V,TB,lms", [(4, 32, 16, 40, True), (1024, 256, 46, 32000, True), (37, 256, 46, 100, True),
+                                          (16, 256, 46, 500, False)])
+def test_joint_fuse_parity(gpu_lib, N, J, V, TB, lms):
+    q = gpu_lib
+    e = synth.normal(81 + N, (TB, J), 1.0)
+    p = synth.normal(82 + N, (N, J), 1.0)
+    fr = np.random.default_rng(83 + N).integers(0, TB, N).astype(np.int32)
+    w = synth.normal(84 + N, (V, J), 1.0 / np.sqrt(J) * 3)
+    b = synth.normal(85 + N, (V,), 0.1)
+    ls = synth.log_probs(86 + N, N, V) if lms else None
+    le = synth.log_probs(87 + N, N, V) if lms else None
+    out = oracle.Linear.from_float(w, b, S_H)
+    m = q.pack_int4(dev(w), q.LAYOUT_TILED)
+    fused, lp, zq = q.joint_fuse(dev(e), dev(fr), dev(p), m, dev(b), None if ls is None else dev(ls),
+                                 None if le is None else dev(le), 0.3, 0.5, rho=0.2, want_lp=True, want_zq=True)
+    zq_r, z_real = oracle.joint_z(e, fr, p, 7.0)
+    assert_codes_close(host(zq), zq_r, z_real * 7.0, "z codes")
+    # second half from the GPU's own codes: a z tie cannot hide or fake an error downstream
+    lp_r, f_r = oracle.joint_out(out, host(zq), ls, le, 0.3, 0.5, rho=0.2, blank=0)
+    assert np.abs(host(lp) - lp_r).max() < 1e-3 and np.abs(host(fused) - f_r).max() < 1e-3
+    assert np.abs(host(fused) - f_r).max() < 2e-5     # what the arithmetic actually gives
+    same = np.all(host(zq) == zq_r, axis=1)
+    _, _, f_full = oracle.joint_fuse(e, fr, p, out, ls, le, 0.3, 0.5, rho=0.2)
+    assert same.mean() > 0.99 and np.abs(host(fused)[same] - f_full[same]).max() < 1e-3
+
+
+@pytest.mark.parametrize("B,W,V", [(2, 2, 16), (64, 16, 46), (3, 5, 7), (1, 16, 46)])
+def test_beam_step_exact(gpu_lib, B, W, V):
+    q = gpu_lib
+    rng = np.random.default_rng(91 + B)
+    score = rng.standard_normal((B, W)).astype(np.float32) * 3
+    fused = synth.log_probs(92 + B, B * W, V)
+    if W > 2:
+        score[0, W // 2:] = -np.inf                 # dead slots
+        score[B - 1, 1:] = -np.inf                  # one live hypothesis only
+    fused[0, 1] = fused[0, 3]                       # a tie inside one parent
+    if W > 1:
+        score[0, 1] = score[0, 0]; fused[1] = fused[0]   # ties across parents
+    for force in (False, True):
+        got = q.beam_step(dev(score), dev(fused), blank=0, force_blank=force)
+        ref = oracle.beam_step(score, fused, blank=0, force_blank=force)
+        for g, r, name in zip(got, ref, ("parent", "token", "score")):
+            assert np.array_equal(host(g), r), f"{name} force={force}"
