@@ -182,6 +182,55 @@ qrnnt_status qrnnt_beam_step(const float *score, const float *fused, int32_t B, 
                              int32_t blank, int32_t force_blank, int32_t *parent_out, int32_t *token_out,
                              float *score_out, void *stream);
 
+/* ---- the whole decoding loop on the device (Sec. 2; Eq. 1) ---- */
+
+#define QRNNT_MAX_LAYERS 4
+
+/* Embedding -> quantizer -> stacked LSTM steps -> quantized linear layer: the
+ * prediction network (log_softmax = 0, output = the joint's prediction input)
+ * or a language model (log_softmax = 1, output = log-probabilities). */
+typedef struct {
+    const int8_t *embed_codes;  /* [device] [V, E] embedding rows already quantized (FIX boundary, Sec. 3.2) */
+    int32_t n_layers;           /* 1..QRNNT_MAX_LAYERS; layer[0].input_size = E */
+    qrnnt_lstm layer[QRNNT_MAX_LAYERS];
+    qrnnt_qmat out;             /* TILED, [out_rows, H_top] */
+    const float *out_bias;      /* [device] [out_rows] or NULL */
+    float out_a_scale;          /* step of the top layer's hidden codes */
+    int32_t log_softmax;
+} qrnnt_net;
+
+typedef struct {
+    qrnnt_net pred, lm_src, lm_ext;
+    int32_t use_src, use_ext;   /* 0 drops the LM and its term of Eq. 1 */
+    qrnnt_qmat joint_out;       /* TILED, [V, J] */
+    const float *joint_bias;    /* [device] [V] or NULL */
+    float z_scale, z_inv_scale; /* quantizer of the joint activation */
+    float lambda_src, lambda_ext, rho;
+    int32_t V, blank;           /* blank doubles as the start symbol fed to all networks */
+} qrnnt_model;
+
+size_t qrnnt_decode_workspace(const qrnnt_model *m, int32_t T, int32_t B, int32_t W, int32_t max_sym);
+
+/* Time-synchronous beam search over enc_proj [device] [T,B,J] fp32, every
+ * utterance of length T, W hypotheses per utterance, at most max_sym labels per
+ * frame.  Per utterance: the beam starts as the empty sequence (score 0, all
+ * networks advanced once on the start symbol from the zero state).  Per frame:
+ * A <- beam; for round v = 0..max_sym: fused scores of A at this frame
+ * (qrnnt_joint_fuse), the W best extensions (qrnnt_beam_step, blank only when
+ * v == max_sym); blank picks join the frame's candidate list with their new
+ * score, label picks form the next A with all networks advanced from the
+ * parent's state (qrnnt_lstm_step with parent gather); after the last round the
+ * beam becomes the W best candidates by (score descending, insertion order).
+ * Equal label sequences are not merged.  All rounds always run (dead slots carry
+ * score -inf), so the launch sequence does not depend on the data and nothing
+ * is copied to the host.
+ * Outputs [device], best first: tokens_out int32 [B,W,max_len] (padded with
+ * -1), len_out int32 [B,W] (-1 for an empty rank), score_out fp32 [B,W].
+ * workspace [device]: qrnnt_decode_workspace bytes, 256-byte aligned. */
+qrnnt_status qrnnt_decode(const qrnnt_model *m, const float *enc_proj, int32_t T, int32_t B, int32_t W,
+                          int32_t max_sym, int32_t max_len, int32_t *tokens_out, int32_t *len_out, float *score_out,
+                          void *workspace, size_t workspace_bytes, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -1,7 +1,7 @@
 // Beam selection: per utterance the W best (parent, token) extensions (Sec. 2:
 // the beam width is the number of hypotheses kept per decoding iteration).
 // Selection runs on the GPU so that the decoding loop never returns to the host.
-#include "qrnnt_common.h"
+#include "kernels.h"
 
 namespace {
 
@@ -53,6 +53,12 @@ __global__ __launch_bounds__(64) void beam_step_kernel(const float *__restrict__
 
 }  // namespace
 
+void qr_launch_beam(const float *score, const float *fused, int B, int W, int V, int blank, int force_blank,
+                    int32_t *parent_out, int32_t *token_out, float *score_out, hipStream_t st)
+{
+    beam_step_kernel<<<B, 64, 0, st>>>(score, fused, W, V, blank, force_blank, parent_out, token_out, score_out);
+}
+
 extern "C" qrnnt_status qrnnt_beam_step(const float *score, const float *fused, int32_t B, int32_t W, int32_t V,
                                         int32_t blank, int32_t force_blank, int32_t *parent_out, int32_t *token_out,
                                         float *score_out, void *stream)
@@ -61,7 +67,6 @@ extern "C" qrnnt_status qrnnt_beam_step(const float *score, const float *fused, 
     QR_REQUIRE(B > 0 && W > 0 && V > 0, QRNNT_ERR_SHAPE);
     QR_REQUIRE(W <= 64, QRNNT_ERR_UNSUPPORTED);
     QR_REQUIRE(blank >= 0 && blank < V, QRNNT_ERR_RANGE);
-    beam_step_kernel<<<B, 64, 0, (hipStream_t)stream>>>(score, fused, W, V, blank, force_blank, parent_out, token_out,
-                                                        score_out);
+    qr_launch_beam(score, fused, B, W, V, blank, force_blank, parent_out, token_out, score_out, (hipStream_t)stream);
     return qr_launch_status();
 }

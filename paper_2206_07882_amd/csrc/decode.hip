@@ -1,0 +1,427 @@
+// The decoding loop, entirely on the device: joint + fusion (Eq. 1), beam
+// selection, hypothesis bookkeeping and the advance of the prediction network
+// and both language models (Sec. 2).  The paper's simulated system sorts
+// hypotheses on an attached CPU and is limited by the link to it (Sec. 4.1);
+// here the selection and the bookkeeping are kernels and the host only enqueues
+// a data-independent launch sequence.
+#include "kernels.h"
+
+namespace {
+
+constexpr int MAX_TENSORS = 32;
+
+struct NetBuf {
+    int8_t *h[QRNNT_MAX_LAYERS];   // [NB][N][H]
+    float *c[QRNNT_MAX_LAYERS];    // [NB][N][H]
+    float *y;                      // [NB][N][out_rows]
+};
+
+struct Plan {
+    int T, B, W, N, R, NB, V, J, max_sym;
+    NetBuf net[3];
+    float *score;        // [NB][B][W]
+    int32_t *node, *len; // [NB][N]
+    float *fused;        // [N][V]
+    int32_t *sel_parent, *sel_token;  float *sel_score;   // [B][W]
+    int32_t *parent_idx, *token;  uint8_t *active;        // [N]
+    float *nx_score;  int32_t *nx_src;  int32_t *nx_count; // [B][R*W], [B]
+    int32_t *beam_src;   // [N]
+    int32_t *node_tok, *node_prev;   // [1 + T*max_sym*N]
+    size_t total;
+};
+
+struct Carver {
+    char *base;  size_t off;
+    template <typename Tp> Tp *take(size_t n)
+    {
+        off = (off + 255) / 256 * 256;
+        Tp *p = base ? (Tp *)(base + off) : nullptr;
+        off += n * sizeof(Tp);
+        return p;
+    }
+};
+
+const qrnnt_net *net_of(const qrnnt_model *m, int k) { return k == 0 ? &m->pred : (k == 1 ? &m->lm_src : &m->lm_ext); }
+bool net_used(const qrnnt_model *m, int k) { return k == 0 || (k == 1 ? m->use_src != 0 : m->use_ext != 0); }
+
+void make_plan(const qrnnt_model *m, int T, int B, int W, int max_sym, void *ws, Plan &p)
+{
+    p.T = T; p.B = B; p.W = W; p.N = B * W; p.max_sym = max_sym;
+    p.R = max_sym + 1; p.NB = max_sym + 2; p.V = m->V; p.J = m->joint_out.cols;
+    Carver cv{(char *)ws, 0};
+    const size_t N = (size_t)p.N, NB = (size_t)p.NB;
+    for (int k = 0; k < 3; ++k) {
+        if (!net_used(m, k)) continue;
+        const qrnnt_net *net = net_of(m, k);
+        for (int l = 0; l < net->n_layers; ++l) {
+            p.net[k].h[l] = cv.take<int8_t>(NB * N * net->layer[l].hidden_size);
+            p.net[k].c[l] = cv.take<float>(NB * N * net->layer[l].hidden_size);
+        }
+        p.net[k].y = cv.take<float>(NB * N * net->out.rows);
+    }
+    p.score = cv.take<float>(NB * N);
+    p.node = cv.take<int32_t>(NB * N);
+    p.len = cv.take<int32_t>(NB * N);
+    p.fused = cv.take<float>(N * p.V);
+    p.sel_parent = cv.take<int32_t>(N);
+    p.sel_token = cv.take<int32_t>(N);
+    p.sel_score = cv.take<float>(N);
+    p.parent_idx = cv.take<int32_t>(N);
+    p.token = cv.take<int32_t>(N);
+    p.active = cv.take<uint8_t>(N);
+    p.nx_score = cv.take<float>((size_t)B * p.R * W);
+    p.nx_src = cv.take<int32_t>((size_t)B * p.R * W);
+    p.nx_count = cv.take<int32_t>(B);
+    p.beam_src = cv.take<int32_t>(N);
+    const size_t pool = 1 + (size_t)T * max_sym * N;
+    p.node_tok = cv.take<int32_t>(pool);
+    p.node_prev = cv.take<int32_t>(pool);
+    p.total = (cv.off + 255) / 256 * 256;
+}
+
+__global__ void fill_words_kernel(uint32_t *p, size_t n_words, uint32_t v)
+{
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n_words) p[i] = v;
+}
+
+// Start of an utterance: slot 0 holds the empty sequence with score 0, every slot
+// is fed the start symbol from the zero state.
+__global__ void decode_init_kernel(float *score0, int32_t *node0, int32_t *len0, int32_t *parent_idx, int32_t *token,
+                                   uint8_t *active, int32_t *nx_count, int32_t *node_tok, int32_t *node_prev, int N,
+                                   int W, int B, int start_symbol)
+{
+    const int n = blockIdx.x * blockDim.x + threadIdx.x;
+    if (n == 0) { node_tok[0] = -1; node_prev[0] = 0; }
+    if (n < B) nx_count[n] = 0;
+    if (n >= N) return;
+    score0[n] = (n % W == 0) ? 0.0f : -INFINITY;
+    node0[n] = 0;
+    len0[n] = 0;
+    parent_idx[n] = n;
+    token[n] = start_symbol;
+    active[n] = 1;
+}
+
+// After the selection of round v: blank picks join the frame's candidate list,
+// label picks become the slots of the next round, in selection order.
+__global__ void route_kernel(const int32_t *__restrict__ sel_parent, const int32_t *__restrict__ sel_token,
+                             const float *__restrict__ sel_score, int B, int W, int R, int blank, int src_buf,
+                             int last_round, const int32_t *__restrict__ node_src, const int32_t *__restrict__ len_src,
+                             float *__restrict__ score_dst, int32_t *__restrict__ node_dst, int32_t *__restrict__ len_dst,
+                             int32_t *__restrict__ parent_idx, int32_t *__restrict__ token, uint8_t *__restrict__ active,
+                             float *__restrict__ nx_score, int32_t *__restrict__ nx_src, int32_t *__restrict__ nx_count,
+                             int32_t *__restrict__ node_tok, int32_t *__restrict__ node_prev, int node_base)
+{
+    const int b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b >= B) return;
+    const int N = B * W;
+    int n_nx = nx_count[b], n_a = 0;
+    for (int r = 0; r < W; ++r) {
+        const int par = sel_parent[b * W + r];
+        if (par < 0) break;
+        const int tok = sel_token[b * W + r];
+        const float sc = sel_score[b * W + r];
+        const int src_slot = b * W + par;
+        if (tok == blank) {
+            nx_score[(size_t)b * R * W + n_nx] = sc;
+            nx_src[(size_t)b * R * W + n_nx] = src_buf * N + src_slot;
+            ++n_nx;
+        } else if (!last_round) {
+            const int dst = b * W + n_a;
+            const int id = node_base + dst;
+            node_tok[id] = tok;
+            node_prev[id] = node_src[src_slot];
+            score_dst[dst] = sc;
+            node_dst[dst] = id;
+            len_dst[dst] = len_src[src_slot] + 1;
+            parent_idx[dst] = src_slot;
+            token[dst] = tok;
+            active[dst] = 1;
+            ++n_a;
+        }
+    }
+    nx_count[b] = n_nx;
+    if (!last_round)
+        for (int a = n_a; a < W; ++a) {
+            const int dst = b * W + a;
+            score_dst[dst] = -INFINITY;
+            node_dst[dst] = 0;
+            len_dst[dst] = 0;
+            parent_idx[dst] = dst;
+            token[dst] = blank;
+            active[dst] = 0;
+        }
+}
+
+__device__ __forceinline__ bool better(float v, int c, float bv, int bc) { return v > bv || (v == bv && c < bc); }
+
+// End of a frame: the new beam is the W best candidates by (score descending,
+// insertion order).  One wave per utterance.
+__global__ __launch_bounds__(64) void frame_end_kernel(const float *__restrict__ nx_score, const int32_t *__restrict__ nx_src,
+                                                        int32_t *__restrict__ nx_count, int W, int R, int N,
+                                                        const int32_t *node_all, const int32_t *len_all,
+                                                        int dst_buf, float *__restrict__ score_all,
+                                                        int32_t *node_all_w, int32_t *len_all_w,
+                                                        int32_t *__restrict__ beam_src)
+{
+    const int b = blockIdx.x, lane = threadIdx.x;
+    const int cnt = nx_count[b];
+    const float *sc = nx_score + (size_t)b * R * W;
+    float last_v = INFINITY;
+    int last_c = -1;
+    bool exhausted = false;
+    for (int r = 0; r < W; ++r) {
+        float bv = -INFINITY;
+        int bc = 0x7fffffff;
+        if (!exhausted) {
+            for (int c = lane; c < cnt; c += 64) {
+                const float v = sc[c];
+                const bool after = v < last_v || (v == last_v && c > last_c);
+                if (after && better(v, c, bv, bc)) { bv = v; bc = c; }
+            }
+#pragma unroll
+            for (int off = 32; off > 0; off >>= 1) {
+                const float ov = __shfl_xor(bv, off);
+                const int oc = __shfl_xor(bc, off);
+                if (better(ov, oc, bv, bc)) { bv = ov; bc = oc; }
+            }
+        }
+        const bool found = bc != 0x7fffffff;
+        if (lane == 0) {
+            const int dst = b * W + r;
+            if (found) {
+                const int src = nx_src[(size_t)b * R * W + bc];
+                score_all[(size_t)dst_buf * N + dst] = bv;
+                node_all_w[(size_t)dst_buf * N + dst] = node_all[src];
+                len_all_w[(size_t)dst_buf * N + dst] = len_all[src];
+                beam_src[dst] = src;
+            } else {
+                score_all[(size_t)dst_buf * N + dst] = -INFINITY;
+                node_all_w[(size_t)dst_buf * N + dst] = 0;
+                len_all_w[(size_t)dst_buf * N + dst] = 0;
+                beam_src[dst] = -1;
+            }
+        }
+        if (found) { last_v = bv; last_c = bc; } else { exhausted = true; }
+    }
+    __syncthreads();
+    if (lane == 0) nx_count[b] = 0;
+}
+
+struct GatherTable {
+    char *base[MAX_TENSORS];
+    int row_bytes[MAX_TENSORS];
+    int n;
+};
+
+// New beam slot n takes the state rows of its source (buffer, slot); an empty
+// rank keeps whatever the destination holds (its score is -inf).
+__global__ __launch_bounds__(64) void gather_state_kernel(const GatherTable tb, const int32_t *__restrict__ beam_src, int N,
+                                                           int dst_buf)
+{
+    const int n = blockIdx.x, t = blockIdx.y;
+    const int src = beam_src[n];
+    if (src < 0) return;
+    const int rb = tb.row_bytes[t];
+    const uint32_t *s = (const uint32_t *)(tb.base[t] + (size_t)src * rb);
+    uint32_t *d = (uint32_t *)(tb.base[t] + ((size_t)dst_buf * N + n) * rb);
+    for (int i = threadIdx.x; i < rb / 4; i += 64) d[i] = s[i];
+}
+
+__global__ void backtrack_kernel(const float *__restrict__ score, const int32_t *__restrict__ node,
+                                 const int32_t *__restrict__ len, const int32_t *__restrict__ node_tok,
+                                 const int32_t *__restrict__ node_prev, int N, int max_len,
+                                 int32_t *__restrict__ tokens_out, int32_t *__restrict__ len_out, float *__restrict__ score_out)
+{
+    const int n = blockIdx.x * blockDim.x + threadIdx.x;
+    if (n >= N) return;
+    const float sc = score[n];
+    const bool live = sc > -INFINITY;
+    const int L = live ? len[n] : 0;
+    int32_t *out = tokens_out + (size_t)n * max_len;
+    for (int i = (L < max_len ? L : max_len); i < max_len; ++i) out[i] = -1;
+    int id = node[n];
+    for (int i = L - 1; i >= 0; --i) {
+        if (i < max_len) out[i] = node_tok[id];
+        id = node_prev[id];
+    }
+    len_out[n] = live ? L : -1;
+    score_out[n] = sc;
+}
+
+qrnnt_status check_net(const qrnnt_net *net, int V, int out_rows)
+{
+    QR_REQUIRE(net->embed_codes != nullptr, QRNNT_ERR_NULL);
+    QR_REQUIRE(net->n_layers >= 1 && net->n_layers <= QRNNT_MAX_LAYERS, QRNNT_ERR_RANGE);
+    QR_REQUIRE(qr_aligned(net->embed_codes, 16), QRNNT_ERR_ALIGN);
+    for (int l = 0; l < net->n_layers; ++l) {
+        qrnnt_status s = qr_check_lstm(&net->layer[l]);
+        if (s != QRNNT_OK) return s;
+        if (l > 0) QR_REQUIRE(net->layer[l].input_size == net->layer[l - 1].hidden_size, QRNNT_ERR_SHAPE);
+    }
+    qrnnt_status s = qr_check_qmat(&net->out, QRNNT_LAYOUT_TILED);
+    if (s != QRNNT_OK) return s;
+    QR_REQUIRE(net->out.cols == net->layer[net->n_layers - 1].hidden_size, QRNNT_ERR_SHAPE);
+    QR_REQUIRE(net->out.rows == out_rows, QRNNT_ERR_SHAPE);
+    QR_REQUIRE(!net->log_softmax || net->out.rows <= 64, QRNNT_ERR_UNSUPPORTED);
+    QR_REQUIRE(net->out_a_scale > 0.0f, QRNNT_ERR_RANGE);
+    (void)V;
+    return QRNNT_OK;
+}
+
+qrnnt_status check_model(const qrnnt_model *m)
+{
+    QR_REQUIRE(m != nullptr, QRNNT_ERR_NULL);
+    qrnnt_status s = qr_check_qmat(&m->joint_out, QRNNT_LAYOUT_TILED);
+    if (s != QRNNT_OK) return s;
+    QR_REQUIRE(m->V > 0 && m->V <= 64 && m->joint_out.rows == m->V, QRNNT_ERR_SHAPE);
+    QR_REQUIRE(m->joint_out.cols % 16 == 0, QRNNT_ERR_SHAPE);
+    QR_REQUIRE(m->blank >= 0 && m->blank < m->V, QRNNT_ERR_RANGE);
+    QR_REQUIRE(m->z_scale > 0.0f && m->z_inv_scale > 0.0f, QRNNT_ERR_RANGE);
+    s = check_net(&m->pred, m->V, m->joint_out.cols);
+    if (s != QRNNT_OK) return s;
+    QR_REQUIRE(!m->pred.log_softmax, QRNNT_ERR_RANGE);
+    if (m->use_src) { s = check_net(&m->lm_src, m->V, m->V); if (s != QRNNT_OK) return s; }
+    if (m->use_ext) { s = check_net(&m->lm_ext, m->V, m->V); if (s != QRNNT_OK) return s; }
+    return QRNNT_OK;
+}
+
+// All used networks consume `token` and move from buffer src to buffer dst.
+void advance_nets(const qrnnt_model *m, const Plan &p, int src, int dst, int n_embed_rows, hipStream_t st)
+{
+    const size_t N = (size_t)p.N;
+    for (int k = 0; k < 3; ++k) {
+        if (!net_used(m, k)) continue;
+        const qrnnt_net *net = net_of(m, k);
+        for (int l = 0; l < net->n_layers; ++l) {
+            const qrnnt_lstm *L = &net->layer[l];
+            const size_t H = (size_t)L->hidden_size;
+            QrStepArgs a = {};
+            qr_fill_lstm_weights(a, L);
+            if (l == 0) {
+                a.x = net->embed_codes;  a.ld_x = L->input_size;  a.x_row = p.token;  a.n_x_rows = n_embed_rows;
+            } else {
+                a.x = p.net[k].h[l - 1] + (size_t)dst * N * L->input_size;  a.ld_x = L->input_size;
+                a.x_row = nullptr;  a.n_x_rows = p.N;
+            }
+            a.parent = p.parent_idx;  a.n_slots = p.N;
+            a.h_prev = p.net[k].h[l] + (size_t)src * N * H;  a.ld_hp = (int64_t)H;
+            a.c_prev = p.net[k].c[l] + (size_t)src * N * H;
+            a.active = p.active;
+            a.h_next = p.net[k].h[l] + (size_t)dst * N * H;  a.ld_hn = (int64_t)H;
+            a.c_next = p.net[k].c[l] + (size_t)dst * N * H;
+            a.N = p.N;
+            qr_launch_lstm_step(a, false, st);
+        }
+        const int top = net->n_layers - 1;
+        QrLinearArgs la = {};
+        la.w = (const v4i *)net->out.packed;
+        la.nkc = qr_round_up(net->out.cols, QRNNT_KCHUNK) / QRNNT_KCHUNK;
+        la.rows = net->out.rows;  la.s_w = net->out.row_scale;  la.bias = net->out_bias;  la.a_scale = net->out_a_scale;
+        la.act = p.net[k].h[top] + (size_t)dst * N * net->out.cols;  la.K = net->out.cols;  la.N = p.N;
+        la.y = p.net[k].y + (size_t)dst * N * net->out.rows;  la.log_softmax = net->log_softmax;
+        qr_launch_linear(la, st);
+    }
+}
+
+}  // namespace
+
+extern "C" size_t qrnnt_decode_workspace(const qrnnt_model *m, int32_t T, int32_t B, int32_t W, int32_t max_sym)
+{
+    if (check_model(m) != QRNNT_OK || T <= 0 || B <= 0 || W <= 0 || W > 64 || max_sym < 0) return 0;
+    Plan p;
+    make_plan(m, T, B, W, max_sym, nullptr, p);
+    return p.total;
+}
+
+extern "C" qrnnt_status qrnnt_decode(const qrnnt_model *m, const float *enc_proj, int32_t T, int32_t B, int32_t W,
+                                     int32_t max_sym, int32_t max_len, int32_t *tokens_out, int32_t *len_out,
+                                     float *score_out, void *workspace, size_t workspace_bytes, void *stream)
+{
+    qrnnt_status s = check_model(m);
+    if (s != QRNNT_OK) return s;
+    QR_REQUIRE(enc_proj && tokens_out && len_out && score_out && workspace, QRNNT_ERR_NULL);
+    QR_REQUIRE(T > 0 && B > 0 && W > 0 && max_len > 0, QRNNT_ERR_SHAPE);
+    QR_REQUIRE(W <= 64, QRNNT_ERR_UNSUPPORTED);
+    QR_REQUIRE(max_sym >= 0 && max_sym <= 16, QRNNT_ERR_RANGE);
+    QR_REQUIRE((double)T * (max_sym > 0 ? max_sym : 1) * B * W < 2.0e9, QRNNT_ERR_UNSUPPORTED);
+    QR_REQUIRE(qr_aligned(enc_proj, 16) && qr_aligned(workspace, 256), QRNNT_ERR_ALIGN);
+    Plan p;
+    make_plan(m, T, B, W, max_sym, workspace, p);
+    QR_REQUIRE(workspace_bytes >= p.total, QRNNT_ERR_WORKSPACE);
+    hipStream_t st = (hipStream_t)stream;
+    const int N = p.N, V = p.V;
+    const size_t Ns = (size_t)N;
+    const int ZB = p.NB - 1;   // second A0 buffer; holds the zero state before the first frame
+    const int n_embed_rows = V;
+
+    // zero state in buffer ZB, then every slot consumes the start symbol into buffer 0
+    for (int k = 0; k < 3; ++k) {
+        if (!net_used(m, k)) continue;
+        const qrnnt_net *net = net_of(m, k);
+        for (int l = 0; l < net->n_layers; ++l) {
+            const size_t H = (size_t)net->layer[l].hidden_size;
+            size_t nw = Ns * H / 4;
+            fill_words_kernel<<<(unsigned)((nw + 255) / 256), 256, 0, st>>>((uint32_t *)(p.net[k].h[l] + (size_t)ZB * Ns * H), nw, 0u);
+            nw = Ns * H;
+            fill_words_kernel<<<(unsigned)((nw + 255) / 256), 256, 0, st>>>((uint32_t *)(p.net[k].c[l] + (size_t)ZB * Ns * H), nw, 0u);
+        }
+    }
+    decode_init_kernel<<<(N + 255) / 256 + 1, 256, 0, st>>>(p.score, p.node, p.len, p.parent_idx, p.token, p.active,
+                                                            p.nx_count, p.node_tok, p.node_prev, N, W, B, m->blank);
+    advance_nets(m, p, ZB, 0, n_embed_rows, st);
+
+    GatherTable tb = {};
+    for (int k = 0; k < 3; ++k) {
+        if (!net_used(m, k)) continue;
+        const qrnnt_net *net = net_of(m, k);
+        for (int l = 0; l < net->n_layers; ++l) {
+            tb.base[tb.n] = (char *)p.net[k].h[l];  tb.row_bytes[tb.n++] = net->layer[l].hidden_size;
+            tb.base[tb.n] = (char *)p.net[k].c[l];  tb.row_bytes[tb.n++] = net->layer[l].hidden_size * 4;
+        }
+        tb.base[tb.n] = (char *)p.net[k].y;  tb.row_bytes[tb.n++] = net->out.rows * 4;
+    }
+
+    QrJointArgs ja = {};
+    ja.enc = enc_proj;  ja.n_enc_rows = T * B;  ja.frame_row = nullptr;  ja.rows_per_utt = W;
+    ja.w = (const v4i *)m->joint_out.packed;  ja.s_w = m->joint_out.row_scale;  ja.b_out = m->joint_bias;
+    ja.z_scale = m->z_scale;  ja.z_inv = m->z_inv_scale;
+    ja.lambda_src = m->lambda_src;  ja.lambda_ext = m->lambda_ext;  ja.rho = m->rho;
+    ja.N = N;  ja.J = p.J;  ja.V = V;  ja.blank = m->blank;
+    ja.nkc = qr_round_up(p.J, QRNNT_KCHUNK) / QRNNT_KCHUNK;
+    ja.fused = p.fused;
+
+    int a0 = 0;   // buffer of the beam at the current frame
+    for (int t = 0; t < T; ++t) {
+        for (int v = 0; v <= max_sym; ++v) {
+            const int cur = (v == 0) ? a0 : v;
+            const int nxt = v + 1;   // only used when v < max_sym
+            ja.frame_base = t * B;
+            ja.pred = p.net[0].y + (size_t)cur * Ns * p.J;
+            ja.lp_src = m->use_src ? p.net[1].y + (size_t)cur * Ns * V : nullptr;
+            ja.lp_ext = m->use_ext ? p.net[2].y + (size_t)cur * Ns * V : nullptr;
+            qr_launch_joint(ja, st);
+            qr_launch_beam(p.score + (size_t)cur * Ns, p.fused, B, W, V, m->blank, v == max_sym, p.sel_parent,
+                           p.sel_token, p.sel_score, st);
+            const int last = (v == max_sym);
+            const int node_base = 1 + (t * max_sym + v) * N;
+            route_kernel<<<(B + 63) / 64, 64, 0, st>>>(p.sel_parent, p.sel_token, p.sel_score, B, W, p.R, m->blank, cur, last,
+                                                       p.node + (size_t)cur * Ns, p.len + (size_t)cur * Ns,
+                                                       p.score + (size_t)nxt * Ns, p.node + (size_t)nxt * Ns,
+                                                       p.len + (size_t)nxt * Ns, p.parent_idx, p.token, p.active,
+                                                       p.nx_score, p.nx_src, p.nx_count, p.node_tok, p.node_prev,
+                                                       node_base);
+            if (!last) advance_nets(m, p, cur, nxt, n_embed_rows, st);
+        }
+        const int dst = (a0 == 0) ? ZB : 0;
+        frame_end_kernel<<<B, 64, 0, st>>>(p.nx_score, p.nx_src, p.nx_count, W, p.R, N, p.node, p.len, dst, p.score,
+                                           p.node, p.len, p.beam_src);
+        gather_state_kernel<<<dim3(N, tb.n), 64, 0, st>>>(tb, p.beam_src, N, dst);
+        a0 = dst;
+    }
+    backtrack_kernel<<<(N + 63) / 64, 64, 0, st>>>(p.score + (size_t)a0 * Ns, p.node + (size_t)a0 * Ns,
+                                                   p.len + (size_t)a0 * Ns, p.node_tok, p.node_prev, N, max_len,
+                                                   tokens_out, len_out, score_out);
+    return qr_launch_status();
+}

@@ -1,33 +1,22 @@
 // Joint network, log-softmax and density-ratio fusion in one kernel (Sec. 2:
 // encoder and prediction outputs are combined multiplicatively, a linear layer
 // and a log-softmax follow; Eq. 1 adds the weighted LM log-probabilities).
+#include "kernels.h"
 #include "mma_core.h"
 
 namespace {
 
-struct JointArgs {
-    const float *enc;  int n_enc_rows;
-    const int32_t *frame_row;
-    const float *pred;
-    const v4i *w;  const float *s_w;  const float *b_out;
-    float z_scale, z_inv;
-    const float *lp_src, *lp_ext;
-    float lambda_src, lambda_ext, rho;
-    int N, J, V, blank, nkc;
-    float *lp_out;  int8_t *dbg_zq;  float *fused;
-};
-
 // One wave per 16 hypotheses.  Lane (col, grp) produces, for every 64-column
 // half, the 16 codes of z that are its own MFMA operand: z never leaves
 // registers.  V <= 64 rows of the output layer are 4 row tiles of this wave.
-__global__ __launch_bounds__(64) void joint_fuse_kernel(const JointArgs a)
+__global__ __launch_bounds__(64) void joint_fuse_kernel(const QrJointArgs a)
 {
     const int lane = threadIdx.x & 63;
     const int col = lane & 15, grp = lane >> 4;
     int n = blockIdx.x * 16 + col;
     const bool nv = n < a.N;
     n = nv ? n : a.N - 1;
-    int fr = a.frame_row[n];
+    int fr = a.frame_row ? a.frame_row[n] : a.frame_base + n / a.rows_per_utt;
     fr = fr < 0 ? 0 : (fr >= a.n_enc_rows ? a.n_enc_rows - 1 : fr);
     const float *e = a.enc + (int64_t)fr * a.J;
     const float *p = a.pred + (int64_t)n * a.J;
@@ -117,6 +106,11 @@ __global__ __launch_bounds__(64) void joint_fuse_kernel(const JointArgs a)
 
 }  // namespace
 
+void qr_launch_joint(const QrJointArgs &a, hipStream_t st)
+{
+    joint_fuse_kernel<<<(a.N + 15) / 16, 64, 0, st>>>(a);
+}
+
 extern "C" qrnnt_status qrnnt_joint_fuse(const float *enc_proj, int32_t n_enc_rows, const int32_t *frame_row,
                                          const float *pred_proj, const qrnnt_qmat *w_out, const float *b_out,
                                          float z_scale, float z_inv_scale, const float *lp_src, const float *lp_ext,
@@ -133,7 +127,7 @@ extern "C" qrnnt_status qrnnt_joint_fuse(const float *enc_proj, int32_t n_enc_ro
     QR_REQUIRE(z_scale > 0.0f && z_inv_scale > 0.0f, QRNNT_ERR_RANGE);
     QR_REQUIRE(qr_aligned(enc_proj, 16) && qr_aligned(pred_proj, 16), QRNNT_ERR_ALIGN);
     QR_REQUIRE(dbg_zq == nullptr || qr_aligned(dbg_zq, 16), QRNNT_ERR_ALIGN);
-    JointArgs a = {};
+    QrJointArgs a = {};
     a.enc = enc_proj;  a.n_enc_rows = n_enc_rows;  a.frame_row = frame_row;  a.pred = pred_proj;
     a.w = (const v4i *)w_out->packed;  a.s_w = w_out->row_scale;  a.b_out = b_out;
     a.z_scale = z_scale;  a.z_inv = z_inv_scale;
@@ -142,6 +136,7 @@ extern "C" qrnnt_status qrnnt_joint_fuse(const float *enc_proj, int32_t n_enc_ro
     a.N = N;  a.J = w_out->cols;  a.V = w_out->rows;  a.blank = blank;
     a.nkc = qr_round_up(w_out->cols, QRNNT_KCHUNK) / QRNNT_KCHUNK;
     a.lp_out = lp_rnnt_out;  a.dbg_zq = dbg_zq;  a.fused = fused_out;
-    joint_fuse_kernel<<<(N + 15) / 16, 64, 0, (hipStream_t)stream>>>(a);
+    a.rows_per_utt = 1;
+    qr_launch_joint(a, (hipStream_t)stream);
     return qr_launch_status();
 }

@@ -1,0 +1,57 @@
+// Internal launch interface between the translation units of libqrnnt.  The
+// public entry points validate and then call these; the decoder calls them
+// directly.  Nothing here is exported.
+#pragma once
+
+#include "qrnnt_common.h"
+
+#define QR_HIDDEN __attribute__((visibility("hidden")))
+
+struct QrStepArgs {
+    const v4i *wih, *whh;             // TILED_GATES blobs
+    const float *s_wih, *s_whh, *bias;
+    const int8_t *x;  int64_t ld_x;   // input codes, row pitch in bytes
+    const int32_t *x_row;  int n_x_rows;
+    const int32_t *gx;  int64_t ld_gx; // precomputed input projection [rows, 4H], tiled-row order (USE_GX only)
+    const int32_t *parent;  int n_slots;
+    const int8_t *h_prev;  int64_t ld_hp;
+    const float *c_prev;
+    const uint8_t *active;
+    int8_t *h_next;  int64_t ld_hn;
+    float *c_next;
+    int8_t *h_copy;                    // optional second copy of the output codes [N, H]
+    int32_t *dbg_accx, *dbg_acch;
+    float *dbg_gates;
+    int I, H, N, nkc_x, nkc_h;
+    float x_scale, h_scale, h_inv;
+};
+
+struct QrLinearArgs {
+    const v4i *w;  int nkc, rows;
+    const float *s_w, *bias;
+    float a_scale;
+    const int8_t *act;  int K, N;
+    float *y;  int32_t *dbg_acc;
+    int log_softmax;
+};
+
+struct QrJointArgs {
+    const float *enc;  int n_enc_rows;
+    const int32_t *frame_row;          // per-row encoder row, or null: row = frame_base + n / rows_per_utt
+    int frame_base, rows_per_utt;
+    const float *pred;
+    const v4i *w;  const float *s_w;  const float *b_out;
+    float z_scale, z_inv;
+    const float *lp_src, *lp_ext;
+    float lambda_src, lambda_ext, rho;
+    int N, J, V, blank, nkc;
+    float *lp_out;  int8_t *dbg_zq;  float *fused;
+};
+
+QR_HIDDEN void qr_fill_lstm_weights(QrStepArgs &a, const qrnnt_lstm *L);
+QR_HIDDEN qrnnt_status qr_check_lstm(const qrnnt_lstm *L);
+QR_HIDDEN void qr_launch_lstm_step(const QrStepArgs &a, bool use_gx, hipStream_t st);
+QR_HIDDEN void qr_launch_linear(const QrLinearArgs &a, hipStream_t st);
+QR_HIDDEN void qr_launch_joint(const QrJointArgs &a, hipStream_t st);
+QR_HIDDEN void qr_launch_beam(const float *score, const float *fused, int B, int W, int V, int blank, int force_blank,
+                              int32_t *parent_out, int32_t *token_out, float *score_out, hipStream_t st);

@@ -1,5 +1,6 @@
 // Quantized linear layer (Sec. 3.2: weights and inputs of linear layers are
 // quantized) with an optional fused log-softmax for the LM output layer (Sec. 2).
+#include "kernels.h"
 #include "mma_core.h"
 
 namespace {
@@ -108,6 +109,23 @@ __global__ __launch_bounds__(64) void linear_logsoftmax_kernel(const v4i *__rest
 
 }  // namespace
 
+void qr_launch_linear(const QrLinearArgs &a, hipStream_t st)
+{
+    const int n_row_tiles = (a.rows + 15) / 16;
+    if (a.log_softmax) {
+        linear_logsoftmax_kernel<<<(a.N + 15) / 16, 64, 0, st>>>(a.w, a.nkc, a.rows, a.s_w, a.bias, a.a_scale, a.act, a.K,
+                                                                 a.N, a.y, a.dbg_acc);
+    } else if (a.N <= 16) {
+        dim3 grid((n_row_tiles + 3) / 4, 1);
+        linear_kernel<1, 1><<<grid, 256, 0, st>>>(a.w, a.nkc, a.rows, a.s_w, a.bias, a.a_scale, a.act, a.K, a.N, a.y,
+                                                  a.dbg_acc);
+    } else {
+        dim3 grid((n_row_tiles + 7) / 8, (a.N + 63) / 64);
+        linear_kernel<2, 4><<<grid, 256, 0, st>>>(a.w, a.nkc, a.rows, a.s_w, a.bias, a.a_scale, a.act, a.K, a.N, a.y,
+                                                  a.dbg_acc);
+    }
+}
+
 extern "C" qrnnt_status qrnnt_linear(const qrnnt_qmat *w, const float *bias, float a_scale, const int8_t *a, int32_t N,
                                      int32_t log_softmax, float *y, int32_t *dbg_acc, void *stream)
 {
@@ -118,20 +136,10 @@ extern "C" qrnnt_status qrnnt_linear(const qrnnt_qmat *w, const float *bias, flo
     QR_REQUIRE(a_scale > 0.0f, QRNNT_ERR_RANGE);
     QR_REQUIRE(qr_aligned(a, 16) && qr_aligned(y, 4), QRNNT_ERR_ALIGN);
     QR_REQUIRE(!log_softmax || w->rows <= 64, QRNNT_ERR_UNSUPPORTED);
-    hipStream_t st = (hipStream_t)stream;
-    const int nkc = qr_round_up(w->cols, QRNNT_KCHUNK) / QRNNT_KCHUNK;
-    const int n_row_tiles = (w->rows + 15) / 16;
-    if (log_softmax) {
-        linear_logsoftmax_kernel<<<(N + 15) / 16, 64, 0, st>>>((const v4i *)w->packed, nkc, w->rows, w->row_scale, bias,
-                                                               a_scale, a, w->cols, N, y, dbg_acc);
-    } else if (N <= 16) {
-        dim3 grid((n_row_tiles + 3) / 4, 1);
-        linear_kernel<1, 1><<<grid, 256, 0, st>>>((const v4i *)w->packed, nkc, w->rows, w->row_scale, bias, a_scale, a,
-                                                  w->cols, N, y, dbg_acc);
-    } else {
-        dim3 grid((n_row_tiles + 7) / 8, (N + 63) / 64);
-        linear_kernel<2, 4><<<grid, 256, 0, st>>>((const v4i *)w->packed, nkc, w->rows, w->row_scale, bias, a_scale, a,
-                                                  w->cols, N, y, dbg_acc);
-    }
+    QrLinearArgs la = {};
+    la.w = (const v4i *)w->packed;  la.nkc = qr_round_up(w->cols, QRNNT_KCHUNK) / QRNNT_KCHUNK;  la.rows = w->rows;
+    la.s_w = w->row_scale;  la.bias = bias;  la.a_scale = a_scale;
+    la.act = a;  la.K = w->cols;  la.N = N;  la.y = y;  la.dbg_acc = dbg_acc;  la.log_softmax = log_softmax;
+    qr_launch_linear(la, (hipStream_t)stream);
     return qr_launch_status();
 }

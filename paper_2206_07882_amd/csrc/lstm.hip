@@ -2,33 +2,15 @@
 // with the whole cell fused behind the contraction (Sec. 3.2: integer MACs for
 // W_ih and W_hh, fp bias and cell state; Sec. 3.4: the hidden state is
 // quantized once, at the cell output).
+#include "kernels.h"
 #include "mma_core.h"
 
 namespace {
 
-struct StepArgs {
-    const v4i *wih, *whh;             // TILED_GATES blobs
-    const float *s_wih, *s_whh, *bias;
-    const int8_t *x;  int64_t ld_x;   // input codes, row pitch in bytes
-    const int32_t *x_row;  int n_x_rows;
-    const int32_t *gx;  int64_t ld_gx; // precomputed input projection [rows, 4H] in tiled-row order (or null)
-    const int32_t *parent;  int n_slots;
-    const int8_t *h_prev;  int64_t ld_hp;
-    const float *c_prev;
-    const uint8_t *active;
-    int8_t *h_next;  int64_t ld_hn;    // row pitch of the output codes
-    float *c_next;
-    int8_t *h_copy;                    // optional second copy of the output codes [N, H]
-    int32_t *dbg_accx, *dbg_acch;
-    float *dbg_gates;
-    int I, H, N, nkc_x, nkc_h;
-    float x_scale, h_scale, h_inv;
-};
-
 // Grid: x = groups of 4*MT row tiles (a wave owns MT tiles = 4*MT cells),
 //       y = groups of NT*16 hypotheses.  No LDS, no barriers.
 template <int MT, int NT, bool USE_GX>
-__global__ __launch_bounds__(256) void lstm_step_kernel(const StepArgs a)
+__global__ __launch_bounds__(256) void lstm_step_kernel(const QrStepArgs a)
 {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int col = lane & 15, grp = lane >> 4;
@@ -141,7 +123,7 @@ __global__ __launch_bounds__(256) void lstm_step_kernel(const StepArgs a)
 }
 
 template <bool USE_GX>
-void launch_step(const StepArgs &a, hipStream_t st)
+void launch_step_t(const QrStepArgs &a, hipStream_t st)
 {
     const int n_row_tiles = a.H >> 2;
     if (a.N <= 16) {
@@ -207,7 +189,9 @@ __global__ void fill_zero_kernel(uint32_t *p, size_t n_words)
     if (i < n_words) p[i] = 0u;
 }
 
-qrnnt_status check_lstm(const qrnnt_lstm *L)
+}  // namespace
+
+qrnnt_status qr_check_lstm(const qrnnt_lstm *L)
 {
     QR_REQUIRE(L != nullptr, QRNNT_ERR_NULL);
     qrnnt_status s = qr_check_qmat(&L->w_ih, QRNNT_LAYOUT_TILED_GATES);
@@ -223,7 +207,7 @@ qrnnt_status check_lstm(const qrnnt_lstm *L)
     return QRNNT_OK;
 }
 
-void fill_weights(StepArgs &a, const qrnnt_lstm *L)
+void qr_fill_lstm_weights(QrStepArgs &a, const qrnnt_lstm *L)
 {
     a.wih = (const v4i *)L->w_ih.packed;
     a.whh = (const v4i *)L->w_hh.packed;
@@ -239,7 +223,10 @@ void fill_weights(StepArgs &a, const qrnnt_lstm *L)
     a.h_inv = L->h_inv_scale;
 }
 
-}  // namespace
+void qr_launch_lstm_step(const QrStepArgs &a, bool use_gx, hipStream_t st)
+{
+    if (use_gx) launch_step_t<true>(a, st); else launch_step_t<false>(a, st);
+}
 
 extern "C" qrnnt_status qrnnt_lstm_step(const qrnnt_lstm *L, const int8_t *x_codes, const int32_t *x_row,
                                         int32_t n_x_rows, const int32_t *parent, const int8_t *h_prev,
@@ -247,7 +234,7 @@ extern "C" qrnnt_status qrnnt_lstm_step(const qrnnt_lstm *L, const int8_t *x_cod
                                         int8_t *h_next, float *c_next, int32_t *dbg_accx, int32_t *dbg_acch,
                                         float *dbg_gates, void *stream)
 {
-    qrnnt_status s = check_lstm(L);
+    qrnnt_status s = qr_check_lstm(L);
     if (s != QRNNT_OK) return s;
     QR_REQUIRE(x_codes && h_prev && c_prev && h_next && c_next, QRNNT_ERR_NULL);
     QR_REQUIRE(N > 0 && n_slots > 0 && n_x_rows > 0, QRNNT_ERR_SHAPE);
@@ -256,15 +243,15 @@ extern "C" qrnnt_status qrnnt_lstm_step(const qrnnt_lstm *L, const int8_t *x_cod
     QR_REQUIRE(qr_aligned(x_codes, 16) && qr_aligned(h_prev, 16), QRNNT_ERR_ALIGN);
     QR_REQUIRE(qr_aligned(c_prev, 4) && qr_aligned(c_next, 4), QRNNT_ERR_ALIGN);
     QR_REQUIRE((const void *)h_next != (const void *)h_prev && c_next != c_prev, QRNNT_ERR_RANGE);
-    StepArgs a = {};
-    fill_weights(a, L);
+    QrStepArgs a = {};
+    qr_fill_lstm_weights(a, L);
     a.x = x_codes;  a.ld_x = L->input_size;  a.x_row = x_row;  a.n_x_rows = n_x_rows;
     a.parent = parent;  a.n_slots = n_slots;
     a.h_prev = h_prev;  a.ld_hp = L->hidden_size;  a.c_prev = c_prev;  a.active = active;
     a.h_next = h_next;  a.ld_hn = L->hidden_size;  a.c_next = c_next;
     a.dbg_accx = dbg_accx;  a.dbg_acch = dbg_acch;  a.dbg_gates = dbg_gates;
     a.N = N;
-    launch_step<false>(a, (hipStream_t)stream);
+    qr_launch_lstm_step(a, false, (hipStream_t)stream);
     return qr_launch_status();
 }
 
@@ -293,7 +280,7 @@ extern "C" qrnnt_status qrnnt_lstm_layer(const qrnnt_lstm *L, const int8_t *x_co
                                          int32_t *dbg_accx, float *dbg_c_all, void *workspace, size_t workspace_bytes,
                                          void *stream)
 {
-    qrnnt_status s = check_lstm(L);
+    qrnnt_status s = qr_check_lstm(L);
     if (s != QRNNT_OK) return s;
     QR_REQUIRE(x_codes && h_out && workspace, QRNNT_ERR_NULL);
     QR_REQUIRE(T > 0 && B > 0, QRNNT_ERR_SHAPE);
@@ -331,8 +318,8 @@ extern "C" qrnnt_status qrnnt_lstm_layer(const qrnnt_lstm *L, const int8_t *x_co
         fill_zero_kernel<<<(unsigned)((nw + 255) / 256), 256, 0, st>>>((uint32_t *)cbuf[0], nw);
     }
     // 3) the recurrence, one fused launch per time step
-    StepArgs a = {};
-    fill_weights(a, L);
+    QrStepArgs a = {};
+    qr_fill_lstm_weights(a, L);
     a.ld_gx = 4 * (int64_t)H;
     a.n_slots = B;
     a.N = B;
@@ -354,7 +341,7 @@ extern "C" qrnnt_status qrnnt_lstm_layer(const qrnnt_lstm *L, const int8_t *x_co
         a.c_next = dbg_c_all ? dbg_c_all + (int64_t)t * B * H : cbuf[cur];
         a.h_next = h_out + (int64_t)t * B * ld_out + col_off;
         a.h_copy = (step == T - 1) ? h_last : nullptr;
-        launch_step<true>(a, st);
+        qr_launch_lstm_step(a, true, st);
         c_prev = a.c_next;
         cur ^= 1;
     }

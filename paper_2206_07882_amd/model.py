@@ -1,0 +1,80 @@
+"""Device-side model assembly: float weights -> packed INT4 blobs via the C ABI.
+
+Everything numeric happens in libqrnnt (qrnnt_pack_int4 quantizes and packs,
+qrnnt_quantize_act quantizes embeddings and features); this module only moves
+host arrays to the GPU and strings the ABI calls together.
+"""
+from __future__ import annotations
+
+from typing import List, Optional
+
+import numpy as np
+import torch
+
+from . import qrnnt as q
+
+S_H = float(np.float32(1.0) / np.float32(7.0))     # FIX +-1 step (Sec. 3.2)
+
+
+def act_scale(alpha: float):
+    a = np.float32(alpha)
+    return float(np.float32(a / np.float32(7.0))), float(np.float32(np.float32(7.0) / a))
+
+
+def _dev(a, device):
+    return torch.from_numpy(np.ascontiguousarray(a)).to(device)
+
+
+def lstm_from_float(f, x_scale: float, device="cuda:0") -> q.Lstm:
+    return q.Lstm(q.pack_int4(_dev(f.w_ih, device), q.LAYOUT_TILED_GATES),
+                  q.pack_int4(_dev(f.w_hh, device), q.LAYOUT_TILED_GATES),
+                  _dev(f.bias, device), x_scale, S_H, 7.0)
+
+
+def net_from_float(f, alpha_e: float, log_softmax: bool, device="cuda:0") -> q.Net:
+    s_e, inv_e = act_scale(alpha_e)
+    embed_codes = q.quantize_act(_dev(f.embed, device), inv_e)
+    layers = [lstm_from_float(lf, s_e if i == 0 else S_H, device) for i, lf in enumerate(f.layers)]
+    out = q.pack_int4(_dev(f.out.w, device), q.LAYOUT_TILED)
+    return q.Net(embed_codes, layers, out, _dev(f.out.bias, device), S_H, log_softmax)
+
+
+def model_from_float(m, device="cuda:0", use_src=True, use_ext=True) -> q.Model:
+    pred = net_from_float(m.pred, m.alpha_e, False, device)
+    src = net_from_float(m.lm_src, m.alpha_e, True, device) if (use_src and m.lm_src is not None) else None
+    ext = net_from_float(m.lm_ext, m.alpha_e, True, device) if (use_ext and m.lm_ext is not None) else None
+    jout = q.pack_int4(_dev(m.joint_out.w, device), q.LAYOUT_TILED)
+    return q.Model(pred, src, ext, jout, _dev(m.joint_out.bias, device), m.lambda_src, m.lambda_ext, m.rho)
+
+
+class Encoder:
+    """Stack of (bi)directional quantized LSTM layers plus the projection to the joint."""
+
+    def __init__(self, m, device="cuda:0"):
+        self.s_x, self.inv_s_x = act_scale(m.alpha_x)
+        self.layers: List[List[q.Lstm]] = []
+        for li, dirs in enumerate(m.enc_layers):
+            self.layers.append([lstm_from_float(d, self.s_x if li == 0 else S_H, device) for d in dirs])
+        self.proj = q.pack_int4(_dev(m.enc_proj.w, device), q.LAYOUT_TILED)
+        self.proj_bias = _dev(m.enc_proj.bias, device)
+        self._ws: Optional[torch.Tensor] = None
+
+    def workspace(self, T: int, B: int, device) -> torch.Tensor:
+        need = max(q.lstm_layer_workspace(L, T, B) for dirs in self.layers for L in dirs)
+        if self._ws is None or self._ws.numel() < need:
+            self._ws = torch.empty(need, dtype=torch.uint8, device=device)
+        return self._ws
+
+    def forward(self, feats: torch.Tensor):
+        """feats [T,B,D] fp32 on the device -> (codes [T,B,dirs*H], e [T,B,J] fp32)."""
+        T, B, _ = feats.shape
+        ws = self.workspace(T, B, feats.device)
+        x = q.quantize_act(feats, self.inv_s_x)
+        for dirs in self.layers:
+            H = dirs[0].H
+            out = torch.empty((T, B, H * len(dirs)), dtype=torch.int8, device=feats.device)
+            for d, L in enumerate(dirs):
+                q.lstm_layer(L, x, reverse=(d == 1), h_out=out, col_off=d * H, workspace=ws)
+            x = out
+        e = q.linear(self.proj, self.proj_bias, S_H, x.reshape(T * B, -1)).reshape(T, B, -1)
+        return x, e

@@ -41,9 +41,24 @@ class CLstm(C.Structure):
                 ("hidden_size", C.c_int32)]
 
 
+MAX_LAYERS = 4
+
+
+class CNet(C.Structure):
+    _fields_ = [("embed_codes", C.c_void_p), ("n_layers", C.c_int32), ("layer", CLstm * MAX_LAYERS), ("out", CQMat),
+                ("out_bias", C.c_void_p), ("out_a_scale", C.c_float), ("log_softmax", C.c_int32)]
+
+
+class CModel(C.Structure):
+    _fields_ = [("pred", CNet), ("lm_src", CNet), ("lm_ext", CNet), ("use_src", C.c_int32), ("use_ext", C.c_int32),
+                ("joint_out", CQMat), ("joint_bias", C.c_void_p), ("z_scale", C.c_float), ("z_inv_scale", C.c_float),
+                ("lambda_src", C.c_float), ("lambda_ext", C.c_float), ("rho", C.c_float), ("V", C.c_int32),
+                ("blank", C.c_int32)]
+
+
 EXPORTS = ["qrnnt_status_str", "qrnnt_abi_version", "qrnnt_pack_int4_bytes", "qrnnt_pack_int4", "qrnnt_unpack_int4",
            "qrnnt_quantize_act", "qrnnt_linear", "qrnnt_lstm_step", "qrnnt_lstm_layer_workspace", "qrnnt_lstm_layer",
-           "qrnnt_joint_fuse", "qrnnt_beam_step"]
+           "qrnnt_joint_fuse", "qrnnt_beam_step", "qrnnt_decode_workspace", "qrnnt_decode"]
 
 
 def load():
@@ -60,6 +75,8 @@ def load():
         lib.qrnnt_pack_int4_bytes.argtypes = [C.c_int32, C.c_int32, C.c_int32]
         lib.qrnnt_lstm_layer_workspace.restype = C.c_size_t
         lib.qrnnt_lstm_layer_workspace.argtypes = [C.c_void_p, C.c_int32, C.c_int32]
+        lib.qrnnt_decode_workspace.restype = C.c_size_t
+        lib.qrnnt_decode_workspace.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32]
         _lib = lib
     return _lib
 
@@ -244,3 +261,78 @@ def beam_step(score: torch.Tensor, fused: torch.Tensor, blank: int = 0, force_bl
                                 _ptr(tok), _ptr(ns), _stream())
     _check(st, "qrnnt_beam_step")
     return par, tok, ns
+
+
+class Net:
+    """Prediction network or LM on the device: quantized embedding table,
+    stacked LSTM layers, quantized output layer."""
+
+    def __init__(self, embed_codes: torch.Tensor, layers, out: QMat, out_bias: Optional[torch.Tensor],
+                 out_a_scale: float, log_softmax: bool):
+        self.embed_codes, self.layers, self.out, self.out_bias = embed_codes, list(layers), out, out_bias
+        self.out_a_scale, self.log_softmax = float(out_a_scale), bool(log_softmax)
+
+    def c(self) -> CNet:
+        n = CNet()
+        n.embed_codes = self.embed_codes.data_ptr()
+        n.n_layers = len(self.layers)
+        for i, l in enumerate(self.layers):
+            n.layer[i] = l.c()
+        n.out = self.out.c()
+        n.out_bias = None if self.out_bias is None else self.out_bias.data_ptr()
+        n.out_a_scale = self.out_a_scale
+        n.log_softmax = 1 if self.log_softmax else 0
+        return n
+
+
+class Model:
+    def __init__(self, pred: Net, lm_src: Optional[Net], lm_ext: Optional[Net], joint_out: QMat,
+                 joint_bias: Optional[torch.Tensor], lambda_src: float, lambda_ext: float, rho: float = 0.0,
+                 blank: int = 0, z_scale: float = 1.0 / 7.0, z_inv_scale: float = 7.0):
+        self.pred, self.lm_src, self.lm_ext, self.joint_out, self.joint_bias = pred, lm_src, lm_ext, joint_out, joint_bias
+        self.lambda_src, self.lambda_ext, self.rho = float(lambda_src), float(lambda_ext), float(rho)
+        self.blank, self.z_scale, self.z_inv_scale = int(blank), float(z_scale), float(z_inv_scale)
+        self.V, self.J = joint_out.rows, joint_out.cols
+
+    def c(self) -> CModel:
+        m = CModel()
+        m.pred = self.pred.c()
+        if self.lm_src is not None:
+            m.lm_src = self.lm_src.c()
+        if self.lm_ext is not None:
+            m.lm_ext = self.lm_ext.c()
+        m.use_src = 0 if self.lm_src is None else 1
+        m.use_ext = 0 if self.lm_ext is None else 1
+        m.joint_out = self.joint_out.c()
+        m.joint_bias = None if self.joint_bias is None else self.joint_bias.data_ptr()
+        m.z_scale, m.z_inv_scale = self.z_scale, self.z_inv_scale
+        m.lambda_src, m.lambda_ext, m.rho = self.lambda_src, self.lambda_ext, self.rho
+        m.V, m.blank = self.V, self.blank
+        return m
+
+
+def decode_workspace(model: Model, T: int, B: int, W: int, max_sym: int) -> int:
+    cm = model.c()
+    return int(load().qrnnt_decode_workspace(C.byref(cm), T, B, W, max_sym))
+
+
+def decode(model: Model, enc_proj: torch.Tensor, W: int, max_sym: int, max_len: Optional[int] = None,
+           workspace: Optional[torch.Tensor] = None):
+    T, B, J = enc_proj.shape
+    dev = enc_proj.device
+    if max_len is None:
+        max_len = max(1, T * max_sym)
+    need = decode_workspace(model, T, B, W, max_sym)
+    if need == 0:
+        _check(2, "qrnnt_decode_workspace")
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=dev)
+    tokens = torch.empty((B, W, max_len), dtype=torch.int32, device=dev)
+    lens = torch.empty((B, W), dtype=torch.int32, device=dev)
+    scores = torch.empty((B, W), dtype=torch.float32, device=dev)
+    cm = model.c()
+    st = load().qrnnt_decode(C.byref(cm), _ptr(enc_proj, torch.float32), C.c_int32(T), C.c_int32(B), C.c_int32(W),
+                             C.c_int32(max_sym), C.c_int32(max_len), _ptr(tokens), _ptr(lens), _ptr(scores),
+                             _ptr(workspace), C.c_size_t(workspace.numel()), _stream())
+    _check(st, "qrnnt_decode")
+    return tokens, lens, scores

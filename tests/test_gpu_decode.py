@@ -1,0 +1,92 @@
+"""End-to-end parity: encoder stack and the on-device beam search against the
+oracle, free-running (no teacher forcing).  The sizes are small enough that a
+rounding tie of a hidden code is improbable; the seeds are fixed, so the outcome
+is deterministic."""
+import os
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from oracle import models as omodels
+from paper_2206_07882_amd import synth
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).to(DEV)
+
+
+def host(t):
+    return t.detach().cpu().numpy()
+
+
+def _compare_beams(got, ref, atol=2e-3):
+    tok_g, len_g, sc_g = (host(x) for x in got)
+    tok_r, len_r, sc_r = ref
+    assert np.array_equal(len_g, len_r)
+    L = min(tok_g.shape[2], tok_r.shape[2])
+    assert np.array_equal(tok_g[:, :, :L], tok_r[:, :, :L])
+    fin = np.isfinite(sc_r)
+    assert np.array_equal(np.isfinite(sc_g), fin)
+    assert np.abs(sc_g[fin] - sc_r[fin]).max() < atol
+
+
+@pytest.mark.parametrize("std", [0.1, 0.6])
+def test_config0_end_to_end_beams_identical(gpu_lib, std):
+    from paper_2206_07882_amd import model as gmodel
+    m = synth.make_model(0, weight_std=std)
+    T, B = 20, 2
+    feats = synth.features(0, T, B, m.feat_dim)
+    # oracle
+    layers, proj = omodels.encoder_from_float(m)
+    x_r, e_r = omodels.encoder_forward(layers, proj, feats, m.alpha_x)
+    ref = oracle.decode(omodels.model_from_float(m), e_r, m.beam, m.max_sym)
+    # GPU
+    enc = gmodel.Encoder(m, DEV)
+    x_g, e_g = enc.forward(dev(feats))
+    assert np.array_equal(host(x_g), x_r)
+    assert np.abs(host(e_g) - e_r).max() < 1e-5
+    G = gmodel.model_from_float(m, DEV)
+    got = gpu_lib.decode(G, e_g, m.beam, m.max_sym)
+    _compare_beams(got, ref)
+    # the stored golden beams say the same
+    path = os.path.join(os.path.dirname(__file__), "golden", "cfg0_decode.txt")
+    lines = [l for l in open(path).read().splitlines() if l.startswith(f"{std} ")]
+    tok_g, len_g, _ = (host(x) for x in got)
+    for l in lines:
+        head, labs = l.split("|")
+        _, b, w, _ = head.split()
+        want = [int(t) for t in labs.split()]
+        assert tok_g[int(b), int(w), :len_g[int(b), int(w)]].tolist() == want
+
+
+@pytest.mark.parametrize("B,W,max_sym,T,lms,std", [(3, 4, 2, 12, True, 0.6), (2, 1, 3, 10, True, 0.6),
+                                                   (4, 16, 4, 6, True, 0.5), (2, 3, 0, 8, False, 0.6),
+                                                   (5, 8, 1, 9, False, 0.4)])
+def test_decode_variants_match_oracle(gpu_lib, B, W, max_sym, T, lms, std):
+    from paper_2206_07882_amd import model as gmodel
+    m = synth.make_model(0, weight_std=std)
+    if not lms:
+        m.lm_src = m.lm_ext = None
+    m.rho = 0.1
+    e = synth.normal(100 + B + W, (T, B, m.J), 1.0)
+    ref = oracle.decode(omodels.model_from_float(m), e, W, max_sym, max_len=max(1, T * max(max_sym, 1)))
+    G = gmodel.model_from_float(m, DEV)
+    got = gpu_lib.decode(G, dev(e), W, max_sym, max_len=max(1, T * max(max_sym, 1)))
+    _compare_beams(got, ref)
+
+
+def test_decode_full_width_networks_small_batch(gpu_lib):
+    """The measured layer widths (pred 768, LMs 2 x 1024, joint 256, V 46) on a
+    short, narrow problem the oracle finishes in seconds."""
+    from paper_2206_07882_amd import model as gmodel
+    m = synth.make_model(4, enc_layers=1)
+    T, B, W, max_sym = 6, 2, 4, 2
+    e = synth.normal(200, (T, B, m.J), 1.0)
+    ref = oracle.decode(omodels.model_from_float(m), e, W, max_sym)
+    got = gpu_lib.decode(gmodel.model_from_float(m, DEV), dev(e), W, max_sym)
+    _compare_beams(got, ref)
