@@ -153,6 +153,14 @@ qrnnt_status qrnnt_lstm_layer(const qrnnt_lstm *L, const int8_t *x_codes, int32_
                               int8_t *h_last, float *c_last, int32_t *dbg_accx, float *dbg_c_all,
                               void *workspace, size_t workspace_bytes, void *stream);
 
+/* The input projection alone (first half of qrnnt_lstm_layer): for M rows of
+ * input codes x [device] [M, I], gx[m, 4*j + g] = sum_k w_ih[g*H + j, k] * x[m, k]
+ * as int32 [M, 4H]; columns are gate-interleaved (the four gate sums of cell j
+ * are adjacent), which is the order the recurrence consumes.  dbg_accx [device]
+ * int32 [M, 4H] in source row order, or NULL. */
+qrnnt_status qrnnt_input_projection(const qrnnt_lstm *L, const int8_t *x_codes, int32_t M, int32_t *gx,
+                                    int32_t *dbg_accx, void *stream);
+
 /* ---- joint network + log-softmax + Eq. 1 ---- */
 
 /* For n in [0,N): e = enc_proj[frame_row[n]], p = pred_proj[n] (length J);

@@ -255,6 +255,29 @@ extern "C" qrnnt_status qrnnt_lstm_step(const qrnnt_lstm *L, const int8_t *x_cod
     return qr_launch_status();
 }
 
+static void launch_gx_gemm(const qrnnt_lstm *L, const int8_t *x_codes, int M, int32_t *gx, int32_t *dbg_accx,
+                           hipStream_t st)
+{
+    const int H = L->hidden_size, I = L->input_size;
+    const int n_row_tiles = H >> 2;
+    const int nkc = qr_round_up(I, QRNNT_KCHUNK) / QRNNT_KCHUNK;
+    dim3 grid((n_row_tiles + 7) / 8, (M + 127) / 128);
+    gx_gemm_kernel<4, 4><<<grid, 256, 0, st>>>((const v4i *)L->w_ih.packed, nkc, n_row_tiles, x_codes, I, M, I, gx, H,
+                                               dbg_accx);
+}
+
+extern "C" qrnnt_status qrnnt_input_projection(const qrnnt_lstm *L, const int8_t *x_codes, int32_t M, int32_t *gx,
+                                               int32_t *dbg_accx, void *stream)
+{
+    qrnnt_status s = qr_check_lstm(L);
+    if (s != QRNNT_OK) return s;
+    QR_REQUIRE(x_codes && gx, QRNNT_ERR_NULL);
+    QR_REQUIRE(M > 0, QRNNT_ERR_SHAPE);
+    QR_REQUIRE(qr_aligned(x_codes, 16) && qr_aligned(gx, 16), QRNNT_ERR_ALIGN);
+    launch_gx_gemm(L, x_codes, M, gx, dbg_accx, (hipStream_t)stream);
+    return qr_launch_status();
+}
+
 // Workspace layout of qrnnt_lstm_layer:
 //   [0, gx_bytes)                int32 gx [T*B, 4H]
 //   then h state 2 x [B, H] int8 (rounded up to 256 B), c state 2 x [B, H] fp32.
@@ -300,14 +323,7 @@ extern "C" qrnnt_status qrnnt_lstm_layer(const qrnnt_lstm *L, const int8_t *x_co
     float *cbuf[2] = {(float *)(ws + gx_b + 2 * h_b), (float *)(ws + gx_b + 2 * h_b + c_b)};
 
     // 1) input projection for all T*B frames
-    {
-        const int n_row_tiles = H >> 2;
-        const int nkc = qr_round_up(I, QRNNT_KCHUNK) / QRNNT_KCHUNK;
-        const int M = T * B;
-        dim3 grid((n_row_tiles + 7) / 8, (M + 127) / 128);
-        gx_gemm_kernel<4, 4><<<grid, 256, 0, st>>>((const v4i *)L->w_ih.packed, nkc, n_row_tiles, x_codes, I, M, I, gx,
-                                                   H, dbg_accx);
-    }
+    launch_gx_gemm(L, x_codes, T * B, gx, dbg_accx, st);
     // 2) zero initial state where none is given
     if (h0 == nullptr) {
         const size_t nw = h_b / 4;

@@ -58,6 +58,7 @@ class CModel(C.Structure):
 
 EXPORTS = ["qrnnt_status_str", "qrnnt_abi_version", "qrnnt_pack_int4_bytes", "qrnnt_pack_int4", "qrnnt_unpack_int4",
            "qrnnt_quantize_act", "qrnnt_linear", "qrnnt_lstm_step", "qrnnt_lstm_layer_workspace", "qrnnt_lstm_layer",
+           "qrnnt_input_projection",
            "qrnnt_joint_fuse", "qrnnt_beam_step", "qrnnt_decode_workspace", "qrnnt_decode"]
 
 
@@ -196,6 +197,29 @@ def lstm_step(L: Lstm, x_codes, h_prev, c_prev, N: Optional[int] = None, x_row=N
     if debug:
         return h_next, c_next, dict(accx=accx, acch=acch, gates=gates)
     return h_next, c_next
+
+
+def lstm_step_into(L: Lstm, x_codes, h_prev, c_prev, h_next, c_next, N: int, x_row=None, parent=None, active=None):
+    """qrnnt_lstm_step with caller-provided outputs (no allocation)."""
+    cl = L.c()
+    st = load().qrnnt_lstm_step(C.byref(cl), _ptr(x_codes, torch.int8), _ptr(x_row, torch.int32),
+                                C.c_int32(x_codes.shape[0]), _ptr(parent, torch.int32), _ptr(h_prev, torch.int8),
+                                _ptr(c_prev, torch.float32), C.c_int32(h_prev.shape[0]), _ptr(active, torch.uint8),
+                                C.c_int32(N), _ptr(h_next, torch.int8), _ptr(c_next, torch.float32), None, None, None,
+                                _stream())
+    _check(st, "qrnnt_lstm_step")
+
+
+def input_projection(L: Lstm, x_codes: torch.Tensor, gx: Optional[torch.Tensor] = None, debug: bool = False):
+    M = x_codes.shape[0]
+    dev = x_codes.device
+    if gx is None:
+        gx = torch.empty((M, 4 * L.H), dtype=torch.int32, device=dev)
+    acc = torch.zeros((M, 4 * L.H), dtype=torch.int32, device=dev) if debug else None
+    cl = L.c()
+    _check(load().qrnnt_input_projection(C.byref(cl), _ptr(x_codes, torch.int8), C.c_int32(M), _ptr(gx, torch.int32),
+                                         _ptr(acc), _stream()), "qrnnt_input_projection")
+    return gx, acc
 
 
 def lstm_layer_workspace(L: Lstm, T: int, B: int) -> int:
