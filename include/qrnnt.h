@@ -136,6 +136,20 @@ qrnnt_status qrnnt_lstm_step(const qrnnt_lstm *L, const int8_t *x_codes, const i
                              const uint8_t *active, int32_t N, int8_t *h_next, float *c_next,
                              int32_t *dbg_accx, int32_t *dbg_acch, float *dbg_gates, void *stream);
 
+/* Up to 3 independent steps (e.g. the first layers of the prediction network and
+ * of both LMs) in one launch, so that small problems fill the GPU together.
+ * Each descriptor carries the arguments of qrnnt_lstm_step (no debug outputs).
+ * steps [host] is read during the call only. */
+typedef struct {
+    const qrnnt_lstm *L;
+    const int8_t *x_codes;  const int32_t *x_row;  int32_t n_x_rows;
+    const int32_t *parent;  const int8_t *h_prev;  const float *c_prev;  int32_t n_slots;
+    const uint8_t *active;  int32_t N;
+    int8_t *h_next;  float *c_next;
+} qrnnt_step_desc;
+
+qrnnt_status qrnnt_lstm_step_group(const qrnnt_step_desc *steps, int32_t n_steps, void *stream);
+
 /* ---- LSTM: one layer-direction over whole utterances (Sec. 2 encoder, Sec. 3.4) ---- */
 
 size_t qrnnt_lstm_layer_workspace(const qrnnt_lstm *L, int32_t T, int32_t B);

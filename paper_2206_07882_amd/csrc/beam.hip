@@ -8,31 +8,56 @@ namespace {
 // Total order: larger value first, then smaller flat index.
 __device__ __forceinline__ bool better(float v, int c, float bv, int bc) { return v > bv || (v == bv && c < bc); }
 
-// One wave per utterance; W rounds, each an arg-best over the W*V candidates
-// that come strictly after the previous pick in the total order, so nothing has
-// to be marked as taken.
-__global__ __launch_bounds__(64) void beam_step_kernel(const float *__restrict__ score, const float *__restrict__ fused,
-                                                        int W, int V, int blank, int force_blank,
-                                                        int32_t *__restrict__ parent_out, int32_t *__restrict__ token_out,
-                                                        float *__restrict__ score_out)
+constexpr int PER_LANE = 16;   // candidates held in registers per lane: W*V <= 1024 takes the fast path
+
+// One wave per utterance.  The W*V candidate values are formed once (fp32 add) and
+// kept in registers; each of the W rounds is an arg-best over the candidates that
+// come strictly after the previous pick in the total order, so nothing is marked
+// as taken.  After round r lane r holds pick r: (flat index, value), index -1 if
+// the candidates ran out.
+__device__ __forceinline__ void select_w(const float *__restrict__ sc, const float *__restrict__ fu, int W, int V,
+                                         int blank, int force_blank, int lane, int &my_c, float &my_v)
 {
-    const int b = blockIdx.x, lane = threadIdx.x;
     const int C = W * V;
-    const float *sc = score + (int64_t)b * W;
-    const float *fu = fused + (int64_t)b * W * V;
+    float val[PER_LANE];
+    const bool fast = C <= 64 * PER_LANE;
+    if (fast) {
+#pragma unroll
+        for (int i = 0; i < PER_LANE; ++i) {
+            const int c = lane + 64 * i;
+            float v = -INFINITY;
+            if (c < C) {
+                const int w = c / V, k = c - w * V;
+                if (!force_blank || k == blank) v = sc[w] + fu[c];
+            }
+            val[i] = v;
+        }
+    }
     float last_v = INFINITY;
     int last_c = -1;
+    bool exhausted = false;
+    my_c = -1;
+    my_v = -INFINITY;
     for (int r = 0; r < W; ++r) {
         float bv = -INFINITY;
         int bc = 0x7fffffff;
-        if (last_c != -2) {
-            for (int c = lane; c < C; c += 64) {
-                const int w = c / V, k = c - w * V;
-                if (force_blank && k != blank) continue;
-                const float v = sc[w] + fu[c];
-                if (!(v > -INFINITY)) continue;
-                const bool after = v < last_v || (v == last_v && c > last_c);
-                if (after && better(v, c, bv, bc)) { bv = v; bc = c; }
+        if (!exhausted) {
+            if (fast) {
+#pragma unroll
+                for (int i = 0; i < PER_LANE; ++i) {
+                    const int c = lane + 64 * i;
+                    const float v = val[i];
+                    const bool ok = v > -INFINITY && (v < last_v || (v == last_v && c > last_c));
+                    if (ok && better(v, c, bv, bc)) { bv = v; bc = c; }
+                }
+            } else {
+                for (int c = lane; c < C; c += 64) {
+                    const int w = c / V, k = c - w * V;
+                    if (force_blank && k != blank) continue;
+                    const float v = sc[w] + fu[c];
+                    const bool ok = v > -INFINITY && (v < last_v || (v == last_v && c > last_c));
+                    if (ok && better(v, c, bv, bc)) { bv = v; bc = c; }
+                }
             }
 #pragma unroll
             for (int off = 32; off > 0; off >>= 1) {
@@ -42,12 +67,74 @@ __global__ __launch_bounds__(64) void beam_step_kernel(const float *__restrict__
             }
         }
         const bool found = bc != 0x7fffffff;
-        if (lane == 0) {
-            parent_out[(int64_t)b * W + r] = found ? bc / V : -1;
-            token_out[(int64_t)b * W + r] = found ? bc % V : -1;
-            score_out[(int64_t)b * W + r] = found ? bv : -INFINITY;
-        }
-        if (found) { last_v = bv; last_c = bc; } else { last_c = -2; }   // exhausted: remaining ranks stay empty
+        if (lane == r) { my_c = found ? bc : -1; my_v = found ? bv : -INFINITY; }
+        if (found) { last_v = bv; last_c = bc; } else { exhausted = true; }
+    }
+}
+
+__global__ __launch_bounds__(64) void beam_step_kernel(const float *__restrict__ score, const float *__restrict__ fused,
+                                                        int W, int V, int blank, int force_blank,
+                                                        int32_t *__restrict__ parent_out, int32_t *__restrict__ token_out,
+                                                        float *__restrict__ score_out)
+{
+    const int b = blockIdx.x, lane = threadIdx.x;
+    int c;
+    float v;
+    select_w(score + (int64_t)b * W, fused + (int64_t)b * W * V, W, V, blank, force_blank, lane, c, v);
+    if (lane < W) {
+        parent_out[(int64_t)b * W + lane] = c >= 0 ? c / V : -1;
+        token_out[(int64_t)b * W + lane] = c >= 0 ? c % V : -1;
+        score_out[(int64_t)b * W + lane] = v;
+    }
+}
+
+// Selection fused with the routing of the picks inside the decoding loop: blank
+// picks join the frame's candidate list, label picks become the slots of the next
+// round in selection order (prefix counts by ballot), the remaining slots die.
+__global__ __launch_bounds__(64) void beam_route_kernel(const QrRouteArgs a)
+{
+    const int b = blockIdx.x, lane = threadIdx.x;
+    const int W = a.W, V = a.V, N = a.B * a.W;
+    int c;
+    float v;
+    select_w(a.score_src + (int64_t)b * W, a.fused + (int64_t)b * W * V, W, V, a.blank, a.last_round, lane, c, v);
+    const bool in = lane < W;
+    const bool found = in && c >= 0;
+    const int par = found ? c / V : 0, tok = found ? c - (c / V) * V : 0;
+    const bool is_blank = found && tok == a.blank;
+    const bool is_lab = found && tok != a.blank && !a.last_round;
+    const unsigned long long bm = __ballot(is_blank), lm = __ballot(is_lab);
+    const unsigned long long lt = (1ull << lane) - 1ull;
+    const int src_slot = b * W + par;
+    const int nx0 = a.nx_count[b];
+    if (is_blank) {
+        const int e = nx0 + __popcll(bm & lt);
+        a.nx_score[(size_t)b * a.R * W + e] = v;
+        a.nx_src[(size_t)b * a.R * W + e] = a.src_buf * N + src_slot;
+    }
+    if (lane == 0) a.nx_count[b] = nx0 + __popcll(bm);
+    if (a.last_round) return;
+    const int n_lab = __popcll(lm);
+    if (is_lab) {
+        const int dst = b * W + __popcll(lm & lt);
+        const int id = a.node_base + dst;
+        a.node_tok[id] = tok;
+        a.node_prev[id] = a.node_src[src_slot];
+        a.score_dst[dst] = v;
+        a.node_dst[dst] = id;
+        a.len_dst[dst] = a.len_src[src_slot] + 1;
+        a.parent_idx[dst] = src_slot;
+        a.token[dst] = tok;
+        a.active[dst] = 1;
+    }
+    if (in && lane >= n_lab) {
+        const int dst = b * W + lane;
+        a.score_dst[dst] = -INFINITY;
+        a.node_dst[dst] = 0;
+        a.len_dst[dst] = 0;
+        a.parent_idx[dst] = dst;
+        a.token[dst] = a.blank;
+        a.active[dst] = 0;
     }
 }
 
@@ -58,6 +145,8 @@ void qr_launch_beam(const float *score, const float *fused, int B, int W, int V,
 {
     beam_step_kernel<<<B, 64, 0, st>>>(score, fused, W, V, blank, force_blank, parent_out, token_out, score_out);
 }
+
+void qr_launch_beam_route(const QrRouteArgs &a, hipStream_t st) { beam_route_kernel<<<a.B, 64, 0, st>>>(a); }
 
 extern "C" qrnnt_status qrnnt_beam_step(const float *score, const float *fused, int32_t B, int32_t W, int32_t V,
                                         int32_t blank, int32_t force_blank, int32_t *parent_out, int32_t *token_out,

@@ -22,7 +22,6 @@ struct Plan {
     float *score;        // [NB][B][W]
     int32_t *node, *len; // [NB][N]
     float *fused;        // [N][V]
-    int32_t *sel_parent, *sel_token;  float *sel_score;   // [B][W]
     int32_t *parent_idx, *token;  uint8_t *active;        // [N]
     float *nx_score;  int32_t *nx_src;  int32_t *nx_count; // [B][R*W], [B]
     int32_t *beam_src;   // [N]
@@ -63,9 +62,6 @@ void make_plan(const qrnnt_model *m, int T, int B, int W, int max_sym, void *ws,
     p.node = cv.take<int32_t>(NB * N);
     p.len = cv.take<int32_t>(NB * N);
     p.fused = cv.take<float>(N * p.V);
-    p.sel_parent = cv.take<int32_t>(N);
-    p.sel_token = cv.take<int32_t>(N);
-    p.sel_score = cv.take<float>(N);
     p.parent_idx = cv.take<int32_t>(N);
     p.token = cv.take<int32_t>(N);
     p.active = cv.take<uint8_t>(N);
@@ -101,57 +97,6 @@ __global__ void decode_init_kernel(float *score0, int32_t *node0, int32_t *len0,
     parent_idx[n] = n;
     token[n] = start_symbol;
     active[n] = 1;
-}
-
-// After the selection of round v: blank picks join the frame's candidate list,
-// label picks become the slots of the next round, in selection order.
-__global__ void route_kernel(const int32_t *__restrict__ sel_parent, const int32_t *__restrict__ sel_token,
-                             const float *__restrict__ sel_score, int B, int W, int R, int blank, int src_buf,
-                             int last_round, const int32_t *__restrict__ node_src, const int32_t *__restrict__ len_src,
-                             float *__restrict__ score_dst, int32_t *__restrict__ node_dst, int32_t *__restrict__ len_dst,
-                             int32_t *__restrict__ parent_idx, int32_t *__restrict__ token, uint8_t *__restrict__ active,
-                             float *__restrict__ nx_score, int32_t *__restrict__ nx_src, int32_t *__restrict__ nx_count,
-                             int32_t *__restrict__ node_tok, int32_t *__restrict__ node_prev, int node_base)
-{
-    const int b = blockIdx.x * blockDim.x + threadIdx.x;
-    if (b >= B) return;
-    const int N = B * W;
-    int n_nx = nx_count[b], n_a = 0;
-    for (int r = 0; r < W; ++r) {
-        const int par = sel_parent[b * W + r];
-        if (par < 0) break;
-        const int tok = sel_token[b * W + r];
-        const float sc = sel_score[b * W + r];
-        const int src_slot = b * W + par;
-        if (tok == blank) {
-            nx_score[(size_t)b * R * W + n_nx] = sc;
-            nx_src[(size_t)b * R * W + n_nx] = src_buf * N + src_slot;
-            ++n_nx;
-        } else if (!last_round) {
-            const int dst = b * W + n_a;
-            const int id = node_base + dst;
-            node_tok[id] = tok;
-            node_prev[id] = node_src[src_slot];
-            score_dst[dst] = sc;
-            node_dst[dst] = id;
-            len_dst[dst] = len_src[src_slot] + 1;
-            parent_idx[dst] = src_slot;
-            token[dst] = tok;
-            active[dst] = 1;
-            ++n_a;
-        }
-    }
-    nx_count[b] = n_nx;
-    if (!last_round)
-        for (int a = n_a; a < W; ++a) {
-            const int dst = b * W + a;
-            score_dst[dst] = -INFINITY;
-            node_dst[dst] = 0;
-            len_dst[dst] = 0;
-            parent_idx[dst] = dst;
-            token[dst] = blank;
-            active[dst] = 0;
-        }
 }
 
 __device__ __forceinline__ bool better(float v, int c, float bv, int bc) { return v > bv || (v == bv && c < bc); }
@@ -287,17 +232,25 @@ qrnnt_status check_model(const qrnnt_model *m)
     return QRNNT_OK;
 }
 
-// All used networks consume `token` and move from buffer src to buffer dst.
+// All used networks consume `token` and move from buffer src to buffer dst.  Layer l
+// of every network goes out as one grouped launch (the networks are independent).
 void advance_nets(const qrnnt_model *m, const Plan &p, int src, int dst, int n_embed_rows, hipStream_t st)
 {
     const size_t N = (size_t)p.N;
-    for (int k = 0; k < 3; ++k) {
-        if (!net_used(m, k)) continue;
-        const qrnnt_net *net = net_of(m, k);
-        for (int l = 0; l < net->n_layers; ++l) {
+    int max_layers = 0;
+    for (int k = 0; k < 3; ++k)
+        if (net_used(m, k) && net_of(m, k)->n_layers > max_layers) max_layers = net_of(m, k)->n_layers;
+    for (int l = 0; l < max_layers; ++l) {
+        QrStepGroup g;
+        g.n = 0;
+        for (int k = 0; k < 3; ++k) {
+            if (!net_used(m, k)) continue;
+            const qrnnt_net *net = net_of(m, k);
+            if (l >= net->n_layers) continue;
             const qrnnt_lstm *L = &net->layer[l];
             const size_t H = (size_t)L->hidden_size;
-            QrStepArgs a = {};
+            QrStepArgs &a = g.p[g.n++];
+            a = QrStepArgs{};
             qr_fill_lstm_weights(a, L);
             if (l == 0) {
                 a.x = net->embed_codes;  a.ld_x = L->input_size;  a.x_row = p.token;  a.n_x_rows = n_embed_rows;
@@ -312,17 +265,24 @@ void advance_nets(const qrnnt_model *m, const Plan &p, int src, int dst, int n_e
             a.h_next = p.net[k].h[l] + (size_t)dst * N * H;  a.ld_hn = (int64_t)H;
             a.c_next = p.net[k].c[l] + (size_t)dst * N * H;
             a.N = p.N;
-            qr_launch_lstm_step(a, false, st);
         }
+        qr_launch_lstm_step_group(g, st);
+    }
+    QrLinearGroup lg;
+    lg.n = 0;
+    for (int k = 0; k < 3; ++k) {
+        if (!net_used(m, k)) continue;
+        const qrnnt_net *net = net_of(m, k);
         const int top = net->n_layers - 1;
-        QrLinearArgs la = {};
+        QrLinearArgs &la = lg.p[lg.n++];
+        la = QrLinearArgs{};
         la.w = (const v4i *)net->out.packed;
         la.nkc = qr_round_up(net->out.cols, QRNNT_KCHUNK) / QRNNT_KCHUNK;
         la.rows = net->out.rows;  la.s_w = net->out.row_scale;  la.bias = net->out_bias;  la.a_scale = net->out_a_scale;
         la.act = p.net[k].h[top] + (size_t)dst * N * net->out.cols;  la.K = net->out.cols;  la.N = p.N;
         la.y = p.net[k].y + (size_t)dst * N * net->out.rows;  la.log_softmax = net->log_softmax;
-        qr_launch_linear(la, st);
     }
+    qr_launch_linear_group(lg, st);
 }
 
 }  // namespace
@@ -402,16 +362,18 @@ extern "C" qrnnt_status qrnnt_decode(const qrnnt_model *m, const float *enc_proj
             ja.lp_src = m->use_src ? p.net[1].y + (size_t)cur * Ns * V : nullptr;
             ja.lp_ext = m->use_ext ? p.net[2].y + (size_t)cur * Ns * V : nullptr;
             qr_launch_joint(ja, st);
-            qr_launch_beam(p.score + (size_t)cur * Ns, p.fused, B, W, V, m->blank, v == max_sym, p.sel_parent,
-                           p.sel_token, p.sel_score, st);
             const int last = (v == max_sym);
-            const int node_base = 1 + (t * max_sym + v) * N;
-            route_kernel<<<(B + 63) / 64, 64, 0, st>>>(p.sel_parent, p.sel_token, p.sel_score, B, W, p.R, m->blank, cur, last,
-                                                       p.node + (size_t)cur * Ns, p.len + (size_t)cur * Ns,
-                                                       p.score + (size_t)nxt * Ns, p.node + (size_t)nxt * Ns,
-                                                       p.len + (size_t)nxt * Ns, p.parent_idx, p.token, p.active,
-                                                       p.nx_score, p.nx_src, p.nx_count, p.node_tok, p.node_prev,
-                                                       node_base);
+            QrRouteArgs ra = {};
+            ra.score_src = p.score + (size_t)cur * Ns;  ra.fused = p.fused;
+            ra.B = B;  ra.W = W;  ra.V = V;  ra.R = p.R;  ra.blank = m->blank;  ra.src_buf = cur;  ra.last_round = last;
+            ra.node_base = 1 + (t * max_sym + v) * N;
+            ra.node_src = p.node + (size_t)cur * Ns;  ra.len_src = p.len + (size_t)cur * Ns;
+            ra.score_dst = p.score + (size_t)nxt * Ns;  ra.node_dst = p.node + (size_t)nxt * Ns;
+            ra.len_dst = p.len + (size_t)nxt * Ns;
+            ra.parent_idx = p.parent_idx;  ra.token = p.token;  ra.active = p.active;
+            ra.nx_score = p.nx_score;  ra.nx_src = p.nx_src;  ra.nx_count = p.nx_count;
+            ra.node_tok = p.node_tok;  ra.node_prev = p.node_prev;
+            qr_launch_beam_route(ra, st);
             if (!last) advance_nets(m, p, cur, nxt, n_embed_rows, st);
         }
         const int dst = (a0 == 0) ? ZB : 0;

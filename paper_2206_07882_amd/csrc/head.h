@@ -1,0 +1,64 @@
+// Split-K contraction for "head" layers: few weight rows (a block owns 64 of them),
+// 16 activation rows per block, the 64-column K blocks dealt round-robin to the 4
+// waves, partial sums reduced through LDS into wave 0.  All loads of a wave are
+// issued before its first MFMA, so a block exposes one memory latency.
+#pragma once
+
+#include "qrnnt_common.h"
+
+#define QR_HEAD_BATCH 4   // K blocks per wave per batch (registers: 4 x (4+1) fragments)
+
+// bfrag(kb) returns this lane's 16 activation codes of K block kb (zero beyond K).
+template <class BFrag>
+__device__ __forceinline__ void qr_head_mma(const v4i *__restrict__ w, int nkc, int n_row_tiles, int rt0, int K,
+                                            BFrag &&bfrag, v4i (&acc)[4], v4i *lds /* [4][4][64] */)
+{
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int nkb = (K + 63) >> 6;
+    const v4i zero = {0, 0, 0, 0};
+    const int m = (int)0xF0F0F0F0u;
+#pragma unroll
+    for (int mt = 0; mt < 4; ++mt) acc[mt] = zero;
+    for (int kb0 = wave; kb0 < nkb; kb0 += 4 * QR_HEAD_BATCH) {
+        v4i pa[QR_HEAD_BATCH][4], pb[QR_HEAD_BATCH];
+#pragma unroll
+        for (int it = 0; it < QR_HEAD_BATCH; ++it) {
+            const int kb = kb0 + 4 * it;
+            const bool ok = kb < nkb;
+            const int kc = ok ? (kb >> 1) : 0;
+#pragma unroll
+            for (int mt = 0; mt < 4; ++mt) {
+                int rt = rt0 + mt;
+                rt = rt < n_row_tiles ? rt : n_row_tiles - 1;
+                pa[it][mt] = w[((size_t)rt * nkc + kc) * 64 + lane];
+            }
+            pb[it] = ok ? bfrag(kb) : zero;
+        }
+#pragma unroll
+        for (int it = 0; it < QR_HEAD_BATCH; ++it) {
+            const int kb = kb0 + 4 * it;
+            if (kb < nkb) {
+                const bool hi = kb & 1;
+#pragma unroll
+                for (int mt = 0; mt < 4; ++mt) {
+                    const v4i a = hi ? (pa[it][mt] & m) : ((pa[it][mt] << 4) & m);
+                    acc[mt] = qr_mfma(a, pb[it], acc[mt]);
+                }
+            }
+        }
+    }
+    // reduce the four partial sums into wave 0
+    if (wave != 0) {
+#pragma unroll
+        for (int mt = 0; mt < 4; ++mt) lds[(wave * 4 + mt) * 64 + lane] = acc[mt];
+    }
+    __syncthreads();
+    if (wave == 0) {
+#pragma unroll
+        for (int wv = 1; wv < 4; ++wv)
+#pragma unroll
+            for (int mt = 0; mt < 4; ++mt) acc[mt] += lds[(wv * 4 + mt) * 64 + lane];
+#pragma unroll
+        for (int mt = 0; mt < 4; ++mt) acc[mt] = acc[mt] >> 4;
+    }
+}

@@ -1,65 +1,53 @@
 // Joint network, log-softmax and density-ratio fusion in one kernel (Sec. 2:
 // encoder and prediction outputs are combined multiplicatively, a linear layer
 // and a log-softmax follow; Eq. 1 adds the weighted LM log-probabilities).
+#include "head.h"
 #include "kernels.h"
-#include "mma_core.h"
 
 namespace {
 
-// One wave per 16 hypotheses.  Lane (col, grp) produces, for every 64-column
-// half, the 16 codes of z that are its own MFMA operand: z never leaves
-// registers.  V <= 64 rows of the output layer are 4 row tiles of this wave.
-__global__ __launch_bounds__(64) void joint_fuse_kernel(const QrJointArgs a)
+// One block (4 waves) per 16 hypotheses; the J columns are dealt to the waves in
+// 64-column blocks.  Lane (col, grp) produces the 16 codes of z that are its own
+// MFMA operand for that block, so z never leaves registers; partial sums meet in
+// wave 0, which holds all V <= 64 rows of the output layer for the log-softmax.
+__global__ __launch_bounds__(256) void joint_fuse_kernel(const QrJointArgs a)
 {
-    const int lane = threadIdx.x & 63;
+    __shared__ v4i lds[4 * 4 * 64];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int col = lane & 15, grp = lane >> 4;
     int n = blockIdx.x * 16 + col;
     const bool nv = n < a.N;
     n = nv ? n : a.N - 1;
     int fr = a.frame_row ? a.frame_row[n] : a.frame_base + n / a.rows_per_utt;
     fr = fr < 0 ? 0 : (fr >= a.n_enc_rows ? a.n_enc_rows - 1 : fr);
-    const float *e = a.enc + (int64_t)fr * a.J;
-    const float *p = a.pred + (int64_t)n * a.J;
-    const int n_row_tiles = (a.V + 15) >> 4;
-
-    v4i acc[4];
-    const v4i zero = {0, 0, 0, 0};
+    const float *e = a.enc + (int64_t)fr * a.J + grp * 16;
+    const float *p = a.pred + (int64_t)n * a.J + grp * 16;
+    int8_t *zq = a.dbg_zq ? a.dbg_zq + (int64_t)n * a.J + grp * 16 : nullptr;
+    const int J = a.J;
+    const float z_inv = a.z_inv;
+    auto bfrag = [&](int kb) -> v4i {
+        v4i b = {0, 0, 0, 0};
+        if (kb * 64 + grp * 16 < J) {
 #pragma unroll
-    for (int mt = 0; mt < 4; ++mt) acc[mt] = zero;
-
-    for (int kc = 0; kc < a.nkc; ++kc) {
-        v4i b[2];
+            for (int d = 0; d < 4; ++d) {
+                const v4f ev = *(const v4f *)(e + kb * 64 + 4 * d);
+                const v4f pv = *(const v4f *)(p + kb * 64 + 4 * d);
+                uint32_t word = 0;
 #pragma unroll
-        for (int half = 0; half < 2; ++half) {
-            const int k0 = kc * QRNNT_KCHUNK + half * 64 + grp * 16;
-            b[half] = zero;
-            if (k0 < a.J) {
-#pragma unroll
-                for (int d = 0; d < 4; ++d) {
-                    const v4f ev = *(const v4f *)(e + k0 + 4 * d);
-                    const v4f pv = *(const v4f *)(p + k0 + 4 * d);
-                    uint32_t word = 0;
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) {
-                        const float z = tanhf(ev[i] * pv[i]);
-                        const int q = qr_quant4(z, a.z_inv);
-                        word |= (uint32_t)(q & 0xFF) << (8 * i);
-                    }
-                    b[half][d] = (int)word;
+                for (int i = 0; i < 4; ++i) {
+                    const float z = qr_tanh(ev[i] * pv[i]);
+                    word |= (uint32_t)(qr_quant4(z, z_inv) & 0xFF) << (8 * i);
                 }
-                if (a.dbg_zq && nv) *(v4i *)(a.dbg_zq + (int64_t)n * a.J + k0) = b[half];
+                b[d] = (int)word;
             }
+            if (zq && nv) *(v4i *)(zq + kb * 64) = b;
         }
-#pragma unroll
-        for (int mt = 0; mt < 4; ++mt) {
-            const int rt = mt < n_row_tiles ? mt : n_row_tiles - 1;
-            const v4i pw = a.w[((size_t)rt * a.nkc + kc) * 64 + lane];
-            v4i lo, hi;
-            qr_unpack(pw, lo, hi);
-            acc[mt] = qr_mfma(lo, b[0], acc[mt]);
-            acc[mt] = qr_mfma(hi, b[1], acc[mt]);
-        }
-    }
+        return b;
+    };
+    const int n_row_tiles = (a.V + 15) >> 4;
+    v4i acc[4];
+    qr_head_mma(a.w, a.nkc, n_row_tiles, 0, J, bfrag, acc, lds);
+    if (wave != 0) return;
 
     float v[4][4];
     float m = -INFINITY;
@@ -69,7 +57,7 @@ __global__ __launch_bounds__(64) void joint_fuse_kernel(const QrJointArgs a)
         for (int i = 0; i < 4; ++i) {
             const int k = mt * 16 + grp * 4 + i;
             if (k < a.V) {
-                v[mt][i] = (a.z_scale * a.s_w[k]) * (float)(acc[mt][i] >> 4) + (a.b_out ? a.b_out[k] : 0.0f);
+                v[mt][i] = (a.z_scale * a.s_w[k]) * (float)acc[mt][i] + (a.b_out ? a.b_out[k] : 0.0f);
                 m = fmaxf(m, v[mt][i]);
             } else {
                 v[mt][i] = -INFINITY;
@@ -108,7 +96,7 @@ __global__ __launch_bounds__(64) void joint_fuse_kernel(const QrJointArgs a)
 
 void qr_launch_joint(const QrJointArgs &a, hipStream_t st)
 {
-    joint_fuse_kernel<<<(a.N + 15) / 16, 64, 0, st>>>(a);
+    joint_fuse_kernel<<<(a.N + 15) / 16, 256, 0, st>>>(a);
 }
 
 extern "C" qrnnt_status qrnnt_joint_fuse(const float *enc_proj, int32_t n_enc_rows, const int32_t *frame_row,

@@ -26,6 +26,12 @@ struct QrStepArgs {
     float x_scale, h_scale, h_inv;
 };
 
+#define QR_MAX_GROUP 3
+struct QrStepGroup {
+    QrStepArgs p[QR_MAX_GROUP];
+    int n;
+};
+
 struct QrLinearArgs {
     const v4i *w;  int nkc, rows;
     const float *s_w, *bias;
@@ -33,6 +39,11 @@ struct QrLinearArgs {
     const int8_t *act;  int K, N;
     float *y;  int32_t *dbg_acc;
     int log_softmax;
+};
+
+struct QrLinearGroup {
+    QrLinearArgs p[QR_MAX_GROUP];
+    int n;
 };
 
 struct QrJointArgs {
@@ -48,9 +59,22 @@ struct QrJointArgs {
     float *lp_out;  int8_t *dbg_zq;  float *fused;
 };
 
+struct QrRouteArgs {
+    const float *score_src;  const float *fused;   // [B,W], [B*W,V] of the current round
+    int B, W, V, R, blank, src_buf, last_round, node_base;
+    const int32_t *node_src, *len_src;              // [N] of the current round
+    float *score_dst;  int32_t *node_dst, *len_dst; // [N] of the next round
+    int32_t *parent_idx, *token;  uint8_t *active;  // [N] inputs of the next network advance
+    float *nx_score;  int32_t *nx_src, *nx_count;   // the frame's candidate list
+    int32_t *node_tok, *node_prev;                  // label trie
+};
+
+QR_HIDDEN void qr_launch_beam_route(const QrRouteArgs &a, hipStream_t st);
 QR_HIDDEN void qr_fill_lstm_weights(QrStepArgs &a, const qrnnt_lstm *L);
 QR_HIDDEN qrnnt_status qr_check_lstm(const qrnnt_lstm *L);
 QR_HIDDEN void qr_launch_lstm_step(const QrStepArgs &a, bool use_gx, hipStream_t st);
+QR_HIDDEN void qr_launch_lstm_step_group(const QrStepGroup &g, hipStream_t st);
+QR_HIDDEN void qr_launch_linear_group(const QrLinearGroup &g, hipStream_t st);
 QR_HIDDEN void qr_launch_linear(const QrLinearArgs &a, hipStream_t st);
 QR_HIDDEN void qr_launch_joint(const QrJointArgs &a, hipStream_t st);
 QR_HIDDEN void qr_launch_beam(const float *score, const float *fused, int B, int W, int V, int blank, int force_blank,

@@ -1,129 +1,90 @@
 // Quantized linear layer (Sec. 3.2: weights and inputs of linear layers are
 // quantized) with an optional fused log-softmax for the LM output layer (Sec. 2).
+#include "head.h"
 #include "kernels.h"
-#include "mma_core.h"
 
 namespace {
 
-// Grid: x = groups of 4*MT row tiles, y = groups of NT*16 activation rows.
-template <int MT, int NT>
-__global__ __launch_bounds__(256) void linear_kernel(const v4i *__restrict__ w, int nkc, int rows, const float *__restrict__ s_w,
-                                                      const float *__restrict__ bias, float a_scale,
-                                                      const int8_t *__restrict__ act, int K, int N,
-                                                      float *__restrict__ y, int32_t *__restrict__ dbg_acc)
+// Grid: x = blocks of 16 activation rows, y = blocks of 64 weight rows, z = problem.
+__global__ __launch_bounds__(256) void linear_head_kernel(const QrLinearGroup g)
 {
+    __shared__ v4i lds[4 * 4 * 64];
+    const QrLinearArgs &a = g.p[blockIdx.z];
+    const int n_row_tiles = (a.rows + 15) >> 4;
+    const int rt0 = blockIdx.y * 4;
+    if (rt0 >= n_row_tiles || (int)blockIdx.x * 16 >= a.N) return;   // uniform per block
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int col = lane & 15, grp = lane >> 4;
-    const int n_row_tiles = (rows + 15) >> 4;
-    const int rt0 = (blockIdx.x * 4 + wave) * MT;
-    if (rt0 >= n_row_tiles) return;
-    const int8_t *aptr[NT];
-#pragma unroll
-    for (int nt = 0; nt < NT; ++nt) {
-        int n = (blockIdx.y * NT + nt) * 16 + col;
-        n = n < N ? n : N - 1;
-        aptr[nt] = act + (int64_t)n * K + grp * 16;
-    }
-    v4i acc[MT][NT];
-    const v4i zero = {0, 0, 0, 0};
-#pragma unroll
-    for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-        for (int nt = 0; nt < NT; ++nt) acc[mt][nt] = zero;
-    qr_mma_range<MT, NT>(w, nkc, n_row_tiles, rt0, lane, aptr, K, acc);
-#pragma unroll
-    for (int mt = 0; mt < MT; ++mt) {
-        const int r0 = (rt0 + mt) * 16 + grp * 4;
-#pragma unroll
-        for (int nt = 0; nt < NT; ++nt) {
-            const int n = (blockIdx.y * NT + nt) * 16 + col;
-            if (n >= N) continue;
-            const v4i v = acc[mt][nt] >> 4;
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int r = r0 + i;
-                if (r >= rows) continue;
-                y[(int64_t)n * rows + r] = (a_scale * s_w[r]) * (float)v[i] + (bias ? bias[r] : 0.0f);
-                if (dbg_acc) dbg_acc[(int64_t)n * rows + r] = v[i];
-            }
-        }
-    }
-}
-
-// rows <= 64: one wave owns all rows of 16 activation rows, so the log-softmax
-// over the rows is a reduction over the lane's own values and the four lane
-// groups (xor 16, 32).
-__global__ __launch_bounds__(64) void linear_logsoftmax_kernel(const v4i *__restrict__ w, int nkc, int rows,
-                                                                const float *__restrict__ s_w, const float *__restrict__ bias,
-                                                                float a_scale, const int8_t *__restrict__ act, int K, int N,
-                                                                float *__restrict__ y, int32_t *__restrict__ dbg_acc)
-{
-    const int lane = threadIdx.x & 63;
-    const int col = lane & 15, grp = lane >> 4;
-    const int n_row_tiles = (rows + 15) >> 4;
-    const int8_t *aptr[1];
     int n = blockIdx.x * 16 + col;
-    const bool nv = n < N;
-    n = nv ? n : N - 1;
-    aptr[0] = act + (int64_t)n * K + grp * 16;
-    v4i acc[4][1];
-    const v4i zero = {0, 0, 0, 0};
-#pragma unroll
-    for (int mt = 0; mt < 4; ++mt) acc[mt][0] = zero;
-    qr_mma_range<4, 1>(w, nkc, n_row_tiles, 0, lane, aptr, K, acc);
+    const bool nv = n < a.N;
+    n = nv ? n : a.N - 1;
+    const int8_t *arow = a.act + (int64_t)n * a.K + grp * 16;
+    const int K = a.K;
+    auto bfrag = [&](int kb) -> v4i {
+        const v4i zero = {0, 0, 0, 0};
+        return (kb * 64 + grp * 16 < K) ? *(const v4i *)(arow + kb * 64) : zero;
+    };
+    v4i acc[4];
+    qr_head_mma(a.w, a.nkc, n_row_tiles, rt0, K, bfrag, acc, lds);
+    if (wave != 0) return;
+
     float v[4][4];
-    float m = -INFINITY;
+    float mx = -INFINITY;
 #pragma unroll
     for (int mt = 0; mt < 4; ++mt)
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            const int r = mt * 16 + grp * 4 + i;
-            const int a = acc[mt][0][i] >> 4;
-            if (r < rows) {
-                v[mt][i] = (a_scale * s_w[r]) * (float)a + (bias ? bias[r] : 0.0f);
-                if (dbg_acc && nv) dbg_acc[(int64_t)n * rows + r] = a;
-                m = fmaxf(m, v[mt][i]);
+            const int r = (rt0 + mt) * 16 + grp * 4 + i;
+            if (r < a.rows) {
+                v[mt][i] = (a.a_scale * a.s_w[r]) * (float)acc[mt][i] + (a.bias ? a.bias[r] : 0.0f);
+                if (a.dbg_acc && nv) a.dbg_acc[(int64_t)n * a.rows + r] = acc[mt][i];
+                mx = fmaxf(mx, v[mt][i]);
             } else {
                 v[mt][i] = -INFINITY;
             }
         }
-    m = fmaxf(m, __shfl_xor(m, 16));
-    m = fmaxf(m, __shfl_xor(m, 32));
-    float sum = 0.0f;
+    float lse = 0.0f;
+    if (a.log_softmax) {   // rows <= 64: the whole row set is in this wave (4 lane groups x 16 values)
+        mx = fmaxf(mx, __shfl_xor(mx, 16));
+        mx = fmaxf(mx, __shfl_xor(mx, 32));
+        float sum = 0.0f;
 #pragma unroll
-    for (int mt = 0; mt < 4; ++mt)
+        for (int mt = 0; mt < 4; ++mt)
 #pragma unroll
-        for (int i = 0; i < 4; ++i) sum += (mt * 16 + grp * 4 + i < rows) ? expf(v[mt][i] - m) : 0.0f;
-    sum += __shfl_xor(sum, 16);
-    sum += __shfl_xor(sum, 32);
-    const float lse = m + logf(sum);
+            for (int i = 0; i < 4; ++i) sum += (mt * 16 + grp * 4 + i < a.rows) ? expf(v[mt][i] - mx) : 0.0f;
+        sum += __shfl_xor(sum, 16);
+        sum += __shfl_xor(sum, 32);
+        lse = mx + logf(sum);
+    }
     if (!nv) return;
 #pragma unroll
     for (int mt = 0; mt < 4; ++mt)
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            const int r = mt * 16 + grp * 4 + i;
-            if (r < rows) y[(int64_t)n * rows + r] = v[mt][i] - lse;
+            const int r = (rt0 + mt) * 16 + grp * 4 + i;
+            if (r < a.rows) a.y[(int64_t)n * a.rows + r] = v[mt][i] - lse;
         }
 }
 
 }  // namespace
 
+void qr_launch_linear_group(const QrLinearGroup &g, hipStream_t st)
+{
+    int gx = 0, gy = 0;
+    for (int i = 0; i < g.n; ++i) {
+        const int nb = (g.p[i].N + 15) / 16, rb = ((g.p[i].rows + 15) / 16 + 3) / 4;
+        gx = nb > gx ? nb : gx;
+        gy = rb > gy ? rb : gy;
+    }
+    linear_head_kernel<<<dim3(gx, gy, g.n), 256, 0, st>>>(g);
+}
+
 void qr_launch_linear(const QrLinearArgs &a, hipStream_t st)
 {
-    const int n_row_tiles = (a.rows + 15) / 16;
-    if (a.log_softmax) {
-        linear_logsoftmax_kernel<<<(a.N + 15) / 16, 64, 0, st>>>(a.w, a.nkc, a.rows, a.s_w, a.bias, a.a_scale, a.act, a.K,
-                                                                 a.N, a.y, a.dbg_acc);
-    } else if (a.N <= 16) {
-        dim3 grid((n_row_tiles + 3) / 4, 1);
-        linear_kernel<1, 1><<<grid, 256, 0, st>>>(a.w, a.nkc, a.rows, a.s_w, a.bias, a.a_scale, a.act, a.K, a.N, a.y,
-                                                  a.dbg_acc);
-    } else {
-        dim3 grid((n_row_tiles + 7) / 8, (a.N + 63) / 64);
-        linear_kernel<2, 4><<<grid, 256, 0, st>>>(a.w, a.nkc, a.rows, a.s_w, a.bias, a.a_scale, a.act, a.K, a.N, a.y,
-                                                  a.dbg_acc);
-    }
+    QrLinearGroup g;
+    g.p[0] = a;
+    g.n = 1;
+    qr_launch_linear_group(g, st);
 }
 
 extern "C" qrnnt_status qrnnt_linear(const qrnnt_qmat *w, const float *bias, float a_scale, const int8_t *a, int32_t N,

@@ -2,7 +2,9 @@
 // with the whole cell fused behind the contraction (Sec. 3.2: integer MACs for
 // W_ih and W_hh, fp bias and cell state; Sec. 3.4: the hidden state is
 // quantized once, at the cell output).
+#include <cstdlib>
 #include "kernels.h"
+#include "mma_pipe.h"
 #include "mma_core.h"
 
 namespace {
@@ -106,9 +108,9 @@ __global__ __launch_bounds__(256) void lstm_step_kernel(const QrStepArgs a)
                 float p[4];
 #pragma unroll
                 for (int g = 0; g < 4; ++g) p[g] = pre[mt][nt][g] + (sh[g] * (float)ah[g] + bb[g]);
-                const float gi = qr_sigmoid(p[0]), gf = qr_sigmoid(p[1]), gg = tanhf(p[2]), go = qr_sigmoid(p[3]);
+                const float gi = qr_sigmoid(p[0]), gf = qr_sigmoid(p[1]), gg = qr_tanh(p[2]), go = qr_sigmoid(p[3]);
                 cn = gf * cp + gi * gg;
-                const float h = go * tanhf(cn);
+                const float h = go * qr_tanh(cn);
                 code = (int8_t)qr_quant4(h, a.h_inv);
                 if (a.dbg_gates) {
                     float *dg = a.dbg_gates + (int64_t)n * 4 * a.H + j;
@@ -122,6 +124,226 @@ __global__ __launch_bounds__(256) void lstm_step_kernel(const QrStepArgs a)
     }
 }
 
+
+// Compute-bound variant (many hypotheses): multi-stage LDS ring, see mma_pipe.h.
+// Grid: x = blocks of 32*MT gate rows (8*MT cells), y = blocks of 32*NT hypotheses,
+// z = problem of a group (independent layer-steps batched into one launch).
+// Every global load outside the ring is issued in a batch ahead of its first use
+// and the cell update is branch-free, so a block exposes one memory latency per
+// batch instead of one per element.  DBG adds the int32 / gate outputs.
+template <int MT, int NT, int S, bool USE_GX, bool DBG>
+__global__ __launch_bounds__(256, 2) void lstm_step_pipe_kernel(const QrStepGroup g)
+{
+    using P = QrPipe<MT, NT, S>;
+    extern __shared__ __attribute__((aligned(1024))) char lds[];
+    const QrStepArgs &a = g.p[blockIdx.z];
+    const int H = a.H, N = a.N;
+    const int n_row_tiles = H >> 2;
+    const int block_rt0 = blockIdx.x * 2 * MT;
+    const int n0 = blockIdx.y * P::BN;
+    if (block_rt0 >= n_row_tiles || n0 >= N) return;   // uniform per block
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int col = lane & 15, grp = lane >> 4;
+    const int wm = wave & 1, wn = wave >> 1;
+    const int rt0 = block_rt0 + wm * MT;
+
+    // ---- indices: rows this thread stages (ld_*) and hypotheses this lane finishes (n_of)
+    int ld_n[NT], ld_s[NT], ld_x[NT], n_of[NT], src_of[NT];
+#pragma unroll
+    for (int i = 0; i < NT; ++i) {
+        const int n = n0 + qr_pipe_b_row<NT>(wave, i, col);
+        ld_n[i] = n < N ? n : N - 1;
+        const int m = n0 + (wn * NT + i) * 16 + col;
+        n_of[i] = m;
+        src_of[i] = m < N ? m : N - 1;
+    }
+    if (a.parent) {
+#pragma unroll
+        for (int i = 0; i < NT; ++i) { ld_s[i] = a.parent[ld_n[i]]; src_of[i] = a.parent[src_of[i]]; }
+    } else {
+#pragma unroll
+        for (int i = 0; i < NT; ++i) ld_s[i] = ld_n[i];
+    }
+    if (!USE_GX && a.x_row) {
+#pragma unroll
+        for (int i = 0; i < NT; ++i) ld_x[i] = a.x_row[ld_n[i]];
+    } else {
+#pragma unroll
+        for (int i = 0; i < NT; ++i) ld_x[i] = ld_n[i];
+    }
+    constexpr int NPH = USE_GX ? 1 : 2;
+    QrPhase<NT> ph[NPH];
+#pragma unroll
+    for (int i = 0; i < NT; ++i) {
+        int s = ld_s[i];
+        s = s < 0 ? 0 : (s >= a.n_slots ? a.n_slots - 1 : s);
+        ph[NPH - 1].row[i] = a.h_prev + (int64_t)s * a.ld_hp;
+        if (!USE_GX) {
+            int xr = ld_x[i];
+            xr = xr < 0 ? 0 : (xr >= a.n_x_rows ? a.n_x_rows - 1 : xr);
+            ph[0].row[i] = a.x + (int64_t)xr * a.ld_x;
+        }
+        int q = src_of[i];
+        src_of[i] = q < 0 ? 0 : (q >= a.n_slots ? a.n_slots - 1 : q);
+    }
+    if (!USE_GX) { ph[0].w = a.wih;  ph[0].nkc = a.nkc_x;  ph[0].K = a.I; }
+    ph[NPH - 1].w = a.whh;  ph[NPH - 1].nkc = a.nkc_h;  ph[NPH - 1].K = H;
+
+    v4i acc[MT][NT];
+    float pre[MT][NT][4];
+    const v4i zero = {0, 0, 0, 0};
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) acc[mt][nt] = zero;
+
+    // cell index of (mt, this lane); clamped copy for loads
+    int jc[MT];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+        const int j = (rt0 + mt) * 4 + grp;
+        jc[mt] = j < H ? j : H - 1;
+    }
+
+    // input part -> fp32 (s_x * s_wih[r] * accx); the accumulators restart for the recurrent part
+    auto x_done = [&]() {
+        float sx[MT][4];
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+            for (int gt = 0; gt < 4; ++gt) sx[mt][gt] = a.x_scale * a.s_wih[gt * H + jc[mt]];
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) {
+                const v4i ax = acc[mt][nt] >> 4;
+                if (DBG && a.dbg_accx && (rt0 + mt) * 4 + grp < H && n_of[nt] < N)
+#pragma unroll
+                    for (int gt = 0; gt < 4; ++gt) a.dbg_accx[(int64_t)n_of[nt] * 4 * H + gt * H + jc[mt]] = ax[gt];
+#pragma unroll
+                for (int gt = 0; gt < 4; ++gt) pre[mt][nt][gt] = sx[mt][gt] * (float)ax[gt];
+                acc[mt][nt] = zero;
+            }
+    };
+    if (USE_GX) {
+        float sx[MT][4];
+        v4i ax[MT][NT];
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+#pragma unroll
+            for (int gt = 0; gt < 4; ++gt) sx[mt][gt] = a.x_scale * a.s_wih[gt * H + jc[mt]];
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) {
+                const int n = n_of[nt] < N ? n_of[nt] : N - 1;
+                ax[mt][nt] = *(const v4i *)(a.gx + (int64_t)n * a.ld_gx + 4 * jc[mt]);
+            }
+        }
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) {
+                if (DBG && a.dbg_accx && (rt0 + mt) * 4 + grp < H && n_of[nt] < N)
+#pragma unroll
+                    for (int gt = 0; gt < 4; ++gt) a.dbg_accx[(int64_t)n_of[nt] * 4 * H + gt * H + jc[mt]] = ax[mt][nt][gt];
+#pragma unroll
+                for (int gt = 0; gt < 4; ++gt) pre[mt][nt][gt] = sx[mt][gt] * (float)ax[mt][nt][gt];
+            }
+    }
+
+    qr_pipe_mma<MT, NT, S, NPH>(ph, n_row_tiles, block_rt0, lds, acc, x_done);
+
+    // ---- fused cell: batched loads, then branch-free arithmetic, then stores
+    float cp[MT][NT], sh[MT][4], bb[MT][4];
+    int act[NT], hp_code[MT][NT];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+#pragma unroll
+        for (int gt = 0; gt < 4; ++gt) {
+            sh[mt][gt] = a.h_scale * a.s_whh[gt * H + jc[mt]];
+            bb[mt][gt] = a.bias[gt * H + jc[mt]];
+        }
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) cp[mt][nt] = a.c_prev[(int64_t)src_of[nt] * H + jc[mt]];
+    }
+    if (a.active) {
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) {
+            act[nt] = a.active[n_of[nt] < N ? n_of[nt] : N - 1];
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) hp_code[mt][nt] = a.h_prev[(int64_t)src_of[nt] * a.ld_hp + jc[mt]];
+        }
+    } else {
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) {
+            act[nt] = 1;
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) hp_code[mt][nt] = 0;
+        }
+    }
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+        const bool jv = (rt0 + mt) * 4 + grp < H;
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) {
+            const int n = n_of[nt];
+            const v4i ah = acc[mt][nt] >> 4;
+            float p[4];
+#pragma unroll
+            for (int gt = 0; gt < 4; ++gt) p[gt] = pre[mt][nt][gt] + (sh[mt][gt] * (float)ah[gt] + bb[mt][gt]);
+            const float gi = qr_sigmoid(p[0]), gf = qr_sigmoid(p[1]), gg = qr_tanh(p[2]), go = qr_sigmoid(p[3]);
+            float cn = gf * cp[mt][nt] + gi * gg;
+            const float h = go * qr_tanh(cn);
+            int code = qr_quant4(h, a.h_inv);
+            const bool on = act[nt] != 0;
+            cn = on ? cn : cp[mt][nt];
+            code = on ? code : hp_code[mt][nt];
+            if (jv && n < N) {
+                a.c_next[(int64_t)n * H + jc[mt]] = cn;
+                a.h_next[(int64_t)n * a.ld_hn + jc[mt]] = (int8_t)code;
+                if (a.h_copy) a.h_copy[(int64_t)n * H + jc[mt]] = (int8_t)code;
+                if (DBG) {
+                    if (a.dbg_acch)
+#pragma unroll
+                        for (int gt = 0; gt < 4; ++gt) a.dbg_acch[(int64_t)n * 4 * H + gt * H + jc[mt]] = ah[gt];
+                    if (a.dbg_gates && on) {
+                        float *dg = a.dbg_gates + (int64_t)n * 4 * H + jc[mt];
+                        dg[0] = gi; dg[H] = gf; dg[2 * H] = gg; dg[3 * H] = go;
+                    }
+                }
+            }
+        }
+    }
+}
+
+template <int MT, int NT, int S, bool USE_GX, bool DBG>
+void launch_pipe_d(const QrStepGroup &g, hipStream_t st)
+{
+    using P = QrPipe<MT, NT, S>;
+    static bool configured = false;
+    auto kern = lstm_step_pipe_kernel<MT, NT, S, USE_GX, DBG>;
+    if (!configured) {
+        (void)hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, P::LDS_BYTES);
+        configured = true;
+    }
+    int gx = 0, gy = 0;
+    for (int i = 0; i < g.n; ++i) {
+        const int rb = ((g.p[i].H >> 2) + 2 * MT - 1) / (2 * MT), nb = (g.p[i].N + P::BN - 1) / P::BN;
+        gx = rb > gx ? rb : gx;
+        gy = nb > gy ? nb : gy;
+    }
+    kern<<<dim3(gx, gy, g.n), 256, P::LDS_BYTES, st>>>(g);
+}
+
+template <int MT, int NT, int S, bool USE_GX>
+void launch_pipe(const QrStepGroup &g, hipStream_t st)
+{
+    bool dbg = false;
+    for (int i = 0; i < g.n; ++i) dbg = dbg || g.p[i].dbg_accx || g.p[i].dbg_acch || g.p[i].dbg_gates;
+    if (dbg) launch_pipe_d<MT, NT, S, USE_GX, true>(g, st);
+    else launch_pipe_d<MT, NT, S, USE_GX, false>(g, st);
+}
+
 template <bool USE_GX>
 void launch_step_t(const QrStepArgs &a, hipStream_t st)
 {
@@ -133,8 +355,14 @@ void launch_step_t(const QrStepArgs &a, hipStream_t st)
         dim3 grid((n_row_tiles + 3) / 4, 1);
         lstm_step_kernel<1, 2, USE_GX><<<grid, 256, 0, st>>>(a);
     } else {
-        dim3 grid((n_row_tiles + 7) / 8, (a.N + 63) / 64);
-        lstm_step_kernel<2, 4, USE_GX><<<grid, 256, 0, st>>>(a);
+        QrStepGroup g;
+        g.p[0] = a;
+        g.n = 1;
+        static int exp_s = getenv("QRNNT_S") ? atoi(getenv("QRNNT_S")) : 3;
+        if (a.N <= 64) launch_pipe<4, 2, 3, USE_GX>(g, st);
+        else if (exp_s == 4) launch_pipe<4, 4, 4, USE_GX>(g, st);
+        else if (exp_s == 2) launch_pipe<4, 4, 2, USE_GX>(g, st);
+        else launch_pipe<4, 4, 3, USE_GX>(g, st);
     }
 }
 
@@ -228,11 +456,19 @@ void qr_launch_lstm_step(const QrStepArgs &a, bool use_gx, hipStream_t st)
     if (use_gx) launch_step_t<true>(a, st); else launch_step_t<false>(a, st);
 }
 
-extern "C" qrnnt_status qrnnt_lstm_step(const qrnnt_lstm *L, const int8_t *x_codes, const int32_t *x_row,
-                                        int32_t n_x_rows, const int32_t *parent, const int8_t *h_prev,
-                                        const float *c_prev, int32_t n_slots, const uint8_t *active, int32_t N,
-                                        int8_t *h_next, float *c_next, int32_t *dbg_accx, int32_t *dbg_acch,
-                                        float *dbg_gates, void *stream)
+void qr_launch_lstm_step_group(const QrStepGroup &g, hipStream_t st)
+{
+    // one launch when every member is in the compute-bound regime, else member by member
+    bool all_big = true;
+    for (int i = 0; i < g.n; ++i) all_big = all_big && g.p[i].N > 64;
+    if (all_big && g.n > 1) launch_pipe<4, 4, 3, false>(g, st);
+    else
+        for (int i = 0; i < g.n; ++i) launch_step_t<false>(g.p[i], st);
+}
+
+static qrnnt_status make_step_args(QrStepArgs &a, const qrnnt_lstm *L, const int8_t *x_codes, const int32_t *x_row,
+                                   int32_t n_x_rows, const int32_t *parent, const int8_t *h_prev, const float *c_prev,
+                                   int32_t n_slots, const uint8_t *active, int32_t N, int8_t *h_next, float *c_next)
 {
     qrnnt_status s = qr_check_lstm(L);
     if (s != QRNNT_OK) return s;
@@ -243,15 +479,44 @@ extern "C" qrnnt_status qrnnt_lstm_step(const qrnnt_lstm *L, const int8_t *x_cod
     QR_REQUIRE(qr_aligned(x_codes, 16) && qr_aligned(h_prev, 16), QRNNT_ERR_ALIGN);
     QR_REQUIRE(qr_aligned(c_prev, 4) && qr_aligned(c_next, 4), QRNNT_ERR_ALIGN);
     QR_REQUIRE((const void *)h_next != (const void *)h_prev && c_next != c_prev, QRNNT_ERR_RANGE);
-    QrStepArgs a = {};
+    a = QrStepArgs{};
     qr_fill_lstm_weights(a, L);
     a.x = x_codes;  a.ld_x = L->input_size;  a.x_row = x_row;  a.n_x_rows = n_x_rows;
     a.parent = parent;  a.n_slots = n_slots;
     a.h_prev = h_prev;  a.ld_hp = L->hidden_size;  a.c_prev = c_prev;  a.active = active;
     a.h_next = h_next;  a.ld_hn = L->hidden_size;  a.c_next = c_next;
-    a.dbg_accx = dbg_accx;  a.dbg_acch = dbg_acch;  a.dbg_gates = dbg_gates;
     a.N = N;
+    return QRNNT_OK;
+}
+
+extern "C" qrnnt_status qrnnt_lstm_step(const qrnnt_lstm *L, const int8_t *x_codes, const int32_t *x_row,
+                                        int32_t n_x_rows, const int32_t *parent, const int8_t *h_prev,
+                                        const float *c_prev, int32_t n_slots, const uint8_t *active, int32_t N,
+                                        int8_t *h_next, float *c_next, int32_t *dbg_accx, int32_t *dbg_acch,
+                                        float *dbg_gates, void *stream)
+{
+    QrStepArgs a;
+    qrnnt_status s = make_step_args(a, L, x_codes, x_row, n_x_rows, parent, h_prev, c_prev, n_slots, active, N, h_next,
+                                    c_next);
+    if (s != QRNNT_OK) return s;
+    a.dbg_accx = dbg_accx;  a.dbg_acch = dbg_acch;  a.dbg_gates = dbg_gates;
     qr_launch_lstm_step(a, false, (hipStream_t)stream);
+    return qr_launch_status();
+}
+
+extern "C" qrnnt_status qrnnt_lstm_step_group(const qrnnt_step_desc *steps, int32_t n_steps, void *stream)
+{
+    QR_REQUIRE(steps != nullptr, QRNNT_ERR_NULL);
+    QR_REQUIRE(n_steps >= 1 && n_steps <= QR_MAX_GROUP, QRNNT_ERR_RANGE);
+    QrStepGroup g;
+    g.n = n_steps;
+    for (int i = 0; i < n_steps; ++i) {
+        const qrnnt_step_desc &d = steps[i];
+        qrnnt_status s = make_step_args(g.p[i], d.L, d.x_codes, d.x_row, d.n_x_rows, d.parent, d.h_prev, d.c_prev,
+                                        d.n_slots, d.active, d.N, d.h_next, d.c_next);
+        if (s != QRNNT_OK) return s;
+    }
+    qr_launch_lstm_step_group(g, (hipStream_t)stream);
     return qr_launch_status();
 }
 

@@ -1,0 +1,162 @@
+// Block-level W4A8 contraction with a multi-stage LDS ring fed by direct
+// global->LDS loads (gfx950 global_load_lds_dwordx4), for the compute-bound shapes.
+//
+// 256 threads = 2 x 2 waves; a wave owns MT x NT 16x16 MFMA tiles, a block
+// BM = 32*MT weight rows x BN = 32*NT activation rows.  Per 128-column chunk a
+// stage of the ring holds
+//   A: 2*MT weight blocks of 1 KiB, copied verbatim from the TILED blob (the blob
+//      is already in operand order, so lane l later reads bytes [16l, 16l+16));
+//   B: 4*NT activation blocks of 1 KiB, one per (column tile, 64-column half),
+//      gathered so that lane l = 16*grp + col of a block holds row (tile*16+col),
+//      bytes half*64 + grp*16 .. +16: again exactly the lane's MFMA operand.
+// Every LDS read is therefore a linear, conflict-free 128-bit read, and the data
+// never passes through registers on its way in, so S-1 chunks can be in flight
+// per block (what hides the ~1 us L2/HBM latency at this consumption rate).
+//
+// The direct loads are issued from inline asm (the compiler would otherwise wait
+// for all of them before any LDS read); their completion is tracked by hand with
+// s_waitcnt vmcnt(n) + s_barrier.  Between the first issue and the end of
+// qr_pipe_mma no other vector-memory instruction may be issued by the caller.
+// Activation columns >= K inside the last chunk are fetched from column 0 of the
+// same row: they meet the zero padding of the weight blob.
+#pragma once
+
+#include "qrnnt_common.h"
+
+template <int NT>
+struct QrPhase {
+    const v4i *w;            // TILED blob
+    int nkc;                 // 128-column chunks
+    int K;                   // valid activation columns
+    const int8_t *row[NT];   // this thread's activation rows (one per B block it loads)
+};
+
+template <int MT, int NT, int S>
+struct QrPipe {
+    static_assert(MT % 2 == 0 && NT % 2 == 0, "tiles per wave must be even");
+    static constexpr int BM = 32 * MT, BN = 32 * NT;
+    static constexpr int A_BLOCKS = 2 * MT, B_BLOCKS = 4 * NT;
+    static constexpr int A_PER_WAVE = A_BLOCKS / 4, B_PER_WAVE = NT;
+    static constexpr int LOADS = A_PER_WAVE + B_PER_WAVE;   // vector-memory loads per thread per chunk
+    static constexpr int STAGE_BYTES = (A_BLOCKS + B_BLOCKS) * 1024;
+    static constexpr int LDS_BYTES = S * STAGE_BYTES;
+    static constexpr int DIST = S - 1;                       // chunks in flight
+};
+
+__device__ __forceinline__ void qr_load_lds16(const void *gptr, unsigned lds_addr)
+{
+    // M0 carries the wave-uniform LDS base; each lane's 16 bytes land at base + 16*lane.
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gptr), "s"(lds_addr) : "memory");
+}
+
+template <int N>
+__device__ __forceinline__ void qr_wait_vmcnt()
+{
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
+// Which activation row block `i` of this thread's B loads refers to, relative to the block's first row.
+template <int NT>
+__device__ __forceinline__ int qr_pipe_b_row(int wave, int i, int col)
+{
+    const int bb = wave * NT + i;
+    return (bb >> 1) * 16 + col;
+}
+
+template <int MT, int NT, int S, int NPH, class PhaseEnd>
+__device__ __forceinline__ void qr_pipe_mma(const QrPhase<NT> (&ph)[NPH], int n_row_tiles, int block_rt0, char *lds,
+                                            v4i (&acc)[MT][NT], PhaseEnd &&on_phase_end)
+{
+    using P = QrPipe<MT, NT, S>;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int grp = lane >> 4;
+    const int wm = wave & 1, wn = wave >> 1;
+    const unsigned lds_base = (unsigned)(size_t)lds;
+    const int nk0 = ph[0].nkc;
+    const int total = nk0 + (NPH == 2 ? ph[NPH - 1].nkc : 0);
+
+    // Issue stream: running source pointers, advanced by one chunk per call and
+    // re-based when the stream crosses from phase 0 to phase 1.
+    const int boff = grp * 16;   // + 64 for odd B blocks
+    const v4i *cur_a[P::A_PER_WAVE];
+    const int8_t *cur_b[P::B_PER_WAVE];
+    int cur_p = 0, cur_kc = 0, cur_nkc = 0, cur_K = 0;
+    auto rebase = [&](int p) {
+        const QrPhase<NT> &ps = ph[p];
+        cur_nkc = ps.nkc;
+        cur_K = ps.K;
+#pragma unroll
+        for (int a = 0; a < P::A_PER_WAVE; ++a) {
+            int rt = block_rt0 + wave * P::A_PER_WAVE + a;
+            rt = rt < n_row_tiles ? rt : n_row_tiles - 1;
+            cur_a[a] = ps.w + (size_t)rt * ps.nkc * 64 + lane;
+        }
+#pragma unroll
+        for (int i = 0; i < P::B_PER_WAVE; ++i) cur_b[i] = ps.row[i] + (((wave * NT + i) & 1) * 64 + boff);
+    };
+    rebase(0);
+    auto issue = [&](int stage) {
+        const unsigned sbase = lds_base + stage * P::STAGE_BYTES;
+        const bool tail = (cur_kc == cur_nkc - 1) && (cur_K & (QRNNT_KCHUNK - 1));   // uniform
+#pragma unroll
+        for (int a = 0; a < P::A_PER_WAVE; ++a) {
+            qr_load_lds16(cur_a[a], sbase + (wave * P::A_PER_WAVE + a) * 1024);
+            cur_a[a] += 64;
+        }
+#pragma unroll
+        for (int i = 0; i < P::B_PER_WAVE; ++i) {
+            const int8_t *src = cur_b[i];
+            if (tail) {
+                const int k = cur_kc * QRNNT_KCHUNK + ((wave * NT + i) & 1) * 64 + boff;
+                if (k >= cur_K) src = cur_b[i] - k;   // row start: any valid bytes do, they meet zero weights
+            }
+            qr_load_lds16(src, sbase + (P::A_BLOCKS + wave * NT + i) * 1024);
+            cur_b[i] += QRNNT_KCHUNK;
+        }
+        if (++cur_kc == cur_nkc && NPH == 2 && cur_p == 0) {
+            cur_p = 1;
+            cur_kc = 0;
+            rebase(1);
+        }
+    };
+
+    // prologue: fill DIST stages
+#pragma unroll
+    for (int v = 0; v < P::DIST; ++v)
+        if (v < total) issue(v);
+
+    int stage = 0, istage = P::DIST % S;
+    for (int c = 0; c < total; ++c) {
+        const int after = total - 1 - c;   // chunks after c; min(DIST-1, after) of them are already in flight
+        static_assert(P::DIST >= 1 && P::DIST <= 3, "ring depth 2..4");
+        if (P::DIST >= 3 && after >= 2) qr_wait_vmcnt<2 * P::LOADS>();
+        else if (P::DIST >= 2 && after >= 1) qr_wait_vmcnt<P::LOADS>();
+        else qr_wait_vmcnt<0>();
+        __builtin_amdgcn_s_barrier();
+        if (c + P::DIST < total) issue(istage);
+        istage = (istage + 1 == S) ? 0 : istage + 1;
+
+        const char *sb = lds + stage * P::STAGE_BYTES + lane * 16;
+        stage = (stage + 1 == S) ? 0 : stage + 1;
+        v4i pa[MT], b0[NT], b1[NT];
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) pa[mt] = *(const v4i *)(sb + (wm * MT + mt) * 1024);
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) {
+            b0[nt] = *(const v4i *)(sb + (P::A_BLOCKS + (wn * NT + nt) * 2) * 1024);
+            b1[nt] = *(const v4i *)(sb + (P::A_BLOCKS + (wn * NT + nt) * 2 + 1) * 1024);
+        }
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+            v4i lo, hi;
+            qr_unpack(pa[mt], lo, hi);
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) {
+                acc[mt][nt] = qr_mfma(lo, b0[nt], acc[mt][nt]);
+                acc[mt][nt] = qr_mfma(hi, b1[nt], acc[mt][nt]);
+            }
+        }
+        if (NPH == 2 && c == nk0 - 1) on_phase_end();
+    }
+}

@@ -58,7 +58,7 @@ class CModel(C.Structure):
 
 EXPORTS = ["qrnnt_status_str", "qrnnt_abi_version", "qrnnt_pack_int4_bytes", "qrnnt_pack_int4", "qrnnt_unpack_int4",
            "qrnnt_quantize_act", "qrnnt_linear", "qrnnt_lstm_step", "qrnnt_lstm_layer_workspace", "qrnnt_lstm_layer",
-           "qrnnt_input_projection",
+           "qrnnt_input_projection", "qrnnt_lstm_step_group",
            "qrnnt_joint_fuse", "qrnnt_beam_step", "qrnnt_decode_workspace", "qrnnt_decode"]
 
 
@@ -208,6 +208,32 @@ def lstm_step_into(L: Lstm, x_codes, h_prev, c_prev, h_next, c_next, N: int, x_r
                                 C.c_int32(N), _ptr(h_next, torch.int8), _ptr(c_next, torch.float32), None, None, None,
                                 _stream())
     _check(st, "qrnnt_lstm_step")
+
+
+class CStepDesc(C.Structure):
+    _fields_ = [("L", C.c_void_p), ("x_codes", C.c_void_p), ("x_row", C.c_void_p), ("n_x_rows", C.c_int32),
+                ("parent", C.c_void_p), ("h_prev", C.c_void_p), ("c_prev", C.c_void_p), ("n_slots", C.c_int32),
+                ("active", C.c_void_p), ("N", C.c_int32), ("h_next", C.c_void_p), ("c_next", C.c_void_p)]
+
+
+class StepGroup:
+    """Prepared argument block for qrnnt_lstm_step_group (built once, launched many times)."""
+
+    def __init__(self, steps):
+        """steps: list of dicts with keys L, x_codes, h_prev, c_prev, h_next, c_next, N and optional x_row, parent, active."""
+        self._keep = []
+        self.n = len(steps)
+        self.arr = (CStepDesc * self.n)()
+        p = lambda t: None if t is None else t.data_ptr()
+        for i, d in enumerate(steps):
+            cl = d["L"].c()
+            self._keep.append((cl, d))
+            self.arr[i] = CStepDesc(C.addressof(cl), p(d["x_codes"]), p(d.get("x_row")), d["x_codes"].shape[0],
+                                    p(d.get("parent")), p(d["h_prev"]), p(d["c_prev"]), d["h_prev"].shape[0],
+                                    p(d.get("active")), d["N"], p(d["h_next"]), p(d["c_next"]))
+
+    def launch(self):
+        _check(load().qrnnt_lstm_step_group(self.arr, C.c_int32(self.n), _stream()), "qrnnt_lstm_step_group")
 
 
 def input_projection(L: Lstm, x_codes: torch.Tensor, gx: Optional[torch.Tensor] = None, debug: bool = False):
