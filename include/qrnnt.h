@@ -161,11 +161,23 @@ size_t qrnnt_lstm_layer_workspace(const qrnnt_lstm *L, int32_t T, int32_t B);
  * use the FIX +-1 grid, Sec. 3.2).  h0/c0 [device] [B,H] or NULL (zero state,
  * as Sec. 3.4 assumes).  h_last/c_last [device] [B,H] or NULL.  Debug
  * [device] or NULL: dbg_accx int32 [T,B,4H] (source row order), dbg_c_all fp32
- * [T,B,H].  All utterances have length T. */
+ * [T,B,H].  All utterances have length T.  For H <= 1024 (multiple of 8) and
+ * B <= 128 the recurrence runs as one persistent kernel whose workgroups exchange
+ * hidden codes through the workspace; its waits are bounded, and if one ever runs
+ * out the int32 at workspace + workspace_bytes_needed - 256 is set to 1 and the
+ * outputs are invalid (it stays 0 otherwise). */
 qrnnt_status qrnnt_lstm_layer(const qrnnt_lstm *L, const int8_t *x_codes, int32_t T, int32_t B, int32_t reverse,
                               const int8_t *h0, const float *c0, int8_t *h_out, int32_t ld_out, int32_t col_off,
                               int8_t *h_last, float *c_last, int32_t *dbg_accx, float *dbg_c_all,
                               void *workspace, size_t workspace_bytes, void *stream);
+
+/* Both directions of a bidirectional layer in one call (zero initial state):
+ * forward codes go to columns [0,H) and backward codes to [H,2H) of h_out [device]
+ * [T,B,2H].  The two recurrences advance concurrently in one launch.  workspace
+ * [device]: qrnnt_bilstm_layer_workspace bytes, 256-byte aligned. */
+size_t qrnnt_bilstm_layer_workspace(const qrnnt_lstm *fwd, const qrnnt_lstm *bwd, int32_t T, int32_t B);
+qrnnt_status qrnnt_bilstm_layer(const qrnnt_lstm *fwd, const qrnnt_lstm *bwd, const int8_t *x_codes, int32_t T,
+                                int32_t B, int8_t *h_out, void *workspace, size_t workspace_bytes, void *stream);
 
 /* The input projection alone (first half of qrnnt_lstm_layer): for M rows of
  * input codes x [device] [M, I], gx[m, 4*j + g] = sum_k w_ih[g*H + j, k] * x[m, k]

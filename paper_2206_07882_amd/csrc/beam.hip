@@ -2,73 +2,44 @@
 // the beam width is the number of hypotheses kept per decoding iteration).
 // Selection runs on the GPU so that the decoding loop never returns to the host.
 #include "kernels.h"
+#include "select.h"
 
 namespace {
 
-// Total order: larger value first, then smaller flat index.
-__device__ __forceinline__ bool better(float v, int c, float bv, int bc) { return v > bv || (v == bv && c < bc); }
-
-constexpr int PER_LANE = 16;   // candidates held in registers per lane: W*V <= 1024 takes the fast path
-
 // One wave per utterance.  The W*V candidate values are formed once (fp32 add) and
-// kept in registers; each of the W rounds is an arg-best over the candidates that
-// come strictly after the previous pick in the total order, so nothing is marked
-// as taken.  After round r lane r holds pick r: (flat index, value), index -1 if
-// the candidates ran out.
+// kept in registers; see qr_select_from_regs in select.h.
+template <int PER>
+__device__ __forceinline__ void select_w_regs(const float *__restrict__ sc, const float *__restrict__ fu, int W, int V,
+                                              int blank, int force_blank, int lane, int &my_c, float &my_v)
+{
+    const int C = W * V;
+    float val[PER];
+    const int c0 = lane * PER;
+    int w = c0 / V, k = c0 - w * V;
+#pragma unroll
+    for (int i = 0; i < PER; ++i) {
+        const int c = c0 + i;
+        float v = -INFINITY;
+        if (c < C && (!force_blank || k == blank)) v = (sc[w] + fu[c]) + 0.0f;   // + 0: -0 becomes +0, one key per value
+        val[i] = v;
+        if (++k == V) { k = 0; ++w; }
+    }
+    qr_select_from_regs<PER>(val, c0, W, lane, my_c, my_v);
+}
+
 __device__ __forceinline__ void select_w(const float *__restrict__ sc, const float *__restrict__ fu, int W, int V,
                                          int blank, int force_blank, int lane, int &my_c, float &my_v)
 {
-    const int C = W * V;
-    float val[PER_LANE];
-    const bool fast = C <= 64 * PER_LANE;
-    if (fast) {
-#pragma unroll
-        for (int i = 0; i < PER_LANE; ++i) {
-            const int c = lane + 64 * i;
-            float v = -INFINITY;
-            if (c < C) {
-                const int w = c / V, k = c - w * V;
-                if (!force_blank || k == blank) v = sc[w] + fu[c];
-            }
-            val[i] = v;
-        }
-    }
-    float last_v = INFINITY;
-    int last_c = -1;
-    bool exhausted = false;
-    my_c = -1;
-    my_v = -INFINITY;
-    for (int r = 0; r < W; ++r) {
-        float bv = -INFINITY;
-        int bc = 0x7fffffff;
-        if (!exhausted) {
-            if (fast) {
-#pragma unroll
-                for (int i = 0; i < PER_LANE; ++i) {
-                    const int c = lane + 64 * i;
-                    const float v = val[i];
-                    const bool ok = v > -INFINITY && (v < last_v || (v == last_v && c > last_c));
-                    if (ok && better(v, c, bv, bc)) { bv = v; bc = c; }
-                }
-            } else {
-                for (int c = lane; c < C; c += 64) {
-                    const int w = c / V, k = c - w * V;
-                    if (force_blank && k != blank) continue;
-                    const float v = sc[w] + fu[c];
-                    const bool ok = v > -INFINITY && (v < last_v || (v == last_v && c > last_c));
-                    if (ok && better(v, c, bv, bc)) { bv = v; bc = c; }
-                }
-            }
-#pragma unroll
-            for (int off = 32; off > 0; off >>= 1) {
-                const float ov = __shfl_xor(bv, off);
-                const int oc = __shfl_xor(bc, off);
-                if (better(ov, oc, bv, bc)) { bv = ov; bc = oc; }
-            }
-        }
-        const bool found = bc != 0x7fffffff;
-        if (lane == r) { my_c = found ? bc : -1; my_v = found ? bv : -INFINITY; }
-        if (found) { last_v = bv; last_c = bc; } else { exhausted = true; }
+    const int C = W * V;   // uniform
+    if (C <= 64 * 4) select_w_regs<4>(sc, fu, W, V, blank, force_blank, lane, my_c, my_v);
+    else if (C <= 64 * 12) select_w_regs<12>(sc, fu, W, V, blank, force_blank, lane, my_c, my_v);
+    else if (C <= 64 * 16) select_w_regs<16>(sc, fu, W, V, blank, force_blank, lane, my_c, my_v);
+    else {
+        auto value = [&](int c) -> float {
+            const int w = c / V, k = c - w * V;
+            return (force_blank && k != blank) ? -INFINITY : (sc[w] + fu[c]) + 0.0f;
+        };
+        qr_select_from_mem(value, C, W, lane, my_c, my_v);
     }
 }
 

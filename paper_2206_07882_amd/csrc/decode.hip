@@ -5,6 +5,7 @@
 // here the selection and the bookkeeping are kernels and the host only enqueues
 // a data-independent launch sequence.
 #include "kernels.h"
+#include "select.h"
 
 namespace {
 
@@ -99,8 +100,6 @@ __global__ void decode_init_kernel(float *score0, int32_t *node0, int32_t *len0,
     active[n] = 1;
 }
 
-__device__ __forceinline__ bool better(float v, int c, float bv, int bc) { return v > bv || (v == bv && c < bc); }
-
 // End of a frame: the new beam is the W best candidates by (score descending,
 // insertion order).  One wave per utterance.
 __global__ __launch_bounds__(64) void frame_end_kernel(const float *__restrict__ nx_score, const int32_t *__restrict__ nx_src,
@@ -113,44 +112,32 @@ __global__ __launch_bounds__(64) void frame_end_kernel(const float *__restrict__
     const int b = blockIdx.x, lane = threadIdx.x;
     const int cnt = nx_count[b];
     const float *sc = nx_score + (size_t)b * R * W;
-    float last_v = INFINITY;
-    int last_c = -1;
-    bool exhausted = false;
-    for (int r = 0; r < W; ++r) {
-        float bv = -INFINITY;
-        int bc = 0x7fffffff;
-        if (!exhausted) {
-            for (int c = lane; c < cnt; c += 64) {
-                const float v = sc[c];
-                const bool after = v < last_v || (v == last_v && c > last_c);
-                if (after && better(v, c, bv, bc)) { bv = v; bc = c; }
-            }
+    int c;
+    float v;
+    if (R * W <= 128) {
+        float val[2];
 #pragma unroll
-            for (int off = 32; off > 0; off >>= 1) {
-                const float ov = __shfl_xor(bv, off);
-                const int oc = __shfl_xor(bc, off);
-                if (better(ov, oc, bv, bc)) { bv = ov; bc = oc; }
-            }
-        }
-        const bool found = bc != 0x7fffffff;
-        if (lane == 0) {
-            const int dst = b * W + r;
-            if (found) {
-                const int src = nx_src[(size_t)b * R * W + bc];
-                score_all[(size_t)dst_buf * N + dst] = bv;
-                node_all_w[(size_t)dst_buf * N + dst] = node_all[src];
-                len_all_w[(size_t)dst_buf * N + dst] = len_all[src];
-                beam_src[dst] = src;
-            } else {
-                score_all[(size_t)dst_buf * N + dst] = -INFINITY;
-                node_all_w[(size_t)dst_buf * N + dst] = 0;
-                len_all_w[(size_t)dst_buf * N + dst] = 0;
-                beam_src[dst] = -1;
-            }
-        }
-        if (found) { last_v = bv; last_c = bc; } else { exhausted = true; }
+        for (int i = 0; i < 2; ++i) val[i] = (lane * 2 + i < cnt) ? sc[lane * 2 + i] + 0.0f : -INFINITY;
+        qr_select_from_regs<2>(val, lane * 2, W, lane, c, v);
+    } else {
+        auto value = [&](int i) -> float { return sc[i] + 0.0f; };
+        qr_select_from_mem(value, cnt, W, lane, c, v);
     }
-    __syncthreads();
+    if (lane < W) {
+        const int dst = b * W + lane;
+        if (c >= 0) {
+            const int src = nx_src[(size_t)b * R * W + c];
+            score_all[(size_t)dst_buf * N + dst] = v;
+            node_all_w[(size_t)dst_buf * N + dst] = node_all[src];
+            len_all_w[(size_t)dst_buf * N + dst] = len_all[src];
+            beam_src[dst] = src;
+        } else {
+            score_all[(size_t)dst_buf * N + dst] = -INFINITY;
+            node_all_w[(size_t)dst_buf * N + dst] = 0;
+            len_all_w[(size_t)dst_buf * N + dst] = 0;
+            beam_src[dst] = -1;
+        }
+    }
     if (lane == 0) nx_count[b] = 0;
 }
 

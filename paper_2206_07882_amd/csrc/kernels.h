@@ -69,6 +69,26 @@ struct QrRouteArgs {
     int32_t *node_tok, *node_prev;                  // label trie
 };
 
+// One direction of the persistent recurrence (see recurrence.hip).
+struct QrRecArgs {
+    const v4i *whh;  const float *s_wih, *s_whh, *bias;
+    const int32_t *gx;                 // [T*B, 4H] gate-interleaved input projection
+    const int8_t *h0;  const float *c0;
+    int8_t *h_out;  int64_t ld_out;  int col_off;
+    int8_t *h_last;  float *c_last;  float *dbg_c_all;
+    unsigned long long *xbuf;          // [2][B][H/4] exchange words, zeroed before the launch
+    int *err;                          // set to 1 when a bounded wait ran out
+    int T, B, H, nkc_h, reverse, spin_limit;
+    float x_scale, h_scale, h_inv;
+};
+struct QrRecGroup {
+    QrRecArgs d[2];
+    int n;
+};
+QR_HIDDEN bool qr_rec_supported(int H, int B);
+QR_HIDDEN size_t qr_rec_xbuf_bytes(int H, int B);
+QR_HIDDEN bool qr_launch_recurrence(const QrRecGroup &g, hipStream_t st);
+
 QR_HIDDEN void qr_launch_beam_route(const QrRouteArgs &a, hipStream_t st);
 QR_HIDDEN void qr_fill_lstm_weights(QrStepArgs &a, const qrnnt_lstm *L);
 QR_HIDDEN qrnnt_status qr_check_lstm(const qrnnt_lstm *L);

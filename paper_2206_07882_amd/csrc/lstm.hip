@@ -543,24 +543,142 @@ extern "C" qrnnt_status qrnnt_input_projection(const qrnnt_lstm *L, const int8_t
     return qr_launch_status();
 }
 
-// Workspace layout of qrnnt_lstm_layer:
-//   [0, gx_bytes)                int32 gx [T*B, 4H]
-//   then h state 2 x [B, H] int8 (rounded up to 256 B), c state 2 x [B, H] fp32.
-static size_t layer_ws_parts(const qrnnt_lstm *L, int T, int B, size_t *gx_b, size_t *h_b, size_t *c_b)
+// Workspace layout of one layer-direction:
+//   int32 gx [T*B, 4H] | h state 2 x [B,H] int8 | c state 2 x [B,H] fp32 |
+//   exchange words of the persistent recurrence | error flag
+struct LayerWs {
+    size_t gx_b, h_b, c_b, x_b, total;
+};
+static LayerWs layer_ws(const qrnnt_lstm *L, int T, int B)
 {
+    LayerWs w;
     const size_t H = (size_t)L->hidden_size;
-    *gx_b = ((size_t)T * B * 4 * H * sizeof(int32_t) + 255) / 256 * 256;
-    *h_b = ((size_t)B * H + 255) / 256 * 256;
-    *c_b = ((size_t)B * H * sizeof(float) + 255) / 256 * 256;
-    return *gx_b + 2 * *h_b + 2 * *c_b;
+    auto up = [](size_t v) { return (v + 255) / 256 * 256; };
+    w.gx_b = up((size_t)T * B * 4 * H * sizeof(int32_t));
+    w.h_b = up((size_t)B * H);
+    w.c_b = up((size_t)B * H * sizeof(float));
+    w.x_b = up(qr_rec_xbuf_bytes((int)H, B));
+    w.total = w.gx_b + 2 * w.h_b + 2 * w.c_b + w.x_b + 256;
+    return w;
 }
 
 extern "C" size_t qrnnt_lstm_layer_workspace(const qrnnt_lstm *L, int32_t T, int32_t B)
 {
     if (L == nullptr || T <= 0 || B <= 0 || L->hidden_size <= 0) return 0;
-    size_t g, h, c;
-    return layer_ws_parts(L, T, B, &g, &h, &c);
+    return layer_ws(L, T, B).total;
 }
+
+namespace {
+
+struct LayerCall {
+    const qrnnt_lstm *L;
+    int reverse;
+    const int8_t *h0;  const float *c0;
+    int col_off;
+    int8_t *h_last;  float *c_last;
+    int32_t *dbg_accx;  float *dbg_c_all;
+    char *ws;
+};
+
+qrnnt_status check_layer_call(const LayerCall &c, const int8_t *x_codes, int T, int B, const int8_t *h_out, int ld_out)
+{
+    qrnnt_status s = qr_check_lstm(c.L);
+    if (s != QRNNT_OK) return s;
+    QR_REQUIRE(x_codes && h_out && c.ws, QRNNT_ERR_NULL);
+    QR_REQUIRE(T > 0 && B > 0, QRNNT_ERR_SHAPE);
+    QR_REQUIRE(c.col_off >= 0 && ld_out >= c.col_off + c.L->hidden_size, QRNNT_ERR_SHAPE);
+    QR_REQUIRE(ld_out % 16 == 0 && c.col_off % 16 == 0, QRNNT_ERR_SHAPE);
+    QR_REQUIRE(qr_aligned(x_codes, 16) && qr_aligned(h_out, 16) && qr_aligned(c.ws, 256), QRNNT_ERR_ALIGN);
+    QR_REQUIRE(c.h0 == nullptr || qr_aligned(c.h0, 16), QRNNT_ERR_ALIGN);
+    return QRNNT_OK;
+}
+
+// 1 or 2 directions over the same input: projections, then either the persistent
+// recurrence (both directions in one launch) or one fused launch per time step.
+qrnnt_status run_layer(const LayerCall *calls, int n, const int8_t *x_codes, int T, int B, int8_t *h_out, int ld_out,
+                       hipStream_t st)
+{
+    const int H = calls[0].L->hidden_size;
+    static const bool no_persist = getenv("QRNNT_STEPWISE_RECURRENCE") != nullptr;
+    bool persist = !no_persist && qr_rec_supported(H, B);
+    for (int d = 1; d < n; ++d) persist = persist && calls[d].L->hidden_size == H;
+    QrRecGroup rg;
+    rg.n = n;
+    for (int d = 0; d < n; ++d) {
+        const LayerCall &c = calls[d];
+        const qrnnt_lstm *L = c.L;
+        const LayerWs w = layer_ws(L, T, B);
+        int32_t *gx = (int32_t *)c.ws;
+        launch_gx_gemm(L, x_codes, T * B, gx, c.dbg_accx, st);
+        if (persist) {
+            char *xb = c.ws + w.gx_b + 2 * w.h_b + 2 * w.c_b;
+            const size_t nw = (w.x_b + 256) / 4;
+            fill_zero_kernel<<<(unsigned)((nw + 255) / 256), 256, 0, st>>>((uint32_t *)xb, nw);
+            QrRecArgs &a = rg.d[d];
+            a = QrRecArgs{};
+            a.whh = (const v4i *)L->w_hh.packed;  a.s_wih = L->w_ih.row_scale;  a.s_whh = L->w_hh.row_scale;
+            a.bias = L->bias;  a.gx = gx;  a.h0 = c.h0;  a.c0 = c.c0;
+            a.h_out = h_out;  a.ld_out = ld_out;  a.col_off = c.col_off;
+            a.h_last = c.h_last;  a.c_last = c.c_last;  a.dbg_c_all = c.dbg_c_all;
+            a.xbuf = (unsigned long long *)xb;  a.err = (int *)(xb + w.x_b);
+            a.T = T;  a.B = B;  a.H = H;  a.nkc_h = qr_round_up(H, QRNNT_KCHUNK) / QRNNT_KCHUNK;
+            a.reverse = c.reverse;  a.spin_limit = 1 << 18;
+            a.x_scale = L->x_scale;  a.h_scale = L->h_scale;  a.h_inv = L->h_inv_scale;
+        }
+    }
+    if (persist) {
+        if (!qr_launch_recurrence(rg, st)) return QRNNT_ERR_HIP;
+        return qr_launch_status();
+    }
+    for (int d = 0; d < n; ++d) {
+        const LayerCall &c = calls[d];
+        const qrnnt_lstm *L = c.L;
+        const LayerWs w = layer_ws(L, T, B);
+        int32_t *gx = (int32_t *)c.ws;
+        int8_t *hbuf = (int8_t *)(c.ws + w.gx_b);
+        float *cbuf[2] = {(float *)(c.ws + w.gx_b + 2 * w.h_b), (float *)(c.ws + w.gx_b + 2 * w.h_b + w.c_b)};
+        if (c.h0 == nullptr) {
+            const size_t nw = w.h_b / 4;
+            fill_zero_kernel<<<(unsigned)((nw + 255) / 256), 256, 0, st>>>((uint32_t *)hbuf, nw);
+        }
+        if (c.c0 == nullptr) {
+            const size_t nw = w.c_b / 4;
+            fill_zero_kernel<<<(unsigned)((nw + 255) / 256), 256, 0, st>>>((uint32_t *)cbuf[0], nw);
+        }
+        QrStepArgs a = {};
+        qr_fill_lstm_weights(a, L);
+        a.ld_gx = 4 * (int64_t)H;
+        a.n_slots = B;
+        a.N = B;
+        a.ld_hn = ld_out;
+        const float *c_prev = c.c0 ? c.c0 : cbuf[0];
+        int cur = c.c0 ? 0 : 1;   // next c buffer to write
+        for (int step = 0; step < T; ++step) {
+            const int t = c.reverse ? T - 1 - step : step;
+            a.gx = gx + (int64_t)t * B * 4 * H;
+            if (step == 0) {
+                a.h_prev = c.h0 ? c.h0 : hbuf;
+                a.ld_hp = H;
+            } else {
+                const int tp = c.reverse ? t + 1 : t - 1;
+                a.h_prev = h_out + (int64_t)tp * B * ld_out + c.col_off;
+                a.ld_hp = ld_out;
+            }
+            a.c_prev = c_prev;
+            a.c_next = c.dbg_c_all ? c.dbg_c_all + (int64_t)t * B * H : cbuf[cur];
+            a.h_next = h_out + (int64_t)t * B * ld_out + c.col_off;
+            a.h_copy = (step == T - 1) ? c.h_last : nullptr;
+            qr_launch_lstm_step(a, true, st);
+            c_prev = a.c_next;
+            cur ^= 1;
+        }
+        if (c.c_last)
+            (void)hipMemcpyAsync(c.c_last, c_prev, (size_t)B * H * sizeof(float), hipMemcpyDeviceToDevice, st);
+    }
+    return qr_launch_status();
+}
+
+}  // namespace
 
 extern "C" qrnnt_status qrnnt_lstm_layer(const qrnnt_lstm *L, const int8_t *x_codes, int32_t T, int32_t B,
                                          int32_t reverse, const int8_t *h0, const float *c0, int8_t *h_out,
@@ -568,65 +686,33 @@ extern "C" qrnnt_status qrnnt_lstm_layer(const qrnnt_lstm *L, const int8_t *x_co
                                          int32_t *dbg_accx, float *dbg_c_all, void *workspace, size_t workspace_bytes,
                                          void *stream)
 {
-    qrnnt_status s = qr_check_lstm(L);
+    LayerCall c = {L, reverse, h0, c0, col_off, h_last, c_last, dbg_accx, dbg_c_all, (char *)workspace};
+    qrnnt_status s = check_layer_call(c, x_codes, T, B, h_out, ld_out);
     if (s != QRNNT_OK) return s;
-    QR_REQUIRE(x_codes && h_out && workspace, QRNNT_ERR_NULL);
-    QR_REQUIRE(T > 0 && B > 0, QRNNT_ERR_SHAPE);
-    const int H = L->hidden_size, I = L->input_size;
-    QR_REQUIRE(col_off >= 0 && ld_out >= col_off + H, QRNNT_ERR_SHAPE);
-    QR_REQUIRE(ld_out % 16 == 0 && col_off % 16 == 0, QRNNT_ERR_SHAPE);
-    QR_REQUIRE(qr_aligned(x_codes, 16) && qr_aligned(h_out, 16) && qr_aligned(workspace, 256), QRNNT_ERR_ALIGN);
-    QR_REQUIRE(h0 == nullptr || qr_aligned(h0, 16), QRNNT_ERR_ALIGN);
-    size_t gx_b, h_b, c_b;
-    const size_t need = layer_ws_parts(L, T, B, &gx_b, &h_b, &c_b);
-    QR_REQUIRE(workspace_bytes >= need, QRNNT_ERR_WORKSPACE);
-    hipStream_t st = (hipStream_t)stream;
+    QR_REQUIRE(workspace_bytes >= layer_ws(L, T, B).total, QRNNT_ERR_WORKSPACE);
+    return run_layer(&c, 1, x_codes, T, B, h_out, ld_out, (hipStream_t)stream);
+}
 
-    char *ws = (char *)workspace;
-    int32_t *gx = (int32_t *)ws;
-    int8_t *hbuf = (int8_t *)(ws + gx_b);           // [0]: zero / h0 staging is not needed: h0 is read in place
-    float *cbuf[2] = {(float *)(ws + gx_b + 2 * h_b), (float *)(ws + gx_b + 2 * h_b + c_b)};
+extern "C" size_t qrnnt_bilstm_layer_workspace(const qrnnt_lstm *fwd, const qrnnt_lstm *bwd, int32_t T, int32_t B)
+{
+    const size_t a = qrnnt_lstm_layer_workspace(fwd, T, B), b = qrnnt_lstm_layer_workspace(bwd, T, B);
+    return (a == 0 || b == 0) ? 0 : a + b;
+}
 
-    // 1) input projection for all T*B frames
-    launch_gx_gemm(L, x_codes, T * B, gx, dbg_accx, st);
-    // 2) zero initial state where none is given
-    if (h0 == nullptr) {
-        const size_t nw = h_b / 4;
-        fill_zero_kernel<<<(unsigned)((nw + 255) / 256), 256, 0, st>>>((uint32_t *)hbuf, nw);
+extern "C" qrnnt_status qrnnt_bilstm_layer(const qrnnt_lstm *fwd, const qrnnt_lstm *bwd, const int8_t *x_codes, int32_t T,
+                                           int32_t B, int8_t *h_out, void *workspace, size_t workspace_bytes, void *stream)
+{
+    QR_REQUIRE(fwd && bwd, QRNNT_ERR_NULL);
+    QR_REQUIRE(fwd->hidden_size > 0 && fwd->hidden_size == bwd->hidden_size && fwd->input_size == bwd->input_size,
+               QRNNT_ERR_SHAPE);
+    const int H = fwd->hidden_size;
+    LayerCall c[2] = {{fwd, 0, nullptr, nullptr, 0, nullptr, nullptr, nullptr, nullptr, (char *)workspace},
+                      {bwd, 1, nullptr, nullptr, H, nullptr, nullptr, nullptr, nullptr, nullptr}};
+    if (T > 0 && B > 0 && workspace) c[1].ws = (char *)workspace + layer_ws(fwd, T, B).total;
+    for (int d = 0; d < 2; ++d) {
+        qrnnt_status s = check_layer_call(c[d], x_codes, T, B, h_out, 2 * H);
+        if (s != QRNNT_OK) return s;
     }
-    if (c0 == nullptr) {
-        const size_t nw = c_b / 4;
-        fill_zero_kernel<<<(unsigned)((nw + 255) / 256), 256, 0, st>>>((uint32_t *)cbuf[0], nw);
-    }
-    // 3) the recurrence, one fused launch per time step
-    QrStepArgs a = {};
-    qr_fill_lstm_weights(a, L);
-    a.ld_gx = 4 * (int64_t)H;
-    a.n_slots = B;
-    a.N = B;
-    a.ld_hn = ld_out;
-    const float *c_prev = c0 ? c0 : cbuf[0];
-    int cur = c0 ? 0 : 1;   // next c buffer to write
-    for (int step = 0; step < T; ++step) {
-        const int t = reverse ? T - 1 - step : step;
-        a.gx = gx + (int64_t)t * B * 4 * H;
-        if (step == 0) {
-            a.h_prev = h0 ? h0 : hbuf;
-            a.ld_hp = H;
-        } else {
-            const int tp = reverse ? t + 1 : t - 1;
-            a.h_prev = h_out + (int64_t)tp * B * ld_out + col_off;
-            a.ld_hp = ld_out;
-        }
-        a.c_prev = c_prev;
-        a.c_next = dbg_c_all ? dbg_c_all + (int64_t)t * B * H : cbuf[cur];
-        a.h_next = h_out + (int64_t)t * B * ld_out + col_off;
-        a.h_copy = (step == T - 1) ? h_last : nullptr;
-        qr_launch_lstm_step(a, true, st);
-        c_prev = a.c_next;
-        cur ^= 1;
-    }
-    if (c_last)
-        (void)hipMemcpyAsync(c_last, c_prev, (size_t)B * H * sizeof(float), hipMemcpyDeviceToDevice, st);
-    return qr_launch_status();
+    QR_REQUIRE(workspace_bytes >= layer_ws(fwd, T, B).total + layer_ws(bwd, T, B).total, QRNNT_ERR_WORKSPACE);
+    return run_layer(c, 2, x_codes, T, B, h_out, 2 * H, (hipStream_t)stream);
 }

@@ -72,4 +72,36 @@ __device__ __forceinline__ int qr_quant4(float x, float inv_step)
     return (int)r;
 }
 
+// Wave-wide max / min of a 32-bit unsigned value on the DPP path (row scans, then
+// the two cross-row broadcasts of gfx9), result broadcast through lane 63.
+template <bool IS_MAX>
+__device__ __forceinline__ unsigned qr_wave_reduce_u32(unsigned v)
+{
+    const unsigned id = IS_MAX ? 0u : 0xFFFFFFFFu;
+#define QR_DPP_STEP(ctrl, rmask)                                                                       \
+    {                                                                                                  \
+        const unsigned o = (unsigned)__builtin_amdgcn_update_dpp((int)id, (int)v, ctrl, rmask, 0xf, false); \
+        v = IS_MAX ? (v > o ? v : o) : (v < o ? v : o);                                                \
+    }
+    QR_DPP_STEP(0x111, 0xf)   // row_shr:1
+    QR_DPP_STEP(0x112, 0xf)   // row_shr:2
+    QR_DPP_STEP(0x114, 0xf)   // row_shr:4
+    QR_DPP_STEP(0x118, 0xf)   // row_shr:8
+    QR_DPP_STEP(0x142, 0xa)   // row_bcast:15 into rows 1 and 3
+    QR_DPP_STEP(0x143, 0xc)   // row_bcast:31 into rows 2 and 3
+#undef QR_DPP_STEP
+    return (unsigned)__builtin_amdgcn_readlane((int)v, 63);
+}
+
+// Monotone map fp32 -> uint32 (larger float <=> larger unsigned); never returns 0 for a non-NaN input.
+__device__ __forceinline__ unsigned qr_float_key(float f)
+{
+    const unsigned u = __float_as_uint(f);
+    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+__device__ __forceinline__ float qr_key_float(unsigned k)
+{
+    return __uint_as_float((k & 0x80000000u) ? (k & 0x7FFFFFFFu) : ~k);
+}
+
 #endif  // __HIPCC__

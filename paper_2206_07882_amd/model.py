@@ -60,7 +60,7 @@ class Encoder:
         self._ws: Optional[torch.Tensor] = None
 
     def workspace(self, T: int, B: int, device) -> torch.Tensor:
-        need = max(q.lstm_layer_workspace(L, T, B) for dirs in self.layers for L in dirs)
+        need = max(sum(q.lstm_layer_workspace(L, T, B) for L in dirs) for dirs in self.layers)
         if self._ws is None or self._ws.numel() < need:
             self._ws = torch.empty(need, dtype=torch.uint8, device=device)
         return self._ws
@@ -73,8 +73,10 @@ class Encoder:
         for dirs in self.layers:
             H = dirs[0].H
             out = torch.empty((T, B, H * len(dirs)), dtype=torch.int8, device=feats.device)
-            for d, L in enumerate(dirs):
-                q.lstm_layer(L, x, reverse=(d == 1), h_out=out, col_off=d * H, workspace=ws)
+            if len(dirs) == 2:
+                q.bilstm_layer(dirs[0], dirs[1], x, h_out=out, workspace=ws)
+            else:
+                q.lstm_layer(dirs[0], x, h_out=out, col_off=0, workspace=ws)
             x = out
         e = q.linear(self.proj, self.proj_bias, S_H, x.reshape(T * B, -1)).reshape(T, B, -1)
         return x, e

@@ -59,6 +59,7 @@ class CModel(C.Structure):
 EXPORTS = ["qrnnt_status_str", "qrnnt_abi_version", "qrnnt_pack_int4_bytes", "qrnnt_pack_int4", "qrnnt_unpack_int4",
            "qrnnt_quantize_act", "qrnnt_linear", "qrnnt_lstm_step", "qrnnt_lstm_layer_workspace", "qrnnt_lstm_layer",
            "qrnnt_input_projection", "qrnnt_lstm_step_group",
+           "qrnnt_bilstm_layer_workspace", "qrnnt_bilstm_layer",
            "qrnnt_joint_fuse", "qrnnt_beam_step", "qrnnt_decode_workspace", "qrnnt_decode"]
 
 
@@ -76,6 +77,8 @@ def load():
         lib.qrnnt_pack_int4_bytes.argtypes = [C.c_int32, C.c_int32, C.c_int32]
         lib.qrnnt_lstm_layer_workspace.restype = C.c_size_t
         lib.qrnnt_lstm_layer_workspace.argtypes = [C.c_void_p, C.c_int32, C.c_int32]
+        lib.qrnnt_bilstm_layer_workspace.restype = C.c_size_t
+        lib.qrnnt_bilstm_layer_workspace.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32]
         lib.qrnnt_decode_workspace.restype = C.c_size_t
         lib.qrnnt_decode_workspace.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32]
         _lib = lib
@@ -276,6 +279,31 @@ def lstm_layer(L: Lstm, x_codes: torch.Tensor, reverse: bool = False, h0=None, c
                                  _ptr(accx), _ptr(c_all), _ptr(workspace), C.c_size_t(workspace.numel()), _stream())
     _check(st, "qrnnt_lstm_layer")
     return dict(h_out=h_out, h_last=h_last, c_last=c_last, accx=accx, c_all=c_all)
+
+
+def bilstm_layer_workspace(fwd: Lstm, bwd: Lstm, T: int, B: int) -> int:
+    cf, cb = fwd.c(), bwd.c()
+    return int(load().qrnnt_bilstm_layer_workspace(C.byref(cf), C.byref(cb), T, B))
+
+
+def bilstm_layer(fwd: Lstm, bwd: Lstm, x_codes: torch.Tensor, h_out: Optional[torch.Tensor] = None,
+                 workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+    T, B, _ = x_codes.shape
+    dev = x_codes.device
+    if h_out is None:
+        h_out = torch.empty((T, B, 2 * fwd.H), dtype=torch.int8, device=dev)
+    if workspace is None:
+        workspace = torch.empty(bilstm_layer_workspace(fwd, bwd, T, B), dtype=torch.uint8, device=dev)
+    cf, cb = fwd.c(), bwd.c()
+    st = load().qrnnt_bilstm_layer(C.byref(cf), C.byref(cb), _ptr(x_codes, torch.int8), C.c_int32(T), C.c_int32(B),
+                                   _ptr(h_out, torch.int8), _ptr(workspace), C.c_size_t(workspace.numel()), _stream())
+    _check(st, "qrnnt_bilstm_layer")
+    return h_out
+
+
+def layer_error_flag(workspace: torch.Tensor, need: int) -> int:
+    """The bounded-wait flag of the persistent recurrence (0 = all waits ended normally)."""
+    return int(workspace[need - 256:need - 252].view(torch.int32).item())
 
 
 def joint_fuse(enc_proj, frame_row, pred_proj, w_out: QMat, b_out, lp_src, lp_ext, lambda_src: float,
