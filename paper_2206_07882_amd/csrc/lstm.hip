@@ -626,10 +626,7 @@ qrnnt_status run_layer(const LayerCall *calls, int n, const int8_t *x_codes, int
             a.x_scale = L->x_scale;  a.h_scale = L->h_scale;  a.h_inv = L->h_inv_scale;
         }
     }
-    if (persist) {
-        if (!qr_launch_recurrence(rg, st)) return QRNNT_ERR_HIP;
-        return qr_launch_status();
-    }
+    if (persist && qr_launch_recurrence(rg, st)) return qr_launch_status();
     for (int d = 0; d < n; ++d) {
         const LayerCall &c = calls[d];
         const qrnnt_lstm *L = c.L;
