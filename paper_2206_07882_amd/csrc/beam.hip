@@ -6,15 +6,15 @@
 
 namespace {
 
-// One wave per utterance.  The W*V candidate values are formed once (fp32 add) and
-// kept in registers; see qr_select_from_regs in select.h.
+// One workgroup (4 waves) per utterance.  The W*V candidate values are formed once
+// (fp32 add) and kept in registers; see select.h.
 template <int PER>
 __device__ __forceinline__ void select_w_regs(const float *__restrict__ sc, const float *__restrict__ fu, int W, int V,
-                                              int blank, int force_blank, int lane, int &my_c, float &my_v)
+                                              int blank, int force_blank, int tid, unsigned *slots, int &my_c, float &my_v)
 {
     const int C = W * V;
     float val[PER];
-    const int c0 = lane * PER;
+    const int c0 = tid * PER;
     int w = c0 / V, k = c0 - w * V;
 #pragma unroll
     for (int i = 0; i < PER; ++i) {
@@ -24,51 +24,59 @@ __device__ __forceinline__ void select_w_regs(const float *__restrict__ sc, cons
         val[i] = v;
         if (++k == V) { k = 0; ++w; }
     }
-    qr_select_from_regs<PER>(val, c0, W, lane, my_c, my_v);
+    qr_block_select_from_regs<PER>(val, c0, W, tid, slots, my_c, my_v);
 }
 
+// Thread r < W ends up with pick r.  Uniform control flow across the workgroup.
 __device__ __forceinline__ void select_w(const float *__restrict__ sc, const float *__restrict__ fu, int W, int V,
-                                         int blank, int force_blank, int lane, int &my_c, float &my_v)
+                                         int blank, int force_blank, int tid, unsigned *slots, int &my_c, float &my_v)
 {
     const int C = W * V;   // uniform
-    if (C <= 64 * 4) select_w_regs<4>(sc, fu, W, V, blank, force_blank, lane, my_c, my_v);
-    else if (C <= 64 * 12) select_w_regs<12>(sc, fu, W, V, blank, force_blank, lane, my_c, my_v);
-    else if (C <= 64 * 16) select_w_regs<16>(sc, fu, W, V, blank, force_blank, lane, my_c, my_v);
+    if (C <= 256) select_w_regs<1>(sc, fu, W, V, blank, force_blank, tid, slots, my_c, my_v);
+    else if (C <= 256 * 3) select_w_regs<3>(sc, fu, W, V, blank, force_blank, tid, slots, my_c, my_v);
+    else if (C <= 256 * 6) select_w_regs<6>(sc, fu, W, V, blank, force_blank, tid, slots, my_c, my_v);
     else {
-        auto value = [&](int c) -> float {
-            const int w = c / V, k = c - w * V;
-            return (force_blank && k != blank) ? -INFINITY : (sc[w] + fu[c]) + 0.0f;
-        };
-        qr_select_from_mem(value, C, W, lane, my_c, my_v);
+        my_c = -1;
+        my_v = -INFINITY;
+        if (tid < 64) {   // any size: wave 0 re-forms the candidates from memory in every round
+            auto value = [&](int c) -> float {
+                const int w = c / V, k = c - w * V;
+                return (force_blank && k != blank) ? -INFINITY : (sc[w] + fu[c]) + 0.0f;
+            };
+            qr_select_from_mem(value, C, W, tid, my_c, my_v);
+        }
     }
 }
 
-__global__ __launch_bounds__(64) void beam_step_kernel(const float *__restrict__ score, const float *__restrict__ fused,
-                                                        int W, int V, int blank, int force_blank,
-                                                        int32_t *__restrict__ parent_out, int32_t *__restrict__ token_out,
-                                                        float *__restrict__ score_out)
+__global__ __launch_bounds__(256) void beam_step_kernel(const float *__restrict__ score, const float *__restrict__ fused,
+                                                         int W, int V, int blank, int force_blank,
+                                                         int32_t *__restrict__ parent_out, int32_t *__restrict__ token_out,
+                                                         float *__restrict__ score_out)
 {
-    const int b = blockIdx.x, lane = threadIdx.x;
+    __shared__ unsigned slots[16];
+    const int b = blockIdx.x, tid = threadIdx.x;
     int c;
     float v;
-    select_w(score + (int64_t)b * W, fused + (int64_t)b * W * V, W, V, blank, force_blank, lane, c, v);
-    if (lane < W) {
-        parent_out[(int64_t)b * W + lane] = c >= 0 ? c / V : -1;
-        token_out[(int64_t)b * W + lane] = c >= 0 ? c % V : -1;
-        score_out[(int64_t)b * W + lane] = v;
+    select_w(score + (int64_t)b * W, fused + (int64_t)b * W * V, W, V, blank, force_blank, tid, slots, c, v);
+    if (tid < W) {
+        parent_out[(int64_t)b * W + tid] = c >= 0 ? c / V : -1;
+        token_out[(int64_t)b * W + tid] = c >= 0 ? c % V : -1;
+        score_out[(int64_t)b * W + tid] = v;
     }
 }
 
 // Selection fused with the routing of the picks inside the decoding loop: blank
 // picks join the frame's candidate list, label picks become the slots of the next
 // round in selection order (prefix counts by ballot), the remaining slots die.
-__global__ __launch_bounds__(64) void beam_route_kernel(const QrRouteArgs a)
+__global__ __launch_bounds__(256) void beam_route_kernel(const QrRouteArgs a)
 {
+    __shared__ unsigned slots[16];
     const int b = blockIdx.x, lane = threadIdx.x;
     const int W = a.W, V = a.V, N = a.B * a.W;
     int c;
     float v;
-    select_w(a.score_src + (int64_t)b * W, a.fused + (int64_t)b * W * V, W, V, a.blank, a.last_round, lane, c, v);
+    select_w(a.score_src + (int64_t)b * W, a.fused + (int64_t)b * W * V, W, V, a.blank, a.last_round, lane, slots, c, v);
+    if (lane >= 64) return;   // the picks live in threads 0 .. W-1 <= 63: wave 0 routes them
     const bool in = lane < W;
     const bool found = in && c >= 0;
     const int par = found ? c / V : 0, tok = found ? c - (c / V) * V : 0;
@@ -114,10 +122,10 @@ __global__ __launch_bounds__(64) void beam_route_kernel(const QrRouteArgs a)
 void qr_launch_beam(const float *score, const float *fused, int B, int W, int V, int blank, int force_blank,
                     int32_t *parent_out, int32_t *token_out, float *score_out, hipStream_t st)
 {
-    beam_step_kernel<<<B, 64, 0, st>>>(score, fused, W, V, blank, force_blank, parent_out, token_out, score_out);
+    beam_step_kernel<<<B, 256, 0, st>>>(score, fused, W, V, blank, force_blank, parent_out, token_out, score_out);
 }
 
-void qr_launch_beam_route(const QrRouteArgs &a, hipStream_t st) { beam_route_kernel<<<a.B, 64, 0, st>>>(a); }
+void qr_launch_beam_route(const QrRouteArgs &a, hipStream_t st) { beam_route_kernel<<<a.B, 256, 0, st>>>(a); }
 
 extern "C" qrnnt_status qrnnt_beam_step(const float *score, const float *fused, int32_t B, int32_t W, int32_t V,
                                         int32_t blank, int32_t force_blank, int32_t *parent_out, int32_t *token_out,

@@ -13,7 +13,8 @@ template <class BFrag>
 __device__ __forceinline__ void qr_head_mma(const v4i *__restrict__ w, int nkc, int n_row_tiles, int rt0, int K,
                                             BFrag &&bfrag, v4i (&acc)[4], v4i *lds /* [4][4][64] */)
 {
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // scalar: MFMAs below sit under wave-uniform branches
     const int nkb = (K + 63) >> 6;
     const v4i zero = {0, 0, 0, 0};
     const int m = (int)0xF0F0F0F0u;

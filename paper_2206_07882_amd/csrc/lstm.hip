@@ -9,121 +9,198 @@
 
 namespace {
 
-// Grid: x = groups of 4*MT row tiles (a wave owns MT tiles = 4*MT cells),
-//       y = groups of NT*16 hypotheses.  No LDS, no barriers.
-template <int MT, int NT, bool USE_GX>
-__global__ __launch_bounds__(256) void lstm_step_kernel(const QrStepArgs a)
-{
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int col = lane & 15, grp = lane >> 4;
-    const int n_row_tiles = a.H >> 2;   // 4H / 16
-    const int rt0 = (blockIdx.x * 4 + wave) * MT;
-    if (rt0 >= n_row_tiles) return;
+// Bandwidth-bound variant (at most 16*NT hypotheses, e.g. one utterance at beam 16).
+// The packed weights are streamed exactly once: a workgroup owns one row tile
+// (4 cells); its 128-column chunks of W_ih and W_hh are dealt round-robin to the 4
+// waves, every wave issues all of its loads before its first MFMA (what keeps the
+// whole matrix in flight across the chip), and the partial sums meet in LDS.  Wave 0
+// then finishes the 4 cells, one (cell, hypothesis) per lane and column tile.
+// N = 16 is exactly one 16-column MFMA tile, so the matrix cores serve this regime
+// too: the kernel is bound by the weight stream, not by arithmetic.
+// Grid: x = row tiles, z = problem of a group.
+constexpr int SMALL_BATCH = 4;   // chunks per wave per batch (K <= 2048 in one batch)
 
-    int n_of[NT], src_of[NT];
-    const int8_t *xptr[NT], *hptr[NT];
+template <int NT, bool USE_GX>
+__global__ __launch_bounds__(256) void lstm_step_small_kernel(const QrStepGroup g)
+{
+    __shared__ v4i part[3][2][NT][64];   // waves 1..3: [x|h][column tile][lane]
+    const QrStepArgs &a = g.p[blockIdx.z];
+    const int H = a.H, N = a.N;
+    const int rt = blockIdx.x;
+    if (rt >= (H >> 2)) return;   // uniform
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // scalar: MFMAs below sit under wave-uniform branches
+    const int col = lane & 15, grp = lane >> 4;
+    const v4i zero = {0, 0, 0, 0};
+    const int m = (int)0xF0F0F0F0u;
+
+    int src_of[NT];
+    const int8_t *xrow[NT], *hrow[NT];
+    int nn[NT];
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) {
-        int n = (blockIdx.y * NT + nt) * 16 + col;
-        n_of[nt] = n;
-        int nn = n < a.N ? n : a.N - 1;
-        int s = a.parent ? a.parent[nn] : nn;
+        const int n = nt * 16 + col;
+        nn[nt] = n < N ? n : N - 1;
+    }
+    if (a.parent) {
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) src_of[nt] = a.parent[nn[nt]];
+    } else {
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) src_of[nt] = nn[nt];
+    }
+    int xr[NT];
+    if (!USE_GX && a.x_row) {
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) xr[nt] = a.x_row[nn[nt]];
+    } else {
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) xr[nt] = nn[nt];
+    }
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+        int s = src_of[nt];
         s = s < 0 ? 0 : (s >= a.n_slots ? a.n_slots - 1 : s);
         src_of[nt] = s;
-        hptr[nt] = a.h_prev + (int64_t)s * a.ld_hp + grp * 16;
-        if (!USE_GX) {
-            int xr = a.x_row ? a.x_row[nn] : nn;
-            xr = xr < 0 ? 0 : (xr >= a.n_x_rows ? a.n_x_rows - 1 : xr);
-            xptr[nt] = a.x + (int64_t)xr * a.ld_x + grp * 16;
-        } else {
-            xptr[nt] = nullptr;
-        }
+        hrow[nt] = a.h_prev + (int64_t)s * a.ld_hp + grp * 16;
+        int r = xr[nt];
+        r = r < 0 ? 0 : (r >= a.n_x_rows ? a.n_x_rows - 1 : r);
+        xrow[nt] = USE_GX ? nullptr : a.x + (int64_t)r * a.ld_x + grp * 16;
     }
 
-    v4i acc[MT][NT];
-    float pre[MT][NT][4];
-    const v4i zero = {0, 0, 0, 0};
+    const int nkx = USE_GX ? 0 : a.nkc_x;
+    const int total = nkx + a.nkc_h;
+    v4i accx[NT], acch[NT];
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-        for (int nt = 0; nt < NT; ++nt) acc[mt][nt] = zero;
+    for (int nt = 0; nt < NT; ++nt) { accx[nt] = zero; acch[nt] = zero; }
 
-    // ---- input part: s_x * s_wih[r] * accx
-    if (!USE_GX) qr_mma_range<MT, NT>(a.wih, a.nkc_x, n_row_tiles, rt0, lane, xptr, a.I, acc);
+    for (int v0 = wave; v0 < total; v0 += 4 * SMALL_BATCH) {
+        v4i pa[SMALL_BATCH], b0[SMALL_BATCH][NT], b1[SMALL_BATCH][NT];
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt) {
-        const int j = (rt0 + mt) * 4 + grp;     // cell index; the lane's 4 accumulators are its gates i,f,g,o
-        const bool jv = j < a.H;
-        float sx[4];
+        for (int it = 0; it < SMALL_BATCH; ++it) {
+            const int v = v0 + 4 * it;
+            const bool ok = v < total;
+            const bool isx = ok && v < nkx;
+            const int kc = ok ? (isx ? v : v - nkx) : 0;
+            const v4i *w = isx ? a.wih : a.whh;
+            const int nkc = isx ? a.nkc_x : a.nkc_h;
+            const int K = isx ? a.I : H;
+            pa[it] = ok ? w[((size_t)rt * nkc + kc) * 64 + lane] : zero;
+            const int k0 = kc * QRNNT_KCHUNK + grp * 16;
 #pragma unroll
-        for (int g = 0; g < 4; ++g) sx[g] = jv ? a.x_scale * a.s_wih[g * a.H + j] : 0.0f;
-#pragma unroll
-        for (int nt = 0; nt < NT; ++nt) {
-            v4i ax;
-            if (USE_GX) {
-                const int n = n_of[nt] < a.N ? n_of[nt] : a.N - 1;
-                ax = jv ? *(const v4i *)(a.gx + (int64_t)n * a.ld_gx + 4 * j) : zero;
-            } else {
-                ax = acc[mt][nt] >> 4;
+            for (int nt = 0; nt < NT; ++nt) {
+                const int8_t *row = isx ? xrow[nt] : hrow[nt];
+                b0[it][nt] = (ok && k0 < K) ? *(const v4i *)(row + kc * QRNNT_KCHUNK) : zero;
+                b1[it][nt] = (ok && k0 + 64 < K) ? *(const v4i *)(row + kc * QRNNT_KCHUNK + 64) : zero;
             }
-            if (a.dbg_accx && jv && n_of[nt] < a.N)
-#pragma unroll
-                for (int g = 0; g < 4; ++g) a.dbg_accx[(int64_t)n_of[nt] * 4 * a.H + g * a.H + j] = ax[g];
-#pragma unroll
-            for (int g = 0; g < 4; ++g) pre[mt][nt][g] = sx[g] * (float)ax[g];
-            acc[mt][nt] = zero;
-        }
-    }
-
-    // ---- recurrent part: s_h * s_whh[r] * acch
-    qr_mma_range<MT, NT>(a.whh, a.nkc_h, n_row_tiles, rt0, lane, hptr, a.H, acc);
-
-    // ---- fused cell
-#pragma unroll
-    for (int mt = 0; mt < MT; ++mt) {
-        const int j = (rt0 + mt) * 4 + grp;
-        if (j >= a.H) continue;
-        float sh[4], bb[4];
-#pragma unroll
-        for (int g = 0; g < 4; ++g) {
-            sh[g] = a.h_scale * a.s_whh[g * a.H + j];
-            bb[g] = a.bias[g * a.H + j];
         }
 #pragma unroll
-        for (int nt = 0; nt < NT; ++nt) {
-            const int n = n_of[nt];
-            if (n >= a.N) continue;
-            const v4i ah = acc[mt][nt] >> 4;
-            const int s = src_of[nt];
-            const float cp = a.c_prev[(int64_t)s * a.H + j];
-            if (a.dbg_acch)
+        for (int it = 0; it < SMALL_BATCH; ++it) {
+            const int v = v0 + 4 * it;
+            if (v < total) {   // uniform per wave
+                const v4i lo = (pa[it] << 4) & m, hi = pa[it] & m;
+                if (v < nkx) {
 #pragma unroll
-                for (int g = 0; g < 4; ++g) a.dbg_acch[(int64_t)n * 4 * a.H + g * a.H + j] = ah[g];
-            int8_t code;
-            float cn;
-            if (a.active && !a.active[n]) {
-                code = a.h_prev[(int64_t)s * a.ld_hp + j];
-                cn = cp;
-            } else {
-                float p[4];
+                    for (int nt = 0; nt < NT; ++nt) {
+                        accx[nt] = qr_mfma(lo, b0[it][nt], accx[nt]);
+                        accx[nt] = qr_mfma(hi, b1[it][nt], accx[nt]);
+                    }
+                } else {
 #pragma unroll
-                for (int g = 0; g < 4; ++g) p[g] = pre[mt][nt][g] + (sh[g] * (float)ah[g] + bb[g]);
-                const float gi = qr_sigmoid(p[0]), gf = qr_sigmoid(p[1]), gg = qr_tanh(p[2]), go = qr_sigmoid(p[3]);
-                cn = gf * cp + gi * gg;
-                const float h = go * qr_tanh(cn);
-                code = (int8_t)qr_quant4(h, a.h_inv);
-                if (a.dbg_gates) {
-                    float *dg = a.dbg_gates + (int64_t)n * 4 * a.H + j;
-                    dg[0] = gi; dg[a.H] = gf; dg[2 * a.H] = gg; dg[3 * a.H] = go;
+                    for (int nt = 0; nt < NT; ++nt) {
+                        acch[nt] = qr_mfma(lo, b0[it][nt], acch[nt]);
+                        acch[nt] = qr_mfma(hi, b1[it][nt], acch[nt]);
+                    }
                 }
             }
-            a.c_next[(int64_t)n * a.H + j] = cn;
-            a.h_next[(int64_t)n * a.ld_hn + j] = code;
-            if (a.h_copy) a.h_copy[(int64_t)n * a.H + j] = code;
+        }
+    }
+    if (wave != 0) {
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) {
+            part[wave - 1][0][nt][lane] = accx[nt];
+            part[wave - 1][1][nt][lane] = acch[nt];
+        }
+    }
+    __syncthreads();
+    if (wave != 0) return;
+
+    // ---- wave 0: cell j = 4*rt + grp for hypotheses col (+16 per column tile)
+    const int j = rt * 4 + grp;
+    float sx[4], sh[4], bb[4];
+#pragma unroll
+    for (int gt = 0; gt < 4; ++gt) {
+        sx[gt] = a.x_scale * a.s_wih[gt * H + j];
+        sh[gt] = a.h_scale * a.s_whh[gt * H + j];
+        bb[gt] = a.bias[gt * H + j];
+    }
+    float cp[NT];
+    int act[NT], hp_code[NT];
+    v4i gxv[NT];
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+        cp[nt] = a.c_prev[(int64_t)src_of[nt] * H + j];
+        if (USE_GX) gxv[nt] = *(const v4i *)(a.gx + (int64_t)nn[nt] * a.ld_gx + 4 * j);
+    }
+    if (a.active) {
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) {
+            act[nt] = a.active[nn[nt]];
+            hp_code[nt] = a.h_prev[(int64_t)src_of[nt] * a.ld_hp + j];
+        }
+    } else {
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) { act[nt] = 1; hp_code[nt] = 0; }
+    }
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+        const int n = nt * 16 + col;
+        v4i ax = accx[nt], ah = acch[nt];
+#pragma unroll
+        for (int wv = 0; wv < 3; ++wv) { ax += part[wv][0][nt][lane]; ah += part[wv][1][nt][lane]; }
+        ax = USE_GX ? gxv[nt] : (ax >> 4);
+        ah = ah >> 4;
+        float p[4];
+#pragma unroll
+        for (int gt = 0; gt < 4; ++gt) p[gt] = sx[gt] * (float)ax[gt] + (sh[gt] * (float)ah[gt] + bb[gt]);
+        const float gi = qr_sigmoid(p[0]), gf = qr_sigmoid(p[1]), gg = qr_tanh(p[2]), go = qr_sigmoid(p[3]);
+        float cn = gf * cp[nt] + gi * gg;
+        const float h = go * qr_tanh(cn);
+        int code = qr_quant4(h, a.h_inv);
+        const bool on = act[nt] != 0;
+        cn = on ? cn : cp[nt];
+        code = on ? code : hp_code[nt];
+        if (n < N) {
+            a.c_next[(int64_t)n * H + j] = cn;
+            a.h_next[(int64_t)n * a.ld_hn + j] = (int8_t)code;
+            if (a.h_copy) a.h_copy[(int64_t)n * H + j] = (int8_t)code;
+            if (a.dbg_accx)
+#pragma unroll
+                for (int gt = 0; gt < 4; ++gt) a.dbg_accx[(int64_t)n * 4 * H + gt * H + j] = ax[gt];
+            if (a.dbg_acch)
+#pragma unroll
+                for (int gt = 0; gt < 4; ++gt) a.dbg_acch[(int64_t)n * 4 * H + gt * H + j] = ah[gt];
+            if (a.dbg_gates && on) {
+                float *dg = a.dbg_gates + (int64_t)n * 4 * H + j;
+                dg[0] = gi; dg[H] = gf; dg[2 * H] = gg; dg[3 * H] = go;
+            }
         }
     }
 }
 
+template <bool USE_GX>
+void launch_small(const QrStepGroup &g, hipStream_t st)
+{
+    int max_n = 0, max_rt = 0;
+    for (int i = 0; i < g.n; ++i) {
+        max_n = g.p[i].N > max_n ? g.p[i].N : max_n;
+        max_rt = (g.p[i].H >> 2) > max_rt ? (g.p[i].H >> 2) : max_rt;
+    }
+    dim3 grid(max_rt, 1, g.n);
+    if (max_n <= 16) lstm_step_small_kernel<1, USE_GX><<<grid, 256, 0, st>>>(g);
+    else if (max_n <= 32) lstm_step_small_kernel<2, USE_GX><<<grid, 256, 0, st>>>(g);
+    else lstm_step_small_kernel<4, USE_GX><<<grid, 256, 0, st>>>(g);
+}
 
 // Compute-bound variant (many hypotheses): multi-stage LDS ring, see mma_pipe.h.
 // Grid: x = blocks of 32*MT gate rows (8*MT cells), y = blocks of 32*NT hypotheses,
@@ -131,7 +208,8 @@ __global__ __launch_bounds__(256) void lstm_step_kernel(const QrStepArgs a)
 // Every global load outside the ring is issued in a batch ahead of its first use
 // and the cell update is branch-free, so a block exposes one memory latency per
 // batch instead of one per element.  DBG adds the int32 / gate outputs.
-template <int MT, int NT, int S, bool USE_GX, bool DBG>
+// FAST: every K is a multiple of 128, every tile is full (no bounds checks needed).
+template <int MT, int NT, int S, bool USE_GX, bool DBG, bool FAST>
 __global__ __launch_bounds__(256, 2) void lstm_step_pipe_kernel(const QrStepGroup g)
 {
     using P = QrPipe<MT, NT, S>;
@@ -251,7 +329,7 @@ __global__ __launch_bounds__(256, 2) void lstm_step_pipe_kernel(const QrStepGrou
             }
     }
 
-    qr_pipe_mma<MT, NT, S, NPH>(ph, n_row_tiles, block_rt0, lds, acc, x_done);
+    qr_pipe_mma<MT, NT, S, NPH, !FAST>(ph, n_row_tiles, block_rt0, lds, acc, x_done);
 
     // ---- fused cell: batched loads, then branch-free arithmetic, then stores
     float cp[MT][NT], sh[MT][4], bb[MT][4];
@@ -283,7 +361,7 @@ __global__ __launch_bounds__(256, 2) void lstm_step_pipe_kernel(const QrStepGrou
     }
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
-        const bool jv = (rt0 + mt) * 4 + grp < H;
+        const bool jv = FAST || (rt0 + mt) * 4 + grp < H;
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) {
             const int n = n_of[nt];
@@ -298,7 +376,7 @@ __global__ __launch_bounds__(256, 2) void lstm_step_pipe_kernel(const QrStepGrou
             const bool on = act[nt] != 0;
             cn = on ? cn : cp[mt][nt];
             code = on ? code : hp_code[mt][nt];
-            if (jv && n < N) {
+            if (FAST || (jv && n < N)) {
                 a.c_next[(int64_t)n * H + jc[mt]] = cn;
                 a.h_next[(int64_t)n * a.ld_hn + jc[mt]] = (int8_t)code;
                 if (a.h_copy) a.h_copy[(int64_t)n * H + jc[mt]] = (int8_t)code;
@@ -316,12 +394,12 @@ __global__ __launch_bounds__(256, 2) void lstm_step_pipe_kernel(const QrStepGrou
     }
 }
 
-template <int MT, int NT, int S, bool USE_GX, bool DBG>
-void launch_pipe_d(const QrStepGroup &g, hipStream_t st)
+template <int MT, int NT, int S, bool USE_GX, bool DBG, bool FAST>
+void launch_pipe_f(const QrStepGroup &g, hipStream_t st)
 {
     using P = QrPipe<MT, NT, S>;
     static bool configured = false;
-    auto kern = lstm_step_pipe_kernel<MT, NT, S, USE_GX, DBG>;
+    auto kern = lstm_step_pipe_kernel<MT, NT, S, USE_GX, DBG, FAST>;
     if (!configured) {
         (void)hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, P::LDS_BYTES);
         configured = true;
@@ -338,32 +416,27 @@ void launch_pipe_d(const QrStepGroup &g, hipStream_t st)
 template <int MT, int NT, int S, bool USE_GX>
 void launch_pipe(const QrStepGroup &g, hipStream_t st)
 {
-    bool dbg = false;
-    for (int i = 0; i < g.n; ++i) dbg = dbg || g.p[i].dbg_accx || g.p[i].dbg_acch || g.p[i].dbg_gates;
-    if (dbg) launch_pipe_d<MT, NT, S, USE_GX, true>(g, st);
-    else launch_pipe_d<MT, NT, S, USE_GX, false>(g, st);
+    using P = QrPipe<MT, NT, S>;
+    bool dbg = false, fast = true;
+    for (int i = 0; i < g.n; ++i) {
+        const QrStepArgs &a = g.p[i];
+        dbg = dbg || a.dbg_accx || a.dbg_acch || a.dbg_gates;
+        fast = fast && a.H % (8 * MT) == 0 && a.N % P::BN == 0 && a.H % QRNNT_KCHUNK == 0 &&
+               (USE_GX || a.I % QRNNT_KCHUNK == 0);
+    }
+    if (dbg) launch_pipe_f<MT, NT, S, USE_GX, true, false>(g, st);
+    else if (fast) launch_pipe_f<MT, NT, S, USE_GX, false, true>(g, st);
+    else launch_pipe_f<MT, NT, S, USE_GX, false, false>(g, st);
 }
 
 template <bool USE_GX>
 void launch_step_t(const QrStepArgs &a, hipStream_t st)
 {
-    const int n_row_tiles = a.H >> 2;
-    if (a.N <= 16) {
-        dim3 grid((n_row_tiles + 3) / 4, 1);
-        lstm_step_kernel<1, 1, USE_GX><<<grid, 256, 0, st>>>(a);
-    } else if (a.N <= 32) {
-        dim3 grid((n_row_tiles + 3) / 4, 1);
-        lstm_step_kernel<1, 2, USE_GX><<<grid, 256, 0, st>>>(a);
-    } else {
-        QrStepGroup g;
-        g.p[0] = a;
-        g.n = 1;
-        static int exp_s = getenv("QRNNT_S") ? atoi(getenv("QRNNT_S")) : 3;
-        if (a.N <= 64) launch_pipe<4, 2, 3, USE_GX>(g, st);
-        else if (exp_s == 4) launch_pipe<4, 4, 4, USE_GX>(g, st);
-        else if (exp_s == 2) launch_pipe<4, 4, 2, USE_GX>(g, st);
-        else launch_pipe<4, 4, 3, USE_GX>(g, st);
-    }
+    QrStepGroup g;
+    g.p[0] = a;
+    g.n = 1;
+    if (a.N <= 64) launch_small<USE_GX>(g, st);
+    else launch_pipe<4, 4, 3, USE_GX>(g, st);
 }
 
 // Input projection of all frames: gx[m, 4j+g] = sum_k Wih[g*H+j, k] * x[m, k].
@@ -459,9 +532,13 @@ void qr_launch_lstm_step(const QrStepArgs &a, bool use_gx, hipStream_t st)
 void qr_launch_lstm_step_group(const QrStepGroup &g, hipStream_t st)
 {
     // one launch when every member is in the compute-bound regime, else member by member
-    bool all_big = true;
-    for (int i = 0; i < g.n; ++i) all_big = all_big && g.p[i].N > 64;
-    if (all_big && g.n > 1) launch_pipe<4, 4, 3, false>(g, st);
+    bool all_big = true, all_small = true;
+    for (int i = 0; i < g.n; ++i) {
+        all_big = all_big && g.p[i].N > 64;
+        all_small = all_small && g.p[i].N <= 64;
+    }
+    if (all_big) launch_pipe<4, 4, 3, false>(g, st);
+    else if (all_small) launch_small<false>(g, st);
     else
         for (int i = 0; i < g.n; ++i) launch_step_t<false>(g.p[i], st);
 }

@@ -63,7 +63,7 @@ __device__ __forceinline__ int qr_pipe_b_row(int wave, int i, int col)
     return (bb >> 1) * 16 + col;
 }
 
-template <int MT, int NT, int S, int NPH, class PhaseEnd>
+template <int MT, int NT, int S, int NPH, bool TAIL, class PhaseEnd>
 __device__ __forceinline__ void qr_pipe_mma(const QrPhase<NT> (&ph)[NPH], int n_row_tiles, int block_rt0, char *lds,
                                             v4i (&acc)[MT][NT], PhaseEnd &&on_phase_end)
 {
@@ -98,7 +98,7 @@ __device__ __forceinline__ void qr_pipe_mma(const QrPhase<NT> (&ph)[NPH], int n_
     rebase(0);
     auto issue = [&](int stage) {
         const unsigned sbase = lds_base + stage * P::STAGE_BYTES;
-        const bool tail = (cur_kc == cur_nkc - 1) && (cur_K & (QRNNT_KCHUNK - 1));   // uniform
+        const bool tail = TAIL && (cur_kc == cur_nkc - 1) && (cur_K & (QRNNT_KCHUNK - 1));   // uniform
 #pragma unroll
         for (int a = 0; a < P::A_PER_WAVE; ++a) {
             qr_load_lds16(cur_a[a], sbase + (wave * P::A_PER_WAVE + a) * 1024);
@@ -107,7 +107,7 @@ __device__ __forceinline__ void qr_pipe_mma(const QrPhase<NT> (&ph)[NPH], int n_
 #pragma unroll
         for (int i = 0; i < P::B_PER_WAVE; ++i) {
             const int8_t *src = cur_b[i];
-            if (tail) {
+            if (TAIL && tail) {
                 const int k = cur_kc * QRNNT_KCHUNK + ((wave * NT + i) & 1) * 64 + boff;
                 if (k >= cur_K) src = cur_b[i] - k;   // row start: any valid bytes do, they meet zero weights
             }
