@@ -15,6 +15,7 @@ struct NetBuf {
     int8_t *h[QRNNT_MAX_LAYERS];   // [NB][N][H]
     float *c[QRNNT_MAX_LAYERS];    // [NB][N][H]
     float *y;                      // [NB][N][out_rows]
+    int32_t *gx0;                  // [V][4*H0]: input projection of layer 0 for every token
 };
 
 struct Plan {
@@ -58,6 +59,7 @@ void make_plan(const qrnnt_model *m, int T, int B, int W, int max_sym, void *ws,
             p.net[k].c[l] = cv.take<float>(NB * N * net->layer[l].hidden_size);
         }
         p.net[k].y = cv.take<float>(NB * N * net->out.rows);
+        p.net[k].gx0 = cv.take<int32_t>((size_t)m->V * 4 * net->layer[0].hidden_size);
     }
     p.score = cv.take<float>(NB * N);
     p.node = cv.take<int32_t>(NB * N);
@@ -240,7 +242,10 @@ void advance_nets(const qrnnt_model *m, const Plan &p, int src, int dst, int n_e
             a = QrStepArgs{};
             qr_fill_lstm_weights(a, L);
             if (l == 0) {
+                // The input of layer 0 is one of V embedding rows, so its integer input
+                // projection is a table lookup (exactly the sums the contraction would give).
                 a.x = net->embed_codes;  a.ld_x = L->input_size;  a.x_row = p.token;  a.n_x_rows = n_embed_rows;
+                a.gx = p.net[k].gx0;  a.ld_gx = 4 * (int64_t)H;
             } else {
                 a.x = p.net[k].h[l - 1] + (size_t)dst * N * L->input_size;  a.ld_x = L->input_size;
                 a.x_row = nullptr;  a.n_x_rows = p.N;
@@ -253,7 +258,7 @@ void advance_nets(const qrnnt_model *m, const Plan &p, int src, int dst, int n_e
             a.c_next = p.net[k].c[l] + (size_t)dst * N * H;
             a.N = p.N;
         }
-        qr_launch_lstm_step_group(g, st);
+        qr_launch_lstm_step_group(g, l == 0, st);
     }
     QrLinearGroup lg;
     lg.n = 0;
@@ -315,6 +320,9 @@ extern "C" qrnnt_status qrnnt_decode(const qrnnt_model *m, const float *enc_proj
             fill_words_kernel<<<(unsigned)((nw + 255) / 256), 256, 0, st>>>((uint32_t *)(p.net[k].c[l] + (size_t)ZB * Ns * H), nw, 0u);
         }
     }
+    for (int k = 0; k < 3; ++k)
+        if (net_used(m, k))
+            qr_launch_input_projection(&net_of(m, k)->layer[0], net_of(m, k)->embed_codes, V, p.net[k].gx0, nullptr, st);
     decode_init_kernel<<<(N + 255) / 256 + 1, 256, 0, st>>>(p.score, p.node, p.len, p.parent_idx, p.token, p.active,
                                                             p.nx_count, p.node_tok, p.node_prev, N, W, B, m->blank);
     advance_nets(m, p, ZB, 0, n_embed_rows, st);

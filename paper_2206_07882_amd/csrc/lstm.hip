@@ -5,7 +5,6 @@
 #include <cstdlib>
 #include "kernels.h"
 #include "mma_pipe.h"
-#include "mma_core.h"
 
 namespace {
 
@@ -49,8 +48,8 @@ __global__ __launch_bounds__(256) void lstm_step_small_kernel(const QrStepGroup 
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) src_of[nt] = nn[nt];
     }
-    int xr[NT];
-    if (!USE_GX && a.x_row) {
+    int xr[NT];   // row of the input codes, or of the precomputed input projection
+    if (a.x_row) {
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) xr[nt] = a.x_row[nn[nt]];
     } else {
@@ -65,6 +64,7 @@ __global__ __launch_bounds__(256) void lstm_step_small_kernel(const QrStepGroup 
         hrow[nt] = a.h_prev + (int64_t)s * a.ld_hp + grp * 16;
         int r = xr[nt];
         r = r < 0 ? 0 : (r >= a.n_x_rows ? a.n_x_rows - 1 : r);
+        xr[nt] = r;
         xrow[nt] = USE_GX ? nullptr : a.x + (int64_t)r * a.ld_x + grp * 16;
     }
 
@@ -140,7 +140,7 @@ __global__ __launch_bounds__(256) void lstm_step_small_kernel(const QrStepGroup 
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) {
         cp[nt] = a.c_prev[(int64_t)src_of[nt] * H + j];
-        if (USE_GX) gxv[nt] = *(const v4i *)(a.gx + (int64_t)nn[nt] * a.ld_gx + 4 * j);
+        if (USE_GX) gxv[nt] = *(const v4i *)(a.gx + (int64_t)xr[nt] * a.ld_gx + 4 * j);
     }
     if (a.active) {
 #pragma unroll
@@ -227,10 +227,10 @@ __global__ __launch_bounds__(256, 2) void lstm_step_pipe_kernel(const QrStepGrou
     const int rt0 = block_rt0 + wm * MT;
 
     // ---- indices: rows this thread stages (ld_*) and hypotheses this lane finishes (n_of)
-    int ld_n[NT], ld_s[NT], ld_x[NT], n_of[NT], src_of[NT];
+    int ld_n[NT], ld_s[NT], ld_x[NT], n_of[NT], src_of[NT], gx_of[NT];
 #pragma unroll
     for (int i = 0; i < NT; ++i) {
-        const int n = n0 + qr_pipe_b_row<NT>(wave, i, col);
+        const int n = n0 + qr_pipe_b_row<NT>(wave, i, lane);
         ld_n[i] = n < N ? n : N - 1;
         const int m = n0 + (wn * NT + i) * 16 + col;
         n_of[i] = m;
@@ -249,6 +249,14 @@ __global__ __launch_bounds__(256, 2) void lstm_step_pipe_kernel(const QrStepGrou
     } else {
 #pragma unroll
         for (int i = 0; i < NT; ++i) ld_x[i] = ld_n[i];
+    }
+    if (USE_GX) {   // row of the precomputed input projection for the hypotheses this lane finishes
+#pragma unroll
+        for (int i = 0; i < NT; ++i) {
+            const int n = n_of[i] < N ? n_of[i] : N - 1;
+            int r = a.x_row ? a.x_row[n] : n;
+            gx_of[i] = r < 0 ? 0 : (r >= a.n_x_rows ? a.n_x_rows - 1 : r);
+        }
     }
     constexpr int NPH = USE_GX ? 1 : 2;
     QrPhase<NT> ph[NPH];
@@ -313,8 +321,7 @@ __global__ __launch_bounds__(256, 2) void lstm_step_pipe_kernel(const QrStepGrou
             for (int gt = 0; gt < 4; ++gt) sx[mt][gt] = a.x_scale * a.s_wih[gt * H + jc[mt]];
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt) {
-                const int n = n_of[nt] < N ? n_of[nt] : N - 1;
-                ax[mt][nt] = *(const v4i *)(a.gx + (int64_t)n * a.ld_gx + 4 * jc[mt]);
+                ax[mt][nt] = *(const v4i *)(a.gx + (int64_t)gx_of[nt] * a.ld_gx + 4 * jc[mt]);
             }
         }
 #pragma unroll
@@ -440,25 +447,32 @@ void launch_step_t(const QrStepArgs &a, hipStream_t st)
 }
 
 // Input projection of all frames: gx[m, 4j+g] = sum_k Wih[g*H+j, k] * x[m, k].
-// Output columns stay in tiled-row (gate-interleaved) order so that the step
-// kernel fetches a cell's four gate sums with one 128-bit load.
-template <int MT, int NT>
-__global__ __launch_bounds__(256) void gx_gemm_kernel(const v4i *__restrict__ wih, int nkc, int n_row_tiles,
-                                                       const int8_t *__restrict__ x, int64_t ld_x, int M, int K,
-                                                       int32_t *__restrict__ gx, int H, int32_t *__restrict__ dbg_accx)
+// Output columns stay in tiled-row (gate-interleaved) order so that the recurrence
+// fetches a cell's four gate sums with one 128-bit load.  A true dense contraction:
+// the LDS ring of mma_pipe.h with a 32*MT x 32*NT block tile; no second phase, so the
+// registers that the step kernel spends on the input part go into a taller tile.
+// Grid: x = blocks of 32*MT gate rows, y = blocks of 32*NT frames.
+template <int MT, int NT, int S, bool TAIL>
+__global__ __launch_bounds__(256, 1) void gx_gemm_pipe_kernel(const v4i *__restrict__ wih, int nkc, int n_row_tiles,
+                                                              const int8_t *__restrict__ x, int64_t ld_x, int M, int K,
+                                                              int32_t *__restrict__ gx, int H,
+                                                              int32_t *__restrict__ dbg_accx)
 {
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    using P = QrPipe<MT, NT, S>;
+    extern __shared__ __attribute__((aligned(1024))) char lds[];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int col = lane & 15, grp = lane >> 4;
-    // 2 x 2 waves: wave&1 along weight rows, wave>>1 along frames
-    const int rt0 = (blockIdx.x * 2 + (wave & 1)) * MT;
-    const int m0 = (blockIdx.y * 2 + (wave >> 1)) * NT * 16;
-    if (rt0 >= n_row_tiles || m0 >= M) return;
-    const int8_t *xptr[NT];
+    const int wm = wave & 1, wn = wave >> 1;
+    const int block_rt0 = blockIdx.x * 2 * MT;
+    const int m0 = blockIdx.y * P::BN;
+    const int rt0 = block_rt0 + wm * MT;
+    QrPhase<NT> ph[1];
+    ph[0].w = wih;  ph[0].nkc = nkc;  ph[0].K = K;
 #pragma unroll
-    for (int nt = 0; nt < NT; ++nt) {
-        int m = m0 + nt * 16 + col;
+    for (int i = 0; i < NT; ++i) {
+        int m = m0 + qr_pipe_b_row<NT>(wave, i, lane);
         m = m < M ? m : M - 1;
-        xptr[nt] = x + (int64_t)m * ld_x + grp * 16;
+        ph[0].row[i] = x + (int64_t)m * ld_x;
     }
     v4i acc[MT][NT];
     const v4i zero = {0, 0, 0, 0};
@@ -466,22 +480,46 @@ __global__ __launch_bounds__(256) void gx_gemm_kernel(const v4i *__restrict__ wi
     for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) acc[mt][nt] = zero;
-    qr_mma_range<MT, NT>(wih, nkc, n_row_tiles, rt0, lane, xptr, K, acc);
+    qr_pipe_mma<MT, NT, S, 1, TAIL>(ph, n_row_tiles, block_rt0, lds, acc, [] {});
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
         const int j = (rt0 + mt) * 4 + grp;
         if (j >= H) continue;
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) {
-            const int m = m0 + nt * 16 + col;
+            const int m = m0 + (wn * NT + nt) * 16 + col;
             if (m >= M) continue;
             const v4i v = acc[mt][nt] >> 4;
             *(v4i *)(gx + (int64_t)m * 4 * H + 4 * j) = v;
             if (dbg_accx)
 #pragma unroll
-                for (int g = 0; g < 4; ++g) dbg_accx[(int64_t)m * 4 * H + g * H + j] = v[g];
+                for (int gt = 0; gt < 4; ++gt) dbg_accx[(int64_t)m * 4 * H + gt * H + j] = v[gt];
         }
     }
+}
+
+template <int MT, int NT, int S>
+void launch_gx_pipe(const qrnnt_lstm *L, const int8_t *x_codes, int M, int32_t *gx, int32_t *dbg_accx, hipStream_t st)
+{
+    using P = QrPipe<MT, NT, S>;
+    const int H = L->hidden_size, I = L->input_size;
+    const int n_row_tiles = H >> 2;
+    const int nkc = qr_round_up(I, QRNNT_KCHUNK) / QRNNT_KCHUNK;
+    dim3 grid((n_row_tiles + 2 * MT - 1) / (2 * MT), (M + P::BN - 1) / P::BN);
+    static bool configured = false;
+    if (!configured) {
+        (void)hipFuncSetAttribute((const void *)gx_gemm_pipe_kernel<MT, NT, S, true>,
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, P::LDS_BYTES);
+        (void)hipFuncSetAttribute((const void *)gx_gemm_pipe_kernel<MT, NT, S, false>,
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, P::LDS_BYTES);
+        configured = true;
+    }
+    if (I % QRNNT_KCHUNK)
+        gx_gemm_pipe_kernel<MT, NT, S, true><<<grid, 256, P::LDS_BYTES, st>>>((const v4i *)L->w_ih.packed, nkc, n_row_tiles,
+                                                                             x_codes, I, M, I, gx, H, dbg_accx);
+    else
+        gx_gemm_pipe_kernel<MT, NT, S, false><<<grid, 256, P::LDS_BYTES, st>>>((const v4i *)L->w_ih.packed, nkc, n_row_tiles,
+                                                                              x_codes, I, M, I, gx, H, dbg_accx);
 }
 
 __global__ void fill_zero_kernel(uint32_t *p, size_t n_words)
@@ -529,7 +567,8 @@ void qr_launch_lstm_step(const QrStepArgs &a, bool use_gx, hipStream_t st)
     if (use_gx) launch_step_t<true>(a, st); else launch_step_t<false>(a, st);
 }
 
-void qr_launch_lstm_step_group(const QrStepGroup &g, hipStream_t st)
+template <bool USE_GX>
+static void launch_group_t(const QrStepGroup &g, hipStream_t st)
 {
     // one launch when every member is in the compute-bound regime, else member by member
     bool all_big = true, all_small = true;
@@ -537,10 +576,15 @@ void qr_launch_lstm_step_group(const QrStepGroup &g, hipStream_t st)
         all_big = all_big && g.p[i].N > 64;
         all_small = all_small && g.p[i].N <= 64;
     }
-    if (all_big) launch_pipe<4, 4, 3, false>(g, st);
-    else if (all_small) launch_small<false>(g, st);
+    if (all_big) launch_pipe<4, 4, 3, USE_GX>(g, st);
+    else if (all_small) launch_small<USE_GX>(g, st);
     else
-        for (int i = 0; i < g.n; ++i) launch_step_t<false>(g.p[i], st);
+        for (int i = 0; i < g.n; ++i) launch_step_t<USE_GX>(g.p[i], st);
+}
+
+void qr_launch_lstm_step_group(const QrStepGroup &g, bool use_gx, hipStream_t st)
+{
+    if (use_gx) launch_group_t<true>(g, st); else launch_group_t<false>(g, st);
 }
 
 static qrnnt_status make_step_args(QrStepArgs &a, const qrnnt_lstm *L, const int8_t *x_codes, const int32_t *x_row,
@@ -593,19 +637,17 @@ extern "C" qrnnt_status qrnnt_lstm_step_group(const qrnnt_step_desc *steps, int3
                                         d.n_slots, d.active, d.N, d.h_next, d.c_next);
         if (s != QRNNT_OK) return s;
     }
-    qr_launch_lstm_step_group(g, (hipStream_t)stream);
+    qr_launch_lstm_step_group(g, false, (hipStream_t)stream);
     return qr_launch_status();
 }
 
-static void launch_gx_gemm(const qrnnt_lstm *L, const int8_t *x_codes, int M, int32_t *gx, int32_t *dbg_accx,
-                           hipStream_t st)
+void qr_launch_input_projection(const qrnnt_lstm *L, const int8_t *x_codes, int M, int32_t *gx, int32_t *dbg_accx,
+                                hipStream_t st)
 {
-    const int H = L->hidden_size, I = L->input_size;
-    const int n_row_tiles = H >> 2;
-    const int nkc = qr_round_up(I, QRNNT_KCHUNK) / QRNNT_KCHUNK;
-    dim3 grid((n_row_tiles + 7) / 8, (M + 127) / 128);
-    gx_gemm_kernel<4, 4><<<grid, 256, 0, st>>>((const v4i *)L->w_ih.packed, nkc, n_row_tiles, x_codes, I, M, I, gx, H,
-                                               dbg_accx);
+    static const int cfg = getenv("QRNNT_GEMM_TILE") ? atoi(getenv("QRNNT_GEMM_TILE")) : 44;
+    if (M <= 256 || cfg == 44) launch_gx_pipe<4, 4, 3>(L, x_codes, M, gx, dbg_accx, st);
+    else if (cfg == 48) launch_gx_pipe<4, 8, 3>(L, x_codes, M, gx, dbg_accx, st);
+    else launch_gx_pipe<8, 4, 3>(L, x_codes, M, gx, dbg_accx, st);
 }
 
 extern "C" qrnnt_status qrnnt_input_projection(const qrnnt_lstm *L, const int8_t *x_codes, int32_t M, int32_t *gx,
@@ -616,7 +658,7 @@ extern "C" qrnnt_status qrnnt_input_projection(const qrnnt_lstm *L, const int8_t
     QR_REQUIRE(x_codes && gx, QRNNT_ERR_NULL);
     QR_REQUIRE(M > 0, QRNNT_ERR_SHAPE);
     QR_REQUIRE(qr_aligned(x_codes, 16) && qr_aligned(gx, 16), QRNNT_ERR_ALIGN);
-    launch_gx_gemm(L, x_codes, M, gx, dbg_accx, (hipStream_t)stream);
+    qr_launch_input_projection(L, x_codes, M, gx, dbg_accx, (hipStream_t)stream);
     return qr_launch_status();
 }
 
@@ -686,7 +728,7 @@ qrnnt_status run_layer(const LayerCall *calls, int n, const int8_t *x_codes, int
         const qrnnt_lstm *L = c.L;
         const LayerWs w = layer_ws(L, T, B);
         int32_t *gx = (int32_t *)c.ws;
-        launch_gx_gemm(L, x_codes, T * B, gx, c.dbg_accx, st);
+        qr_launch_input_projection(L, x_codes, T * B, gx, c.dbg_accx, st);
         if (persist) {
             char *xb = c.ws + w.gx_b + 2 * w.h_b + 2 * w.c_b;
             const size_t nw = (w.x_b + 256) / 4;

@@ -6,12 +6,15 @@
 // stage of the ring holds
 //   A: 2*MT weight blocks of 1 KiB, copied verbatim from the TILED blob (the blob
 //      is already in operand order, so lane l later reads bytes [16l, 16l+16));
-//   B: 4*NT activation blocks of 1 KiB, one per (column tile, 64-column half),
-//      gathered so that lane l = 16*grp + col of a block holds row (tile*16+col),
-//      bytes half*64 + grp*16 .. +16: again exactly the lane's MFMA operand.
-// Every LDS read is therefore a linear, conflict-free 128-bit read, and the data
-// never passes through registers on its way in, so S-1 chunks can be in flight
-// per block (what hides the ~1 us L2/HBM latency at this consumption rate).
+//   B: 4*NT activation blocks of 1 KiB, each 8 activation rows x the chunk's 128
+//      bytes.  Lane l of the loading wave fetches row l/8, 16-byte piece
+//      (l%8) ^ (l/8): every load instruction covers 8 whole 128-byte lines (half
+//      lines cost the vector-memory path as much as whole ones, measured: twice
+//      the time per byte), and the XOR spreads the 8 rows that the lanes of one
+//      MFMA operand read at the same piece index over all LDS banks.
+// Every LDS read is a conflict-free 128-bit read, and the data never passes
+// through registers on its way in, so S-1 chunks can be in flight per block
+// (what hides the ~1 us L2/HBM latency at this consumption rate).
 //
 // The direct loads are issued from inline asm (the compiler would otherwise wait
 // for all of them before any LDS read); their completion is tracked by hand with
@@ -55,12 +58,11 @@ __device__ __forceinline__ void qr_wait_vmcnt()
     asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 }
 
-// Which activation row block `i` of this thread's B loads refers to, relative to the block's first row.
+// Which activation row load `i` of this thread's B loads fetches, relative to the block's first row.
 template <int NT>
-__device__ __forceinline__ int qr_pipe_b_row(int wave, int i, int col)
+__device__ __forceinline__ int qr_pipe_b_row(int wave, int i, int lane)
 {
-    const int bb = wave * NT + i;
-    return (bb >> 1) * 16 + col;
+    return (wave * NT + i) * 8 + (lane >> 3);
 }
 
 template <int MT, int NT, int S, int NPH, bool TAIL, class PhaseEnd>
@@ -70,15 +72,16 @@ __device__ __forceinline__ void qr_pipe_mma(const QrPhase<NT> (&ph)[NPH], int n_
     using P = QrPipe<MT, NT, S>;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int grp = lane >> 4;
+    const int grp = lane >> 4, col = lane & 15;
     const int wm = wave & 1, wn = wave >> 1;
+    const int p0 = (grp ^ (col & 7)) * 16, p1 = ((4 + grp) ^ (col & 7)) * 16;   // swizzled pieces of the two K halves
     const unsigned lds_base = (unsigned)(size_t)lds;
     const int nk0 = ph[0].nkc;
     const int total = nk0 + (NPH == 2 ? ph[NPH - 1].nkc : 0);
 
     // Issue stream: running source pointers, advanced by one chunk per call and
     // re-based when the stream crosses from phase 0 to phase 1.
-    const int boff = grp * 16;   // + 64 for odd B blocks
+    const int boff = ((lane & 7) ^ (lane >> 3)) * 16;   // this lane's 16-byte piece of a chunk row
     const v4i *cur_a[P::A_PER_WAVE];
     const int8_t *cur_b[P::B_PER_WAVE];
     int cur_p = 0, cur_kc = 0, cur_nkc = 0, cur_K = 0;
@@ -93,7 +96,7 @@ __device__ __forceinline__ void qr_pipe_mma(const QrPhase<NT> (&ph)[NPH], int n_
             cur_a[a] = ps.w + (size_t)rt * ps.nkc * 64 + lane;
         }
 #pragma unroll
-        for (int i = 0; i < P::B_PER_WAVE; ++i) cur_b[i] = ps.row[i] + (((wave * NT + i) & 1) * 64 + boff);
+        for (int i = 0; i < P::B_PER_WAVE; ++i) cur_b[i] = ps.row[i] + boff;
     };
     rebase(0);
     auto issue = [&](int stage) {
@@ -108,7 +111,7 @@ __device__ __forceinline__ void qr_pipe_mma(const QrPhase<NT> (&ph)[NPH], int n_
         for (int i = 0; i < P::B_PER_WAVE; ++i) {
             const int8_t *src = cur_b[i];
             if (TAIL && tail) {
-                const int k = cur_kc * QRNNT_KCHUNK + ((wave * NT + i) & 1) * 64 + boff;
+                const int k = cur_kc * QRNNT_KCHUNK + boff;
                 if (k >= cur_K) src = cur_b[i] - k;   // row start: any valid bytes do, they meet zero weights
             }
             qr_load_lds16(src, sbase + (P::A_BLOCKS + wave * NT + i) * 1024);
@@ -138,14 +141,15 @@ __device__ __forceinline__ void qr_pipe_mma(const QrPhase<NT> (&ph)[NPH], int n_
         istage = (istage + 1 == S) ? 0 : istage + 1;
 
         const char *sb = lds + stage * P::STAGE_BYTES + lane * 16;
+        const char *sbb = lds + stage * P::STAGE_BYTES + (P::A_BLOCKS + (col >> 3)) * 1024 + (col & 7) * 128;
         stage = (stage + 1 == S) ? 0 : stage + 1;
         v4i pa[MT], b0[NT], b1[NT];
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) pa[mt] = *(const v4i *)(sb + (wm * MT + mt) * 1024);
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) {
-            b0[nt] = *(const v4i *)(sb + (P::A_BLOCKS + (wn * NT + nt) * 2) * 1024);
-            b1[nt] = *(const v4i *)(sb + (P::A_BLOCKS + (wn * NT + nt) * 2 + 1) * 1024);
+            b0[nt] = *(const v4i *)(sbb + (wn * NT + nt) * 2048 + p0);
+            b1[nt] = *(const v4i *)(sbb + (wn * NT + nt) * 2048 + p1);
         }
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) {

@@ -66,7 +66,7 @@ def test_config0_end_to_end_beams_identical(gpu_lib, std):
 
 @pytest.mark.parametrize("B,W,max_sym,T,lms,std", [(3, 4, 2, 12, True, 0.6), (2, 1, 3, 10, True, 0.6),
                                                    (4, 16, 4, 6, True, 0.5), (2, 3, 0, 8, False, 0.6),
-                                                   (5, 8, 1, 9, False, 0.4)])
+                                                   (5, 8, 1, 9, False, 0.4), (5, 16, 2, 6, True, 0.5)])
 def test_decode_variants_match_oracle(gpu_lib, B, W, max_sym, T, lms, std):
     from paper_2206_07882_amd import model as gmodel
     m = synth.make_model(0, weight_std=std)
@@ -87,6 +87,18 @@ def test_decode_full_width_networks_small_batch(gpu_lib):
     m = synth.make_model(4, enc_layers=1)
     T, B, W, max_sym = 6, 2, 4, 2
     e = synth.normal(200, (T, B, m.J), 1.0)
+    ref = oracle.decode(omodels.model_from_float(m), e, W, max_sym)
+    got = gpu_lib.decode(gmodel.model_from_float(m, DEV), dev(e), W, max_sym)
+    _compare_beams(got, ref)
+
+
+def test_decode_full_width_networks_128_hypotheses(gpu_lib):
+    """Same widths at 8 utterances x beam 16 = 128 hypotheses: the compute-bound step
+    kernel with full tiles and the per-token table of layer-0 input projections."""
+    from paper_2206_07882_amd import model as gmodel
+    m = synth.make_model(4, enc_layers=1)
+    T, B, W, max_sym = 2, 8, 16, 2
+    e = synth.normal(201, (T, B, m.J), 1.0)
     ref = oracle.decode(omodels.model_from_float(m), e, W, max_sym)
     got = gpu_lib.decode(gmodel.model_from_float(m, DEV), dev(e), W, max_sym)
     _compare_beams(got, ref)
