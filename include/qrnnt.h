@@ -61,9 +61,12 @@ uint32_t qrnnt_abi_version(void);
  *   low nibble, W[16*row_tile + l%16][128*k_chunk + 16*(l/16) + 4*d + b] and,
  *   in its high nibble, the element 64 columns further.  One 128-bit load per
  *   lane thus yields two int8 MFMA operands after two mask/shift operations.
- * TILED_GATES: TILED applied after permuting the 4H gate rows so that tiled
- *   row 4*j + g is source row g*H + j: the four gates of a cell land in one
- *   lane's accumulator quartet.  Row scales and biases stay in source order. */
+ * TILED_GATES: TILED applied after permuting the 4H gate rows (source row
+ *   g*H + j = gate g of cell j) in groups of 16 cells = 64 tiled rows: cell
+ *   j = 16*q + 4*a + b, gate g is tiled row 64*q + 16*b + 4*a + g (rows padded
+ *   to a multiple of 64).  The four gates of a cell land in one lane's
+ *   accumulator quartet, and over the 4 row tiles of a group a lane owns 4
+ *   consecutive cells.  Row scales and biases stay in source order. */
 enum { QRNNT_LAYOUT_ROWMAJOR = 0, QRNNT_LAYOUT_TILED = 1, QRNNT_LAYOUT_TILED_GATES = 2 };
 enum { QRNNT_SRC_INT8_CODES = 0, QRNNT_SRC_FP32 = 1 };
 

@@ -125,8 +125,8 @@ __global__ __launch_bounds__(256) void lstm_step_small_kernel(const QrStepGroup 
     __syncthreads();
     if (wave != 0) return;
 
-    // ---- wave 0: cell j = 4*rt + grp for hypotheses col (+16 per column tile)
-    const int j = rt * 4 + grp;
+    // ---- wave 0: the cell of (row tile, grp) for hypotheses col (+16 per column tile)
+    const int j = qr_gates_cell(rt, grp);
     float sx[4], sh[4], bb[4];
 #pragma unroll
     for (int gt = 0; gt < 4; ++gt) {
@@ -140,7 +140,7 @@ __global__ __launch_bounds__(256) void lstm_step_small_kernel(const QrStepGroup 
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) {
         cp[nt] = a.c_prev[(int64_t)src_of[nt] * H + j];
-        if (USE_GX) gxv[nt] = *(const v4i *)(a.gx + (int64_t)xr[nt] * a.ld_gx + 4 * j);
+        if (USE_GX) gxv[nt] = *(const v4i *)(a.gx + (int64_t)xr[nt] * a.ld_gx + rt * 16 + 4 * grp);
     }
     if (a.active) {
 #pragma unroll
@@ -284,118 +284,135 @@ __global__ __launch_bounds__(256, 2) void lstm_step_pipe_kernel(const QrStepGrou
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) acc[mt][nt] = zero;
 
-    // cell index of (mt, this lane); clamped copy for loads
-    int jc[MT];
+    // This lane finishes cells jb[q] .. jb[q]+3 (row tiles 4q .. 4q+3 of the wave) for
+    // hypotheses n_of[nt]; out-of-range quartets are clamped for loads and skipped at the stores.
+    static_assert(MT % 4 == 0, "a wave owns whole 64-row groups");
+    constexpr int MQ = MT / 4;
+    int jb[MQ];
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt) {
-        const int j = (rt0 + mt) * 4 + grp;
-        jc[mt] = j < H ? j : H - 1;
+    for (int q = 0; q < MQ; ++q) {
+        const int j = qr_gates_cell(rt0 + 4 * q, grp);
+        jb[q] = j < H ? j : H - 4;
     }
+    auto load4 = [](const float *p) { return *(const v4f *)p; };
 
     // input part -> fp32 (s_x * s_wih[r] * accx); the accumulators restart for the recurrent part
     auto x_done = [&]() {
-        float sx[MT][4];
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt)
+        for (int q = 0; q < MQ; ++q) {
+            v4f sx[4];
 #pragma unroll
-            for (int gt = 0; gt < 4; ++gt) sx[mt][gt] = a.x_scale * a.s_wih[gt * H + jc[mt]];
+            for (int gt = 0; gt < 4; ++gt) sx[gt] = load4(a.s_wih + gt * H + jb[q]) * a.x_scale;
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt)
+            for (int i = 0; i < 4; ++i)
 #pragma unroll
-            for (int nt = 0; nt < NT; ++nt) {
-                const v4i ax = acc[mt][nt] >> 4;
-                if (DBG && a.dbg_accx && (rt0 + mt) * 4 + grp < H && n_of[nt] < N)
+                for (int nt = 0; nt < NT; ++nt) {
+                    const int mt = 4 * q + i;
+                    const v4i ax = acc[mt][nt] >> 4;
+                    if (DBG && a.dbg_accx && jb[q] == qr_gates_cell(rt0 + 4 * q, grp) && n_of[nt] < N)
 #pragma unroll
-                    for (int gt = 0; gt < 4; ++gt) a.dbg_accx[(int64_t)n_of[nt] * 4 * H + gt * H + jc[mt]] = ax[gt];
+                        for (int gt = 0; gt < 4; ++gt) a.dbg_accx[(int64_t)n_of[nt] * 4 * H + gt * H + jb[q] + i] = ax[gt];
 #pragma unroll
-                for (int gt = 0; gt < 4; ++gt) pre[mt][nt][gt] = sx[mt][gt] * (float)ax[gt];
-                acc[mt][nt] = zero;
-            }
+                    for (int gt = 0; gt < 4; ++gt) pre[mt][nt][gt] = sx[gt][i] * (float)ax[gt];
+                    acc[mt][nt] = zero;
+                }
+        }
     };
     if (USE_GX) {
-        float sx[MT][4];
         v4i ax[MT][NT];
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) {
+            int tr = (rt0 + mt) * 16 + 4 * grp;   // gx columns are in tiled-row order
+            tr = tr < 4 * H ? tr : 4 * H - 4;
 #pragma unroll
-            for (int gt = 0; gt < 4; ++gt) sx[mt][gt] = a.x_scale * a.s_wih[gt * H + jc[mt]];
-#pragma unroll
-            for (int nt = 0; nt < NT; ++nt) {
-                ax[mt][nt] = *(const v4i *)(a.gx + (int64_t)gx_of[nt] * a.ld_gx + 4 * jc[mt]);
-            }
+            for (int nt = 0; nt < NT; ++nt) ax[mt][nt] = *(const v4i *)(a.gx + (int64_t)gx_of[nt] * a.ld_gx + tr);
         }
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt)
+        for (int q = 0; q < MQ; ++q) {
+            v4f sx[4];
 #pragma unroll
-            for (int nt = 0; nt < NT; ++nt) {
-                if (DBG && a.dbg_accx && (rt0 + mt) * 4 + grp < H && n_of[nt] < N)
+            for (int gt = 0; gt < 4; ++gt) sx[gt] = load4(a.s_wih + gt * H + jb[q]) * a.x_scale;
 #pragma unroll
-                    for (int gt = 0; gt < 4; ++gt) a.dbg_accx[(int64_t)n_of[nt] * 4 * H + gt * H + jc[mt]] = ax[mt][nt][gt];
+            for (int i = 0; i < 4; ++i)
 #pragma unroll
-                for (int gt = 0; gt < 4; ++gt) pre[mt][nt][gt] = sx[mt][gt] * (float)ax[mt][nt][gt];
-            }
+                for (int nt = 0; nt < NT; ++nt) {
+                    const int mt = 4 * q + i;
+                    if (DBG && a.dbg_accx && jb[q] == qr_gates_cell(rt0 + 4 * q, grp) && n_of[nt] < N)
+#pragma unroll
+                        for (int gt = 0; gt < 4; ++gt)
+                            a.dbg_accx[(int64_t)n_of[nt] * 4 * H + gt * H + jb[q] + i] = ax[mt][nt][gt];
+#pragma unroll
+                    for (int gt = 0; gt < 4; ++gt) pre[mt][nt][gt] = sx[gt][i] * (float)ax[mt][nt][gt];
+                }
+        }
     }
 
     qr_pipe_mma<MT, NT, S, NPH, !FAST>(ph, n_row_tiles, block_rt0, lds, acc, x_done);
 
-    // ---- fused cell: batched loads, then branch-free arithmetic, then stores
-    float cp[MT][NT], sh[MT][4], bb[MT][4];
-    int act[NT], hp_code[MT][NT];
+    // ---- fused cell: batched 128-bit loads, then branch-free arithmetic, then 128-bit / 32-bit stores
+    v4f cp[MQ][NT], sh[MQ][4], bb[MQ][4];
+    int act[NT], hp_code[MQ][NT];
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt) {
+    for (int q = 0; q < MQ; ++q) {
 #pragma unroll
         for (int gt = 0; gt < 4; ++gt) {
-            sh[mt][gt] = a.h_scale * a.s_whh[gt * H + jc[mt]];
-            bb[mt][gt] = a.bias[gt * H + jc[mt]];
+            sh[q][gt] = load4(a.s_whh + gt * H + jb[q]) * a.h_scale;
+            bb[q][gt] = load4(a.bias + gt * H + jb[q]);
         }
 #pragma unroll
-        for (int nt = 0; nt < NT; ++nt) cp[mt][nt] = a.c_prev[(int64_t)src_of[nt] * H + jc[mt]];
+        for (int nt = 0; nt < NT; ++nt) cp[q][nt] = load4(a.c_prev + (int64_t)src_of[nt] * H + jb[q]);
     }
     if (a.active) {
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) {
             act[nt] = a.active[n_of[nt] < N ? n_of[nt] : N - 1];
 #pragma unroll
-            for (int mt = 0; mt < MT; ++mt) hp_code[mt][nt] = a.h_prev[(int64_t)src_of[nt] * a.ld_hp + jc[mt]];
+            for (int q = 0; q < MQ; ++q) hp_code[q][nt] = *(const int *)(a.h_prev + (int64_t)src_of[nt] * a.ld_hp + jb[q]);
         }
     } else {
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) {
             act[nt] = 1;
 #pragma unroll
-            for (int mt = 0; mt < MT; ++mt) hp_code[mt][nt] = 0;
+            for (int q = 0; q < MQ; ++q) hp_code[q][nt] = 0;
         }
     }
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt) {
-        const bool jv = FAST || (rt0 + mt) * 4 + grp < H;
+    for (int q = 0; q < MQ; ++q) {
+        const bool jv = FAST || qr_gates_cell(rt0 + 4 * q, grp) < H;
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) {
             const int n = n_of[nt];
-            const v4i ah = acc[mt][nt] >> 4;
-            float p[4];
-#pragma unroll
-            for (int gt = 0; gt < 4; ++gt) p[gt] = pre[mt][nt][gt] + (sh[mt][gt] * (float)ah[gt] + bb[mt][gt]);
-            const float gi = qr_sigmoid(p[0]), gf = qr_sigmoid(p[1]), gg = qr_tanh(p[2]), go = qr_sigmoid(p[3]);
-            float cn = gf * cp[mt][nt] + gi * gg;
-            const float h = go * qr_tanh(cn);
-            int code = qr_quant4(h, a.h_inv);
             const bool on = act[nt] != 0;
-            cn = on ? cn : cp[mt][nt];
-            code = on ? code : hp_code[mt][nt];
-            if (FAST || (jv && n < N)) {
-                a.c_next[(int64_t)n * H + jc[mt]] = cn;
-                a.h_next[(int64_t)n * a.ld_hn + jc[mt]] = (int8_t)code;
-                if (a.h_copy) a.h_copy[(int64_t)n * H + jc[mt]] = (int8_t)code;
-                if (DBG) {
+            v4f cn;
+            unsigned codes = 0;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int mt = 4 * q + i;
+                const v4i ah = acc[mt][nt] >> 4;
+                float p[4];
+#pragma unroll
+                for (int gt = 0; gt < 4; ++gt) p[gt] = pre[mt][nt][gt] + (sh[q][gt][i] * (float)ah[gt] + bb[q][gt][i]);
+                const float gi = qr_sigmoid(p[0]), gf = qr_sigmoid(p[1]), gg = qr_tanh(p[2]), go = qr_sigmoid(p[3]);
+                const float c1 = gf * cp[q][nt][i] + gi * gg;
+                const float h = go * qr_tanh(c1);
+                cn[i] = on ? c1 : cp[q][nt][i];
+                codes |= (unsigned)(qr_quant4(h, a.h_inv) & 0xFF) << (8 * i);
+                if (DBG && jv && n < N) {
                     if (a.dbg_acch)
 #pragma unroll
-                        for (int gt = 0; gt < 4; ++gt) a.dbg_acch[(int64_t)n * 4 * H + gt * H + jc[mt]] = ah[gt];
+                        for (int gt = 0; gt < 4; ++gt) a.dbg_acch[(int64_t)n * 4 * H + gt * H + jb[q] + i] = ah[gt];
                     if (a.dbg_gates && on) {
-                        float *dg = a.dbg_gates + (int64_t)n * 4 * H + jc[mt];
+                        float *dg = a.dbg_gates + (int64_t)n * 4 * H + jb[q] + i;
                         dg[0] = gi; dg[H] = gf; dg[2 * H] = gg; dg[3 * H] = go;
                     }
                 }
+            }
+            codes = on ? codes : (unsigned)hp_code[q][nt];
+            if (FAST || (jv && n < N)) {
+                *(v4f *)(a.c_next + (int64_t)n * H + jb[q]) = cn;
+                *(unsigned *)(a.h_next + (int64_t)n * a.ld_hn + jb[q]) = codes;
+                if (a.h_copy) *(unsigned *)(a.h_copy + (int64_t)n * H + jb[q]) = codes;
             }
         }
     }
@@ -483,14 +500,14 @@ __global__ __launch_bounds__(256, 1) void gx_gemm_pipe_kernel(const v4i *__restr
     qr_pipe_mma<MT, NT, S, 1, TAIL>(ph, n_row_tiles, block_rt0, lds, acc, [] {});
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
-        const int j = (rt0 + mt) * 4 + grp;
+        const int j = qr_gates_cell(rt0 + mt, grp);
         if (j >= H) continue;
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) {
             const int m = m0 + (wn * NT + nt) * 16 + col;
             if (m >= M) continue;
             const v4i v = acc[mt][nt] >> 4;
-            *(v4i *)(gx + (int64_t)m * 4 * H + 4 * j) = v;
+            *(v4i *)(gx + (int64_t)m * 4 * H + (rt0 + mt) * 16 + 4 * grp) = v;
             if (dbg_accx)
 #pragma unroll
                 for (int gt = 0; gt < 4; ++gt) dbg_accx[(int64_t)m * 4 * H + gt * H + j] = v[gt];
@@ -538,6 +555,8 @@ qrnnt_status qr_check_lstm(const qrnnt_lstm *L)
     s = qr_check_qmat(&L->w_hh, QRNNT_LAYOUT_TILED_GATES);
     if (s != QRNNT_OK) return s;
     QR_REQUIRE(L->bias != nullptr, QRNNT_ERR_NULL);
+    QR_REQUIRE(qr_aligned(L->bias, 16) && qr_aligned(L->w_ih.row_scale, 16) && qr_aligned(L->w_hh.row_scale, 16),
+               QRNNT_ERR_ALIGN);
     QR_REQUIRE(L->input_size > 0 && L->hidden_size > 0, QRNNT_ERR_SHAPE);
     QR_REQUIRE(L->input_size % 16 == 0 && L->hidden_size % 16 == 0, QRNNT_ERR_SHAPE);
     QR_REQUIRE(L->w_ih.rows == 4 * L->hidden_size && L->w_hh.rows == 4 * L->hidden_size, QRNNT_ERR_SHAPE);
@@ -598,7 +617,7 @@ static qrnnt_status make_step_args(QrStepArgs &a, const qrnnt_lstm *L, const int
     QR_REQUIRE(parent != nullptr || n_slots >= N, QRNNT_ERR_SHAPE);
     QR_REQUIRE(x_row != nullptr || n_x_rows >= N, QRNNT_ERR_SHAPE);
     QR_REQUIRE(qr_aligned(x_codes, 16) && qr_aligned(h_prev, 16), QRNNT_ERR_ALIGN);
-    QR_REQUIRE(qr_aligned(c_prev, 4) && qr_aligned(c_next, 4), QRNNT_ERR_ALIGN);
+    QR_REQUIRE(qr_aligned(c_prev, 16) && qr_aligned(c_next, 16) && qr_aligned(h_next, 4), QRNNT_ERR_ALIGN);
     QR_REQUIRE((const void *)h_next != (const void *)h_prev && c_next != c_prev, QRNNT_ERR_RANGE);
     a = QrStepArgs{};
     qr_fill_lstm_weights(a, L);

@@ -27,8 +27,9 @@ extern "C" size_t qrnnt_pack_int4_bytes(int32_t rows, int32_t cols, int32_t layo
     if (layout == QRNNT_LAYOUT_ROWMAJOR) return (size_t)rows * (size_t)(qr_round_up(cols, 64) / 2);
     if (layout == QRNNT_LAYOUT_TILED || layout == QRNNT_LAYOUT_TILED_GATES) {
         if (layout == QRNNT_LAYOUT_TILED_GATES && rows % 4 != 0) return 0;
-        return (size_t)(qr_round_up(rows, 16) / 16) * (size_t)(qr_round_up(cols, QRNNT_KCHUNK) / QRNNT_KCHUNK) *
-               QRNNT_BLOCK_BYTES;
+        // TILED_GATES works in groups of 16 cells = 64 rows
+        const int rp = layout == QRNNT_LAYOUT_TILED_GATES ? qr_round_up(rows, 64) : qr_round_up(rows, 16);
+        return (size_t)(rp / 16) * (size_t)(qr_round_up(cols, QRNNT_KCHUNK) / QRNNT_KCHUNK) * QRNNT_BLOCK_BYTES;
     }
     return 0;
 }
@@ -68,9 +69,10 @@ __global__ __launch_bounds__(256) void pack_tiled_kernel(const void *__restrict_
     const int rt = (int)(blk / nkc);
     const int tr = rt * 16 + (lane & 15);
     uint32_t word = 0;
-    if (tr < rows) {
-        const int H = rows >> 2;
-        const int r = gates ? (tr & 3) * H + (tr >> 2) : tr;
+    const int H = rows >> 2;
+    const int cell = qr_gates_cell(rt, (lane & 15) >> 2);
+    if (gates ? cell < H : tr < rows) {
+        const int r = gates ? (tr & 3) * H + cell : tr;
         float inv = 0.0f;
         if (FP32) inv = inv_alpha7[r];
         const int kbase = kc * QRNNT_KCHUNK + (lane >> 4) * 16 + d * 4;
@@ -192,7 +194,7 @@ __global__ __launch_bounds__(256) void unpack_kernel(const uint8_t *__restrict__
     } else {
         const int nkc = qr_round_up(cols, QRNNT_KCHUNK) / QRNNT_KCHUNK;
         const int H = rows >> 2;
-        const int tr = (layout == QRNNT_LAYOUT_TILED_GATES) ? (r % H) * 4 + r / H : r;
+        const int tr = (layout == QRNNT_LAYOUT_TILED_GATES) ? qr_gates_tiled_row(r % H, r / H) : r;
         const int rt = tr >> 4, kc = k / QRNNT_KCHUNK, kk = k % QRNNT_KCHUNK;
         const int half = kk >> 6, k16 = (kk & 63) >> 4, d = (kk & 15) >> 2, b = kk & 3;
         const int lane = k16 * 16 + (tr & 15);

@@ -14,6 +14,16 @@ typedef float v4f __attribute__((ext_vector_type(4)));
 #define QRNNT_BLOCK_BYTES 1024  // 16 rows x 128 nibbles
 
 __host__ __device__ static inline int qr_round_up(int a, int b) { return (a + b - 1) / b * b; }
+
+// TILED_GATES row order.  Tiled row 16*rt + 4*grp + gate holds gate `gate` of cell
+// 16*(rt/4) + 4*grp + rt%4: an MFMA output lane (grp, col) of row tile rt receives the
+// four gate sums of that cell, and over the 4 row tiles of a 64-row group the lane
+// owns 4 consecutive cells (16 bytes of cell state, 4 bytes of hidden codes).
+__host__ __device__ static inline int qr_gates_cell(int rt, int grp) { return ((rt >> 2) << 4) + (grp << 2) + (rt & 3); }
+__host__ __device__ static inline int qr_gates_tiled_row(int cell, int gate)
+{
+    return ((((cell >> 4) << 2) + (cell & 3)) << 4) + (((cell >> 2) & 3) << 2) + gate;
+}
 static inline bool qr_aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
 
 #define QR_REQUIRE(cond, err) \

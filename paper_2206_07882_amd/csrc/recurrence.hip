@@ -92,7 +92,7 @@ __global__ __launch_bounds__(256) void lstm_rec_kernel(const QrRecGroup g)
             }
         }
     // ---- the cell this lane finishes: row tile = wave, cell j, utterance n
-    const int j = cg * 16 + wave * 4 + grp;
+    const int j = qr_gates_cell(cg * 4 + wave, grp);   // = 16*cg + 4*grp + wave
     const int n = ug * 16 + col;
     const int nn = n < B ? n : B - 1;
     float sx[4], sh[4], bb[4];
@@ -110,7 +110,7 @@ __global__ __launch_bounds__(256) void lstm_rec_kernel(const QrRecGroup g)
     const size_t xparity = (size_t)((B + 15) >> 4) * xgroup;
     for (int s = 0; s < T; ++s) {
         const int t = a.reverse ? T - 1 - s : s;
-        const v4i gxv = *(const v4i *)(a.gx + ((int64_t)t * B + nn) * 4 * H + 4 * j);   // independent of h: first
+        const v4i gxv = *(const v4i *)(a.gx + ((int64_t)t * B + nn) * 4 * H + (cg * 4 + wave) * 16 + 4 * grp);   // independent of h: first
         v4i acc[4] = {zero, zero, zero, zero};
         bool failed = false;
         if (s > 0 || a.h0) {
@@ -172,7 +172,7 @@ __global__ __launch_bounds__(256) void lstm_rec_kernel(const QrRecGroup g)
         const float gi = qr_sigmoid(p[0]), gf = qr_sigmoid(p[1]), gg = qr_tanh(p[2]), go = qr_sigmoid(p[3]);
         c = gf * c + gi * gg;
         const float h = go * qr_tanh(c);
-        hc[col][wave * 4 + grp] = (int8_t)qr_quant4(h, a.h_inv);
+        hc[col][grp * 4 + wave] = (int8_t)qr_quant4(h, a.h_inv);
         if (a.dbg_c_all && n < B) a.dbg_c_all[((int64_t)t * B + n) * H + j] = c;
         __syncthreads();
         // publish: 16 utterances x 4 quads, one 8-byte word each, tagged s+1
