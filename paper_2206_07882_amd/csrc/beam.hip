@@ -65,58 +65,6 @@ __global__ __launch_bounds__(256) void beam_step_kernel(const float *__restrict_
     }
 }
 
-// Selection fused with the routing of the picks inside the decoding loop: blank
-// picks join the frame's candidate list, label picks become the slots of the next
-// round in selection order (prefix counts by ballot), the remaining slots die.
-__global__ __launch_bounds__(256) void beam_route_kernel(const QrRouteArgs a)
-{
-    __shared__ unsigned slots[16];
-    const int b = blockIdx.x, lane = threadIdx.x;
-    const int W = a.W, V = a.V, N = a.B * a.W;
-    int c;
-    float v;
-    select_w(a.score_src + (int64_t)b * W, a.fused + (int64_t)b * W * V, W, V, a.blank, a.last_round, lane, slots, c, v);
-    if (lane >= 64) return;   // the picks live in threads 0 .. W-1 <= 63: wave 0 routes them
-    const bool in = lane < W;
-    const bool found = in && c >= 0;
-    const int par = found ? c / V : 0, tok = found ? c - (c / V) * V : 0;
-    const bool is_blank = found && tok == a.blank;
-    const bool is_lab = found && tok != a.blank && !a.last_round;
-    const unsigned long long bm = __ballot(is_blank), lm = __ballot(is_lab);
-    const unsigned long long lt = (1ull << lane) - 1ull;
-    const int src_slot = b * W + par;
-    const int nx0 = a.nx_count[b];
-    if (is_blank) {
-        const int e = nx0 + __popcll(bm & lt);
-        a.nx_score[(size_t)b * a.R * W + e] = v;
-        a.nx_src[(size_t)b * a.R * W + e] = a.src_buf * N + src_slot;
-    }
-    if (lane == 0) a.nx_count[b] = nx0 + __popcll(bm);
-    if (a.last_round) return;
-    const int n_lab = __popcll(lm);
-    if (is_lab) {
-        const int dst = b * W + __popcll(lm & lt);
-        const int id = a.node_base + dst;
-        a.node_tok[id] = tok;
-        a.node_prev[id] = a.node_src[src_slot];
-        a.score_dst[dst] = v;
-        a.node_dst[dst] = id;
-        a.len_dst[dst] = a.len_src[src_slot] + 1;
-        a.parent_idx[dst] = src_slot;
-        a.token[dst] = tok;
-        a.active[dst] = 1;
-    }
-    if (in && lane >= n_lab) {
-        const int dst = b * W + lane;
-        a.score_dst[dst] = -INFINITY;
-        a.node_dst[dst] = 0;
-        a.len_dst[dst] = 0;
-        a.parent_idx[dst] = dst;
-        a.token[dst] = a.blank;
-        a.active[dst] = 0;
-    }
-}
-
 }  // namespace
 
 void qr_launch_beam(const float *score, const float *fused, int B, int W, int V, int blank, int force_blank,
@@ -124,8 +72,6 @@ void qr_launch_beam(const float *score, const float *fused, int B, int W, int V,
 {
     beam_step_kernel<<<B, 256, 0, st>>>(score, fused, W, V, blank, force_blank, parent_out, token_out, score_out);
 }
-
-void qr_launch_beam_route(const QrRouteArgs &a, hipStream_t st) { beam_route_kernel<<<a.B, 256, 0, st>>>(a); }
 
 extern "C" qrnnt_status qrnnt_beam_step(const float *score, const float *fused, int32_t B, int32_t W, int32_t V,
                                         int32_t blank, int32_t force_blank, int32_t *parent_out, int32_t *token_out,

@@ -23,7 +23,6 @@ struct Plan {
     NetBuf net[3];
     float *score;        // [NB][B][W]
     int32_t *node, *len; // [NB][N]
-    float *fused;        // [N][V]
     int32_t *parent_idx, *token;  uint8_t *active;        // [N]
     float *nx_score;  int32_t *nx_src;  int32_t *nx_count; // [B][R*W], [B]
     int32_t *beam_src;   // [N]
@@ -64,7 +63,6 @@ void make_plan(const qrnnt_model *m, int T, int B, int W, int max_sym, void *ws,
     p.score = cv.take<float>(NB * N);
     p.node = cv.take<int32_t>(NB * N);
     p.len = cv.take<int32_t>(NB * N);
-    p.fused = cv.take<float>(N * p.V);
     p.parent_idx = cv.take<int32_t>(N);
     p.token = cv.take<int32_t>(N);
     p.active = cv.take<uint8_t>(N);
@@ -345,7 +343,6 @@ extern "C" qrnnt_status qrnnt_decode(const qrnnt_model *m, const float *enc_proj
     ja.lambda_src = m->lambda_src;  ja.lambda_ext = m->lambda_ext;  ja.rho = m->rho;
     ja.N = N;  ja.J = p.J;  ja.V = V;  ja.blank = m->blank;
     ja.nkc = qr_round_up(p.J, QRNNT_KCHUNK) / QRNNT_KCHUNK;
-    ja.fused = p.fused;
 
     int a0 = 0;   // buffer of the beam at the current frame
     for (int t = 0; t < T; ++t) {
@@ -356,10 +353,9 @@ extern "C" qrnnt_status qrnnt_decode(const qrnnt_model *m, const float *enc_proj
             ja.pred = p.net[0].y + (size_t)cur * Ns * p.J;
             ja.lp_src = m->use_src ? p.net[1].y + (size_t)cur * Ns * V : nullptr;
             ja.lp_ext = m->use_ext ? p.net[2].y + (size_t)cur * Ns * V : nullptr;
-            qr_launch_joint(ja, st);
             const int last = (v == max_sym);
             QrRouteArgs ra = {};
-            ra.score_src = p.score + (size_t)cur * Ns;  ra.fused = p.fused;
+            ra.score_src = p.score + (size_t)cur * Ns;
             ra.B = B;  ra.W = W;  ra.V = V;  ra.R = p.R;  ra.blank = m->blank;  ra.src_buf = cur;  ra.last_round = last;
             ra.node_base = 1 + (t * max_sym + v) * N;
             ra.node_src = p.node + (size_t)cur * Ns;  ra.len_src = p.len + (size_t)cur * Ns;
@@ -368,7 +364,7 @@ extern "C" qrnnt_status qrnnt_decode(const qrnnt_model *m, const float *enc_proj
             ra.parent_idx = p.parent_idx;  ra.token = p.token;  ra.active = p.active;
             ra.nx_score = p.nx_score;  ra.nx_src = p.nx_src;  ra.nx_count = p.nx_count;
             ra.node_tok = p.node_tok;  ra.node_prev = p.node_prev;
-            qr_launch_beam_route(ra, st);
+            qr_launch_joint_route(ja, ra, st);
             if (!last) advance_nets(m, p, cur, nxt, n_embed_rows, st);
         }
         const int dst = (a0 == 0) ? ZB : 0;

@@ -3,6 +3,8 @@
 // and a log-softmax follow; Eq. 1 adds the weighted LM log-probabilities).
 #include "head.h"
 #include "kernels.h"
+#include "route.h"
+#include "select.h"
 
 namespace {
 
@@ -92,7 +94,153 @@ __global__ __launch_bounds__(256) void joint_fuse_kernel(const QrJointArgs a)
         }
 }
 
+// Decoding-loop variant: one block per utterance does the joint + fusion for its W
+// hypotheses (NTW column tiles of 16), and wave 0, which ends up holding every fused
+// score of the utterance in registers, goes straight on to select the W best
+// (parent, token) extensions and to route them (route.h).  The fused scores never
+// touch memory and a decoding round saves a launch.
+// Lane (grp, col) of wave 0 holds, in slot s = 16*nt + 4*mt + i, the candidate
+// (hypothesis w = 16*nt + col, token k = 16*mt + 4*grp + i); its flat index
+// w*V + k grows with s, so the first best slot of a lane is its lowest index.
+template <int NTW>
+__global__ __launch_bounds__(256) void joint_route_kernel(const QrJointArgs a, const QrRouteArgs r)
+{
+    __shared__ v4i lds[4 * 4 * 64];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int col = lane & 15, grp = lane >> 4;
+    const int b = blockIdx.x;
+    const int W = r.W, V = a.V, J = a.J;
+    int fr = a.frame_base + b;
+    fr = fr < 0 ? 0 : (fr >= a.n_enc_rows ? a.n_enc_rows - 1 : fr);
+    const float *e = a.enc + (int64_t)fr * J + grp * 16;
+    const float z_inv = a.z_inv;
+    const int n_row_tiles = (V + 15) >> 4;
+    constexpr int PER = 16 * NTW;
+    float val[PER];
+    // per-token constants of this lane's 16 tokens
+    float wscale[4][4], wbias[4][4];
+    if (wave == 0) {
+#pragma unroll
+        for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int k = mt * 16 + grp * 4 + i;
+                const int kk = k < V ? k : V - 1;
+                wscale[mt][i] = a.z_scale * a.s_w[kk];
+                wbias[mt][i] = a.b_out ? a.b_out[kk] : 0.0f;
+            }
+    }
+#pragma unroll
+    for (int nt = 0; nt < NTW; ++nt) {
+        const int w = nt * 16 + col;
+        const bool wv = w < W;
+        const int n = b * W + (wv ? w : W - 1);
+        const float *p = a.pred + (int64_t)n * J + grp * 16;
+        auto bfrag = [&](int kb) -> v4i {
+            v4i bq = {0, 0, 0, 0};
+            if (kb * 64 + grp * 16 < J) {
+#pragma unroll
+                for (int d = 0; d < 4; ++d) {
+                    const v4f ev = *(const v4f *)(e + kb * 64 + 4 * d);
+                    const v4f pv = *(const v4f *)(p + kb * 64 + 4 * d);
+                    uint32_t word = 0;
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        const float z = qr_tanh(ev[i] * pv[i]);
+                        word |= (uint32_t)(qr_quant4(z, z_inv) & 0xFF) << (8 * i);
+                    }
+                    bq[d] = (int)word;
+                }
+            }
+            return bq;
+        };
+        // LM log-probabilities and the running score: issued before the contraction
+        float ls[4][4], le[4][4], sc = 0.0f;
+        if (wave == 0) {
+            sc = r.score_src[(int64_t)b * W + (wv ? w : W - 1)];
+#pragma unroll
+            for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const int k = mt * 16 + grp * 4 + i;
+                    const int kk = k < V ? k : V - 1;
+                    ls[mt][i] = a.lp_src ? a.lp_src[(int64_t)n * V + kk] : 0.0f;
+                    le[mt][i] = a.lp_ext ? a.lp_ext[(int64_t)n * V + kk] : 0.0f;
+                }
+        }
+        v4i acc[4];
+        if (nt > 0) __syncthreads();   // the reduction buffer of the previous tile has been read
+        qr_head_mma(a.w, a.nkc, n_row_tiles, 0, J, bfrag, acc, lds);
+        if (wave == 0) {
+            float v[4][4];
+            float m = -INFINITY;
+#pragma unroll
+            for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const int k = mt * 16 + grp * 4 + i;
+                    v[mt][i] = k < V ? wscale[mt][i] * (float)acc[mt][i] + wbias[mt][i] : -INFINITY;
+                    m = fmaxf(m, v[mt][i]);
+                }
+            m = fmaxf(m, __shfl_xor(m, 16));
+            m = fmaxf(m, __shfl_xor(m, 32));
+            float sum = 0.0f;
+#pragma unroll
+            for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) sum += (mt * 16 + grp * 4 + i < V) ? expf(v[mt][i] - m) : 0.0f;
+            sum += __shfl_xor(sum, 16);
+            sum += __shfl_xor(sum, 32);
+            const float lse = m + logf(sum);
+#pragma unroll
+            for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const int k = mt * 16 + grp * 4 + i;
+                    float f = v[mt][i] - lse;
+                    if (k != a.blank) {
+                        if (a.lp_src) f -= a.lambda_src * ls[mt][i];
+                        if (a.lp_ext) f += a.lambda_ext * le[mt][i];
+                        f += a.rho;
+                    }
+                    const bool ok = wv && k < V && (!r.last_round || k == a.blank);
+                    val[nt * 16 + mt * 4 + i] = ok ? (sc + f) + 0.0f : -INFINITY;   // + 0: one key per value
+                }
+        }
+    }
+    if (wave != 0) return;
+
+    // ---- the W best under (value descending, flat index ascending)
+    const int cbase = col * V + grp * 4;   // flat index of slot s: cbase + (s>>4)*16*V + ((s>>2)&3)*16 + (s&3)
+    auto index_of = [&](int s) { return cbase + (s >> 4) * 16 * V + ((s >> 2) & 3) * 16 + (s & 3); };
+    float last_v = INFINITY;
+    int last_c = -1, my_c = -1;
+    float my_v = -INFINITY;
+    const bool fast = qr_select_pruned<PER>(val, index_of, W, lane, (unsigned *)lds, (int *)lds + 64, my_c, my_v);
+    for (int rd = 0; !fast && rd < W; ++rd) {   // general case: W rounds of arg-best
+        float bv = -INFINITY;
+        int bc = 0x7fffffff;
+#pragma unroll
+        for (int s = 0; s < PER; ++s) {
+            const int c = cbase + (s >> 4) * 16 * V + ((s >> 2) & 3) * 16 + (s & 3);
+            const float v = val[s];
+            const bool ok = v > -INFINITY && (v < last_v || (v == last_v && c > last_c));
+            if (ok && v > bv) { bv = v; bc = c; }   // slots are visited in index order: first best wins
+        }
+        if (!qr_select_round(bv, bc, rd, lane, last_v, last_c, my_c, my_v)) break;
+    }
+    qr_route_picks(r, b, lane, my_c, my_v);
+}
+
 }  // namespace
+
+void qr_launch_joint_route(const QrJointArgs &a, const QrRouteArgs &r, hipStream_t st)
+{
+    if (r.W <= 16) joint_route_kernel<1><<<r.B, 256, 0, st>>>(a, r);
+    else if (r.W <= 32) joint_route_kernel<2><<<r.B, 256, 0, st>>>(a, r);
+    else joint_route_kernel<4><<<r.B, 256, 0, st>>>(a, r);
+}
 
 void qr_launch_joint(const QrJointArgs &a, hipStream_t st)
 {

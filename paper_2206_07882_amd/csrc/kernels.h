@@ -60,7 +60,7 @@ struct QrJointArgs {
 };
 
 struct QrRouteArgs {
-    const float *score_src;  const float *fused;   // [B,W], [B*W,V] of the current round
+    const float *score_src;                         // [B,W] of the current round
     int B, W, V, R, blank, src_buf, last_round, node_base;
     const int32_t *node_src, *len_src;              // [N] of the current round
     float *score_dst;  int32_t *node_dst, *len_dst; // [N] of the next round
@@ -89,7 +89,6 @@ QR_HIDDEN bool qr_rec_supported(int H, int B);
 QR_HIDDEN size_t qr_rec_xbuf_bytes(int H, int B);
 QR_HIDDEN bool qr_launch_recurrence(const QrRecGroup &g, hipStream_t st);
 
-QR_HIDDEN void qr_launch_beam_route(const QrRouteArgs &a, hipStream_t st);
 QR_HIDDEN void qr_fill_lstm_weights(QrStepArgs &a, const qrnnt_lstm *L);
 QR_HIDDEN qrnnt_status qr_check_lstm(const qrnnt_lstm *L);
 QR_HIDDEN void qr_launch_lstm_step(const QrStepArgs &a, bool use_gx, hipStream_t st);
@@ -99,5 +98,6 @@ QR_HIDDEN void qr_launch_input_projection(const qrnnt_lstm *L, const int8_t *x_c
 QR_HIDDEN void qr_launch_linear_group(const QrLinearGroup &g, hipStream_t st);
 QR_HIDDEN void qr_launch_linear(const QrLinearArgs &a, hipStream_t st);
 QR_HIDDEN void qr_launch_joint(const QrJointArgs &a, hipStream_t st);
+QR_HIDDEN void qr_launch_joint_route(const QrJointArgs &a, const QrRouteArgs &r, hipStream_t st);
 QR_HIDDEN void qr_launch_beam(const float *score, const float *fused, int B, int W, int V, int blank, int force_blank,
                               int32_t *parent_out, int32_t *token_out, float *score_out, hipStream_t st);

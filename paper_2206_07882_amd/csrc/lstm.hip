@@ -225,6 +225,10 @@ __global__ __launch_bounds__(256, 2) void lstm_step_pipe_kernel(const QrStepGrou
     const int col = lane & 15, grp = lane >> 4;
     const int wm = wave & 1, wn = wave >> 1;
     const int rt0 = block_rt0 + wm * MT;
+#ifdef QR_STEP_TS
+    long long ts[4];
+    ts[0] = clock64();
+#endif
 
     // ---- indices: rows this thread stages (ld_*) and hypotheses this lane finishes (n_of)
     int ld_n[NT], ld_s[NT], ld_x[NT], n_of[NT], src_of[NT], gx_of[NT];
@@ -347,7 +351,13 @@ __global__ __launch_bounds__(256, 2) void lstm_step_pipe_kernel(const QrStepGrou
         }
     }
 
+#ifdef QR_STEP_TS
+    ts[1] = clock64();
+#endif
     qr_pipe_mma<MT, NT, S, NPH, !FAST>(ph, n_row_tiles, block_rt0, lds, acc, x_done);
+#ifdef QR_STEP_TS
+    ts[2] = clock64();
+#endif
 
     // ---- fused cell: batched 128-bit loads, then branch-free arithmetic, then 128-bit / 32-bit stores
     v4f cp[MQ][NT], sh[MQ][4], bb[MQ][4];
@@ -416,6 +426,14 @@ __global__ __launch_bounds__(256, 2) void lstm_step_pipe_kernel(const QrStepGrou
             }
         }
     }
+#ifdef QR_STEP_TS
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    ts[3] = clock64();
+    if (a.dbg_gates && (tid & 63) == 0) {
+        long long *o = (long long *)a.dbg_gates + ((size_t)(blockIdx.x + gridDim.x * blockIdx.y) * 4 + wave) * 4;
+        o[0] = ts[0]; o[1] = ts[1]; o[2] = ts[2]; o[3] = ts[3];
+    }
+#endif
 }
 
 template <int MT, int NT, int S, bool USE_GX, bool DBG, bool FAST>
@@ -444,7 +462,9 @@ void launch_pipe(const QrStepGroup &g, hipStream_t st)
     bool dbg = false, fast = true;
     for (int i = 0; i < g.n; ++i) {
         const QrStepArgs &a = g.p[i];
+#ifndef QR_STEP_TS
         dbg = dbg || a.dbg_accx || a.dbg_acch || a.dbg_gates;
+#endif
         fast = fast && a.H % (8 * MT) == 0 && a.N % P::BN == 0 && a.H % QRNNT_KCHUNK == 0 &&
                (USE_GX || a.I % QRNNT_KCHUNK == 0);
     }

@@ -108,3 +108,68 @@ __device__ __forceinline__ void qr_block_select_from_regs(const float (&val)[PER
         if (tid == r) { my_c = last_c; my_v = last_v; }
     }
 }
+
+// Pruned selection for one wave holding PER candidate slots per lane (slot s of a
+// lane has flat index index_of(s), increasing with s; val = -inf where absent).
+//   1. each lane's best key; the W-th largest of those 64 keys, found by bisection
+//      over the key bits with one ballot per bit, is a lower bound T of the W-th best
+//      candidate (W lanes hold a candidate >= T);
+//   2. the candidates >= T are compacted into LDS (ballot prefix counts);
+//   3. if at most 64 survive, lane l takes survivor l and counts the survivors that
+//      precede it in the total order: that count is its rank, rank r < W is pick r.
+// Cost: a few hundred instructions instead of W dependent wave reductions over all
+// slots.  Returns false (nothing written) when more than 64 candidates survive, e.g.
+// fewer than W lanes hold anything: the caller then runs the round-by-round selection.
+// After a true return lane r < W holds pick r (index -1, value -inf if none).
+// sk / sc: 64 words of LDS each, private to the calling wave.
+template <int PER, class IndexOf>
+__device__ __forceinline__ bool qr_select_pruned(const float (&val)[PER], IndexOf &&index_of, int W, int lane,
+                                                 unsigned *sk, int *sc, int &my_c, float &my_v)
+{
+    unsigned key[PER];
+    unsigned lmax = 0u;
+#pragma unroll
+    for (int s = 0; s < PER; ++s) {
+        key[s] = val[s] > -INFINITY ? qr_float_key(val[s]) : 0u;
+        lmax = key[s] > lmax ? key[s] : lmax;
+    }
+    unsigned T = 0u;
+    for (int bit = 31; bit >= 0; --bit) {
+        const unsigned trial = T | (1u << bit);
+        if (__popcll(__ballot(lmax >= trial)) >= W) T = trial;   // uniform
+    }
+    T = T ? T : 1u;   // fewer than W lanes hold a candidate: every candidate survives
+    int M = 0;
+#pragma unroll
+    for (int s = 0; s < PER; ++s) M += __popcll(__ballot(key[s] >= T));
+    if (M > 64) return false;
+    int base = 0;
+#pragma unroll
+    for (int s = 0; s < PER; ++s) {
+        const bool keep = key[s] >= T;
+        const unsigned long long mk = __ballot(keep);
+        const int pos = base + (int)__builtin_amdgcn_mbcnt_hi((unsigned)(mk >> 32), __builtin_amdgcn_mbcnt_lo((unsigned)mk, 0u));
+        if (keep) { sk[pos] = key[s]; sc[pos] = index_of(s); }
+        base += __popcll(mk);
+    }
+    __builtin_amdgcn_wave_barrier();
+    const unsigned k = lane < M ? sk[lane] : 0u;
+    const int c = lane < M ? sc[lane] : 0x7fffffff;
+    int rank = 0;
+    for (int j = 0; j < M; ++j) {
+        const unsigned kj = (unsigned)__builtin_amdgcn_readlane((int)k, j);
+        const int cj = __builtin_amdgcn_readlane(c, j);
+        rank += (kj > k || (kj == k && cj < c)) ? 1 : 0;
+    }
+    __builtin_amdgcn_wave_barrier();
+    sk[lane] = 0u;
+    sc[lane] = -1;
+    __builtin_amdgcn_wave_barrier();
+    if (lane < M && rank < 64) { sk[rank] = k; sc[rank] = c; }
+    __builtin_amdgcn_wave_barrier();
+    const unsigned pk = sk[lane];
+    const int pc = sc[lane];
+    my_c = (lane < W) ? pc : -1;
+    my_v = (lane < W && pc >= 0) ? qr_key_float(pk) : -INFINITY;
+    return true;
+}
