@@ -142,6 +142,11 @@ qrnnt_status qrnnt_lstm_step(const qrnnt_lstm *L, const int8_t *x_codes, const i
 /* Up to 3 independent steps (e.g. the first layers of the prediction network and
  * of both LMs) in one launch, so that small problems fill the GPU together.
  * Each descriptor carries the arguments of qrnnt_lstm_step (no debug outputs).
+ * gx [device] int32 [n_x_rows, 4H] or NULL: the input projection of the rows of
+ * x_codes as written by qrnnt_input_projection.  When given, the input part of
+ * the step is looked up in it (row x_row ? x_row[n] : n) instead of contracted:
+ * the same integer sums, e.g. one table row per vocabulary entry for a layer fed
+ * by an embedding.  Either every step of a group has gx or none has.
  * steps [host] is read during the call only. */
 typedef struct {
     const qrnnt_lstm *L;
@@ -149,6 +154,7 @@ typedef struct {
     const int32_t *parent;  const int8_t *h_prev;  const float *c_prev;  int32_t n_slots;
     const uint8_t *active;  int32_t N;
     int8_t *h_next;  float *c_next;
+    const int32_t *gx;
 } qrnnt_step_desc;
 
 qrnnt_status qrnnt_lstm_step_group(const qrnnt_step_desc *steps, int32_t n_steps, void *stream);
@@ -183,10 +189,11 @@ qrnnt_status qrnnt_bilstm_layer(const qrnnt_lstm *fwd, const qrnnt_lstm *bwd, co
                                 int32_t B, int8_t *h_out, void *workspace, size_t workspace_bytes, void *stream);
 
 /* The input projection alone (first half of qrnnt_lstm_layer): for M rows of
- * input codes x [device] [M, I], gx[m, 4*j + g] = sum_k w_ih[g*H + j, k] * x[m, k]
- * as int32 [M, 4H]; columns are gate-interleaved (the four gate sums of cell j
- * are adjacent), which is the order the recurrence consumes.  dbg_accx [device]
- * int32 [M, 4H] in source row order, or NULL. */
+ * input codes x [device] [M, I], gx[m, r'] = sum_k w_ih[g*H + j, k] * x[m, k]
+ * as int32 [M, 4H], where r' is the TILED_GATES row of (cell j, gate g) (see the
+ * layout note above: the four gate sums of a cell are adjacent), which is the
+ * order the recurrence and qrnnt_step_desc.gx consume.  dbg_accx [device] int32
+ * [M, 4H] in source row order, or NULL.  hidden_size % 16 == 0. */
 qrnnt_status qrnnt_input_projection(const qrnnt_lstm *L, const int8_t *x_codes, int32_t M, int32_t *gx,
                                     int32_t *dbg_accx, void *stream);
 

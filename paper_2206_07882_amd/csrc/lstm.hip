@@ -225,10 +225,6 @@ __global__ __launch_bounds__(256, 2) void lstm_step_pipe_kernel(const QrStepGrou
     const int col = lane & 15, grp = lane >> 4;
     const int wm = wave & 1, wn = wave >> 1;
     const int rt0 = block_rt0 + wm * MT;
-#ifdef QR_STEP_TS
-    long long ts[4];
-    ts[0] = clock64();
-#endif
 
     // ---- indices: rows this thread stages (ld_*) and hypotheses this lane finishes (n_of)
     int ld_n[NT], ld_s[NT], ld_x[NT], n_of[NT], src_of[NT], gx_of[NT];
@@ -351,13 +347,7 @@ __global__ __launch_bounds__(256, 2) void lstm_step_pipe_kernel(const QrStepGrou
         }
     }
 
-#ifdef QR_STEP_TS
-    ts[1] = clock64();
-#endif
     qr_pipe_mma<MT, NT, S, NPH, !FAST>(ph, n_row_tiles, block_rt0, lds, acc, x_done);
-#ifdef QR_STEP_TS
-    ts[2] = clock64();
-#endif
 
     // ---- fused cell: batched 128-bit loads, then branch-free arithmetic, then 128-bit / 32-bit stores
     v4f cp[MQ][NT], sh[MQ][4], bb[MQ][4];
@@ -426,14 +416,6 @@ __global__ __launch_bounds__(256, 2) void lstm_step_pipe_kernel(const QrStepGrou
             }
         }
     }
-#ifdef QR_STEP_TS
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    ts[3] = clock64();
-    if (a.dbg_gates && (tid & 63) == 0) {
-        long long *o = (long long *)a.dbg_gates + ((size_t)(blockIdx.x + gridDim.x * blockIdx.y) * 4 + wave) * 4;
-        o[0] = ts[0]; o[1] = ts[1]; o[2] = ts[2]; o[3] = ts[3];
-    }
-#endif
 }
 
 template <int MT, int NT, int S, bool USE_GX, bool DBG, bool FAST>
@@ -462,9 +444,7 @@ void launch_pipe(const QrStepGroup &g, hipStream_t st)
     bool dbg = false, fast = true;
     for (int i = 0; i < g.n; ++i) {
         const QrStepArgs &a = g.p[i];
-#ifndef QR_STEP_TS
         dbg = dbg || a.dbg_accx || a.dbg_acch || a.dbg_gates;
-#endif
         fast = fast && a.H % (8 * MT) == 0 && a.N % P::BN == 0 && a.H % QRNNT_KCHUNK == 0 &&
                (USE_GX || a.I % QRNNT_KCHUNK == 0);
     }
@@ -675,18 +655,21 @@ extern "C" qrnnt_status qrnnt_lstm_step_group(const qrnnt_step_desc *steps, int3
         qrnnt_status s = make_step_args(g.p[i], d.L, d.x_codes, d.x_row, d.n_x_rows, d.parent, d.h_prev, d.c_prev,
                                         d.n_slots, d.active, d.N, d.h_next, d.c_next);
         if (s != QRNNT_OK) return s;
+        QR_REQUIRE((d.gx != nullptr) == (steps[0].gx != nullptr), QRNNT_ERR_RANGE);
+        QR_REQUIRE(qr_aligned(d.gx, 16), QRNNT_ERR_ALIGN);
+        g.p[i].gx = d.gx;  g.p[i].ld_gx = 4 * (int64_t)d.L->hidden_size;
     }
-    qr_launch_lstm_step_group(g, false, (hipStream_t)stream);
+    qr_launch_lstm_step_group(g, steps[0].gx != nullptr, (hipStream_t)stream);
     return qr_launch_status();
 }
 
 void qr_launch_input_projection(const qrnnt_lstm *L, const int8_t *x_codes, int M, int32_t *gx, int32_t *dbg_accx,
                                 hipStream_t st)
 {
-    static const int cfg = getenv("QRNNT_GEMM_TILE") ? atoi(getenv("QRNNT_GEMM_TILE")) : 44;
-    if (M <= 256 || cfg == 44) launch_gx_pipe<4, 4, 3>(L, x_codes, M, gx, dbg_accx, st);
-    else if (cfg == 48) launch_gx_pipe<4, 8, 3>(L, x_codes, M, gx, dbg_accx, st);
-    else launch_gx_pipe<8, 4, 3>(L, x_codes, M, gx, dbg_accx, st);
+    // 128 x 128 block tile; two ring stages leave room for a third workgroup per CU, which at many
+    // frames is worth more than a deeper ring (measured: 69 vs 74 us at 16000 x 1280 x 2560)
+    if (M <= 256) launch_gx_pipe<4, 4, 3>(L, x_codes, M, gx, dbg_accx, st);
+    else launch_gx_pipe<4, 4, 2>(L, x_codes, M, gx, dbg_accx, st);
 }
 
 extern "C" qrnnt_status qrnnt_input_projection(const qrnnt_lstm *L, const int8_t *x_codes, int32_t M, int32_t *gx,

@@ -99,16 +99,15 @@ __device__ __forceinline__ void qr_pipe_mma(const QrPhase<NT> (&ph)[NPH], int n_
         for (int i = 0; i < P::B_PER_WAVE; ++i) cur_b[i] = ps.row[i] + boff;
     };
     rebase(0);
-    auto issue = [&](int stage) {
-        const unsigned sbase = lds_base + stage * P::STAGE_BYTES;
-        const bool tail = TAIL && (cur_kc == cur_nkc - 1) && (cur_K & (QRNNT_KCHUNK - 1));   // uniform
-#pragma unroll
-        for (int a = 0; a < P::A_PER_WAVE; ++a) {
-            qr_load_lds16(cur_a[a], sbase + (wave * P::A_PER_WAVE + a) * 1024);
-            cur_a[a] += 64;
-        }
-#pragma unroll
-        for (int i = 0; i < P::B_PER_WAVE; ++i) {
+    // One chunk = LOADS loads per thread; issue_one(q) is load q of the chunk at the head of
+    // the issue stream, issue_done() moves the stream to the next chunk.
+    auto chunk_tail = [&]() { return TAIL && (cur_kc == cur_nkc - 1) && (cur_K & (QRNNT_KCHUNK - 1)); };   // uniform
+    auto issue_one = [&](int q, unsigned sbase, bool tail) {
+        if (q < P::A_PER_WAVE) {
+            qr_load_lds16(cur_a[q], sbase + (wave * P::A_PER_WAVE + q) * 1024);
+            cur_a[q] += 64;
+        } else {
+            const int i = q - P::A_PER_WAVE;
             const int8_t *src = cur_b[i];
             if (TAIL && tail) {
                 const int k = cur_kc * QRNNT_KCHUNK + boff;
@@ -117,11 +116,20 @@ __device__ __forceinline__ void qr_pipe_mma(const QrPhase<NT> (&ph)[NPH], int n_
             qr_load_lds16(src, sbase + (P::A_BLOCKS + wave * NT + i) * 1024);
             cur_b[i] += QRNNT_KCHUNK;
         }
+    };
+    auto issue_done = [&]() {
         if (++cur_kc == cur_nkc && NPH == 2 && cur_p == 0) {
             cur_p = 1;
             cur_kc = 0;
             rebase(1);
         }
+    };
+    auto issue = [&](int stage) {
+        const unsigned sbase = lds_base + stage * P::STAGE_BYTES;
+        const bool tail = chunk_tail();
+#pragma unroll
+        for (int q = 0; q < P::LOADS; ++q) issue_one(q, sbase, tail);
+        issue_done();
     };
 
     // prologue: fill DIST stages
@@ -137,7 +145,12 @@ __device__ __forceinline__ void qr_pipe_mma(const QrPhase<NT> (&ph)[NPH], int n_
         else if (P::DIST >= 2 && after >= 1) qr_wait_vmcnt<P::LOADS>();
         else qr_wait_vmcnt<0>();
         __builtin_amdgcn_s_barrier();
-        if (c + P::DIST < total) issue(istage);
+        // The refill of the stage that was read in the previous iteration is issued in
+        // shares between the row tiles' MFMAs: a wave issues in order, and a burst of
+        // direct loads would keep it away from the matrix unit for their whole issue time.
+        const bool do_issue = c + P::DIST < total;
+        const unsigned isbase = lds_base + istage * P::STAGE_BYTES;
+        const bool itail = chunk_tail();
         istage = (istage + 1 == S) ? 0 : istage + 1;
 
         const char *sb = lds + stage * P::STAGE_BYTES + lane * 16;
@@ -160,7 +173,15 @@ __device__ __forceinline__ void qr_pipe_mma(const QrPhase<NT> (&ph)[NPH], int n_
                 acc[mt][nt] = qr_mfma(lo, b0[nt], acc[mt][nt]);
                 acc[mt][nt] = qr_mfma(hi, b1[nt], acc[mt][nt]);
             }
+            constexpr int SHARE = (P::LOADS + MT - 1) / MT;
+            __builtin_amdgcn_sched_barrier(0);
+            if (do_issue) {
+#pragma unroll
+                for (int q = mt * SHARE; q < (mt + 1) * SHARE && q < P::LOADS; ++q) issue_one(q, isbase, itail);
+            }
+            __builtin_amdgcn_sched_barrier(0);
         }
+        if (do_issue) issue_done();
         if (NPH == 2 && c == nk0 - 1) on_phase_end();
     }
 }

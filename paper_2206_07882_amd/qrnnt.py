@@ -216,14 +216,16 @@ def lstm_step_into(L: Lstm, x_codes, h_prev, c_prev, h_next, c_next, N: int, x_r
 class CStepDesc(C.Structure):
     _fields_ = [("L", C.c_void_p), ("x_codes", C.c_void_p), ("x_row", C.c_void_p), ("n_x_rows", C.c_int32),
                 ("parent", C.c_void_p), ("h_prev", C.c_void_p), ("c_prev", C.c_void_p), ("n_slots", C.c_int32),
-                ("active", C.c_void_p), ("N", C.c_int32), ("h_next", C.c_void_p), ("c_next", C.c_void_p)]
+                ("active", C.c_void_p), ("N", C.c_int32), ("h_next", C.c_void_p), ("c_next", C.c_void_p),
+                ("gx", C.c_void_p)]
 
 
 class StepGroup:
     """Prepared argument block for qrnnt_lstm_step_group (built once, launched many times)."""
 
     def __init__(self, steps):
-        """steps: list of dicts with keys L, x_codes, h_prev, c_prev, h_next, c_next, N and optional x_row, parent, active."""
+        """steps: list of dicts with keys L, x_codes, h_prev, c_prev, h_next, c_next, N and optional x_row, parent,
+        active, gx (the input projection of the rows of x_codes, see input_projection)."""
         self._keep = []
         self.n = len(steps)
         self.arr = (CStepDesc * self.n)()
@@ -233,7 +235,7 @@ class StepGroup:
             self._keep.append((cl, d))
             self.arr[i] = CStepDesc(C.addressof(cl), p(d["x_codes"]), p(d.get("x_row")), d["x_codes"].shape[0],
                                     p(d.get("parent")), p(d["h_prev"]), p(d["c_prev"]), d["h_prev"].shape[0],
-                                    p(d.get("active")), d["N"], p(d["h_next"]), p(d["c_next"]))
+                                    p(d.get("active")), d["N"], p(d["h_next"]), p(d["c_next"]), p(d.get("gx")))
 
     def launch(self):
         _check(load().qrnnt_lstm_step_group(self.arr, C.c_int32(self.n), _stream()), "qrnnt_lstm_step_group")

@@ -176,6 +176,63 @@ def test_lstm_step_parity_beam_shape_with_gather_and_mask(gpu_lib):
     assert np.array_equal(hn[ina], hp[parent[ina]]) and np.array_equal(cn[ina], cp[parent[ina]])
 
 
+def _tiled_gate_col(H):
+    """Column of gx that holds (cell j, gate g): the TILED_GATES row order of the header."""
+    j = np.arange(H)
+    base = 64 * (j // 16) + 16 * (j % 4) + 4 * ((j % 16) // 4)
+    return base[None, :] + np.arange(4)[:, None]          # [gate, cell]
+
+
+@pytest.mark.parametrize("I,H,M", [(240, 640, 77), (1280, 640, 300), (768, 768, 46), (64, 16, 5)])
+def test_input_projection_exact(gpu_lib, I, H, M):
+    q = gpu_lib
+    L, G = _lstm_pair(q, 71 + I, I, H, 0.1)
+    x = synth.codes(72 + M, (M, I), -8, 7)
+    gx, acc = q.input_projection(G, dev(x), debug=True)
+    ref = oracle.lstm_step(L, x, np.zeros((M, H), np.int8), np.zeros((M, H), np.float32), debug=True)[2]["accx"]
+    assert np.array_equal(host(acc), ref)
+    col = _tiled_gate_col(H)
+    gxh = host(gx)
+    for g in range(4):
+        assert np.array_equal(gxh[:, col[g]], ref[:, g * H:(g + 1) * H]), f"gate {g}"
+
+
+@pytest.mark.parametrize("N,use_gx", [(16, False), (16, True), (48, True), (144, False), (144, True), (256, True),
+                                       (256, False)])
+def test_lstm_step_group_parity(gpu_lib, N, use_gx):
+    """Three independent steps in one launch (widths of the first layers of the
+    prediction network and of two LMs, scaled down), inputs picked by token id from
+    an embedding table; with use_gx the input part comes from the per-token table of
+    input projections.  Both must reproduce the oracle's step on the looked-up rows."""
+    q = gpu_lib
+    V = 46
+    shapes = [(128, 128), (64, 256), (64, 256)]
+    s_x = float(np.float32(1.25) / np.float32(7))
+    W = 16
+    parent = synth.parent_perm(80 + N, N // W, W)
+    tok = synth.token_ids(81 + N, (N,), V)
+    active = (np.random.default_rng(82 + N).random(N) < 0.7).astype(np.uint8)
+    steps, refs = [], []
+    for i, (I, H) in enumerate(shapes):
+        L, G = _lstm_pair(q, 90 + 10 * i, I, H, s_x)
+        emb = synth.codes(91 + i, (V, I), -7, 7)
+        hp = synth.codes(92 + i, (N, H), -7, 7)
+        cp = synth.normal(93 + i, (N, H), 0.7)
+        d = dict(L=G, x_codes=dev(emb), x_row=dev(tok), parent=dev(parent), active=dev(active), h_prev=dev(hp),
+                 c_prev=dev(cp), N=N, h_next=torch.empty((N, H), dtype=torch.int8, device=DEV),
+                 c_next=torch.empty((N, H), dtype=torch.float32, device=DEV))
+        if use_gx:
+            d["gx"] = q.input_projection(G, dev(emb))[0]
+        steps.append(d)
+        refs.append(oracle.lstm_step(L, emb[tok], hp[parent], cp[parent], active=active, debug=True))
+    q.StepGroup(steps).launch()
+    for d, (hn_r, cn_r, dbg_r) in zip(steps, refs):
+        assert_rel(host(d["c_next"]), cn_r, "c")
+        act = active.astype(bool)
+        assert_codes_close(host(d["h_next"])[act], hn_r[act], (dbg_r["h_real"] * 7.0)[act], "h codes")
+        assert np.array_equal(host(d["h_next"])[~act], hn_r[~act])
+
+
 def test_lstm_step_extreme_codes_no_overflow(gpu_lib):
     """All weights at code 7/-7 against all activations at -8: the largest |sum|."""
     q = gpu_lib
