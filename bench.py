@@ -10,10 +10,9 @@ All inputs are resident in HBM before the timed region.  The printed value is th
 real-time factor (processing time / audio duration, lower is better).
 
 Besides the end-to-end figure the JSON line carries
-  roofline      the dominant kernel (the fused LSTM step at 1024 hypotheses, as
-                launched in one decoding round: prediction net, 2 x LM layer 1,
-                2 x LM layer 2) against the dense int8 MFMA peak, timed with HIP
-                events on the launch stream;
+  roofline      the dominant kernel (the fused LSTM step at 1024 hypotheses, the
+                two grouped launches of one decoding round) against the dense int8
+                MFMA peak, timed with HIP events on the launch stream;
   extra         input-projection GEMM TOP/s, beam-16 (N=16) step GB/s, encoder
                 and decoder split;
   cpu_baseline  the CPU oracle timed on this host on a bounded slice.
@@ -32,17 +31,6 @@ HBM_PEAK_GBPS = 8000.0
 FRAME_SEC = 0.04
 
 
-def step_ops(I, H, N):
-    return 2.0 * 4 * H * (I + H) * N
-
-
-def step_bytes(I, H, N):
-    """Algorithmic bytes of one fused LSTM step: packed weights, two scale vectors
-    and the bias, input and hidden codes in (int8 containers), fp32 cell state in
-    and out, hidden codes out, parent indices."""
-    return 4 * H * (I + H) / 2 + 4 * H * 12 + N * (I + H) + 2 * N * H * 4 + N * H + 4 * N
-
-
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -53,6 +41,8 @@ def main():
     ap.add_argument("--B", type=int, default=64)
     ap.add_argument("--T", type=int, default=1000)
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle leg")
+    ap.add_argument("--no-graph", action="store_true",
+                    help="time the kernel legs with direct launches instead of HIP-graph replays (for counter runs)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (utterances would shard with no "
@@ -95,6 +85,28 @@ def main():
         torch.cuda.synchronize()
         return a.elapsed_time(b) / iters * 1e-3   # seconds per call
 
+    def timed_graph(fn, per_graph, replays=5):
+        """Seconds per call of fn with the host out of the loop: per_graph launches are captured
+        into one HIP graph (kernel launches only) and the replays are bracketed by HIP events on
+        the launch stream."""
+        if args.no_graph:
+            return timed(fn, per_graph * replays, warm=3)
+        fn()
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            for _ in range(per_graph):
+                fn()
+        g.replay()
+        torch.cuda.synchronize()
+        a, b = ev(), ev()
+        a.record()
+        for _ in range(replays):
+            g.replay()
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) / (replays * per_graph) * 1e-3
+
     # ---------------------------------------------------------------- end to end
     if args.leg in ("all", "e2e"):
         feats = torch.from_numpy(synth.features(4, T, B, m.feat_dim)).to(dev)
@@ -130,84 +142,99 @@ def main():
 
     # ---------------------------------------------------------------- kernel legs
     if args.leg in ("all", "kernels"):
-        N = 1024
-        rng = np.random.default_rng(7)
-
         def mk_state(n, H):
             return (torch.from_numpy(synth.codes(1, (n, H))).to(dev), torch.from_numpy(synth.normal(2, (n, H), 0.5)).to(dev))
 
-        # the five LSTM launches of one decoding round at N = 64 x 16 hypotheses
-        nets = [(G.pred, 0), (G.lm_src, 0), (G.lm_ext, 0), (G.lm_src, 1), (G.lm_ext, 1)]
-        tok = torch.from_numpy(synth.token_ids(3, (N,), m.V)).to(dev)
-        parent = torch.from_numpy(synth.parent_perm(4, N // W, W)).to(dev)
-        calls, ops, byt = [], 0.0, 0.0
-        for net, l in nets:
-            L = net.layers[l]
-            hp, cp = mk_state(N, L.H)
-            if l == 0:
-                x, xr = net.embed_codes, tok
-            else:
-                x, xr = torch.from_numpy(synth.codes(5, (N, L.I))).to(dev), None
-            hn = torch.empty((N, L.H), dtype=torch.int8, device=dev)
-            cn = torch.empty((N, L.H), dtype=torch.float32, device=dev)
-            calls.append((L, x, xr, hp, cp, hn, cn))
-            ops += step_ops(L.I, L.H, N)
-            byt += step_bytes(L.I, L.H, N)
+        def round_groups(N):
+            """The two LSTM launches of one decoding round at N hypotheses, as qrnnt_decode issues them:
+            first layers of the prediction network and of both LMs (input part looked up in the per-token
+            table of input projections), then the second layers of both LMs."""
+            tok = torch.from_numpy(synth.token_ids(3, (N,), m.V)).to(dev)
+            parent = torch.from_numpy(synth.parent_perm(4, max(N // W, 1), min(W, N))).to(dev)
+            groups = []
+            for layer_idx, nets in ((0, (G.pred, G.lm_src, G.lm_ext)), (1, (G.lm_src, G.lm_ext))):
+                steps, ops, byt = [], 0.0, 0.0
+                for net in nets:
+                    L = net.layers[layer_idx]
+                    hp, cp = mk_state(N, L.H)
+                    d = dict(L=L, h_prev=hp, c_prev=cp, parent=parent, N=N,
+                             h_next=torch.empty((N, L.H), dtype=torch.int8, device=dev),
+                             c_next=torch.empty((N, L.H), dtype=torch.float32, device=dev))
+                    if layer_idx == 0:
+                        d["x_codes"], d["x_row"] = net.embed_codes, tok
+                        d["gx"] = q.input_projection(L, net.embed_codes)[0]
+                        k_in = 0
+                        byt += m.V * 4 * L.H * 4   # the table of per-token int32 sums
+                    else:
+                        d["x_codes"] = torch.from_numpy(synth.codes(5, (N, L.I))).to(dev)
+                        k_in = L.I
+                        byt += 4 * L.H * L.I / 2 + N * L.I
+                    steps.append(d)
+                    ops += 2.0 * 4 * L.H * (k_in + L.H) * N
+                    # W_hh, scales and bias, hidden codes in/out, fp32 cell state in/out, parent indices
+                    byt += 4 * L.H * L.H / 2 + 4 * L.H * 12 + N * L.H * (1 + 1 + 4 + 4) + 4 * N
+                groups.append((q.StepGroup(steps), ops, byt))
+            return groups
 
-        def round_steps():
-            for (L, x, xr, hp, cp, hn, cn) in calls:
-                q.lstm_step_into(L, x, hp, cp, hn, cn, N, x_row=xr, parent=parent)
-
-        t_round = timed(round_steps, 50, warm=5)
-        per_launch = t_round / len(calls)
-        ach = ops / len(calls) / per_launch / 1e12
-        result["roofline"] = {"bound": "mfma", "kernel": "lstm_step_kernel (fused W4A4 LSTM step), N=1024 decode-round mix",
+        # ---- decoding-round launches at 64 utterances x beam 16 = 1024 hypotheses (matrix-core bound)
+        names = ("lstm_step_pipe_kernel<USE_GX=true>: pred L1 + 2 x LM L1, input part from the token table",
+                 "lstm_step_pipe_kernel<USE_GX=false>: 2 x LM L2")
+        launches, tot_ops, tot_t = [], 0.0, 0.0
+        for name, (grp, ops, byt) in zip(names, round_groups(B * W)):
+            t = timed_graph(grp.launch, 50)
+            launches.append({"kernel": name, "avg_launch_us": t * 1e6, "ops": ops, "TOPs": ops / t / 1e12,
+                             "frac_int8_mfma": ops / t / 1e12 / INT8_MFMA_PEAK_TOPS, "algorithmic_bytes": byt})
+            tot_ops += ops
+            tot_t += t
+        ach = tot_ops / tot_t / 1e12
+        result["roofline"] = {"bound": "mfma",
+                              "kernel": "lstm_step_pipe_kernel (fused W4A4 LSTM step), the two launches of one decoding "
+                                        f"round at N={B * W} hypotheses",
                               "achieved": ach, "peak": INT8_MFMA_PEAK_TOPS, "unit": "TOP/s",
                               "frac": ach / INT8_MFMA_PEAK_TOPS, "traffic": None,
-                              "avg_launch_us": per_launch * 1e6, "ops_per_launch": ops / len(calls),
-                              "algorithmic_bytes_per_launch": byt / len(calls),
-                              "achieved_GBps": byt / len(calls) / per_launch / 1e9}
+                              "avg_launch_us": tot_t / 2 * 1e6, "ops_per_launch": tot_ops / 2, "launches": launches}
+        tr = os.path.join(ROOT, "profiles", "lstm_step_pipe_kernel_decode_round_hbm_traffic.txt")
+        if os.path.exists(tr):   # HBM bytes per launch from the committed rocprofv3 --pmc summary (counters cannot run here)
+            import re
+            hit = re.search(r"^hbm_bytes_per_launch:\s*(\d+)", open(tr).read(), re.M)
+            result["roofline"]["traffic"] = int(hit.group(1)) if hit else None
 
-        # beam-16 regime (one utterance): weight streaming, reported against HBM
-        N16 = 16
-        parent16 = torch.from_numpy(synth.parent_perm(6, 1, W)).to(dev)
-        calls16, byt16, ops16 = [], 0.0, 0.0
-        for net, l in nets:
-            L = net.layers[l]
-            hp, cp = mk_state(N16, L.H)
-            if l == 0:
-                x, xr = net.embed_codes, tok[:N16].contiguous()
-            else:
-                x, xr = torch.from_numpy(synth.codes(5, (N16, L.I))).to(dev), None
-            hn = torch.empty((N16, L.H), dtype=torch.int8, device=dev)
-            cn = torch.empty((N16, L.H), dtype=torch.float32, device=dev)
-            calls16.append((L, x, xr, hp, cp, hn, cn))
-            byt16 += step_bytes(L.I, L.H, N16)
-            ops16 += step_ops(L.I, L.H, N16)
+        # ---- beam-16 regime (one utterance, N = 16): weight streaming, against HBM
+        byt16, t16 = 0.0, 0.0
+        for grp, ops, byt in round_groups(16):
+            t16 += timed_graph(grp.launch, 100)
+            byt16 += byt
+        extra["step_n16"] = {"kernel": "lstm_step_small_kernel, the two launches of one decoding round at N=16",
+                             "us_per_round": t16 * 1e6, "algorithmic_bytes_per_round": byt16,
+                             "GBps": byt16 / t16 / 1e9, "frac_hbm": byt16 / t16 / 1e9 / HBM_PEAK_GBPS,
+                             "note": "weights re-read every round; warm (the 18 MB of weights stay in L2 / MALL)"}
 
-        def round16():
-            for (L, x, xr, hp, cp, hn, cn) in calls16:
-                q.lstm_step_into(L, x, hp, cp, hn, cn, N16, x_row=xr, parent=parent16)
+        # ---- a plain device copy of known size: the HBM rate this box sustains, and the kernel that
+        # calibrates the FETCH_SIZE / WRITE_SIZE counters of the profiles
+        src = torch.empty(256 << 20, dtype=torch.uint8, device=dev).random_(0, 255)
+        dst = torch.empty_like(src)
+        tc = timed(lambda: dst.copy_(src), 10, warm=2)
+        extra["hbm_copy_reference"] = {"bytes_read": src.numel(), "bytes_written": src.numel(), "us": tc * 1e6,
+                                       "GBps": 2 * src.numel() / tc / 1e9}
+        del src, dst
 
-        t16 = timed(round16, 200, warm=10)
-        extra["step_n16_warm"] = {"us_per_launch": t16 / 5 * 1e6, "GBps": byt16 / t16 / 1e9,
-                                  "frac_hbm": byt16 / t16 / 1e9 / HBM_PEAK_GBPS, "bytes_per_round": byt16}
-
-        # input-projection GEMM, encoder layers 1-5 shape: [T*B = 16000, 1280] x [1280, 2560]
+        # ---- input-projection GEMM, encoder layers 2-6 shape: [T*B = 16000, 1280] x [1280, 2560]
         L = enc.layers[1][0]
         M = 16000
         xg = torch.from_numpy(synth.codes(8, (M, L.I))).to(dev)
         gx = torch.empty((M, 4 * L.H), dtype=torch.int32, device=dev)
-        tg = timed(lambda: q.input_projection(L, xg, gx), 20, warm=3)
+        tg = timed_graph(lambda: q.input_projection(L, xg, gx), 20)
         gops = 2.0 * M * L.I * 4 * L.H
-        extra["input_projection_gemm"] = {"M": M, "K": L.I, "N": 4 * L.H, "ms": tg * 1e3, "TOPs": gops / tg / 1e12,
-                                          "frac_int8_mfma": gops / tg / 1e12 / INT8_MFMA_PEAK_TOPS}
+        gbytes = M * L.I + 4 * L.H * L.I / 2 + M * 4 * L.H * 4
+        extra["input_projection_gemm"] = {"M": M, "K": L.I, "N": 4 * L.H, "us": tg * 1e6, "TOPs": gops / tg / 1e12,
+                                          "frac_int8_mfma": gops / tg / 1e12 / INT8_MFMA_PEAK_TOPS,
+                                          "algorithmic_bytes": gbytes, "GBps": gbytes / tg / 1e9}
 
     # ---------------------------------------------------------------- CPU oracle on a bounded slice
     if not args.no_cpu and args.leg in ("all",):
         import oracle
         from oracle import models as omodels
-        Bc, Tc = min(oracle.get_max_threads(), 16), 12
+        Bc, Tc = min(oracle.get_max_threads(), 16), 40
         mo = synth.make_model(4)
         t0 = time.perf_counter()
         layers, proj = omodels.encoder_from_float(mo)
