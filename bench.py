@@ -145,17 +145,22 @@ def main():
         def mk_state(n, H):
             return (torch.from_numpy(synth.codes(1, (n, H))).to(dev), torch.from_numpy(synth.normal(2, (n, H), 0.5)).to(dev))
 
-        def round_groups(N):
+        def clone_lstm(L):
+            cm = lambda mq: q.QMat(mq.packed.clone(), mq.row_scale.clone(), mq.rows, mq.cols, mq.layout)
+            return q.Lstm(cm(L.w_ih), cm(L.w_hh), L.bias.clone(), L.x_scale, L.h_scale, L.h_inv_scale)
+
+        def round_groups(N, fresh_weights=False):
             """The two LSTM launches of one decoding round at N hypotheses, as qrnnt_decode issues them:
             first layers of the prediction network and of both LMs (input part looked up in the per-token
-            table of input projections), then the second layers of both LMs."""
+            table of input projections), then the second layers of both LMs.  fresh_weights: private
+            copies of every weight tensor (for the cache-cold rotation)."""
             tok = torch.from_numpy(synth.token_ids(3, (N,), m.V)).to(dev)
             parent = torch.from_numpy(synth.parent_perm(4, max(N // W, 1), min(W, N))).to(dev)
             groups = []
             for layer_idx, nets in ((0, (G.pred, G.lm_src, G.lm_ext)), (1, (G.lm_src, G.lm_ext))):
                 steps, ops, byt = [], 0.0, 0.0
                 for net in nets:
-                    L = net.layers[layer_idx]
+                    L = clone_lstm(net.layers[layer_idx]) if fresh_weights else net.layers[layer_idx]
                     hp, cp = mk_state(N, L.H)
                     d = dict(L=L, h_prev=hp, c_prev=cp, parent=parent, N=N,
                              h_next=torch.empty((N, L.H), dtype=torch.int8, device=dev),
@@ -208,6 +213,32 @@ def main():
                              "us_per_round": t16 * 1e6, "algorithmic_bytes_per_round": byt16,
                              "GBps": byt16 / t16 / 1e9, "frac_hbm": byt16 / t16 / 1e9 / HBM_PEAK_GBPS,
                              "note": "weights re-read every round; warm (the 18 MB of weights stay in L2 / MALL)"}
+
+        # ---- the same at N = 16 with the weights coming from HBM: 28 private copies of all weight tensors
+        # (28 x 13.3 MB, more than the 256 MB MALL) visited in turn, so no launch finds its weights in a cache
+        copies = [round_groups(16, fresh_weights=True) for _ in range(28)]
+
+        def cold_round():
+            for grps in copies:
+                for grp, _, _ in grps:
+                    grp.launch()
+
+        tcold = timed_graph(cold_round, 2, replays=3) / len(copies)
+        extra["step_n16_cold"] = {"us_per_round": tcold * 1e6, "GBps": byt16 / tcold / 1e9,
+                                  "frac_hbm": byt16 / tcold / 1e9 / HBM_PEAK_GBPS,
+                                  "note": "28 rotating weight copies (372 MB > MALL): every launch streams its weights from HBM"}
+        del copies
+
+        # ---- sweep of the hypothesis count: where weight streaming hands over to the matrix cores
+        sweep = []
+        for Ns in (16, 32, 64, 128, 256, 1024, 4096):
+            ts, ops_s, byt_s = 0.0, 0.0, 0.0
+            for grp, ops, byt in round_groups(Ns):
+                ts += timed_graph(grp.launch, 50)
+                ops_s += ops
+                byt_s += byt
+            sweep.append({"N": Ns, "us_per_round": ts * 1e6, "TOPs": ops_s / ts / 1e12, "GBps": byt_s / ts / 1e9})
+        extra["step_round_sweep"] = sweep
 
         # ---- a plain device copy of known size: the HBM rate this machine sustains, and the kernel that
         # calibrates the FETCH_SIZE / WRITE_SIZE counters of the profiles

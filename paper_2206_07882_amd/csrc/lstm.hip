@@ -8,74 +8,39 @@
 
 namespace {
 
-// Bandwidth-bound variant (at most 16*NT hypotheses, e.g. one utterance at beam 16).
-// The packed weights are streamed exactly once: a workgroup owns one row tile
-// (4 cells); its 128-column chunks of W_ih and W_hh are dealt round-robin to the 4
-// waves, every wave issues all of its loads before its first MFMA (what keeps the
-// whole matrix in flight across the chip), and the partial sums meet in LDS.  Wave 0
-// then finishes the 4 cells, one (cell, hypothesis) per lane and column tile.
-// N = 16 is exactly one 16-column MFMA tile, so the matrix cores serve this regime
-// too: the kernel is bound by the weight stream, not by arithmetic.
-// Grid: x = row tiles, z = problem of a group.
+// Bandwidth-bound variant (few hypotheses, e.g. one utterance at beam 16).
+// The packed weights are streamed exactly once per 16 hypotheses: a workgroup owns one row
+// tile (4 cells) x one column tile (16 hypotheses); its 128-column chunks of W_ih and W_hh are
+// dealt round-robin to the 4 waves, every wave issues all of its loads before its first MFMA
+// (what keeps the whole matrix in flight across the chip), and the partial sums meet in LDS.
+// Wave 0 then finishes the 4 cells, one (cell, hypothesis) per lane.  N = 16 is exactly one
+// 16-column MFMA tile, so the matrix cores serve this regime too: the kernel is bound by the
+// weight stream and by its chain of dependent loads, which is kept to two links: the weight
+// loads (which depend on nothing) go first, then the row indices, then everything that
+// depends on them, including what the cell update will need.
+// Grid: x = row tiles, y = column tiles, z = problem of a group.
 constexpr int SMALL_BATCH = 4;   // chunks per wave per batch (K <= 2048 in one batch)
 
-template <int NT, bool USE_GX>
+template <bool USE_GX>
 __global__ __launch_bounds__(256) void lstm_step_small_kernel(const QrStepGroup g)
 {
-    __shared__ v4i part[3][2][NT][64];   // waves 1..3: [x|h][column tile][lane]
+    __shared__ v4i part[3][2][64];   // waves 1..3: [x|h][lane]
     const QrStepArgs &a = g.p[blockIdx.z];
     const int H = a.H, N = a.N;
     const int rt = blockIdx.x;
-    if (rt >= (H >> 2)) return;   // uniform
+    const int n0 = blockIdx.y * 16;
+    if (rt >= (H >> 2) || n0 >= N) return;   // uniform
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // scalar: MFMAs below sit under wave-uniform branches
     const int col = lane & 15, grp = lane >> 4;
     const v4i zero = {0, 0, 0, 0};
     const int m = (int)0xF0F0F0F0u;
-
-    int src_of[NT];
-    const int8_t *xrow[NT], *hrow[NT];
-    int nn[NT];
-#pragma unroll
-    for (int nt = 0; nt < NT; ++nt) {
-        const int n = nt * 16 + col;
-        nn[nt] = n < N ? n : N - 1;
-    }
-    if (a.parent) {
-#pragma unroll
-        for (int nt = 0; nt < NT; ++nt) src_of[nt] = a.parent[nn[nt]];
-    } else {
-#pragma unroll
-        for (int nt = 0; nt < NT; ++nt) src_of[nt] = nn[nt];
-    }
-    int xr[NT];   // row of the input codes, or of the precomputed input projection
-    if (a.x_row) {
-#pragma unroll
-        for (int nt = 0; nt < NT; ++nt) xr[nt] = a.x_row[nn[nt]];
-    } else {
-#pragma unroll
-        for (int nt = 0; nt < NT; ++nt) xr[nt] = nn[nt];
-    }
-#pragma unroll
-    for (int nt = 0; nt < NT; ++nt) {
-        int s = src_of[nt];
-        s = s < 0 ? 0 : (s >= a.n_slots ? a.n_slots - 1 : s);
-        src_of[nt] = s;
-        hrow[nt] = a.h_prev + (int64_t)s * a.ld_hp + grp * 16;
-        int r = xr[nt];
-        r = r < 0 ? 0 : (r >= a.n_x_rows ? a.n_x_rows - 1 : r);
-        xr[nt] = r;
-        xrow[nt] = USE_GX ? nullptr : a.x + (int64_t)r * a.ld_x + grp * 16;
-    }
-
     const int nkx = USE_GX ? 0 : a.nkc_x;
     const int total = nkx + a.nkc_h;
-    v4i accx[NT], acch[NT];
-#pragma unroll
-    for (int nt = 0; nt < NT; ++nt) { accx[nt] = zero; acch[nt] = zero; }
 
-    for (int v0 = wave; v0 < total; v0 += 4 * SMALL_BATCH) {
-        v4i pa[SMALL_BATCH], b0[SMALL_BATCH][NT], b1[SMALL_BATCH][NT];
+    // ---- first batch of weight fragments: independent of every index
+    v4i pa[SMALL_BATCH];
+    auto load_weights = [&](int v0) {
 #pragma unroll
         for (int it = 0; it < SMALL_BATCH; ++it) {
             const int v = v0 + 4 * it;
@@ -84,15 +49,55 @@ __global__ __launch_bounds__(256) void lstm_step_small_kernel(const QrStepGroup 
             const int kc = ok ? (isx ? v : v - nkx) : 0;
             const v4i *w = isx ? a.wih : a.whh;
             const int nkc = isx ? a.nkc_x : a.nkc_h;
-            const int K = isx ? a.I : H;
             pa[it] = ok ? w[((size_t)rt * nkc + kc) * 64 + lane] : zero;
-            const int k0 = kc * QRNNT_KCHUNK + grp * 16;
+        }
+    };
+    load_weights(wave);
+
+    // ---- indices, then everything that hangs on them
+    const int n = n0 + col;
+    const int nn = n < N ? n : N - 1;
+    int s = a.parent ? a.parent[nn] : nn;
+    int xr = a.x_row ? a.x_row[nn] : nn;
+    s = s < 0 ? 0 : (s >= a.n_slots ? a.n_slots - 1 : s);
+    xr = xr < 0 ? 0 : (xr >= a.n_x_rows ? a.n_x_rows - 1 : xr);
+    const int8_t *hrow = a.h_prev + (int64_t)s * a.ld_hp + grp * 16;
+    const int8_t *xrow = USE_GX ? nullptr : a.x + (int64_t)xr * a.ld_x + grp * 16;
+    // the cell update of wave 0: cell j of (row tile, grp) for hypothesis n
+    const int j = qr_gates_cell(rt, grp);
+    float sx[4], sh[4], bb[4], cp = 0.0f;
+    int act = 1, hp_code = 0;
+    v4i gxv = zero;
+    if (wave == 0) {
 #pragma unroll
-            for (int nt = 0; nt < NT; ++nt) {
-                const int8_t *row = isx ? xrow[nt] : hrow[nt];
-                b0[it][nt] = (ok && k0 < K) ? *(const v4i *)(row + kc * QRNNT_KCHUNK) : zero;
-                b1[it][nt] = (ok && k0 + 64 < K) ? *(const v4i *)(row + kc * QRNNT_KCHUNK + 64) : zero;
-            }
+        for (int gt = 0; gt < 4; ++gt) {
+            sx[gt] = a.x_scale * a.s_wih[gt * H + j];
+            sh[gt] = a.h_scale * a.s_whh[gt * H + j];
+            bb[gt] = a.bias[gt * H + j];
+        }
+        cp = a.c_prev[(int64_t)s * H + j];
+        if (USE_GX) gxv = *(const v4i *)(a.gx + (int64_t)xr * a.ld_gx + rt * 16 + 4 * grp);
+        if (a.active) {
+            act = a.active[nn];
+            hp_code = a.h_prev[(int64_t)s * a.ld_hp + j];
+        }
+    }
+
+    v4i accx = zero, acch = zero;
+    for (int v0 = wave; v0 < total; v0 += 4 * SMALL_BATCH) {
+        if (v0 != wave) load_weights(v0);
+        v4i b0[SMALL_BATCH], b1[SMALL_BATCH];
+#pragma unroll
+        for (int it = 0; it < SMALL_BATCH; ++it) {
+            const int v = v0 + 4 * it;
+            const bool ok = v < total;
+            const bool isx = ok && v < nkx;
+            const int kc = ok ? (isx ? v : v - nkx) : 0;
+            const int K = isx ? a.I : H;
+            const int k0 = kc * QRNNT_KCHUNK + grp * 16;
+            const int8_t *row = isx ? xrow : hrow;
+            b0[it] = (ok && k0 < K) ? *(const v4i *)(row + kc * QRNNT_KCHUNK) : zero;
+            b1[it] = (ok && k0 + 64 < K) ? *(const v4i *)(row + kc * QRNNT_KCHUNK + 64) : zero;
         }
 #pragma unroll
         for (int it = 0; it < SMALL_BATCH; ++it) {
@@ -100,90 +105,50 @@ __global__ __launch_bounds__(256) void lstm_step_small_kernel(const QrStepGroup 
             if (v < total) {   // uniform per wave
                 const v4i lo = (pa[it] << 4) & m, hi = pa[it] & m;
                 if (v < nkx) {
-#pragma unroll
-                    for (int nt = 0; nt < NT; ++nt) {
-                        accx[nt] = qr_mfma(lo, b0[it][nt], accx[nt]);
-                        accx[nt] = qr_mfma(hi, b1[it][nt], accx[nt]);
-                    }
+                    accx = qr_mfma(lo, b0[it], accx);
+                    accx = qr_mfma(hi, b1[it], accx);
                 } else {
-#pragma unroll
-                    for (int nt = 0; nt < NT; ++nt) {
-                        acch[nt] = qr_mfma(lo, b0[it][nt], acch[nt]);
-                        acch[nt] = qr_mfma(hi, b1[it][nt], acch[nt]);
-                    }
+                    acch = qr_mfma(lo, b0[it], acch);
+                    acch = qr_mfma(hi, b1[it], acch);
                 }
             }
         }
     }
     if (wave != 0) {
-#pragma unroll
-        for (int nt = 0; nt < NT; ++nt) {
-            part[wave - 1][0][nt][lane] = accx[nt];
-            part[wave - 1][1][nt][lane] = acch[nt];
-        }
+        part[wave - 1][0][lane] = accx;
+        part[wave - 1][1][lane] = acch;
     }
     __syncthreads();
     if (wave != 0) return;
 
-    // ---- wave 0: the cell of (row tile, grp) for hypotheses col (+16 per column tile)
-    const int j = qr_gates_cell(rt, grp);
-    float sx[4], sh[4], bb[4];
+    v4i ax = accx, ah = acch;
 #pragma unroll
-    for (int gt = 0; gt < 4; ++gt) {
-        sx[gt] = a.x_scale * a.s_wih[gt * H + j];
-        sh[gt] = a.h_scale * a.s_whh[gt * H + j];
-        bb[gt] = a.bias[gt * H + j];
-    }
-    float cp[NT];
-    int act[NT], hp_code[NT];
-    v4i gxv[NT];
+    for (int wv = 0; wv < 3; ++wv) { ax += part[wv][0][lane]; ah += part[wv][1][lane]; }
+    ax = USE_GX ? gxv : (ax >> 4);
+    ah = ah >> 4;
+    float p[4];
 #pragma unroll
-    for (int nt = 0; nt < NT; ++nt) {
-        cp[nt] = a.c_prev[(int64_t)src_of[nt] * H + j];
-        if (USE_GX) gxv[nt] = *(const v4i *)(a.gx + (int64_t)xr[nt] * a.ld_gx + rt * 16 + 4 * grp);
-    }
-    if (a.active) {
+    for (int gt = 0; gt < 4; ++gt) p[gt] = sx[gt] * (float)ax[gt] + (sh[gt] * (float)ah[gt] + bb[gt]);
+    const float gi = qr_sigmoid(p[0]), gf = qr_sigmoid(p[1]), gg = qr_tanh(p[2]), go = qr_sigmoid(p[3]);
+    float cn = gf * cp + gi * gg;
+    const float h = go * qr_tanh(cn);
+    int code = qr_quant4(h, a.h_inv);
+    const bool on = act != 0;
+    cn = on ? cn : cp;
+    code = on ? code : hp_code;
+    if (n < N) {
+        a.c_next[(int64_t)n * H + j] = cn;
+        a.h_next[(int64_t)n * a.ld_hn + j] = (int8_t)code;
+        if (a.h_copy) a.h_copy[(int64_t)n * H + j] = (int8_t)code;
+        if (a.dbg_accx)
 #pragma unroll
-        for (int nt = 0; nt < NT; ++nt) {
-            act[nt] = a.active[nn[nt]];
-            hp_code[nt] = a.h_prev[(int64_t)src_of[nt] * a.ld_hp + j];
-        }
-    } else {
+            for (int gt = 0; gt < 4; ++gt) a.dbg_accx[(int64_t)n * 4 * H + gt * H + j] = ax[gt];
+        if (a.dbg_acch)
 #pragma unroll
-        for (int nt = 0; nt < NT; ++nt) { act[nt] = 1; hp_code[nt] = 0; }
-    }
-#pragma unroll
-    for (int nt = 0; nt < NT; ++nt) {
-        const int n = nt * 16 + col;
-        v4i ax = accx[nt], ah = acch[nt];
-#pragma unroll
-        for (int wv = 0; wv < 3; ++wv) { ax += part[wv][0][nt][lane]; ah += part[wv][1][nt][lane]; }
-        ax = USE_GX ? gxv[nt] : (ax >> 4);
-        ah = ah >> 4;
-        float p[4];
-#pragma unroll
-        for (int gt = 0; gt < 4; ++gt) p[gt] = sx[gt] * (float)ax[gt] + (sh[gt] * (float)ah[gt] + bb[gt]);
-        const float gi = qr_sigmoid(p[0]), gf = qr_sigmoid(p[1]), gg = qr_tanh(p[2]), go = qr_sigmoid(p[3]);
-        float cn = gf * cp[nt] + gi * gg;
-        const float h = go * qr_tanh(cn);
-        int code = qr_quant4(h, a.h_inv);
-        const bool on = act[nt] != 0;
-        cn = on ? cn : cp[nt];
-        code = on ? code : hp_code[nt];
-        if (n < N) {
-            a.c_next[(int64_t)n * H + j] = cn;
-            a.h_next[(int64_t)n * a.ld_hn + j] = (int8_t)code;
-            if (a.h_copy) a.h_copy[(int64_t)n * H + j] = (int8_t)code;
-            if (a.dbg_accx)
-#pragma unroll
-                for (int gt = 0; gt < 4; ++gt) a.dbg_accx[(int64_t)n * 4 * H + gt * H + j] = ax[gt];
-            if (a.dbg_acch)
-#pragma unroll
-                for (int gt = 0; gt < 4; ++gt) a.dbg_acch[(int64_t)n * 4 * H + gt * H + j] = ah[gt];
-            if (a.dbg_gates && on) {
-                float *dg = a.dbg_gates + (int64_t)n * 4 * H + j;
-                dg[0] = gi; dg[H] = gf; dg[2 * H] = gg; dg[3 * H] = go;
-            }
+            for (int gt = 0; gt < 4; ++gt) a.dbg_acch[(int64_t)n * 4 * H + gt * H + j] = ah[gt];
+        if (a.dbg_gates && on) {
+            float *dg = a.dbg_gates + (int64_t)n * 4 * H + j;
+            dg[0] = gi; dg[H] = gf; dg[2 * H] = gg; dg[3 * H] = go;
         }
     }
 }
@@ -196,10 +161,7 @@ void launch_small(const QrStepGroup &g, hipStream_t st)
         max_n = g.p[i].N > max_n ? g.p[i].N : max_n;
         max_rt = (g.p[i].H >> 2) > max_rt ? (g.p[i].H >> 2) : max_rt;
     }
-    dim3 grid(max_rt, 1, g.n);
-    if (max_n <= 16) lstm_step_small_kernel<1, USE_GX><<<grid, 256, 0, st>>>(g);
-    else if (max_n <= 32) lstm_step_small_kernel<2, USE_GX><<<grid, 256, 0, st>>>(g);
-    else lstm_step_small_kernel<4, USE_GX><<<grid, 256, 0, st>>>(g);
+    lstm_step_small_kernel<USE_GX><<<dim3(max_rt, (max_n + 15) / 16, g.n), 256, 0, st>>>(g);
 }
 
 // Compute-bound variant (many hypotheses): multi-stage LDS ring, see mma_pipe.h.
@@ -209,8 +171,12 @@ void launch_small(const QrStepGroup &g, hipStream_t st)
 // and the cell update is branch-free, so a block exposes one memory latency per
 // batch instead of one per element.  DBG adds the int32 / gate outputs.
 // FAST: every K is a multiple of 128, every tile is full (no bounds checks needed).
+// With a precomputed input projection (USE_GX) there is one contraction phase and no fp32 copy
+// of the input part to keep alive across it: that variant is held to 168 registers so that three
+// workgroups share a CU (with a two-stage ring), which is what lets the 704 workgroups of the
+// decoder's first-layer launch run in one round instead of two.
 template <int MT, int NT, int S, bool USE_GX, bool DBG, bool FAST>
-__global__ __launch_bounds__(256, 2) void lstm_step_pipe_kernel(const QrStepGroup g)
+__global__ __launch_bounds__(256, (USE_GX && !DBG) ? 3 : 2) void lstm_step_pipe_kernel(const QrStepGroup g)
 {
     using P = QrPipe<MT, NT, S>;
     extern __shared__ __attribute__((aligned(1024))) char lds[];
@@ -302,36 +268,7 @@ __global__ __launch_bounds__(256, 2) void lstm_step_pipe_kernel(const QrStepGrou
         for (int q = 0; q < MQ; ++q) {
             v4f sx[4];
 #pragma unroll
-            for (int gt = 0; gt < 4; ++gt) sx[gt] = load4(a.s_wih + gt * H + jb[q]) * a.x_scale;
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-#pragma unroll
-                for (int nt = 0; nt < NT; ++nt) {
-                    const int mt = 4 * q + i;
-                    const v4i ax = acc[mt][nt] >> 4;
-                    if (DBG && a.dbg_accx && jb[q] == qr_gates_cell(rt0 + 4 * q, grp) && n_of[nt] < N)
-#pragma unroll
-                        for (int gt = 0; gt < 4; ++gt) a.dbg_accx[(int64_t)n_of[nt] * 4 * H + gt * H + jb[q] + i] = ax[gt];
-#pragma unroll
-                    for (int gt = 0; gt < 4; ++gt) pre[mt][nt][gt] = sx[gt][i] * (float)ax[gt];
-                    acc[mt][nt] = zero;
-                }
-        }
-    };
-    if (USE_GX) {
-        v4i ax[MT][NT];
-#pragma unroll
-        for (int mt = 0; mt < MT; ++mt) {
-            int tr = (rt0 + mt) * 16 + 4 * grp;   // gx columns are in tiled-row order
-            tr = tr < 4 * H ? tr : 4 * H - 4;
-#pragma unroll
-            for (int nt = 0; nt < NT; ++nt) ax[mt][nt] = *(const v4i *)(a.gx + (int64_t)gx_of[nt] * a.ld_gx + tr);
-        }
-#pragma unroll
-        for (int q = 0; q < MQ; ++q) {
-            v4f sx[4];
-#pragma unroll
-            for (int gt = 0; gt < 4; ++gt) sx[gt] = load4(a.s_wih + gt * H + jb[q]) * a.x_scale;
+            for (int gt = 0; gt < 4; ++gt) sx[gt] = load4(a.s_wih + gt * H + jb[q]) * a.x_scale * 0.0625f;   // accumulators hold 16 x sum
 #pragma unroll
             for (int i = 0; i < 4; ++i)
 #pragma unroll
@@ -340,24 +277,25 @@ __global__ __launch_bounds__(256, 2) void lstm_step_pipe_kernel(const QrStepGrou
                     if (DBG && a.dbg_accx && jb[q] == qr_gates_cell(rt0 + 4 * q, grp) && n_of[nt] < N)
 #pragma unroll
                         for (int gt = 0; gt < 4; ++gt)
-                            a.dbg_accx[(int64_t)n_of[nt] * 4 * H + gt * H + jb[q] + i] = ax[mt][nt][gt];
+                            a.dbg_accx[(int64_t)n_of[nt] * 4 * H + gt * H + jb[q] + i] = acc[mt][nt][gt] >> 4;
 #pragma unroll
-                    for (int gt = 0; gt < 4; ++gt) pre[mt][nt][gt] = sx[gt][i] * (float)ax[mt][nt][gt];
+                    for (int gt = 0; gt < 4; ++gt) pre[mt][nt][gt] = sx[gt][i] * (float)acc[mt][nt][gt];
+                    acc[mt][nt] = zero;
                 }
         }
-    }
-
+    };
     qr_pipe_mma<MT, NT, S, NPH, !FAST>(ph, n_row_tiles, block_rt0, lds, acc, x_done);
 
     // ---- fused cell: batched 128-bit loads, then branch-free arithmetic, then 128-bit / 32-bit stores
-    v4f cp[MQ][NT], sh[MQ][4], bb[MQ][4];
+    v4f cp[MQ][NT], sh[MQ][4], bb[MQ][4], sxg[MQ][4];
     int act[NT], hp_code[MQ][NT];
 #pragma unroll
     for (int q = 0; q < MQ; ++q) {
 #pragma unroll
         for (int gt = 0; gt < 4; ++gt) {
-            sh[q][gt] = load4(a.s_whh + gt * H + jb[q]) * a.h_scale;
+            sh[q][gt] = load4(a.s_whh + gt * H + jb[q]) * a.h_scale * 0.0625f;   // accumulators hold 16 x sum
             bb[q][gt] = load4(a.bias + gt * H + jb[q]);
+            if (USE_GX) sxg[q][gt] = load4(a.s_wih + gt * H + jb[q]) * a.x_scale;
         }
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) cp[q][nt] = load4(a.c_prev + (int64_t)src_of[nt] * H + jb[q]);
@@ -377,6 +315,17 @@ __global__ __launch_bounds__(256, 2) void lstm_step_pipe_kernel(const QrStepGrou
             for (int q = 0; q < MQ; ++q) hp_code[q][nt] = 0;
         }
     }
+    // precomputed input part: the four gate quartets of (q, nt), fetched one column tile ahead of their use
+    auto load_gx = [&](int q, int nt, v4i (&dst)[4]) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            int tr = (rt0 + 4 * q + i) * 16 + 4 * grp;   // gx columns are in tiled-row order
+            tr = tr < 4 * H ? tr : 4 * H - 4;
+            dst[i] = *(const v4i *)(a.gx + (int64_t)gx_of[nt] * a.ld_gx + tr);
+        }
+    };
+    v4i gxv[2][4];
+    if (USE_GX) load_gx(0, 0, gxv[0]);
 #pragma unroll
     for (int q = 0; q < MQ; ++q) {
         const bool jv = FAST || qr_gates_cell(rt0 + 4 * q, grp) < H;
@@ -384,24 +333,32 @@ __global__ __launch_bounds__(256, 2) void lstm_step_pipe_kernel(const QrStepGrou
         for (int nt = 0; nt < NT; ++nt) {
             const int n = n_of[nt];
             const bool on = act[nt] != 0;
+            const int cur = (q * NT + nt) & 1;
+            if (USE_GX && q * NT + nt + 1 < MQ * NT) load_gx((q * NT + nt + 1) / NT, (q * NT + nt + 1) % NT, gxv[cur ^ 1]);
             v4f cn;
             unsigned codes = 0;
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 const int mt = 4 * q + i;
-                const v4i ah = acc[mt][nt] >> 4;
                 float p[4];
 #pragma unroll
-                for (int gt = 0; gt < 4; ++gt) p[gt] = pre[mt][nt][gt] + (sh[q][gt][i] * (float)ah[gt] + bb[q][gt][i]);
+                for (int gt = 0; gt < 4; ++gt) {
+                    const float xin = USE_GX ? sxg[q][gt][i] * (float)gxv[cur][i][gt] : pre[mt][nt][gt];
+                    p[gt] = xin + (sh[q][gt][i] * (float)acc[mt][nt][gt] + bb[q][gt][i]);
+                }
                 const float gi = qr_sigmoid(p[0]), gf = qr_sigmoid(p[1]), gg = qr_tanh(p[2]), go = qr_sigmoid(p[3]);
                 const float c1 = gf * cp[q][nt][i] + gi * gg;
                 const float h = go * qr_tanh(c1);
                 cn[i] = on ? c1 : cp[q][nt][i];
                 codes |= (unsigned)(qr_quant4(h, a.h_inv) & 0xFF) << (8 * i);
                 if (DBG && jv && n < N) {
+                    if (USE_GX && a.dbg_accx)
+#pragma unroll
+                        for (int gt = 0; gt < 4; ++gt) a.dbg_accx[(int64_t)n * 4 * H + gt * H + jb[q] + i] = gxv[cur][i][gt];
                     if (a.dbg_acch)
 #pragma unroll
-                        for (int gt = 0; gt < 4; ++gt) a.dbg_acch[(int64_t)n * 4 * H + gt * H + jb[q] + i] = ah[gt];
+                        for (int gt = 0; gt < 4; ++gt)
+                            a.dbg_acch[(int64_t)n * 4 * H + gt * H + jb[q] + i] = acc[mt][nt][gt] >> 4;
                     if (a.dbg_gates && on) {
                         float *dg = a.dbg_gates + (int64_t)n * 4 * H + jb[q] + i;
                         dg[0] = gi; dg[H] = gf; dg[2 * H] = gg; dg[3 * H] = go;
@@ -453,14 +410,20 @@ void launch_pipe(const QrStepGroup &g, hipStream_t st)
     else launch_pipe_f<MT, NT, S, USE_GX, false, false>(g, st);
 }
 
+// Hypothesis counts up to this go to the weight-streaming kernel.
+static int small_n_max()
+{
+    return 64;   // measured: 64 hypotheses take 21 us per decoding round here, 27 us in the tiled kernel
+}
+
 template <bool USE_GX>
 void launch_step_t(const QrStepArgs &a, hipStream_t st)
 {
     QrStepGroup g;
     g.p[0] = a;
     g.n = 1;
-    if (a.N <= 64) launch_small<USE_GX>(g, st);
-    else launch_pipe<4, 4, 3, USE_GX>(g, st);
+    if (a.N <= small_n_max()) launch_small<USE_GX>(g, st);
+    else launch_pipe<4, 4, USE_GX ? 2 : 3, USE_GX>(g, st);
 }
 
 // Input projection of all frames: gx[m, 4j+g] = sum_k Wih[g*H+j, k] * x[m, k].
@@ -474,7 +437,7 @@ void launch_step_t(const QrStepArgs &a, hipStream_t st)
 // by one L2 only (measured before: 181 MB fetched for 22 MB of operands), while the small
 // weight matrix lives in every L2.
 template <int MT, int NT, int S, bool TAIL>
-__global__ __launch_bounds__(256, 1) void gx_gemm_pipe_kernel(const v4i *__restrict__ wih, int nkc, int n_row_tiles,
+__global__ __launch_bounds__(256, S == 2 ? 3 : 2) void gx_gemm_pipe_kernel(const v4i *__restrict__ wih, int nkc, int n_row_tiles,
                                                               const int8_t *__restrict__ x, int64_t ld_x, int M, int K,
                                                               int32_t *__restrict__ gx, int H,
                                                               int32_t *__restrict__ dbg_accx)
@@ -601,10 +564,10 @@ static void launch_group_t(const QrStepGroup &g, hipStream_t st)
     // one launch when every member is in the compute-bound regime, else member by member
     bool all_big = true, all_small = true;
     for (int i = 0; i < g.n; ++i) {
-        all_big = all_big && g.p[i].N > 64;
-        all_small = all_small && g.p[i].N <= 64;
+        all_big = all_big && g.p[i].N > small_n_max();
+        all_small = all_small && g.p[i].N <= small_n_max();
     }
-    if (all_big) launch_pipe<4, 4, 3, USE_GX>(g, st);
+    if (all_big) launch_pipe<4, 4, USE_GX ? 2 : 3, USE_GX>(g, st);
     else if (all_small) launch_small<USE_GX>(g, st);
     else
         for (int i = 0; i < g.n; ++i) launch_step_t<USE_GX>(g.p[i], st);

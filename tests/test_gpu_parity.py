@@ -233,6 +233,46 @@ def test_lstm_step_group_parity(gpu_lib, N, use_gx):
         assert np.array_equal(host(d["h_next"])[~act], hn_r[~act])
 
 
+def test_lstm_step_group_full_size_sampled(gpu_lib):
+    """The two grouped launches of one decoding round exactly as the benchmark times them (64 utterances x
+    beam 16 = 1024 hypotheses; prediction network 768 and both LMs' first layers 1024 fed from the per-token
+    table, then both LMs' second layers 1024 <- 1024), checked on a sample of hypotheses the oracle computes
+    one by one."""
+    q = gpu_lib
+    V, W, B = 46, 16, 64
+    N = B * W
+    s_x = float(np.float32(1.25) / np.float32(7))
+    parent = synth.parent_perm(180, B, W)
+    tok = synth.token_ids(181, (N,), V)
+    active = (np.random.default_rng(182).random(N) < 0.9).astype(np.uint8)
+    rows = np.random.default_rng(183).choice(N, 48, replace=False)
+    act = active[rows].astype(bool)
+    for shapes, table in (([(768, 768), (256, 1024), (256, 1024)], True), ([(1024, 1024), (1024, 1024)], False)):
+        steps, refs = [], []
+        for i, (I, H) in enumerate(shapes):
+            L, G = _lstm_pair(q, 190 + 10 * i + I, I, H, s_x if table else S_H)
+            hp = synth.codes(192 + i, (N, H), -7, 7)
+            cp = synth.normal(193 + i, (N, H), 0.7)
+            d = dict(L=G, parent=dev(parent), active=dev(active), h_prev=dev(hp), c_prev=dev(cp), N=N,
+                     h_next=torch.empty((N, H), dtype=torch.int8, device=DEV),
+                     c_next=torch.empty((N, H), dtype=torch.float32, device=DEV))
+            if table:
+                emb = synth.codes(191 + i, (V, I), -7, 7)
+                d.update(x_codes=dev(emb), x_row=dev(tok), gx=q.input_projection(G, dev(emb))[0])
+                x_rows = emb[tok[rows]]
+            else:
+                x = synth.codes(194 + i, (N, I), -7, 7)
+                d.update(x_codes=dev(x))
+                x_rows = x[rows]
+            steps.append(d)
+            refs.append(oracle.lstm_step(L, x_rows, hp[parent[rows]], cp[parent[rows]], active=active[rows], debug=True))
+        q.StepGroup(steps).launch()
+        for d, (hn_r, cn_r, dbg_r) in zip(steps, refs):
+            assert_rel(host(d["c_next"])[rows], cn_r, "c")
+            assert_codes_close(host(d["h_next"])[rows][act], hn_r[act], (dbg_r["h_real"] * 7.0)[act], "h codes")
+            assert np.array_equal(host(d["h_next"])[rows][~act], hn_r[~act])
+
+
 def test_lstm_step_extreme_codes_no_overflow(gpu_lib):
     """All weights at code 7/-7 against all activations at -8: the largest |sum|."""
     q = gpu_lib
