@@ -261,6 +261,10 @@ __global__ __launch_bounds__(256, (USE_GX && !DBG) ? 3 : 2) void lstm_step_pipe_
         jb[q] = j < H ? j : H - 4;
     }
     auto load4 = [](const float *p) { return *(const v4f *)p; };
+    // The pre-activations are formed already multiplied by the constant their activation feeds to
+    // exp2 (-log2 e for the sigmoids, -2 log2 e for tanh): folded into the per-row scales and the
+    // bias, it costs nothing per element.
+    auto gate_k = [](int gt) { return gt == 2 ? -2.885390081777927f : -1.4426950408889634f; };
 
     // input part -> fp32 (s_x * s_wih[r] * accx); the accumulators restart for the recurrent part
     auto x_done = [&]() {
@@ -268,7 +272,8 @@ __global__ __launch_bounds__(256, (USE_GX && !DBG) ? 3 : 2) void lstm_step_pipe_
         for (int q = 0; q < MQ; ++q) {
             v4f sx[4];
 #pragma unroll
-            for (int gt = 0; gt < 4; ++gt) sx[gt] = load4(a.s_wih + gt * H + jb[q]) * a.x_scale * 0.0625f;   // accumulators hold 16 x sum
+            for (int gt = 0; gt < 4; ++gt)   // accumulators hold 16 x sum; gate_k: see the epilogue
+                sx[gt] = load4(a.s_wih + gt * H + jb[q]) * a.x_scale * (0.0625f * gate_k(gt));
 #pragma unroll
             for (int i = 0; i < 4; ++i)
 #pragma unroll
@@ -293,9 +298,9 @@ __global__ __launch_bounds__(256, (USE_GX && !DBG) ? 3 : 2) void lstm_step_pipe_
     for (int q = 0; q < MQ; ++q) {
 #pragma unroll
         for (int gt = 0; gt < 4; ++gt) {
-            sh[q][gt] = load4(a.s_whh + gt * H + jb[q]) * a.h_scale * 0.0625f;   // accumulators hold 16 x sum
-            bb[q][gt] = load4(a.bias + gt * H + jb[q]);
-            if (USE_GX) sxg[q][gt] = load4(a.s_wih + gt * H + jb[q]) * a.x_scale;
+            sh[q][gt] = load4(a.s_whh + gt * H + jb[q]) * a.h_scale * (0.0625f * gate_k(gt));   // accumulators hold 16 x sum
+            bb[q][gt] = load4(a.bias + gt * H + jb[q]) * gate_k(gt);
+            if (USE_GX) sxg[q][gt] = load4(a.s_wih + gt * H + jb[q]) * a.x_scale * gate_k(gt);
         }
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) cp[q][nt] = load4(a.c_prev + (int64_t)src_of[nt] * H + jb[q]);
@@ -346,7 +351,8 @@ __global__ __launch_bounds__(256, (USE_GX && !DBG) ? 3 : 2) void lstm_step_pipe_
                     const float xin = USE_GX ? sxg[q][gt][i] * (float)gxv[cur][i][gt] : pre[mt][nt][gt];
                     p[gt] = xin + (sh[q][gt][i] * (float)acc[mt][nt][gt] + bb[q][gt][i]);
                 }
-                const float gi = qr_sigmoid(p[0]), gf = qr_sigmoid(p[1]), gg = qr_tanh(p[2]), go = qr_sigmoid(p[3]);
+                const float gi = qr_sigmoid_scaled(p[0]), gf = qr_sigmoid_scaled(p[1]);
+                const float gg = 2.0f * qr_sigmoid_scaled(p[2]) - 1.0f, go = qr_sigmoid_scaled(p[3]);
                 const float c1 = gf * cp[q][nt][i] + gi * gg;
                 const float h = go * qr_tanh(c1);
                 cn[i] = on ? c1 : cp[q][nt][i];

@@ -71,7 +71,12 @@ __device__ __forceinline__ float qr_sigmoid(float v)
 {
     return __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.44269504088896f * v));
 }
-__device__ __forceinline__ float qr_tanh(float v) { return 2.0f * qr_sigmoid(2.0f * v) - 1.0f; }
+__device__ __forceinline__ float qr_tanh(float v)
+{
+    return 2.0f * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-2.885390081777927f * v)) - 1.0f;
+}
+// sigmoid(v) given u = -log2(e) * v (the constant folded into whatever produced u)
+__device__ __forceinline__ float qr_sigmoid_scaled(float u) { return __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(u)); }
 
 // Symmetric 4-bit quantizer: clamp(rne(x * inv_step)), product in fp32.
 __device__ __forceinline__ int qr_quant4(float x, float inv_step)

@@ -359,6 +359,53 @@ def test_bilstm_layer_parity(gpu_lib, T, B, I, H):
         assert (free == hg).mean() >= (1.0 if T * B * H < 5000 else 0.999)
 
 
+@pytest.mark.parametrize("reverse", [False, True])
+def test_lstm_layer_full_size_sampled_steps(gpu_lib, reverse):
+    """An encoder layer at its measured size (500 frames x 32 utterances, 1280 -> 640: the launch
+    configuration of the persistent recurrence and of the 16000-row input-projection GEMM), checked
+    on sampled time steps: one oracle step from the GPU's own state of the step before, plus sampled
+    rows of the GEMM, plus the bounded-wait error flag."""
+    q = gpu_lib
+    T, B, I, H = 500, 32, 1280, 640
+    L, G = _lstm_pair(q, 371, I, H, S_H)
+    x = synth.codes(372, (T, B, I), -7, 7)
+    need = q.lstm_layer_workspace(G, T, B)
+    ws = torch.empty(need, dtype=torch.uint8, device=DEV)
+    out = q.lstm_layer(G, dev(x), reverse=reverse, want_last=True, debug=True, workspace=ws)
+    assert q.layer_error_flag(ws, need) == 0
+    hg, cg = host(out["h_out"]), host(out["c_all"])
+    rows = np.random.default_rng(373).choice(T * B, 64, replace=False)
+    assert np.array_equal(host(out["accx"]).reshape(T * B, 4 * H)[rows], oracle.matmul_i32(L.w_ih, x.reshape(T * B, I)[rows]))
+    steps = sorted(np.random.default_rng(374).choice(np.arange(1, T - 1), 6, replace=False).tolist()) + [0, T - 1]
+    for t in steps:
+        tp = t + 1 if reverse else t - 1            # the step computed before t
+        first = (t == T - 1) if reverse else (t == 0)
+        hp = np.zeros((B, H), np.int8) if first else hg[tp]
+        cp = np.zeros((B, H), np.float32) if first else cg[tp]
+        hr, cr, dbg = oracle.lstm_step(L, x[t], hp, cp, debug=True)
+        assert_rel(cg[t], cr, f"c t={t}")
+        assert_codes_close(hg[t], hr, dbg["h_real"] * 7.0, f"h t={t}")
+    last = 0 if reverse else T - 1
+    assert np.array_equal(host(out["h_last"]), hg[last]) and np.array_equal(host(out["c_last"]), cg[last])
+
+
+def test_bilstm_layer_full_size_equals_single_directions(gpu_lib):
+    """Both directions in one launch give exactly the codes of the two single-direction calls
+    (same kernels, different grouping), at the measured encoder size."""
+    q = gpu_lib
+    T, B, I, H = 500, 32, 1280, 640
+    _, Gf = _lstm_pair(q, 381, I, H, S_H)
+    _, Gb = _lstm_pair(q, 391, I, H, S_H)
+    x = dev(synth.codes(382, (T, B, I), -7, 7))
+    need = q.bilstm_layer_workspace(Gf, Gb, T, B)
+    ws = torch.empty(need, dtype=torch.uint8, device=DEV)
+    both = host(q.bilstm_layer(Gf, Gb, x, workspace=ws))
+    assert q.layer_error_flag(ws, need) == 0
+    f = host(q.lstm_layer(Gf, x)["h_out"])
+    b = host(q.lstm_layer(Gb, x, reverse=True)["h_out"])
+    assert np.array_equal(both[:, :, :H], f) and np.array_equal(both[:, :, H:], b)
+
+
 # ------------------------------------------------------------------ joint + fusion, beam
 
 @pytest.mark.parametrize("N,J,V,TB,lms", [(4, 32, 16, 40, True), (1024, 256, 46, 32000, True), (37, 256, 46, 100, True),
