@@ -100,47 +100,6 @@ __global__ void decode_init_kernel(float *score0, int32_t *node0, int32_t *len0,
     active[n] = 1;
 }
 
-// End of a frame: the new beam is the W best candidates by (score descending,
-// insertion order).  One wave per utterance.
-__global__ __launch_bounds__(64) void frame_end_kernel(const float *__restrict__ nx_score, const int32_t *__restrict__ nx_src,
-                                                        int32_t *__restrict__ nx_count, int W, int R, int N,
-                                                        const int32_t *node_all, const int32_t *len_all,
-                                                        int dst_buf, float *__restrict__ score_all,
-                                                        int32_t *node_all_w, int32_t *len_all_w,
-                                                        int32_t *__restrict__ beam_src)
-{
-    const int b = blockIdx.x, lane = threadIdx.x;
-    const int cnt = nx_count[b];
-    const float *sc = nx_score + (size_t)b * R * W;
-    int c;
-    float v;
-    if (R * W <= 128) {
-        float val[2];
-#pragma unroll
-        for (int i = 0; i < 2; ++i) val[i] = (lane * 2 + i < cnt) ? sc[lane * 2 + i] + 0.0f : -INFINITY;
-        qr_select_from_regs<2>(val, lane * 2, W, lane, c, v);
-    } else {
-        auto value = [&](int i) -> float { return sc[i] + 0.0f; };
-        qr_select_from_mem(value, cnt, W, lane, c, v);
-    }
-    if (lane < W) {
-        const int dst = b * W + lane;
-        if (c >= 0) {
-            const int src = nx_src[(size_t)b * R * W + c];
-            score_all[(size_t)dst_buf * N + dst] = v;
-            node_all_w[(size_t)dst_buf * N + dst] = node_all[src];
-            len_all_w[(size_t)dst_buf * N + dst] = len_all[src];
-            beam_src[dst] = src;
-        } else {
-            score_all[(size_t)dst_buf * N + dst] = -INFINITY;
-            node_all_w[(size_t)dst_buf * N + dst] = 0;
-            len_all_w[(size_t)dst_buf * N + dst] = 0;
-            beam_src[dst] = -1;
-        }
-    }
-    if (lane == 0) nx_count[b] = 0;
-}
-
 struct GatherTable {
     char *base[MAX_TENSORS];
     int row_bytes[MAX_TENSORS];
@@ -364,12 +323,13 @@ extern "C" qrnnt_status qrnnt_decode(const qrnnt_model *m, const float *enc_proj
             ra.parent_idx = p.parent_idx;  ra.token = p.token;  ra.active = p.active;
             ra.nx_score = p.nx_score;  ra.nx_src = p.nx_src;  ra.nx_count = p.nx_count;
             ra.node_tok = p.node_tok;  ra.node_prev = p.node_prev;
+            ra.fe_dst_buf = (a0 == 0) ? ZB : 0;
+            ra.fe_node_all = p.node;  ra.fe_len_all = p.len;  ra.fe_score_all = p.score;
+            ra.fe_node_all_w = p.node;  ra.fe_len_all_w = p.len;  ra.beam_src = p.beam_src;
             qr_launch_joint_route(ja, ra, st);
             if (!last) advance_nets(m, p, cur, nxt, n_embed_rows, st);
         }
         const int dst = (a0 == 0) ? ZB : 0;
-        frame_end_kernel<<<B, 64, 0, st>>>(p.nx_score, p.nx_src, p.nx_count, W, p.R, N, p.node, p.len, dst, p.score,
-                                           p.node, p.len, p.beam_src);
         gather_state_kernel<<<dim3(N, tb.n), 64, 0, st>>>(tb, p.beam_src, N, dst);
         a0 = dst;
     }

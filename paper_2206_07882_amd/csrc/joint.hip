@@ -230,7 +230,11 @@ __global__ __launch_bounds__(256) void joint_route_kernel(const QrJointArgs a, c
         }
         if (!qr_select_round(bv, bc, rd, lane, last_v, last_c, my_c, my_v)) break;
     }
-    qr_route_picks(r, b, lane, my_c, my_v);
+    const int cnt = qr_route_picks(r, b, lane, my_c, my_v);
+    if (r.last_round) {   // the frame is complete for this utterance: prune its candidate list to the new beam
+        __threadfence();
+        qr_frame_end(r, b, lane, cnt);
+    }
 }
 
 }  // namespace

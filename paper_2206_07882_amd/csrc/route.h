@@ -6,8 +6,10 @@
 #pragma once
 
 #include "kernels.h"
+#include "select.h"
 
-__device__ __forceinline__ void qr_route_picks(const QrRouteArgs &a, int b, int lane, int c, float v)
+// Returns the length of the utterance's candidate list after this round (uniform).
+__device__ __forceinline__ int qr_route_picks(const QrRouteArgs &a, int b, int lane, int c, float v)
 {
     const int W = a.W, V = a.V, N = a.B * a.W;
     const bool in = lane < W;
@@ -24,8 +26,9 @@ __device__ __forceinline__ void qr_route_picks(const QrRouteArgs &a, int b, int 
         a.nx_score[(size_t)b * a.R * W + e] = v;
         a.nx_src[(size_t)b * a.R * W + e] = a.src_buf * N + src_slot;
     }
-    if (lane == 0) a.nx_count[b] = nx0 + __popcll(bm);
-    if (a.last_round) return;
+    const int cnt = nx0 + __popcll(bm);
+    if (lane == 0) a.nx_count[b] = cnt;
+    if (a.last_round) return cnt;
     const int n_lab = __popcll(lm);
     if (is_lab) {
         const int dst = b * W + __popcll(lm & lt);
@@ -48,4 +51,44 @@ __device__ __forceinline__ void qr_route_picks(const QrRouteArgs &a, int b, int 
         a.token[dst] = a.blank;
         a.active[dst] = 0;
     }
+    return cnt;
+}
+
+// End of a frame for utterance b (one wave): the new beam is the W best of the cnt candidates by
+// (score descending, insertion order); slot r of buffer fe_dst_buf takes score, trie node and length
+// of its source, beam_src[r] tells the state gather where the states are.  The candidates of the
+// current round were stored by this same wave a moment ago: they are read back from L2 (agent-scope
+// loads after a fence), not through the CU's vector cache.
+__device__ __forceinline__ void qr_frame_end(const QrRouteArgs &a, int b, int lane, int cnt)
+{
+    const int W = a.W, R = a.R, N = a.B * a.W;
+    const float *sc = a.nx_score + (size_t)b * R * W;
+    auto score_at = [&](int i) { return __hip_atomic_load(sc + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + 0.0f; };
+    int c;
+    float v;
+    if (R * W <= 128) {
+        float val[2];
+#pragma unroll
+        for (int i = 0; i < 2; ++i) val[i] = (lane * 2 + i < cnt) ? score_at(lane * 2 + i) : -INFINITY;
+        qr_select_from_regs<2>(val, lane * 2, W, lane, c, v);
+    } else {
+        qr_select_from_mem(score_at, cnt, W, lane, c, v);
+    }
+    if (lane < W) {
+        const int dst = b * W + lane;
+        const size_t o = (size_t)a.fe_dst_buf * N + dst;
+        if (c >= 0) {
+            const int src = __hip_atomic_load(a.nx_src + (size_t)b * R * W + c, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            a.fe_score_all[o] = v;
+            a.fe_node_all_w[o] = a.fe_node_all[src];
+            a.fe_len_all_w[o] = a.fe_len_all[src];
+            a.beam_src[dst] = src;
+        } else {
+            a.fe_score_all[o] = -INFINITY;
+            a.fe_node_all_w[o] = 0;
+            a.fe_len_all_w[o] = 0;
+            a.beam_src[dst] = -1;
+        }
+    }
+    if (lane == 0) a.nx_count[b] = 0;
 }
