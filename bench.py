@@ -45,8 +45,8 @@ def main():
                     help="time the kernel legs with direct launches instead of HIP-graph replays (for counter runs)")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py measures one GPU: this build has no multi-GPU path (utterances would shard with no "
-              "collective; see DESIGN.md). Run with --gpus 1.", file=sys.stderr)
+        print("bench.py measures one GPU: this build has no multi-GPU path (utterances are independent and would "
+              "shard across GPUs without any collective). Run with --gpus 1.", file=sys.stderr)
         sys.exit(2)
 
     import numpy as np
