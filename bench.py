@@ -138,7 +138,18 @@ def main():
         extra["audio_seconds_per_second"] = audio / sec
         lens = out[1].cpu().numpy()
         extra["mean_labels_best_hyp"] = float(lens[:, 0].mean())
-        del feats, ws_dec, e, out
+        # decoder time against the beam width (same encoder output, 200 frames): how search cost grows with W
+        Ts = min(T, 200)
+        es = e[:Ts].contiguous()
+        sweep_w = []
+        for Wb in (1, 2, 4, 8, 16):
+            wsb = torch.empty(q.decode_workspace(G, Ts, B, Wb, MAX_SYM), dtype=torch.uint8, device=dev)
+            tb = timed(lambda: q.decode(G, es, Wb, MAX_SYM, max_len=Ts * MAX_SYM, workspace=wsb), 1, warm=1)
+            sweep_w.append({"beam": Wb, "decoder_ms_per_1000_frames": tb * 1e3 * 1000.0 / Ts,
+                            "decoder_rtf": tb / (B * Ts * FRAME_SEC)})
+            del wsb
+        extra["beam_sweep"] = sweep_w
+        del feats, ws_dec, e, es, out
 
     # ---------------------------------------------------------------- kernel legs
     if args.leg in ("all", "kernels"):

@@ -62,6 +62,41 @@ def test_pack_roundtrip_and_canonical_bytes(gpu_lib, rows, cols):
             assert np.array_equal(host(m.packed).reshape(rows, cp // 2), oracle.pack_rows(codes, cp))
 
 
+def _tiled_blob(codes, gates):
+    """The TILED / TILED_GATES blob written out from the layout notes of the header, in numpy."""
+    rows, cols = codes.shape
+    H = rows // 4
+    rp = (rows + 63) // 64 * 64 if gates else (rows + 15) // 16 * 16
+    nkc = (cols + 127) // 128
+    padded = np.zeros((rp, nkc * 128), np.int8)
+    if gates:
+        for j in range(H):
+            q, a, b = j // 16, (j % 16) // 4, j % 4
+            for g in range(4):
+                padded[64 * q + 16 * b + 4 * a + g, :cols] = codes[g * H + j]
+    else:
+        padded[:rows, :cols] = codes
+    blob = np.zeros((rp // 16, nkc, 64, 16), np.uint8)
+    nib = (padded.astype(np.int16) & 0xF).astype(np.uint8)
+    for lane in range(64):
+        r, kq = lane % 16, lane // 16
+        lo = nib[r::16, :].reshape(rp // 16, nkc, 128)[:, :, 16 * kq:16 * kq + 16]
+        hi = nib[r::16, :].reshape(rp // 16, nkc, 128)[:, :, 64 + 16 * kq:64 + 16 * kq + 16]
+        blob[:, :, lane, :] = lo | (hi << 4)
+    return blob.reshape(-1)
+
+
+@pytest.mark.parametrize("rows,cols", [(64, 32), (2560, 240), (48, 256), (46, 256), (4, 16), (3072, 768)])
+def test_pack_tiled_bytes_follow_the_documented_layout(gpu_lib, rows, cols):
+    q = gpu_lib
+    codes = synth.codes(15 + rows + cols, (rows, cols), -8, 7)
+    m = q.pack_int4(dev(codes), q.LAYOUT_TILED)
+    assert np.array_equal(host(m.packed), _tiled_blob(codes, False))
+    if rows % 4 == 0:
+        m = q.pack_int4(dev(codes), q.LAYOUT_TILED_GATES)
+        assert np.array_equal(host(m.packed), _tiled_blob(codes, True))
+
+
 @pytest.mark.parametrize("rows,cols", [(64, 32), (3072, 768), (46, 256)])
 def test_pack_from_fp32_matches_oracle_quantizer(gpu_lib, rows, cols):
     q = gpu_lib
