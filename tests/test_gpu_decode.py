@@ -102,3 +102,19 @@ def test_decode_full_width_networks_128_hypotheses(gpu_lib):
     ref = oracle.decode(omodels.model_from_float(m), e, W, max_sym)
     got = gpu_lib.decode(gmodel.model_from_float(m, DEV), dev(e), W, max_sym)
     _compare_beams(got, ref)
+
+
+def test_decode_benchmark_shape_sampled_utterances(gpu_lib):
+    """The decoder in the launch configuration the benchmark times (64 utterances x beam 16 = 1024
+    hypotheses, at most 4 labels per frame, full layer widths), on a few frames.  Utterances do not
+    interact, so the oracle decodes two sampled ones alone and must find the GPU's beams for them."""
+    from paper_2206_07882_amd import model as gmodel
+    m = synth.make_model(4, enc_layers=1)
+    T, B, W, max_sym = 3, 64, 16, 4
+    e = synth.normal(202, (T, B, m.J), 1.0)
+    got = gpu_lib.decode(gmodel.model_from_float(m, DEV), dev(e), W, max_sym)
+    tok_g, len_g, sc_g = (host(x) for x in got)
+    M = omodels.model_from_float(m)
+    for b in (5, 41):
+        ref = oracle.decode(M, np.ascontiguousarray(e[:, b:b + 1]), W, max_sym)
+        _compare_beams((torch.from_numpy(tok_g[b:b + 1]), torch.from_numpy(len_g[b:b + 1]), torch.from_numpy(sc_g[b:b + 1])), ref)
