@@ -24,6 +24,19 @@ __global__ __launch_bounds__(256) void linear_head_kernel(const QrLinearGroup g)
         const v4i zero = {0, 0, 0, 0};
         return (kb * 64 + grp * 16 < K) ? *(const v4i *)(arow + kb * 64) : zero;
     };
+    // row constants of the lanes that finish the rows (wave 0): fetched ahead of the contraction
+    float sw[4][4], bs[4][4];
+    if (wave == 0) {
+#pragma unroll
+        for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int r = (rt0 + mt) * 16 + grp * 4 + i;
+                const int rr = r < a.rows ? r : a.rows - 1;
+                sw[mt][i] = a.a_scale * a.s_w[rr];
+                bs[mt][i] = a.bias ? a.bias[rr] : 0.0f;
+            }
+    }
     v4i acc[4];
     qr_head_mma(a.w, a.nkc, n_row_tiles, rt0, K, bfrag, acc, lds);
     if (wave != 0) return;
@@ -36,7 +49,7 @@ __global__ __launch_bounds__(256) void linear_head_kernel(const QrLinearGroup g)
         for (int i = 0; i < 4; ++i) {
             const int r = (rt0 + mt) * 16 + grp * 4 + i;
             if (r < a.rows) {
-                v[mt][i] = (a.a_scale * a.s_w[r]) * (float)acc[mt][i] + (a.bias ? a.bias[r] : 0.0f);
+                v[mt][i] = sw[mt][i] * (float)acc[mt][i] + bs[mt][i];
                 if (a.dbg_acc && nv) a.dbg_acc[(int64_t)n * a.rows + r] = acc[mt][i];
                 mx = fmaxf(mx, v[mt][i]);
             } else {
@@ -57,13 +70,18 @@ __global__ __launch_bounds__(256) void linear_head_kernel(const QrLinearGroup g)
         lse = mx + logf(sum);
     }
     if (!nv) return;
+    const bool wide = (a.rows & 3) == 0 && ((uintptr_t)a.y & 15) == 0;   // rows of y are 16-byte aligned: one 128-bit store per lane and row tile
 #pragma unroll
-    for (int mt = 0; mt < 4; ++mt)
+    for (int mt = 0; mt < 4; ++mt) {
+        const int r0 = (rt0 + mt) * 16 + grp * 4;
+        if (wide) {
+            if (r0 < a.rows) *(v4f *)(a.y + (int64_t)n * a.rows + r0) = v4f{v[mt][0] - lse, v[mt][1] - lse, v[mt][2] - lse, v[mt][3] - lse};
+        } else {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int r = (rt0 + mt) * 16 + grp * 4 + i;
-            if (r < a.rows) a.y[(int64_t)n * a.rows + r] = v[mt][i] - lse;
+            for (int i = 0; i < 4; ++i)
+                if (r0 + i < a.rows) a.y[(int64_t)n * a.rows + r0 + i] = v[mt][i] - lse;
         }
+    }
 }
 
 }  // namespace
