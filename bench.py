@@ -149,6 +149,20 @@ def main():
                             "decoder_rtf": tb / (B * Ts * FRAME_SEC)})
             del wsb
         extra["beam_sweep"] = sweep_w
+        # the early-stop variant of the search (same beams; rounds without a live hypothesis return at once)
+        es_rows = []
+        for Wb in (1, 16):
+            wsb = torch.empty(q.decode_workspace(G, Ts, B, Wb, MAX_SYM), dtype=torch.uint8, device=dev)
+            tf = timed(lambda: q.decode(G, es, Wb, MAX_SYM, max_len=Ts * MAX_SYM, workspace=wsb), 1, warm=1)
+            te = timed(lambda: q.decode(G, es, Wb, MAX_SYM, max_len=Ts * MAX_SYM, workspace=wsb,
+                                        flags=q.DECODE_EARLY_STOP), 1, warm=1)
+            es_rows.append({"beam": Wb, "fixed_rounds_ms_per_1000_frames": tf * 1e3 * 1000.0 / Ts,
+                            "early_stop_ms_per_1000_frames": te * 1e3 * 1000.0 / Ts})
+            del wsb
+        extra["early_stop"] = {"rows": es_rows,
+                               "note": "a round dies only when no utterance of the batch picked a label in the round before: "
+                                       "with beam 16 the 16 picks of a round always include labels, so nothing is skipped "
+                                       "and the flag costs its loads; greedy search (beam 1) on this model skips most rounds"}
         del feats, ws_dec, e, es, out
 
     # ---------------------------------------------------------------- kernel legs

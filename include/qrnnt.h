@@ -275,6 +275,17 @@ qrnnt_status qrnnt_decode(const qrnnt_model *m, const float *enc_proj, int32_t T
                           int32_t max_sym, int32_t max_len, int32_t *tokens_out, int32_t *len_out, float *score_out,
                           void *workspace, size_t workspace_bytes, void *stream);
 
+/* qrnnt_decode with options.  flags: QRNNT_DECODE_EARLY_STOP makes every kernel
+ * of a round start by reading a device-side count of the utterances that carried
+ * a label into that round and return at once when it is zero (then no later round
+ * of the frame can pick anything either): same results, a few loads more per
+ * kernel, and the cost of a frame follows the labels it actually emits.  The host
+ * still enqueues the same launch sequence.  flags == 0 is qrnnt_decode. */
+#define QRNNT_DECODE_EARLY_STOP 1u
+qrnnt_status qrnnt_decode_ex(const qrnnt_model *m, const float *enc_proj, int32_t T, int32_t B, int32_t W,
+                             int32_t max_sym, int32_t max_len, uint32_t flags, int32_t *tokens_out, int32_t *len_out,
+                             float *score_out, void *workspace, size_t workspace_bytes, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -27,6 +27,7 @@ struct Plan {
     float *nx_score;  int32_t *nx_src;  int32_t *nx_count; // [B][R*W], [B]
     int32_t *beam_src;   // [N]
     int32_t *node_tok, *node_prev;   // [1 + T*max_sym*N]
+    int32_t *live;       // [2][max_sym+2]: utterances that carried a label into round v of the frame (early stop)
     size_t total;
 };
 
@@ -73,6 +74,7 @@ void make_plan(const qrnnt_model *m, int T, int B, int W, int max_sym, void *ws,
     const size_t pool = 1 + (size_t)T * max_sym * N;
     p.node_tok = cv.take<int32_t>(pool);
     p.node_prev = cv.take<int32_t>(pool);
+    p.live = cv.take<int32_t>(2 * (size_t)(max_sym + 2));
     p.total = (cv.off + 255) / 256 * 256;
 }
 
@@ -180,7 +182,8 @@ qrnnt_status check_model(const qrnnt_model *m)
 
 // All used networks consume `token` and move from buffer src to buffer dst.  Layer l
 // of every network goes out as one grouped launch (the networks are independent).
-void advance_nets(const qrnnt_model *m, const Plan &p, int src, int dst, int n_embed_rows, hipStream_t st)
+void advance_nets(const qrnnt_model *m, const Plan &p, int src, int dst, int n_embed_rows, const int32_t *gate,
+                  hipStream_t st)
 {
     const size_t N = (size_t)p.N;
     int max_layers = 0;
@@ -189,6 +192,7 @@ void advance_nets(const qrnnt_model *m, const Plan &p, int src, int dst, int n_e
     for (int l = 0; l < max_layers; ++l) {
         QrStepGroup g;
         g.n = 0;
+        g.gate = gate;
         for (int k = 0; k < 3; ++k) {
             if (!net_used(m, k)) continue;
             const qrnnt_net *net = net_of(m, k);
@@ -219,6 +223,7 @@ void advance_nets(const qrnnt_model *m, const Plan &p, int src, int dst, int n_e
     }
     QrLinearGroup lg;
     lg.n = 0;
+    lg.gate = gate;
     for (int k = 0; k < 3; ++k) {
         if (!net_used(m, k)) continue;
         const qrnnt_net *net = net_of(m, k);
@@ -248,12 +253,23 @@ extern "C" qrnnt_status qrnnt_decode(const qrnnt_model *m, const float *enc_proj
                                      int32_t max_sym, int32_t max_len, int32_t *tokens_out, int32_t *len_out,
                                      float *score_out, void *workspace, size_t workspace_bytes, void *stream)
 {
+    return qrnnt_decode_ex(m, enc_proj, T, B, W, max_sym, max_len, 0u, tokens_out, len_out, score_out, workspace,
+                           workspace_bytes, stream);
+}
+
+extern "C" qrnnt_status qrnnt_decode_ex(const qrnnt_model *m, const float *enc_proj, int32_t T, int32_t B, int32_t W,
+                                        int32_t max_sym, int32_t max_len, uint32_t flags, int32_t *tokens_out,
+                                        int32_t *len_out, float *score_out, void *workspace, size_t workspace_bytes,
+                                        void *stream)
+{
     qrnnt_status s = check_model(m);
     if (s != QRNNT_OK) return s;
     QR_REQUIRE(enc_proj && tokens_out && len_out && score_out && workspace, QRNNT_ERR_NULL);
     QR_REQUIRE(T > 0 && B > 0 && W > 0 && max_len > 0, QRNNT_ERR_SHAPE);
     QR_REQUIRE(W <= 64, QRNNT_ERR_UNSUPPORTED);
     QR_REQUIRE(max_sym >= 0 && max_sym <= 16, QRNNT_ERR_RANGE);
+    QR_REQUIRE((flags & ~(uint32_t)QRNNT_DECODE_EARLY_STOP) == 0u, QRNNT_ERR_RANGE);
+    const bool early = (flags & QRNNT_DECODE_EARLY_STOP) != 0u;
     QR_REQUIRE((double)T * (max_sym > 0 ? max_sym : 1) * B * W < 2.0e9, QRNNT_ERR_UNSUPPORTED);
     QR_REQUIRE(qr_aligned(enc_proj, 16) && qr_aligned(workspace, 256), QRNNT_ERR_ALIGN);
     Plan p;
@@ -280,9 +296,10 @@ extern "C" qrnnt_status qrnnt_decode(const qrnnt_model *m, const float *enc_proj
     for (int k = 0; k < 3; ++k)
         if (net_used(m, k))
             qr_launch_input_projection(&net_of(m, k)->layer[0], net_of(m, k)->embed_codes, V, p.net[k].gx0, nullptr, st);
+    fill_words_kernel<<<1, 256, 0, st>>>((uint32_t *)p.live, 2 * (size_t)(max_sym + 2), 0u);
     decode_init_kernel<<<(N + 255) / 256 + 1, 256, 0, st>>>(p.score, p.node, p.len, p.parent_idx, p.token, p.active,
                                                             p.nx_count, p.node_tok, p.node_prev, N, W, B, m->blank);
-    advance_nets(m, p, ZB, 0, n_embed_rows, st);
+    advance_nets(m, p, ZB, 0, n_embed_rows, nullptr, st);
 
     GatherTable tb = {};
     for (int k = 0; k < 3; ++k) {
@@ -326,8 +343,14 @@ extern "C" qrnnt_status qrnnt_decode(const qrnnt_model *m, const float *enc_proj
             ra.fe_dst_buf = (a0 == 0) ? ZB : 0;
             ra.fe_node_all = p.node;  ra.fe_len_all = p.len;  ra.fe_score_all = p.score;
             ra.fe_node_all_w = p.node;  ra.fe_len_all_w = p.len;  ra.beam_src = p.beam_src;
+            if (early) {   // live[t&1][v] = utterances that carried a label into round v of this frame
+                int32_t *lv = p.live + (size_t)(t & 1) * (max_sym + 2), *lo = p.live + (size_t)((t + 1) & 1) * (max_sym + 2);
+                ra.gate = v > 0 ? lv + v : nullptr;
+                ra.live_next = lv + v + 1;
+                ra.live_clear = lo + v + 1;
+            }
             qr_launch_joint_route(ja, ra, st);
-            if (!last) advance_nets(m, p, cur, nxt, n_embed_rows, st);
+            if (!last) advance_nets(m, p, cur, nxt, n_embed_rows, early ? ra.live_next : nullptr, st);
         }
         const int dst = (a0 == 0) ? ZB : 0;
         gather_state_kernel<<<dim3(N, tb.n), 64, 0, st>>>(tb, p.beam_src, N, dst);

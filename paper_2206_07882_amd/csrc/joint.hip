@@ -111,6 +111,13 @@ __global__ __launch_bounds__(256) void joint_route_kernel(const QrJointArgs a, c
     const int col = lane & 15, grp = lane >> 4;
     const int b = blockIdx.x;
     const int W = r.W, V = a.V, J = a.J;
+    if (r.gate && *r.gate == 0) {   // uniform: no utterance carried a label into this round, nothing can be picked
+        if (wave == 0) {
+            if (lane == 0 && b == 0 && r.live_clear) *r.live_clear = 0;
+            if (r.last_round) qr_frame_end(r, b, lane, r.nx_count[b]);
+        }
+        return;
+    }
     int fr = a.frame_base + b;
     fr = fr < 0 ? 0 : (fr >= a.n_enc_rows ? a.n_enc_rows - 1 : fr);
     const float *e = a.enc + (int64_t)fr * J + grp * 16;

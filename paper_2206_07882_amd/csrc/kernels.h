@@ -30,6 +30,7 @@ struct QrStepArgs {
 struct QrStepGroup {
     QrStepArgs p[QR_MAX_GROUP];
     int n;
+    const int32_t *gate;               // optional [device]: the launch does nothing when *gate == 0
 };
 
 struct QrLinearArgs {
@@ -44,6 +45,7 @@ struct QrLinearArgs {
 struct QrLinearGroup {
     QrLinearArgs p[QR_MAX_GROUP];
     int n;
+    const int32_t *gate;               // optional [device]: the launch does nothing when *gate == 0
 };
 
 struct QrJointArgs {
@@ -72,6 +74,9 @@ struct QrRouteArgs {
     const int32_t *fe_node_all, *fe_len_all;        // [NB][N]
     float *fe_score_all;  int32_t *fe_node_all_w, *fe_len_all_w;
     int32_t *beam_src;                              // [N] flat source (buffer, slot) of every new beam slot, or -1
+    // early stop (all optional): the round is dead when *gate == 0; an utterance that picked a label
+    // adds 1 to *live_next; workgroup 0 clears *live_clear for a later frame
+    const int32_t *gate;  int32_t *live_next, *live_clear;
 };
 
 // One direction of the persistent recurrence (see recurrence.hip).

@@ -9,6 +9,7 @@ namespace {
 __global__ __launch_bounds__(256) void linear_head_kernel(const QrLinearGroup g)
 {
     __shared__ v4i lds[4 * 4 * 64];
+    if (g.gate && *g.gate == 0) return;   // uniform: a decoding round without any live hypothesis
     const QrLinearArgs &a = g.p[blockIdx.z];
     const int n_row_tiles = (a.rows + 15) >> 4;
     const int rt0 = blockIdx.y * 4;
@@ -102,6 +103,7 @@ void qr_launch_linear(const QrLinearArgs &a, hipStream_t st)
     QrLinearGroup g;
     g.p[0] = a;
     g.n = 1;
+    g.gate = nullptr;
     qr_launch_linear_group(g, st);
 }
 

@@ -25,6 +25,7 @@ template <bool USE_GX>
 __global__ __launch_bounds__(256) void lstm_step_small_kernel(const QrStepGroup g)
 {
     __shared__ v4i part[3][2][64];   // waves 1..3: [x|h][lane]
+    if (g.gate && *g.gate == 0) return;   // uniform: a decoding round without any live hypothesis
     const QrStepArgs &a = g.p[blockIdx.z];
     const int H = a.H, N = a.N;
     const int rt = blockIdx.x;
@@ -180,6 +181,7 @@ __global__ __launch_bounds__(256, (USE_GX && !DBG) ? 3 : 2) void lstm_step_pipe_
 {
     using P = QrPipe<MT, NT, S>;
     extern __shared__ __attribute__((aligned(1024))) char lds[];
+    if (g.gate && *g.gate == 0) return;   // uniform: a decoding round without any live hypothesis
     const QrStepArgs &a = g.p[blockIdx.z];
     const int H = a.H, N = a.N;
     const int n_row_tiles = H >> 2;
@@ -428,6 +430,7 @@ void launch_step_t(const QrStepArgs &a, hipStream_t st)
     QrStepGroup g;
     g.p[0] = a;
     g.n = 1;
+    g.gate = nullptr;
     if (a.N <= small_n_max()) launch_small<USE_GX>(g, st);
     else launch_pipe<4, 4, USE_GX ? 2 : 3, USE_GX>(g, st);
 }
@@ -628,6 +631,7 @@ extern "C" qrnnt_status qrnnt_lstm_step_group(const qrnnt_step_desc *steps, int3
     QR_REQUIRE(n_steps >= 1 && n_steps <= QR_MAX_GROUP, QRNNT_ERR_RANGE);
     QrStepGroup g;
     g.n = n_steps;
+    g.gate = nullptr;
     for (int i = 0; i < n_steps; ++i) {
         const qrnnt_step_desc &d = steps[i];
         qrnnt_status s = make_step_args(g.p[i], d.L, d.x_codes, d.x_row, d.n_x_rows, d.parent, d.h_prev, d.c_prev,

@@ -11,6 +11,7 @@
 // Returns the length of the utterance's candidate list after this round (uniform).
 __device__ __forceinline__ int qr_route_picks(const QrRouteArgs &a, int b, int lane, int c, float v)
 {
+    if (lane == 0 && b == 0 && a.live_clear) *a.live_clear = 0;
     const int W = a.W, V = a.V, N = a.B * a.W;
     const bool in = lane < W;
     const bool found = in && c >= 0;
@@ -30,6 +31,7 @@ __device__ __forceinline__ int qr_route_picks(const QrRouteArgs &a, int b, int l
     if (lane == 0) a.nx_count[b] = cnt;
     if (a.last_round) return cnt;
     const int n_lab = __popcll(lm);
+    if (lane == 0 && n_lab > 0 && a.live_next) atomicAdd(a.live_next, 1);
     if (is_lab) {
         const int dst = b * W + __popcll(lm & lt);
         const int id = a.node_base + dst;

@@ -60,7 +60,9 @@ EXPORTS = ["qrnnt_status_str", "qrnnt_abi_version", "qrnnt_pack_int4_bytes", "qr
            "qrnnt_quantize_act", "qrnnt_linear", "qrnnt_lstm_step", "qrnnt_lstm_layer_workspace", "qrnnt_lstm_layer",
            "qrnnt_input_projection", "qrnnt_lstm_step_group",
            "qrnnt_bilstm_layer_workspace", "qrnnt_bilstm_layer",
-           "qrnnt_joint_fuse", "qrnnt_beam_step", "qrnnt_decode_workspace", "qrnnt_decode"]
+           "qrnnt_joint_fuse", "qrnnt_beam_step", "qrnnt_decode_workspace", "qrnnt_decode", "qrnnt_decode_ex"]
+
+DECODE_EARLY_STOP = 1
 
 
 def load():
@@ -397,7 +399,7 @@ def decode_workspace(model: Model, T: int, B: int, W: int, max_sym: int) -> int:
 
 
 def decode(model: Model, enc_proj: torch.Tensor, W: int, max_sym: int, max_len: Optional[int] = None,
-           workspace: Optional[torch.Tensor] = None):
+           workspace: Optional[torch.Tensor] = None, flags: int = 0):
     T, B, J = enc_proj.shape
     dev = enc_proj.device
     if max_len is None:
@@ -411,8 +413,8 @@ def decode(model: Model, enc_proj: torch.Tensor, W: int, max_sym: int, max_len: 
     lens = torch.empty((B, W), dtype=torch.int32, device=dev)
     scores = torch.empty((B, W), dtype=torch.float32, device=dev)
     cm = model.c()
-    st = load().qrnnt_decode(C.byref(cm), _ptr(enc_proj, torch.float32), C.c_int32(T), C.c_int32(B), C.c_int32(W),
-                             C.c_int32(max_sym), C.c_int32(max_len), _ptr(tokens), _ptr(lens), _ptr(scores),
-                             _ptr(workspace), C.c_size_t(workspace.numel()), _stream())
-    _check(st, "qrnnt_decode")
+    st = load().qrnnt_decode_ex(C.byref(cm), _ptr(enc_proj, torch.float32), C.c_int32(T), C.c_int32(B), C.c_int32(W),
+                                C.c_int32(max_sym), C.c_int32(max_len), C.c_uint32(flags), _ptr(tokens), _ptr(lens),
+                                _ptr(scores), _ptr(workspace), C.c_size_t(workspace.numel()), _stream())
+    _check(st, "qrnnt_decode_ex")
     return tokens, lens, scores

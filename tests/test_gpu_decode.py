@@ -118,3 +118,23 @@ def test_decode_benchmark_shape_sampled_utterances(gpu_lib):
     for b in (5, 41):
         ref = oracle.decode(M, np.ascontiguousarray(e[:, b:b + 1]), W, max_sym)
         _compare_beams((torch.from_numpy(tok_g[b:b + 1]), torch.from_numpy(len_g[b:b + 1]), torch.from_numpy(sc_g[b:b + 1])), ref)
+
+
+@pytest.mark.parametrize("blank_bias", [0.0, 6.0])
+def test_decode_early_stop_gives_the_same_beams(gpu_lib, blank_bias):
+    """With the early-stop flag the kernels of a round return at once when no utterance carried a label
+    into it.  Same beams as the fixed-round search and as the oracle; the blank-heavy variant (joint bias
+    of blank raised) makes most rounds after the first die, the plain one keeps them all alive."""
+    from paper_2206_07882_amd import model as gmodel
+    m = synth.make_model(0, weight_std=0.6)
+    m.joint_out.bias = m.joint_out.bias.copy()
+    m.joint_out.bias[0] += np.float32(blank_bias)   # blank is token 0
+    T, B, W, max_sym = 14, 5, 4, 3
+    e = synth.normal(210, (T, B, m.J), 1.0)
+    ref = oracle.decode(omodels.model_from_float(m), e, W, max_sym)
+    G = gmodel.model_from_float(m, DEV)
+    fixed = gpu_lib.decode(G, dev(e), W, max_sym)
+    early = gpu_lib.decode(G, dev(e), W, max_sym, flags=gpu_lib.DECODE_EARLY_STOP)
+    _compare_beams(fixed, ref)
+    for a, b in zip(fixed, early):
+        assert torch.equal(a, b)
