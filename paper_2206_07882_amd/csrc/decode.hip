@@ -16,6 +16,7 @@ struct NetBuf {
     float *c[QRNNT_MAX_LAYERS];    // [NB][N][H]
     float *y;                      // [NB][N][out_rows]
     int32_t *gx0;                  // [V][4*H0]: input projection of layer 0 for every token
+    float *tab0;                   // the same as fp32 pre-activation contributions (scales, bias folded in)
 };
 
 struct Plan {
@@ -60,6 +61,7 @@ void make_plan(const qrnnt_model *m, int T, int B, int W, int max_sym, void *ws,
         }
         p.net[k].y = cv.take<float>(NB * N * net->out.rows);
         p.net[k].gx0 = cv.take<int32_t>((size_t)m->V * 4 * net->layer[0].hidden_size);
+        p.net[k].tab0 = cv.take<float>((size_t)m->V * 4 * net->layer[0].hidden_size);
     }
     p.score = cv.take<float>(NB * N);
     p.node = cv.take<int32_t>(NB * N);
@@ -206,7 +208,7 @@ void advance_nets(const qrnnt_model *m, const Plan &p, int src, int dst, int n_e
                 // The input of layer 0 is one of V embedding rows, so its integer input
                 // projection is a table lookup (exactly the sums the contraction would give).
                 a.x = net->embed_codes;  a.ld_x = L->input_size;  a.x_row = p.token;  a.n_x_rows = n_embed_rows;
-                a.gx = p.net[k].gx0;  a.ld_gx = 4 * (int64_t)H;
+                a.gx = p.net[k].gx0;  a.ld_gx = 4 * (int64_t)H;  a.tabf = p.net[k].tab0;
             } else {
                 a.x = p.net[k].h[l - 1] + (size_t)dst * N * L->input_size;  a.ld_x = L->input_size;
                 a.x_row = nullptr;  a.n_x_rows = p.N;
@@ -293,9 +295,11 @@ extern "C" qrnnt_status qrnnt_decode_ex(const qrnnt_model *m, const float *enc_p
             fill_words_kernel<<<(unsigned)((nw + 255) / 256), 256, 0, st>>>((uint32_t *)(p.net[k].c[l] + (size_t)ZB * Ns * H), nw, 0u);
         }
     }
-    for (int k = 0; k < 3; ++k)
-        if (net_used(m, k))
-            qr_launch_input_projection(&net_of(m, k)->layer[0], net_of(m, k)->embed_codes, V, p.net[k].gx0, nullptr, st);
+    for (int k = 0; k < 3; ++k) {
+        if (!net_used(m, k)) continue;
+        qr_launch_input_projection(&net_of(m, k)->layer[0], net_of(m, k)->embed_codes, V, p.net[k].gx0, nullptr, st);
+        qr_launch_gx_table(&net_of(m, k)->layer[0], p.net[k].gx0, V, p.net[k].tab0, st);
+    }
     fill_words_kernel<<<1, 256, 0, st>>>((uint32_t *)p.live, 2 * (size_t)(max_sym + 2), 0u);
     decode_init_kernel<<<(N + 255) / 256 + 1, 256, 0, st>>>(p.score, p.node, p.len, p.parent_idx, p.token, p.active,
                                                             p.nx_count, p.node_tok, p.node_prev, N, W, B, m->blank);

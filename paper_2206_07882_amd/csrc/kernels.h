@@ -13,6 +13,7 @@ struct QrStepArgs {
     const int8_t *x;  int64_t ld_x;   // input codes, row pitch in bytes
     const int32_t *x_row;  int n_x_rows; // optional row index into x (or into gx) per hypothesis; rows available
     const int32_t *gx;  int64_t ld_gx; // precomputed input projection [rows, 4H], tiled-row order (USE_GX only)
+    const float *tabf;                 // optional fp32 form of gx with scales, bias and exp2 constants folded in
     const int32_t *parent;  int n_slots;
     const int8_t *h_prev;  int64_t ld_hp;
     const float *c_prev;
@@ -103,6 +104,7 @@ QR_HIDDEN void qr_fill_lstm_weights(QrStepArgs &a, const qrnnt_lstm *L);
 QR_HIDDEN qrnnt_status qr_check_lstm(const qrnnt_lstm *L);
 QR_HIDDEN void qr_launch_lstm_step(const QrStepArgs &a, bool use_gx, hipStream_t st);
 QR_HIDDEN void qr_launch_lstm_step_group(const QrStepGroup &g, bool use_gx, hipStream_t st);
+QR_HIDDEN void qr_launch_gx_table(const qrnnt_lstm *L, const int32_t *gx, int M, float *tab, hipStream_t st);
 QR_HIDDEN void qr_launch_input_projection(const qrnnt_lstm *L, const int8_t *x_codes, int M, int32_t *gx, int32_t *dbg_accx,
                                           hipStream_t st);
 QR_HIDDEN void qr_launch_linear_group(const QrLinearGroup &g, hipStream_t st);

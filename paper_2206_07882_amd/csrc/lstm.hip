@@ -176,7 +176,10 @@ void launch_small(const QrStepGroup &g, hipStream_t st)
 // of the input part to keep alive across it: that variant is held to 168 registers so that three
 // workgroups share a CU (with a two-stage ring), which is what lets the 704 workgroups of the
 // decoder's first-layer launch run in one round instead of two.
-template <int MT, int NT, int S, bool USE_GX, bool DBG, bool FAST>
+// TAB (with USE_GX): the looked-up input part is an fp32 table that already holds
+// gate_k * (x_scale * s_wih[r] * sum + bias[r]) (see qr_launch_gx_table): one fused multiply-add per gate
+// is all that is left of the dequantisation.
+template <int MT, int NT, int S, bool USE_GX, bool TAB, bool DBG, bool FAST>
 __global__ __launch_bounds__(256, (USE_GX && !DBG) ? 3 : 2) void lstm_step_pipe_kernel(const QrStepGroup g)
 {
     using P = QrPipe<MT, NT, S>;
@@ -272,10 +275,12 @@ __global__ __launch_bounds__(256, (USE_GX && !DBG) ? 3 : 2) void lstm_step_pipe_
     auto x_done = [&]() {
 #pragma unroll
         for (int q = 0; q < MQ; ++q) {
-            v4f sx[4];
+            v4f sx[4], bx[4];
 #pragma unroll
-            for (int gt = 0; gt < 4; ++gt)   // accumulators hold 16 x sum; gate_k: see the epilogue
+            for (int gt = 0; gt < 4; ++gt) {   // accumulators hold 16 x sum; gate_k: see the epilogue
                 sx[gt] = load4(a.s_wih + gt * H + jb[q]) * a.x_scale * (0.0625f * gate_k(gt));
+                bx[gt] = load4(a.bias + gt * H + jb[q]) * gate_k(gt);   // the bias rides with the input part
+            }
 #pragma unroll
             for (int i = 0; i < 4; ++i)
 #pragma unroll
@@ -286,7 +291,7 @@ __global__ __launch_bounds__(256, (USE_GX && !DBG) ? 3 : 2) void lstm_step_pipe_
                         for (int gt = 0; gt < 4; ++gt)
                             a.dbg_accx[(int64_t)n_of[nt] * 4 * H + gt * H + jb[q] + i] = acc[mt][nt][gt] >> 4;
 #pragma unroll
-                    for (int gt = 0; gt < 4; ++gt) pre[mt][nt][gt] = sx[gt][i] * (float)acc[mt][nt][gt];
+                    for (int gt = 0; gt < 4; ++gt) pre[mt][nt][gt] = sx[gt][i] * (float)acc[mt][nt][gt] + bx[gt][i];
                     acc[mt][nt] = zero;
                 }
         }
@@ -301,8 +306,8 @@ __global__ __launch_bounds__(256, (USE_GX && !DBG) ? 3 : 2) void lstm_step_pipe_
 #pragma unroll
         for (int gt = 0; gt < 4; ++gt) {
             sh[q][gt] = load4(a.s_whh + gt * H + jb[q]) * a.h_scale * (0.0625f * gate_k(gt));   // accumulators hold 16 x sum
-            bb[q][gt] = load4(a.bias + gt * H + jb[q]) * gate_k(gt);
-            if (USE_GX) sxg[q][gt] = load4(a.s_wih + gt * H + jb[q]) * a.x_scale * gate_k(gt);
+            if (USE_GX && !TAB) bb[q][gt] = load4(a.bias + gt * H + jb[q]) * gate_k(gt);
+            if (USE_GX && !TAB) sxg[q][gt] = load4(a.s_wih + gt * H + jb[q]) * a.x_scale * gate_k(gt);
         }
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) cp[q][nt] = load4(a.c_prev + (int64_t)src_of[nt] * H + jb[q]);
@@ -328,11 +333,12 @@ __global__ __launch_bounds__(256, (USE_GX && !DBG) ? 3 : 2) void lstm_step_pipe_
         for (int i = 0; i < 4; ++i) {
             int tr = (rt0 + 4 * q + i) * 16 + 4 * grp;   // gx columns are in tiled-row order
             tr = tr < 4 * H ? tr : 4 * H - 4;
-            dst[i] = *(const v4i *)(a.gx + (int64_t)gx_of[nt] * a.ld_gx + tr);
+            dst[i] = *(const v4i *)((TAB ? (const int32_t *)a.tabf : a.gx) + (int64_t)gx_of[nt] * a.ld_gx + tr);
         }
     };
     v4i gxv[2][4];
     if (USE_GX) load_gx(0, 0, gxv[0]);
+    const float hinv2 = 2.0f * a.h_inv;
 #pragma unroll
     for (int q = 0; q < MQ; ++q) {
         const bool jv = FAST || qr_gates_cell(rt0 + 4 * q, grp) < H;
@@ -350,17 +356,20 @@ __global__ __launch_bounds__(256, (USE_GX && !DBG) ? 3 : 2) void lstm_step_pipe_
                 float p[4];
 #pragma unroll
                 for (int gt = 0; gt < 4; ++gt) {
-                    const float xin = USE_GX ? sxg[q][gt][i] * (float)gxv[cur][i][gt] : pre[mt][nt][gt];
-                    p[gt] = xin + (sh[q][gt][i] * (float)acc[mt][nt][gt] + bb[q][gt][i]);
+                    if (TAB) p[gt] = sh[q][gt][i] * (float)acc[mt][nt][gt] + __int_as_float(gxv[cur][i][gt]);
+                    else if (USE_GX) p[gt] = sxg[q][gt][i] * (float)gxv[cur][i][gt] + (sh[q][gt][i] * (float)acc[mt][nt][gt] + bb[q][gt][i]);
+                    else p[gt] = sh[q][gt][i] * (float)acc[mt][nt][gt] + pre[mt][nt][gt];
                 }
                 const float gi = qr_sigmoid_scaled(p[0]), gf = qr_sigmoid_scaled(p[1]);
                 const float gg = 2.0f * qr_sigmoid_scaled(p[2]) - 1.0f, go = qr_sigmoid_scaled(p[3]);
                 const float c1 = gf * cp[q][nt][i] + gi * gg;
-                const float h = go * qr_tanh(c1);
+                // h * h_inv with the factor folded into tanh's last multiply-add: (2r - 1) * h_inv
+                const float rc = __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-2.885390081777927f * c1));
+                const float hq = go * (hinv2 * rc - a.h_inv);
                 cn[i] = on ? c1 : cp[q][nt][i];
-                codes |= (unsigned)(qr_quant4(h, a.h_inv) & 0xFF) << (8 * i);
+                codes |= (unsigned)((int)fminf(fmaxf(__builtin_rintf(hq), -8.0f), 7.0f) & 0xFF) << (8 * i);
                 if (DBG && jv && n < N) {
-                    if (USE_GX && a.dbg_accx)
+                    if (USE_GX && !TAB && a.dbg_accx)
 #pragma unroll
                         for (int gt = 0; gt < 4; ++gt) a.dbg_accx[(int64_t)n * 4 * H + gt * H + jb[q] + i] = gxv[cur][i][gt];
                     if (a.dbg_acch)
@@ -383,12 +392,12 @@ __global__ __launch_bounds__(256, (USE_GX && !DBG) ? 3 : 2) void lstm_step_pipe_
     }
 }
 
-template <int MT, int NT, int S, bool USE_GX, bool DBG, bool FAST>
+template <int MT, int NT, int S, bool USE_GX, bool TAB, bool DBG, bool FAST>
 void launch_pipe_f(const QrStepGroup &g, hipStream_t st)
 {
     using P = QrPipe<MT, NT, S>;
     static bool configured = false;
-    auto kern = lstm_step_pipe_kernel<MT, NT, S, USE_GX, DBG, FAST>;
+    auto kern = lstm_step_pipe_kernel<MT, NT, S, USE_GX, TAB, DBG, FAST>;
     if (!configured) {
         (void)hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, P::LDS_BYTES);
         configured = true;
@@ -406,16 +415,19 @@ template <int MT, int NT, int S, bool USE_GX>
 void launch_pipe(const QrStepGroup &g, hipStream_t st)
 {
     using P = QrPipe<MT, NT, S>;
-    bool dbg = false, fast = true;
+    bool dbg = false, fast = true, tab = USE_GX;
     for (int i = 0; i < g.n; ++i) {
         const QrStepArgs &a = g.p[i];
         dbg = dbg || a.dbg_accx || a.dbg_acch || a.dbg_gates;
+        tab = tab && a.tabf != nullptr;
         fast = fast && a.H % (8 * MT) == 0 && a.N % P::BN == 0 && a.H % QRNNT_KCHUNK == 0 &&
                (USE_GX || a.I % QRNNT_KCHUNK == 0);
     }
-    if (dbg) launch_pipe_f<MT, NT, S, USE_GX, true, false>(g, st);
-    else if (fast) launch_pipe_f<MT, NT, S, USE_GX, false, true>(g, st);
-    else launch_pipe_f<MT, NT, S, USE_GX, false, false>(g, st);
+    if (dbg) launch_pipe_f<MT, NT, S, USE_GX, false, true, false>(g, st);
+    else if (USE_GX && tab && fast) launch_pipe_f<MT, NT, S, USE_GX, USE_GX, false, true>(g, st);
+    else if (USE_GX && tab) launch_pipe_f<MT, NT, S, USE_GX, USE_GX, false, false>(g, st);
+    else if (fast) launch_pipe_f<MT, NT, S, USE_GX, false, false, true>(g, st);
+    else launch_pipe_f<MT, NT, S, USE_GX, false, false, false>(g, st);
 }
 
 // Hypothesis counts up to this go to the weight-streaming kernel.
@@ -520,6 +532,20 @@ void launch_gx_pipe(const qrnnt_lstm *L, const int8_t *x_codes, int M, int32_t *
                                                                               x_codes, I, M, I, gx, H, dbg_accx);
 }
 
+// fp32 form of a precomputed input projection: tab[m, r'] = k * (x_scale * s_wih[r] * gx[m, r'] + bias[r]),
+// r' the TILED_GATES position of source row r, k the exp2 constant of the row's gate.
+__global__ void gx_table_kernel(const int32_t *__restrict__ gx, const float *__restrict__ s_wih,
+                                const float *__restrict__ bias, float x_scale, int H, size_t n, float *__restrict__ tab)
+{
+    const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= n) return;
+    const int tr = (int)(idx % (size_t)(4 * H));
+    const int gt = tr & 3, j = qr_gates_cell(tr >> 4, (tr & 15) >> 2);
+    const float k = gt == 2 ? -2.885390081777927f : -1.4426950408889634f;
+    const int r = gt * H + j;
+    tab[idx] = (s_wih[r] * x_scale * k) * (float)gx[idx] + bias[r] * k;
+}
+
 __global__ void fill_zero_kernel(uint32_t *p, size_t n_words)
 {
     size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -544,6 +570,13 @@ qrnnt_status qr_check_lstm(const qrnnt_lstm *L)
     QR_REQUIRE(L->w_ih.cols == L->input_size && L->w_hh.cols == L->hidden_size, QRNNT_ERR_SHAPE);
     QR_REQUIRE(L->x_scale > 0.0f && L->h_scale > 0.0f && L->h_inv_scale > 0.0f, QRNNT_ERR_RANGE);
     return QRNNT_OK;
+}
+
+void qr_launch_gx_table(const qrnnt_lstm *L, const int32_t *gx, int M, float *tab, hipStream_t st)
+{
+    const size_t n = (size_t)M * 4 * L->hidden_size;
+    gx_table_kernel<<<(unsigned)((n + 255) / 256), 256, 0, st>>>(gx, L->w_ih.row_scale, L->bias, L->x_scale, L->hidden_size, n,
+                                                                  tab);
 }
 
 void qr_fill_lstm_weights(QrStepArgs &a, const qrnnt_lstm *L)
