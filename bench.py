@@ -193,6 +193,7 @@ def main():
                     if layer_idx == 0:
                         d["x_codes"], d["x_row"] = net.embed_codes, tok
                         d["gx"] = q.input_projection(L, net.embed_codes)[0]
+                        d["gx_table"] = q.input_table(L, d["gx"])
                         k_in = 0
                         byt += m.V * 4 * L.H * 4   # the table of per-token int32 sums
                     else:
@@ -207,7 +208,7 @@ def main():
             return groups
 
         # ---- decoding-round launches at 64 utterances x beam 16 = 1024 hypotheses (matrix-core bound)
-        names = ("lstm_step_pipe_kernel<USE_GX=true>: pred L1 + 2 x LM L1, input part from the token table",
+        names = ("lstm_step_pipe_kernel<USE_GX=true,TAB=true>: pred L1 + 2 x LM L1, input part from the token table",
                  "lstm_step_pipe_kernel<USE_GX=false>: 2 x LM L2")
         launches, tot_ops, tot_t = [], 0.0, 0.0
         for name, (grp, ops, byt) in zip(names, round_groups(B * W)):

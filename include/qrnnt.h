@@ -147,6 +147,10 @@ qrnnt_status qrnnt_lstm_step(const qrnnt_lstm *L, const int8_t *x_codes, const i
  * the step is looked up in it (row x_row ? x_row[n] : n) instead of contracted:
  * the same integer sums, e.g. one table row per vocabulary entry for a layer fed
  * by an embedding.  Either every step of a group has gx or none has.
+ * gx_table [device] fp32 [n_x_rows, 4H] or NULL: the same rows as written by
+ * qrnnt_input_table (scales and bias folded in); steps that have gx may add it,
+ * and a launch whose steps all have it uses it in place of gx where that is
+ * faster (many hypotheses).
  * steps [host] is read during the call only. */
 typedef struct {
     const qrnnt_lstm *L;
@@ -155,6 +159,7 @@ typedef struct {
     const uint8_t *active;  int32_t N;
     int8_t *h_next;  float *c_next;
     const int32_t *gx;
+    const float *gx_table;
 } qrnnt_step_desc;
 
 qrnnt_status qrnnt_lstm_step_group(const qrnnt_step_desc *steps, int32_t n_steps, void *stream);
@@ -196,6 +201,14 @@ qrnnt_status qrnnt_bilstm_layer(const qrnnt_lstm *fwd, const qrnnt_lstm *bwd, co
  * [M, 4H] in source row order, or NULL.  hidden_size % 16 == 0. */
 qrnnt_status qrnnt_input_projection(const qrnnt_lstm *L, const int8_t *x_codes, int32_t M, int32_t *gx,
                                     int32_t *dbg_accx, void *stream);
+
+/* fp32 form of M rows of an input projection gx (as written by
+ * qrnnt_input_projection): table[m, r'] = k * (x_scale * row_scale[r] * gx[m, r']
+ * + bias[r]) for the TILED_GATES position r' of row r, with k = -log2(e) for the
+ * sigmoid gates and -2 log2(e) for the tanh gate (the constants the cell feeds to
+ * exp2).  Consumed through qrnnt_step_desc.gx_table.  table [device] fp32
+ * [M, 4H], 16-byte aligned. */
+qrnnt_status qrnnt_input_table(const qrnnt_lstm *L, const int32_t *gx, int32_t M, float *table, void *stream);
 
 /* ---- joint network + log-softmax + Eq. 1 ---- */
 

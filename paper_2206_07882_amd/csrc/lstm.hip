@@ -672,7 +672,9 @@ extern "C" qrnnt_status qrnnt_lstm_step_group(const qrnnt_step_desc *steps, int3
         if (s != QRNNT_OK) return s;
         QR_REQUIRE((d.gx != nullptr) == (steps[0].gx != nullptr), QRNNT_ERR_RANGE);
         QR_REQUIRE(qr_aligned(d.gx, 16), QRNNT_ERR_ALIGN);
-        g.p[i].gx = d.gx;  g.p[i].ld_gx = 4 * (int64_t)d.L->hidden_size;
+        QR_REQUIRE(d.gx_table == nullptr || d.gx != nullptr, QRNNT_ERR_NULL);
+        QR_REQUIRE(qr_aligned(d.gx_table, 16), QRNNT_ERR_ALIGN);
+        g.p[i].gx = d.gx;  g.p[i].ld_gx = 4 * (int64_t)d.L->hidden_size;  g.p[i].tabf = d.gx_table;
     }
     qr_launch_lstm_step_group(g, steps[0].gx != nullptr, (hipStream_t)stream);
     return qr_launch_status();
@@ -685,6 +687,17 @@ void qr_launch_input_projection(const qrnnt_lstm *L, const int8_t *x_codes, int 
     // frames is worth more than a deeper ring (measured: 69 vs 74 us at 16000 x 1280 x 2560)
     if (M <= 256) launch_gx_pipe<4, 4, 3>(L, x_codes, M, gx, dbg_accx, st);
     else launch_gx_pipe<4, 4, 2>(L, x_codes, M, gx, dbg_accx, st);
+}
+
+extern "C" qrnnt_status qrnnt_input_table(const qrnnt_lstm *L, const int32_t *gx, int32_t M, float *table, void *stream)
+{
+    qrnnt_status s = qr_check_lstm(L);
+    if (s != QRNNT_OK) return s;
+    QR_REQUIRE(gx && table, QRNNT_ERR_NULL);
+    QR_REQUIRE(M > 0, QRNNT_ERR_SHAPE);
+    QR_REQUIRE(qr_aligned(gx, 16) && qr_aligned(table, 16), QRNNT_ERR_ALIGN);
+    qr_launch_gx_table(L, gx, M, table, (hipStream_t)stream);
+    return qr_launch_status();
 }
 
 extern "C" qrnnt_status qrnnt_input_projection(const qrnnt_lstm *L, const int8_t *x_codes, int32_t M, int32_t *gx,

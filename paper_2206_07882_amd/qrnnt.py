@@ -58,7 +58,7 @@ class CModel(C.Structure):
 
 EXPORTS = ["qrnnt_status_str", "qrnnt_abi_version", "qrnnt_pack_int4_bytes", "qrnnt_pack_int4", "qrnnt_unpack_int4",
            "qrnnt_quantize_act", "qrnnt_linear", "qrnnt_lstm_step", "qrnnt_lstm_layer_workspace", "qrnnt_lstm_layer",
-           "qrnnt_input_projection", "qrnnt_lstm_step_group",
+           "qrnnt_input_projection", "qrnnt_input_table", "qrnnt_lstm_step_group",
            "qrnnt_bilstm_layer_workspace", "qrnnt_bilstm_layer",
            "qrnnt_joint_fuse", "qrnnt_beam_step", "qrnnt_decode_workspace", "qrnnt_decode", "qrnnt_decode_ex"]
 
@@ -219,7 +219,7 @@ class CStepDesc(C.Structure):
     _fields_ = [("L", C.c_void_p), ("x_codes", C.c_void_p), ("x_row", C.c_void_p), ("n_x_rows", C.c_int32),
                 ("parent", C.c_void_p), ("h_prev", C.c_void_p), ("c_prev", C.c_void_p), ("n_slots", C.c_int32),
                 ("active", C.c_void_p), ("N", C.c_int32), ("h_next", C.c_void_p), ("c_next", C.c_void_p),
-                ("gx", C.c_void_p)]
+                ("gx", C.c_void_p), ("gx_table", C.c_void_p)]
 
 
 class StepGroup:
@@ -227,7 +227,7 @@ class StepGroup:
 
     def __init__(self, steps):
         """steps: list of dicts with keys L, x_codes, h_prev, c_prev, h_next, c_next, N and optional x_row, parent,
-        active, gx (the input projection of the rows of x_codes, see input_projection)."""
+        active, gx (the input projection of the rows of x_codes, see input_projection) and gx_table (input_table)."""
         self._keep = []
         self.n = len(steps)
         self.arr = (CStepDesc * self.n)()
@@ -237,7 +237,8 @@ class StepGroup:
             self._keep.append((cl, d))
             self.arr[i] = CStepDesc(C.addressof(cl), p(d["x_codes"]), p(d.get("x_row")), d["x_codes"].shape[0],
                                     p(d.get("parent")), p(d["h_prev"]), p(d["c_prev"]), d["h_prev"].shape[0],
-                                    p(d.get("active")), d["N"], p(d["h_next"]), p(d["c_next"]), p(d.get("gx")))
+                                    p(d.get("active")), d["N"], p(d["h_next"]), p(d["c_next"]), p(d.get("gx")),
+                                    p(d.get("gx_table")))
 
     def launch(self):
         _check(load().qrnnt_lstm_step_group(self.arr, C.c_int32(self.n), _stream()), "qrnnt_lstm_step_group")
@@ -253,6 +254,15 @@ def input_projection(L: Lstm, x_codes: torch.Tensor, gx: Optional[torch.Tensor] 
     _check(load().qrnnt_input_projection(C.byref(cl), _ptr(x_codes, torch.int8), C.c_int32(M), _ptr(gx, torch.int32),
                                          _ptr(acc), _stream()), "qrnnt_input_projection")
     return gx, acc
+
+
+def input_table(L: Lstm, gx: torch.Tensor) -> torch.Tensor:
+    """fp32 form of an input projection with scales, bias and exp2 constants folded in (qrnnt_input_table)."""
+    tab = torch.empty(gx.shape, dtype=torch.float32, device=gx.device)
+    cl = L.c()
+    _check(load().qrnnt_input_table(C.byref(cl), _ptr(gx, torch.int32), C.c_int32(gx.shape[0]), _ptr(tab), _stream()),
+           "qrnnt_input_table")
+    return tab
 
 
 def lstm_layer_workspace(L: Lstm, T: int, B: int) -> int:

@@ -233,7 +233,7 @@ def test_input_projection_exact(gpu_lib, I, H, M):
 
 
 @pytest.mark.parametrize("N,use_gx", [(16, False), (16, True), (48, True), (144, False), (144, True), (256, True),
-                                       (256, False)])
+                                       (256, False), (16, "table"), (144, "table"), (256, "table")])
 def test_lstm_step_group_parity(gpu_lib, N, use_gx):
     """Three independent steps in one launch (widths of the first layers of the
     prediction network and of two LMs, scaled down), inputs picked by token id from
@@ -258,6 +258,8 @@ def test_lstm_step_group_parity(gpu_lib, N, use_gx):
                  c_next=torch.empty((N, H), dtype=torch.float32, device=DEV))
         if use_gx:
             d["gx"] = q.input_projection(G, dev(emb))[0]
+        if use_gx == "table":   # the fp32 form with scales and bias folded in
+            d["gx_table"] = q.input_table(G, d["gx"])
         steps.append(d)
         refs.append(oracle.lstm_step(L, emb[tok], hp[parent], cp[parent], active=active, debug=True))
     q.StepGroup(steps).launch()
@@ -293,7 +295,8 @@ def test_lstm_step_group_full_size_sampled(gpu_lib):
                      c_next=torch.empty((N, H), dtype=torch.float32, device=DEV))
             if table:
                 emb = synth.codes(191 + i, (V, I), -7, 7)
-                d.update(x_codes=dev(emb), x_row=dev(tok), gx=q.input_projection(G, dev(emb))[0])
+                gx = q.input_projection(G, dev(emb))[0]
+                d.update(x_codes=dev(emb), x_row=dev(tok), gx=gx, gx_table=q.input_table(G, gx))
                 x_rows = emb[tok[rows]]
             else:
                 x = synth.codes(194 + i, (N, I), -7, 7)
