@@ -71,10 +71,10 @@ __global__ __launch_bounds__(256) void joint_fuse_kernel(const QrJointArgs a)
 #pragma unroll
     for (int mt = 0; mt < 4; ++mt)
 #pragma unroll
-        for (int i = 0; i < 4; ++i) sum += (mt * 16 + grp * 4 + i < a.V) ? expf(v[mt][i] - m) : 0.0f;
+        for (int i = 0; i < 4; ++i) sum += (mt * 16 + grp * 4 + i < a.V) ? qr_exp(v[mt][i] - m) : 0.0f;
     sum += __shfl_xor(sum, 16);
     sum += __shfl_xor(sum, 32);
-    const float lse = m + logf(sum);
+    const float lse = m + qr_log(sum);
     if (!nv) return;
 #pragma unroll
     for (int mt = 0; mt < 4; ++mt)
@@ -196,10 +196,10 @@ __global__ __launch_bounds__(256) void joint_route_kernel(const QrJointArgs a, c
 #pragma unroll
             for (int mt = 0; mt < 4; ++mt)
 #pragma unroll
-                for (int i = 0; i < 4; ++i) sum += (mt * 16 + grp * 4 + i < V) ? expf(v[mt][i] - m) : 0.0f;
+                for (int i = 0; i < 4; ++i) sum += (mt * 16 + grp * 4 + i < V) ? qr_exp(v[mt][i] - m) : 0.0f;
             sum += __shfl_xor(sum, 16);
             sum += __shfl_xor(sum, 32);
-            const float lse = m + logf(sum);
+            const float lse = m + qr_log(sum);
 #pragma unroll
             for (int mt = 0; mt < 4; ++mt)
 #pragma unroll

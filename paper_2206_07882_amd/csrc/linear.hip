@@ -65,10 +65,10 @@ __global__ __launch_bounds__(256) void linear_head_kernel(const QrLinearGroup g)
 #pragma unroll
         for (int mt = 0; mt < 4; ++mt)
 #pragma unroll
-            for (int i = 0; i < 4; ++i) sum += (mt * 16 + grp * 4 + i < a.rows) ? expf(v[mt][i] - mx) : 0.0f;
+            for (int i = 0; i < 4; ++i) sum += (mt * 16 + grp * 4 + i < a.rows) ? qr_exp(v[mt][i] - mx) : 0.0f;
         sum += __shfl_xor(sum, 16);
         sum += __shfl_xor(sum, 32);
-        lse = mx + logf(sum);
+        lse = mx + qr_log(sum);
     }
     if (!nv) return;
     const bool wide = (a.rows & 3) == 0 && ((uintptr_t)a.y & 15) == 0;   // rows of y are 16-byte aligned: one 128-bit store per lane and row tile

@@ -78,6 +78,10 @@ __device__ __forceinline__ float qr_tanh(float v)
 // sigmoid(v) given u = -log2(e) * v (the constant folded into whatever produced u)
 __device__ __forceinline__ float qr_sigmoid_scaled(float u) { return __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(u)); }
 
+// exp and log on the hardware exp2 / log2 units (about 1 ulp each), for the log-softmax epilogues
+__device__ __forceinline__ float qr_exp(float v) { return __builtin_amdgcn_exp2f(1.4426950408889634f * v); }
+__device__ __forceinline__ float qr_log(float v) { return 0.6931471805599453f * __builtin_amdgcn_logf(v); }
+
 // Symmetric 4-bit quantizer: clamp(rne(x * inv_step)), product in fp32.
 __device__ __forceinline__ int qr_quant4(float x, float inv_step)
 {
