@@ -27,11 +27,46 @@ __device__ __forceinline__ void select_w_regs(const float *__restrict__ sc, cons
     qr_block_select_from_regs<PER>(val, c0, W, tid, slots, my_c, my_v);
 }
 
+// Up to 64 * PER candidates held by one wave, lane l owning indices l*PER .. l*PER+PER-1: the pruned
+// rank-based selection of select.h.  Returns false when more than 64 candidates survive its threshold.
+template <int PER>
+__device__ __forceinline__ bool select_w_pruned(const float *__restrict__ sc, const float *__restrict__ fu, int W, int V,
+                                                int blank, int force_blank, int lane, unsigned *scratch, int &my_c,
+                                                float &my_v)
+{
+    const int C = W * V;
+    float val[PER];
+    const int c0 = lane * PER;
+    int w = c0 / V, k = c0 - w * V;
+#pragma unroll
+    for (int i = 0; i < PER; ++i) {
+        const int c = c0 + i;
+        float v = -INFINITY;
+        if (c < C && (!force_blank || k == blank)) v = (sc[w] + fu[c]) + 0.0f;   // + 0: -0 becomes +0, one key per value
+        val[i] = v;
+        if (++k == V) { k = 0; ++w; }
+    }
+    auto index_of = [&](int s) { return c0 + s; };
+    return qr_select_pruned<PER>(val, index_of, W, lane, scratch, (int *)scratch + 64, my_c, my_v);
+}
+
 // Thread r < W ends up with pick r.  Uniform control flow across the workgroup.
 __device__ __forceinline__ void select_w(const float *__restrict__ sc, const float *__restrict__ fu, int W, int V,
                                          int blank, int force_blank, int tid, unsigned *slots, int &my_c, float &my_v)
 {
     const int C = W * V;   // uniform
+    // fast path: wave 0 alone, candidates in its registers (the other waves only meet it at the barrier)
+    __shared__ unsigned pruned_scratch[128];
+    __shared__ int pruned_ok;
+    if (C <= 64 * 16) {
+        if (tid < 64) {
+            const bool ok = C <= 64 * 4 ? select_w_pruned<4>(sc, fu, W, V, blank, force_blank, tid, pruned_scratch, my_c, my_v)
+                                         : select_w_pruned<16>(sc, fu, W, V, blank, force_blank, tid, pruned_scratch, my_c, my_v);
+            if (tid == 0) pruned_ok = ok ? 1 : 0;
+        }
+        __syncthreads();
+        if (pruned_ok) return;   // uniform
+    }
     if (C <= 256) select_w_regs<1>(sc, fu, W, V, blank, force_blank, tid, slots, my_c, my_v);
     else if (C <= 256 * 3) select_w_regs<3>(sc, fu, W, V, blank, force_blank, tid, slots, my_c, my_v);
     else if (C <= 256 * 6) select_w_regs<6>(sc, fu, W, V, blank, force_blank, tid, slots, my_c, my_v);
