@@ -164,6 +164,22 @@ def main():
                                        "with beam 16 the 16 picks of a round always include labels, so nothing is skipped "
                                        "and the flag costs its loads; greedy search (beam 1) on this model skips most rounds"}
         del feats, ws_dec, e, es, out
+        # the same pipeline with the layer shapes of the paper's Sec. 2 (340 features, prediction network and
+        # source LM 1 x 768, external LM 2 x 2048 + bottleneck 256, fusion weights 0.7 / 0.5 / 0.2), all 4-bit
+        m5 = synth.make_model(5)
+        enc5 = gmodel.Encoder(m5, dev)
+        G5 = gmodel.model_from_float(m5, dev)
+        feats5 = torch.from_numpy(synth.features(5, T, B, m5.feat_dim)).to(dev)
+        ws5 = torch.empty(q.decode_workspace(G5, T, B, W, MAX_SYM), dtype=torch.uint8, device=dev)
+        _, e5 = enc5.forward(feats5)
+        t_enc5 = timed(lambda: enc5.forward(feats5), 1, warm=0)
+        t_dec5 = timed(lambda: q.decode(G5, e5, W, MAX_SYM, max_len=T * MAX_SYM, workspace=ws5), 1, warm=1)
+        extra["paper_shapes"] = {"workload": f"Sec. 2 shapes, all 4-bit: 6x bi-LSTM-640 over 340 features, pred 1x768, source LM "
+                                             f"1x768, external LM 2x2048 + bottleneck 256, beam {W}, max {MAX_SYM} labels/frame, "
+                                             f"B={B} x T={T}",
+                                 "encoder_ms": t_enc5 * 1e3, "decoder_ms": t_dec5 * 1e3,
+                                 "rtf": (t_enc5 + t_dec5) / audio}
+        del m5, enc5, G5, feats5, ws5, e5
 
     # ---------------------------------------------------------------- kernel legs
     if args.leg in ("all", "kernels"):

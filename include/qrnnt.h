@@ -123,6 +123,13 @@ qrnnt_status qrnnt_quantize_act(const float *x, int64_t n, float inv_scale, int8
 qrnnt_status qrnnt_linear(const qrnnt_qmat *w, const float *bias, float a_scale, const int8_t *a, int32_t N,
                           int32_t log_softmax, float *y, int32_t *dbg_acc, void *stream);
 
+/* qrnnt_linear feeding another quantized linear layer (Sec. 3.2: linear layers
+ * quantize their inputs): q[n,r] = clamp(rne(y[n,r] * inv_scale), -8, 7) with y
+ * as in qrnnt_linear (no log-softmax); the fp32 y is not stored.  q [device]
+ * [N, rows] int8.  This is the bottleneck layer of the external LM (Sec. 2). */
+qrnnt_status qrnnt_linear_quant(const qrnnt_qmat *w, const float *bias, float a_scale, const int8_t *a, int32_t N,
+                                float inv_scale, int8_t *q, void *stream);
+
 /* ---- LSTM: one step for a set of hypotheses (Sec. 3.2, Sec. 3.4) ---- */
 
 /* For n in [0,N): input row x_codes[x_row ? x_row[n] : n] (length I), previous
@@ -245,15 +252,23 @@ qrnnt_status qrnnt_beam_step(const float *score, const float *fused, int32_t B, 
 
 /* Embedding -> quantizer -> stacked LSTM steps -> quantized linear layer: the
  * prediction network (log_softmax = 0, output = the joint's prediction input)
- * or a language model (log_softmax = 1, output = log-probabilities). */
+ * or a language model (log_softmax = 1, output = log-probabilities).
+ * Optional bottleneck (Sec. 2, the external LM: LSTM stack -> bottleneck ->
+ * output layer), present when mid.packed != NULL: the top hidden codes go
+ * through mid (qrnnt_linear_quant with a_scale = out_a_scale, quantizer
+ * mid_inv_scale; no activation function, the paper names none) and `out` then
+ * reads those codes with step mid_scale. */
 typedef struct {
     const int8_t *embed_codes;  /* [device] [V, E] embedding rows already quantized (FIX boundary, Sec. 3.2) */
     int32_t n_layers;           /* 1..QRNNT_MAX_LAYERS; layer[0].input_size = E */
     qrnnt_lstm layer[QRNNT_MAX_LAYERS];
-    qrnnt_qmat out;             /* TILED, [out_rows, H_top] */
+    qrnnt_qmat out;             /* TILED, [out_rows, H_top] ([out_rows, M] behind a bottleneck) */
     const float *out_bias;      /* [device] [out_rows] or NULL */
     float out_a_scale;          /* step of the top layer's hidden codes */
     int32_t log_softmax;
+    qrnnt_qmat mid;             /* TILED, [M, H_top], M % 16 == 0; packed == NULL: no bottleneck */
+    const float *mid_bias;      /* [device] [M] or NULL */
+    float mid_scale, mid_inv_scale; /* alpha/7 and 7/alpha of the quantizer on the bottleneck's output */
 } qrnnt_net;
 
 typedef struct {

@@ -82,7 +82,8 @@ class _CLinear(C.Structure):
 
 class _CNet(C.Structure):
     _fields_ = [("embed", C.c_void_p), ("E", C.c_int32), ("L", C.c_int32), ("inv_s_e", C.c_float),
-                ("layer", _CLstm * MAX_LAYERS), ("out", _CLinear), ("log_softmax", C.c_int32)]
+                ("layer", _CLstm * MAX_LAYERS), ("out", _CLinear), ("log_softmax", C.c_int32),
+                ("has_mid", C.c_int32), ("mid", _CLinear), ("inv_s_mid", C.c_float)]
 
 
 class _CModel(C.Structure):
@@ -314,7 +315,11 @@ def beam_step(score, fused, blank=0, force_blank=False):
 class Net:
     """Embedding -> quantizer -> stacked LSTM steps -> linear (-> log-softmax)."""
 
-    def __init__(self, embed, alpha_e, layers, out: Linear, log_softmax: bool):
+    def __init__(self, embed, alpha_e, layers, out: Linear, log_softmax: bool, mid: Linear = None, alpha_mid=None):
+        """mid: optional bottleneck layer between the LSTM stack and out (Sec. 2, external LM); its
+        output is quantized with boundary alpha_mid and out.s_a must be alpha_mid / 7."""
+        self.mid = mid
+        self.inv_s_mid = np.float32(0.0) if mid is None else np.float32(np.float32(7.0) / np.float32(alpha_mid))
         self.embed = _arr(embed, np.float32)
         self.E = self.embed.shape[1]
         self.inv_s_e = np.float32(np.float32(7.0) / np.float32(alpha_e))
@@ -333,6 +338,10 @@ class Net:
             n.layer[i] = l.c()
         n.out = self.out.c()
         n.log_softmax = 1 if self.log_softmax else 0
+        n.has_mid = 0 if self.mid is None else 1
+        if self.mid is not None:
+            n.mid = self.mid.c()
+            n.inv_s_mid = float(self.inv_s_mid)
         return n
 
 

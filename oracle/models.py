@@ -28,6 +28,11 @@ def net_from_float(f, alpha_e, log_softmax):
     layers = []
     for i, lf in enumerate(f.layers):
         layers.append(lstm_from_float(lf, s_e if i == 0 else S_H))
+    mid = getattr(f, "mid", None)
+    if mid is not None:   # bottleneck layer (Sec. 2): its output is quantized with boundary alpha_mid
+        s_m, _ = act_scale(f.alpha_mid)
+        return Net(f.embed, alpha_e, layers, Linear.from_float(f.out.w, f.out.bias, s_m), log_softmax,
+                   mid=Linear.from_float(mid.w, mid.bias, S_H), alpha_mid=f.alpha_mid)
     out = Linear.from_float(f.out.w, f.out.bias, S_H)
     return Net(f.embed, alpha_e, layers, out, log_softmax)
 

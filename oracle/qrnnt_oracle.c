@@ -414,7 +414,11 @@ void oq_beam_step(const float *score, const float *fused, int B, int W, int V, i
 /* A language model or the prediction network: embedding lookup, the symmetric
  * quantizer on the embedding (FIX boundary, Sec. 3.2), L stacked quantized
  * LSTM steps, one quantized linear layer.  The LM applies log-softmax to the
- * linear output, the prediction network does not. */
+ * linear output, the prediction network does not.
+ * The external LM of Sec. 2 has a bottleneck layer between its LSTM stack and
+ * its output layer (has_mid): a second quantized linear layer whose fp32 output
+ * is quantized (linear layers quantize their inputs, Sec. 3.2) and feeds `out`.
+ * The paper names no activation for it; none is applied. */
 typedef struct {
     const float *embed;   /* [V, E] fp32 */
     int32_t E, L;
@@ -422,6 +426,9 @@ typedef struct {
     oq_lstm_t layer[OQ_MAX_LAYERS];
     oq_linear_t out;
     int32_t log_softmax;  /* 1: LM, 0: prediction network */
+    int32_t has_mid;
+    oq_linear_t mid;      /* [M, H_top]; then out is [rows, M] and out.s_a the step of the codes of mid's output */
+    float inv_s_mid;      /* 7/alpha of the quantizer on mid's output */
 } oq_net_t;
 
 typedef struct {
@@ -472,7 +479,16 @@ static void net_advance(const oq_net_t *net, const net_state *src, int token, ne
                      dst->h[l], dst->c[l], NULL, NULL, NULL, NULL);
         memcpy(xin, dst->h[l], (size_t)net->layer[l].H);
     }
-    oq_linear(&net->out, xin, 1, dst->y, NULL);
+    if (net->has_mid) {
+        float *ym = (float *)malloc((size_t)net->mid.rows * sizeof(float));
+        int8_t *qm = (int8_t *)malloc((size_t)net->mid.rows);
+        oq_linear(&net->mid, xin, 1, ym, NULL);
+        oq_quantize_sym4(ym, net->mid.rows, net->inv_s_mid, qm);
+        oq_linear(&net->out, qm, 1, dst->y, NULL);
+        free(ym); free(qm);
+    } else {
+        oq_linear(&net->out, xin, 1, dst->y, NULL);
+    }
     if (net->log_softmax) oq_log_softmax(dst->y, 1, net->out.rows, dst->y);
     free(xin);
 }

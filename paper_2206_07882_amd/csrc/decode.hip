@@ -17,6 +17,7 @@ struct NetBuf {
     float *y;                      // [NB][N][out_rows]
     int32_t *gx0;                  // [V][4*H0]: input projection of layer 0 for every token
     float *tab0;                   // the same as fp32 pre-activation contributions (scales, bias folded in)
+    int8_t *mid_q;                 // [N][M]: codes of the bottleneck's output (consumed in the same advance)
 };
 
 struct Plan {
@@ -62,6 +63,7 @@ void make_plan(const qrnnt_model *m, int T, int B, int W, int max_sym, void *ws,
         p.net[k].y = cv.take<float>(NB * N * net->out.rows);
         p.net[k].gx0 = cv.take<int32_t>((size_t)m->V * 4 * net->layer[0].hidden_size);
         p.net[k].tab0 = cv.take<float>((size_t)m->V * 4 * net->layer[0].hidden_size);
+        p.net[k].mid_q = net->mid.packed ? cv.take<int8_t>(N * net->mid.rows) : nullptr;
     }
     p.score = cv.take<float>(NB * N);
     p.node = cv.take<int32_t>(NB * N);
@@ -157,7 +159,15 @@ qrnnt_status check_net(const qrnnt_net *net, int V, int out_rows)
     }
     qrnnt_status s = qr_check_qmat(&net->out, QRNNT_LAYOUT_TILED);
     if (s != QRNNT_OK) return s;
-    QR_REQUIRE(net->out.cols == net->layer[net->n_layers - 1].hidden_size, QRNNT_ERR_SHAPE);
+    if (net->mid.packed) {
+        s = qr_check_qmat(&net->mid, QRNNT_LAYOUT_TILED);
+        if (s != QRNNT_OK) return s;
+        QR_REQUIRE(net->mid.cols == net->layer[net->n_layers - 1].hidden_size, QRNNT_ERR_SHAPE);
+        QR_REQUIRE(net->mid.rows % 16 == 0 && net->out.cols == net->mid.rows, QRNNT_ERR_SHAPE);
+        QR_REQUIRE(net->mid_scale > 0.0f && net->mid_inv_scale > 0.0f, QRNNT_ERR_RANGE);
+    } else {
+        QR_REQUIRE(net->out.cols == net->layer[net->n_layers - 1].hidden_size, QRNNT_ERR_SHAPE);
+    }
     QR_REQUIRE(net->out.rows == out_rows, QRNNT_ERR_SHAPE);
     QR_REQUIRE(!net->log_softmax || net->out.rows <= 64, QRNNT_ERR_UNSUPPORTED);
     QR_REQUIRE(net->out_a_scale > 0.0f, QRNNT_ERR_RANGE);
@@ -223,22 +233,39 @@ void advance_nets(const qrnnt_model *m, const Plan &p, int src, int dst, int n_e
         }
         qr_launch_lstm_step_group(g, l == 0, st);
     }
-    QrLinearGroup lg;
-    lg.n = 0;
-    lg.gate = gate;
+    // Output layers: one grouped launch; a network with a bottleneck sends that layer (fused with the
+    // quantizer of its output) in the first launch and its output layer in a second one.
+    QrLinearGroup lg, lg2;
+    lg.n = lg2.n = 0;
+    lg.gate = lg2.gate = gate;
     for (int k = 0; k < 3; ++k) {
         if (!net_used(m, k)) continue;
         const qrnnt_net *net = net_of(m, k);
         const int top = net->n_layers - 1;
-        QrLinearArgs &la = lg.p[lg.n++];
-        la = QrLinearArgs{};
-        la.w = (const v4i *)net->out.packed;
-        la.nkc = qr_round_up(net->out.cols, QRNNT_KCHUNK) / QRNNT_KCHUNK;
-        la.rows = net->out.rows;  la.s_w = net->out.row_scale;  la.bias = net->out_bias;  la.a_scale = net->out_a_scale;
-        la.act = p.net[k].h[top] + (size_t)dst * N * net->out.cols;  la.K = net->out.cols;  la.N = p.N;
-        la.y = p.net[k].y + (size_t)dst * N * net->out.rows;  la.log_softmax = net->log_softmax;
+        const bool has_mid = net->mid.packed != nullptr;
+        QrLinearArgs out = QrLinearArgs{};
+        out.w = (const v4i *)net->out.packed;
+        out.nkc = qr_round_up(net->out.cols, QRNNT_KCHUNK) / QRNNT_KCHUNK;
+        out.rows = net->out.rows;  out.s_w = net->out.row_scale;  out.bias = net->out_bias;
+        out.K = net->out.cols;  out.N = p.N;
+        out.y = p.net[k].y + (size_t)dst * N * net->out.rows;  out.log_softmax = net->log_softmax;
+        if (has_mid) {
+            QrLinearArgs &la = lg.p[lg.n++];
+            la = QrLinearArgs{};
+            la.w = (const v4i *)net->mid.packed;
+            la.nkc = qr_round_up(net->mid.cols, QRNNT_KCHUNK) / QRNNT_KCHUNK;
+            la.rows = net->mid.rows;  la.s_w = net->mid.row_scale;  la.bias = net->mid_bias;  la.a_scale = net->out_a_scale;
+            la.act = p.net[k].h[top] + (size_t)dst * N * net->mid.cols;  la.K = net->mid.cols;  la.N = p.N;
+            la.q_out = p.net[k].mid_q;  la.q_inv = net->mid_inv_scale;
+            out.a_scale = net->mid_scale;  out.act = p.net[k].mid_q;
+            lg2.p[lg2.n++] = out;
+        } else {
+            out.a_scale = net->out_a_scale;  out.act = p.net[k].h[top] + (size_t)dst * N * net->out.cols;
+            lg.p[lg.n++] = out;
+        }
     }
     qr_launch_linear_group(lg, st);
+    if (lg2.n) qr_launch_linear_group(lg2, st);
 }
 
 }  // namespace

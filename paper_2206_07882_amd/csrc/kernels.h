@@ -41,6 +41,7 @@ struct QrLinearArgs {
     const int8_t *act;  int K, N;
     float *y;  int32_t *dbg_acc;
     int log_softmax;
+    int8_t *q_out;  float q_inv;       // optional: codes of y under the next layer's input quantizer, [N, rows]
 };
 
 struct QrLinearGroup {

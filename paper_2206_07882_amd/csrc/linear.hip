@@ -71,6 +71,24 @@ __global__ __launch_bounds__(256) void linear_head_kernel(const QrLinearGroup g)
         lse = mx + qr_log(sum);
     }
     if (!nv) return;
+    if (a.q_out) {   // the fp32 result goes straight through the quantizer of the layer that consumes it
+        const bool wide_q = (a.rows & 3) == 0 && ((uintptr_t)a.q_out & 3) == 0;
+#pragma unroll
+        for (int mt = 0; mt < 4; ++mt) {
+            const int r0 = (rt0 + mt) * 16 + grp * 4;
+            unsigned word = 0;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) word |= (unsigned)(qr_quant4(v[mt][i] - lse, a.q_inv) & 0xFF) << (8 * i);
+            if (wide_q) {
+                if (r0 < a.rows) *(unsigned *)(a.q_out + (int64_t)n * a.rows + r0) = word;
+            } else {
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    if (r0 + i < a.rows) a.q_out[(int64_t)n * a.rows + r0 + i] = (int8_t)(word >> (8 * i));
+            }
+        }
+        if (!a.y) return;
+    }
     const bool wide = (a.rows & 3) == 0 && ((uintptr_t)a.y & 15) == 0;   // rows of y are 16-byte aligned: one 128-bit store per lane and row tile
 #pragma unroll
     for (int mt = 0; mt < 4; ++mt) {
@@ -105,6 +123,23 @@ void qr_launch_linear(const QrLinearArgs &a, hipStream_t st)
     g.n = 1;
     g.gate = nullptr;
     qr_launch_linear_group(g, st);
+}
+
+extern "C" qrnnt_status qrnnt_linear_quant(const qrnnt_qmat *w, const float *bias, float a_scale, const int8_t *a, int32_t N,
+                                           float inv_scale, int8_t *q, void *stream)
+{
+    qrnnt_status s = qr_check_qmat(w, QRNNT_LAYOUT_TILED);
+    if (s != QRNNT_OK) return s;
+    QR_REQUIRE(a != nullptr && q != nullptr, QRNNT_ERR_NULL);
+    QR_REQUIRE(N > 0 && w->cols % 16 == 0, QRNNT_ERR_SHAPE);
+    QR_REQUIRE(a_scale > 0.0f && inv_scale > 0.0f, QRNNT_ERR_RANGE);
+    QR_REQUIRE(qr_aligned(a, 16), QRNNT_ERR_ALIGN);
+    QrLinearArgs la = {};
+    la.w = (const v4i *)w->packed;  la.nkc = qr_round_up(w->cols, QRNNT_KCHUNK) / QRNNT_KCHUNK;  la.rows = w->rows;
+    la.s_w = w->row_scale;  la.bias = bias;  la.a_scale = a_scale;
+    la.act = a;  la.K = w->cols;  la.N = N;  la.q_out = q;  la.q_inv = inv_scale;
+    qr_launch_linear(la, (hipStream_t)stream);
+    return qr_launch_status();
 }
 
 extern "C" qrnnt_status qrnnt_linear(const qrnnt_qmat *w, const float *bias, float a_scale, const int8_t *a, int32_t N,

@@ -19,7 +19,7 @@ extern "C" const char *qrnnt_status_str(qrnnt_status s)
     return "unknown status";
 }
 
-extern "C" uint32_t qrnnt_abi_version(void) { return 1u; }
+extern "C" uint32_t qrnnt_abi_version(void) { return 2u; }
 
 extern "C" size_t qrnnt_pack_int4_bytes(int32_t rows, int32_t cols, int32_t layout)
 {

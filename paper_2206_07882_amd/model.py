@@ -36,6 +36,12 @@ def net_from_float(f, alpha_e: float, log_softmax: bool, device="cuda:0") -> q.N
     embed_codes = q.quantize_act(_dev(f.embed, device), inv_e)
     layers = [lstm_from_float(lf, s_e if i == 0 else S_H, device) for i, lf in enumerate(f.layers)]
     out = q.pack_int4(_dev(f.out.w, device), q.LAYOUT_TILED)
+    mid = getattr(f, "mid", None)
+    if mid is not None:   # bottleneck between the LSTM stack and the output layer (Sec. 2, external LM)
+        s_m, inv_m = act_scale(f.alpha_mid)
+        return q.Net(embed_codes, layers, out, _dev(f.out.bias, device), S_H, log_softmax,
+                     mid=q.pack_int4(_dev(mid.w, device), q.LAYOUT_TILED), mid_bias=_dev(mid.bias, device),
+                     mid_scale=s_m, mid_inv_scale=inv_m)
     return q.Net(embed_codes, layers, out, _dev(f.out.bias, device), S_H, log_softmax)
 
 

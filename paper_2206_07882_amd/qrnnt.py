@@ -46,7 +46,8 @@ MAX_LAYERS = 4
 
 class CNet(C.Structure):
     _fields_ = [("embed_codes", C.c_void_p), ("n_layers", C.c_int32), ("layer", CLstm * MAX_LAYERS), ("out", CQMat),
-                ("out_bias", C.c_void_p), ("out_a_scale", C.c_float), ("log_softmax", C.c_int32)]
+                ("out_bias", C.c_void_p), ("out_a_scale", C.c_float), ("log_softmax", C.c_int32),
+                ("mid", CQMat), ("mid_bias", C.c_void_p), ("mid_scale", C.c_float), ("mid_inv_scale", C.c_float)]
 
 
 class CModel(C.Structure):
@@ -57,7 +58,7 @@ class CModel(C.Structure):
 
 
 EXPORTS = ["qrnnt_status_str", "qrnnt_abi_version", "qrnnt_pack_int4_bytes", "qrnnt_pack_int4", "qrnnt_unpack_int4",
-           "qrnnt_quantize_act", "qrnnt_linear", "qrnnt_lstm_step", "qrnnt_lstm_layer_workspace", "qrnnt_lstm_layer",
+           "qrnnt_quantize_act", "qrnnt_linear", "qrnnt_linear_quant", "qrnnt_lstm_step", "qrnnt_lstm_layer_workspace", "qrnnt_lstm_layer",
            "qrnnt_input_projection", "qrnnt_input_table", "qrnnt_lstm_step_group",
            "qrnnt_bilstm_layer_workspace", "qrnnt_bilstm_layer",
            "qrnnt_joint_fuse", "qrnnt_beam_step", "qrnnt_decode_workspace", "qrnnt_decode", "qrnnt_decode_ex"]
@@ -164,6 +165,16 @@ def linear(w: QMat, bias: Optional[torch.Tensor], a_scale: float, a: torch.Tenso
                                C.c_int32(N), C.c_int32(1 if log_softmax else 0), _ptr(y), _ptr(acc), _stream()),
            "qrnnt_linear")
     return (y, acc) if want_acc else y
+
+
+def linear_quant(w: QMat, bias: Optional[torch.Tensor], a_scale: float, a: torch.Tensor, inv_scale: float) -> torch.Tensor:
+    N = a.shape[0]
+    q = torch.empty((N, w.rows), dtype=torch.int8, device=a.device)
+    cw = w.c()
+    _check(load().qrnnt_linear_quant(C.byref(cw), _ptr(bias, torch.float32), C.c_float(a_scale), _ptr(a, torch.int8),
+                                     C.c_int32(N), C.c_float(inv_scale), _ptr(q, torch.int8), _stream()),
+           "qrnnt_linear_quant")
+    return q
 
 
 class Lstm:
@@ -360,9 +371,11 @@ class Net:
     stacked LSTM layers, quantized output layer."""
 
     def __init__(self, embed_codes: torch.Tensor, layers, out: QMat, out_bias: Optional[torch.Tensor],
-                 out_a_scale: float, log_softmax: bool):
+                 out_a_scale: float, log_softmax: bool, mid: Optional[QMat] = None,
+                 mid_bias: Optional[torch.Tensor] = None, mid_scale: float = 0.0, mid_inv_scale: float = 0.0):
         self.embed_codes, self.layers, self.out, self.out_bias = embed_codes, list(layers), out, out_bias
         self.out_a_scale, self.log_softmax = float(out_a_scale), bool(log_softmax)
+        self.mid, self.mid_bias, self.mid_scale, self.mid_inv_scale = mid, mid_bias, float(mid_scale), float(mid_inv_scale)
 
     def c(self) -> CNet:
         n = CNet()
@@ -374,6 +387,10 @@ class Net:
         n.out_bias = None if self.out_bias is None else self.out_bias.data_ptr()
         n.out_a_scale = self.out_a_scale
         n.log_softmax = 1 if self.log_softmax else 0
+        if self.mid is not None:
+            n.mid = self.mid.c()
+            n.mid_bias = None if self.mid_bias is None else self.mid_bias.data_ptr()
+            n.mid_scale, n.mid_inv_scale = self.mid_scale, self.mid_inv_scale
         return n
 
 

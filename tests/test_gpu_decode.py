@@ -104,6 +104,39 @@ def test_decode_full_width_networks_128_hypotheses(gpu_lib):
     _compare_beams(got, ref)
 
 
+@pytest.mark.parametrize("B,W,max_sym,T", [(3, 4, 2, 8), (5, 16, 3, 5)])
+def test_decode_with_bottleneck_and_unequal_depths(gpu_lib, B, W, max_sym, T):
+    """Networks of unequal depth and an external LM with a bottleneck layer (Sec. 2) on the tiny
+    configuration: source LM 1 layer, external LM 2 layers + bottleneck 16."""
+    from paper_2206_07882_amd import model as gmodel
+    m = synth.make_model(0, weight_std=0.5)
+    rng = np.random.default_rng(77)
+    m.lm_ext = synth._net(rng, m.V, 64, 64, 2, m.V, 0.5, mid=16)
+    m.lm_ext.alpha_mid = 2.0
+    m.rho = 0.2
+    e = synth.normal(300 + B, (T, B, m.J), 1.0)
+    ref = oracle.decode(omodels.model_from_float(m), e, W, max_sym)
+    got = gpu_lib.decode(gmodel.model_from_float(m, DEV), dev(e), W, max_sym)
+    _compare_beams(got, ref)
+    assert (ref[1] > 0).any()
+
+
+def test_decode_paper_shapes_small_batch(gpu_lib):
+    """The layer shapes of Sec. 2 (prediction network and source LM 1 x 768 over a padded 10-dimensional
+    embedding, external LM 2 x 2048 + bottleneck 256, fusion weights 0.7 / 0.5 / 0.2) on a short, narrow
+    problem the oracle finishes in seconds; once at 8 hypotheses (weight-streaming step kernel) and once
+    at 128 (tiled step kernel)."""
+    from paper_2206_07882_amd import model as gmodel
+    m = synth.make_model(5, enc_layers=1)
+    M = omodels.model_from_float(m)
+    G = gmodel.model_from_float(m, DEV)
+    for (T, B, W, max_sym) in ((4, 2, 4, 2), (2, 8, 16, 1)):
+        e = synth.normal(310 + B, (T, B, m.J), 1.0)
+        ref = oracle.decode(M, e, W, max_sym)
+        got = gpu_lib.decode(G, dev(e), W, max_sym)
+        _compare_beams(got, ref)
+
+
 def test_decode_benchmark_shape_sampled_utterances(gpu_lib):
     """The decoder in the launch configuration the benchmark times (64 utterances x beam 16 = 1024
     hypotheses, at most 4 labels per frame, full layer widths), on a few frames.  Utterances do not

@@ -143,6 +143,29 @@ def test_linear_parity(gpu_lib, rows, cols, N, lsm):
         assert_rel(host(y), ry, "linear y")
 
 
+@pytest.mark.parametrize("rows,cols,N", [(256, 2048, 40), (16, 64, 3), (48, 128, 17), (30, 96, 33)])
+def test_linear_quant_parity(gpu_lib, rows, cols, N):
+    """Linear layer fused with the quantizer of the layer it feeds (the bottleneck of the external LM,
+    Sec. 2): codes must equal the oracle's quantizer applied to the oracle's linear output, except
+    where the fp32 result sits on a rounding tie (then one code apart)."""
+    q = gpu_lib
+    w = synth.normal(61 + rows, (rows, cols), 1.0 / np.sqrt(cols))
+    b = synth.normal(62 + rows, (rows,), 0.1)
+    a = synth.codes(63 + N, (N, cols), -8, 7)
+    P = oracle.Linear.from_float(w, b, S_H)
+    m = q.pack_int4(dev(w), q.LAYOUT_TILED)
+    inv = float(np.float32(7.0) / np.float32(0.6))     # boundary inside the output range: the clamp is exercised
+    got = host(q.linear_quant(m, dev(b), S_H, dev(a), inv))
+    ry = oracle.linear(P, a)
+    ref = oracle.quant_sym4(ry, inv)
+    assert got.min() == -8 and got.max() == 7
+    diff = got.astype(np.int32) - ref
+    bad = np.nonzero(diff)
+    assert len(bad[0]) <= max(1, got.size // 10000)
+    t = ry[bad].astype(np.float64) * inv
+    assert np.all(np.abs(diff[bad]) == 1) and np.all(np.abs(np.abs(t - np.floor(t)) - 0.5) < 1e-3)
+
+
 # ------------------------------------------------------------------ LSTM step
 
 def _lstm_pair(q, seed, I, H, s_x, std=None):

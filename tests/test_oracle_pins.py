@@ -425,6 +425,46 @@ def test_net_run_matches_manual_steps():
     assert np.allclose(np.exp(y.astype(np.float64)).sum(1), 1, atol=1e-6)
 
 
+def test_net_bottleneck_against_float_restatement():
+    # Sec. 2 (external LM): LSTM stack -> bottleneck -> output layer -> log-softmax.  The network with a
+    # bottleneck must equal, at every step, the same LSTM stack followed by a numpy restatement of the
+    # two dequantized matrix products with the quantizer between them.
+    rng = np.random.default_rng(33)
+    V, E, H, M = 7, 16, 32, 16
+    embed = (rng.standard_normal((V, E)) * 0.5).astype(np.float32)
+    L = oracle.Lstm.from_float((rng.standard_normal((4 * H, E)) * 0.3).astype(np.float32),
+                               (rng.standard_normal((4 * H, H)) * 0.3).astype(np.float32),
+                               (rng.standard_normal(4 * H) * 0.1).astype(np.float32), np.float32(1.25 / 7))
+    alpha_mid = 0.35
+    s_m = np.float32(np.float32(alpha_mid) / np.float32(7))
+    mid = oracle.Linear.from_float((rng.standard_normal((M, H)) * 0.4).astype(np.float32),
+                                   (rng.standard_normal(M) * 0.1).astype(np.float32), np.float32(1) / np.float32(7))
+    out = oracle.Linear.from_float((rng.standard_normal((V, M)) * 0.5).astype(np.float32),
+                                   (rng.standard_normal(V) * 0.1).astype(np.float32), s_m)
+    net = oracle.Net(embed, 1.25, [L], out, True, mid=mid, alpha_mid=alpha_mid)
+    plain = oracle.Net(embed, 1.25, [L], oracle.Linear(np.eye(H, dtype=np.int8), np.ones(H, np.float32), None, 1.0), False)
+    toks = np.array([0, 3, 6, 1, 1, 5], np.int32)
+    y = oracle.net_run(net, toks)
+    h_codes = oracle.net_run(plain, toks)          # identity output layer with unit scales: the top hidden codes
+    assert np.array_equal(h_codes, np.rint(h_codes)) and np.abs(h_codes).max() <= 7
+    saw_clip = False
+    for i in range(len(toks)):
+        ym = (mid.w.astype(np.float64) * mid.s_w[:, None].astype(np.float64)) @ (h_codes[i].astype(np.float64) / 7) + mid.bias
+        t = ym * float(np.float32(7) / np.float32(alpha_mid))
+        if np.abs(np.abs(t - np.floor(t)) - 0.5).min() < 1e-4:
+            continue                                # too close to a rounding tie for a float restatement
+        qm = np.clip(np.rint(t), -8, 7)
+        saw_clip = saw_clip or np.abs(t).max() > 7.5
+        yo = (out.w.astype(np.float64) * out.s_w[:, None].astype(np.float64)) @ (qm * float(s_m)) + out.bias
+        ref = yo - (np.log(np.exp(yo - yo.max()).sum()) + yo.max())
+        assert np.abs(y[i] - ref).max() < 2e-5, i
+    assert saw_clip                                 # the quantizer between the layers does clip here
+    # without the bottleneck the same network gives other values (the layer is really applied)
+    direct = oracle.Net(embed, 1.25, [L], oracle.Linear.from_float(
+        (rng.standard_normal((V, H)) * 0.5).astype(np.float32), None, np.float32(1) / np.float32(7)), True)
+    assert np.abs(oracle.net_run(direct, toks) - y).max() > 1e-2
+
+
 def test_beam1_equals_independent_greedy():
     # W = 1 is greedy decoding with a cap on labels per frame
     for seed, lms in ((21, True), (22, False)):
