@@ -179,7 +179,20 @@ def main():
                                              f"B={B} x T={T}",
                                  "encoder_ms": t_enc5 * 1e3, "decoder_ms": t_dec5 * 1e3,
                                  "rtf": (t_enc5 + t_dec5) / audio}
-        del m5, enc5, G5, feats5, ws5, e5
+        del m5, enc5, G5, ws5, e5
+        # ... and with the precision map of Sec. 3.2: 8-bit features, first encoder layer, encoder projection,
+        # prediction-network output layer and joint output layer (8-bit weights straight onto the int8 MFMA)
+        m6 = synth.make_model(5, mixed=True)
+        enc6 = gmodel.Encoder(m6, dev)
+        G6 = gmodel.model_from_float(m6, dev)
+        ws6 = torch.empty(q.decode_workspace(G6, T, B, W, MAX_SYM), dtype=torch.uint8, device=dev)
+        _, e6 = enc6.forward(feats5)
+        t_enc6 = timed(lambda: enc6.forward(feats5), 1, warm=0)
+        t_dec6 = timed(lambda: q.decode(G6, e6, W, MAX_SYM, max_len=T * MAX_SYM, workspace=ws6), 1, warm=1)
+        extra["paper_shapes_mixed_precision"] = {"workload": "the same, first encoder layer and the RNN-T's linear layers at 8 bits (Sec. 3.2)",
+                                                 "encoder_ms": t_enc6 * 1e3, "decoder_ms": t_dec6 * 1e3,
+                                                 "rtf": (t_enc6 + t_dec6) / audio}
+        del m6, enc6, G6, feats5, ws6, e6
 
     # ---------------------------------------------------------------- kernel legs
     if args.leg in ("all", "kernels"):

@@ -66,7 +66,14 @@ uint32_t qrnnt_abi_version(void);
  *   j = 16*q + 4*a + b, gate g is tiled row 64*q + 16*b + 4*a + g (rows padded
  *   to a multiple of 64).  The four gates of a cell land in one lane's
  *   accumulator quartet, and over the 4 row tiles of a group a lane owns 4
- *   consecutive cells.  Row scales and biases stay in source order. */
+ *   consecutive cells.  Row scales and biases stay in source order.
+ * 8-bit matrices (bits = 8; Sec. 3.2 keeps the first encoder layer and the
+ * RNN-T's linear layers at 8 bits) use the same three layouts with one byte per
+ * element: ROWMAJOR rows are padded to a multiple of 64 bytes; in TILED and
+ * TILED_GATES every [row_tile][k_chunk] position holds two 1 KiB blocks, the
+ * first with W[16*row_tile + l%16][128*k_chunk + 16*(l/16) + 4*d + b] at byte
+ * 16*l + 4*d + b, the second with the elements 64 columns further: the two
+ * MFMA operands of the chunk as they are. */
 enum { QRNNT_LAYOUT_ROWMAJOR = 0, QRNNT_LAYOUT_TILED = 1, QRNNT_LAYOUT_TILED_GATES = 2 };
 enum { QRNNT_SRC_INT8_CODES = 0, QRNNT_SRC_FP32 = 1 };
 
@@ -76,10 +83,15 @@ typedef struct {
     const float *row_scale; /* [device] [rows] fp32 */
     int32_t rows, cols;     /* logical size */
     int32_t layout;         /* QRNNT_LAYOUT_* */
+    int32_t bits;           /* 4 (0 is read as 4: qrnnt_pack_int4) or 8 (qrnnt_pack_int8) */
 } qrnnt_qmat;
 
 /* One LSTM layer-direction (Sec. 3.2): both matrices in TILED_GATES layout,
- * rows = 4*hidden_size. */
+ * rows = 4*hidden_size, both of the same width.  The hidden-state quantizer
+ * has the width of the weights: codes in [-8,7] for a 4-bit layer, [-128,127]
+ * for an 8-bit one (FIX +-1: h_inv_scale 7 resp. 127).  8-bit layers run in
+ * qrnnt_input_projection, qrnnt_lstm_layer and qrnnt_bilstm_layer (the encoder's
+ * first layer); the single-step entry points take 4-bit layers only. */
 typedef struct {
     qrnnt_qmat w_ih;        /* [4H, I] */
     qrnnt_qmat w_hh;        /* [4H, H] */
@@ -104,14 +116,24 @@ size_t qrnnt_pack_int4_bytes(int32_t rows, int32_t cols, int32_t layout);
 qrnnt_status qrnnt_pack_int4(const void *src, int32_t src_dtype, int32_t rows, int32_t cols, int32_t layout,
                              void *packed_out, float *row_scale_out, void *stream);
 
+/* The same at 8 bits (Sec. 3.2: MAX quantizer, 8 bits): codes in [-128,127] are
+ * taken as they are; fp32 rows get alpha = max|w|, row_scale_out[r] = alpha/127,
+ * code = clamp(rne(w * (127/alpha)), -128, 127).  The caller sets bits = 8 in
+ * the qrnnt_qmat that describes the result. */
+size_t qrnnt_pack_int8_bytes(int32_t rows, int32_t cols, int32_t layout);
+qrnnt_status qrnnt_pack_int8(const void *src, int32_t src_dtype, int32_t rows, int32_t cols, int32_t layout,
+                             void *packed_out, float *row_scale_out, void *stream);
+
 /* Inverse of the packing, for tests: codes_out [device] rows x cols int8 in
- * source row order. */
+ * source row order.  Reads m->bits (both widths). */
 qrnnt_status qrnnt_unpack_int4(const qrnnt_qmat *m, int8_t *codes_out, void *stream);
 
 /* ---- activations (Sec. 3.1 symmetric LQ with a FIX boundary, Sec. 3.2) ---- */
 
 /* q[i] = clamp(rne(x[i] * inv_scale), -8, 7); x, q [device], n elements. */
 qrnnt_status qrnnt_quantize_act(const float *x, int64_t n, float inv_scale, int8_t *q, void *stream);
+/* The 8-bit form (input of the encoder's first layer, Sec. 3.2): clamp to [-128, 127]. */
+qrnnt_status qrnnt_quantize_act8(const float *x, int64_t n, float inv_scale, int8_t *q, void *stream);
 
 /* ---- quantized linear layer (Sec. 3.2: weights and inputs quantized) ---- */
 
@@ -119,16 +141,19 @@ qrnnt_status qrnnt_quantize_act(const float *x, int64_t n, float inv_scale, int8
  * log_softmax != 0 each row of y is replaced by its log-softmax (LM output
  * layer, Sec. 2).  w: TILED layout.  a [device] [N, cols] int8, 16-byte aligned,
  * cols % 16 == 0.  bias [device] [rows] or NULL.  y [device] [N, rows] fp32.
- * dbg_acc [device] [N, rows] int32 or NULL.  log_softmax needs rows <= 64. */
+ * dbg_acc [device] [N, rows] int32 or NULL.  log_softmax needs rows <= 64.
+ * w may be 4- or 8-bit; the codes in a are contracted as they are (any int8). */
 qrnnt_status qrnnt_linear(const qrnnt_qmat *w, const float *bias, float a_scale, const int8_t *a, int32_t N,
                           int32_t log_softmax, float *y, int32_t *dbg_acc, void *stream);
 
 /* qrnnt_linear feeding another quantized linear layer (Sec. 3.2: linear layers
- * quantize their inputs): q[n,r] = clamp(rne(y[n,r] * inv_scale), -8, 7) with y
- * as in qrnnt_linear (no log-softmax); the fp32 y is not stored.  q [device]
- * [N, rows] int8.  This is the bottleneck layer of the external LM (Sec. 2). */
+ * quantize their inputs): q[n,r] = clamp(rne(y[n,r] * inv_scale), lo, hi) with y
+ * as in qrnnt_linear (no log-softmax) and [lo,hi] = [-8,7] for bits = 4,
+ * [-128,127] for bits = 8 (the width of the consuming layer); the fp32 y is not
+ * stored.  q [device] [N, rows] int8.  This is the bottleneck layer of the
+ * external LM (Sec. 2). */
 qrnnt_status qrnnt_linear_quant(const qrnnt_qmat *w, const float *bias, float a_scale, const int8_t *a, int32_t N,
-                                float inv_scale, int8_t *q, void *stream);
+                                float inv_scale, int32_t bits, int8_t *q, void *stream);
 
 /* ---- LSTM: one step for a set of hypotheses (Sec. 3.2, Sec. 3.4) ---- */
 
@@ -225,6 +250,9 @@ qrnnt_status qrnnt_input_table(const qrnnt_lstm *L, const int32_t *gx, int32_t M
  *   lp = log_softmax(logit);
  *   fused[n,blank] = lp[blank];
  *   fused[n,k] = lp[k] - lambda_src*lp_src[n,k] + lambda_ext*lp_ext[n,k] + rho  (k != blank).
+ * The quantizer of z has the width of w_out (Sec. 3.2: a linear layer's weights
+ * and inputs share one precision): codes in [-8,7], or [-128,127] when
+ * w_out->bits == 8 (then z_inv_scale is 127/alpha).
  * w_out: TILED layout, rows = V <= 64, cols = J (multiple of 64).  lp_src /
  * lp_ext [device] [N,V] or NULL (term dropped).  Optional outputs [device]:
  * lp_rnnt_out fp32 [N,V], dbg_zq int8 [N,J].  frame_row values are clamped to
@@ -256,8 +284,8 @@ qrnnt_status qrnnt_beam_step(const float *score, const float *fused, int32_t B, 
  * Optional bottleneck (Sec. 2, the external LM: LSTM stack -> bottleneck ->
  * output layer), present when mid.packed != NULL: the top hidden codes go
  * through mid (qrnnt_linear_quant with a_scale = out_a_scale, quantizer
- * mid_inv_scale; no activation function, the paper names none) and `out` then
- * reads those codes with step mid_scale. */
+ * mid_inv_scale at the width of `out`; no activation function, the paper names
+ * none) and `out` then reads those codes with step mid_scale. */
 typedef struct {
     const int8_t *embed_codes;  /* [device] [V, E] embedding rows already quantized (FIX boundary, Sec. 3.2) */
     int32_t n_layers;           /* 1..QRNNT_MAX_LAYERS; layer[0].input_size = E */

@@ -72,12 +72,12 @@ def _arr(a, dtype):
 class _CLstm(C.Structure):
     _fields_ = [("w_ih", C.c_void_p), ("w_hh", C.c_void_p), ("s_wih", C.c_void_p), ("s_whh", C.c_void_p),
                 ("bias", C.c_void_p), ("I", C.c_int32), ("H", C.c_int32),
-                ("s_x", C.c_float), ("s_h", C.c_float), ("inv_s_h", C.c_float)]
+                ("s_x", C.c_float), ("s_h", C.c_float), ("inv_s_h", C.c_float), ("bits", C.c_int32)]
 
 
 class _CLinear(C.Structure):
     _fields_ = [("w", C.c_void_p), ("s_w", C.c_void_p), ("bias", C.c_void_p),
-                ("rows", C.c_int32), ("cols", C.c_int32), ("s_a", C.c_float)]
+                ("rows", C.c_int32), ("cols", C.c_int32), ("s_a", C.c_float), ("bits", C.c_int32)]
 
 
 class _CNet(C.Structure):
@@ -101,6 +101,14 @@ def quant_sym4(x, inv_s):
     return q
 
 
+def quant_sym(x, inv_s, bits):
+    """Symmetric b-bit codes clamp(rne(x * inv_s), -2^(b-1), 2^(b-1)-1) as int8."""
+    x = _arr(x, np.float32)
+    q = np.empty(x.shape, np.int8)
+    lib().oq_quantize_sym(_p(x), C.c_int64(x.size), C.c_float(inv_s), C.c_int(bits), _p(q))
+    return q
+
+
 def quantize_asym(x, bits, a_lo, a_hi):
     x = _arr(x, np.float32)
     xi = np.empty(x.shape, np.int32)
@@ -109,12 +117,15 @@ def quantize_asym(x, bits, a_lo, a_hi):
     return xi, xq
 
 
-def quantize_weight_rows(w):
+def quantize_weight_rows(w, bits=4):
     w = _arr(w, np.float32)
     rows, cols = w.shape
     codes = np.empty((rows, cols), np.int8)
     scale = np.empty(rows, np.float32)
-    lib().oq_quantize_weight_rows(_p(w), C.c_int(rows), C.c_int(cols), _p(codes), _p(scale))
+    if bits == 4:
+        lib().oq_quantize_weight_rows(_p(w), C.c_int(rows), C.c_int(cols), _p(codes), _p(scale))
+    else:
+        lib().oq_quantize_weight_rows_bits(_p(w), C.c_int(rows), C.c_int(cols), C.c_int(bits), _p(codes), _p(scale))
     return codes, scale
 
 
@@ -150,7 +161,8 @@ def matmul_i32(w, a):
 class Lstm:
     """One quantized LSTM layer-direction: integer codes + fp32 scales/bias."""
 
-    def __init__(self, w_ih, s_wih, w_hh, s_whh, bias, s_x, s_h=1.0 / 7.0, inv_s_h=7.0):
+    def __init__(self, w_ih, s_wih, w_hh, s_whh, bias, s_x, s_h=1.0 / 7.0, inv_s_h=7.0, bits=4):
+        self.bits = int(bits)
         self.w_ih = _arr(w_ih, np.int8)
         self.w_hh = _arr(w_hh, np.int8)
         self.s_wih = _arr(s_wih, np.float32)
@@ -162,18 +174,19 @@ class Lstm:
         self.s_x, self.s_h, self.inv_s_h = np.float32(s_x), np.float32(s_h), np.float32(inv_s_h)
 
     @classmethod
-    def from_float(cls, w_ih, w_hh, bias, s_x, s_h=1.0 / 7.0, inv_s_h=7.0):
-        qi, si = quantize_weight_rows(w_ih)
-        qh, sh = quantize_weight_rows(w_hh)
-        return cls(qi, si, qh, sh, bias, s_x, s_h, inv_s_h)
+    def from_float(cls, w_ih, w_hh, bias, s_x, s_h=1.0 / 7.0, inv_s_h=7.0, bits=4):
+        qi, si = quantize_weight_rows(w_ih, bits)
+        qh, sh = quantize_weight_rows(w_hh, bits)
+        return cls(qi, si, qh, sh, bias, s_x, s_h, inv_s_h, bits)
 
     def c(self):
         return _CLstm(_p(self.w_ih), _p(self.w_hh), _p(self.s_wih), _p(self.s_whh), _p(self.bias),
-                      self.I, self.H, float(self.s_x), float(self.s_h), float(self.inv_s_h))
+                      self.I, self.H, float(self.s_x), float(self.s_h), float(self.inv_s_h), self.bits)
 
 
 class Linear:
-    def __init__(self, w, s_w, bias, s_a):
+    def __init__(self, w, s_w, bias, s_a, bits=4):
+        self.bits = int(bits)
         self.w = _arr(w, np.int8)
         self.s_w = _arr(s_w, np.float32)
         self.bias = None if bias is None else _arr(bias, np.float32)
@@ -181,12 +194,12 @@ class Linear:
         self.s_a = np.float32(s_a)
 
     @classmethod
-    def from_float(cls, w, bias, s_a):
-        q, s = quantize_weight_rows(w)
-        return cls(q, s, bias, s_a)
+    def from_float(cls, w, bias, s_a, bits=4):
+        q, s = quantize_weight_rows(w, bits)
+        return cls(q, s, bias, s_a, bits)
 
     def c(self):
-        return _CLinear(_p(self.w), _p(self.s_w), _p(self.bias), self.rows, self.cols, float(self.s_a))
+        return _CLinear(_p(self.w), _p(self.s_w), _p(self.bias), self.rows, self.cols, float(self.s_a), self.bits)
 
 
 def lstm_step(L: Lstm, x, h_prev, c_prev, parent=None, active=None, debug=False):
@@ -252,14 +265,15 @@ def log_softmax(x):
     return lp
 
 
-def joint_z(enc_proj, frame_row, pred_proj, inv_s_z=7.0):
+def joint_z(enc_proj, frame_row, pred_proj, inv_s_z=7.0, bits=4):
     enc_proj = _arr(enc_proj, np.float32)
     pred_proj = _arr(pred_proj, np.float32)
     frame_row = _arr(frame_row, np.int32)
     N, J = pred_proj.shape
     zq = np.empty((N, J), np.int8)
     zr = np.empty((N, J), np.float64)
-    lib().oq_joint_z(_p(enc_proj), _p(frame_row), _p(pred_proj), C.c_int(N), C.c_int(J), C.c_float(inv_s_z), _p(zq), _p(zr))
+    lib().oq_joint_z(_p(enc_proj), _p(frame_row), _p(pred_proj), C.c_int(N), C.c_int(J), C.c_float(inv_s_z), C.c_int(bits),
+                     _p(zq), _p(zr))
     return zq, zr
 
 

@@ -12,7 +12,10 @@
  * Arithmetic conventions (each is a reading of the paper, which prints no
  * bit-level definition):
  *   - symmetric b=4 grid: signed codes in [-8,7], step s = alpha/7 (Sec. 3.1,
- *     symmetric LQ has one boundary alpha and no zero point);
+ *     symmetric LQ has one boundary alpha and no zero point); the 8-bit layers
+ *     of Sec. 3.2 use the same grid with 127 steps per side, and a layer's own
+ *     quantizer (hidden state; z for the joint's output layer) has the width
+ *     of the layer's weights (`bits` of oq_lstm_t / oq_linear_t);
  *   - the rounding operator of Eq. 2 is round-half-to-even;
  *   - a value is quantized as clamp(rne(x * inv_s)) with the product taken in
  *     fp32, because that product decides an integer and the GPU path takes the
@@ -60,6 +63,27 @@ void oq_quantize_sym4(const float *x, int64_t n, float inv_s, int8_t *q)
     for (int64_t i = 0; i < n; ++i) q[i] = oq_quant_sym4(x[i], inv_s);
 }
 
+/* The same symmetric quantizer at b bits (Sec. 3.2 keeps the first encoder layer
+ * and the linear layers of the RNN-T at 8 bits): codes in [-2^(b-1), 2^(b-1)-1],
+ * step alpha/(2^(b-1)-1).  bits == 0 means 4.  Pinned by: equals oq_quant_sym4 at
+ * b = 4, clip range and grid identity on all 256 codes at b = 8, hand values. */
+int8_t oq_quant_sym(float x, float inv_s, int bits)
+{
+    if (bits == 0) bits = 4;
+    float lo = -(float)(1 << (bits - 1)), hi = (float)((1 << (bits - 1)) - 1);
+    float t = x * inv_s;
+    float r = nearbyintf(t);
+    if (r < lo) r = lo;
+    if (r > hi) r = hi;
+    return (int8_t)r;
+}
+
+void oq_quantize_sym(const float *x, int64_t n, float inv_s, int bits, int8_t *q)
+{
+    g_quant_tensor_calls += 1;
+    for (int64_t i = 0; i < n; ++i) q[i] = oq_quant_sym(x[i], inv_s, bits);
+}
+
 /* Asymmetric LQ, Eq. 2 and Eq. 3, for b bits and boundaries alpha_-/alpha_+.
  * Not on the integer path (weights are symmetric and every activation range
  * used is +-alpha); carried as a utility.  Pinned by: alpha_- maps to 0,
@@ -102,6 +126,32 @@ void oq_quantize_weight_rows(const float *w, int rows, int cols, int8_t *codes, 
         float inv = 7.0f / alpha;
         scale[r] = s;
         for (int k = 0; k < cols; ++k) codes[(int64_t)r * cols + k] = oq_quant_sym4(wr[k], inv);
+    }
+}
+
+/* The same at b bits: scale[r] = alpha_r/qmax, inv = qmax/alpha_r with
+ * qmax = 2^(b-1)-1 (the 8-bit MAX quantizer of Sec. 3.2).  Pinned by: |code|
+ * reaches qmax on the max-abs element, equals the 4-bit routine at b = 4,
+ * dequantization error <= scale/2. */
+void oq_quantize_weight_rows_bits(const float *w, int rows, int cols, int bits, int8_t *codes, float *scale)
+{
+    if (bits == 0) bits = 4;
+    const float qmax = (float)((1 << (bits - 1)) - 1);
+    for (int r = 0; r < rows; ++r) {
+        const float *wr = w + (int64_t)r * cols;
+        float alpha = 0.0f;
+        for (int k = 0; k < cols; ++k) {
+            float a = fabsf(wr[k]);
+            if (a > alpha) alpha = a;
+        }
+        if (alpha == 0.0f) {
+            scale[r] = 1.0f;
+            for (int k = 0; k < cols; ++k) codes[(int64_t)r * cols + k] = 0;
+            continue;
+        }
+        float inv = qmax / alpha;
+        scale[r] = alpha / qmax;
+        for (int k = 0; k < cols; ++k) codes[(int64_t)r * cols + k] = oq_quant_sym(wr[k], inv, bits);
     }
 }
 
@@ -165,7 +215,8 @@ typedef struct {
     int32_t I, H;
     float s_x;            /* step of the input codes  */
     float s_h;            /* step of the hidden codes (FIX +-1: 1/7) */
-    float inv_s_h;        /* 7/alpha_h (FIX +-1: 7) */
+    float inv_s_h;        /* 7/alpha_h (FIX +-1: 7); 127/alpha_h for an 8-bit layer */
+    int32_t bits;         /* width of the layer (weights and hidden-state quantizer, Sec. 3.2): 0 or 4, or 8 */
 } oq_lstm_t;
 
 static double sigm(double v) { return 1.0 / (1.0 + exp(-v)); }
@@ -217,7 +268,7 @@ void oq_lstm_step(const oq_lstm_t *L, const int8_t *x, const int32_t *parent,
             double c = gf * (double)cp[j] + gi * gg;
             double h = go * tanh(c);
             c_next[(int64_t)n * H + j] = (float)c;
-            h_next[(int64_t)n * H + j] = oq_quant_sym4((float)h, L->inv_s_h);
+            h_next[(int64_t)n * H + j] = oq_quant_sym((float)h, L->inv_s_h, L->bits);
             if (gates_out) {
                 double *g = gates_out + (int64_t)n * R;
                 g[j] = gi; g[H + j] = gf; g[2 * H + j] = gg; g[3 * H + j] = go;
@@ -269,6 +320,7 @@ typedef struct {
     const float *bias;    /* [rows] or NULL */
     int32_t rows, cols;
     float s_a;            /* step of the input codes */
+    int32_t bits;         /* width of the layer (weights and its own input quantizer, Sec. 3.2): 0 or 4, or 8 */
 } oq_linear_t;
 
 /* y[n,r] = s_a*s_w[r]*acc[n,r] + b[r], fp64, stored fp32.
@@ -315,14 +367,14 @@ void oq_log_softmax(const float *x, int N, int V, float *lp)
  * is the input of a quantized linear layer (Sec. 3.2).  Row n uses encoder row
  * frame_row[n].  Pinned by: numpy restatement, |code| <= 7. */
 void oq_joint_z(const float *enc_proj, const int32_t *frame_row, const float *pred_proj,
-                int N, int J, float inv_s_z, int8_t *zq, double *z_real)
+                int N, int J, float inv_s_z, int bits, int8_t *zq, double *z_real)
 {
     for (int n = 0; n < N; ++n) {
         const float *e = enc_proj + (int64_t)frame_row[n] * J, *p = pred_proj + (int64_t)n * J;
         for (int j = 0; j < J; ++j) {
             double z = tanh((double)e[j] * (double)p[j]);
             if (z_real) z_real[(int64_t)n * J + j] = z;
-            zq[(int64_t)n * J + j] = oq_quant_sym4((float)z, inv_s_z);
+            zq[(int64_t)n * J + j] = oq_quant_sym((float)z, inv_s_z, bits);
         }
     }
 }
@@ -366,7 +418,7 @@ void oq_joint_fuse(const float *enc_proj, const int32_t *frame_row, const float 
                    int8_t *zq_out, float *lp_rnnt, float *fused)
 {
     int8_t *zq = zq_out ? zq_out : (int8_t *)malloc((size_t)N * out->cols);
-    oq_joint_z(enc_proj, frame_row, pred_proj, N, out->cols, inv_s_z, zq, NULL);
+    oq_joint_z(enc_proj, frame_row, pred_proj, N, out->cols, inv_s_z, out->bits, zq, NULL);
     oq_joint_out(out, zq, lp_src, lp_ext, lambda_src, lambda_ext, rho, N, blank, lp_rnnt, fused);
     if (!zq_out) free(zq);
 }

@@ -155,6 +155,7 @@ qrnnt_status check_net(const qrnnt_net *net, int V, int out_rows)
     for (int l = 0; l < net->n_layers; ++l) {
         qrnnt_status s = qr_check_lstm(&net->layer[l]);
         if (s != QRNNT_OK) return s;
+        QR_REQUIRE(qr_bits(&net->layer[l].w_hh) == 4, QRNNT_ERR_UNSUPPORTED);   // the step kernels unpack nibbles
         if (l > 0) QR_REQUIRE(net->layer[l].input_size == net->layer[l - 1].hidden_size, QRNNT_ERR_SHAPE);
     }
     qrnnt_status s = qr_check_qmat(&net->out, QRNNT_LAYOUT_TILED);
@@ -247,7 +248,7 @@ void advance_nets(const qrnnt_model *m, const Plan &p, int src, int dst, int n_e
         out.w = (const v4i *)net->out.packed;
         out.nkc = qr_round_up(net->out.cols, QRNNT_KCHUNK) / QRNNT_KCHUNK;
         out.rows = net->out.rows;  out.s_w = net->out.row_scale;  out.bias = net->out_bias;
-        out.K = net->out.cols;  out.N = p.N;
+        out.K = net->out.cols;  out.N = p.N;  out.w8 = qr_bits(&net->out) == 8;
         out.y = p.net[k].y + (size_t)dst * N * net->out.rows;  out.log_softmax = net->log_softmax;
         if (has_mid) {
             QrLinearArgs &la = lg.p[lg.n++];
@@ -256,7 +257,7 @@ void advance_nets(const qrnnt_model *m, const Plan &p, int src, int dst, int n_e
             la.nkc = qr_round_up(net->mid.cols, QRNNT_KCHUNK) / QRNNT_KCHUNK;
             la.rows = net->mid.rows;  la.s_w = net->mid.row_scale;  la.bias = net->mid_bias;  la.a_scale = net->out_a_scale;
             la.act = p.net[k].h[top] + (size_t)dst * N * net->mid.cols;  la.K = net->mid.cols;  la.N = p.N;
-            la.q_out = p.net[k].mid_q;  la.q_inv = net->mid_inv_scale;
+            la.q_out = p.net[k].mid_q;  la.q_inv = net->mid_inv_scale;  la.q_bits = qr_bits(&net->out);  la.w8 = qr_bits(&net->mid) == 8;
             out.a_scale = net->mid_scale;  out.act = p.net[k].mid_q;
             lg2.p[lg2.n++] = out;
         } else {
@@ -350,6 +351,7 @@ extern "C" qrnnt_status qrnnt_decode_ex(const qrnnt_model *m, const float *enc_p
     ja.lambda_src = m->lambda_src;  ja.lambda_ext = m->lambda_ext;  ja.rho = m->rho;
     ja.N = N;  ja.J = p.J;  ja.V = V;  ja.blank = m->blank;
     ja.nkc = qr_round_up(p.J, QRNNT_KCHUNK) / QRNNT_KCHUNK;
+    ja.w8 = qr_bits(&m->joint_out) == 8;
 
     int a0 = 0;   // buffer of the beam at the current frame
     for (int t = 0; t < T; ++t) {

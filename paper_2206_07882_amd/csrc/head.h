@@ -9,9 +9,10 @@
 #define QR_HEAD_BATCH 4   // K blocks per wave per batch (registers: 4 x (4+1) fragments)
 
 // bfrag(kb) returns this lane's 16 activation codes of K block kb (zero beyond K).
+// w8 (uniform): the weights are 8-bit (two blocks per chunk, operands as stored).
 template <class BFrag>
 __device__ __forceinline__ void qr_head_mma(const v4i *__restrict__ w, int nkc, int n_row_tiles, int rt0, int K,
-                                            BFrag &&bfrag, v4i (&acc)[4], v4i *lds /* [4][4][64] */)
+                                            BFrag &&bfrag, v4i (&acc)[4], v4i *lds /* [4][4][64] */, bool w8 = false)
 {
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // scalar: MFMAs below sit under wave-uniform branches
@@ -31,7 +32,7 @@ __device__ __forceinline__ void qr_head_mma(const v4i *__restrict__ w, int nkc, 
             for (int mt = 0; mt < 4; ++mt) {
                 int rt = rt0 + mt;
                 rt = rt < n_row_tiles ? rt : n_row_tiles - 1;
-                pa[it][mt] = w[((size_t)rt * nkc + kc) * 64 + lane];
+                pa[it][mt] = w8 ? w[(((size_t)rt * nkc + kc) * 2 + (kb & 1)) * 64 + lane] : w[((size_t)rt * nkc + kc) * 64 + lane];
             }
             pb[it] = ok ? bfrag(kb) : zero;
         }
@@ -42,7 +43,7 @@ __device__ __forceinline__ void qr_head_mma(const v4i *__restrict__ w, int nkc, 
                 const bool hi = kb & 1;
 #pragma unroll
                 for (int mt = 0; mt < 4; ++mt) {
-                    const v4i a = hi ? (pa[it][mt] & m) : ((pa[it][mt] << 4) & m);
+                    const v4i a = w8 ? pa[it][mt] : (hi ? (pa[it][mt] & m) : ((pa[it][mt] << 4) & m));
                     acc[mt] = qr_mfma(a, pb[it], acc[mt]);
                 }
             }
@@ -60,6 +61,6 @@ __device__ __forceinline__ void qr_head_mma(const v4i *__restrict__ w, int nkc, 
 #pragma unroll
             for (int mt = 0; mt < 4; ++mt) acc[mt] += lds[(wv * 4 + mt) * 64 + lane];
 #pragma unroll
-        for (int mt = 0; mt < 4; ++mt) acc[mt] = acc[mt] >> 4;
+        for (int mt = 0; mt < 4; ++mt) acc[mt] = w8 ? acc[mt] : (acc[mt] >> 4);   // 4-bit operands carry a factor 16
     }
 }

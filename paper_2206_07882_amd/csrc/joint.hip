@@ -27,6 +27,7 @@ __global__ __launch_bounds__(256) void joint_fuse_kernel(const QrJointArgs a)
     int8_t *zq = a.dbg_zq ? a.dbg_zq + (int64_t)n * a.J + grp * 16 : nullptr;
     const int J = a.J;
     const float z_inv = a.z_inv;
+    const int zbits = a.w8 ? 8 : 4;
     auto bfrag = [&](int kb) -> v4i {
         v4i b = {0, 0, 0, 0};
         if (kb * 64 + grp * 16 < J) {
@@ -38,7 +39,7 @@ __global__ __launch_bounds__(256) void joint_fuse_kernel(const QrJointArgs a)
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
                     const float z = qr_tanh(ev[i] * pv[i]);
-                    word |= (uint32_t)(qr_quant4(z, z_inv) & 0xFF) << (8 * i);
+                    word |= (uint32_t)(qr_quant(z, z_inv, zbits) & 0xFF) << (8 * i);
                 }
                 b[d] = (int)word;
             }
@@ -48,7 +49,7 @@ __global__ __launch_bounds__(256) void joint_fuse_kernel(const QrJointArgs a)
     };
     const int n_row_tiles = (a.V + 15) >> 4;
     v4i acc[4];
-    qr_head_mma(a.w, a.nkc, n_row_tiles, 0, J, bfrag, acc, lds);
+    qr_head_mma(a.w, a.nkc, n_row_tiles, 0, J, bfrag, acc, lds, a.w8 != 0);
     if (wave != 0) return;
 
     float v[4][4];
@@ -122,6 +123,7 @@ __global__ __launch_bounds__(256) void joint_route_kernel(const QrJointArgs a, c
     fr = fr < 0 ? 0 : (fr >= a.n_enc_rows ? a.n_enc_rows - 1 : fr);
     const float *e = a.enc + (int64_t)fr * J + grp * 16;
     const float z_inv = a.z_inv;
+    const int zbits = a.w8 ? 8 : 4;
     const int n_row_tiles = (V + 15) >> 4;
     constexpr int PER = 16 * NTW;
     float val[PER];
@@ -155,7 +157,7 @@ __global__ __launch_bounds__(256) void joint_route_kernel(const QrJointArgs a, c
 #pragma unroll
                     for (int i = 0; i < 4; ++i) {
                         const float z = qr_tanh(ev[i] * pv[i]);
-                        word |= (uint32_t)(qr_quant4(z, z_inv) & 0xFF) << (8 * i);
+                        word |= (uint32_t)(qr_quant(z, z_inv, zbits) & 0xFF) << (8 * i);
                     }
                     bq[d] = (int)word;
                 }
@@ -178,7 +180,7 @@ __global__ __launch_bounds__(256) void joint_route_kernel(const QrJointArgs a, c
         }
         v4i acc[4];
         if (nt > 0) __syncthreads();   // the reduction buffer of the previous tile has been read
-        qr_head_mma(a.w, a.nkc, n_row_tiles, 0, J, bfrag, acc, lds);
+        qr_head_mma(a.w, a.nkc, n_row_tiles, 0, J, bfrag, acc, lds, a.w8 != 0);
         if (wave == 0) {
             float v[4][4];
             float m = -INFINITY;
@@ -282,6 +284,7 @@ extern "C" qrnnt_status qrnnt_joint_fuse(const float *enc_proj, int32_t n_enc_ro
     a.lambda_src = lambda_src;  a.lambda_ext = lambda_ext;  a.rho = rho;
     a.N = N;  a.J = w_out->cols;  a.V = w_out->rows;  a.blank = blank;
     a.nkc = qr_round_up(w_out->cols, QRNNT_KCHUNK) / QRNNT_KCHUNK;
+    a.w8 = qr_bits(w_out) == 8;
     a.lp_out = lp_rnnt_out;  a.dbg_zq = dbg_zq;  a.fused = fused_out;
     a.rows_per_utt = 1;
     qr_launch_joint(a, (hipStream_t)stream);

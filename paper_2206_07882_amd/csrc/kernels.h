@@ -41,7 +41,8 @@ struct QrLinearArgs {
     const int8_t *act;  int K, N;
     float *y;  int32_t *dbg_acc;
     int log_softmax;
-    int8_t *q_out;  float q_inv;       // optional: codes of y under the next layer's input quantizer, [N, rows]
+    int8_t *q_out;  float q_inv;  int q_bits;   // optional: codes of y under the next layer's input quantizer, [N, rows]
+    int w8;                            // 8-bit weights
 };
 
 struct QrLinearGroup {
@@ -61,6 +62,7 @@ struct QrJointArgs {
     float lambda_src, lambda_ext, rho;
     int N, J, V, blank, nkc;
     float *lp_out;  int8_t *dbg_zq;  float *fused;
+    int w8;                            // 8-bit output layer: 8-bit weights and an 8-bit quantizer on z
 };
 
 struct QrRouteArgs {
@@ -92,6 +94,7 @@ struct QrRecArgs {
     int *err;                          // set to 1 when a bounded wait ran out
     int T, B, H, nkc_h, reverse, spin_limit;
     float x_scale, h_scale, h_inv;
+    int w8;                            // 8-bit layer: 8-bit W_hh blob and an 8-bit hidden-state quantizer
 };
 struct QrRecGroup {
     QrRecArgs d[2];

@@ -39,7 +39,7 @@ __global__ __launch_bounds__(256) void linear_head_kernel(const QrLinearGroup g)
             }
     }
     v4i acc[4];
-    qr_head_mma(a.w, a.nkc, n_row_tiles, rt0, K, bfrag, acc, lds);
+    qr_head_mma(a.w, a.nkc, n_row_tiles, rt0, K, bfrag, acc, lds, a.w8 != 0);
     if (wave != 0) return;
 
     float v[4][4];
@@ -78,7 +78,7 @@ __global__ __launch_bounds__(256) void linear_head_kernel(const QrLinearGroup g)
             const int r0 = (rt0 + mt) * 16 + grp * 4;
             unsigned word = 0;
 #pragma unroll
-            for (int i = 0; i < 4; ++i) word |= (unsigned)(qr_quant4(v[mt][i] - lse, a.q_inv) & 0xFF) << (8 * i);
+            for (int i = 0; i < 4; ++i) word |= (unsigned)(qr_quant(v[mt][i] - lse, a.q_inv, a.q_bits) & 0xFF) << (8 * i);
             if (wide_q) {
                 if (r0 < a.rows) *(unsigned *)(a.q_out + (int64_t)n * a.rows + r0) = word;
             } else {
@@ -126,8 +126,9 @@ void qr_launch_linear(const QrLinearArgs &a, hipStream_t st)
 }
 
 extern "C" qrnnt_status qrnnt_linear_quant(const qrnnt_qmat *w, const float *bias, float a_scale, const int8_t *a, int32_t N,
-                                           float inv_scale, int8_t *q, void *stream)
+                                           float inv_scale, int32_t bits, int8_t *q, void *stream)
 {
+    QR_REQUIRE(bits == 4 || bits == 8, QRNNT_ERR_RANGE);
     qrnnt_status s = qr_check_qmat(w, QRNNT_LAYOUT_TILED);
     if (s != QRNNT_OK) return s;
     QR_REQUIRE(a != nullptr && q != nullptr, QRNNT_ERR_NULL);
@@ -136,8 +137,8 @@ extern "C" qrnnt_status qrnnt_linear_quant(const qrnnt_qmat *w, const float *bia
     QR_REQUIRE(qr_aligned(a, 16), QRNNT_ERR_ALIGN);
     QrLinearArgs la = {};
     la.w = (const v4i *)w->packed;  la.nkc = qr_round_up(w->cols, QRNNT_KCHUNK) / QRNNT_KCHUNK;  la.rows = w->rows;
-    la.s_w = w->row_scale;  la.bias = bias;  la.a_scale = a_scale;
-    la.act = a;  la.K = w->cols;  la.N = N;  la.q_out = q;  la.q_inv = inv_scale;
+    la.s_w = w->row_scale;  la.bias = bias;  la.a_scale = a_scale;  la.w8 = qr_bits(w) == 8;
+    la.act = a;  la.K = w->cols;  la.N = N;  la.q_out = q;  la.q_inv = inv_scale;  la.q_bits = bits;
     qr_launch_linear(la, (hipStream_t)stream);
     return qr_launch_status();
 }
@@ -154,7 +155,7 @@ extern "C" qrnnt_status qrnnt_linear(const qrnnt_qmat *w, const float *bias, flo
     QR_REQUIRE(!log_softmax || w->rows <= 64, QRNNT_ERR_UNSUPPORTED);
     QrLinearArgs la = {};
     la.w = (const v4i *)w->packed;  la.nkc = qr_round_up(w->cols, QRNNT_KCHUNK) / QRNNT_KCHUNK;  la.rows = w->rows;
-    la.s_w = w->row_scale;  la.bias = bias;  la.a_scale = a_scale;
+    la.s_w = w->row_scale;  la.bias = bias;  la.a_scale = a_scale;  la.w8 = qr_bits(w) == 8;
     la.act = a;  la.K = w->cols;  la.N = N;  la.y = y;  la.dbg_acc = dbg_acc;  la.log_softmax = log_softmax;
     qr_launch_linear(la, (hipStream_t)stream);
     return qr_launch_status();

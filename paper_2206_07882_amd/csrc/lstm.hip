@@ -457,13 +457,13 @@ void launch_step_t(const QrStepArgs &a, hipStream_t st)
 // blocks, all row blocks of a frame block in a row: an activation tile is fetched from HBM
 // by one L2 only (measured before: 181 MB fetched for 22 MB of operands), while the small
 // weight matrix lives in every L2.
-template <int MT, int NT, int S, bool TAIL>
-__global__ __launch_bounds__(256, S == 2 ? 3 : 2) void gx_gemm_pipe_kernel(const v4i *__restrict__ wih, int nkc, int n_row_tiles,
+template <int MT, int NT, int S, bool TAIL, bool W8>
+__global__ __launch_bounds__(256, (S == 2 && !W8) ? 3 : 2) void gx_gemm_pipe_kernel(const v4i *__restrict__ wih, int nkc, int n_row_tiles,
                                                               const int8_t *__restrict__ x, int64_t ld_x, int M, int K,
                                                               int32_t *__restrict__ gx, int H,
                                                               int32_t *__restrict__ dbg_accx)
 {
-    using P = QrPipe<MT, NT, S>;
+    using P = QrPipe<MT, NT, S, W8>;
     extern __shared__ __attribute__((aligned(1024))) char lds[];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int col = lane & 15, grp = lane >> 4;
@@ -489,7 +489,7 @@ __global__ __launch_bounds__(256, S == 2 ? 3 : 2) void gx_gemm_pipe_kernel(const
     for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) acc[mt][nt] = zero;
-    qr_pipe_mma<MT, NT, S, 1, TAIL>(ph, n_row_tiles, block_rt0, lds, acc, [] {});
+    qr_pipe_mma<MT, NT, S, 1, TAIL, W8>(ph, n_row_tiles, block_rt0, lds, acc, [] {});
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
         const int j = qr_gates_cell(rt0 + mt, grp);
@@ -498,7 +498,7 @@ __global__ __launch_bounds__(256, S == 2 ? 3 : 2) void gx_gemm_pipe_kernel(const
         for (int nt = 0; nt < NT; ++nt) {
             const int m = m0 + (wn * NT + nt) * 16 + col;
             if (m >= M) continue;
-            const v4i v = acc[mt][nt] >> 4;
+            const v4i v = W8 ? acc[mt][nt] : (acc[mt][nt] >> 4);   // 4-bit operands carry a factor 16
             *(v4i *)(gx + (int64_t)m * 4 * H + (rt0 + mt) * 16 + 4 * grp) = v;
             if (dbg_accx)
 #pragma unroll
@@ -507,10 +507,10 @@ __global__ __launch_bounds__(256, S == 2 ? 3 : 2) void gx_gemm_pipe_kernel(const
     }
 }
 
-template <int MT, int NT, int S>
+template <int MT, int NT, int S, bool W8>
 void launch_gx_pipe(const qrnnt_lstm *L, const int8_t *x_codes, int M, int32_t *gx, int32_t *dbg_accx, hipStream_t st)
 {
-    using P = QrPipe<MT, NT, S>;
+    using P = QrPipe<MT, NT, S, W8>;
     const int H = L->hidden_size, I = L->input_size;
     const int n_row_tiles = H >> 2;
     const int nkc = qr_round_up(I, QRNNT_KCHUNK) / QRNNT_KCHUNK;
@@ -518,18 +518,18 @@ void launch_gx_pipe(const qrnnt_lstm *L, const int8_t *x_codes, int M, int32_t *
     dim3 grid((unsigned)(nbx * 8 * ((nby + 7) / 8)));
     static bool configured = false;
     if (!configured) {
-        (void)hipFuncSetAttribute((const void *)gx_gemm_pipe_kernel<MT, NT, S, true>,
+        (void)hipFuncSetAttribute((const void *)gx_gemm_pipe_kernel<MT, NT, S, true, W8>,
                                   hipFuncAttributeMaxDynamicSharedMemorySize, P::LDS_BYTES);
-        (void)hipFuncSetAttribute((const void *)gx_gemm_pipe_kernel<MT, NT, S, false>,
+        (void)hipFuncSetAttribute((const void *)gx_gemm_pipe_kernel<MT, NT, S, false, W8>,
                                   hipFuncAttributeMaxDynamicSharedMemorySize, P::LDS_BYTES);
         configured = true;
     }
     if (I % QRNNT_KCHUNK)
-        gx_gemm_pipe_kernel<MT, NT, S, true><<<grid, 256, P::LDS_BYTES, st>>>((const v4i *)L->w_ih.packed, nkc, n_row_tiles,
-                                                                             x_codes, I, M, I, gx, H, dbg_accx);
+        gx_gemm_pipe_kernel<MT, NT, S, true, W8><<<grid, 256, P::LDS_BYTES, st>>>((const v4i *)L->w_ih.packed, nkc, n_row_tiles,
+                                                                                 x_codes, I, M, I, gx, H, dbg_accx);
     else
-        gx_gemm_pipe_kernel<MT, NT, S, false><<<grid, 256, P::LDS_BYTES, st>>>((const v4i *)L->w_ih.packed, nkc, n_row_tiles,
-                                                                              x_codes, I, M, I, gx, H, dbg_accx);
+        gx_gemm_pipe_kernel<MT, NT, S, false, W8><<<grid, 256, P::LDS_BYTES, st>>>((const v4i *)L->w_ih.packed, nkc, n_row_tiles,
+                                                                                  x_codes, I, M, I, gx, H, dbg_accx);
 }
 
 // fp32 form of a precomputed input projection: tab[m, r'] = k * (x_scale * s_wih[r] * gx[m, r'] + bias[r]),
@@ -569,6 +569,7 @@ qrnnt_status qr_check_lstm(const qrnnt_lstm *L)
     QR_REQUIRE(L->w_ih.rows == 4 * L->hidden_size && L->w_hh.rows == 4 * L->hidden_size, QRNNT_ERR_SHAPE);
     QR_REQUIRE(L->w_ih.cols == L->input_size && L->w_hh.cols == L->hidden_size, QRNNT_ERR_SHAPE);
     QR_REQUIRE(L->x_scale > 0.0f && L->h_scale > 0.0f && L->h_inv_scale > 0.0f, QRNNT_ERR_RANGE);
+    QR_REQUIRE(qr_bits(&L->w_ih) == qr_bits(&L->w_hh), QRNNT_ERR_RANGE);
     return QRNNT_OK;
 }
 
@@ -626,6 +627,7 @@ static qrnnt_status make_step_args(QrStepArgs &a, const qrnnt_lstm *L, const int
 {
     qrnnt_status s = qr_check_lstm(L);
     if (s != QRNNT_OK) return s;
+    QR_REQUIRE(qr_bits(&L->w_hh) == 4, QRNNT_ERR_UNSUPPORTED);   // the step kernels unpack nibbles
     QR_REQUIRE(x_codes && h_prev && c_prev && h_next && c_next, QRNNT_ERR_NULL);
     QR_REQUIRE(N > 0 && n_slots > 0 && n_x_rows > 0, QRNNT_ERR_SHAPE);
     QR_REQUIRE(parent != nullptr || n_slots >= N, QRNNT_ERR_SHAPE);
@@ -685,8 +687,9 @@ void qr_launch_input_projection(const qrnnt_lstm *L, const int8_t *x_codes, int 
 {
     // 128 x 128 block tile; two ring stages leave room for a third workgroup per CU, which at many
     // frames is worth more than a deeper ring (measured: 69 vs 74 us at 16000 x 1280 x 2560)
-    if (M <= 256) launch_gx_pipe<4, 4, 3>(L, x_codes, M, gx, dbg_accx, st);
-    else launch_gx_pipe<4, 4, 2>(L, x_codes, M, gx, dbg_accx, st);
+    if (qr_bits(&L->w_ih) == 8) launch_gx_pipe<4, 4, 2, true>(L, x_codes, M, gx, dbg_accx, st);   // 8-bit layer (the encoder's first)
+    else if (M <= 256) launch_gx_pipe<4, 4, 3, false>(L, x_codes, M, gx, dbg_accx, st);
+    else launch_gx_pipe<4, 4, 2, false>(L, x_codes, M, gx, dbg_accx, st);
 }
 
 extern "C" qrnnt_status qrnnt_input_table(const qrnnt_lstm *L, const int32_t *gx, int32_t M, float *table, void *stream)
@@ -771,6 +774,9 @@ qrnnt_status run_layer(const LayerCall *calls, int n, const int8_t *x_codes, int
     static const bool no_persist = getenv("QRNNT_STEPWISE_RECURRENCE") != nullptr;
     bool persist = !no_persist && qr_rec_supported(H, B);
     for (int d = 1; d < n; ++d) persist = persist && calls[d].L->hidden_size == H;
+    bool any8 = false;
+    for (int d = 0; d < n; ++d) any8 = any8 || qr_bits(&calls[d].L->w_hh) == 8;
+    QR_REQUIRE(!any8 || persist, QRNNT_ERR_UNSUPPORTED);   // 8-bit layers run in the persistent recurrence only
     QrRecGroup rg;
     rg.n = n;
     for (int d = 0; d < n; ++d) {
@@ -793,9 +799,11 @@ qrnnt_status run_layer(const LayerCall *calls, int n, const int8_t *x_codes, int
             a.T = T;  a.B = B;  a.H = H;  a.nkc_h = qr_round_up(H, QRNNT_KCHUNK) / QRNNT_KCHUNK;
             a.reverse = c.reverse;  a.spin_limit = 1 << 18;
             a.x_scale = L->x_scale;  a.h_scale = L->h_scale;  a.h_inv = L->h_inv_scale;
+            a.w8 = qr_bits(&L->w_hh) == 8;
         }
     }
     if (persist && qr_launch_recurrence(rg, st)) return qr_launch_status();
+    QR_REQUIRE(!any8, QRNNT_ERR_UNSUPPORTED);
     for (int d = 0; d < n; ++d) {
         const LayerCall &c = calls[d];
         const qrnnt_lstm *L = c.L;

@@ -34,11 +34,12 @@ struct QrPhase {
     const int8_t *row[NT];   // this thread's activation rows (one per B block it loads)
 };
 
-template <int MT, int NT, int S>
+// W8: 8-bit weights, two blocks per row tile and chunk (the two operands as stored) instead of one.
+template <int MT, int NT, int S, bool W8 = false>
 struct QrPipe {
     static_assert(MT % 2 == 0 && NT % 2 == 0, "tiles per wave must be even");
     static constexpr int BM = 32 * MT, BN = 32 * NT;
-    static constexpr int A_BLOCKS = 2 * MT, B_BLOCKS = 4 * NT;
+    static constexpr int A_BLOCKS = (W8 ? 4 : 2) * MT, B_BLOCKS = 4 * NT;
     static constexpr int A_PER_WAVE = A_BLOCKS / 4, B_PER_WAVE = NT;
     static constexpr int LOADS = A_PER_WAVE + B_PER_WAVE;   // vector-memory loads per thread per chunk
     static constexpr int STAGE_BYTES = (A_BLOCKS + B_BLOCKS) * 1024;
@@ -65,11 +66,11 @@ __device__ __forceinline__ int qr_pipe_b_row(int wave, int i, int lane)
     return (wave * NT + i) * 8 + (lane >> 3);
 }
 
-template <int MT, int NT, int S, int NPH, bool TAIL, class PhaseEnd>
+template <int MT, int NT, int S, int NPH, bool TAIL, bool W8 = false, class PhaseEnd>
 __device__ __forceinline__ void qr_pipe_mma(const QrPhase<NT> (&ph)[NPH], int n_row_tiles, int block_rt0, char *lds,
                                             v4i (&acc)[MT][NT], PhaseEnd &&on_phase_end)
 {
-    using P = QrPipe<MT, NT, S>;
+    using P = QrPipe<MT, NT, S, W8>;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int grp = lane >> 4, col = lane & 15;
@@ -91,9 +92,10 @@ __device__ __forceinline__ void qr_pipe_mma(const QrPhase<NT> (&ph)[NPH], int n_
         cur_K = ps.K;
 #pragma unroll
         for (int a = 0; a < P::A_PER_WAVE; ++a) {
-            int rt = block_rt0 + wave * P::A_PER_WAVE + a;
+            const int ab = wave * P::A_PER_WAVE + a;   // block of the stage: row tile ab (4-bit) or (row tile ab/2, K half ab%2)
+            int rt = block_rt0 + (W8 ? ab >> 1 : ab);
             rt = rt < n_row_tiles ? rt : n_row_tiles - 1;
-            cur_a[a] = ps.w + (size_t)rt * ps.nkc * 64 + lane;
+            cur_a[a] = W8 ? ps.w + ((size_t)rt * ps.nkc * 2 + (ab & 1)) * 64 + lane : ps.w + (size_t)rt * ps.nkc * 64 + lane;
         }
 #pragma unroll
         for (int i = 0; i < P::B_PER_WAVE; ++i) cur_b[i] = ps.row[i] + boff;
@@ -105,7 +107,7 @@ __device__ __forceinline__ void qr_pipe_mma(const QrPhase<NT> (&ph)[NPH], int n_
     auto issue_one = [&](int q, unsigned sbase, bool tail) {
         if (q < P::A_PER_WAVE) {
             qr_load_lds16(cur_a[q], sbase + (wave * P::A_PER_WAVE + q) * 1024);
-            cur_a[q] += 64;
+            cur_a[q] += W8 ? 128 : 64;
         } else {
             const int i = q - P::A_PER_WAVE;
             const int8_t *src = cur_b[i];
@@ -156,9 +158,16 @@ __device__ __forceinline__ void qr_pipe_mma(const QrPhase<NT> (&ph)[NPH], int n_
         const char *sb = lds + stage * P::STAGE_BYTES + lane * 16;
         const char *sbb = lds + stage * P::STAGE_BYTES + (P::A_BLOCKS + (col >> 3)) * 1024 + (col & 7) * 128;
         stage = (stage + 1 == S) ? 0 : stage + 1;
-        v4i pa[MT], b0[NT], b1[NT];
+        v4i pa[MT], pa_hi[W8 ? MT : 1], b0[NT], b1[NT];
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt) pa[mt] = *(const v4i *)(sb + (wm * MT + mt) * 1024);
+        for (int mt = 0; mt < MT; ++mt) {
+            if (W8) {
+                pa[mt] = *(const v4i *)(sb + ((wm * MT + mt) * 2) * 1024);
+                pa_hi[mt] = *(const v4i *)(sb + ((wm * MT + mt) * 2 + 1) * 1024);
+            } else {
+                pa[mt] = *(const v4i *)(sb + (wm * MT + mt) * 1024);
+            }
+        }
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) {
             b0[nt] = *(const v4i *)(sbb + (wn * NT + nt) * 2048 + p0);
@@ -167,7 +176,8 @@ __device__ __forceinline__ void qr_pipe_mma(const QrPhase<NT> (&ph)[NPH], int n_
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) {
             v4i lo, hi;
-            qr_unpack(pa[mt], lo, hi);
+            if (W8) { lo = pa[mt]; hi = pa_hi[mt]; }
+            else qr_unpack(pa[mt], lo, hi);
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt) {
                 acc[mt][nt] = qr_mfma(lo, b0[nt], acc[mt][nt]);

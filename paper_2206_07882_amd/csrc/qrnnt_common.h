@@ -39,6 +39,7 @@ static inline qrnnt_status qr_check_qmat(const qrnnt_qmat *m, int want_layout)
     QR_REQUIRE(m != nullptr && m->packed != nullptr && m->row_scale != nullptr, QRNNT_ERR_NULL);
     QR_REQUIRE(m->rows > 0 && m->cols > 0, QRNNT_ERR_SHAPE);
     QR_REQUIRE(m->layout == want_layout, QRNNT_ERR_LAYOUT);
+    QR_REQUIRE(m->bits == 0 || m->bits == 4 || m->bits == 8, QRNNT_ERR_RANGE);
     QR_REQUIRE(qr_aligned(m->packed, 16), QRNNT_ERR_ALIGN);
     return QRNNT_OK;
 }
@@ -90,6 +91,18 @@ __device__ __forceinline__ int qr_quant4(float x, float inv_step)
     r = fminf(fmaxf(r, -8.0f), 7.0f);
     return (int)r;
 }
+
+// The same quantizer at 4 or 8 bits: clamp to [-2^(bits-1), 2^(bits-1) - 1].
+__device__ __forceinline__ int qr_quant(float x, float inv_step, int bits)
+{
+    const float hi = bits == 8 ? 127.0f : 7.0f;
+    float r = __builtin_rintf(x * inv_step);
+    r = fminf(fmaxf(r, -hi - 1.0f), hi);
+    return (int)r;
+}
+
+// bits field of a qrnnt_qmat: 0 is read as 4.
+static inline int qr_bits(const qrnnt_qmat *m) { return m->bits == 8 ? 8 : 4; }
 
 // Wave-wide max / min of a 32-bit unsigned value on the DPP path (row scans, then
 // the two cross-row broadcasts of gfx9), result broadcast through lane 63.

@@ -87,8 +87,12 @@ __global__ __launch_bounds__(256) void lstm_rec_kernel(const QrRecGroup g)
             const int ks = wave + 4 * k;
             A[rt][k] = zero;
             if (ks < nks) {
-                const v4i p = a.whh[((size_t)(cg * 4 + rt) * a.nkc_h + (ks >> 1)) * 64 + lane];
-                A[rt][k] = (ks & 1) ? (p & m) : ((p << 4) & m);
+                if (a.w8) {   // 8-bit layer: the operand as stored, two blocks per 128-column chunk
+                    A[rt][k] = a.whh[(((size_t)(cg * 4 + rt) * a.nkc_h + (ks >> 1)) * 2 + (ks & 1)) * 64 + lane];
+                } else {
+                    const v4i p = a.whh[((size_t)(cg * 4 + rt) * a.nkc_h + (ks >> 1)) * 64 + lane];
+                    A[rt][k] = (ks & 1) ? (p & m) : ((p << 4) & m);
+                }
             }
         }
     // ---- the cell this lane finishes: row tile = wave, cell j, utterance n
@@ -165,14 +169,15 @@ __global__ __launch_bounds__(256) void lstm_rec_kernel(const QrRecGroup g)
         for (int rt = 0; rt < 4; ++rt) part[wave][rt][lane] = acc[rt];
         __syncthreads();
         const int fail_now = s_fail;   // written only before this barrier, read only after it: uniform
-        const v4i ah = (part[0][wave][lane] + part[1][wave][lane] + part[2][wave][lane] + part[3][wave][lane]) >> 4;
+        const v4i asum = part[0][wave][lane] + part[1][wave][lane] + part[2][wave][lane] + part[3][wave][lane];
+        const v4i ah = a.w8 ? asum : (asum >> 4);   // 4-bit operands carry a factor 16
         float p[4];
 #pragma unroll
         for (int gt = 0; gt < 4; ++gt) p[gt] = sx[gt] * (float)gxv[gt] + (sh[gt] * (float)ah[gt] + bb[gt]);
         const float gi = qr_sigmoid(p[0]), gf = qr_sigmoid(p[1]), gg = qr_tanh(p[2]), go = qr_sigmoid(p[3]);
         c = gf * c + gi * gg;
         const float h = go * qr_tanh(c);
-        hc[col][grp * 4 + wave] = (int8_t)qr_quant4(h, a.h_inv);
+        hc[col][grp * 4 + wave] = (int8_t)qr_quant(h, a.h_inv, a.w8 ? 8 : 4);
         if (a.dbg_c_all && n < B) a.dbg_c_all[((int64_t)t * B + n) * H + j] = c;
         __syncthreads();
         // publish: 16 utterances x 4 quads, one 8-byte word each, tagged s+1

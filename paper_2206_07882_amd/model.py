@@ -14,28 +14,36 @@ import torch
 from . import qrnnt as q
 
 S_H = float(np.float32(1.0) / np.float32(7.0))     # FIX +-1 step (Sec. 3.2)
+S_H8 = float(np.float32(1.0) / np.float32(127.0))  # the same boundary at 8 bits
 
 
-def act_scale(alpha: float):
+def act_scale(alpha: float, bits: int = 4):
     a = np.float32(alpha)
-    return float(np.float32(a / np.float32(7.0))), float(np.float32(np.float32(7.0) / a))
+    qmax = np.float32(127.0 if bits == 8 else 7.0)
+    return float(np.float32(a / qmax)), float(np.float32(qmax / a))
+
+
+def _pack(w, layout, bits):
+    return q.pack_int8(w, layout) if bits == 8 else q.pack_int4(w, layout)
 
 
 def _dev(a, device):
     return torch.from_numpy(np.ascontiguousarray(a)).to(device)
 
 
-def lstm_from_float(f, x_scale: float, device="cuda:0") -> q.Lstm:
-    return q.Lstm(q.pack_int4(_dev(f.w_ih, device), q.LAYOUT_TILED_GATES),
-                  q.pack_int4(_dev(f.w_hh, device), q.LAYOUT_TILED_GATES),
-                  _dev(f.bias, device), x_scale, S_H, 7.0)
+def lstm_from_float(f, x_scale: float, device="cuda:0", bits: int = 4) -> q.Lstm:
+    return q.Lstm(_pack(_dev(f.w_ih, device), q.LAYOUT_TILED_GATES, bits),
+                  _pack(_dev(f.w_hh, device), q.LAYOUT_TILED_GATES, bits),
+                  _dev(f.bias, device), x_scale, S_H8 if bits == 8 else S_H, 127.0 if bits == 8 else 7.0)
 
 
-def net_from_float(f, alpha_e: float, log_softmax: bool, device="cuda:0") -> q.Net:
+def net_from_float(f, alpha_e: float, log_softmax: bool, device="cuda:0", out_bits: int = 4) -> q.Net:
+    """out_bits = 8: the output layer's weights at 8 bits (Sec. 3.2, the RNN-T's linear layers); its input
+    stays the top layer's hidden codes, quantized once at the cell output (Sec. 3.4)."""
     s_e, inv_e = act_scale(alpha_e)
     embed_codes = q.quantize_act(_dev(f.embed, device), inv_e)
     layers = [lstm_from_float(lf, s_e if i == 0 else S_H, device) for i, lf in enumerate(f.layers)]
-    out = q.pack_int4(_dev(f.out.w, device), q.LAYOUT_TILED)
+    out = _pack(_dev(f.out.w, device), q.LAYOUT_TILED, out_bits)
     mid = getattr(f, "mid", None)
     if mid is not None:   # bottleneck between the LSTM stack and the output layer (Sec. 2, external LM)
         s_m, inv_m = act_scale(f.alpha_mid)
@@ -46,6 +54,15 @@ def net_from_float(f, alpha_e: float, log_softmax: bool, device="cuda:0") -> q.N
 
 
 def model_from_float(m, device="cuda:0", use_src=True, use_ext=True) -> q.Model:
+    if getattr(m, "mixed_precision", False):
+        # Sec. 3.2: the RNN-T's linear layers (prediction-network output, joint output) at 8 bits, z quantized
+        # at 8 bits with them; the LMs stay 4-bit throughout
+        pred = net_from_float(m.pred, m.alpha_e, False, device, out_bits=8)
+        src = net_from_float(m.lm_src, m.alpha_e, True, device) if (use_src and m.lm_src is not None) else None
+        ext = net_from_float(m.lm_ext, m.alpha_e, True, device) if (use_ext and m.lm_ext is not None) else None
+        jout = q.pack_int8(_dev(m.joint_out.w, device), q.LAYOUT_TILED)
+        return q.Model(pred, src, ext, jout, _dev(m.joint_out.bias, device), m.lambda_src, m.lambda_ext, m.rho,
+                       z_scale=S_H8, z_inv_scale=127.0)
     pred = net_from_float(m.pred, m.alpha_e, False, device)
     src = net_from_float(m.lm_src, m.alpha_e, True, device) if (use_src and m.lm_src is not None) else None
     ext = net_from_float(m.lm_ext, m.alpha_e, True, device) if (use_ext and m.lm_ext is not None) else None
@@ -57,11 +74,17 @@ class Encoder:
     """Stack of (bi)directional quantized LSTM layers plus the projection to the joint."""
 
     def __init__(self, m, device="cuda:0"):
-        self.s_x, self.inv_s_x = act_scale(m.alpha_x)
+        # mixed precision (Sec. 3.2): first layer and the projection at 8 bits; the second layer reads the first
+        # layer's 8-bit hidden codes (one quantizer per cell output, Sec. 3.4)
+        self.mixed = bool(getattr(m, "mixed_precision", False))
+        self.s_x, self.inv_s_x = act_scale(m.alpha_x, 8 if self.mixed else 4)
         self.layers: List[List[q.Lstm]] = []
         for li, dirs in enumerate(m.enc_layers):
-            self.layers.append([lstm_from_float(d, self.s_x if li == 0 else S_H, device) for d in dirs])
-        self.proj = q.pack_int4(_dev(m.enc_proj.w, device), q.LAYOUT_TILED)
+            bits = 8 if (self.mixed and li == 0) else 4
+            x_scale = self.s_x if li == 0 else (S_H8 if (self.mixed and li == 1) else S_H)
+            self.layers.append([lstm_from_float(d, x_scale, device, bits) for d in dirs])
+        self.proj = _pack(_dev(m.enc_proj.w, device), q.LAYOUT_TILED, 8 if self.mixed else 4)
+        self.proj_a_scale = S_H8 if (self.mixed and len(m.enc_layers) == 1) else S_H
         self.proj_bias = _dev(m.enc_proj.bias, device)
         self._ws: Optional[torch.Tensor] = None
 
@@ -75,7 +98,7 @@ class Encoder:
         """feats [T,B,D] fp32 on the device -> (codes [T,B,dirs*H], e [T,B,J] fp32)."""
         T, B, _ = feats.shape
         ws = self.workspace(T, B, feats.device)
-        x = q.quantize_act(feats, self.inv_s_x)
+        x = q.quantize_act8(feats, self.inv_s_x) if self.mixed else q.quantize_act(feats, self.inv_s_x)
         for dirs in self.layers:
             H = dirs[0].H
             out = torch.empty((T, B, H * len(dirs)), dtype=torch.int8, device=feats.device)
@@ -84,5 +107,5 @@ class Encoder:
             else:
                 q.lstm_layer(dirs[0], x, h_out=out, col_off=0, workspace=ws)
             x = out
-        e = q.linear(self.proj, self.proj_bias, S_H, x.reshape(T * B, -1)).reshape(T, B, -1)
+        e = q.linear(self.proj, self.proj_bias, self.proj_a_scale, x.reshape(T * B, -1)).reshape(T, B, -1)
         return x, e

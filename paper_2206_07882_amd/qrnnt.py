@@ -32,7 +32,7 @@ class QrnntError(RuntimeError):
 
 class CQMat(C.Structure):
     _fields_ = [("packed", C.c_void_p), ("row_scale", C.c_void_p), ("rows", C.c_int32), ("cols", C.c_int32),
-                ("layout", C.c_int32)]
+                ("layout", C.c_int32), ("bits", C.c_int32)]
 
 
 class CLstm(C.Structure):
@@ -58,6 +58,7 @@ class CModel(C.Structure):
 
 
 EXPORTS = ["qrnnt_status_str", "qrnnt_abi_version", "qrnnt_pack_int4_bytes", "qrnnt_pack_int4", "qrnnt_unpack_int4",
+           "qrnnt_pack_int8_bytes", "qrnnt_pack_int8", "qrnnt_quantize_act8",
            "qrnnt_quantize_act", "qrnnt_linear", "qrnnt_linear_quant", "qrnnt_lstm_step", "qrnnt_lstm_layer_workspace", "qrnnt_lstm_layer",
            "qrnnt_input_projection", "qrnnt_input_table", "qrnnt_lstm_step_group",
            "qrnnt_bilstm_layer_workspace", "qrnnt_bilstm_layer",
@@ -78,6 +79,10 @@ def load():
         lib.qrnnt_abi_version.restype = C.c_uint32
         lib.qrnnt_pack_int4_bytes.restype = C.c_size_t
         lib.qrnnt_pack_int4_bytes.argtypes = [C.c_int32, C.c_int32, C.c_int32]
+        lib.qrnnt_pack_int8_bytes.restype = C.c_size_t
+        lib.qrnnt_pack_int8_bytes.argtypes = [C.c_int32, C.c_int32, C.c_int32]
+        if lib.qrnnt_abi_version() != 2:
+            raise RuntimeError(f"{LIB_PATH} has ABI version {lib.qrnnt_abi_version()}, this binding needs 2: rebuild")
         lib.qrnnt_lstm_layer_workspace.restype = C.c_size_t
         lib.qrnnt_lstm_layer_workspace.argtypes = [C.c_void_p, C.c_int32, C.c_int32]
         lib.qrnnt_bilstm_layer_workspace.restype = C.c_size_t
@@ -107,38 +112,51 @@ def _check(status: int, where: str):
         raise QrnntError(status, where)
 
 
-def pack_bytes(rows: int, cols: int, layout: int) -> int:
-    return int(load().qrnnt_pack_int4_bytes(rows, cols, layout))
+def pack_bytes(rows: int, cols: int, layout: int, bits: int = 4) -> int:
+    fn = load().qrnnt_pack_int8_bytes if bits == 8 else load().qrnnt_pack_int4_bytes
+    return int(fn(rows, cols, layout))
 
 
 class QMat:
-    """A packed INT4 matrix on the device plus its per-row scales."""
+    """A packed INT4 (or INT8) matrix on the device plus its per-row scales."""
 
-    def __init__(self, packed: torch.Tensor, row_scale: torch.Tensor, rows: int, cols: int, layout: int):
+    def __init__(self, packed: torch.Tensor, row_scale: torch.Tensor, rows: int, cols: int, layout: int, bits: int = 4):
         self.packed, self.row_scale, self.rows, self.cols, self.layout = packed, row_scale, rows, cols, layout
+        self.bits = int(bits)
 
     def c(self) -> CQMat:
-        return CQMat(self.packed.data_ptr(), self.row_scale.data_ptr(), self.rows, self.cols, self.layout)
+        return CQMat(self.packed.data_ptr(), self.row_scale.data_ptr(), self.rows, self.cols, self.layout, self.bits)
+
+
+def _pack(bits: int, src: torch.Tensor, layout: int, row_scale: Optional[torch.Tensor]) -> QMat:
+    assert src.dim() == 2 and src.is_cuda
+    rows, cols = src.shape
+    name = "qrnnt_pack_int8" if bits == 8 else "qrnnt_pack_int4"
+    fn = getattr(load(), name)
+    nbytes = pack_bytes(rows, cols, layout, bits)
+    if nbytes == 0:
+        _check(2, name + "_bytes")
+    packed = torch.empty(nbytes, dtype=torch.uint8, device=src.device)
+    if src.dtype == torch.float32:
+        scale = torch.empty(rows, dtype=torch.float32, device=src.device)
+        st = fn(_ptr(src), SRC_FP32, rows, cols, layout, _ptr(packed), _ptr(scale), _stream())
+    elif src.dtype == torch.int8:
+        scale = row_scale if row_scale is not None else torch.ones(rows, dtype=torch.float32, device=src.device)
+        st = fn(_ptr(src), SRC_INT8_CODES, rows, cols, layout, _ptr(packed), None, _stream())
+    else:
+        raise TypeError("src must be float32 or int8")
+    _check(st, name)
+    return QMat(packed, scale, rows, cols, layout, bits)
 
 
 def pack_int4(src: torch.Tensor, layout: int, row_scale: Optional[torch.Tensor] = None) -> QMat:
     """fp32 weights (quantized per row) or int8 codes (row_scale given by the caller) -> QMat."""
-    assert src.dim() == 2 and src.is_cuda
-    rows, cols = src.shape
-    nbytes = pack_bytes(rows, cols, layout)
-    if nbytes == 0:
-        _check(2, "qrnnt_pack_int4_bytes")
-    packed = torch.empty(nbytes, dtype=torch.uint8, device=src.device)
-    if src.dtype == torch.float32:
-        scale = torch.empty(rows, dtype=torch.float32, device=src.device)
-        st = load().qrnnt_pack_int4(_ptr(src), SRC_FP32, rows, cols, layout, _ptr(packed), _ptr(scale), _stream())
-    elif src.dtype == torch.int8:
-        scale = row_scale if row_scale is not None else torch.ones(rows, dtype=torch.float32, device=src.device)
-        st = load().qrnnt_pack_int4(_ptr(src), SRC_INT8_CODES, rows, cols, layout, _ptr(packed), None, _stream())
-    else:
-        raise TypeError("src must be float32 or int8")
-    _check(st, "qrnnt_pack_int4")
-    return QMat(packed, scale, rows, cols, layout)
+    return _pack(4, src, layout, row_scale)
+
+
+def pack_int8(src: torch.Tensor, layout: int, row_scale: Optional[torch.Tensor] = None) -> QMat:
+    """The same at 8 bits (Sec. 3.2: the encoder's first layer and the RNN-T's linear layers)."""
+    return _pack(8, src, layout, row_scale)
 
 
 def unpack_int4(m: QMat) -> torch.Tensor:
@@ -155,6 +173,13 @@ def quantize_act(x: torch.Tensor, inv_scale: float) -> torch.Tensor:
     return q
 
 
+def quantize_act8(x: torch.Tensor, inv_scale: float) -> torch.Tensor:
+    q = torch.empty(x.shape, dtype=torch.int8, device=x.device)
+    _check(load().qrnnt_quantize_act8(_ptr(x, torch.float32), C.c_int64(x.numel()), C.c_float(inv_scale), _ptr(q),
+                                      _stream()), "qrnnt_quantize_act8")
+    return q
+
+
 def linear(w: QMat, bias: Optional[torch.Tensor], a_scale: float, a: torch.Tensor, log_softmax: bool = False,
            want_acc: bool = False):
     N = a.shape[0]
@@ -167,12 +192,13 @@ def linear(w: QMat, bias: Optional[torch.Tensor], a_scale: float, a: torch.Tenso
     return (y, acc) if want_acc else y
 
 
-def linear_quant(w: QMat, bias: Optional[torch.Tensor], a_scale: float, a: torch.Tensor, inv_scale: float) -> torch.Tensor:
+def linear_quant(w: QMat, bias: Optional[torch.Tensor], a_scale: float, a: torch.Tensor, inv_scale: float,
+                 bits: int = 4) -> torch.Tensor:
     N = a.shape[0]
     q = torch.empty((N, w.rows), dtype=torch.int8, device=a.device)
     cw = w.c()
     _check(load().qrnnt_linear_quant(C.byref(cw), _ptr(bias, torch.float32), C.c_float(a_scale), _ptr(a, torch.int8),
-                                     C.c_int32(N), C.c_float(inv_scale), _ptr(q, torch.int8), _stream()),
+                                     C.c_int32(N), C.c_float(inv_scale), C.c_int32(bits), _ptr(q, torch.int8), _stream()),
            "qrnnt_linear_quant")
     return q
 

@@ -63,6 +63,7 @@ class ModelF:
     rho: float = 0.0
     beam: int = 16
     max_sym: int = 4
+    mixed_precision: bool = False   # Sec. 3.2: first encoder layer and the RNN-T's linear layers at 8 bits
 
 
 def _lstm(rng, I, H, std_ih=None, std_hh=None):
@@ -97,11 +98,20 @@ def _net(rng, V, E, hidden, n_layers, out_rows, std=None, E_used=None, mid=None)
                 alpha_mid=4.0 * 0.45)
 
 
-def make_model(config: int, *, enc_layers: Optional[int] = None, weight_std: float = 0.1) -> ModelF:
+def make_model(config: int, *, enc_layers: Optional[int] = None, weight_std: float = 0.1, mixed: bool = False) -> ModelF:
     """Float weights of configuration 0..4.  Configurations 1-3 describe parts
     of the full network; each returns only the parts it names.  ``weight_std``
     applies to configuration 0 only (its description fixes 0.1; larger values
-    give a tiny network that actually emits labels, for search tests)."""
+    give a tiny network that actually emits labels, for search tests).
+    Configuration 5 is the full network with the layer shapes of the paper's
+    Sec. 2.  ``mixed`` marks the model for the precision map of Sec. 3.2 (first
+    encoder layer and the RNN-T's linear layers at 8 bits); the float weights
+    are the same either way."""
+    if mixed:   # same float weights, quantized with the precision map of Sec. 3.2
+        m = make_model(config, enc_layers=enc_layers, weight_std=weight_std)
+        m.mixed_precision = True
+        m.name += "-mixed"
+        return m
     rng = np.random.default_rng(BASE_SEED + config)
     if config == 0:
         V, J, H = 16, 32, 64

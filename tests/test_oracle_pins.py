@@ -182,6 +182,71 @@ def test_lstm_step_against_numpy_cell():
     assert np.abs(hn).max() <= 7    # h = tanh * sigma is in [-1,1]: FIX +-1 never clips (Sec. 3.2)
 
 
+def test_8bit_quantizers_range_grid_and_hand_values():
+    # Sec. 3.2 keeps the first encoder layer and the RNN-T's linear layers at 8 bits (MAX for weights
+    # and inputs, FIX +-1 for hidden states): the same symmetric quantizer with 2^7 - 1 = 127 steps per side.
+    rng = np.random.default_rng(61)
+    x = (rng.standard_normal(4000) * 2).astype(np.float32)
+    for inv in (7.0, 3.3):
+        assert np.array_equal(oracle.quant_sym(x, inv, 4), oracle.quant_sym4(x, inv))      # b = 4 is the 4-bit routine
+    inv = np.float32(127.0)                                                                 # FIX +-1 at 8 bits
+    q = oracle.quant_sym(x, inv, 8)
+    assert q.min() == -128 and q.max() == 127                                               # clip range
+    codes = np.arange(-128, 128, dtype=np.float32)
+    assert np.array_equal(oracle.quant_sym(codes * (np.float32(1) / inv), inv, 8), codes.astype(np.int8))  # grid identity
+    assert oracle.quant_sym(np.zeros(1, np.float32), inv, 8)[0] == 0
+    hand = np.array([0.5, 1.5, 2.5, -0.5, -1.5, 126.5, 127.5, 300.0, -128.5, -129.5], np.float32) / inv
+    assert oracle.quant_sym(hand, inv, 8).tolist() == [0, 2, 2, 0, -2, 126, 127, 127, -128, -128]     # ties to even, clamp
+    inside = np.abs(x) < 0.99
+    assert np.abs(q[inside] / 127.0 - x[inside]).max() <= 0.5 / 127 + 1e-6                  # residual <= s/2
+    # weights: per-row MAX at 8 bits
+    w = (rng.standard_normal((5, 33)) * np.array([0.01, 0.3, 1.0, 5.0, 0.0])[:, None]).astype(np.float32)
+    c8, s8 = oracle.quantize_weight_rows(w, 8)
+    c4, s4 = oracle.quantize_weight_rows(w, 4)
+    assert np.array_equal(np.abs(c8[:4]).max(1), [127] * 4) and np.array_equal(np.abs(c4[:4]).max(1), [7] * 4)
+    assert np.array_equal(c8[4], np.zeros(33)) and s8[4] == 1.0
+    assert np.allclose(s8[:4], np.abs(w[:4]).max(1) / 127, rtol=1e-6)
+    assert np.all(np.abs(c8[:4] * s8[:4, None] - w[:4]) <= s8[:4, None] * 0.5 * (1 + 1e-5))
+    assert np.abs(c8[:4] * s8[:4, None] - w[:4]).max() < np.abs(c4[:4] * s4[:4, None] - w[:4]).max() / 8
+    row = np.array([[0.5, -1.0, 0.25, 1.0 / 127 * 1.5, 0.0]], np.float32)
+    assert oracle.quantize_weight_rows(row, 8)[0].tolist() == [[64, -127, 32, 2, 0]]      # 63.5 -> 64, 31.75 -> 32, 1.5 -> 2
+
+
+def test_8bit_lstm_layer_and_joint_against_numpy():
+    # the hidden-state quantizer of an 8-bit layer has 127 steps per side; everything else is the same cell
+    rng = np.random.default_rng(62)
+    I, H, N = 24, 16, 9
+    L = oracle.Lstm.from_float((rng.standard_normal((4 * H, I)) * 0.3).astype(np.float32),
+                               (rng.standard_normal((4 * H, H)) * 0.3).astype(np.float32),
+                               (rng.standard_normal(4 * H) * 0.1).astype(np.float32),
+                               np.float32(4.0 / 127), np.float32(1.0) / np.float32(127.0), 127.0, bits=8)
+    assert np.abs(L.w_ih).max() == 127
+    x = rng.integers(-128, 128, (N, I)).astype(np.int8)
+    hp = rng.integers(-127, 128, (N, H)).astype(np.int8)
+    cp = rng.standard_normal((N, H)).astype(np.float32)
+    hn, cn, dbg = oracle.lstm_step(L, x, hp, cp, debug=True)
+    Wih = L.w_ih.astype(np.float64) * L.s_wih.astype(np.float64)[:, None]
+    Whh = L.w_hh.astype(np.float64) * L.s_whh.astype(np.float64)[:, None]
+    pre = (x.astype(np.float64) * float(L.s_x)) @ Wih.T + (hp.astype(np.float64) * float(L.s_h)) @ Whh.T + L.bias
+    sg = lambda v: 1 / (1 + np.exp(-v))
+    gi, gf, gg, go = sg(pre[:, :H]), sg(pre[:, H:2 * H]), np.tanh(pre[:, 2 * H:3 * H]), sg(pre[:, 3 * H:])
+    c = gf * cp + gi * gg
+    h = go * np.tanh(c)
+    assert np.allclose(cn, c, rtol=1e-6, atol=1e-7)
+    tie = np.abs(h * 127 - np.floor(h * 127) - 0.5) < 1e-4
+    assert np.all((hn == np.rint(h * 127)) | tie) and np.abs(hn.astype(int)).max() > 7
+    assert np.array_equal(dbg["accx"], x.astype(np.int64) @ L.w_ih.astype(np.int64).T)
+    # joint with an 8-bit output layer: z is quantized with 127 steps per side
+    e, p, fr, out4, ls, le = _joint_setup(rng)
+    out8 = oracle.Linear.from_float(out4.w * out4.s_w[:, None], out4.bias, np.float32(1.0) / np.float32(127.0), bits=8)
+    zq, lp, _ = oracle.joint_fuse(e, fr, p, out8, None, None, 0.0, 0.0, inv_s_z=127.0)
+    z = np.tanh(e[fr].astype(np.float64) * p.astype(np.float64))
+    tie = np.abs(z * 127 - np.floor(z * 127) - 0.5) < 1e-4
+    assert np.all((zq == np.rint(z * 127)) | tie) and np.abs(zq.astype(int)).max() > 7
+    logits = (zq.astype(np.float64) * float(out8.s_a)) @ (out8.w * out8.s_w.astype(np.float64)[:, None]).T + out8.bias
+    assert np.allclose(lp, logits - np.log(np.exp(logits).sum(1, keepdims=True)), atol=1e-5)
+
+
 def test_lstm_gate_roles_by_saturation():
     # saturating one gate at a time shows each block of rows plays its textbook role
     H, I = 4, 3
