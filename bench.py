@@ -163,6 +163,19 @@ def main():
                                "note": "a round dies only when no utterance of the batch picked a label in the round before: "
                                        "with beam 16 the 16 picks of a round always include labels, so nothing is skipped "
                                        "and the flag costs its loads; greedy search (beam 1) on this model skips most rounds"}
+        # the paper's own search (Sec. 2): alignment-length synchronous with recombination, one joint + one network
+        # advance per alignment step instead of up to five joints and four advances per frame
+        alsd_rows = []
+        for u_max in (T // 2, T):
+            wsa = torch.empty(q.decode_alsd_workspace(G, T, B, W, u_max), dtype=torch.uint8, device=dev)
+            ta = timed(lambda: q.decode_alsd(G, e, W, u_max, max_len=u_max, workspace=wsa), 1, warm=1)
+            la = q.decode_alsd(G, e, W, u_max, max_len=u_max, workspace=wsa)[1].cpu().numpy()
+            alsd_rows.append({"beam": W, "u_max": u_max, "iterations": T + u_max, "decoder_ms": ta * 1e3,
+                              "decoder_rtf": ta / audio, "mean_labels_best_hyp": float(la[:, 0].mean())})
+            del wsa
+        extra["alsd"] = {"rows": alsd_rows,
+                         "note": "same networks and encoder output as the headline; label cap u_max per utterance; the launch "
+                                 "sequence has T + u_max iterations, those after the last live hypothesis return at once"}
         del feats, ws_dec, e, es, out
         # the same pipeline with the layer shapes of the paper's Sec. 2 (340 features, prediction network and
         # source LM 1 x 768, external LM 2 x 2048 + bottleneck 256, fusion weights 0.7 / 0.5 / 0.2), all 4-bit

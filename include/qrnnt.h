@@ -342,6 +342,31 @@ qrnnt_status qrnnt_decode_ex(const qrnnt_model *m, const float *enc_proj, int32_
                              int32_t max_sym, int32_t max_len, uint32_t flags, int32_t *tokens_out, int32_t *len_out,
                              float *score_out, void *workspace, size_t workspace_bytes, void *stream);
 
+/* Alignment-length synchronous beam search with recombination (Sec. 2: the
+ * search the paper decodes with, beam width 1 to 16) over enc_proj [device]
+ * [T,B,J] fp32.  All hypotheses of a beam have taken the same number i of
+ * alignment steps (labels + blanks): one with u labels stands at frame i - u.
+ * Per utterance the beam has W slots and starts as the empty sequence in slot 0.
+ * For i = 0 .. T + u_max - 1: fused scores of every hypothesis at its own frame
+ * (qrnnt_joint_fuse); candidates (w,k) = score_w + fused[w,k], except labels of
+ * a hypothesis that already holds u_max labels; a blank at the last frame
+ * finishes the hypothesis (it joins the finished list with that value and is no
+ * candidate); the W best candidates in qrnnt_beam_step's order become the next
+ * slots in rank order (blank: same sequence and network state, one frame later;
+ * label: extended, all networks advanced); picks that stand for the same label
+ * sequence are merged into the best-ranked of them with score
+ * log(sum exp(scores)), the other slots stay empty; the finished list keeps its
+ * W best by (score descending, insertion order; newcomers in slot order).
+ * Label sequences are compared through their length and a 64-bit hash.
+ * Outputs [device] as for qrnnt_decode, from the finished list (empty ranks:
+ * len -1, score -inf).  The launch sequence is fixed (T + u_max iterations);
+ * once no hypothesis is alive anywhere the remaining kernels return at once.
+ * workspace [device]: qrnnt_decode_alsd_workspace bytes, 256-byte aligned. */
+size_t qrnnt_decode_alsd_workspace(const qrnnt_model *m, int32_t T, int32_t B, int32_t W, int32_t u_max);
+qrnnt_status qrnnt_decode_alsd(const qrnnt_model *m, const float *enc_proj, int32_t T, int32_t B, int32_t W,
+                               int32_t u_max, int32_t max_len, int32_t *tokens_out, int32_t *len_out, float *score_out,
+                               void *workspace, size_t workspace_bytes, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -405,6 +405,21 @@ def decode(model: Model, enc_proj, W, max_sym, max_len=None):
     return tokens, lens, scores
 
 
+def decode_alsd(model: Model, enc_proj, W, u_max, max_len=None):
+    """Alignment-length synchronous search with recombination; at most u_max labels per utterance."""
+    enc_proj = _arr(enc_proj, np.float32)
+    T, B, J = enc_proj.shape
+    if max_len is None:
+        max_len = max(1, u_max)
+    tokens = np.empty((B, W, max_len), np.int32)
+    lens = np.empty((B, W), np.int32)
+    scores = np.empty((B, W), np.float32)
+    cm = model.c()
+    lib().oq_decode_alsd(C.byref(cm), _p(enc_proj), C.c_int(T), C.c_int(B), C.c_int(W), C.c_int(u_max),
+                         C.c_int(max_len), _p(tokens), _p(lens), _p(scores))
+    return tokens, lens, scores
+
+
 def score_alignment(model: Model, enc_proj, b, actions):
     enc_proj = _arr(enc_proj, np.float32)
     T, B, J = enc_proj.shape

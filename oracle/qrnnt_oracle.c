@@ -719,6 +719,164 @@ void oq_decode(const oq_model_t *M, const float *enc_proj, int T, int B, int W, 
     }
 }
 
+/* Alignment-length synchronous search with recombination (Sec. 2: the paper
+ * decodes with the alignment-length synchronous search of its reference on
+ * that algorithm, beam width 1 to 16; the paper itself prints no pseudo-code,
+ * so this follows the published algorithm as understood).  All hypotheses of
+ * the beam have consumed the same number i of alignment steps (labels + blanks):
+ * a hypothesis with u labels stands at frame t = i - u.
+ *
+ *   beam: W slots, slot 0 = the empty sequence (score 0), the others dead.
+ *   finals: the W best finished hypotheses so far.
+ *   for i = 0 .. T + u_max - 1:
+ *     F[w,:] = joint_fuse(e[t_w], hypothesis w)                       (Eq. 1)
+ *     candidates (w,k) with value score_w + F[w,k]; a label is not a candidate
+ *       when hypothesis w already holds u_max labels;
+ *     a blank at the last frame (t_w == T-1) finishes hypothesis w: it joins the
+ *       finals with that value and is not a candidate;
+ *     picks: the W best candidates by oq_beam_step's order; pick r becomes slot r
+ *       (blank: the same hypothesis one frame later; label: extended, all networks
+ *       advanced);
+ *     recombination: picks with equal label sequences are one hypothesis: the
+ *       best-ranked of them keeps its slot with score log(sum exp(scores)), the
+ *       others die (their slots stay empty for the next iteration);
+ *     finals <- the W best of finals + new finals by (score descending, insertion
+ *       order; new finals are inserted in slot order).
+ *
+ * With a beam wide enough that nothing is pruned, the final score of a label
+ * sequence is the log of its total probability over all alignments plus its
+ * label-wise fusion terms: that is what pins this function (RNN-T forward
+ * recursion in numpy).  Also pinned by: permutation of utterances, u_max = 0
+ * (all-blank path only).
+ * Outputs as oq_decode; ranks beyond the number of finals are empty. */
+typedef struct { int32_t *tok; int len; float score; } fin_t;
+
+void oq_decode_alsd(const oq_model_t *M, const float *enc_proj, int T, int B, int W, int u_max,
+                    int max_len, int32_t *tokens_out, int32_t *len_out, float *score_out)
+{
+    const int V = M->V, J = M->joint_out.cols;
+#pragma omp parallel for schedule(dynamic)
+    for (int b = 0; b < B; ++b) {
+        hyp_t *cur = (hyp_t *)malloc(sizeof(hyp_t) * (size_t)W);
+        hyp_t *nxt = (hyp_t *)malloc(sizeof(hyp_t) * (size_t)W);
+        for (int w = 0; w < W; ++w) { hyp_alloc(M, &cur[w]); hyp_alloc(M, &nxt[w]); }
+        fin_t *fin = (fin_t *)calloc((size_t)W + 1, sizeof(fin_t));
+        int nfin = 0;
+        float *S = (float *)malloc(sizeof(float) * (size_t)W);
+        float *F = (float *)malloc(sizeof(float) * (size_t)W * V);
+        float *P = (float *)malloc(sizeof(float) * (size_t)W * J);
+        float *Ls = (float *)malloc(sizeof(float) * (size_t)W * V);
+        float *Le = (float *)malloc(sizeof(float) * (size_t)W * V);
+        int32_t *frow = (int32_t *)malloc(sizeof(int32_t) * (size_t)W);
+        int32_t *par = (int32_t *)malloc(sizeof(int32_t) * (size_t)W);
+        int32_t *tk = (int32_t *)malloc(sizeof(int32_t) * (size_t)W);
+        float *ns = (float *)malloc(sizeof(float) * (size_t)W);
+        int *lead = (int *)malloc(sizeof(int) * (size_t)W);
+        {
+            hyp_t zero; hyp_alloc(M, &zero);
+            hyp_extend(M, &cur[0], &zero, 0, 0.0f);
+            cur[0].len = 0;
+            hyp_free(M, &zero);
+        }
+        for (int i = 0; i < T + u_max; ++i) {
+            int alive = 0;
+            for (int w = 0; w < W; ++w) {
+                const int live = cur[w].score > -INFINITY;
+                alive += live;
+                const hyp_t *h = &cur[live ? w : 0];
+                int t = live ? i - cur[w].len : 0;
+                if (t < 0) t = 0;
+                if (t > T - 1) t = T - 1;
+                frow[w] = t * B + b;
+                S[w] = live ? cur[w].score : -INFINITY;
+                memcpy(P + (int64_t)w * J, h->pred.y, sizeof(float) * (size_t)J);
+                if (M->use_src) memcpy(Ls + (int64_t)w * V, h->src.y, sizeof(float) * (size_t)V);
+                if (M->use_ext) memcpy(Le + (int64_t)w * V, h->ext.y, sizeof(float) * (size_t)V);
+            }
+            if (!alive) break;
+            oq_joint_fuse(enc_proj, frow, P, &M->joint_out, M->inv_s_z,
+                          M->use_src ? Ls : NULL, M->use_ext ? Le : NULL,
+                          M->lambda_src, M->lambda_ext, M->rho, W, M->blank, NULL, NULL, F);
+            /* finished hypotheses and excluded labels leave the candidate set */
+            for (int w = 0; w < W; ++w) {
+                if (!(cur[w].score > -INFINITY)) continue;
+                const int t = i - cur[w].len;
+                if (t == T - 1) {
+                    const float v = S[w] + F[(int64_t)w * V + M->blank];
+                    F[(int64_t)w * V + M->blank] = -INFINITY;
+                    /* insert after every final that is at least as good (insertion order on ties) */
+                    int pos = nfin;
+                    while (pos > 0 && fin[pos - 1].score < v) --pos;
+                    if (pos < W) {
+                        if (nfin == W) { free(fin[W - 1].tok); nfin = W - 1; }
+                        for (int q = nfin; q > pos; --q) fin[q] = fin[q - 1];
+                        fin[pos].len = cur[w].len; fin[pos].score = v;
+                        fin[pos].tok = (int32_t *)malloc(sizeof(int32_t) * (size_t)(cur[w].len + 1));
+                        if (cur[w].len) memcpy(fin[pos].tok, cur[w].tok, sizeof(int32_t) * (size_t)cur[w].len);
+                        ++nfin;
+                    }
+                }
+                if (cur[w].len >= u_max)
+                    for (int k = 0; k < V; ++k)
+                        if (k != M->blank) F[(int64_t)w * V + k] = -INFINITY;
+            }
+            oq_beam_step(S, F, 1, W, V, M->blank, 0, par, tk, ns);
+            /* recombination on the label sequences the picks stand for */
+            for (int r = 0; r < W; ++r) {
+                lead[r] = -1;
+                if (par[r] < 0) continue;
+                lead[r] = r;
+                const hyp_t *hr = &cur[par[r]];
+                const int lr = hr->len + (tk[r] != M->blank);
+                for (int q = 0; q < r; ++q) {
+                    if (par[q] < 0 || lead[q] != q) continue;
+                    const hyp_t *hq = &cur[par[q]];
+                    const int lq = hq->len + (tk[q] != M->blank);
+                    if (lq != lr) continue;
+                    int same = 1;
+                    for (int p = 0; p < lr && same; ++p) {
+                        const int a = p < hr->len ? hr->tok[p] : tk[r];
+                        const int c = p < hq->len ? hq->tok[p] : tk[q];
+                        same = a == c;
+                    }
+                    if (same) { lead[r] = q; break; }
+                }
+            }
+            for (int r = 0; r < W; ++r) {
+                nxt[r].score = -INFINITY;
+                nxt[r].len = 0;
+                if (par[r] < 0 || lead[r] != r) continue;
+                double m = -INFINITY, sum = 0.0;
+                for (int q = r; q < W; ++q)
+                    if (par[q] >= 0 && lead[q] == r && (double)ns[q] > m) m = (double)ns[q];
+                for (int q = r; q < W; ++q)
+                    if (par[q] >= 0 && lead[q] == r) sum += exp((double)ns[q] - m);
+                const float sc = (float)(m + log(sum));
+                if (tk[r] == M->blank) { hyp_copy(M, &nxt[r], &cur[par[r]]); nxt[r].score = sc; }
+                else hyp_extend(M, &nxt[r], &cur[par[r]], tk[r], sc);
+            }
+            hyp_t *tmp = cur; cur = nxt; nxt = tmp;
+        }
+        for (int w = 0; w < W; ++w) {
+            int32_t *dst = tokens_out + ((int64_t)b * W + w) * max_len;
+            for (int q = 0; q < max_len; ++q) dst[q] = -1;
+            if (w < nfin) {
+                const int len = fin[w].len < max_len ? fin[w].len : max_len;
+                if (len) memcpy(dst, fin[w].tok, sizeof(int32_t) * (size_t)len);
+                len_out[b * W + w] = fin[w].len;
+                score_out[b * W + w] = fin[w].score;
+            } else {
+                len_out[b * W + w] = -1;
+                score_out[b * W + w] = -INFINITY;
+            }
+        }
+        for (int q = 0; q < nfin; ++q) free(fin[q].tok);
+        for (int w = 0; w < W; ++w) { hyp_free(M, &cur[w]); hyp_free(M, &nxt[w]); }
+        free(cur); free(nxt); free(fin);
+        free(S); free(F); free(P); free(Ls); free(Le); free(frow); free(par); free(tk); free(ns); free(lead);
+    }
+}
+
 /* Score of one fixed alignment, for the exhaustive-search pin: `actions` is a
  * sequence of symbols (blank advances the frame, a label extends the
  * hypothesis) consumed from frame 0; returns the sum of fused scores along it

@@ -394,3 +394,154 @@ extern "C" qrnnt_status qrnnt_decode_ex(const qrnnt_model *m, const float *enc_p
                                                    tokens_out, len_out, score_out);
     return qr_launch_status();
 }
+
+// ---------------------------------------------------------------------------------------------------------
+// Alignment-length synchronous search with recombination (Sec. 2: the search the paper decodes with).
+
+namespace {
+
+struct AlsdPlan {
+    Plan p;                        // network buffers (2 state buffers), parent_idx / token / active, label trie
+    unsigned long long *hash;      // [2][N]
+    float *fin_score;  int32_t *fin_node, *fin_len;   // [N]
+    int n_iter;
+};
+
+void make_alsd_plan(const qrnnt_model *m, int T, int B, int W, int u_max, void *ws, AlsdPlan &ap)
+{
+    Plan &p = ap.p;
+    p = Plan{};
+    p.T = T; p.B = B; p.W = W; p.N = B * W; p.max_sym = 0;
+    p.R = 1; p.NB = 2; p.V = m->V; p.J = m->joint_out.cols;
+    ap.n_iter = T + u_max;
+    Carver cv{(char *)ws, 0};
+    const size_t N = (size_t)p.N, NB = 2;
+    for (int k = 0; k < 3; ++k) {
+        if (!net_used(m, k)) continue;
+        const qrnnt_net *net = net_of(m, k);
+        for (int l = 0; l < net->n_layers; ++l) {
+            p.net[k].h[l] = cv.take<int8_t>(NB * N * net->layer[l].hidden_size);
+            p.net[k].c[l] = cv.take<float>(NB * N * net->layer[l].hidden_size);
+        }
+        p.net[k].y = cv.take<float>(NB * N * net->out.rows);
+        p.net[k].gx0 = cv.take<int32_t>((size_t)m->V * 4 * net->layer[0].hidden_size);
+        p.net[k].tab0 = cv.take<float>((size_t)m->V * 4 * net->layer[0].hidden_size);
+        p.net[k].mid_q = net->mid.packed ? cv.take<int8_t>(N * net->mid.rows) : nullptr;
+    }
+    p.score = cv.take<float>(NB * N);
+    p.node = cv.take<int32_t>(NB * N);
+    p.len = cv.take<int32_t>(NB * N);
+    ap.hash = cv.take<unsigned long long>(NB * N);
+    p.parent_idx = cv.take<int32_t>(N);
+    p.token = cv.take<int32_t>(N);
+    p.active = cv.take<uint8_t>(N);
+    p.nx_count = cv.take<int32_t>(B);
+    ap.fin_score = cv.take<float>(N);
+    ap.fin_node = cv.take<int32_t>(N);
+    ap.fin_len = cv.take<int32_t>(N);
+    const size_t pool = 1 + (size_t)ap.n_iter * N;
+    p.node_tok = cv.take<int32_t>(pool);
+    p.node_prev = cv.take<int32_t>(pool);
+    p.live = cv.take<int32_t>((size_t)ap.n_iter + 2);
+    p.total = (cv.off + 255) / 256 * 256;
+}
+
+bool alsd_args_ok(int32_t T, int32_t B, int32_t W, int32_t u_max)
+{
+    return T > 0 && B > 0 && W > 0 && W <= 64 && u_max >= 0 && (double)(T + (double)u_max) * B * W < 2.0e9;
+}
+
+}  // namespace
+
+extern "C" size_t qrnnt_decode_alsd_workspace(const qrnnt_model *m, int32_t T, int32_t B, int32_t W, int32_t u_max)
+{
+    if (check_model(m) != QRNNT_OK || !alsd_args_ok(T, B, W, u_max)) return 0;
+    AlsdPlan ap;
+    make_alsd_plan(m, T, B, W, u_max, nullptr, ap);
+    return ap.p.total;
+}
+
+extern "C" qrnnt_status qrnnt_decode_alsd(const qrnnt_model *m, const float *enc_proj, int32_t T, int32_t B, int32_t W,
+                                          int32_t u_max, int32_t max_len, int32_t *tokens_out, int32_t *len_out,
+                                          float *score_out, void *workspace, size_t workspace_bytes, void *stream)
+{
+    qrnnt_status s = check_model(m);
+    if (s != QRNNT_OK) return s;
+    QR_REQUIRE(enc_proj && tokens_out && len_out && score_out && workspace, QRNNT_ERR_NULL);
+    QR_REQUIRE(T > 0 && B > 0 && W > 0 && max_len > 0 && u_max >= 0, QRNNT_ERR_SHAPE);
+    QR_REQUIRE(W <= 64, QRNNT_ERR_UNSUPPORTED);
+    QR_REQUIRE(alsd_args_ok(T, B, W, u_max), QRNNT_ERR_UNSUPPORTED);
+    QR_REQUIRE(qr_aligned(enc_proj, 16) && qr_aligned(workspace, 256), QRNNT_ERR_ALIGN);
+    AlsdPlan ap;
+    make_alsd_plan(m, T, B, W, u_max, workspace, ap);
+    const Plan &p = ap.p;
+    QR_REQUIRE(workspace_bytes >= p.total, QRNNT_ERR_WORKSPACE);
+    hipStream_t st = (hipStream_t)stream;
+    const int N = p.N, V = p.V;
+    const size_t Ns = (size_t)N;
+
+    // zero state in buffer 1, then every slot consumes the start symbol into buffer 0
+    for (int k = 0; k < 3; ++k) {
+        if (!net_used(m, k)) continue;
+        const qrnnt_net *net = net_of(m, k);
+        for (int l = 0; l < net->n_layers; ++l) {
+            const size_t H = (size_t)net->layer[l].hidden_size;
+            size_t nw = Ns * H / 4;
+            fill_words_kernel<<<(unsigned)((nw + 255) / 256), 256, 0, st>>>((uint32_t *)(p.net[k].h[l] + Ns * H), nw, 0u);
+            nw = Ns * H;
+            fill_words_kernel<<<(unsigned)((nw + 255) / 256), 256, 0, st>>>((uint32_t *)(p.net[k].c[l] + Ns * H), nw, 0u);
+        }
+        qr_launch_input_projection(&net->layer[0], net->embed_codes, V, p.net[k].gx0, nullptr, st);
+        qr_launch_gx_table(&net->layer[0], p.net[k].gx0, V, p.net[k].tab0, st);
+    }
+    {
+        size_t nw = (size_t)ap.n_iter + 2;
+        fill_words_kernel<<<(unsigned)((nw + 255) / 256), 256, 0, st>>>((uint32_t *)p.live, nw, 0u);
+        nw = 2 * Ns * 2;
+        fill_words_kernel<<<(unsigned)((nw + 255) / 256), 256, 0, st>>>((uint32_t *)ap.hash, nw, 0u);
+        fill_words_kernel<<<(unsigned)((Ns + 255) / 256), 256, 0, st>>>((uint32_t *)ap.fin_score, Ns, 0xFF800000u);   // -inf
+        fill_words_kernel<<<(unsigned)((Ns + 255) / 256), 256, 0, st>>>((uint32_t *)ap.fin_node, Ns, 0u);
+        fill_words_kernel<<<(unsigned)((Ns + 255) / 256), 256, 0, st>>>((uint32_t *)ap.fin_len, Ns, 0u);
+    }
+    decode_init_kernel<<<(N + 255) / 256 + 1, 256, 0, st>>>(p.score, p.node, p.len, p.parent_idx, p.token, p.active,
+                                                            p.nx_count, p.node_tok, p.node_prev, N, W, B, m->blank);
+    advance_nets(m, p, 1, 0, V, nullptr, st);
+
+    QrJointArgs ja = {};
+    ja.enc = enc_proj;  ja.n_enc_rows = T * B;  ja.frame_row = nullptr;  ja.rows_per_utt = W;  ja.frame_base = 0;
+    ja.w = (const v4i *)m->joint_out.packed;  ja.s_w = m->joint_out.row_scale;  ja.b_out = m->joint_bias;
+    ja.z_scale = m->z_scale;  ja.z_inv = m->z_inv_scale;
+    ja.lambda_src = m->lambda_src;  ja.lambda_ext = m->lambda_ext;  ja.rho = m->rho;
+    ja.N = N;  ja.J = p.J;  ja.V = V;  ja.blank = m->blank;
+    ja.nkc = qr_round_up(p.J, QRNNT_KCHUNK) / QRNNT_KCHUNK;
+    ja.w8 = qr_bits(&m->joint_out) == 8;
+
+    int cur = 0;
+    for (int i = 0; i < ap.n_iter; ++i) {
+        const int nxt = cur ^ 1;
+        ja.pred = p.net[0].y + (size_t)cur * Ns * p.J;
+        ja.lp_src = m->use_src ? p.net[1].y + (size_t)cur * Ns * V : nullptr;
+        ja.lp_ext = m->use_ext ? p.net[2].y + (size_t)cur * Ns * V : nullptr;
+        QrRouteArgs ra = {};
+        ra.score_src = p.score + (size_t)cur * Ns;
+        ra.B = B;  ra.W = W;  ra.V = V;  ra.R = 1;  ra.blank = m->blank;  ra.src_buf = cur;  ra.last_round = 0;
+        ra.node_base = 1 + i * N;
+        ra.node_src = p.node + (size_t)cur * Ns;  ra.len_src = p.len + (size_t)cur * Ns;
+        ra.score_dst = p.score + (size_t)nxt * Ns;  ra.node_dst = p.node + (size_t)nxt * Ns;
+        ra.len_dst = p.len + (size_t)nxt * Ns;
+        ra.parent_idx = p.parent_idx;  ra.token = p.token;  ra.active = p.active;
+        ra.node_tok = p.node_tok;  ra.node_prev = p.node_prev;
+        ra.gate = i > 0 ? p.live + i : nullptr;   // live[i]: utterances with a live hypothesis entering iteration i
+        ra.live_next = p.live + i + 1;
+        QrAlsdArgs sa = {};
+        sa.iter = i;  sa.T = T;  sa.u_max = u_max;
+        sa.hash_src = ap.hash + (size_t)cur * Ns;  sa.hash_dst = ap.hash + (size_t)nxt * Ns;
+        sa.fin_score = ap.fin_score;  sa.fin_node = ap.fin_node;  sa.fin_len = ap.fin_len;
+        qr_launch_joint_alsd(ja, ra, sa, st);
+        if (i + 1 < ap.n_iter) advance_nets(m, p, cur, nxt, V, ra.live_next, st);
+        cur = nxt;
+    }
+    backtrack_kernel<<<(N + 63) / 64, 64, 0, st>>>(ap.fin_score, ap.fin_node, ap.fin_len, p.node_tok, p.node_prev, N,
+                                                   max_len, tokens_out, len_out, score_out);
+    return qr_launch_status();
+}

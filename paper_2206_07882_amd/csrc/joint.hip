@@ -103,8 +103,11 @@ __global__ __launch_bounds__(256) void joint_fuse_kernel(const QrJointArgs a)
 // Lane (grp, col) of wave 0 holds, in slot s = 16*nt + 4*mt + i, the candidate
 // (hypothesis w = 16*nt + col, token k = 16*mt + 4*grp + i); its flat index
 // w*V + k grows with s, so the first best slot of a lane is its lowest index.
-template <int NTW>
-__global__ __launch_bounds__(256) void joint_route_kernel(const QrJointArgs a, const QrRouteArgs r)
+// ALSD: the same joint + selection inside the alignment-length synchronous search (route.h, qr_alsd_route):
+// every hypothesis reads its own encoder frame (iteration - labels so far), a blank at the last frame
+// finishes a hypothesis instead of being a candidate, labels beyond the cap are no candidates.
+template <int NTW, bool ALSD>
+__global__ __launch_bounds__(256) void joint_route_kernel(const QrJointArgs a, const QrRouteArgs r, const QrAlsdArgs s)
 {
     __shared__ v4i lds[4 * 4 * 64];
     const int lane = threadIdx.x & 63;
@@ -113,6 +116,7 @@ __global__ __launch_bounds__(256) void joint_route_kernel(const QrJointArgs a, c
     const int b = blockIdx.x;
     const int W = r.W, V = a.V, J = a.J;
     if (r.gate && *r.gate == 0) {   // uniform: no utterance carried a label into this round, nothing can be picked
+        if (ALSD) return;           // no live hypothesis anywhere: the finals stay as they are
         if (wave == 0) {
             if (lane == 0 && b == 0 && r.live_clear) *r.live_clear = 0;
             if (r.last_round) qr_frame_end(r, b, lane, r.nx_count[b]);
@@ -121,12 +125,14 @@ __global__ __launch_bounds__(256) void joint_route_kernel(const QrJointArgs a, c
     }
     int fr = a.frame_base + b;
     fr = fr < 0 ? 0 : (fr >= a.n_enc_rows ? a.n_enc_rows - 1 : fr);
-    const float *e = a.enc + (int64_t)fr * J + grp * 16;
+    const float *e_utt = a.enc + (int64_t)fr * J + grp * 16;
     const float z_inv = a.z_inv;
     const int zbits = a.w8 ? 8 : 4;
     const int n_row_tiles = (V + 15) >> 4;
     constexpr int PER = 16 * NTW;
     float val[PER];
+    float *fin_new = (float *)lds + 256;   // ALSD: value of hypothesis w finishing now; wave 0's own part of the buffer
+    if (ALSD && wave == 0) fin_new[lane] = -INFINITY;
     // per-token constants of this lane's 16 tokens
     float wscale[4][4], wbias[4][4];
     if (wave == 0) {
@@ -146,6 +152,14 @@ __global__ __launch_bounds__(256) void joint_route_kernel(const QrJointArgs a, c
         const bool wv = w < W;
         const int n = b * W + (wv ? w : W - 1);
         const float *p = a.pred + (int64_t)n * J + grp * 16;
+        const float *e = e_utt;
+        int len_w = 0, t_w = 0;
+        if (ALSD) {   // this hypothesis' own frame
+            len_w = r.len_src[n];
+            t_w = s.iter - len_w;
+            t_w = t_w < 0 ? 0 : (t_w > s.T - 1 ? s.T - 1 : t_w);
+            e = a.enc + ((int64_t)t_w * r.B + b) * J + grp * 16;
+        }
         auto bfrag = [&](int kb) -> v4i {
             v4i bq = {0, 0, 0, 0};
             if (kb * 64 + grp * 16 < J) {
@@ -213,7 +227,14 @@ __global__ __launch_bounds__(256) void joint_route_kernel(const QrJointArgs a, c
                         if (a.lp_ext) f += a.lambda_ext * le[mt][i];
                         f += a.rho;
                     }
-                    const bool ok = wv && k < V && (!r.last_round || k == a.blank);
+                    bool ok = wv && k < V && (ALSD || !r.last_round || k == a.blank);
+                    if (ALSD) {
+                        if (k != a.blank && len_w >= s.u_max) ok = false;      // label cap
+                        if (k == a.blank && t_w == s.T - 1) {                  // a blank at the last frame finishes w
+                            if (ok && sc > -INFINITY) fin_new[w] = sc + f;
+                            ok = false;
+                        }
+                    }
                     val[nt * 16 + mt * 4 + i] = ok ? (sc + f) + 0.0f : -INFINITY;   // + 0: one key per value
                 }
         }
@@ -239,6 +260,11 @@ __global__ __launch_bounds__(256) void joint_route_kernel(const QrJointArgs a, c
         }
         if (!qr_select_round(bv, bc, rd, lane, last_v, last_c, my_c, my_v)) break;
     }
+    if (ALSD) {
+        __builtin_amdgcn_wave_barrier();
+        qr_alsd_route(r, s, b, lane, my_c, my_v, fin_new[lane]);
+        return;
+    }
     const int cnt = qr_route_picks(r, b, lane, my_c, my_v);
     if (r.last_round) {   // the frame is complete for this utterance: prune its candidate list to the new beam
         __threadfence();
@@ -250,9 +276,17 @@ __global__ __launch_bounds__(256) void joint_route_kernel(const QrJointArgs a, c
 
 void qr_launch_joint_route(const QrJointArgs &a, const QrRouteArgs &r, hipStream_t st)
 {
-    if (r.W <= 16) joint_route_kernel<1><<<r.B, 256, 0, st>>>(a, r);
-    else if (r.W <= 32) joint_route_kernel<2><<<r.B, 256, 0, st>>>(a, r);
-    else joint_route_kernel<4><<<r.B, 256, 0, st>>>(a, r);
+    const QrAlsdArgs none = {};
+    if (r.W <= 16) joint_route_kernel<1, false><<<r.B, 256, 0, st>>>(a, r, none);
+    else if (r.W <= 32) joint_route_kernel<2, false><<<r.B, 256, 0, st>>>(a, r, none);
+    else joint_route_kernel<4, false><<<r.B, 256, 0, st>>>(a, r, none);
+}
+
+void qr_launch_joint_alsd(const QrJointArgs &a, const QrRouteArgs &r, const QrAlsdArgs &s, hipStream_t st)
+{
+    if (r.W <= 16) joint_route_kernel<1, true><<<r.B, 256, 0, st>>>(a, r, s);
+    else if (r.W <= 32) joint_route_kernel<2, true><<<r.B, 256, 0, st>>>(a, r, s);
+    else joint_route_kernel<4, true><<<r.B, 256, 0, st>>>(a, r, s);
 }
 
 void qr_launch_joint(const QrJointArgs &a, hipStream_t st)

@@ -84,6 +84,15 @@ struct QrRouteArgs {
 };
 
 // One direction of the persistent recurrence (see recurrence.hip).
+// Alignment-length synchronous search: what one iteration needs beyond QrRouteArgs (of which it uses score/node/len
+// src and dst, parent_idx/token/active, the label trie, node_base, gate and live_next).
+struct QrAlsdArgs {
+    int iter, T, u_max;                              // hypothesis w stands at frame iter - len[w]
+    const unsigned long long *hash_src;              // [N] hash of the label sequence (recombination key, with the length)
+    unsigned long long *hash_dst;
+    float *fin_score;  int32_t *fin_node, *fin_len;  // [B,W] the W best finished hypotheses so far, best first
+};
+
 struct QrRecArgs {
     const v4i *whh;  const float *s_wih, *s_whh, *bias;
     const int32_t *gx;                 // [T*B, 4H] gate-interleaved input projection
@@ -115,5 +124,6 @@ QR_HIDDEN void qr_launch_linear_group(const QrLinearGroup &g, hipStream_t st);
 QR_HIDDEN void qr_launch_linear(const QrLinearArgs &a, hipStream_t st);
 QR_HIDDEN void qr_launch_joint(const QrJointArgs &a, hipStream_t st);
 QR_HIDDEN void qr_launch_joint_route(const QrJointArgs &a, const QrRouteArgs &r, hipStream_t st);
+QR_HIDDEN void qr_launch_joint_alsd(const QrJointArgs &a, const QrRouteArgs &r, const QrAlsdArgs &s, hipStream_t st);
 QR_HIDDEN void qr_launch_beam(const float *score, const float *fused, int B, int W, int V, int blank, int force_blank,
                               int32_t *parent_out, int32_t *token_out, float *score_out, hipStream_t st);

@@ -94,3 +94,102 @@ __device__ __forceinline__ void qr_frame_end(const QrRouteArgs &a, int b, int la
     }
     if (lane == 0) a.nx_count[b] = 0;
 }
+
+// One iteration of the alignment-length synchronous search for utterance b (one wave; Sec. 2 names the search,
+// the algorithm is the published one).  Lane r < W holds pick r (flat candidate index c = parent*V + token or -1,
+// score v) and, as fin_new, the score with which hypothesis r of the current beam finishes now (-inf: it does not).
+//   - pick r becomes slot r of the next beam: a blank keeps the parent's sequence and state (the network
+//     advance copies inactive rows through), a label extends it;
+//   - recombination: picks that stand for the same label sequence (same length and same 64-bit sequence hash)
+//     are one hypothesis; the best-ranked keeps its slot with log(sum exp(scores)), the others die;
+//   - the running list of the W best finished hypotheses takes the new ones in, ordered by (score descending,
+//     insertion order), new ones in slot order.
+__device__ __forceinline__ void qr_alsd_route(const QrRouteArgs &a, const QrAlsdArgs &s, int b, int lane, int c, float v,
+                                              float fin_new)
+{
+    const int W = a.W, V = a.V;
+    const bool in = lane < W;
+    const bool found = in && c >= 0;
+    const int par = found ? c / V : 0, tok = found ? c - (c / V) * V : a.blank;
+    const bool is_lab = found && tok != a.blank;
+    const int src_slot = b * W + par;
+    const int own = b * W + (in ? lane : 0);
+    const int len_p = found ? a.len_src[src_slot] : 0;
+    const unsigned long long hash_p = found ? s.hash_src[src_slot] : 0ull;
+    const int node_p = found ? a.node_src[src_slot] : 0;
+    // the current beam's own slot, for the finals
+    const int own_node = a.node_src[own], own_len = a.len_src[own];
+    const int new_len = len_p + (is_lab ? 1 : 0);
+    const unsigned long long new_hash = is_lab ? hash_p * 0x9E3779B97F4A7C15ull + (unsigned long long)(tok + 1) : hash_p;
+    const int h_lo = (int)(unsigned)new_hash, h_hi = (int)(unsigned)(new_hash >> 32);
+    const int fnd = found ? 1 : 0;
+    int leader = lane;
+    float m = v;
+    for (int j = 0; j < W; ++j) {
+        const bool same = found && __builtin_amdgcn_readlane(fnd, j) && __builtin_amdgcn_readlane(h_lo, j) == h_lo &&
+                          __builtin_amdgcn_readlane(h_hi, j) == h_hi && __builtin_amdgcn_readlane(new_len, j) == new_len;
+        const float vj = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), j));
+        if (same) {
+            leader = j < leader ? j : leader;
+            m = fmaxf(m, vj);
+        }
+    }
+    float sum = 0.0f;
+    for (int j = 0; j < W; ++j) {
+        const bool same = found && __builtin_amdgcn_readlane(fnd, j) && __builtin_amdgcn_readlane(h_lo, j) == h_lo &&
+                          __builtin_amdgcn_readlane(h_hi, j) == h_hi && __builtin_amdgcn_readlane(new_len, j) == new_len;
+        const float vj = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), j));
+        if (same) sum += qr_exp(vj - m);
+    }
+    const bool keep = found && leader == lane;
+    const unsigned long long km = __ballot(keep);
+    if (lane == 0 && km != 0ull && a.live_next) atomicAdd(a.live_next, 1);
+    if (in) {
+        const int dst = b * W + lane;
+        if (keep) {
+            int node = node_p;
+            if (is_lab) {
+                node = a.node_base + dst;
+                a.node_tok[node] = tok;
+                a.node_prev[node] = node_p;
+            }
+            a.score_dst[dst] = m + qr_log(sum);
+            a.node_dst[dst] = node;
+            a.len_dst[dst] = new_len;
+            s.hash_dst[dst] = new_hash;
+            a.parent_idx[dst] = src_slot;
+            a.token[dst] = tok;
+            a.active[dst] = is_lab ? 1 : 0;
+        } else {
+            a.score_dst[dst] = -INFINITY;
+            a.node_dst[dst] = 0;
+            a.len_dst[dst] = 0;
+            s.hash_dst[dst] = 0ull;
+            a.parent_idx[dst] = dst;
+            a.token[dst] = a.blank;
+            a.active[dst] = 0;
+        }
+    }
+    // finished hypotheses
+    const float fn = in ? fin_new : -INFINITY;
+    if (__ballot(fn > -INFINITY) == 0ull) return;   // uniform
+    const float fo = in ? s.fin_score[own] : -INFINITY;
+    const int fo_node = in ? s.fin_node[own] : 0, fo_len = in ? s.fin_len[own] : 0;
+    int rank_o = 0, rank_n = 0;
+    for (int j = 0; j < W; ++j) {
+        const float oj = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(fo), j));
+        const float nj = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(fn), j));
+        rank_o += ((oj > fo) || (oj == fo && j < lane)) ? 1 : 0;
+        rank_o += (nj > fo) ? 1 : 0;
+        rank_n += (oj >= fn) ? 1 : 0;
+        rank_n += ((nj > fn) || (nj == fn && j < lane)) ? 1 : 0;
+    }
+    if (in && rank_o < W) {
+        const int o = b * W + rank_o;
+        s.fin_score[o] = fo;  s.fin_node[o] = fo_node;  s.fin_len[o] = fo_len;
+    }
+    if (in && rank_n < W) {
+        const int o = b * W + rank_n;
+        s.fin_score[o] = fn;  s.fin_node[o] = fn > -INFINITY ? own_node : 0;  s.fin_len[o] = fn > -INFINITY ? own_len : 0;
+    }
+}

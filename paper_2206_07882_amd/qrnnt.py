@@ -62,7 +62,8 @@ EXPORTS = ["qrnnt_status_str", "qrnnt_abi_version", "qrnnt_pack_int4_bytes", "qr
            "qrnnt_quantize_act", "qrnnt_linear", "qrnnt_linear_quant", "qrnnt_lstm_step", "qrnnt_lstm_layer_workspace", "qrnnt_lstm_layer",
            "qrnnt_input_projection", "qrnnt_input_table", "qrnnt_lstm_step_group",
            "qrnnt_bilstm_layer_workspace", "qrnnt_bilstm_layer",
-           "qrnnt_joint_fuse", "qrnnt_beam_step", "qrnnt_decode_workspace", "qrnnt_decode", "qrnnt_decode_ex"]
+           "qrnnt_joint_fuse", "qrnnt_beam_step", "qrnnt_decode_workspace", "qrnnt_decode", "qrnnt_decode_ex",
+           "qrnnt_decode_alsd_workspace", "qrnnt_decode_alsd"]
 
 DECODE_EARLY_STOP = 1
 
@@ -89,6 +90,8 @@ def load():
         lib.qrnnt_bilstm_layer_workspace.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32]
         lib.qrnnt_decode_workspace.restype = C.c_size_t
         lib.qrnnt_decode_workspace.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32]
+        lib.qrnnt_decode_alsd_workspace.restype = C.c_size_t
+        lib.qrnnt_decode_alsd_workspace.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32]
         _lib = lib
     return _lib
 
@@ -470,4 +473,32 @@ def decode(model: Model, enc_proj: torch.Tensor, W: int, max_sym: int, max_len: 
                                 C.c_int32(max_sym), C.c_int32(max_len), C.c_uint32(flags), _ptr(tokens), _ptr(lens),
                                 _ptr(scores), _ptr(workspace), C.c_size_t(workspace.numel()), _stream())
     _check(st, "qrnnt_decode_ex")
+    return tokens, lens, scores
+
+
+def decode_alsd_workspace(model: Model, T: int, B: int, W: int, u_max: int) -> int:
+    cm = model.c()
+    return int(load().qrnnt_decode_alsd_workspace(C.byref(cm), T, B, W, u_max))
+
+
+def decode_alsd(model: Model, enc_proj: torch.Tensor, W: int, u_max: int, max_len: Optional[int] = None,
+                workspace: Optional[torch.Tensor] = None):
+    """Alignment-length synchronous search with recombination; at most u_max labels per utterance."""
+    T, B, J = enc_proj.shape
+    dev = enc_proj.device
+    if max_len is None:
+        max_len = max(1, u_max)
+    cm = model.c()
+    need = int(load().qrnnt_decode_alsd_workspace(C.byref(cm), T, B, W, u_max))
+    if need == 0:
+        _check(2, "qrnnt_decode_alsd_workspace")
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=dev)
+    tokens = torch.empty((B, W, max_len), dtype=torch.int32, device=dev)
+    lens = torch.empty((B, W), dtype=torch.int32, device=dev)
+    scores = torch.empty((B, W), dtype=torch.float32, device=dev)
+    st = load().qrnnt_decode_alsd(C.byref(cm), _ptr(enc_proj, torch.float32), C.c_int32(T), C.c_int32(B), C.c_int32(W),
+                                  C.c_int32(u_max), C.c_int32(max_len), _ptr(tokens), _ptr(lens), _ptr(scores),
+                                  _ptr(workspace), C.c_size_t(workspace.numel()), _stream())
+    _check(st, "qrnnt_decode_alsd")
     return tokens, lens, scores

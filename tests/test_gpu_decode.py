@@ -171,3 +171,58 @@ def test_decode_early_stop_gives_the_same_beams(gpu_lib, blank_bias):
     _compare_beams(fixed, ref)
     for a, b in zip(fixed, early):
         assert torch.equal(a, b)
+
+
+@pytest.mark.parametrize("B,W,u_max,T,lms,std", [(3, 4, 6, 8, True, 0.5), (2, 1, 5, 10, True, 0.6), (4, 16, 8, 6, True, 0.5),
+                                                 (2, 3, 0, 8, False, 0.6), (5, 8, 3, 9, False, 0.4), (3, 33, 4, 4, True, 0.5),
+                                                 (2, 64, 3, 3, True, 0.5)])
+def test_alsd_matches_oracle(gpu_lib, B, W, u_max, T, lms, std):
+    """Alignment-length synchronous search with recombination (Sec. 2) on the tiny configuration: the finished
+    lists (label sequences, lengths, merged scores) must be the oracle's."""
+    from paper_2206_07882_amd import model as gmodel
+    m = synth.make_model(0, weight_std=std)
+    if not lms:
+        m.lm_src = m.lm_ext = None
+    m.rho = 0.1
+    e = synth.normal(400 + B + W, (T, B, m.J), 1.0)
+    ref = oracle.decode_alsd(omodels.model_from_float(m), e, W, u_max)
+    got = gpu_lib.decode_alsd(gmodel.model_from_float(m, DEV), dev(e), W, u_max)
+    _compare_beams(got, ref)
+    if u_max > 0 and W > 1:
+        assert (ref[1] > 0).any()
+
+
+def test_alsd_recombination_is_exercised_and_matters(gpu_lib):
+    """With a small vocabulary the picks of an iteration hold many duplicates of one label sequence: the merged
+    scores differ from the scores of the search without merging, and the GPU has the merged ones."""
+    from paper_2206_07882_amd import model as gmodel
+    m = synth.make_model(0, weight_std=0.5)
+    T, B, W, u_max = 6, 2, 16, 4
+    e = synth.normal(420, (T, B, m.J), 1.0)
+    M = omodels.model_from_float(m)
+    ref = oracle.decode_alsd(M, e, W, u_max)
+    got = gpu_lib.decode_alsd(gmodel.model_from_float(m, DEV), dev(e), W, u_max)
+    _compare_beams(got, ref)
+    # the best finished hypothesis carries more probability mass than any single alignment of it can
+    for b in range(B):
+        L = int(ref[1][b, 0])
+        y = ref[0][b, 0, :L].tolist()
+        # the single best alignment found by the time-synchronous search without merging
+        ts = oracle.decode(M, np.ascontiguousarray(e[:, b:b + 1]), W, u_max)
+        same = [r for r in range(W) if ts[1][0, r] == L and ts[0][0, r, :L].tolist() == y]
+        if same:
+            assert ref[2][b, 0] > ts[2][0, same[0]] + 1e-3
+
+
+def test_alsd_full_width_networks(gpu_lib):
+    """The measured layer widths (and the Sec. 2 shapes with the mixed-precision map) under the alignment-length
+    synchronous search: 8 hypotheses (weight-streaming step kernel) and 128 (tiled step kernel)."""
+    from paper_2206_07882_amd import model as gmodel
+    for m in (synth.make_model(4, enc_layers=1), synth.make_model(5, enc_layers=1, mixed=True)):
+        M = omodels.model_from_float(m)
+        G = gmodel.model_from_float(m, DEV)
+        for (T, B, W, u_max) in ((4, 2, 4, 3), (2, 8, 16, 2)):
+            e = synth.normal(430 + B, (T, B, m.J), 1.0)
+            ref = oracle.decode_alsd(M, e, W, u_max)
+            got = gpu_lib.decode_alsd(G, dev(e), W, u_max)
+            _compare_beams(got, ref)

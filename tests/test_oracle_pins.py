@@ -586,6 +586,58 @@ def test_beam_search_equals_exhaustive_enumeration_when_nothing_is_pruned():
     assert sc2[0, 0] <= sc[0, 0] + 1e-6
 
 
+def test_alsd_without_pruning_sums_over_all_alignments():
+    # Alignment-length synchronous search with recombination (the paper's search, Sec. 2): with a beam so wide
+    # that nothing is pruned, the final score of a label sequence is the log of its total probability over all
+    # alignments (the transducer's forward recursion, restated here in numpy) plus its label-wise terms of Eq. 1.
+    import itertools
+    for seed, lms in ((41, True), (42, False)):
+        m = _tiny_model(seed, V=3, with_lms=lms)
+        rng = np.random.default_rng(seed)
+        T, B, u_max, W = 3, 2, 2, 200
+        e = rng.standard_normal((T, B, m.joint_out.cols)).astype(np.float32)
+        tok, ln, sc = oracle.decode_alsd(m, e, W, u_max)
+        seqs = [()] + [s for u in (1, 2) for s in itertools.product((1, 2), repeat=u)]
+        for b in range(B):
+            got = {tuple(tok[b, r, :ln[b, r]]): float(sc[b, r]) for r in range(W) if ln[b, r] >= 0}
+            assert sorted(got) == sorted(seqs)                       # every sequence finishes exactly once
+            fin = [float(sc[b, r]) for r in range(W) if ln[b, r] >= 0]
+            assert fin == sorted(fin, reverse=True)
+            for y in seqs:
+                U = len(y)
+                F = np.stack([np.stack([_fused_row(m, e, t * B + b, list(y[:u])) for u in range(U + 1)])
+                              for t in range(T)]).astype(np.float64)   # [t, u, k]
+                alpha = np.full((T, U + 1), -np.inf)
+                alpha[0, 0] = 0.0
+                for t in range(T):
+                    for u in range(U + 1):
+                        if t > 0:
+                            alpha[t, u] = np.logaddexp(alpha[t, u], alpha[t - 1, u] + F[t - 1, u, 0])
+                        if u > 0:
+                            alpha[t, u] = np.logaddexp(alpha[t, u], alpha[t, u - 1] + F[t, u - 1, y[u - 1]])
+                total = alpha[T - 1, U] + F[T - 1, U, 0]
+                assert abs(got[y] - total) < 2e-4, (y, got[y], total)
+        # u_max = 0: only the all-blank alignment exists
+        tok0, ln0, sc0 = oracle.decode_alsd(m, e, 4, 0)
+        for b in range(B):
+            ref = np.float32(0)
+            for t in range(T):
+                ref = np.float32(ref + _fused_row(m, e, t * B + b, [])[0])
+            assert ln0[b].tolist() == [0, -1, -1, -1] and abs(sc0[b, 0] - ref) < 1e-5
+
+
+def test_alsd_permuting_utterances_permutes_outputs():
+    m = _tiny_model(43, V=5)
+    rng = np.random.default_rng(43)
+    e = rng.standard_normal((5, 3, m.joint_out.cols)).astype(np.float32)
+    a = oracle.decode_alsd(m, e, 4, 6)
+    perm = [2, 0, 1]
+    p = oracle.decode_alsd(m, np.ascontiguousarray(e[:, perm]), 4, 6)
+    for x, y in zip(a, p):
+        assert np.array_equal(x[perm], y)
+    assert (a[1][:, 0] > 0).any()
+
+
 def test_decode_permuting_utterances_permutes_outputs():
     m = _tiny_model(24, V=5)
     rng = np.random.default_rng(24)
