@@ -132,7 +132,11 @@ __global__ __launch_bounds__(256) void joint_route_kernel(const QrJointArgs a, c
     constexpr int PER = 16 * NTW;
     float val[PER];
     float *fin_new = (float *)lds + 256;   // ALSD: value of hypothesis w finishing now; wave 0's own part of the buffer
-    if (ALSD && wave == 0) fin_new[lane] = -INFINITY;
+    QrAlsdOwn own = {};
+    if (ALSD && wave == 0) {
+        fin_new[lane] = -INFINITY;
+        own = qr_alsd_load_own(r, s, b, lane);
+    }
     // per-token constants of this lane's 16 tokens
     float wscale[4][4], wbias[4][4];
     if (wave == 0) {
@@ -262,7 +266,7 @@ __global__ __launch_bounds__(256) void joint_route_kernel(const QrJointArgs a, c
     }
     if (ALSD) {
         __builtin_amdgcn_wave_barrier();
-        qr_alsd_route(r, s, b, lane, my_c, my_v, fin_new[lane]);
+        qr_alsd_route(r, s, b, lane, my_c, my_v, fin_new[lane], own);
         return;
     }
     const int cnt = qr_route_picks(r, b, lane, my_c, my_v);

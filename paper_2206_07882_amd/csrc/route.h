@@ -104,8 +104,25 @@ __device__ __forceinline__ void qr_frame_end(const QrRouteArgs &a, int b, int la
 //     are one hypothesis; the best-ranked keeps its slot with log(sum exp(scores)), the others die;
 //   - the running list of the W best finished hypotheses takes the new ones in, ordered by (score descending,
 //     insertion order), new ones in slot order.
+// What lane w < W of the routing wave knows about hypothesis w of the current beam and rank w of the finished
+// list: fetched at the start of the kernel, so that nothing in the routing waits for memory.
+struct QrAlsdOwn {
+    int len, node;
+    unsigned long long hash;
+    float fin_score;  int fin_node, fin_len;
+};
+
+__device__ __forceinline__ QrAlsdOwn qr_alsd_load_own(const QrRouteArgs &a, const QrAlsdArgs &s, int b, int lane)
+{
+    const int own = b * a.W + (lane < a.W ? lane : 0);
+    QrAlsdOwn o;
+    o.len = a.len_src[own];  o.node = a.node_src[own];  o.hash = s.hash_src[own];
+    o.fin_score = s.fin_score[own];  o.fin_node = s.fin_node[own];  o.fin_len = s.fin_len[own];
+    return o;
+}
+
 __device__ __forceinline__ void qr_alsd_route(const QrRouteArgs &a, const QrAlsdArgs &s, int b, int lane, int c, float v,
-                                              float fin_new)
+                                              float fin_new, const QrAlsdOwn &o)
 {
     const int W = a.W, V = a.V;
     const bool in = lane < W;
@@ -114,11 +131,12 @@ __device__ __forceinline__ void qr_alsd_route(const QrRouteArgs &a, const QrAlsd
     const bool is_lab = found && tok != a.blank;
     const int src_slot = b * W + par;
     const int own = b * W + (in ? lane : 0);
-    const int len_p = found ? a.len_src[src_slot] : 0;
-    const unsigned long long hash_p = found ? s.hash_src[src_slot] : 0ull;
-    const int node_p = found ? a.node_src[src_slot] : 0;
-    // the current beam's own slot, for the finals
-    const int own_node = a.node_src[own], own_len = a.len_src[own];
+    // the parent's sequence, taken from the lane that holds it
+    const int len_p = __shfl(o.len, par);
+    const int node_p = __shfl(o.node, par);
+    const unsigned long long hash_p = ((unsigned long long)(unsigned)__shfl((int)(unsigned)(o.hash >> 32), par) << 32) |
+                                      (unsigned long long)(unsigned)__shfl((int)(unsigned)o.hash, par);
+    const int own_node = o.node, own_len = o.len;
     const int new_len = len_p + (is_lab ? 1 : 0);
     const unsigned long long new_hash = is_lab ? hash_p * 0x9E3779B97F4A7C15ull + (unsigned long long)(tok + 1) : hash_p;
     const int h_lo = (int)(unsigned)new_hash, h_hi = (int)(unsigned)(new_hash >> 32);
@@ -173,8 +191,8 @@ __device__ __forceinline__ void qr_alsd_route(const QrRouteArgs &a, const QrAlsd
     // finished hypotheses
     const float fn = in ? fin_new : -INFINITY;
     if (__ballot(fn > -INFINITY) == 0ull) return;   // uniform
-    const float fo = in ? s.fin_score[own] : -INFINITY;
-    const int fo_node = in ? s.fin_node[own] : 0, fo_len = in ? s.fin_len[own] : 0;
+    const float fo = in ? o.fin_score : -INFINITY;
+    const int fo_node = o.fin_node, fo_len = o.fin_len;
     int rank_o = 0, rank_n = 0;
     for (int j = 0; j < W; ++j) {
         const float oj = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(fo), j));
