@@ -94,6 +94,36 @@ def test_argument_validation_happens_before_any_launch():
     assert lib.qrnnt_status_str(5) == b"workspace too small"
 
 
+def test_validation_of_the_8bit_and_search_entry_points():
+    lib = qrnnt.load()
+    P = C.c_void_p
+    # 8-bit blobs take twice the bytes of 4-bit ones, layout rules are the same
+    assert qrnnt.pack_bytes(2560, 352, qrnnt.LAYOUT_TILED_GATES, 8) == 160 * 3 * 2048
+    assert qrnnt.pack_bytes(5, 70, qrnnt.LAYOUT_ROWMAJOR, 8) == 5 * 128
+    assert qrnnt.pack_bytes(6, 64, qrnnt.LAYOUT_TILED_GATES, 8) == 0
+    assert lib.qrnnt_pack_int8(None, 0, 4, 16, 1, P(0x1000), None, None) == 1
+    assert lib.qrnnt_pack_int8(P(0x1000), 0, 4, 16, 1, P(0x1001), None, None) == 3
+    assert lib.qrnnt_quantize_act8(None, C.c_int64(4), C.c_float(1.0), P(0x1000), None) == 1
+    assert lib.qrnnt_quantize_act8(P(0x1000), C.c_int64(4), C.c_float(0.0), P(0x1000), None) == 4
+    # a width other than 4 or 8 is refused; the single-step entry points refuse 8-bit layers
+    bad = _qmat(rows=46, cols=256, layout=1); bad.bits = 5
+    assert lib.qrnnt_linear(C.byref(bad), None, C.c_float(0.1), P(0x1000), 4, 0, P(0x2000), None, None) == 4
+    w8 = _qmat(rows=64, cols=64); w8.bits = 8
+    h8 = _qmat(rows=64, cols=16); h8.bits = 8
+    args = lambda L: (C.byref(L), P(0x1000), None, 4, None, P(0x2000), P(0x4000), 4, None, 4, P(0x3000), P(0x5000),
+                      None, None, None, None)
+    assert lib.qrnnt_lstm_step(*args(_lstm(w_ih=w8, w_hh=h8))) == 7
+    assert lib.qrnnt_lstm_step(*args(_lstm(w_ih=w8, w_hh=_qmat(rows=64, cols=16)))) == 4      # widths must agree
+    # linear_quant: the consumer's width is 4 or 8
+    w = _qmat(rows=48, cols=256, layout=1)
+    lq = lambda bits, q=P(0x2000): (C.byref(w), None, C.c_float(0.1), P(0x1000), 4, C.c_float(7.0), bits, q, None)
+    assert lib.qrnnt_linear_quant(*lq(6)) == 4
+    assert lib.qrnnt_linear_quant(*lq(4, None)) == 1
+    # searches: a NULL model or impossible sizes give a zero workspace
+    assert lib.qrnnt_decode_alsd_workspace(None, 10, 2, 4, 5) == 0
+    assert lib.qrnnt_decode_workspace(None, 10, 2, 4, 2) == 0
+
+
 def test_product_path_does_not_reference_the_oracle():
     """The GPU package must never import or call the test oracle."""
     pkg = os.path.join(ROOT, "paper_2206_07882_amd")
