@@ -8,6 +8,11 @@
 
 namespace {
 
+// The 16 encoder and 16 prediction values of one lane's K block, as loaded.
+struct QrJointRaw {
+    v4f e[4], p[4];
+};
+
 // One block (4 waves) per 16 hypotheses; the J columns are dealt to the waves in
 // 64-column blocks.  Lane (col, grp) produces the 16 codes of z that are its own
 // MFMA operand for that block, so z never leaves registers; partial sums meet in
@@ -28,17 +33,26 @@ __global__ __launch_bounds__(256) void joint_fuse_kernel(const QrJointArgs a)
     const int J = a.J;
     const float z_inv = a.z_inv;
     const int zbits = a.w8 ? 8 : 4;
-    auto bfrag = [&](int kb) -> v4i {
+    auto bload = [&](int kb) -> QrJointRaw {
+        QrJointRaw raw = {};
+        if (kb * 64 + grp * 16 < J) {
+#pragma unroll
+            for (int d = 0; d < 4; ++d) {
+                raw.e[d] = *(const v4f *)(e + kb * 64 + 4 * d);
+                raw.p[d] = *(const v4f *)(p + kb * 64 + 4 * d);
+            }
+        }
+        return raw;
+    };
+    auto bmake = [&](const QrJointRaw &raw, int kb) -> v4i {
         v4i b = {0, 0, 0, 0};
         if (kb * 64 + grp * 16 < J) {
 #pragma unroll
             for (int d = 0; d < 4; ++d) {
-                const v4f ev = *(const v4f *)(e + kb * 64 + 4 * d);
-                const v4f pv = *(const v4f *)(p + kb * 64 + 4 * d);
                 uint32_t word = 0;
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
-                    const float z = qr_tanh(ev[i] * pv[i]);
+                    const float z = qr_tanh(raw.e[d][i] * raw.p[d][i]);
                     word |= (uint32_t)(qr_quant(z, z_inv, zbits) & 0xFF) << (8 * i);
                 }
                 b[d] = (int)word;
@@ -49,7 +63,7 @@ __global__ __launch_bounds__(256) void joint_fuse_kernel(const QrJointArgs a)
     };
     const int n_row_tiles = (a.V + 15) >> 4;
     v4i acc[4];
-    qr_head_mma(a.w, a.nkc, n_row_tiles, 0, J, bfrag, acc, lds, a.w8 != 0);
+    qr_head_mma<1>(a.w, a.nkc, n_row_tiles, 0, J, bload, bmake, [] {}, acc, lds, a.w8 != 0);
     if (wave != 0) return;
 
     float v[4][4];
@@ -137,19 +151,8 @@ __global__ __launch_bounds__(256) void joint_route_kernel(const QrJointArgs a, c
         fin_new[lane] = -INFINITY;
         own = qr_alsd_load_own(r, s, b, lane);
     }
-    // per-token constants of this lane's 16 tokens
+    // per-token constants of this lane's 16 tokens (fetched behind the first tile's operands, see qr_head_mma)
     float wscale[4][4], wbias[4][4];
-    if (wave == 0) {
-#pragma unroll
-        for (int mt = 0; mt < 4; ++mt)
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int k = mt * 16 + grp * 4 + i;
-                const int kk = k < V ? k : V - 1;
-                wscale[mt][i] = a.z_scale * a.s_w[kk];
-                wbias[mt][i] = a.b_out ? a.b_out[kk] : 0.0f;
-            }
-    }
 #pragma unroll
     for (int nt = 0; nt < NTW; ++nt) {
         const int w = nt * 16 + col;
@@ -164,17 +167,26 @@ __global__ __launch_bounds__(256) void joint_route_kernel(const QrJointArgs a, c
             t_w = t_w < 0 ? 0 : (t_w > s.T - 1 ? s.T - 1 : t_w);
             e = a.enc + ((int64_t)t_w * r.B + b) * J + grp * 16;
         }
-        auto bfrag = [&](int kb) -> v4i {
+        auto bload = [&](int kb) -> QrJointRaw {
+            QrJointRaw raw = {};
+            if (kb * 64 + grp * 16 < J) {
+#pragma unroll
+                for (int d = 0; d < 4; ++d) {
+                    raw.e[d] = *(const v4f *)(e + kb * 64 + 4 * d);
+                    raw.p[d] = *(const v4f *)(p + kb * 64 + 4 * d);
+                }
+            }
+            return raw;
+        };
+        auto bmake = [&](const QrJointRaw &raw, int kb) -> v4i {
             v4i bq = {0, 0, 0, 0};
             if (kb * 64 + grp * 16 < J) {
 #pragma unroll
                 for (int d = 0; d < 4; ++d) {
-                    const v4f ev = *(const v4f *)(e + kb * 64 + 4 * d);
-                    const v4f pv = *(const v4f *)(p + kb * 64 + 4 * d);
                     uint32_t word = 0;
 #pragma unroll
                     for (int i = 0; i < 4; ++i) {
-                        const float z = qr_tanh(ev[i] * pv[i]);
+                        const float z = qr_tanh(raw.e[d][i] * raw.p[d][i]);
                         word |= (uint32_t)(qr_quant(z, z_inv, zbits) & 0xFF) << (8 * i);
                     }
                     bq[d] = (int)word;
@@ -182,23 +194,30 @@ __global__ __launch_bounds__(256) void joint_route_kernel(const QrJointArgs a, c
             }
             return bq;
         };
-        // LM log-probabilities and the running score: issued before the contraction
+        // LM log-probabilities, the running score and (first tile) the per-token constants: what only the
+        // epilogue of wave 0 needs
         float ls[4][4], le[4][4], sc = 0.0f;
-        if (wave == 0) {
-            sc = r.score_src[(int64_t)b * W + (wv ? w : W - 1)];
+        auto epilogue_loads = [&]() {
+            if (wave == 0) {
+                sc = r.score_src[(int64_t)b * W + (wv ? w : W - 1)];
 #pragma unroll
-            for (int mt = 0; mt < 4; ++mt)
+                for (int mt = 0; mt < 4; ++mt)
 #pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    const int k = mt * 16 + grp * 4 + i;
-                    const int kk = k < V ? k : V - 1;
-                    ls[mt][i] = a.lp_src ? a.lp_src[(int64_t)n * V + kk] : 0.0f;
-                    le[mt][i] = a.lp_ext ? a.lp_ext[(int64_t)n * V + kk] : 0.0f;
-                }
-        }
+                    for (int i = 0; i < 4; ++i) {
+                        const int k = mt * 16 + grp * 4 + i;
+                        const int kk = k < V ? k : V - 1;
+                        ls[mt][i] = a.lp_src ? a.lp_src[(int64_t)n * V + kk] : 0.0f;
+                        le[mt][i] = a.lp_ext ? a.lp_ext[(int64_t)n * V + kk] : 0.0f;
+                        if (nt == 0) {
+                            wscale[mt][i] = a.z_scale * a.s_w[kk];
+                            wbias[mt][i] = a.b_out ? a.b_out[kk] : 0.0f;
+                        }
+                    }
+            }
+        };
         v4i acc[4];
         if (nt > 0) __syncthreads();   // the reduction buffer of the previous tile has been read
-        qr_head_mma(a.w, a.nkc, n_row_tiles, 0, J, bfrag, acc, lds, a.w8 != 0);
+        qr_head_mma<1>(a.w, a.nkc, n_row_tiles, 0, J, bload, bmake, epilogue_loads, acc, lds, a.w8 != 0);
         if (wave == 0) {
             float v[4][4];
             float m = -INFINITY;

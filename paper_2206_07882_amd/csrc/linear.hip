@@ -21,25 +21,28 @@ __global__ __launch_bounds__(256) void linear_head_kernel(const QrLinearGroup g)
     n = nv ? n : a.N - 1;
     const int8_t *arow = a.act + (int64_t)n * a.K + grp * 16;
     const int K = a.K;
-    auto bfrag = [&](int kb) -> v4i {
+    auto bload = [&](int kb) -> v4i {
         const v4i zero = {0, 0, 0, 0};
         return (kb * 64 + grp * 16 < K) ? *(const v4i *)(arow + kb * 64) : zero;
     };
-    // row constants of the lanes that finish the rows (wave 0): fetched ahead of the contraction
+    auto bmake = [](const v4i &raw, int) -> v4i { return raw; };
+    // row constants of the lanes that finish the rows (wave 0): fetched behind the operands of the contraction
     float sw[4][4], bs[4][4];
-    if (wave == 0) {
+    auto row_constants = [&]() {
+        if (wave == 0) {
 #pragma unroll
-        for (int mt = 0; mt < 4; ++mt)
+            for (int mt = 0; mt < 4; ++mt)
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int r = (rt0 + mt) * 16 + grp * 4 + i;
-                const int rr = r < a.rows ? r : a.rows - 1;
-                sw[mt][i] = a.a_scale * a.s_w[rr];
-                bs[mt][i] = a.bias ? a.bias[rr] : 0.0f;
-            }
-    }
+                for (int i = 0; i < 4; ++i) {
+                    const int r = (rt0 + mt) * 16 + grp * 4 + i;
+                    const int rr = r < a.rows ? r : a.rows - 1;
+                    sw[mt][i] = a.a_scale * a.s_w[rr];
+                    bs[mt][i] = a.bias ? a.bias[rr] : 0.0f;
+                }
+        }
+    };
     v4i acc[4];
-    qr_head_mma(a.w, a.nkc, n_row_tiles, rt0, K, bfrag, acc, lds, a.w8 != 0);
+    qr_head_mma<QR_HEAD_BATCH>(a.w, a.nkc, n_row_tiles, rt0, K, bload, bmake, row_constants, acc, lds, a.w8 != 0);
     if (wave != 0) return;
 
     float v[4][4];
