@@ -151,6 +151,11 @@ __global__ __launch_bounds__(256) void joint_route_kernel(const QrJointArgs a, c
         fin_new[lane] = -INFINITY;
         own = qr_alsd_load_own(r, s, b, lane);
     }
+    if (!ALSD && wave == 0 && !r.last_round) {   // what the routing will need of this lane's hypothesis
+        const int o = b * W + (lane < W ? lane : 0);
+        own.node = r.node_src[o];
+        own.len = r.len_src[o];
+    }
     // per-token constants of this lane's 16 tokens (fetched behind the first tile's operands, see qr_head_mma)
     float wscale[4][4], wbias[4][4];
 #pragma unroll
@@ -288,7 +293,7 @@ __global__ __launch_bounds__(256) void joint_route_kernel(const QrJointArgs a, c
         qr_alsd_route(r, s, b, lane, my_c, my_v, fin_new[lane], own);
         return;
     }
-    const int cnt = qr_route_picks(r, b, lane, my_c, my_v);
+    const int cnt = qr_route_picks(r, b, lane, my_c, my_v, own.node, own.len);
     if (r.last_round) {   // the frame is complete for this utterance: prune its candidate list to the new beam
         __threadfence();
         qr_frame_end(r, b, lane, cnt);

@@ -9,7 +9,10 @@
 #include "select.h"
 
 // Returns the length of the utterance's candidate list after this round (uniform).
-__device__ __forceinline__ int qr_route_picks(const QrRouteArgs &a, int b, int lane, int c, float v)
+// own_node / own_len: trie node and length of hypothesis `lane` of the current round (fetched at the start of the
+// kernel, so that the routing does not wait for memory); a pick reads its parent's from that lane.
+__device__ __forceinline__ int qr_route_picks(const QrRouteArgs &a, int b, int lane, int c, float v, int own_node,
+                                              int own_len)
 {
     if (lane == 0 && b == 0 && a.live_clear) *a.live_clear = 0;
     const int W = a.W, V = a.V, N = a.B * a.W;
@@ -21,6 +24,7 @@ __device__ __forceinline__ int qr_route_picks(const QrRouteArgs &a, int b, int l
     const unsigned long long bm = __ballot(is_blank), lm = __ballot(is_lab);
     const unsigned long long lt = (1ull << lane) - 1ull;
     const int src_slot = b * W + par;
+    const int par_node = __shfl(own_node, par), par_len = __shfl(own_len, par);
     const int nx0 = a.nx_count[b];
     if (is_blank) {
         const int e = nx0 + __popcll(bm & lt);
@@ -36,10 +40,10 @@ __device__ __forceinline__ int qr_route_picks(const QrRouteArgs &a, int b, int l
         const int dst = b * W + __popcll(lm & lt);
         const int id = a.node_base + dst;
         a.node_tok[id] = tok;
-        a.node_prev[id] = a.node_src[src_slot];
+        a.node_prev[id] = par_node;
         a.score_dst[dst] = v;
         a.node_dst[dst] = id;
-        a.len_dst[dst] = a.len_src[src_slot] + 1;
+        a.len_dst[dst] = par_len + 1;
         a.parent_idx[dst] = src_slot;
         a.token[dst] = tok;
         a.active[dst] = 1;
