@@ -226,3 +226,30 @@ def test_alsd_full_width_networks(gpu_lib):
             ref = oracle.decode_alsd(M, e, W, u_max)
             got = gpu_lib.decode_alsd(G, dev(e), W, u_max)
             _compare_beams(got, ref)
+
+
+@pytest.mark.parametrize("std", [0.1, 0.6])
+def test_alsd_config0_end_to_end_matches_golden(gpu_lib, std):
+    """Encoder + alignment-length synchronous search on the tiny configuration against the oracle and against the
+    stored finished lists (tests/golden/cfg0_alsd.txt, written by the oracle alone)."""
+    from paper_2206_07882_amd import model as gmodel
+    from tests.golden import make_golden as mg
+    m = synth.make_model(0, weight_std=std)
+    feats = synth.features(0, mg.T, mg.B, m.feat_dim)
+    layers, proj = omodels.encoder_from_float(m)
+    _, e_r = omodels.encoder_forward(layers, proj, feats, m.alpha_x)
+    ref = oracle.decode_alsd(omodels.model_from_float(m), e_r, mg.ALSD_W, mg.ALSD_UMAX)
+    _, e_g = gmodel.Encoder(m, DEV).forward(dev(feats))
+    got = gpu_lib.decode_alsd(gmodel.model_from_float(m, DEV), e_g, mg.ALSD_W, mg.ALSD_UMAX)
+    _compare_beams(got, ref)
+    tok_g, len_g, _ = (host(x) for x in got)
+    path = os.path.join(os.path.dirname(__file__), "golden", "cfg0_alsd.txt")
+    n = 0
+    for l in open(path).read().splitlines():
+        if not l.startswith(f"{std} "):
+            continue
+        head, labs = l.split("|")
+        _, b, w, _ = head.split()
+        assert tok_g[int(b), int(w), :len_g[int(b), int(w)]].tolist() == [int(t) for t in labs.split()]
+        n += 1
+    assert n >= 6

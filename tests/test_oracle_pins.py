@@ -669,3 +669,10 @@ def test_golden_config0_decode_is_reproducible():
         pytest.skip("golden file not generated")
     from tests.golden import make_golden
     assert open(path).read() == make_golden.render()
+
+
+def test_golden_config0_alsd_is_reproducible():
+    """The stored finished lists of the alignment-length synchronous search (same script, oracle only)."""
+    path = os.path.join(GOLD, "cfg0_alsd.txt")
+    from tests.golden import make_golden
+    assert open(path).read() == make_golden.render_alsd()
