@@ -329,6 +329,19 @@ def main():
                                           "frac_int8_mfma": gops / tg / 1e12 / INT8_MFMA_PEAK_TOPS,
                                           "algorithmic_bytes": gbytes, "GBps": gbytes / tg / 1e9}
 
+        # ---- the encoder stack alone at the sizes of configuration 1: 32 utterances x 500 frames, and one utterance
+        rows = []
+        for (Be, Te) in ((32, 500), (1, 500)):
+            fe = torch.from_numpy(synth.features(4, Te, Be, m.feat_dim)).to(dev)
+            enc.workspace(Te, Be, dev)
+            te = timed(lambda: enc.forward(fe), 3, warm=1)
+            rows.append({"B": Be, "T": Te, "ms": te * 1e3, "rtf": te / (Be * Te * FRAME_SEC),
+                         "us_per_layer_step": te * 1e6 / (len(enc.layers) * Te)})
+            del fe
+        extra["encoder_stack"] = {"rows": rows,
+                                  "note": "6 bidirectional layers + projection; us_per_layer_step = time / (6 layers x T steps): both "
+                                          "directions of a layer advance in the same persistent launch, input projections included"}
+
     # ---------------------------------------------------------------- CPU oracle on a bounded slice
     if not args.no_cpu and args.leg in ("all",):
         import oracle
@@ -348,6 +361,17 @@ def main():
                                   "kind": "oracle",
                                   "sample": f"same network, B={Bc} utterances x T={Tc} frames, beam {W}, max {MAX_SYM} labels/frame "
                                             f"({t_cpu:.1f} s of CPU work; weight quantization {t_build:.1f} s excluded)"}
+
+        # one thread on one utterance, for the per-core rate
+        oracle.set_threads(1)
+        f1 = synth.features(4, 10, 1, mo.feat_dim)
+        t0 = time.perf_counter()
+        _, e_1 = omodels.encoder_forward(layers, proj, f1, mo.alpha_x)
+        oracle.decode(M_o, e_1, W, MAX_SYM)
+        t_1 = time.perf_counter() - t0
+        oracle.set_threads(Bc)
+        extra["cpu_oracle_single_thread"] = {"value": t_1 / (10 * FRAME_SEC), "unit": "s/s", "cores": 1,
+                                             "sample": f"B=1 x T=10 frames ({t_1:.1f} s)"}
 
     result["extra"] = extra
     if "value" not in result:
