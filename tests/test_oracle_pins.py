@@ -676,3 +676,33 @@ def test_golden_config0_alsd_is_reproducible():
     path = os.path.join(GOLD, "cfg0_alsd.txt")
     from tests.golden import make_golden
     assert open(path).read() == make_golden.render_alsd()
+
+
+def test_quantizer_properties_over_random_boundaries():
+    """Properties that Sec. 3.1's symmetric quantizer has at any boundary and width: codes stay in range, the map
+    is odd except at the clipped end, monotone, idempotent on its own grid, and the residual inside the range is
+    at most half a step."""
+    from hypothesis import given, settings, strategies as st
+
+    @settings(max_examples=60, deadline=None)
+    @given(st.floats(0.05, 50.0), st.sampled_from([4, 8]), st.integers(0, 2 ** 31 - 1))
+    def check(alpha, bits, seed):
+        qmax = 127 if bits == 8 else 7
+        inv = np.float32(qmax) / np.float32(alpha)
+        step = float(np.float32(alpha) / np.float32(qmax))
+        rng = np.random.default_rng(seed)
+        x = (rng.standard_normal(400) * alpha).astype(np.float32)
+        q = oracle.quant_sym(x, inv, bits).astype(np.int32)
+        assert q.min() >= -qmax - 1 and q.max() <= qmax
+        qn = oracle.quant_sym(-x, inv, bits).astype(np.int32)
+        odd = (np.abs(q) <= qmax) & (np.abs(qn) <= qmax)
+        assert np.array_equal(q[odd], -qn[odd])                         # rounding to even is an odd function
+        order = np.argsort(x, kind="stable")
+        assert np.all(np.diff(q[order]) >= 0)
+        grid = (np.arange(-qmax, qmax + 1, dtype=np.float32) * np.float32(step)).astype(np.float32)
+        back = oracle.quant_sym(grid, inv, bits).astype(np.int32)
+        assert np.abs(back - np.arange(-qmax, qmax + 1)).max() <= (0 if bits == 4 else 1)   # fp32 alpha/qmax * qmax/alpha
+        inside = np.abs(x) <= alpha
+        assert np.all(np.abs(x[inside].astype(np.float64) - q[inside] * step) <= step / 2 * (1 + 1e-3) + 1e-7)
+
+    check()
