@@ -9,7 +9,6 @@
 
 namespace {
 
-constexpr int MAX_TENSORS = 32;
 
 struct NetBuf {
     int8_t *h[QRNNT_MAX_LAYERS];   // [NB][N][H]
@@ -104,26 +103,6 @@ __global__ void decode_init_kernel(float *score0, int32_t *node0, int32_t *len0,
     parent_idx[n] = n;
     token[n] = start_symbol;
     active[n] = 1;
-}
-
-struct GatherTable {
-    char *base[MAX_TENSORS];
-    int row_bytes[MAX_TENSORS];
-    int n;
-};
-
-// New beam slot n takes the state rows of its source (buffer, slot); an empty
-// rank keeps whatever the destination holds (its score is -inf).
-__global__ __launch_bounds__(64) void gather_state_kernel(const GatherTable tb, const int32_t *__restrict__ beam_src, int N,
-                                                           int dst_buf)
-{
-    const int n = blockIdx.x, t = blockIdx.y;
-    const int src = beam_src[n];
-    if (src < 0) return;
-    const int rb = tb.row_bytes[t];
-    const uint32_t *s = (const uint32_t *)(tb.base[t] + (size_t)src * rb);
-    uint32_t *d = (uint32_t *)(tb.base[t] + ((size_t)dst_buf * N + n) * rb);
-    for (int i = threadIdx.x; i < rb / 4; i += 64) d[i] = s[i];
 }
 
 __global__ void backtrack_kernel(const float *__restrict__ score, const int32_t *__restrict__ node,
@@ -333,7 +312,9 @@ extern "C" qrnnt_status qrnnt_decode_ex(const qrnnt_model *m, const float *enc_p
                                                             p.nx_count, p.node_tok, p.node_prev, N, W, B, m->blank);
     advance_nets(m, p, ZB, 0, n_embed_rows, nullptr, st);
 
-    GatherTable tb = {};
+    // The state rows a new beam slot takes over from its source (copied by the first joint + selection kernel of
+    // the next frame, see joint_route_kernel)
+    QrGatherTable tb = {};
     for (int k = 0; k < 3; ++k) {
         if (!net_used(m, k)) continue;
         const qrnnt_net *net = net_of(m, k);
@@ -343,6 +324,8 @@ extern "C" qrnnt_status qrnnt_decode_ex(const qrnnt_model *m, const float *enc_p
         }
         tb.base[tb.n] = (char *)p.net[k].y;  tb.row_bytes[tb.n++] = net->out.rows * 4;
     }
+    tb.beam_src = p.beam_src;  tb.N = N;
+    const QrGatherTable no_copy = {};
 
     QrJointArgs ja = {};
     ja.enc = enc_proj;  ja.n_enc_rows = T * B;  ja.frame_row = nullptr;  ja.rows_per_utt = W;
@@ -359,9 +342,16 @@ extern "C" qrnnt_status qrnnt_decode_ex(const qrnnt_model *m, const float *enc_p
             const int cur = (v == 0) ? a0 : v;
             const int nxt = v + 1;   // only used when v < max_sym
             ja.frame_base = t * B;
-            ja.pred = p.net[0].y + (size_t)cur * Ns * p.J;
-            ja.lp_src = m->use_src ? p.net[1].y + (size_t)cur * Ns * V : nullptr;
-            ja.lp_ext = m->use_ext ? p.net[2].y + (size_t)cur * Ns * V : nullptr;
+            // first round of a frame after the first: the beam's cached outputs are still where their sources left
+            // them (read through beam_src); this kernel's spare workgroups move all state rows into buffer `cur`
+            const bool moving = (v == 0 && t > 0);
+            const size_t yb = moving ? 0 : (size_t)cur;
+            ja.pred = p.net[0].y + yb * Ns * p.J;
+            ja.lp_src = m->use_src ? p.net[1].y + yb * Ns * V : nullptr;
+            ja.lp_ext = m->use_ext ? p.net[2].y + yb * Ns * V : nullptr;
+            ja.row_idx = moving ? p.beam_src : nullptr;
+            ja.row_idx_buf = cur;
+            tb.dst_buf = cur;
             const int last = (v == max_sym);
             QrRouteArgs ra = {};
             ra.score_src = p.score + (size_t)cur * Ns;
@@ -382,12 +372,10 @@ extern "C" qrnnt_status qrnnt_decode_ex(const qrnnt_model *m, const float *enc_p
                 ra.live_next = lv + v + 1;
                 ra.live_clear = lo + v + 1;
             }
-            qr_launch_joint_route(ja, ra, st);
+            qr_launch_joint_route(ja, ra, moving ? tb : no_copy, st);
             if (!last) advance_nets(m, p, cur, nxt, n_embed_rows, early ? ra.live_next : nullptr, st);
         }
-        const int dst = (a0 == 0) ? ZB : 0;
-        gather_state_kernel<<<dim3(N, tb.n), 64, 0, st>>>(tb, p.beam_src, N, dst);
-        a0 = dst;
+        a0 = (a0 == 0) ? ZB : 0;   // the new beam's buffer; its state rows follow in the next frame's first kernel
     }
     backtrack_kernel<<<(N + 63) / 64, 64, 0, st>>>(p.score + (size_t)a0 * Ns, p.node + (size_t)a0 * Ns,
                                                    p.len + (size_t)a0 * Ns, p.node_tok, p.node_prev, N, max_len,

@@ -120,12 +120,42 @@ __global__ __launch_bounds__(256) void joint_fuse_kernel(const QrJointArgs a)
 // ALSD: the same joint + selection inside the alignment-length synchronous search (route.h, qr_alsd_route):
 // every hypothesis reads its own encoder frame (iteration - labels so far), a blank at the last frame
 // finishes a hypothesis instead of being a candidate, labels beyond the cap are no candidates.
+// Workgroups beyond the B utterances (time-synchronous search, first round of a frame) copy the state rows of the
+// new beam from their sources into the beam's buffer, one (slot, tensor) pair per wave: that copy only has to be
+// done before the next network advance, so it runs here, on the CUs this kernel leaves idle, instead of in a launch
+// of its own.  The joint of this round reads its inputs through the same source indices (QrJointArgs.row_idx).
 template <int NTW, bool ALSD>
-__global__ __launch_bounds__(256) void joint_route_kernel(const QrJointArgs a, const QrRouteArgs r, const QrAlsdArgs s)
+__global__ __launch_bounds__(256) void joint_route_kernel(const QrJointArgs a, const QrRouteArgs r, const QrAlsdArgs s,
+                                                          const QrGatherTable gt)
 {
     __shared__ v4i lds[4 * 4 * 64];
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    if (!ALSD && (int)blockIdx.x >= r.B) {   // uniform per workgroup
+        const int pair = ((int)blockIdx.x - r.B) * 4 + wave;
+        if (pair >= gt.N * gt.n) return;
+        const int n = pair % gt.N, t = pair / gt.N;
+        const int src = gt.beam_src[n];
+        if (src < 0) return;   // an empty rank keeps whatever the destination holds (its score is -inf)
+        const int rb = gt.row_bytes[t];
+        const char *sp = gt.base[t] + (size_t)src * rb;
+        char *dp = gt.base[t] + ((size_t)gt.dst_buf * gt.N + n) * rb;
+        if ((rb & 15) == 0 && (((uintptr_t)sp | (uintptr_t)dp) & 15) == 0) {   // 4 KiB of the row in flight per wave
+            const int n16 = rb >> 4;
+            for (int i0 = 0; i0 < n16; i0 += 256) {
+                v4i tmp[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u)
+                    if (i0 + u * 64 + lane < n16) tmp[u] = ((const v4i *)sp)[i0 + u * 64 + lane];
+#pragma unroll
+                for (int u = 0; u < 4; ++u)
+                    if (i0 + u * 64 + lane < n16) ((v4i *)dp)[i0 + u * 64 + lane] = tmp[u];
+            }
+        } else {
+            for (int i = lane; i < rb / 4; i += 64) ((uint32_t *)dp)[i] = ((const uint32_t *)sp)[i];
+        }
+        return;
+    }
     const int col = lane & 15, grp = lane >> 4;
     const int b = blockIdx.x;
     const int W = r.W, V = a.V, J = a.J;
@@ -163,7 +193,12 @@ __global__ __launch_bounds__(256) void joint_route_kernel(const QrJointArgs a, c
         const int w = nt * 16 + col;
         const bool wv = w < W;
         const int n = b * W + (wv ? w : W - 1);
-        const float *p = a.pred + (int64_t)n * J + grp * 16;
+        int64_t nrow = n;   // row of the cached network outputs that hypothesis n reads
+        if (!ALSD && a.row_idx) {
+            const int src = a.row_idx[n];
+            nrow = src >= 0 ? (int64_t)src : (int64_t)a.row_idx_buf * a.N + n;
+        }
+        const float *p = a.pred + nrow * J + grp * 16;
         const float *e = e_utt;
         int len_w = 0, t_w = 0;
         if (ALSD) {   // this hypothesis' own frame
@@ -211,8 +246,8 @@ __global__ __launch_bounds__(256) void joint_route_kernel(const QrJointArgs a, c
                     for (int i = 0; i < 4; ++i) {
                         const int k = mt * 16 + grp * 4 + i;
                         const int kk = k < V ? k : V - 1;
-                        ls[mt][i] = a.lp_src ? a.lp_src[(int64_t)n * V + kk] : 0.0f;
-                        le[mt][i] = a.lp_ext ? a.lp_ext[(int64_t)n * V + kk] : 0.0f;
+                        ls[mt][i] = a.lp_src ? a.lp_src[nrow * V + kk] : 0.0f;
+                        le[mt][i] = a.lp_ext ? a.lp_ext[nrow * V + kk] : 0.0f;
                         if (nt == 0) {
                             wscale[mt][i] = a.z_scale * a.s_w[kk];
                             wbias[mt][i] = a.b_out ? a.b_out[kk] : 0.0f;
@@ -302,19 +337,21 @@ __global__ __launch_bounds__(256) void joint_route_kernel(const QrJointArgs a, c
 
 }  // namespace
 
-void qr_launch_joint_route(const QrJointArgs &a, const QrRouteArgs &r, hipStream_t st)
+void qr_launch_joint_route(const QrJointArgs &a, const QrRouteArgs &r, const QrGatherTable &gt, hipStream_t st)
 {
     const QrAlsdArgs none = {};
-    if (r.W <= 16) joint_route_kernel<1, false><<<r.B, 256, 0, st>>>(a, r, none);
-    else if (r.W <= 32) joint_route_kernel<2, false><<<r.B, 256, 0, st>>>(a, r, none);
-    else joint_route_kernel<4, false><<<r.B, 256, 0, st>>>(a, r, none);
+    const unsigned grid = (unsigned)(r.B + (gt.n > 0 ? (gt.N * gt.n + 3) / 4 : 0));
+    if (r.W <= 16) joint_route_kernel<1, false><<<grid, 256, 0, st>>>(a, r, none, gt);
+    else if (r.W <= 32) joint_route_kernel<2, false><<<grid, 256, 0, st>>>(a, r, none, gt);
+    else joint_route_kernel<4, false><<<grid, 256, 0, st>>>(a, r, none, gt);
 }
 
 void qr_launch_joint_alsd(const QrJointArgs &a, const QrRouteArgs &r, const QrAlsdArgs &s, hipStream_t st)
 {
-    if (r.W <= 16) joint_route_kernel<1, true><<<r.B, 256, 0, st>>>(a, r, s);
-    else if (r.W <= 32) joint_route_kernel<2, true><<<r.B, 256, 0, st>>>(a, r, s);
-    else joint_route_kernel<4, true><<<r.B, 256, 0, st>>>(a, r, s);
+    const QrGatherTable none = {};
+    if (r.W <= 16) joint_route_kernel<1, true><<<r.B, 256, 0, st>>>(a, r, s, none);
+    else if (r.W <= 32) joint_route_kernel<2, true><<<r.B, 256, 0, st>>>(a, r, s, none);
+    else joint_route_kernel<4, true><<<r.B, 256, 0, st>>>(a, r, s, none);
 }
 
 void qr_launch_joint(const QrJointArgs &a, hipStream_t st)

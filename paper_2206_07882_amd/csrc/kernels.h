@@ -51,6 +51,16 @@ struct QrLinearGroup {
     const int32_t *gate;               // optional [device]: the launch does nothing when *gate == 0
 };
 
+// State tensors of the decoder ([buffers][N][row]): what a new beam slot copies from its source (buffer, slot).
+#define QR_MAX_GATHER 32
+struct QrGatherTable {
+    char *base[QR_MAX_GATHER];
+    int row_bytes[QR_MAX_GATHER];
+    int n;                             // 0: nothing to copy
+    const int32_t *beam_src;           // [N] flat source row (buffer * N + slot) of every new beam slot, -1: empty rank
+    int N, dst_buf;
+};
+
 struct QrJointArgs {
     const float *enc;  int n_enc_rows;
     const int32_t *frame_row;          // per-row encoder row, or null: row = frame_base + n / rows_per_utt
@@ -63,6 +73,9 @@ struct QrJointArgs {
     int N, J, V, blank, nkc;
     float *lp_out;  int8_t *dbg_zq;  float *fused;
     int w8;                            // 8-bit output layer: 8-bit weights and an 8-bit quantizer on z
+    const int32_t *row_idx;            // optional (decoding loop): hypothesis n reads row row_idx[n] of pred / lp_src / lp_ext
+                                       // (which then point at buffer 0 of those arrays); < 0: row n of buffer row_idx_buf
+    int row_idx_buf;
 };
 
 struct QrRouteArgs {
@@ -123,7 +136,7 @@ QR_HIDDEN void qr_launch_input_projection(const qrnnt_lstm *L, const int8_t *x_c
 QR_HIDDEN void qr_launch_linear_group(const QrLinearGroup &g, hipStream_t st);
 QR_HIDDEN void qr_launch_linear(const QrLinearArgs &a, hipStream_t st);
 QR_HIDDEN void qr_launch_joint(const QrJointArgs &a, hipStream_t st);
-QR_HIDDEN void qr_launch_joint_route(const QrJointArgs &a, const QrRouteArgs &r, hipStream_t st);
+QR_HIDDEN void qr_launch_joint_route(const QrJointArgs &a, const QrRouteArgs &r, const QrGatherTable &gt, hipStream_t st);
 QR_HIDDEN void qr_launch_joint_alsd(const QrJointArgs &a, const QrRouteArgs &r, const QrAlsdArgs &s, hipStream_t st);
 QR_HIDDEN void qr_launch_beam(const float *score, const float *fused, int B, int W, int V, int blank, int force_blank,
                               int32_t *parent_out, int32_t *token_out, float *score_out, hipStream_t st);
