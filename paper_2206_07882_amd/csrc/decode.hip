@@ -29,6 +29,7 @@ struct Plan {
     int32_t *beam_src;   // [N]
     int32_t *node_tok, *node_prev;   // [1 + T*max_sym*N]
     int32_t *live;       // [2][max_sym+2]: utterances that carried a label into round v of the frame (early stop)
+    v4i *rows;  int32_t *n_rows;   // [N], [2][max_sym+2]: the slots that carry a label into round v of the frame, and how many
     size_t total;
 };
 
@@ -78,6 +79,8 @@ void make_plan(const qrnnt_model *m, int T, int B, int W, int max_sym, void *ws,
     p.node_tok = cv.take<int32_t>(pool);
     p.node_prev = cv.take<int32_t>(pool);
     p.live = cv.take<int32_t>(2 * (size_t)(max_sym + 2));
+    p.rows = cv.take<v4i>(N);
+    p.n_rows = cv.take<int32_t>(2 * (size_t)(max_sym + 2));
     p.total = (cv.off + 255) / 256 * 256;
 }
 
@@ -174,8 +177,10 @@ qrnnt_status check_model(const qrnnt_model *m)
 
 // All used networks consume `token` and move from buffer src to buffer dst.  Layer l
 // of every network goes out as one grouped launch (the networks are independent).
+// n_rows (optional): only the hypotheses p.rows[0 .. *n_rows) advance (the recurrent layers; the output layers
+// are computed for every row, the rows that did not advance are not read afterwards).
 void advance_nets(const qrnnt_model *m, const Plan &p, int src, int dst, int n_embed_rows, const int32_t *gate,
-                  hipStream_t st)
+                  const int32_t *n_rows, hipStream_t st)
 {
     const size_t N = (size_t)p.N;
     int max_layers = 0;
@@ -185,6 +190,8 @@ void advance_nets(const qrnnt_model *m, const Plan &p, int src, int dst, int n_e
         QrStepGroup g;
         g.n = 0;
         g.gate = gate;
+        g.rows = n_rows ? p.rows : nullptr;
+        g.n_rows = n_rows;
         for (int k = 0; k < 3; ++k) {
             if (!net_used(m, k)) continue;
             const qrnnt_net *net = net_of(m, k);
@@ -308,9 +315,10 @@ extern "C" qrnnt_status qrnnt_decode_ex(const qrnnt_model *m, const float *enc_p
         qr_launch_gx_table(&net_of(m, k)->layer[0], p.net[k].gx0, V, p.net[k].tab0, st);
     }
     fill_words_kernel<<<1, 256, 0, st>>>((uint32_t *)p.live, 2 * (size_t)(max_sym + 2), 0u);
+    fill_words_kernel<<<1, 256, 0, st>>>((uint32_t *)p.n_rows, 2 * (size_t)(max_sym + 2), 0u);
     decode_init_kernel<<<(N + 255) / 256 + 1, 256, 0, st>>>(p.score, p.node, p.len, p.parent_idx, p.token, p.active,
                                                             p.nx_count, p.node_tok, p.node_prev, N, W, B, m->blank);
-    advance_nets(m, p, ZB, 0, n_embed_rows, nullptr, st);
+    advance_nets(m, p, ZB, 0, n_embed_rows, nullptr, nullptr, st);
 
     // The state rows a new beam slot takes over from its source (copied by the first joint + selection kernel of
     // the next frame, see joint_route_kernel)
@@ -327,6 +335,7 @@ extern "C" qrnnt_status qrnnt_decode_ex(const qrnnt_model *m, const float *enc_p
     tb.beam_src = p.beam_src;  tb.N = N;
     const QrGatherTable no_copy = {};
 
+    const bool use_list = qr_step_list_pays(N);
     QrJointArgs ja = {};
     ja.enc = enc_proj;  ja.n_enc_rows = T * B;  ja.frame_row = nullptr;  ja.rows_per_utt = W;
     ja.w = (const v4i *)m->joint_out.packed;  ja.s_w = m->joint_out.row_scale;  ja.b_out = m->joint_bias;
@@ -372,8 +381,14 @@ extern "C" qrnnt_status qrnnt_decode_ex(const qrnnt_model *m, const float *enc_p
                 ra.live_next = lv + v + 1;
                 ra.live_clear = lo + v + 1;
             }
+            // n_rows[t&1][v] = slots that carry a label into round v of this frame, listed in p.rows
+            if (use_list) {
+                ra.rows_next = p.rows;
+                ra.n_rows_next = p.n_rows + (size_t)(t & 1) * (max_sym + 2) + v + 1;
+                ra.n_rows_clear = p.n_rows + (size_t)((t + 1) & 1) * (max_sym + 2) + v + 1;
+            }
             qr_launch_joint_route(ja, ra, moving ? tb : no_copy, st);
-            if (!last) advance_nets(m, p, cur, nxt, n_embed_rows, early ? ra.live_next : nullptr, st);
+            if (!last) advance_nets(m, p, cur, nxt, n_embed_rows, early ? ra.live_next : nullptr, ra.n_rows_next, st);
         }
         a0 = (a0 == 0) ? ZB : 0;   // the new beam's buffer; its state rows follow in the next frame's first kernel
     }
@@ -431,6 +446,7 @@ void make_alsd_plan(const qrnnt_model *m, int T, int B, int W, int u_max, void *
     p.node_tok = cv.take<int32_t>(pool);
     p.node_prev = cv.take<int32_t>(pool);
     p.live = cv.take<int32_t>((size_t)ap.n_iter + 2);
+    p.rows = nullptr;  p.n_rows = nullptr;
     p.total = (cv.off + 255) / 256 * 256;
 }
 
@@ -493,7 +509,7 @@ extern "C" qrnnt_status qrnnt_decode_alsd(const qrnnt_model *m, const float *enc
     }
     decode_init_kernel<<<(N + 255) / 256 + 1, 256, 0, st>>>(p.score, p.node, p.len, p.parent_idx, p.token, p.active,
                                                             p.nx_count, p.node_tok, p.node_prev, N, W, B, m->blank);
-    advance_nets(m, p, 1, 0, V, nullptr, st);
+    advance_nets(m, p, 1, 0, V, nullptr, nullptr, st);
 
     QrJointArgs ja = {};
     ja.enc = enc_proj;  ja.n_enc_rows = T * B;  ja.frame_row = nullptr;  ja.rows_per_utt = W;  ja.frame_base = 0;
@@ -526,7 +542,7 @@ extern "C" qrnnt_status qrnnt_decode_alsd(const qrnnt_model *m, const float *enc
         sa.hash_src = ap.hash + (size_t)cur * Ns;  sa.hash_dst = ap.hash + (size_t)nxt * Ns;
         sa.fin_score = ap.fin_score;  sa.fin_node = ap.fin_node;  sa.fin_len = ap.fin_len;
         qr_launch_joint_alsd(ja, ra, sa, st);
-        if (i + 1 < ap.n_iter) advance_nets(m, p, cur, nxt, V, ra.live_next, st);
+        if (i + 1 < ap.n_iter) advance_nets(m, p, cur, nxt, V, ra.live_next, nullptr, st);
         cur = nxt;
     }
     backtrack_kernel<<<(N + 63) / 64, 64, 0, st>>>(ap.fin_score, ap.fin_node, ap.fin_len, p.node_tok, p.node_prev, N,

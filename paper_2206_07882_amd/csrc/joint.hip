@@ -163,6 +163,7 @@ __global__ __launch_bounds__(256) void joint_route_kernel(const QrJointArgs a, c
         if (ALSD) return;           // no live hypothesis anywhere: the finals stay as they are
         if (wave == 0) {
             if (lane == 0 && b == 0 && r.live_clear) *r.live_clear = 0;
+            if (lane == 0 && b == 0 && r.n_rows_clear) *r.n_rows_clear = 0;
             if (r.last_round) qr_frame_end(r, b, lane, r.nx_count[b]);
         }
         return;

@@ -32,6 +32,12 @@ struct QrStepGroup {
     QrStepArgs p[QR_MAX_GROUP];
     int n;
     const int32_t *gate;               // optional [device]: the launch does nothing when *gate == 0
+    // optional [device] (same N, parent and x_row arrays for all members): the launch advances the hypotheses
+    // listed in rows[0 .. *n_rows) and leaves every other row of the outputs untouched.  An entry is
+    // (hypothesis n, parent[n], x_row[n], unused): what the kernel would otherwise fetch through n, so that
+    // the list adds no link to its chain of dependent loads.  Entries beyond the end may hold anything.
+    const v4i *rows = nullptr;
+    const int32_t *n_rows = nullptr;
 };
 
 struct QrLinearArgs {
@@ -94,6 +100,9 @@ struct QrRouteArgs {
     // early stop (all optional): the round is dead when *gate == 0; an utterance that picked a label
     // adds 1 to *live_next; workgroup 0 clears *live_clear for a later frame
     const int32_t *gate;  int32_t *live_next, *live_clear;
+    // list of the slots that carry a label into the next round (optional, see QrStepGroup.rows): every utterance
+    // appends its slots at rows_next[old *n_rows_next ...]; workgroup 0 clears *n_rows_clear for a later frame
+    v4i *rows_next;  int32_t *n_rows_next, *n_rows_clear;
 };
 
 // One direction of the persistent recurrence (see recurrence.hip).
@@ -130,6 +139,9 @@ QR_HIDDEN void qr_fill_lstm_weights(QrStepArgs &a, const qrnnt_lstm *L);
 QR_HIDDEN qrnnt_status qr_check_lstm(const qrnnt_lstm *L);
 QR_HIDDEN void qr_launch_lstm_step(const QrStepArgs &a, bool use_gx, hipStream_t st);
 QR_HIDDEN void qr_launch_lstm_step_group(const QrStepGroup &g, bool use_gx, hipStream_t st);
+// Whether a list of the advancing hypotheses (QrStepGroup.rows) can be expected to pay for the returning atomic
+// that builds it: the weight-streaming kernel drops 16-column blocks, the tiled one 128-column blocks.
+QR_HIDDEN bool qr_step_list_pays(int N);
 QR_HIDDEN void qr_launch_gx_table(const qrnnt_lstm *L, const int32_t *gx, int M, float *tab, hipStream_t st);
 QR_HIDDEN void qr_launch_input_projection(const qrnnt_lstm *L, const int8_t *x_codes, int M, int32_t *gx, int32_t *dbg_accx,
                                           hipStream_t st);

@@ -56,10 +56,22 @@ __global__ __launch_bounds__(256) void lstm_step_small_kernel(const QrStepGroup 
     load_weights(wave);
 
     // ---- indices, then everything that hangs on them
-    const int n = n0 + col;
-    const int nn = n < N ? n : N - 1;
-    int s = a.parent ? a.parent[nn] : nn;
-    int xr = a.x_row ? a.x_row[nn] : nn;
+    bool n_ok = n0 + col < N;
+    int nn = n_ok ? n0 + col : N - 1;
+    int s, xr;
+    if (g.rows) {   // row j of the problem stands for the hypothesis of entry j (see QrStepGroup.rows)
+        const v4i e = g.rows[nn];
+        const int n_cnt = *g.n_rows;
+        if (n0 >= n_cnt) return;   // uniform
+        n_ok = n0 + col < n_cnt;
+        nn = e[0] < 0 ? 0 : (e[0] >= N ? N - 1 : e[0]);
+        s = a.parent ? e[1] : nn;
+        xr = a.x_row ? e[2] : nn;
+    } else {
+        s = a.parent ? a.parent[nn] : nn;
+        xr = a.x_row ? a.x_row[nn] : nn;
+    }
+    const int n = nn;
     s = s < 0 ? 0 : (s >= a.n_slots ? a.n_slots - 1 : s);
     xr = xr < 0 ? 0 : (xr >= a.n_x_rows ? a.n_x_rows - 1 : xr);
     const int8_t *hrow = a.h_prev + (int64_t)s * a.ld_hp + grp * 16;
@@ -137,7 +149,7 @@ __global__ __launch_bounds__(256) void lstm_step_small_kernel(const QrStepGroup 
     const bool on = act != 0;
     cn = on ? cn : cp;
     code = on ? code : hp_code;
-    if (n < N) {
+    if (n_ok) {
         a.c_next[(int64_t)n * H + j] = cn;
         a.h_next[(int64_t)n * a.ld_hn + j] = (int8_t)code;
         if (a.h_copy) a.h_copy[(int64_t)n * H + j] = (int8_t)code;
@@ -199,34 +211,69 @@ __global__ __launch_bounds__(256, (USE_GX && !DBG) ? 3 : 2) void lstm_step_pipe_
 
     // ---- indices: rows this thread stages (ld_*) and hypotheses this lane finishes (n_of)
     int ld_n[NT], ld_s[NT], ld_x[NT], n_of[NT], src_of[NT], gx_of[NT];
-#pragma unroll
-    for (int i = 0; i < NT; ++i) {
-        const int n = n0 + qr_pipe_b_row<NT>(wave, i, lane);
-        ld_n[i] = n < N ? n : N - 1;
-        const int m = n0 + (wn * NT + i) * 16 + col;
-        n_of[i] = m;
-        src_of[i] = m < N ? m : N - 1;
-    }
-    if (a.parent) {
-#pragma unroll
-        for (int i = 0; i < NT; ++i) { ld_s[i] = a.parent[ld_n[i]]; src_of[i] = a.parent[src_of[i]]; }
-    } else {
-#pragma unroll
-        for (int i = 0; i < NT; ++i) ld_s[i] = ld_n[i];
-    }
-    if (!USE_GX && a.x_row) {
-#pragma unroll
-        for (int i = 0; i < NT; ++i) ld_x[i] = a.x_row[ld_n[i]];
-    } else {
-#pragma unroll
-        for (int i = 0; i < NT; ++i) ld_x[i] = ld_n[i];
-    }
-    if (USE_GX) {   // row of the precomputed input projection for the hypotheses this lane finishes
+    bool n_ok[NT];   // the column stands for a hypothesis (not for padding of the last block)
+    // With a list the problem has *n_rows rows, row j standing for the hypothesis of entry j.
+    const v4i *rows = g.rows;
+    if (rows) {
+        // The entries are requested before the length of the list is looked at, so the two fetches overlap
+        // (columns beyond the end compute on whatever their entry names, clamped into range, and store
+        // nothing); an entry brings parent and input row along.
+        v4i el[NT], ef[NT];
 #pragma unroll
         for (int i = 0; i < NT; ++i) {
-            const int n = n_of[i] < N ? n_of[i] : N - 1;
-            int r = a.x_row ? a.x_row[n] : n;
-            gx_of[i] = r < 0 ? 0 : (r >= a.n_x_rows ? a.n_x_rows - 1 : r);
+            const int jl = n0 + qr_pipe_b_row<NT>(wave, i, lane), jf = n0 + (wn * NT + i) * 16 + col;
+            el[i] = rows[jl < N ? jl : N - 1];
+            ef[i] = rows[jf < N ? jf : N - 1];
+        }
+        const int n_cnt = *g.n_rows;
+        if (n0 >= n_cnt) return;   // uniform per block
+#pragma unroll
+        for (int i = 0; i < NT; ++i) {
+            const int jf = n0 + (wn * NT + i) * 16 + col;
+            const v4i &el_i = el[i], &ef_i = ef[i];
+            auto hyp = [&](int r) { return r < 0 ? 0 : (r >= N ? N - 1 : r); };
+            ld_n[i] = hyp(el_i[0]);
+            ld_s[i] = a.parent ? el_i[1] : ld_n[i];
+            ld_x[i] = (!USE_GX && a.x_row) ? el_i[2] : ld_n[i];
+            n_of[i] = hyp(ef_i[0]);
+            src_of[i] = a.parent ? ef_i[1] : n_of[i];
+            n_ok[i] = jf < n_cnt;
+            if (USE_GX) {
+                const int r = a.x_row ? ef_i[2] : n_of[i];
+                gx_of[i] = r < 0 ? 0 : (r >= a.n_x_rows ? a.n_x_rows - 1 : r);
+            }
+        }
+    } else {
+#pragma unroll
+        for (int i = 0; i < NT; ++i) {
+            const int n = n0 + qr_pipe_b_row<NT>(wave, i, lane);
+            ld_n[i] = n < N ? n : N - 1;
+            const int m = n0 + (wn * NT + i) * 16 + col;
+            n_of[i] = m;
+            n_ok[i] = m < N;
+            src_of[i] = m < N ? m : N - 1;
+        }
+        if (a.parent) {
+#pragma unroll
+            for (int i = 0; i < NT; ++i) { ld_s[i] = a.parent[ld_n[i]]; src_of[i] = a.parent[src_of[i]]; }
+        } else {
+#pragma unroll
+            for (int i = 0; i < NT; ++i) ld_s[i] = ld_n[i];
+        }
+        if (!USE_GX && a.x_row) {
+#pragma unroll
+            for (int i = 0; i < NT; ++i) ld_x[i] = a.x_row[ld_n[i]];
+        } else {
+#pragma unroll
+            for (int i = 0; i < NT; ++i) ld_x[i] = ld_n[i];
+        }
+        if (USE_GX) {   // row of the precomputed input projection for the hypotheses this lane finishes
+#pragma unroll
+            for (int i = 0; i < NT; ++i) {
+                const int n = n_of[i] < N ? n_of[i] : N - 1;
+                int r = a.x_row ? a.x_row[n] : n;
+                gx_of[i] = r < 0 ? 0 : (r >= a.n_x_rows ? a.n_x_rows - 1 : r);
+            }
         }
     }
     constexpr int NPH = USE_GX ? 1 : 2;
@@ -286,7 +333,7 @@ __global__ __launch_bounds__(256, (USE_GX && !DBG) ? 3 : 2) void lstm_step_pipe_
 #pragma unroll
                 for (int nt = 0; nt < NT; ++nt) {
                     const int mt = 4 * q + i;
-                    if (DBG && a.dbg_accx && jb[q] == qr_gates_cell(rt0 + 4 * q, grp) && n_of[nt] < N)
+                    if (DBG && a.dbg_accx && jb[q] == qr_gates_cell(rt0 + 4 * q, grp) && n_ok[nt])
 #pragma unroll
                         for (int gt = 0; gt < 4; ++gt)
                             a.dbg_accx[(int64_t)n_of[nt] * 4 * H + gt * H + jb[q] + i] = acc[mt][nt][gt] >> 4;
@@ -368,7 +415,7 @@ __global__ __launch_bounds__(256, (USE_GX && !DBG) ? 3 : 2) void lstm_step_pipe_
                 const float hq = go * (hinv2 * rc - a.h_inv);
                 cn[i] = on ? c1 : cp[q][nt][i];
                 codes |= (unsigned)((int)fminf(fmaxf(__builtin_rintf(hq), -8.0f), 7.0f) & 0xFF) << (8 * i);
-                if (DBG && jv && n < N) {
+                if (DBG && jv && n_ok[nt]) {
                     if (USE_GX && !TAB && a.dbg_accx)
 #pragma unroll
                         for (int gt = 0; gt < 4; ++gt) a.dbg_accx[(int64_t)n * 4 * H + gt * H + jb[q] + i] = gxv[cur][i][gt];
@@ -383,7 +430,7 @@ __global__ __launch_bounds__(256, (USE_GX && !DBG) ? 3 : 2) void lstm_step_pipe_
                 }
             }
             codes = on ? codes : (unsigned)hp_code[q][nt];
-            if (FAST || (jv && n < N)) {
+            if (FAST ? (!rows || n_ok[nt]) : (jv && n_ok[nt])) {
                 *(v4f *)(a.c_next + (int64_t)n * H + jb[q]) = cn;
                 *(unsigned *)(a.h_next + (int64_t)n * a.ld_hn + jb[q]) = codes;
                 if (a.h_copy) *(unsigned *)(a.h_copy + (int64_t)n * H + jb[q]) = codes;
@@ -614,6 +661,13 @@ static void launch_group_t(const QrStepGroup &g, hipStream_t st)
     else if (all_small) launch_small<USE_GX>(g, st);
     else
         for (int i = 0; i < g.n; ++i) launch_step_t<USE_GX>(g.p[i], st);
+}
+
+bool qr_step_list_pays(int N)
+{
+    // measured at 64 utterances: beams 2 - 8 (128 - 512 hypotheses) lose 1 - 3 % of the decoder time to the list,
+    // beam 1 gains 40 % and beam 16 up to 6 %
+    return N <= small_n_max() || N >= 1024;
 }
 
 void qr_launch_lstm_step_group(const QrStepGroup &g, bool use_gx, hipStream_t st)

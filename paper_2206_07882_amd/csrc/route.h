@@ -15,6 +15,7 @@ __device__ __forceinline__ int qr_route_picks(const QrRouteArgs &a, int b, int l
                                               int own_len)
 {
     if (lane == 0 && b == 0 && a.live_clear) *a.live_clear = 0;
+    if (lane == 0 && b == 0 && a.n_rows_clear) *a.n_rows_clear = 0;
     const int W = a.W, V = a.V, N = a.B * a.W;
     const bool in = lane < W;
     const bool found = in && c >= 0;
@@ -36,6 +37,12 @@ __device__ __forceinline__ int qr_route_picks(const QrRouteArgs &a, int b, int l
     if (a.last_round) return cnt;
     const int n_lab = __popcll(lm);
     if (lane == 0 && n_lab > 0 && a.live_next) atomicAdd(a.live_next, 1);
+    if (a.rows_next && n_lab > 0) {   // uniform; the order of the utterances in the list does not matter
+        int base = 0;
+        if (lane == 0) base = atomicAdd(a.n_rows_next, n_lab);
+        base = __builtin_amdgcn_readfirstlane(base);
+        if (is_lab) a.rows_next[base + (int)__popcll(lm & lt)] = v4i{b * W + (int)__popcll(lm & lt), src_slot, tok, 0};
+    }
     if (is_lab) {
         const int dst = b * W + __popcll(lm & lt);
         const int id = a.node_base + dst;

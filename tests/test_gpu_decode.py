@@ -137,12 +137,18 @@ def test_decode_paper_shapes_small_batch(gpu_lib):
         _compare_beams(got, ref)
 
 
-def test_decode_benchmark_shape_sampled_utterances(gpu_lib):
+@pytest.mark.parametrize("blank_bias", [0.0, 1.5])
+def test_decode_benchmark_shape_sampled_utterances(gpu_lib, blank_bias):
     """The decoder in the launch configuration the benchmark times (64 utterances x beam 16 = 1024
     hypotheses, at most 4 labels per frame, full layer widths), on a few frames.  Utterances do not
-    interact, so the oracle decodes two sampled ones alone and must find the GPU's beams for them."""
+    interact, so the oracle decodes two sampled ones alone and must find the GPU's beams for them.
+    The networks advance only for the hypotheses that took a label (a list built on the device): with
+    the plain model nearly all of them do in some rounds and one per utterance in others, with the
+    blank's joint bias raised the lists are short and of uneven length."""
     from paper_2206_07882_amd import model as gmodel
     m = synth.make_model(4, enc_layers=1)
+    m.joint_out.bias = m.joint_out.bias.copy()
+    m.joint_out.bias[0] += np.float32(blank_bias)   # blank is token 0
     T, B, W, max_sym = 3, 64, 16, 4
     e = synth.normal(202, (T, B, m.J), 1.0)
     got = gpu_lib.decode(gmodel.model_from_float(m, DEV), dev(e), W, max_sym)
