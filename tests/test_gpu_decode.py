@@ -66,8 +66,13 @@ def test_config0_end_to_end_beams_identical(gpu_lib, std):
 
 @pytest.mark.parametrize("B,W,max_sym,T,lms,std", [(3, 4, 2, 12, True, 0.6), (2, 1, 3, 10, True, 0.6),
                                                    (4, 16, 4, 6, True, 0.5), (2, 3, 0, 8, False, 0.6),
-                                                   (5, 8, 1, 9, False, 0.4), (5, 16, 2, 6, True, 0.5)])
+                                                   (5, 8, 1, 9, False, 0.4), (5, 16, 2, 6, True, 0.5),
+                                                   (3, 33, 2, 5, True, 0.5), (2, 64, 1, 4, True, 0.5),
+                                                   (1, 16, 4, 1, True, 0.6), (16, 64, 2, 4, True, 0.5)])
 def test_decode_variants_match_oracle(gpu_lib, B, W, max_sym, T, lms, std):
+    """Beam widths on both sides of the 16-column tile and up to the maximum of 64, a single frame, no LMs, no
+    labels (max_sym 0), and 16 x 64 = 1024 hypotheses of the tiny networks: the tiled step kernel with partial
+    K chunks running over the device-built list of advancing hypotheses."""
     from paper_2206_07882_amd import model as gmodel
     m = synth.make_model(0, weight_std=std)
     if not lms:
