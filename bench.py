@@ -216,15 +216,17 @@ def main():
             cm = lambda mq: q.QMat(mq.packed.clone(), mq.row_scale.clone(), mq.rows, mq.cols, mq.layout)
             return q.Lstm(cm(L.w_ih), cm(L.w_hh), L.bias.clone(), L.x_scale, L.h_scale, L.h_inv_scale)
 
-        def round_groups(N, fresh_weights=False):
+        def round_groups(N, fresh_weights=False, mm=None, GG=None):
             """The two LSTM launches of one decoding round at N hypotheses, as qrnnt_decode issues them:
             first layers of the prediction network and of both LMs (input part looked up in the per-token
             table of input projections), then the second layers of both LMs.  fresh_weights: private
             copies of every weight tensor (for the cache-cold rotation)."""
-            tok = torch.from_numpy(synth.token_ids(3, (N,), m.V)).to(dev)
+            mm, GG = (m, G) if mm is None else (mm, GG)
+            tok = torch.from_numpy(synth.token_ids(3, (N,), mm.V)).to(dev)
             parent = torch.from_numpy(synth.parent_perm(4, max(N // W, 1), min(W, N))).to(dev)
             groups = []
-            for layer_idx, nets in ((0, (G.pred, G.lm_src, G.lm_ext)), (1, (G.lm_src, G.lm_ext))):
+            for layer_idx in (0, 1):
+                nets = [net for net in (GG.pred, GG.lm_src, GG.lm_ext) if len(net.layers) > layer_idx]
                 steps, ops, byt = [], 0.0, 0.0
                 for net in nets:
                     L = clone_lstm(net.layers[layer_idx]) if fresh_weights else net.layers[layer_idx]
@@ -237,7 +239,7 @@ def main():
                         d["gx"] = q.input_projection(L, net.embed_codes)[0]
                         d["gx_table"] = q.input_table(L, d["gx"])
                         k_in = 0
-                        byt += m.V * 4 * L.H * 4   # the table of per-token int32 sums
+                        byt += mm.V * 4 * L.H * 4   # the table of per-token int32 sums
                     else:
                         d["x_codes"] = torch.from_numpy(synth.codes(5, (N, L.I))).to(dev)
                         k_in = L.I
@@ -281,6 +283,20 @@ def main():
                              "us_per_round": t16 * 1e6, "algorithmic_bytes_per_round": byt16,
                              "GBps": byt16 / t16 / 1e9, "frac_hbm": byt16 / t16 / 1e9 / HBM_PEAK_GBPS,
                              "note": "weights re-read every round; warm (the 18 MB of weights stay in L2 / MALL)"}
+
+        # ---- N = 16 with the layer shapes of Sec. 2 (external LM 2 x 2048: 25 MB of weights): three times the bytes
+        # per launch for the same launch and latency overhead
+        m5k = synth.make_model(5)
+        G5k = gmodel.model_from_float(m5k, dev)
+        byt5, t5 = 0.0, 0.0
+        for grp, ops, byt in round_groups(16, mm=m5k, GG=G5k):
+            t5 += timed_graph(grp.launch, 100)
+            byt5 += byt
+        extra["step_n16_paper_shapes"] = {"kernel": "the same two launches with the Sec. 2 shapes (pred 768, source LM 768, "
+                                                    "external LM 2 x 2048)",
+                                          "us_per_round": t5 * 1e6, "algorithmic_bytes_per_round": byt5,
+                                          "GBps": byt5 / t5 / 1e9, "frac_hbm": byt5 / t5 / 1e9 / HBM_PEAK_GBPS}
+        del m5k, G5k
 
         # ---- the same at N = 16 with the weights coming from HBM: 28 private copies of all weight tensors
         # (28 x 13.3 MB, more than the 256 MB MALL) visited in turn, so no launch finds its weights in a cache

@@ -256,7 +256,8 @@ def test_input_projection_exact(gpu_lib, I, H, M):
 
 
 @pytest.mark.parametrize("N,use_gx", [(16, False), (16, True), (48, True), (144, False), (144, True), (256, True),
-                                       (256, False), (16, "table"), (144, "table"), (256, "table")])
+                                       (256, False), (16, "table"), (144, "table"), (256, "table"),
+                                       (11, False), (11, "table"), (5, True)])
 def test_lstm_step_group_parity(gpu_lib, N, use_gx):
     """Three independent steps in one launch (widths of the first layers of the
     prediction network and of two LMs, scaled down), inputs picked by token id from
@@ -266,7 +267,7 @@ def test_lstm_step_group_parity(gpu_lib, N, use_gx):
     V = 46
     shapes = [(128, 128), (64, 256), (64, 256)]
     s_x = float(np.float32(1.25) / np.float32(7))
-    W = 16
+    W = min(16, N)
     parent = synth.parent_perm(80 + N, N // W, W)
     tok = synth.token_ids(81 + N, (N,), V)
     active = (np.random.default_rng(82 + N).random(N) < 0.7).astype(np.uint8)
