@@ -535,7 +535,7 @@ static void net_advance(const oq_net_t *net, const net_state *src, int token, ne
         float *ym = (float *)malloc((size_t)net->mid.rows * sizeof(float));
         int8_t *qm = (int8_t *)malloc((size_t)net->mid.rows);
         oq_linear(&net->mid, xin, 1, ym, NULL);
-        oq_quantize_sym4(ym, net->mid.rows, net->inv_s_mid, qm);
+        oq_quantize_sym(ym, net->mid.rows, net->inv_s_mid, net->out.bits, qm); /* the output layer's own input quantizer */
         oq_linear(&net->out, qm, 1, dst->y, NULL);
         free(ym); free(qm);
     } else {
