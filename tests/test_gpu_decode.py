@@ -64,6 +64,41 @@ def test_config0_end_to_end_beams_identical(gpu_lib, std):
         assert tok_g[int(b), int(w), :len_g[int(b), int(w)]].tolist() == want
 
 
+@pytest.mark.parametrize("T,B", [(12, 3), (9, 1)])
+def test_encoder_stack_full_widths_layer_by_layer(gpu_lib, T, B):
+    """The encoder of configuration 1 (6 bidirectional layers of 640 cells over 240 features, then the
+    projection to the joint) on a short batch: every layer is compared with the oracle's layer run on the
+    GPU's own output of the layer below, so that a rounding tie in one layer cannot travel upwards; the
+    projection is compared on the GPU's final codes; the whole stack is also compared free-running."""
+    from paper_2206_07882_amd import model as gmodel
+    q = gpu_lib
+    m = synth.make_model(1)
+    feats = synth.features(1, T, B, m.feat_dim)
+    layers, proj = omodels.encoder_from_float(m)
+    enc = gmodel.Encoder(m, DEV)
+    x_free, e_free = omodels.encoder_forward(layers, proj, feats, m.alpha_x)
+    x_g, e_g = enc.forward(dev(feats))
+    assert (host(x_g) == x_free).mean() >= 0.995
+    # layer by layer on the GPU's own inputs
+    ws = enc.workspace(T, B, DEV)
+    x = q.quantize_act(dev(feats), enc.inv_s_x)
+    assert np.array_equal(host(x), oracle.quant_sym(feats, enc.inv_s_x, 4))
+    for li, (dirs_g, dirs_o) in enumerate(zip(enc.layers, layers)):
+        H = dirs_g[0].H
+        out = torch.empty((T, B, 2 * H), dtype=torch.int8, device=DEV)
+        q.bilstm_layer(dirs_g[0], dirs_g[1], x, h_out=out, workspace=ws)
+        ref = np.zeros((T, B, 2 * H), np.int8)
+        for d, L in enumerate(dirs_o):
+            oracle.lstm_layer(L, host(x), reverse=(d == 1), h_out=ref, col_off=d * H)
+        og = host(out)
+        assert np.abs(og.astype(np.int32) - ref).max() <= 1, f"layer {li}"
+        assert (og == ref).mean() >= 0.999, f"layer {li}: {(og == ref).mean()}"
+        x = out
+    assert np.array_equal(host(x), host(x_g))
+    e_ref = oracle.linear(proj, host(x).reshape(T * B, -1)).reshape(T, B, -1)
+    assert np.abs(host(e_g) - e_ref).max() <= 1e-5 * np.abs(e_ref).max() + 1e-6
+
+
 @pytest.mark.parametrize("B,W,max_sym,T,lms,std", [(3, 4, 2, 12, True, 0.6), (2, 1, 3, 10, True, 0.6),
                                                    (4, 16, 4, 6, True, 0.5), (2, 3, 0, 8, False, 0.6),
                                                    (5, 8, 1, 9, False, 0.4), (5, 16, 2, 6, True, 0.5),
