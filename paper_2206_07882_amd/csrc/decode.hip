@@ -25,7 +25,7 @@ struct Plan {
     float *score;        // [NB][B][W]
     int32_t *node, *len; // [NB][N]
     int32_t *parent_idx, *token;  uint8_t *active;        // [N]
-    float *nx_score;  int32_t *nx_src;  int32_t *nx_count; // [B][R*W], [B]
+    float *nx_score;  v4i *nx_info;  int32_t *nx_count; // [B][R*W], [B]
     int32_t *beam_src;   // [N]
     int32_t *node_tok, *node_prev;   // [1 + T*max_sym*N]
     int32_t *live;       // [2][max_sym+2]: utterances that carried a label into round v of the frame (early stop)
@@ -72,7 +72,7 @@ void make_plan(const qrnnt_model *m, int T, int B, int W, int max_sym, void *ws,
     p.token = cv.take<int32_t>(N);
     p.active = cv.take<uint8_t>(N);
     p.nx_score = cv.take<float>((size_t)B * p.R * W);
-    p.nx_src = cv.take<int32_t>((size_t)B * p.R * W);
+    p.nx_info = cv.take<v4i>((size_t)B * p.R * W);
     p.nx_count = cv.take<int32_t>(B);
     p.beam_src = cv.take<int32_t>(N);
     const size_t pool = 1 + (size_t)T * max_sym * N;
@@ -370,10 +370,10 @@ extern "C" qrnnt_status qrnnt_decode_ex(const qrnnt_model *m, const float *enc_p
             ra.score_dst = p.score + (size_t)nxt * Ns;  ra.node_dst = p.node + (size_t)nxt * Ns;
             ra.len_dst = p.len + (size_t)nxt * Ns;
             ra.parent_idx = p.parent_idx;  ra.token = p.token;  ra.active = p.active;
-            ra.nx_score = p.nx_score;  ra.nx_src = p.nx_src;  ra.nx_count = p.nx_count;
+            ra.nx_score = p.nx_score;  ra.nx_info = p.nx_info;  ra.nx_count = p.nx_count;
             ra.node_tok = p.node_tok;  ra.node_prev = p.node_prev;
             ra.fe_dst_buf = (a0 == 0) ? ZB : 0;
-            ra.fe_node_all = p.node;  ra.fe_len_all = p.len;  ra.fe_score_all = p.score;
+            ra.fe_score_all = p.score;
             ra.fe_node_all_w = p.node;  ra.fe_len_all_w = p.len;  ra.beam_src = p.beam_src;
             if (early) {   // live[t&1][v] = utterances that carried a label into round v of this frame
                 int32_t *lv = p.live + (size_t)(t & 1) * (max_sym + 2), *lo = p.live + (size_t)((t + 1) & 1) * (max_sym + 2);

@@ -182,7 +182,7 @@ __global__ __launch_bounds__(256) void joint_route_kernel(const QrJointArgs a, c
         fin_new[lane] = -INFINITY;
         own = qr_alsd_load_own(r, s, b, lane);
     }
-    if (!ALSD && wave == 0 && !r.last_round) {   // what the routing will need of this lane's hypothesis
+    if (!ALSD && wave == 0) {   // what the routing will need of this lane's hypothesis (its blank picks carry it into the candidate list)
         const int o = b * W + (lane < W ? lane : 0);
         own.node = r.node_src[o];
         own.len = r.len_src[o];

@@ -90,11 +90,10 @@ struct QrRouteArgs {
     const int32_t *node_src, *len_src;              // [N] of the current round
     float *score_dst;  int32_t *node_dst, *len_dst; // [N] of the next round
     int32_t *parent_idx, *token;  uint8_t *active;  // [N] inputs of the next network advance
-    float *nx_score;  int32_t *nx_src, *nx_count;   // the frame's candidate list
+    float *nx_score;  v4i *nx_info;  int32_t *nx_count;   // the frame's candidate list; info = (flat source (buffer, slot), trie node, length, -)
     int32_t *node_tok, *node_prev;                  // label trie
     // end of the frame (used when last_round): the W best of the candidate list become the beam in buffer fe_dst_buf
     int fe_dst_buf;
-    const int32_t *fe_node_all, *fe_len_all;        // [NB][N]
     float *fe_score_all;  int32_t *fe_node_all_w, *fe_len_all_w;
     int32_t *beam_src;                              // [N] flat source (buffer, slot) of every new beam slot, or -1
     // early stop (all optional): the round is dead when *gate == 0; an utterance that picked a label

@@ -30,7 +30,7 @@ __device__ __forceinline__ int qr_route_picks(const QrRouteArgs &a, int b, int l
     if (is_blank) {
         const int e = nx0 + __popcll(bm & lt);
         a.nx_score[(size_t)b * a.R * W + e] = v;
-        a.nx_src[(size_t)b * a.R * W + e] = a.src_buf * N + src_slot;
+        a.nx_info[(size_t)b * a.R * W + e] = v4i{a.src_buf * N + src_slot, par_node, par_len, 0};
     }
     const int cnt = nx0 + __popcll(bm);
     if (lane == 0) a.nx_count[b] = cnt;
@@ -69,7 +69,7 @@ __device__ __forceinline__ int qr_route_picks(const QrRouteArgs &a, int b, int l
 
 // End of a frame for utterance b (one wave): the new beam is the W best of the cnt candidates by
 // (score descending, insertion order); slot r of buffer fe_dst_buf takes score, trie node and length
-// of its source, beam_src[r] tells the state gather where the states are.  The candidates of the
+// that its candidate carried along, beam_src[r] tells the state copy where the states are.  The candidates of the
 // current round were stored by this same wave a moment ago: they are read back from L2 (agent-scope
 // loads after a fence), not through the CU's vector cache.
 __device__ __forceinline__ void qr_frame_end(const QrRouteArgs &a, int b, int lane, int cnt)
@@ -91,10 +91,14 @@ __device__ __forceinline__ void qr_frame_end(const QrRouteArgs &a, int b, int la
         const int dst = b * W + lane;
         const size_t o = (size_t)a.fe_dst_buf * N + dst;
         if (c >= 0) {
-            const int src = __hip_atomic_load(a.nx_src + (size_t)b * R * W + c, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            // what the candidate carried along when it joined the list: three independent loads, no second hop
+            const int *info = (const int *)(a.nx_info + (size_t)b * R * W + c);
+            const int src = __hip_atomic_load(info, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            const int node = __hip_atomic_load(info + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            const int len = __hip_atomic_load(info + 2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             a.fe_score_all[o] = v;
-            a.fe_node_all_w[o] = a.fe_node_all[src];
-            a.fe_len_all_w[o] = a.fe_len_all[src];
+            a.fe_node_all_w[o] = node;
+            a.fe_len_all_w[o] = len;
             a.beam_src[dst] = src;
         } else {
             a.fe_score_all[o] = -INFINITY;
