@@ -121,7 +121,7 @@ __global__ __launch_bounds__(256) void joint_fuse_kernel(const QrJointArgs a)
 // every hypothesis reads its own encoder frame (iteration - labels so far), a blank at the last frame
 // finishes a hypothesis instead of being a candidate, labels beyond the cap are no candidates.
 // Workgroups beyond the B utterances (time-synchronous search, first round of a frame) copy the state rows of the
-// new beam from their sources into the beam's buffer, one (slot, tensor) pair per wave: that copy only has to be
+// new beam from their sources into the beam's buffer, four slots of one tensor per wave: that copy only has to be
 // done before the next network advance, so it runs here, on the CUs this kernel leaves idle, instead of in a launch
 // of its own.  The joint of this round reads its inputs through the same source indices (QrJointArgs.row_idx).
 template <int NTW, bool ALSD>
@@ -132,27 +132,45 @@ __global__ __launch_bounds__(256) void joint_route_kernel(const QrJointArgs a, c
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     if (!ALSD && (int)blockIdx.x >= r.B) {   // uniform per workgroup
-        const int pair = ((int)blockIdx.x - r.B) * 4 + wave;
-        if (pair >= gt.N * gt.n) return;
-        const int n = pair % gt.N, t = pair / gt.N;
-        const int src = gt.beam_src[n];
-        if (src < 0) return;   // an empty rank keeps whatever the destination holds (its score is -inf)
+        // A wave moves the rows of 4 consecutive slots of one tensor.  This kernel's register footprint allows only
+        // 8 waves per CU, so what keeps the copy near the memory rate is the amount each wave has in flight: all
+        // loads of its (up to) four rows are issued before the first store, 16 KiB per wave for 4 KiB rows.
+        const int nq = (gt.N + 3) >> 2;
+        const int quad = ((int)blockIdx.x - r.B) * 4 + wave;
+        if (quad >= nq * gt.n) return;
+        const int t = quad / nq, n0 = (quad - t * nq) * 4;
         const int rb = gt.row_bytes[t];
-        const char *sp = gt.base[t] + (size_t)src * rb;
-        char *dp = gt.base[t] + ((size_t)gt.dst_buf * gt.N + n) * rb;
-        if ((rb & 15) == 0 && (((uintptr_t)sp | (uintptr_t)dp) & 15) == 0) {   // 4 KiB of the row in flight per wave
+        const char *sp[4];
+        char *dp[4];
+        bool ok[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int n = n0 + u;
+            const int src = n < gt.N ? gt.beam_src[n] : -1;   // an empty rank keeps whatever the destination holds (its score is -inf)
+            ok[u] = src >= 0;
+            sp[u] = gt.base[t] + (size_t)(ok[u] ? src : 0) * rb;
+            dp[u] = gt.base[t] + ((size_t)gt.dst_buf * gt.N + (n < gt.N ? n : 0)) * rb;
+        }
+        if ((rb & 15) == 0 && ((uintptr_t)gt.base[t] & 15) == 0) {
             const int n16 = rb >> 4;
             for (int i0 = 0; i0 < n16; i0 += 256) {
-                v4i tmp[4];
+                v4i tmp[4][4];
 #pragma unroll
                 for (int u = 0; u < 4; ++u)
-                    if (i0 + u * 64 + lane < n16) tmp[u] = ((const v4i *)sp)[i0 + u * 64 + lane];
+#pragma unroll
+                    for (int v = 0; v < 4; ++v)
+                        if (ok[u] && i0 + v * 64 + lane < n16) tmp[u][v] = ((const v4i *)sp[u])[i0 + v * 64 + lane];
 #pragma unroll
                 for (int u = 0; u < 4; ++u)
-                    if (i0 + u * 64 + lane < n16) ((v4i *)dp)[i0 + u * 64 + lane] = tmp[u];
+#pragma unroll
+                    for (int v = 0; v < 4; ++v)
+                        if (ok[u] && i0 + v * 64 + lane < n16) ((v4i *)dp[u])[i0 + v * 64 + lane] = tmp[u][v];
             }
         } else {
-            for (int i = lane; i < rb / 4; i += 64) ((uint32_t *)dp)[i] = ((const uint32_t *)sp)[i];
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+                if (ok[u])
+                    for (int i = lane; i < rb / 4; i += 64) ((uint32_t *)dp[u])[i] = ((const uint32_t *)sp[u])[i];
         }
         return;
     }
@@ -341,7 +359,7 @@ __global__ __launch_bounds__(256) void joint_route_kernel(const QrJointArgs a, c
 void qr_launch_joint_route(const QrJointArgs &a, const QrRouteArgs &r, const QrGatherTable &gt, hipStream_t st)
 {
     const QrAlsdArgs none = {};
-    const unsigned grid = (unsigned)(r.B + (gt.n > 0 ? (gt.N * gt.n + 3) / 4 : 0));
+    const unsigned grid = (unsigned)(r.B + (gt.n > 0 ? (((gt.N + 3) / 4) * gt.n + 3) / 4 : 0));   // copy: 4 slots per wave, 4 waves per workgroup
     if (r.W <= 16) joint_route_kernel<1, false><<<grid, 256, 0, st>>>(a, r, none, gt);
     else if (r.W <= 32) joint_route_kernel<2, false><<<grid, 256, 0, st>>>(a, r, none, gt);
     else joint_route_kernel<4, false><<<grid, 256, 0, st>>>(a, r, none, gt);
