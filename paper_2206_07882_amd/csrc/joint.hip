@@ -129,6 +129,7 @@ __global__ __launch_bounds__(256) void joint_route_kernel(const QrJointArgs a, c
                                                           const QrGatherTable gt)
 {
     __shared__ v4i lds[4 * 4 * 64];
+    __shared__ float cand[16 * NTW * 64];   // the utterance's candidates by flat index (second attempt of the selection)
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     if (!ALSD && (int)blockIdx.x >= r.B) {   // uniform per workgroup
@@ -329,18 +330,36 @@ __global__ __launch_bounds__(256) void joint_route_kernel(const QrJointArgs a, c
     float last_v = INFINITY;
     int last_c = -1, my_c = -1;
     float my_v = -INFINITY;
-    const bool fast = qr_select_pruned<PER>(val, index_of, W, lane, (unsigned *)lds, (int *)lds + 64, my_c, my_v);
-    for (int rd = 0; !fast && rd < W; ++rd) {   // general case: W rounds of arg-best
-        float bv = -INFINITY;
-        int bc = 0x7fffffff;
+    bool fast = qr_select_pruned<PER>(val, index_of, W, lane, (unsigned *)lds, (int *)lds + 64, my_c, my_v);
+    if (!fast) {   // uniform
+        // More than 64 candidates passed the bound: the MFMA layout keeps a hypothesis' tokens in 4 lanes, and when
+        // the best candidates of the utterance belong to one or two hypotheses a lane's best says little.  The
+        // candidates change places through LDS (lane l takes the flat indices l, l + 64, ...: every hypothesis is
+        // then spread over all lanes and the bound is tight) and the pruned selection runs again.
 #pragma unroll
-        for (int s = 0; s < PER; ++s) {
-            const int c = cbase + (s >> 4) * 16 * V + ((s >> 2) & 3) * 16 + (s & 3);
-            const float v = val[s];
-            const bool ok = v > -INFINITY && (v < last_v || (v == last_v && c > last_c));
-            if (ok && v > bv) { bv = v; bc = c; }   // slots are visited in index order: first best wins
+        for (int sl = 0; sl < PER; ++sl) {
+            const int w = (sl >> 4) * 16 + col, k = ((sl >> 2) & 3) * 16 + grp * 4 + (sl & 3);
+            if (w < W && k < V) cand[w * V + k] = val[sl];
         }
-        if (!qr_select_round(bv, bc, rd, lane, last_v, last_c, my_c, my_v)) break;
+        __builtin_amdgcn_wave_barrier();
+        const int n_cand = W * V;
+#pragma unroll
+        for (int sl = 0; sl < PER; ++sl) val[sl] = (lane + 64 * sl < n_cand) ? cand[lane + 64 * sl] : -INFINITY;
+        __builtin_amdgcn_wave_barrier();
+        auto index_t = [&](int sl) { return lane + 64 * sl; };
+        fast = qr_select_pruned<PER>(val, index_t, W, lane, (unsigned *)lds, (int *)lds + 64, my_c, my_v);
+        for (int rd = 0; !fast && rd < W; ++rd) {   // general case: W rounds of arg-best
+            float bv = -INFINITY;
+            int bc = 0x7fffffff;
+#pragma unroll
+            for (int sl = 0; sl < PER; ++sl) {
+                const int c = lane + 64 * sl;
+                const float v = val[sl];
+                const bool ok = v > -INFINITY && (v < last_v || (v == last_v && c > last_c));
+                if (ok && v > bv) { bv = v; bc = c; }   // slots are visited in index order: first best wins
+            }
+            if (!qr_select_round(bv, bc, rd, lane, last_v, last_c, my_c, my_v)) break;
+        }
     }
     if (ALSD) {
         __builtin_amdgcn_wave_barrier();
