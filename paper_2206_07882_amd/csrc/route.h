@@ -155,24 +155,25 @@ __device__ __forceinline__ void qr_alsd_route(const QrRouteArgs &a, const QrAlsd
     const int new_len = len_p + (is_lab ? 1 : 0);
     const unsigned long long new_hash = is_lab ? hash_p * 0x9E3779B97F4A7C15ull + (unsigned long long)(tok + 1) : hash_p;
     const int h_lo = (int)(unsigned)new_hash, h_hi = (int)(unsigned)(new_hash >> 32);
-    const int fnd = found ? 1 : 0;
+    // length and "is a pick" in one word: a lane without a pick gets a value no other lane has
+    const int lw = found ? new_len : -1 - lane;
     int leader = lane;
     float m = v;
+    unsigned long long eq = 0ull;   // the picks that stand for this lane's label sequence
     for (int j = 0; j < W; ++j) {
-        const bool same = found && __builtin_amdgcn_readlane(fnd, j) && __builtin_amdgcn_readlane(h_lo, j) == h_lo &&
-                          __builtin_amdgcn_readlane(h_hi, j) == h_hi && __builtin_amdgcn_readlane(new_len, j) == new_len;
+        const bool same = __builtin_amdgcn_readlane(lw, j) == lw && __builtin_amdgcn_readlane(h_lo, j) == h_lo &&
+                          __builtin_amdgcn_readlane(h_hi, j) == h_hi;
         const float vj = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), j));
         if (same) {
+            eq |= 1ull << j;
             leader = j < leader ? j : leader;
             m = fmaxf(m, vj);
         }
     }
     float sum = 0.0f;
     for (int j = 0; j < W; ++j) {
-        const bool same = found && __builtin_amdgcn_readlane(fnd, j) && __builtin_amdgcn_readlane(h_lo, j) == h_lo &&
-                          __builtin_amdgcn_readlane(h_hi, j) == h_hi && __builtin_amdgcn_readlane(new_len, j) == new_len;
         const float vj = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), j));
-        if (same) sum += qr_exp(vj - m);
+        if ((eq >> j) & 1ull) sum += qr_exp(vj - m);
     }
     const bool keep = found && leader == lane;
     const unsigned long long km = __ballot(keep);
