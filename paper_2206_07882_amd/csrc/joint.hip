@@ -197,6 +197,7 @@ __global__ __launch_bounds__(256) void joint_route_kernel(const QrJointArgs a, c
     float val[PER];
     float *fin_new = (float *)lds + 256;   // ALSD: value of hypothesis w finishing now; wave 0's own part of the buffer
     QrAlsdOwn own = {};
+    int nx0 = 0;   // length of the utterance's candidate list before this round
     if (ALSD && wave == 0) {
         fin_new[lane] = -INFINITY;
         own = qr_alsd_load_own(r, s, b, lane);
@@ -205,6 +206,7 @@ __global__ __launch_bounds__(256) void joint_route_kernel(const QrJointArgs a, c
         const int o = b * W + (lane < W ? lane : 0);
         own.node = r.node_src[o];
         own.len = r.len_src[o];
+        nx0 = r.nx_count[b];
     }
     // per-token constants of this lane's 16 tokens (fetched behind the first tile's operands, see qr_head_mma)
     float wscale[4][4], wbias[4][4];
@@ -366,7 +368,7 @@ __global__ __launch_bounds__(256) void joint_route_kernel(const QrJointArgs a, c
         qr_alsd_route(r, s, b, lane, my_c, my_v, fin_new[lane], own);
         return;
     }
-    const int cnt = qr_route_picks(r, b, lane, my_c, my_v, own.node, own.len);
+    const int cnt = qr_route_picks(r, b, lane, my_c, my_v, own.node, own.len, nx0);
     if (r.last_round) {   // the frame is complete for this utterance: prune its candidate list to the new beam
         __threadfence();
         qr_frame_end(r, b, lane, cnt);

@@ -11,8 +11,9 @@
 // Returns the length of the utterance's candidate list after this round (uniform).
 // own_node / own_len: trie node and length of hypothesis `lane` of the current round (fetched at the start of the
 // kernel, so that the routing does not wait for memory); a pick reads its parent's from that lane.
+// nx0: the length of the utterance's candidate list before this round (a.nx_count[b], fetched early as well).
 __device__ __forceinline__ int qr_route_picks(const QrRouteArgs &a, int b, int lane, int c, float v, int own_node,
-                                              int own_len)
+                                              int own_len, int nx0)
 {
     if (lane == 0 && b == 0 && a.live_clear) *a.live_clear = 0;
     if (lane == 0 && b == 0 && a.n_rows_clear) *a.n_rows_clear = 0;
@@ -26,7 +27,6 @@ __device__ __forceinline__ int qr_route_picks(const QrRouteArgs &a, int b, int l
     const unsigned long long lt = (1ull << lane) - 1ull;
     const int src_slot = b * W + par;
     const int par_node = __shfl(own_node, par), par_len = __shfl(own_len, par);
-    const int nx0 = a.nx_count[b];
     if (is_blank) {
         const int e = nx0 + __popcll(bm & lt);
         a.nx_score[(size_t)b * a.R * W + e] = v;
