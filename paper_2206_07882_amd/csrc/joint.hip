@@ -183,7 +183,7 @@ __global__ __launch_bounds__(256) void joint_route_kernel(const QrJointArgs a, c
         if (wave == 0) {
             if (lane == 0 && b == 0 && r.live_clear) *r.live_clear = 0;
             if (lane == 0 && b == 0 && r.n_rows_clear) *r.n_rows_clear = 0;
-            if (r.last_round) qr_frame_end(r, b, lane, r.nx_count[b]);
+            if (r.last_round) qr_frame_end(r, b, lane, r.nx_count[b], (unsigned *)lds, (int *)lds + 64);
         }
         return;
     }
@@ -371,7 +371,7 @@ __global__ __launch_bounds__(256) void joint_route_kernel(const QrJointArgs a, c
     const int cnt = qr_route_picks(r, b, lane, my_c, my_v, own.node, own.len, nx0);
     if (r.last_round) {   // the frame is complete for this utterance: prune its candidate list to the new beam
         __threadfence();
-        qr_frame_end(r, b, lane, cnt);
+        qr_frame_end(r, b, lane, cnt, (unsigned *)lds, (int *)lds + 64);
     }
 }
 

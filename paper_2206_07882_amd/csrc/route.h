@@ -72,7 +72,8 @@ __device__ __forceinline__ int qr_route_picks(const QrRouteArgs &a, int b, int l
 // that its candidate carried along, beam_src[r] tells the state copy where the states are.  The candidates of the
 // current round were stored by this same wave a moment ago: they are read back from L2 (agent-scope
 // loads after a fence), not through the CU's vector cache.
-__device__ __forceinline__ void qr_frame_end(const QrRouteArgs &a, int b, int lane, int cnt)
+// sk / sc: 64 words of LDS each, private to the calling wave (pruned selection of select.h).
+__device__ __forceinline__ void qr_frame_end(const QrRouteArgs &a, int b, int lane, int cnt, unsigned *sk, int *sc_idx)
 {
     const int W = a.W, R = a.R, N = a.B * a.W;
     const float *sc = a.nx_score + (size_t)b * R * W;
@@ -83,7 +84,8 @@ __device__ __forceinline__ void qr_frame_end(const QrRouteArgs &a, int b, int la
         float val[2];
 #pragma unroll
         for (int i = 0; i < 2; ++i) val[i] = (lane * 2 + i < cnt) ? score_at(lane * 2 + i) : -INFINITY;
-        qr_select_from_regs<2>(val, lane * 2, W, lane, c, v);
+        auto index_of = [&](int i) { return lane * 2 + i; };
+        if (!qr_select_pruned<2>(val, index_of, W, lane, sk, sc_idx, c, v)) qr_select_from_regs<2>(val, lane * 2, W, lane, c, v);
     } else {
         qr_select_from_mem(score_at, cnt, W, lane, c, v);
     }
