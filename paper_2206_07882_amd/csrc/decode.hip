@@ -332,7 +332,7 @@ extern "C" qrnnt_status qrnnt_decode_ex(const qrnnt_model *m, const float *enc_p
         }
         tb.base[tb.n] = (char *)p.net[k].y;  tb.row_bytes[tb.n++] = net->out.rows * 4;
     }
-    tb.beam_src = p.beam_src;  tb.N = N;
+    tb.beam_src = p.beam_src;  tb.N = N;  tb.src_limit = p.NB * N;
     const QrGatherTable no_copy = {};
 
     const bool use_list = qr_step_list_pays(N);

@@ -148,7 +148,7 @@ __global__ __launch_bounds__(256) void joint_route_kernel(const QrJointArgs a, c
         for (int u = 0; u < 4; ++u) {
             const int n = n0 + u;
             const int src = n < gt.N ? gt.beam_src[n] : -1;   // an empty rank keeps whatever the destination holds (its score is -inf)
-            ok[u] = src >= 0;
+            ok[u] = src >= 0 && src < gt.src_limit;
             sp[u] = gt.base[t] + (size_t)(ok[u] ? src : 0) * rb;
             dp[u] = gt.base[t] + ((size_t)gt.dst_buf * gt.N + (n < gt.N ? n : 0)) * rb;
         }

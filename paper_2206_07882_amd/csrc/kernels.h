@@ -65,6 +65,7 @@ struct QrGatherTable {
     int n;                             // 0: nothing to copy
     const int32_t *beam_src;           // [N] flat source row (buffer * N + slot) of every new beam slot, -1: empty rank
     int N, dst_buf;
+    int src_limit;                     // flat source rows are below this (buffers x N); anything else is skipped
 };
 
 struct QrJointArgs {

@@ -221,10 +221,10 @@ def test_decode_early_stop_gives_the_same_beams(gpu_lib, blank_bias):
 
 @pytest.mark.parametrize("B,W,u_max,T,lms,std", [(3, 4, 6, 8, True, 0.5), (2, 1, 5, 10, True, 0.6), (4, 16, 8, 6, True, 0.5),
                                                  (2, 3, 0, 8, False, 0.6), (5, 8, 3, 9, False, 0.4), (3, 33, 4, 4, True, 0.5),
-                                                 (2, 64, 3, 3, True, 0.5)])
+                                                 (2, 64, 3, 3, True, 0.5), (16, 64, 3, 4, True, 0.5), (5, 8, 6, 7, True, 0.6)])
 def test_alsd_matches_oracle(gpu_lib, B, W, u_max, T, lms, std):
     """Alignment-length synchronous search with recombination (Sec. 2) on the tiny configuration: the finished
-    lists (label sequences, lengths, merged scores) must be the oracle's."""
+    lists (label sequences, lengths, merged scores) must be the oracle's; beams 1 to 64, up to 1024 slots."""
     from paper_2206_07882_amd import model as gmodel
     m = synth.make_model(0, weight_std=std)
     if not lms:
