@@ -177,8 +177,8 @@ qrnnt_status check_model(const qrnnt_model *m)
 
 // All used networks consume `token` and move from buffer src to buffer dst.  Layer l
 // of every network goes out as one grouped launch (the networks are independent).
-// n_rows (optional): only the hypotheses p.rows[0 .. *n_rows) advance (the recurrent layers; the output layers
-// are computed for every row, the rows that did not advance are not read afterwards).
+// n_rows (optional): only the hypotheses p.rows[0 .. *n_rows) advance (recurrent and output layers; the rows
+// that did not advance are not read afterwards).
 void advance_nets(const qrnnt_model *m, const Plan &p, int src, int dst, int n_embed_rows, const int32_t *gate,
                   const int32_t *n_rows, hipStream_t st)
 {
@@ -225,6 +225,8 @@ void advance_nets(const qrnnt_model *m, const Plan &p, int src, int dst, int n_e
     QrLinearGroup lg, lg2;
     lg.n = lg2.n = 0;
     lg.gate = lg2.gate = gate;
+    lg.rows = lg2.rows = n_rows ? p.rows : nullptr;
+    lg.n_rows = lg2.n_rows = n_rows;
     for (int k = 0; k < 3; ++k) {
         if (!net_used(m, k)) continue;
         const qrnnt_net *net = net_of(m, k);

@@ -312,7 +312,8 @@ __global__ __launch_bounds__(256) void joint_route_kernel(const QrJointArgs a, c
                         if (a.lp_ext) f += a.lambda_ext * le[mt][i];
                         f += a.rho;
                     }
-                    bool ok = wv && k < V && (ALSD || !r.last_round || k == a.blank);
+                    // an empty slot (score -inf) offers nothing, whatever its rows of the network outputs hold
+                    bool ok = wv && k < V && sc > -INFINITY && (ALSD || !r.last_round || k == a.blank);
                     if (ALSD) {
                         if (k != a.blank && len_w >= s.u_max) ok = false;      // label cap
                         if (k == a.blank && t_w == s.T - 1) {                  // a blank at the last frame finishes w

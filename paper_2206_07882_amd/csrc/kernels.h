@@ -55,6 +55,10 @@ struct QrLinearGroup {
     QrLinearArgs p[QR_MAX_GROUP];
     int n;
     const int32_t *gate;               // optional [device]: the launch does nothing when *gate == 0
+    // optional [device] (same N for all members), as in QrStepGroup: only the activation rows n listed in
+    // rows[0 .. *n_rows) (first word of an entry) are computed, every other row of the outputs stays as it is.
+    const v4i *rows = nullptr;
+    const int32_t *n_rows = nullptr;
 };
 
 // State tensors of the decoder ([buffers][N][row]): what a new beam slot copies from its source (buffer, slot).

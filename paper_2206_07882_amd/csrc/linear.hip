@@ -17,8 +17,15 @@ __global__ __launch_bounds__(256) void linear_head_kernel(const QrLinearGroup g)
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int col = lane & 15, grp = lane >> 4;
     int n = blockIdx.x * 16 + col;
-    const bool nv = n < a.N;
+    bool nv = n < a.N;
     n = nv ? n : a.N - 1;
+    if (g.rows) {   // column j stands for the activation row of list entry j; the entry is fetched before the count is looked at
+        const v4i e = g.rows[n];
+        const int n_cnt = *g.n_rows;
+        if ((int)blockIdx.x * 16 >= n_cnt) return;   // uniform per block
+        nv = nv && (int)blockIdx.x * 16 + col < n_cnt;
+        n = e[0] < 0 ? 0 : (e[0] >= a.N ? a.N - 1 : e[0]);
+    }
     const int8_t *arow = a.act + (int64_t)n * a.K + grp * 16;
     const int K = a.K;
     auto bload = [&](int kb) -> v4i {
@@ -125,6 +132,8 @@ void qr_launch_linear(const QrLinearArgs &a, hipStream_t st)
     g.p[0] = a;
     g.n = 1;
     g.gate = nullptr;
+    g.rows = nullptr;
+    g.n_rows = nullptr;
     qr_launch_linear_group(g, st);
 }
 
