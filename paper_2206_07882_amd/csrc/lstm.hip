@@ -3,6 +3,8 @@
 // W_ih and W_hh, fp bias and cell state; Sec. 3.4: the hidden state is
 // quantized once, at the cell output).
 #include <cstdlib>
+#include <type_traits>
+
 #include "kernels.h"
 #include "mma_pipe.h"
 
@@ -212,7 +214,11 @@ __global__ __launch_bounds__(256, (USE_GX && !DBG) ? 3 : 2) void lstm_step_pipe_
     // ---- indices: rows this thread stages (ld_*) and hypotheses this lane finishes (n_of)
     int ld_n[NT], ld_s[NT], ld_x[NT], n_of[NT], src_of[NT], gx_of[NT];
     bool n_ok[NT];   // the column stands for a hypothesis (not for padding of the last block)
-    // With a list the problem has *n_rows rows, row j standing for the hypothesis of entry j.
+    int nt_valid = NT;   // this wave's column tiles from here on are padding (list mode)
+    // With a list the problem has *n_rows rows, row j standing for the hypothesis of entry j.  The 16-column tiles of
+    // the block are dealt to the two column halves of the wave grid in turn (logical tile 2*nt + wn sits at the
+    // wave column wn, position nt), so that a short list keeps both halves equally busy and the tiles past its end,
+    // the same number in every wave, need not be computed.
     const v4i *rows = g.rows;
     if (rows) {
         // The entries are requested before the length of the list is looked at, so the two fetches overlap
@@ -221,15 +227,17 @@ __global__ __launch_bounds__(256, (USE_GX && !DBG) ? 3 : 2) void lstm_step_pipe_
         v4i el[NT], ef[NT];
 #pragma unroll
         for (int i = 0; i < NT; ++i) {
-            const int jl = n0 + qr_pipe_b_row<NT>(wave, i, lane), jf = n0 + (wn * NT + i) * 16 + col;
+            const int rl = qr_pipe_b_row<NT>(wave, i, lane);   // staged row: tile rl / 16 = wn' * NT + nt' of the block
+            const int jl = n0 + (((rl >> 4) % NT) * 2 + (rl >> 4) / NT) * 16 + (rl & 15), jf = n0 + (i * 2 + wn) * 16 + col;
             el[i] = rows[jl < N ? jl : N - 1];
             ef[i] = rows[jf < N ? jf : N - 1];
         }
         const int n_cnt = *g.n_rows;
         if (n0 >= n_cnt) return;   // uniform per block
+        nt_valid = (((n_cnt - n0 + 15) >> 4) + 1) >> 1;   // tiles that hold entries, per wave column (rounded up)
 #pragma unroll
         for (int i = 0; i < NT; ++i) {
-            const int jf = n0 + (wn * NT + i) * 16 + col;
+            const int jf = n0 + (i * 2 + wn) * 16 + col;
             const v4i &el_i = el[i], &ef_i = ef[i];
             auto hyp = [&](int r) { return r < 0 ? 0 : (r >= N ? N - 1 : r); };
             ld_n[i] = hyp(el_i[0]);
@@ -294,13 +302,17 @@ __global__ __launch_bounds__(256, (USE_GX && !DBG) ? 3 : 2) void lstm_step_pipe_
     if (!USE_GX) { ph[0].w = a.wih;  ph[0].nkc = a.nkc_x;  ph[0].K = a.I; }
     ph[NPH - 1].w = a.whh;  ph[NPH - 1].nkc = a.nkc_h;  ph[NPH - 1].K = H;
 
+    // Everything from here on exists twice: for all NT column tiles of the wave, and for its first NT / 2 only
+    // (a list that ends in the first half of the block).
+    auto run = [&](auto ntv_tag) {
+    constexpr int NTV = decltype(ntv_tag)::value;
     v4i acc[MT][NT];
     float pre[MT][NT][4];
     const v4i zero = {0, 0, 0, 0};
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-        for (int nt = 0; nt < NT; ++nt) acc[mt][nt] = zero;
+        for (int nt = 0; nt < NTV; ++nt) acc[mt][nt] = zero;
 
     // This lane finishes cells jb[q] .. jb[q]+3 (row tiles 4q .. 4q+3 of the wave) for
     // hypotheses n_of[nt]; out-of-range quartets are clamped for loads and skipped at the stores.
@@ -331,7 +343,7 @@ __global__ __launch_bounds__(256, (USE_GX && !DBG) ? 3 : 2) void lstm_step_pipe_
 #pragma unroll
             for (int i = 0; i < 4; ++i)
 #pragma unroll
-                for (int nt = 0; nt < NT; ++nt) {
+                for (int nt = 0; nt < NTV; ++nt) {
                     const int mt = 4 * q + i;
                     if (DBG && a.dbg_accx && jb[q] == qr_gates_cell(rt0 + 4 * q, grp) && n_ok[nt])
 #pragma unroll
@@ -343,7 +355,7 @@ __global__ __launch_bounds__(256, (USE_GX && !DBG) ? 3 : 2) void lstm_step_pipe_
                 }
         }
     };
-    qr_pipe_mma<MT, NT, S, NPH, !FAST>(ph, n_row_tiles, block_rt0, lds, acc, x_done);
+    qr_pipe_mma<MT, NT, S, NPH, !FAST, false, NTV>(ph, n_row_tiles, block_rt0, lds, acc, x_done);
 
     // ---- fused cell: batched 128-bit loads, then branch-free arithmetic, then 128-bit / 32-bit stores
     v4f cp[MQ][NT], sh[MQ][4], bb[MQ][4], sxg[MQ][4];
@@ -357,18 +369,18 @@ __global__ __launch_bounds__(256, (USE_GX && !DBG) ? 3 : 2) void lstm_step_pipe_
             if (USE_GX && !TAB) sxg[q][gt] = load4(a.s_wih + gt * H + jb[q]) * a.x_scale * gate_k(gt);
         }
 #pragma unroll
-        for (int nt = 0; nt < NT; ++nt) cp[q][nt] = load4(a.c_prev + (int64_t)src_of[nt] * H + jb[q]);
+        for (int nt = 0; nt < NTV; ++nt) cp[q][nt] = load4(a.c_prev + (int64_t)src_of[nt] * H + jb[q]);
     }
     if (a.active) {
 #pragma unroll
-        for (int nt = 0; nt < NT; ++nt) {
+        for (int nt = 0; nt < NTV; ++nt) {
             act[nt] = a.active[n_of[nt] < N ? n_of[nt] : N - 1];
 #pragma unroll
             for (int q = 0; q < MQ; ++q) hp_code[q][nt] = *(const int *)(a.h_prev + (int64_t)src_of[nt] * a.ld_hp + jb[q]);
         }
     } else {
 #pragma unroll
-        for (int nt = 0; nt < NT; ++nt) {
+        for (int nt = 0; nt < NTV; ++nt) {
             act[nt] = 1;
 #pragma unroll
             for (int q = 0; q < MQ; ++q) hp_code[q][nt] = 0;
@@ -390,11 +402,11 @@ __global__ __launch_bounds__(256, (USE_GX && !DBG) ? 3 : 2) void lstm_step_pipe_
     for (int q = 0; q < MQ; ++q) {
         const bool jv = FAST || qr_gates_cell(rt0 + 4 * q, grp) < H;
 #pragma unroll
-        for (int nt = 0; nt < NT; ++nt) {
+        for (int nt = 0; nt < NTV; ++nt) {
             const int n = n_of[nt];
             const bool on = act[nt] != 0;
-            const int cur = (q * NT + nt) & 1;
-            if (USE_GX && q * NT + nt + 1 < MQ * NT) load_gx((q * NT + nt + 1) / NT, (q * NT + nt + 1) % NT, gxv[cur ^ 1]);
+            const int cur = (q * NTV + nt) & 1;
+            if (USE_GX && q * NTV + nt + 1 < MQ * NTV) load_gx((q * NTV + nt + 1) / NTV, (q * NTV + nt + 1) % NTV, gxv[cur ^ 1]);
             v4f cn;
             unsigned codes = 0;
 #pragma unroll
@@ -437,6 +449,9 @@ __global__ __launch_bounds__(256, (USE_GX && !DBG) ? 3 : 2) void lstm_step_pipe_
             }
         }
     }
+    };
+    if (FAST && !DBG && __builtin_amdgcn_readfirstlane(nt_valid) * 2 <= NT) run(std::integral_constant<int, NT / 2>{});
+    else run(std::integral_constant<int, NT>{});
 }
 
 template <int MT, int NT, int S, bool USE_GX, bool TAB, bool DBG, bool FAST>

@@ -66,7 +66,8 @@ __device__ __forceinline__ int qr_pipe_b_row(int wave, int i, int lane)
     return (wave * NT + i) * 8 + (lane >> 3);
 }
 
-template <int MT, int NT, int S, int NPH, bool TAIL, bool W8 = false, class PhaseEnd>
+// NTV: only the wave's first NTV column tiles are contracted (their rows are staged all the same).
+template <int MT, int NT, int S, int NPH, bool TAIL, bool W8 = false, int NTV = NT, class PhaseEnd>
 __device__ __forceinline__ void qr_pipe_mma(const QrPhase<NT> (&ph)[NPH], int n_row_tiles, int block_rt0, char *lds,
                                             v4i (&acc)[MT][NT], PhaseEnd &&on_phase_end)
 {
@@ -169,7 +170,7 @@ __device__ __forceinline__ void qr_pipe_mma(const QrPhase<NT> (&ph)[NPH], int n_
             }
         }
 #pragma unroll
-        for (int nt = 0; nt < NT; ++nt) {
+        for (int nt = 0; nt < NTV; ++nt) {
             b0[nt] = *(const v4i *)(sbb + (wn * NT + nt) * 2048 + p0);
             b1[nt] = *(const v4i *)(sbb + (wn * NT + nt) * 2048 + p1);
         }
@@ -179,7 +180,7 @@ __device__ __forceinline__ void qr_pipe_mma(const QrPhase<NT> (&ph)[NPH], int n_
             if (W8) { lo = pa[mt]; hi = pa_hi[mt]; }
             else qr_unpack(pa[mt], lo, hi);
 #pragma unroll
-            for (int nt = 0; nt < NT; ++nt) {
+            for (int nt = 0; nt < NTV; ++nt) {
                 acc[mt][nt] = qr_mfma(lo, b0[nt], acc[mt][nt]);
                 acc[mt][nt] = qr_mfma(hi, b1[nt], acc[mt][nt]);
             }
