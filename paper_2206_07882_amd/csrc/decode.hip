@@ -337,7 +337,6 @@ extern "C" qrnnt_status qrnnt_decode_ex(const qrnnt_model *m, const float *enc_p
     tb.beam_src = p.beam_src;  tb.N = N;  tb.src_limit = p.NB * N;
     const QrGatherTable no_copy = {};
 
-    const bool use_list = qr_step_list_pays(N);
     QrJointArgs ja = {};
     ja.enc = enc_proj;  ja.n_enc_rows = T * B;  ja.frame_row = nullptr;  ja.rows_per_utt = W;
     ja.w = (const v4i *)m->joint_out.packed;  ja.s_w = m->joint_out.row_scale;  ja.b_out = m->joint_bias;
@@ -384,11 +383,9 @@ extern "C" qrnnt_status qrnnt_decode_ex(const qrnnt_model *m, const float *enc_p
                 ra.live_clear = lo + v + 1;
             }
             // n_rows[t&1][v] = slots that carry a label into round v of this frame, listed in p.rows
-            if (use_list) {
-                ra.rows_next = p.rows;
-                ra.n_rows_next = p.n_rows + (size_t)(t & 1) * (max_sym + 2) + v + 1;
-                ra.n_rows_clear = p.n_rows + (size_t)((t + 1) & 1) * (max_sym + 2) + v + 1;
-            }
+            ra.rows_next = p.rows;
+            ra.n_rows_next = p.n_rows + (size_t)(t & 1) * (max_sym + 2) + v + 1;
+            ra.n_rows_clear = p.n_rows + (size_t)((t + 1) & 1) * (max_sym + 2) + v + 1;
             qr_launch_joint_route(ja, ra, moving ? tb : no_copy, st);
             if (!last) advance_nets(m, p, cur, nxt, n_embed_rows, early ? ra.live_next : nullptr, ra.n_rows_next, st);
         }

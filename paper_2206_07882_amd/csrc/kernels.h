@@ -143,9 +143,6 @@ QR_HIDDEN void qr_fill_lstm_weights(QrStepArgs &a, const qrnnt_lstm *L);
 QR_HIDDEN qrnnt_status qr_check_lstm(const qrnnt_lstm *L);
 QR_HIDDEN void qr_launch_lstm_step(const QrStepArgs &a, bool use_gx, hipStream_t st);
 QR_HIDDEN void qr_launch_lstm_step_group(const QrStepGroup &g, bool use_gx, hipStream_t st);
-// Whether a list of the advancing hypotheses (QrStepGroup.rows) can be expected to pay for the returning atomic
-// that builds it: the weight-streaming kernel drops 16-column blocks, the tiled one 128-column blocks.
-QR_HIDDEN bool qr_step_list_pays(int N);
 QR_HIDDEN void qr_launch_gx_table(const qrnnt_lstm *L, const int32_t *gx, int M, float *tab, hipStream_t st);
 QR_HIDDEN void qr_launch_input_projection(const qrnnt_lstm *L, const int8_t *x_codes, int M, int32_t *gx, int32_t *dbg_accx,
                                           hipStream_t st);

@@ -678,13 +678,6 @@ static void launch_group_t(const QrStepGroup &g, hipStream_t st)
         for (int i = 0; i < g.n; ++i) launch_step_t<USE_GX>(g.p[i], st);
 }
 
-bool qr_step_list_pays(int N)
-{
-    // measured at 64 utterances: beams 2 - 8 (128 - 512 hypotheses) lose 1 - 3 % of the decoder time to the list,
-    // beam 1 gains 40 % and beam 16 up to 6 %
-    return N <= small_n_max() || N >= 1024;
-}
-
 void qr_launch_lstm_step_group(const QrStepGroup &g, bool use_gx, hipStream_t st)
 {
     if (use_gx) launch_group_t<true>(g, st); else launch_group_t<false>(g, st);
