@@ -215,6 +215,7 @@ __global__ __launch_bounds__(256, (USE_GX && !DBG) ? 3 : 2) void lstm_step_pipe_
     int ld_n[NT], ld_s[NT], ld_x[NT], n_of[NT], src_of[NT], gx_of[NT];
     bool n_ok[NT];   // the column stands for a hypothesis (not for padding of the last block)
     int nt_valid = NT;   // this wave's column tiles from here on are padding (list mode)
+    constexpr bool HALF_OK = FAST && !DBG;   // the variants that have a half-width instance
     // With a list the problem has *n_rows rows, row j standing for the hypothesis of entry j.  The 16-column tiles of
     // the block are dealt to the two column halves of the wave grid in turn (logical tile 2*nt + wn sits at the
     // wave column wn, position nt), so that a short list keeps both halves equally busy and the tiles past its end,
@@ -224,21 +225,29 @@ __global__ __launch_bounds__(256, (USE_GX && !DBG) ? 3 : 2) void lstm_step_pipe_
         // The entries are requested before the length of the list is looked at, so the two fetches overlap
         // (columns beyond the end compute on whatever their entry names, clamped into range, and store
         // nothing); an entry brings parent and input row along.
-        v4i el[NT], ef[NT];
-#pragma unroll
-        for (int i = 0; i < NT; ++i) {
-            const int rl = qr_pipe_b_row<NT>(wave, i, lane);   // staged row: tile rl / 16 = wn' * NT + nt' of the block
-            const int jl = n0 + (((rl >> 4) % NT) * 2 + (rl >> 4) / NT) * 16 + (rl & 15), jf = n0 + (i * 2 + wn) * 16 + col;
-            el[i] = rows[jl < N ? jl : N - 1];
-            ef[i] = rows[jf < N ? jf : N - 1];
-        }
-        const int n_cnt = *g.n_rows;
-        if (n0 >= n_cnt) return;   // uniform per block
-        nt_valid = (((n_cnt - n0 + 15) >> 4) + 1) >> 1;   // tiles that hold entries, per wave column (rounded up)
+        // (the rows a thread stages differ between the full and the half-width instance: both sets are requested)
+        v4i el[NT], ef[NT], el_half[NT / 2];
+        auto entry_of_row = [&](int rl) {   // staged row rl of the block: tile rl / 16 = wn' * NT + nt'
+            const int j = n0 + (((rl >> 4) % NT) * 2 + (rl >> 4) / NT) * 16 + (rl & 15);
+            return rows[j < N ? j : N - 1];
+        };
 #pragma unroll
         for (int i = 0; i < NT; ++i) {
             const int jf = n0 + (i * 2 + wn) * 16 + col;
-            const v4i &el_i = el[i], &ef_i = ef[i];
+            el[i] = entry_of_row(qr_pipe_b_row<NT>(wave, i, lane));
+            ef[i] = rows[jf < N ? jf : N - 1];
+        }
+#pragma unroll
+        for (int i = 0; i < NT / 2; ++i) el_half[i] = entry_of_row(qr_pipe_b_row<NT, NT / 2>(wave, i, lane));
+        const int n_cnt = *g.n_rows;
+        if (n0 >= n_cnt) return;   // uniform per block
+        nt_valid = (((n_cnt - n0 + 15) >> 4) + 1) >> 1;   // tiles that hold entries, per wave column (rounded up)
+        const bool half = HALF_OK && nt_valid * 2 <= NT;   // uniform
+#pragma unroll
+        for (int i = 0; i < NT; ++i) {
+            const int jf = n0 + (i * 2 + wn) * 16 + col;
+            const v4i el_i = (half && i < NT / 2) ? el_half[i < NT / 2 ? i : 0] : el[i];
+            const v4i &ef_i = ef[i];
             auto hyp = [&](int r) { return r < 0 ? 0 : (r >= N ? N - 1 : r); };
             ld_n[i] = hyp(el_i[0]);
             ld_s[i] = a.parent ? el_i[1] : ld_n[i];
@@ -450,7 +459,7 @@ __global__ __launch_bounds__(256, (USE_GX && !DBG) ? 3 : 2) void lstm_step_pipe_
         }
     }
     };
-    if (FAST && !DBG && __builtin_amdgcn_readfirstlane(nt_valid) * 2 <= NT) run(std::integral_constant<int, NT / 2>{});
+    if (HALF_OK && __builtin_amdgcn_readfirstlane(nt_valid) * 2 <= NT) run(std::integral_constant<int, NT / 2>{});
     else run(std::integral_constant<int, NT>{});
 }
 

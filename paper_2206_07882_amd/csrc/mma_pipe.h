@@ -59,19 +59,30 @@ __device__ __forceinline__ void qr_wait_vmcnt()
     asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 }
 
-// Which activation row load `i` of this thread's B loads fetches, relative to the block's first row.
-template <int NT>
-__device__ __forceinline__ int qr_pipe_b_row(int wave, int i, int lane)
+// Which 1 KiB activation block (8 rows) load `i` of a wave's B loads stages.  All 4*NT blocks, NT per wave; or, with
+// NTV < NT, only the blocks of the first NTV column tiles of each of the two wave columns, NTV per wave.
+template <int NT, int NTV = NT>
+__device__ __forceinline__ int qr_pipe_b_block(int wave, int i)
 {
-    return (wave * NT + i) * 8 + (lane >> 3);
+    if (NTV == NT) return wave * NT + i;
+    const int k = wave * NTV + i, tv = k >> 1;   // tv: which of the 2 * NTV staged tiles (two blocks each)
+    return 2 * ((tv / NTV) * NT + tv % NTV) + (k & 1);
 }
 
-// NTV: only the wave's first NTV column tiles are contracted (their rows are staged all the same).
+// Which activation row load `i` of this thread's B loads fetches, relative to the block's first row.
+template <int NT, int NTV = NT>
+__device__ __forceinline__ int qr_pipe_b_row(int wave, int i, int lane)
+{
+    return qr_pipe_b_block<NT, NTV>(wave, i) * 8 + (lane >> 3);
+}
+
+// NTV: only the wave's first NTV column tiles are staged (ph[].row[0 .. NTV), see qr_pipe_b_block) and contracted.
 template <int MT, int NT, int S, int NPH, bool TAIL, bool W8 = false, int NTV = NT, class PhaseEnd>
 __device__ __forceinline__ void qr_pipe_mma(const QrPhase<NT> (&ph)[NPH], int n_row_tiles, int block_rt0, char *lds,
                                             v4i (&acc)[MT][NT], PhaseEnd &&on_phase_end)
 {
     using P = QrPipe<MT, NT, S, W8>;
+    constexpr int LOADS = P::A_PER_WAVE + NTV;   // vector-memory loads per thread per chunk
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int grp = lane >> 4, col = lane & 15;
@@ -85,7 +96,7 @@ __device__ __forceinline__ void qr_pipe_mma(const QrPhase<NT> (&ph)[NPH], int n_
     // re-based when the stream crosses from phase 0 to phase 1.
     const int boff = ((lane & 7) ^ (lane >> 3)) * 16;   // this lane's 16-byte piece of a chunk row
     const v4i *cur_a[P::A_PER_WAVE];
-    const int8_t *cur_b[P::B_PER_WAVE];
+    const int8_t *cur_b[NTV];
     int cur_p = 0, cur_kc = 0, cur_nkc = 0, cur_K = 0;
     auto rebase = [&](int p) {
         const QrPhase<NT> &ps = ph[p];
@@ -99,7 +110,7 @@ __device__ __forceinline__ void qr_pipe_mma(const QrPhase<NT> (&ph)[NPH], int n_
             cur_a[a] = W8 ? ps.w + ((size_t)rt * ps.nkc * 2 + (ab & 1)) * 64 + lane : ps.w + (size_t)rt * ps.nkc * 64 + lane;
         }
 #pragma unroll
-        for (int i = 0; i < P::B_PER_WAVE; ++i) cur_b[i] = ps.row[i] + boff;
+        for (int i = 0; i < NTV; ++i) cur_b[i] = ps.row[i] + boff;
     };
     rebase(0);
     // One chunk = LOADS loads per thread; issue_one(q) is load q of the chunk at the head of
@@ -116,7 +127,7 @@ __device__ __forceinline__ void qr_pipe_mma(const QrPhase<NT> (&ph)[NPH], int n_
                 const int k = cur_kc * QRNNT_KCHUNK + boff;
                 if (k >= cur_K) src = cur_b[i] - k;   // row start: any valid bytes do, they meet zero weights
             }
-            qr_load_lds16(src, sbase + (P::A_BLOCKS + wave * NT + i) * 1024);
+            qr_load_lds16(src, sbase + (P::A_BLOCKS + qr_pipe_b_block<NT, NTV>(wave, i)) * 1024);
             cur_b[i] += QRNNT_KCHUNK;
         }
     };
@@ -131,7 +142,7 @@ __device__ __forceinline__ void qr_pipe_mma(const QrPhase<NT> (&ph)[NPH], int n_
         const unsigned sbase = lds_base + stage * P::STAGE_BYTES;
         const bool tail = chunk_tail();
 #pragma unroll
-        for (int q = 0; q < P::LOADS; ++q) issue_one(q, sbase, tail);
+        for (int q = 0; q < LOADS; ++q) issue_one(q, sbase, tail);
         issue_done();
     };
 
@@ -144,8 +155,8 @@ __device__ __forceinline__ void qr_pipe_mma(const QrPhase<NT> (&ph)[NPH], int n_
     for (int c = 0; c < total; ++c) {
         const int after = total - 1 - c;   // chunks after c; min(DIST-1, after) of them are already in flight
         static_assert(P::DIST >= 1 && P::DIST <= 3, "ring depth 2..4");
-        if (P::DIST >= 3 && after >= 2) qr_wait_vmcnt<2 * P::LOADS>();
-        else if (P::DIST >= 2 && after >= 1) qr_wait_vmcnt<P::LOADS>();
+        if (P::DIST >= 3 && after >= 2) qr_wait_vmcnt<2 * LOADS>();
+        else if (P::DIST >= 2 && after >= 1) qr_wait_vmcnt<LOADS>();
         else qr_wait_vmcnt<0>();
         __builtin_amdgcn_s_barrier();
         // The refill of the stage that was read in the previous iteration is issued in
@@ -184,11 +195,11 @@ __device__ __forceinline__ void qr_pipe_mma(const QrPhase<NT> (&ph)[NPH], int n_
                 acc[mt][nt] = qr_mfma(lo, b0[nt], acc[mt][nt]);
                 acc[mt][nt] = qr_mfma(hi, b1[nt], acc[mt][nt]);
             }
-            constexpr int SHARE = (P::LOADS + MT - 1) / MT;
+            constexpr int SHARE = (LOADS + MT - 1) / MT;
             __builtin_amdgcn_sched_barrier(0);
             if (do_issue) {
 #pragma unroll
-                for (int q = mt * SHARE; q < (mt + 1) * SHARE && q < P::LOADS; ++q) issue_one(q, isbase, itail);
+                for (int q = mt * SHARE; q < (mt + 1) * SHARE && q < LOADS; ++q) issue_one(q, isbase, itail);
             }
             __builtin_amdgcn_sched_barrier(0);
         }
