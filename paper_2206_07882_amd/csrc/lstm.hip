@@ -216,38 +216,70 @@ __global__ __launch_bounds__(256, (USE_GX && !DBG) ? 3 : 2) void lstm_step_pipe_
     bool n_ok[NT];   // the column stands for a hypothesis (not for padding of the last block)
     int nt_valid = NT;   // this wave's column tiles from here on are padding (list mode)
     constexpr bool HALF_OK = FAST && !DBG;   // the variants that have a half-width instance
-    // With a list the problem has *n_rows rows, row j standing for the hypothesis of entry j.  The 16-column tiles of
-    // the block are dealt to the two column halves of the wave grid in turn (logical tile 2*nt + wn sits at the
-    // wave column wn, position nt), so that a short list keeps both halves equally busy and the tiles past its end,
-    // the same number in every wave, need not be computed.
+    // With a list the problem has *n_rows rows, row j standing for the hypothesis of entry j.
+    //  * A workgroup takes 32*NT, 16*NT or 8*NT consecutive entries (width 0, 1, 2): the narrowest width at which the
+    //    launch's column blocks still cover the list and the working workgroups do not outnumber the compute units
+    //    (beyond that, narrower only means fetching the weights more often), so that a short list is spread over
+    //    more workgroups, each of which then runs the half- or quarter-width instance of the body below.
+    //  * The 16-column tiles of a workgroup's entries are dealt to the two column halves of the wave grid in turn
+    //    (logical tile 2*nt + wn sits at wave column wn, position nt), so that every wave holds the same number of
+    //    live tiles; a workgroup at full width whose share of the list ends within its first half runs the
+    //    half-width instance as well.
     const v4i *rows = g.rows;
+    int width = 0;   // log2 of (full width / entries per workgroup)
     if (rows) {
         // The entries are requested before the length of the list is looked at, so the two fetches overlap
         // (columns beyond the end compute on whatever their entry names, clamped into range, and store
-        // nothing); an entry brings parent and input row along.
-        // (the rows a thread stages differ between the full and the half-width instance: both sets are requested)
-        v4i el[NT], ef[NT], el_half[NT / 2];
-        auto entry_of_row = [&](int rl) {   // staged row rl of the block: tile rl / 16 = wn' * NT + nt'
-            const int j = n0 + (((rl >> 4) % NT) * 2 + (rl >> 4) / NT) * 16 + (rl & 15);
-            return rows[j < N ? j : N - 1];
-        };
+        // nothing); an entry brings parent and input row along.  Which entries a thread stages and finishes
+        // depends on the width and on the instance: every set is requested.
+        auto entry = [&](int j) { return rows[j < N ? j : N - 1]; };
+        // staged row rl of a workgroup's range: tile rl / 16 = wn' * NT + nt' -> logical tile 2 * nt' + wn'
+        auto logical = [](int rl) { return (((rl >> 4) % NT) * 2 + (rl >> 4) / NT) * 16 + (rl & 15); };
+        const int n0h = blockIdx.y * (P::BN / 2), n0q = blockIdx.y * (P::BN / 4);
+        v4i el[NT], ef[NT], el_half[NT / 2], el_h[NT / 2], ef_h[NT / 2], el_q[NT / 4], ef_q[NT / 4];
 #pragma unroll
         for (int i = 0; i < NT; ++i) {
-            const int jf = n0 + (i * 2 + wn) * 16 + col;
-            el[i] = entry_of_row(qr_pipe_b_row<NT>(wave, i, lane));
-            ef[i] = rows[jf < N ? jf : N - 1];
+            el[i] = entry(n0 + logical(qr_pipe_b_row<NT>(wave, i, lane)));
+            ef[i] = entry(n0 + (i * 2 + wn) * 16 + col);
         }
 #pragma unroll
-        for (int i = 0; i < NT / 2; ++i) el_half[i] = entry_of_row(qr_pipe_b_row<NT, NT / 2>(wave, i, lane));
+        for (int i = 0; i < NT / 2; ++i) {
+            el_half[i] = entry(n0 + logical(qr_pipe_b_row<NT, NT / 2>(wave, i, lane)));
+            if (HALF_OK) {
+                el_h[i] = entry(n0h + logical(qr_pipe_b_row<NT, NT / 2>(wave, i, lane)));
+                ef_h[i] = entry(n0h + (i * 2 + wn) * 16 + col);
+            }
+        }
+        if (HALF_OK) {
+#pragma unroll
+            for (int i = 0; i < NT / 4; ++i) {
+                el_q[i] = entry(n0q + logical(qr_pipe_b_row<NT, NT / 4>(wave, i, lane)));
+                ef_q[i] = entry(n0q + (i * 2 + wn) * 16 + col);
+            }
+        }
         const int n_cnt = *g.n_rows;
-        if (n0 >= n_cnt) return;   // uniform per block
-        nt_valid = (((n_cnt - n0 + 15) >> 4) + 1) >> 1;   // tiles that hold entries, per wave column (rounded up)
-        const bool half = HALF_OK && nt_valid * 2 <= NT;   // uniform
+        if (HALF_OK) {   // uniform: the narrowest width that covers the list and does not ask for more workgroups than CUs
+#pragma unroll
+            for (int w = 1; w <= 2; ++w) {
+                const int per = P::BN >> w;
+                if (per * (int)gridDim.y >= n_cnt && g.row_blocks * ((n_cnt + per - 1) / per) <= g.n_cu) width = w;
+            }
+        }
+        const int n0w = width == 2 ? n0q : (width == 1 ? n0h : n0);
+        if (n0w >= n_cnt) return;   // uniform per block
+        nt_valid = NT >> width;
+        if (width == 0) {   // tiles that hold entries, per wave column (rounded up); at this width no instance below the half
+            nt_valid = (((n_cnt - n0 + 15) >> 4) + 1) >> 1;
+            nt_valid = nt_valid < NT / 2 ? NT / 2 : nt_valid;
+        }
+        const bool half = HALF_OK && width == 0 && nt_valid * 2 <= NT;   // uniform
 #pragma unroll
         for (int i = 0; i < NT; ++i) {
-            const int jf = n0 + (i * 2 + wn) * 16 + col;
-            const v4i el_i = (half && i < NT / 2) ? el_half[i < NT / 2 ? i : 0] : el[i];
-            const v4i &ef_i = ef[i];
+            const int jf = n0w + (i * 2 + wn) * 16 + col;
+            const int ih = i < NT / 2 ? i : 0, iq = i < NT / 4 ? i : 0;   // (entries past an instance's tiles are not used)
+            v4i el_i = half ? el_half[ih] : el[i], ef_i = ef[i];
+            if (HALF_OK && width == 1) { el_i = el_h[ih]; ef_i = ef_h[ih]; }
+            if (HALF_OK && width == 2) { el_i = el_q[iq]; ef_i = ef_q[iq]; }
             auto hyp = [&](int r) { return r < 0 ? 0 : (r >= N ? N - 1 : r); };
             ld_n[i] = hyp(el_i[0]);
             ld_s[i] = a.parent ? el_i[1] : ld_n[i];
@@ -311,8 +343,8 @@ __global__ __launch_bounds__(256, (USE_GX && !DBG) ? 3 : 2) void lstm_step_pipe_
     if (!USE_GX) { ph[0].w = a.wih;  ph[0].nkc = a.nkc_x;  ph[0].K = a.I; }
     ph[NPH - 1].w = a.whh;  ph[NPH - 1].nkc = a.nkc_h;  ph[NPH - 1].K = H;
 
-    // Everything from here on exists twice: for all NT column tiles of the wave, and for its first NT / 2 only
-    // (a list that ends in the first half of the block).
+    // Everything from here on exists three times: for all NT column tiles of the wave, for its first NT / 2 and for
+    // its first NT / 4 only.
     auto run = [&](auto ntv_tag) {
     constexpr int NTV = decltype(ntv_tag)::value;
     v4i acc[MT][NT];
@@ -459,7 +491,9 @@ __global__ __launch_bounds__(256, (USE_GX && !DBG) ? 3 : 2) void lstm_step_pipe_
         }
     }
     };
-    if (HALF_OK && __builtin_amdgcn_readfirstlane(nt_valid) * 2 <= NT) run(std::integral_constant<int, NT / 2>{});
+    nt_valid = __builtin_amdgcn_readfirstlane(nt_valid);
+    if (HALF_OK && nt_valid * 4 <= NT) run(std::integral_constant<int, NT / 4>{});
+    else if (HALF_OK && nt_valid * 2 <= NT) run(std::integral_constant<int, NT / 2>{});
     else run(std::integral_constant<int, NT>{});
 }
 
@@ -473,13 +507,24 @@ void launch_pipe_f(const QrStepGroup &g, hipStream_t st)
         (void)hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, P::LDS_BYTES);
         configured = true;
     }
+    static int n_cu = 0;
+    if (n_cu == 0) {
+        int dev = 0;
+        if (hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
+            n_cu = 1;
+    }
+    QrStepGroup gg = g;
     int gx = 0, gy = 0;
+    gg.row_blocks = 0;
+    gg.n_cu = n_cu;
     for (int i = 0; i < g.n; ++i) {
         const int rb = ((g.p[i].H >> 2) + 2 * MT - 1) / (2 * MT), nb = (g.p[i].N + P::BN - 1) / P::BN;
         gx = rb > gx ? rb : gx;
         gy = nb > gy ? nb : gy;
+        gg.row_blocks += rb;
     }
-    kern<<<dim3(gx, gy, g.n), 256, P::LDS_BYTES, st>>>(g);
+    kern<<<dim3(gx, gy, g.n), 256, P::LDS_BYTES, st>>>(gg);
 }
 
 template <int MT, int NT, int S, bool USE_GX>
