@@ -196,6 +196,25 @@ typedef struct {
 
 qrnnt_status qrnnt_lstm_step_group(const qrnnt_step_desc *steps, int32_t n_steps, void *stream);
 
+/* The same launch restricted to a list of hypotheses (Sec. 2: in a round of the
+ * beam search only the hypotheses that were extended by a label advance the
+ * prediction network and the LMs).
+ * list [device] int32 [>= N][4], 16-byte aligned: entry j = (n, slot of n's
+ *   previous state, input row of n, unused) for the j-th hypothesis to advance,
+ *   i.e. n together with the values the step would read from parent[n] and
+ *   x_row[n].  Those two arrays are not read; whether a descriptor has them
+ *   (non-NULL) still says whether the entry's second / third word is used or n
+ *   itself.  Values are clamped like parent and x_row.
+ * n_list [device]: the number of entries, read by the kernel, so that a kernel
+ *   earlier on the stream can write list and count without a host round trip.
+ *   Entries at or beyond *n_list may hold anything: they may be read, are
+ *   clamped into range and nothing is stored for them.  *n_list <= N.
+ * Rows of h_next / c_next of hypotheses that are not listed are left untouched
+ * (active[] still applies to the listed ones).  All steps of the group share N,
+ * and all of them or none have parent, likewise x_row. */
+qrnnt_status qrnnt_lstm_step_group_listed(const qrnnt_step_desc *steps, int32_t n_steps, const int32_t *list,
+                                          const int32_t *n_list, void *stream);
+
 /* ---- LSTM: one layer-direction over whole utterances (Sec. 2 encoder, Sec. 3.4) ---- */
 
 size_t qrnnt_lstm_layer_workspace(const qrnnt_lstm *L, int32_t T, int32_t B);

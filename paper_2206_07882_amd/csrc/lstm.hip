@@ -776,13 +776,23 @@ extern "C" qrnnt_status qrnnt_lstm_step(const qrnnt_lstm *L, const int8_t *x_cod
     return qr_launch_status();
 }
 
-extern "C" qrnnt_status qrnnt_lstm_step_group(const qrnnt_step_desc *steps, int32_t n_steps, void *stream)
+namespace {
+
+qrnnt_status step_group(const qrnnt_step_desc *steps, int32_t n_steps, const int32_t *list, const int32_t *n_list,
+                        void *stream)
 {
     QR_REQUIRE(steps != nullptr, QRNNT_ERR_NULL);
     QR_REQUIRE(n_steps >= 1 && n_steps <= QR_MAX_GROUP, QRNNT_ERR_RANGE);
     QrStepGroup g;
     g.n = n_steps;
     g.gate = nullptr;
+    g.rows = (const v4i *)list;
+    g.n_rows = n_list;
+    if (list)   // one list serves all members: same number of hypotheses, same use of parent and x_row
+        for (int i = 1; i < n_steps; ++i)
+            QR_REQUIRE(steps[i].N == steps[0].N && (steps[i].parent != nullptr) == (steps[0].parent != nullptr) &&
+                           (steps[i].x_row != nullptr) == (steps[0].x_row != nullptr),
+                       QRNNT_ERR_RANGE);
     for (int i = 0; i < n_steps; ++i) {
         const qrnnt_step_desc &d = steps[i];
         qrnnt_status s = make_step_args(g.p[i], d.L, d.x_codes, d.x_row, d.n_x_rows, d.parent, d.h_prev, d.c_prev,
@@ -796,6 +806,21 @@ extern "C" qrnnt_status qrnnt_lstm_step_group(const qrnnt_step_desc *steps, int3
     }
     qr_launch_lstm_step_group(g, steps[0].gx != nullptr, (hipStream_t)stream);
     return qr_launch_status();
+}
+
+}  // namespace
+
+extern "C" qrnnt_status qrnnt_lstm_step_group(const qrnnt_step_desc *steps, int32_t n_steps, void *stream)
+{
+    return step_group(steps, n_steps, nullptr, nullptr, stream);
+}
+
+extern "C" qrnnt_status qrnnt_lstm_step_group_listed(const qrnnt_step_desc *steps, int32_t n_steps, const int32_t *list,
+                                                     const int32_t *n_list, void *stream)
+{
+    QR_REQUIRE(list != nullptr && n_list != nullptr, QRNNT_ERR_NULL);
+    QR_REQUIRE(qr_aligned(list, 16) && qr_aligned(n_list, 4), QRNNT_ERR_ALIGN);
+    return step_group(steps, n_steps, list, n_list, stream);
 }
 
 void qr_launch_input_projection(const qrnnt_lstm *L, const int8_t *x_codes, int M, int32_t *gx, int32_t *dbg_accx,

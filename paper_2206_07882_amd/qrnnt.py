@@ -60,7 +60,7 @@ class CModel(C.Structure):
 EXPORTS = ["qrnnt_status_str", "qrnnt_abi_version", "qrnnt_pack_int4_bytes", "qrnnt_pack_int4", "qrnnt_unpack_int4",
            "qrnnt_pack_int8_bytes", "qrnnt_pack_int8", "qrnnt_quantize_act8",
            "qrnnt_quantize_act", "qrnnt_linear", "qrnnt_linear_quant", "qrnnt_lstm_step", "qrnnt_lstm_layer_workspace", "qrnnt_lstm_layer",
-           "qrnnt_input_projection", "qrnnt_input_table", "qrnnt_lstm_step_group",
+           "qrnnt_input_projection", "qrnnt_input_table", "qrnnt_lstm_step_group", "qrnnt_lstm_step_group_listed",
            "qrnnt_bilstm_layer_workspace", "qrnnt_bilstm_layer",
            "qrnnt_joint_fuse", "qrnnt_beam_step", "qrnnt_decode_workspace", "qrnnt_decode", "qrnnt_decode_ex",
            "qrnnt_decode_alsd_workspace", "qrnnt_decode_alsd"]
@@ -280,8 +280,15 @@ class StepGroup:
                                     p(d.get("active")), d["N"], p(d["h_next"]), p(d["c_next"]), p(d.get("gx")),
                                     p(d.get("gx_table")))
 
-    def launch(self):
-        _check(load().qrnnt_lstm_step_group(self.arr, C.c_int32(self.n), _stream()), "qrnnt_lstm_step_group")
+    def launch(self, list=None, n_list=None):
+        """list [>= N, 4] int32 and n_list [1] int32 (device): only the listed hypotheses advance
+        (qrnnt_lstm_step_group_listed)."""
+        if list is None:
+            _check(load().qrnnt_lstm_step_group(self.arr, C.c_int32(self.n), _stream()), "qrnnt_lstm_step_group")
+        else:
+            _check(load().qrnnt_lstm_step_group_listed(self.arr, C.c_int32(self.n), _ptr(list, torch.int32),
+                                                       _ptr(n_list, torch.int32), _stream()),
+                   "qrnnt_lstm_step_group_listed")
 
 
 def input_projection(L: Lstm, x_codes: torch.Tensor, gx: Optional[torch.Tensor] = None, debug: bool = False):

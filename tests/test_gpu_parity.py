@@ -335,6 +335,72 @@ def test_lstm_step_group_full_size_sampled(gpu_lib):
             assert np.array_equal(host(d["h_next"])[rows][~act], hn_r[~act])
 
 
+@pytest.mark.parametrize("N,n_list", [(1024, 0), (1024, 1), (1024, 33), (1024, 64), (1024, 65), (1024, 100), (1024, 128),
+                                      (1024, 129), (1024, 250), (1024, 300), (1024, 512), (1024, 700), (1024, 960),
+                                      (1024, 1024), (512, 64), (256, 40), (144, 70), (128, 64), (128, 20), (48, 17)])
+def test_lstm_step_group_listed(gpu_lib, N, n_list):
+    """qrnnt_lstm_step_group_listed at the shapes of a decoding round (first layers from the per-token table, then
+    the LMs' second layers): the listed hypotheses, in a seeded random order, must get the oracle's step (sampled),
+    every other row of the outputs must keep what it held.  The list lengths walk through the kernel's ways of
+    splitting a list over workgroups (32, 64 or 128 entries each) and their ragged ends; entries beyond the count
+    hold out-of-range values, which must be harmless."""
+    q = gpu_lib
+    V, W = 46, 16
+    s_x = float(np.float32(1.25) / np.float32(7))
+    rng = np.random.default_rng(7000 + 7 * N + n_list)
+    parent = synth.parent_perm(280 + N, N // W, W)
+    tok = synth.token_ids(281 + N, (N,), V)
+    active = (rng.random(N) < 0.9).astype(np.uint8)
+    listed = rng.permutation(N)[:n_list].astype(np.int32)
+    lst = np.empty((N, 4), np.int32)
+    lst[:, 0] = rng.choice([-5, N, N + 1000, 2 ** 30], N)      # what follows the end of the list: out of range
+    lst[:, 1] = rng.choice([-1, N, 2 ** 30], N)
+    lst[:, 2] = rng.choice([-7, V, 2 ** 29], N)
+    lst[:, 3] = 0
+    lst[:n_list, 0] = listed
+    lst[:n_list, 1] = parent[listed]
+    lst[:n_list, 2] = tok[listed]
+    cnt = dev(np.array([n_list], np.int32))
+    rows = listed[:32]
+    act = active[rows].astype(bool)
+    unlisted = np.setdiff1d(np.arange(N), listed)
+    for shapes, table in (([(768, 768), (256, 1024), (256, 1024)], True), ([(1024, 1024), (1024, 1024)], False)):
+        steps, refs = [], []
+        for i, (I, H) in enumerate(shapes):
+            L, G = _lstm_pair(q, 290 + 10 * i + I, I, H, s_x if table else S_H)
+            hp = synth.codes(292 + i, (N, H), -7, 7)
+            cp = synth.normal(293 + i, (N, H), 0.7)
+            d = dict(L=G, parent=dev(parent), active=dev(active), h_prev=dev(hp), c_prev=dev(cp), N=N,
+                     h_next=torch.full((N, H), 5, dtype=torch.int8, device=DEV),
+                     c_next=torch.full((N, H), 123.0, dtype=torch.float32, device=DEV))
+            if table:
+                emb = synth.codes(291 + i, (V, I), -7, 7)
+                gx = q.input_projection(G, dev(emb))[0]
+                d.update(x_codes=dev(emb), x_row=dev(tok), gx=gx, gx_table=q.input_table(G, gx))
+                x_rows = emb[tok[rows]]
+                l_dev = dev(lst)
+            else:                      # no x_row: the entry's third word must not be used
+                x = synth.codes(294 + i, (N, I), -7, 7)
+                d.update(x_codes=dev(x))
+                x_rows = x[rows]
+                l_dev = dev(lst)
+            steps.append(d)
+            refs.append(oracle.lstm_step(L, x_rows, hp[parent[rows]], cp[parent[rows]], active=active[rows], debug=True)
+                        if n_list else None)
+        q.StepGroup(steps).launch(list=l_dev, n_list=cnt)
+        for d, ref in zip(steps, refs):
+            hn, cn = host(d["h_next"]), host(d["c_next"])
+            assert np.all(hn[unlisted] == 5) and np.all(cn[unlisted] == 123.0), "a row outside the list was written"
+            if ref is None:
+                continue
+            hn_r, cn_r, dbg_r = ref
+            assert_rel(cn[rows], cn_r, "c")
+            assert_codes_close(hn[rows][act], hn_r[act], (dbg_r["h_real"] * 7.0)[act], "h codes")
+            assert np.array_equal(hn[rows][~act], hn_r[~act])
+            if n_list > 32:            # the rest of the list: written (no sentinel left in c)
+                assert not np.any(cn[listed[32:]] == 123.0)
+
+
 def test_lstm_step_extreme_codes_no_overflow(gpu_lib):
     """All weights at code 7/-7 against all activations at -8: the largest |sum|."""
     q = gpu_lib
