@@ -38,8 +38,9 @@ struct QrStepGroup {
     // the list adds no link to its chain of dependent loads.  Entries beyond the end may hold anything.
     const v4i *rows = nullptr;
     const int32_t *n_rows = nullptr;
-    // filled in by the launcher of the tiled kernel: row blocks of all members together, compute units of the device
-    int row_blocks = 0, n_cu = 0;
+    // filled in by the launcher of the tiled kernel: row blocks of all members together, compute units of the device,
+    // and (launches without a list) log2 of how many times narrower than the full column block a workgroup's share is
+    int row_blocks = 0, n_cu = 0, width = 0;
 };
 
 struct QrLinearArgs {

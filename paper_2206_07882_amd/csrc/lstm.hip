@@ -204,7 +204,7 @@ __global__ __launch_bounds__(256, (USE_GX && !DBG) ? 3 : 2) void lstm_step_pipe_
     const int n_row_tiles = H >> 2;
     const int block_rt0 = blockIdx.x * 2 * MT;
     const int n0 = blockIdx.y * P::BN;
-    if (block_rt0 >= n_row_tiles || n0 >= N) return;   // uniform per block
+    if (block_rt0 >= n_row_tiles) return;   // uniform per block
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int col = lane & 15, grp = lane >> 4;
@@ -293,11 +293,21 @@ __global__ __launch_bounds__(256, (USE_GX && !DBG) ? 3 : 2) void lstm_step_pipe_
             }
         }
     } else {
+        // Without a list the launcher has chosen the width from N by the same rule (g.width); at full width the
+        // columns keep their natural order.
+        width = HALF_OK ? g.width : 0;   // uniform
+        const int n0w = blockIdx.y * (P::BN >> width);
+        if (n0w >= N) return;   // uniform per block
+        nt_valid = NT >> width;
+        auto logical = [](int rl) { return (((rl >> 4) % NT) * 2 + (rl >> 4) / NT) * 16 + (rl & 15); };
 #pragma unroll
         for (int i = 0; i < NT; ++i) {
-            const int n = n0 + qr_pipe_b_row<NT>(wave, i, lane);
+            int n = qr_pipe_b_row<NT>(wave, i, lane), m = (wn * NT + i) * 16 + col;
+            if (HALF_OK && width == 1) { n = logical(qr_pipe_b_row<NT, NT / 2>(wave, i < NT / 2 ? i : 0, lane)); m = (i * 2 + wn) * 16 + col; }
+            if (HALF_OK && width == 2) { n = logical(qr_pipe_b_row<NT, NT / 4>(wave, i < NT / 4 ? i : 0, lane)); m = (i * 2 + wn) * 16 + col; }
+            n += n0w;
+            m += n0w;
             ld_n[i] = n < N ? n : N - 1;
-            const int m = n0 + (wn * NT + i) * 16 + col;
             n_of[i] = m;
             n_ok[i] = m < N;
             src_of[i] = m < N ? m : N - 1;
@@ -515,16 +525,23 @@ void launch_pipe_f(const QrStepGroup &g, hipStream_t st)
             n_cu = 1;
     }
     QrStepGroup gg = g;
-    int gx = 0, gy = 0;
+    int gx = 0, max_n = 0;
     gg.row_blocks = 0;
     gg.n_cu = n_cu;
     for (int i = 0; i < g.n; ++i) {
-        const int rb = ((g.p[i].H >> 2) + 2 * MT - 1) / (2 * MT), nb = (g.p[i].N + P::BN - 1) / P::BN;
+        const int rb = ((g.p[i].H >> 2) + 2 * MT - 1) / (2 * MT);
         gx = rb > gx ? rb : gx;
-        gy = nb > gy ? nb : gy;
+        max_n = g.p[i].N > max_n ? g.p[i].N : max_n;
         gg.row_blocks += rb;
     }
-    kern<<<dim3(gx, gy, g.n), 256, P::LDS_BYTES, st>>>(gg);
+    // Without a list the width is chosen here, by the rule the kernel applies to a list's length: the narrowest
+    // share per workgroup at which the working workgroups do not outnumber the compute units.
+    gg.width = 0;
+    if (FAST && !DBG && !g.rows)
+        for (int w = 1; w <= 2; ++w)
+            if (gg.row_blocks * ((max_n + (P::BN >> w) - 1) / (P::BN >> w)) <= n_cu) gg.width = w;
+    const int per = P::BN >> gg.width;
+    kern<<<dim3(gx, (max_n + per - 1) / per, g.n), 256, P::LDS_BYTES, st>>>(gg);
 }
 
 template <int MT, int NT, int S, bool USE_GX>
