@@ -215,7 +215,7 @@ __global__ __launch_bounds__(256, (USE_GX && !DBG) ? 3 : 2) void lstm_step_pipe_
     int ld_n[NT], ld_s[NT], ld_x[NT], n_of[NT], src_of[NT], gx_of[NT];
     bool n_ok[NT];   // the column stands for a hypothesis (not for padding of the last block)
     int nt_valid = NT;   // this wave's column tiles from here on are padding (list mode)
-    constexpr bool HALF_OK = FAST && !DBG;   // the variants that have a half-width instance
+    constexpr bool HALF_OK = !DBG;   // the variants that have the narrower instances
     // With a list the problem has *n_rows rows, row j standing for the hypothesis of entry j.
     //  * A workgroup takes 32*NT, 16*NT or 8*NT consecutive entries (width 0, 1, 2): the narrowest width at which the
     //    launch's column blocks still cover the list and the working workgroups do not outnumber the compute units
@@ -537,7 +537,7 @@ void launch_pipe_f(const QrStepGroup &g, hipStream_t st)
     // Without a list the width is chosen here, by the rule the kernel applies to a list's length: the narrowest
     // share per workgroup at which the working workgroups do not outnumber the compute units.
     gg.width = 0;
-    if (FAST && !DBG && !g.rows)
+    if (!DBG && !g.rows)
         for (int w = 1; w <= 2; ++w)
             if (gg.row_blocks * ((max_n + (P::BN >> w) - 1) / (P::BN >> w)) <= n_cu) gg.width = w;
     const int per = P::BN >> gg.width;
@@ -566,7 +566,7 @@ void launch_pipe(const QrStepGroup &g, hipStream_t st)
 // Hypothesis counts up to this go to the weight-streaming kernel.
 static int small_n_max()
 {
-    return 64;   // measured: 64 hypotheses take 21 us per decoding round here, 27 us in the tiled kernel
+    return 32;   // measured per decoding round: 64 hypotheses 21.4 us here, 19.1 us in the tiled kernel at 32 per workgroup
 }
 
 template <bool USE_GX>
