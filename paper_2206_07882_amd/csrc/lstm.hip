@@ -180,8 +180,10 @@ void launch_small(const QrStepGroup &g, hipStream_t st)
 }
 
 // Compute-bound variant (many hypotheses): multi-stage LDS ring, see mma_pipe.h.
-// Grid: x = blocks of 32*MT gate rows (8*MT cells), y = blocks of 32*NT hypotheses,
-// z = problem of a group (independent layer-steps batched into one launch).
+// Grid: x = blocks of 32*MT gate rows (8*MT cells), y = blocks of 32*NT hypotheses (or of a half or a
+// quarter of that: few hypotheses are spread over more workgroups, which then run a narrower instance
+// of the kernel's body, see the index section below), z = problem of a group (independent layer-steps
+// batched into one launch).
 // Every global load outside the ring is issued in a batch ahead of its first use
 // and the cell update is branch-free, so a block exposes one memory latency per
 // batch instead of one per element.  DBG adds the int32 / gate outputs.
