@@ -337,7 +337,8 @@ def test_lstm_step_group_full_size_sampled(gpu_lib):
 
 @pytest.mark.parametrize("N,n_list", [(1024, 0), (1024, 1), (1024, 33), (1024, 64), (1024, 65), (1024, 100), (1024, 128),
                                       (1024, 129), (1024, 250), (1024, 300), (1024, 512), (1024, 700), (1024, 960),
-                                      (1024, 1024), (512, 64), (256, 40), (144, 70), (128, 64), (128, 20), (48, 17)])
+                                      (1024, 1024), (512, 64), (256, 40), (144, 70), (128, 64), (128, 20), (48, 17),
+                                      (32, 10), (16, 16), (16, 5)])
 def test_lstm_step_group_listed(gpu_lib, N, n_list):
     """qrnnt_lstm_step_group_listed at the shapes of a decoding round (first layers from the per-token table, then
     the LMs' second layers): the listed hypotheses, in a seeded random order, must get the oracle's step (sampled),
