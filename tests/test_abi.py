@@ -119,6 +119,22 @@ def test_validation_of_the_8bit_and_search_entry_points():
     lq = lambda bits, q=P(0x2000): (C.byref(w), None, C.c_float(0.1), P(0x1000), 4, C.c_float(7.0), bits, q, None)
     assert lib.qrnnt_linear_quant(*lq(6)) == 4
     assert lib.qrnnt_linear_quant(*lq(4, None)) == 1
+    # listed step group: list and count are required and aligned; one list serves steps of equal N that agree
+    # on the use of parent and x_row
+    good = _lstm(w_ih=_qmat(rows=64, cols=64), w_hh=_qmat(rows=64, cols=16))
+    def desc(N=8, parent=0x6000, x_row=0x7000):
+        return qrnnt.CStepDesc(C.addressof(good), 0x1000, x_row, 46, parent, 0x2000, 0x4000, N, None, N, 0x3000, 0x5000,
+                               None, None)
+    two = lambda a, b: (qrnnt.CStepDesc * 2)(a, b)
+    listed = lambda arr, lst=P(0x8000), cnt=P(0x9000): lib.qrnnt_lstm_step_group_listed(arr, 2, lst, cnt, None)
+    assert listed(two(desc(), desc()), lst=None) == 1
+    assert listed(two(desc(), desc()), cnt=None) == 1
+    assert listed(two(desc(), desc()), lst=P(0x8008)) == 3
+    assert listed(two(desc(), desc(N=16))) == 4
+    assert listed(two(desc(), desc(parent=None))) == 4
+    assert listed(two(desc(), desc(x_row=None))) == 4
+    assert lib.qrnnt_lstm_step_group_listed(None, 2, P(0x8000), P(0x9000), None) == 1
+    assert lib.qrnnt_lstm_step_group_listed(two(desc(), desc()), 4, P(0x8000), P(0x9000), None) == 4
     # searches: a NULL model or impossible sizes give a zero workspace
     assert lib.qrnnt_decode_alsd_workspace(None, 10, 2, 4, 5) == 0
     assert lib.qrnnt_decode_workspace(None, 10, 2, 4, 2) == 0
