@@ -199,6 +199,31 @@ def test_decode_benchmark_shape_sampled_utterances(gpu_lib, blank_bias):
         _compare_beams((torch.from_numpy(tok_g[b:b + 1]), torch.from_numpy(len_g[b:b + 1]), torch.from_numpy(sc_g[b:b + 1])), ref)
 
 
+@pytest.mark.parametrize("B,W,max_sym,blank_bias", [(70, 17, 3, 0.0), (64, 16, 4, 2.0), (64, 64, 2, 1.0), (24, 7, 4, 4.0),
+                                                    (8, 33, 1, 0.0)])
+def test_decode_utterance_alone_equals_batched(gpu_lib, B, W, max_sym, blank_bias):
+    """Utterances do not interact (Sec. 2: the search is per utterance), so an utterance decoded alone must give,
+    bit for bit, the rows it gives inside a batch.  The two runs go through different kernels (few hypotheses: the
+    weight-streaming step kernel or narrow instances of the tiled one; many: full-width tiles, longer lists), so
+    this holds only if all of those compute the same step; and one of the sampled utterances is checked against
+    the oracle, so that "the same" is also "right"."""
+    from paper_2206_07882_amd import model as gmodel
+    m = synth.make_model(0, weight_std=0.5)
+    m.joint_out.bias = m.joint_out.bias.copy()
+    m.joint_out.bias[0] += np.float32(blank_bias)   # blank is token 0
+    T = 6
+    e = synth.normal(230 + B + W, (T, B, m.J), 1.0)
+    G = gmodel.model_from_float(m, DEV)
+    for flags in (0, gpu_lib.DECODE_EARLY_STOP):
+        batched = [host(x) for x in gpu_lib.decode(G, dev(e), W, max_sym, flags=flags)]
+        for b in sorted({0, B // 3, B - 1}):
+            alone = [host(x) for x in gpu_lib.decode(G, dev(e[:, b:b + 1]), W, max_sym, flags=flags)]
+            for x, y in zip(alone, batched):
+                assert np.array_equal(x[0], y[b]), (b, flags)
+    ref = oracle.decode(omodels.model_from_float(m), np.ascontiguousarray(e[:, :1]), W, max_sym)
+    _compare_beams(tuple(torch.from_numpy(x[:1]) for x in batched), ref)
+
+
 @pytest.mark.parametrize("blank_bias", [0.0, 6.0])
 def test_decode_early_stop_gives_the_same_beams(gpu_lib, blank_bias):
     """With the early-stop flag the kernels of a round return at once when no utterance carried a label
