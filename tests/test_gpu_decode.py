@@ -299,6 +299,22 @@ def test_alsd_full_width_networks(gpu_lib):
             _compare_beams(got, ref)
 
 
+@pytest.mark.parametrize("B,W,u_max", [(64, 16, 6), (70, 17, 4), (8, 33, 5)])
+def test_alsd_utterance_alone_equals_batched(gpu_lib, B, W, u_max):
+    """The same independence for the alignment-length synchronous search: alone (few hypotheses, other kernels)
+    and inside a batch an utterance must give the same bits."""
+    from paper_2206_07882_amd import model as gmodel
+    m = synth.make_model(0, weight_std=0.5)
+    T = 5
+    e = synth.normal(260 + B + W, (T, B, m.J), 1.0)
+    G = gmodel.model_from_float(m, DEV)
+    batched = [host(x) for x in gpu_lib.decode_alsd(G, dev(e), W, u_max)]
+    for b in sorted({0, B // 3, B - 1}):
+        alone = [host(x) for x in gpu_lib.decode_alsd(G, dev(e[:, b:b + 1]), W, u_max)]
+        for x, y in zip(alone, batched):
+            assert np.array_equal(x[0], y[b]), b
+
+
 @pytest.mark.parametrize("std", [0.1, 0.6])
 def test_alsd_config0_end_to_end_matches_golden(gpu_lib, std):
     """Encoder + alignment-length synchronous search on the tiny configuration against the oracle and against the
