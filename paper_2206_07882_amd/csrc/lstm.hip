@@ -180,9 +180,9 @@ void launch_small(const QrStepGroup &g, hipStream_t st)
 }
 
 // Compute-bound variant (many hypotheses): multi-stage LDS ring, see mma_pipe.h.
-// Grid: x = blocks of 32*MT gate rows (8*MT cells), y = blocks of 32*NT hypotheses (or of a half or a
+// Grid: x = blocks of 32*MT gate rows (8*MT cells), z = blocks of 32*NT hypotheses (or of a half or a
 // quarter of that: few hypotheses are spread over more workgroups, which then run a narrower instance
-// of the kernel's body, see the index section below), z = problem of a group (independent layer-steps
+// of the kernel's body, see the index section below), y = problem of a group (independent layer-steps
 // batched into one launch).
 // Every global load outside the ring is issued in a batch ahead of its first use
 // and the cell update is branch-free, so a block exposes one memory latency per
@@ -201,11 +201,14 @@ __global__ __launch_bounds__(256, (USE_GX && !DBG) ? 3 : 2) void lstm_step_pipe_
     using P = QrPipe<MT, NT, S>;
     extern __shared__ __attribute__((aligned(1024))) char lds[];
     if (g.gate && *g.gate == 0) return;   // uniform: a decoding round without any live hypothesis
-    const QrStepArgs &a = g.p[blockIdx.z];
+    // The column block is the slowest grid dimension: the workgroups of a short list's few column blocks are then
+    // the first to be dispatched, and those that only look at the count and return follow behind them.
+    const int col_block = blockIdx.z;
+    const QrStepArgs &a = g.p[blockIdx.y];
     const int H = a.H, N = a.N;
     const int n_row_tiles = H >> 2;
     const int block_rt0 = blockIdx.x * 2 * MT;
-    const int n0 = blockIdx.y * P::BN;
+    const int n0 = col_block * P::BN;
     if (block_rt0 >= n_row_tiles) return;   // uniform per block
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -237,7 +240,7 @@ __global__ __launch_bounds__(256, (USE_GX && !DBG) ? 3 : 2) void lstm_step_pipe_
         auto entry = [&](int j) { return rows[j < N ? j : N - 1]; };
         // staged row rl of a workgroup's range: tile rl / 16 = wn' * NT + nt' -> logical tile 2 * nt' + wn'
         auto logical = [](int rl) { return (((rl >> 4) % NT) * 2 + (rl >> 4) / NT) * 16 + (rl & 15); };
-        const int n0h = blockIdx.y * (P::BN / 2), n0q = blockIdx.y * (P::BN / 4);
+        const int n0h = col_block * (P::BN / 2), n0q = col_block * (P::BN / 4);
         v4i el[NT], ef[NT], el_half[NT / 2], el_h[NT / 2], ef_h[NT / 2], el_q[NT / 4], ef_q[NT / 4];
 #pragma unroll
         for (int i = 0; i < NT; ++i) {
@@ -264,7 +267,7 @@ __global__ __launch_bounds__(256, (USE_GX && !DBG) ? 3 : 2) void lstm_step_pipe_
 #pragma unroll
             for (int w = 1; w <= 2; ++w) {
                 const int per = P::BN >> w;
-                if (per * (int)gridDim.y >= n_cnt && g.row_blocks * ((n_cnt + per - 1) / per) <= g.n_cu) width = w;
+                if (per * (int)gridDim.z >= n_cnt && g.row_blocks * ((n_cnt + per - 1) / per) <= g.n_cu) width = w;
             }
         }
         const int n0w = width == 2 ? n0q : (width == 1 ? n0h : n0);
@@ -298,7 +301,7 @@ __global__ __launch_bounds__(256, (USE_GX && !DBG) ? 3 : 2) void lstm_step_pipe_
         // Without a list the launcher has chosen the width from N by the same rule (g.width); at full width the
         // columns keep their natural order.
         width = HALF_OK ? g.width : 0;   // uniform
-        const int n0w = blockIdx.y * (P::BN >> width);
+        const int n0w = col_block * (P::BN >> width);
         if (n0w >= N) return;   // uniform per block
         nt_valid = NT >> width;
         auto logical = [](int rl) { return (((rl >> 4) % NT) * 2 + (rl >> 4) / NT) * 16 + (rl & 15); };
@@ -543,7 +546,7 @@ void launch_pipe_f(const QrStepGroup &g, hipStream_t st)
         for (int w = 1; w <= 2; ++w)
             if (gg.row_blocks * ((max_n + (P::BN >> w) - 1) / (P::BN >> w)) <= n_cu) gg.width = w;
     const int per = P::BN >> gg.width;
-    kern<<<dim3(gx, (max_n + per - 1) / per, g.n), 256, P::LDS_BYTES, st>>>(gg);
+    kern<<<dim3(gx, g.n, (max_n + per - 1) / per), 256, P::LDS_BYTES, st>>>(gg);
 }
 
 template <int MT, int NT, int S, bool USE_GX>
