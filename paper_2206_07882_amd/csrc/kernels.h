@@ -41,6 +41,7 @@ struct QrStepGroup {
     // filled in by the launcher of the tiled kernel: row blocks of all members together, compute units of the device,
     // and (launches without a list) log2 of how many times narrower than the full column block a workgroup's share is
     int row_blocks = 0, n_cu = 0, width = 0;
+    int col_block0 = 0;                // first column block of this launch (a grid's z extent is limited to 65535)
 };
 
 struct QrLinearArgs {

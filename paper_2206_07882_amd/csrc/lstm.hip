@@ -203,7 +203,7 @@ __global__ __launch_bounds__(256, (USE_GX && !DBG) ? 3 : 2) void lstm_step_pipe_
     if (g.gate && *g.gate == 0) return;   // uniform: a decoding round without any live hypothesis
     // The column block is the slowest grid dimension: the workgroups of a short list's few column blocks are then
     // the first to be dispatched, and those that only look at the count and return follow behind them.
-    const int col_block = blockIdx.z;
+    const int col_block = g.col_block0 + (int)blockIdx.z;
     const QrStepArgs &a = g.p[blockIdx.y];
     const int H = a.H, N = a.N;
     const int n_row_tiles = H >> 2;
@@ -267,7 +267,7 @@ __global__ __launch_bounds__(256, (USE_GX && !DBG) ? 3 : 2) void lstm_step_pipe_
 #pragma unroll
             for (int w = 1; w <= 2; ++w) {
                 const int per = P::BN >> w;
-                if (per * (int)gridDim.z >= n_cnt && g.row_blocks * ((n_cnt + per - 1) / per) <= g.n_cu) width = w;
+                if (per * (g.col_block0 + (int)gridDim.z) >= n_cnt && g.row_blocks * ((n_cnt + per - 1) / per) <= g.n_cu) width = w;
             }
         }
         const int n0w = width == 2 ? n0q : (width == 1 ? n0h : n0);
@@ -546,7 +546,11 @@ void launch_pipe_f(const QrStepGroup &g, hipStream_t st)
         for (int w = 1; w <= 2; ++w)
             if (gg.row_blocks * ((max_n + (P::BN >> w) - 1) / (P::BN >> w)) <= n_cu) gg.width = w;
     const int per = P::BN >> gg.width;
-    kern<<<dim3(gx, g.n, (max_n + per - 1) / per), 256, P::LDS_BYTES, st>>>(gg);
+    const int gz = (max_n + per - 1) / per;
+    for (int z0 = 0; z0 < gz; z0 += 65535) {   // a grid's z extent ends at 65535
+        gg.col_block0 = z0;
+        kern<<<dim3(gx, g.n, gz - z0 < 65535 ? gz - z0 : 65535), 256, P::LDS_BYTES, st>>>(gg);
+    }
 }
 
 template <int MT, int NT, int S, bool USE_GX>
