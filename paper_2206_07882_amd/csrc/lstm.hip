@@ -216,6 +216,19 @@ __global__ __launch_bounds__(256, (USE_GX && !DBG) ? 3 : 2) void lstm_step_pipe_
     const int wm = wave & 1, wn = wave >> 1;
     const int rt0 = block_rt0 + wm * MT;
 
+    // Row constants of the input part (two-phase variants): what the hand-over between the phases needs is fetched
+    // now, one value per thread, and parked in LDS, so that the hand-over itself issues no vector-memory load (the
+    // wave's memory counter is in order: waiting for such a load there would wait for the whole ring as well).
+    constexpr int CELLS = 8 * MT;   // cells of a workgroup's row block
+    __shared__ __attribute__((aligned(16))) float xc[USE_GX ? 4 : 8 * CELLS];   // [s_wih, bias][gate][cell]
+    float xc_val = 0.0f;
+    if (!USE_GX) {
+        static_assert(USE_GX || 8 * CELLS == 256, "one constant per thread");
+        int cell = (block_rt0 >> 2) * 16 + (tid & (CELLS - 1));
+        cell = cell < H ? cell : H - 1;
+        xc_val = (tid < 4 * CELLS ? a.s_wih : a.bias)[((tid / CELLS) & 3) * H + cell];
+    }
+
     // ---- indices: rows this thread stages (ld_*) and hypotheses this lane finishes (n_of)
     int ld_n[NT], ld_s[NT], ld_x[NT], n_of[NT], src_of[NT], gx_of[NT];
     bool n_ok[NT];   // the column stands for a hypothesis (not for padding of the last block)
@@ -236,31 +249,18 @@ __global__ __launch_bounds__(256, (USE_GX && !DBG) ? 3 : 2) void lstm_step_pipe_
         // The entries are requested before the length of the list is looked at, so the two fetches overlap
         // (columns beyond the end compute on whatever their entry names, clamped into range, and store
         // nothing); an entry brings parent and input row along.  Which entries a thread stages and finishes
-        // depends on the width and on the instance: every set is requested.
-        auto entry = [&](int j) { return rows[j < N ? j : N - 1]; };
+        // depends on the width and on the instance, which the count decides.
+        // The entries of the workgroup's three possible ranges (full, half and quarter width: 7/4 of a column block in
+        // all) go through LDS, one load per thread; every thread then picks the ones it stages and finishes.  (The
+        // ring is not in use yet; the second barrier below keeps its first loads behind the last of these reads.)
         // staged row rl of a workgroup's range: tile rl / 16 = wn' * NT + nt' -> logical tile 2 * nt' + wn'
         auto logical = [](int rl) { return (((rl >> 4) % NT) * 2 + (rl >> 4) / NT) * 16 + (rl & 15); };
         const int n0h = col_block * (P::BN / 2), n0q = col_block * (P::BN / 4);
-        v4i el[NT], ef[NT], el_half[NT / 2], el_h[NT / 2], ef_h[NT / 2], el_q[NT / 4], ef_q[NT / 4];
-#pragma unroll
-        for (int i = 0; i < NT; ++i) {
-            el[i] = entry(n0 + logical(qr_pipe_b_row<NT>(wave, i, lane)));
-            ef[i] = entry(n0 + (i * 2 + wn) * 16 + col);
-        }
-#pragma unroll
-        for (int i = 0; i < NT / 2; ++i) {
-            el_half[i] = entry(n0 + logical(qr_pipe_b_row<NT, NT / 2>(wave, i, lane)));
-            if (HALF_OK) {
-                el_h[i] = entry(n0h + logical(qr_pipe_b_row<NT, NT / 2>(wave, i, lane)));
-                ef_h[i] = entry(n0h + (i * 2 + wn) * 16 + col);
-            }
-        }
-        if (HALF_OK) {
-#pragma unroll
-            for (int i = 0; i < NT / 4; ++i) {
-                el_q[i] = entry(n0q + logical(qr_pipe_b_row<NT, NT / 4>(wave, i, lane)));
-                ef_q[i] = entry(n0q + (i * 2 + wn) * 16 + col);
-            }
+        static_assert(P::BN + P::BN / 2 + P::BN / 4 <= 256, "one entry per thread");
+        v4i *se = (v4i *)lds;
+        if (tid < P::BN + P::BN / 2 + P::BN / 4) {
+            const int j = tid < P::BN ? n0 + tid : (tid < P::BN + P::BN / 2 ? n0h + tid - P::BN : n0q + tid - P::BN - P::BN / 2);
+            se[tid] = rows[j < N ? j : N - 1];
         }
         const int n_cnt = *g.n_rows;
         if (HALF_OK) {   // uniform: the narrowest width that covers the list and does not ask for more workgroups than CUs
@@ -272,6 +272,8 @@ __global__ __launch_bounds__(256, (USE_GX && !DBG) ? 3 : 2) void lstm_step_pipe_
         }
         const int n0w = width == 2 ? n0q : (width == 1 ? n0h : n0);
         if (n0w >= n_cnt) return;   // uniform per block
+        __syncthreads();
+        const int se0 = width == 2 ? P::BN + P::BN / 2 : (width == 1 ? P::BN : 0);   // where the range of this width starts in se
         nt_valid = NT >> width;
         if (width == 0) {   // tiles that hold entries, per wave column (rounded up); at this width no instance below the half
             nt_valid = (((n_cnt - n0 + 15) >> 4) + 1) >> 1;
@@ -282,9 +284,12 @@ __global__ __launch_bounds__(256, (USE_GX && !DBG) ? 3 : 2) void lstm_step_pipe_
         for (int i = 0; i < NT; ++i) {
             const int jf = n0w + (i * 2 + wn) * 16 + col;
             const int ih = i < NT / 2 ? i : 0, iq = i < NT / 4 ? i : 0;   // (entries past an instance's tiles are not used)
-            v4i el_i = half ? el_half[ih] : el[i], ef_i = ef[i];
-            if (HALF_OK && width == 1) { el_i = el_h[ih]; ef_i = ef_h[ih]; }
-            if (HALF_OK && width == 2) { el_i = el_q[iq]; ef_i = ef_q[iq]; }
+            int rl = qr_pipe_b_row<NT>(wave, i, lane);                        // the row this thread stages with load i
+            if (half || (HALF_OK && width == 1)) rl = qr_pipe_b_row<NT, NT / 2>(wave, ih, lane);
+            if (HALF_OK && width == 2) rl = qr_pipe_b_row<NT, NT / 4>(wave, iq, lane);
+            int fl = (i * 2 + wn) * 16 + col;                                 // the column this lane finishes in tile i
+            fl = fl < (P::BN >> width) ? fl : 0;
+            const v4i el_i = se[se0 + logical(rl)], ef_i = se[se0 + fl];
             auto hyp = [&](int r) { return r < 0 ? 0 : (r >= N ? N - 1 : r); };
             ld_n[i] = hyp(el_i[0]);
             ld_s[i] = a.parent ? el_i[1] : ld_n[i];
@@ -297,6 +302,7 @@ __global__ __launch_bounds__(256, (USE_GX && !DBG) ? 3 : 2) void lstm_step_pipe_
                 gx_of[i] = r < 0 ? 0 : (r >= a.n_x_rows ? a.n_x_rows - 1 : r);
             }
         }
+        __syncthreads();
     } else {
         // Without a list the launcher has chosen the width from N by the same rule (g.width); at full width the
         // columns keep their natural order.
@@ -393,8 +399,9 @@ __global__ __launch_bounds__(256, (USE_GX && !DBG) ? 3 : 2) void lstm_step_pipe_
             v4f sx[4], bx[4];
 #pragma unroll
             for (int gt = 0; gt < 4; ++gt) {   // accumulators hold 16 x sum; gate_k: see the epilogue
-                sx[gt] = load4(a.s_wih + gt * H + jb[q]) * a.x_scale * (0.0625f * gate_k(gt));
-                bx[gt] = load4(a.bias + gt * H + jb[q]) * gate_k(gt);   // the bias rides with the input part
+                const float *xq = xc + gt * CELLS + (wm * MQ + q) * 16 + 4 * grp;   // this lane's four cells
+                sx[gt] = *(const v4f *)xq * a.x_scale * (0.0625f * gate_k(gt));
+                bx[gt] = *(const v4f *)(xq + 4 * CELLS) * gate_k(gt);   // the bias rides with the input part
             }
 #pragma unroll
             for (int i = 0; i < 4; ++i)
@@ -411,6 +418,10 @@ __global__ __launch_bounds__(256, (USE_GX && !DBG) ? 3 : 2) void lstm_step_pipe_
                 }
         }
     };
+    if (!USE_GX) {
+        xc[tid] = xc_val;
+        __syncthreads();
+    }
     qr_pipe_mma<MT, NT, S, NPH, !FAST, false, NTV>(ph, n_row_tiles, block_rt0, lds, acc, x_done);
 
     // ---- fused cell: batched 128-bit loads, then branch-free arithmetic, then 128-bit / 32-bit stores
