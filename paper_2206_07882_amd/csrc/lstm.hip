@@ -204,7 +204,9 @@ __global__ __launch_bounds__(256, (USE_GX && !DBG) ? 3 : 2) void lstm_step_pipe_
     // The column block is the slowest grid dimension: the workgroups of a short list's few column blocks are then
     // the first to be dispatched, and those that only look at the count and return follow behind them.
     const int col_block = g.col_block0 + (int)blockIdx.z;
-    const QrStepArgs &a = g.p[blockIdx.y];
+    // A copy, not a reference: the fields then arrive with a few wide scalar loads up front instead of one load (and
+    // one wait) at a time wherever the code first needs them.
+    const QrStepArgs a = g.p[blockIdx.y];
     const int H = a.H, N = a.N;
     const int n_row_tiles = H >> 2;
     const int block_rt0 = blockIdx.x * 2 * MT;
