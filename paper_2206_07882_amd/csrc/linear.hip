@@ -10,7 +10,7 @@ __global__ __launch_bounds__(256) void linear_head_kernel(const QrLinearGroup g)
 {
     __shared__ v4i lds[4 * 4 * 64];
     if (g.gate && *g.gate == 0) return;   // uniform: a decoding round without any live hypothesis
-    const QrLinearArgs &a = g.p[blockIdx.z];
+    const QrLinearArgs a = g.p[blockIdx.z];   // a copy: the fields arrive with a few wide scalar loads up front
     const int n_row_tiles = (a.rows + 15) >> 4;
     const int rt0 = blockIdx.y * 4;
     if (rt0 >= n_row_tiles || (int)blockIdx.x * 16 >= a.N) return;   // uniform per block

@@ -28,7 +28,7 @@ __global__ __launch_bounds__(256) void lstm_step_small_kernel(const QrStepGroup 
 {
     __shared__ v4i part[3][2][64];   // waves 1..3: [x|h][lane]
     if (g.gate && *g.gate == 0) return;   // uniform: a decoding round without any live hypothesis
-    const QrStepArgs &a = g.p[blockIdx.z];
+    const QrStepArgs a = g.p[blockIdx.z];   // a copy: the fields arrive with a few wide scalar loads up front
     const int H = a.H, N = a.N;
     const int rt = blockIdx.x;
     const int n0 = blockIdx.y * 16;
