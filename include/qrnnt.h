@@ -236,6 +236,22 @@ qrnnt_status qrnnt_lstm_layer(const qrnnt_lstm *L, const int8_t *x_codes, int32_
                               int8_t *h_last, float *c_last, int32_t *dbg_accx, float *dbg_c_all,
                               void *workspace, size_t workspace_bytes, void *stream);
 
+/* qrnnt_lstm_layer for callers that cannot allocate device memory or supply a workspace:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  Same arguments, results and error flag semantics as qrnnt_lstm_layer
+ * without the debug outputs; the workspace is a device array inside the library of
+ * QRNNT_STATIC_WORKSPACE_BYTES bytes (held by every GPU the library runs on until the
+ * process ends).  Returns QRNNT_ERR_WORKSPACE when qrnnt_lstm_layer_workspace(L, T, B)
+ * exceeds that size (roughly T*B*16*H + 10*B*H bytes: e.g. one utterance of 3000
+ * frames at H = 640).  The call allocates nothing.  All calls on one GPU share the
+ * array: calls that may overlap on one GPU (different streams, different threads)
+ * race; calls on one stream are ordered.  The bounded-wait flag of the persistent
+ * recurrence is not visible to the caller here. */
+#define QRNNT_STATIC_WORKSPACE_BYTES (32u << 20)
+qrnnt_status qrnnt_lstm_layer_static(const qrnnt_lstm *L, const int8_t *x_codes, int32_t T, int32_t B, int32_t reverse,
+                                     const int8_t *h0, const float *c0, int8_t *h_out, int32_t ld_out, int32_t col_off,
+                                     int8_t *h_last, float *c_last, void *stream);
+
 /* Both directions of a bidirectional layer in one call (zero initial state):
  * forward codes go to columns [0,H) and backward codes to [H,2H) of h_out [device]
  * [T,B,2H].  The two recurrences advance concurrently in one launch.  workspace

@@ -3,6 +3,7 @@
 // W_ih and W_hh, fp bias and cell state; Sec. 3.4: the hidden state is
 // quantized once, at the cell output).
 #include <cstdlib>
+#include <mutex>
 #include <type_traits>
 
 #include "kernels.h"
@@ -1070,4 +1071,50 @@ extern "C" qrnnt_status qrnnt_bilstm_layer(const qrnnt_lstm *fwd, const qrnnt_ls
     }
     QR_REQUIRE(workspace_bytes >= layer_ws(fwd, T, B).total + layer_ws(bwd, T, B).total, QRNNT_ERR_WORKSPACE);
     return run_layer(c, 2, x_codes, T, B, h_out, 2 * H, (hipStream_t)stream);
+}
+
+// ---------------------------------------------------------------------------------------------------------
+// qrnnt_lstm_layer for callers that cannot allocate device memory: the workspace of the layer (input projection
+// sums, state buffers, exchange words of the persistent recurrence) lives in a file-scope device array.  Every
+// device the library runs on holds its own copy of the array at its own address; the host gets that address once
+// per device from the runtime and hands it to the same code path that qrnnt_lstm_layer takes with a caller's
+// workspace.  The array keeps the previous call's contents: run_layer clears what has to start at zero (exchange
+// words and error flag, zero initial state) on the stream before it is read.
+#define QR_STATIC_WS_BYTES ((size_t)QRNNT_STATIC_WORKSPACE_BYTES)
+static __device__ __align__(256) unsigned char scratch[QR_STATIC_WS_BYTES];
+
+namespace {
+constexpr int QR_MAX_DEVICES = 64;
+std::mutex scratch_mutex;
+void *scratch_ptr[QR_MAX_DEVICES];   // per device: address of `scratch` on that device (nullptr: not asked yet)
+
+// Device address of the scratch array on the device that is current on the calling thread.
+qrnnt_status static_scratch(char **out)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= QR_MAX_DEVICES) return QRNNT_ERR_HIP;
+    std::lock_guard<std::mutex> lock(scratch_mutex);
+    if (scratch_ptr[dev] == nullptr) {
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || p == nullptr) return QRNNT_ERR_HIP;
+        scratch_ptr[dev] = p;
+    }
+    *out = (char *)scratch_ptr[dev];
+    return QRNNT_OK;
+}
+}  // namespace
+
+extern "C" qrnnt_status qrnnt_lstm_layer_static(const qrnnt_lstm *L, const int8_t *x_codes, int32_t T, int32_t B,
+                                                int32_t reverse, const int8_t *h0, const float *c0, int8_t *h_out,
+                                                int32_t ld_out, int32_t col_off, int8_t *h_last, float *c_last,
+                                                void *stream)
+{
+    // validation first (needs no GPU): a dummy non-null workspace address stands in until the size is known to fit
+    LayerCall c = {L, reverse, h0, c0, col_off, h_last, c_last, nullptr, nullptr, (char *)(uintptr_t)256};
+    qrnnt_status s = check_layer_call(c, x_codes, T, B, h_out, ld_out);
+    if (s != QRNNT_OK) return s;
+    QR_REQUIRE(layer_ws(L, T, B).total <= QR_STATIC_WS_BYTES, QRNNT_ERR_WORKSPACE);
+    s = static_scratch(&c.ws);
+    if (s != QRNNT_OK) return s;
+    return run_layer(&c, 1, x_codes, T, B, h_out, ld_out, (hipStream_t)stream);
 }

@@ -61,7 +61,7 @@ EXPORTS = ["qrnnt_status_str", "qrnnt_abi_version", "qrnnt_pack_int4_bytes", "qr
            "qrnnt_pack_int8_bytes", "qrnnt_pack_int8", "qrnnt_quantize_act8",
            "qrnnt_quantize_act", "qrnnt_linear", "qrnnt_linear_quant", "qrnnt_lstm_step", "qrnnt_lstm_layer_workspace", "qrnnt_lstm_layer",
            "qrnnt_input_projection", "qrnnt_input_table", "qrnnt_lstm_step_group", "qrnnt_lstm_step_group_listed",
-           "qrnnt_bilstm_layer_workspace", "qrnnt_bilstm_layer",
+           "qrnnt_bilstm_layer_workspace", "qrnnt_bilstm_layer", "qrnnt_lstm_layer_static",
            "qrnnt_joint_fuse", "qrnnt_beam_step", "qrnnt_decode_workspace", "qrnnt_decode", "qrnnt_decode_ex",
            "qrnnt_decode_alsd_workspace", "qrnnt_decode_alsd"]
 
@@ -340,6 +340,22 @@ def lstm_layer(L: Lstm, x_codes: torch.Tensor, reverse: bool = False, h0=None, c
                                  _ptr(accx), _ptr(c_all), _ptr(workspace), C.c_size_t(workspace.numel()), _stream())
     _check(st, "qrnnt_lstm_layer")
     return dict(h_out=h_out, h_last=h_last, c_last=c_last, accx=accx, c_all=c_all)
+
+
+STATIC_WORKSPACE_BYTES = 32 << 20
+
+
+def lstm_layer_static(L: Lstm, x_codes: torch.Tensor, h_out: torch.Tensor, reverse: bool = False, h0=None, c0=None,
+                      col_off: int = 0, h_last=None, c_last=None):
+    """qrnnt_lstm_layer_static: the layer with the library's own fixed workspace; every output is the caller's."""
+    T, B, _ = x_codes.shape
+    cl = L.c()
+    st = load().qrnnt_lstm_layer_static(C.byref(cl), _ptr(x_codes, torch.int8), C.c_int32(T), C.c_int32(B),
+                                        C.c_int32(1 if reverse else 0), _ptr(h0, torch.int8), _ptr(c0, torch.float32),
+                                        _ptr(h_out, torch.int8), C.c_int32(h_out.shape[2]), C.c_int32(col_off),
+                                        _ptr(h_last, torch.int8), _ptr(c_last, torch.float32), _stream())
+    _check(st, "qrnnt_lstm_layer_static")
+    return h_out
 
 
 def bilstm_layer_workspace(fwd: Lstm, bwd: Lstm, T: int, B: int) -> int:
