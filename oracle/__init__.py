@@ -40,6 +40,8 @@ def lib():
         _lib.oq_quant_sym4.restype = C.c_int8
         _lib.oq_quant_sym4.argtypes = [C.c_float, C.c_float]
         _lib.oq_score_alignment.restype = C.c_float
+        _lib.oq_tie_distance.restype = C.c_double
+        _lib.oq_tie_distance.argtypes = [C.c_float, C.c_float, C.c_int]
         _lib.oq_struct_sizes.restype = C.c_int
         assert _lib.oq_struct_sizes(0) == C.sizeof(_CLstm)
         assert _lib.oq_struct_sizes(1) == C.sizeof(_CLinear)
@@ -107,6 +109,11 @@ def quant_sym(x, inv_s, bits):
     q = np.empty(x.shape, np.int8)
     lib().oq_quantize_sym(_p(x), C.c_int64(x.size), C.c_float(inv_s), C.c_int(bits), _p(q))
     return q
+
+
+def tie_distance(x, inv_s, bits=4):
+    """How close the quantizer's decision on x is to a rounding tie, in 4-bit code steps (inf where the clamp decides)."""
+    return float(lib().oq_tie_distance(C.c_float(x), C.c_float(inv_s), C.c_int(bits)))
 
 
 def quantize_asym(x, bits, a_lo, a_hi):
@@ -226,7 +233,9 @@ def lstm_step(L: Lstm, x, h_prev, c_prev, parent=None, active=None, debug=False)
     return h_next, c_next
 
 
-def lstm_layer(L: Lstm, x, reverse=False, h0=None, c0=None, h_out=None, col_off=0, want_c_all=False):
+def lstm_layer(L: Lstm, x, reverse=False, h0=None, c0=None, h_out=None, col_off=0, want_c_all=False, utt_margin=None):
+    """utt_margin: float64 [B], lowered in place to the smallest tie distance of each utterance's hidden-state
+    quantizer decisions (oq_lstm_layer_margin)."""
     x = _arr(x, np.int8)
     T, B, I = x.shape
     assert I == L.I
@@ -242,6 +251,12 @@ def lstm_layer(L: Lstm, x, reverse=False, h0=None, c0=None, h_out=None, col_off=
     h0a = None if h0 is None else _arr(h0, np.int8)
     c0a = None if c0 is None else _arr(c0, np.float32)
     cl = L.c()
+    if utt_margin is not None:
+        assert utt_margin.dtype == np.float64 and utt_margin.shape == (B,) and utt_margin.flags.c_contiguous
+        lib().oq_lstm_layer_margin(C.byref(cl), _p(x), C.c_int(T), C.c_int(B), C.c_int(1 if reverse else 0), _p(h0a),
+                                   _p(c0a), _p(h_out), C.c_int(ld), C.c_int(col_off), _p(h_last), _p(c_last), _p(c_all),
+                                   _p(utt_margin))
+        return h_out, h_last, c_last, c_all
     lib().oq_lstm_layer(C.byref(cl), _p(x), C.c_int(T), C.c_int(B), C.c_int(1 if reverse else 0), _p(h0a), _p(c0a),
                         _p(h_out), C.c_int(ld), C.c_int(col_off), _p(h_last), _p(c_last), _p(c_all))
     return h_out, h_last, c_last, c_all
@@ -310,7 +325,9 @@ def joint_fuse(enc_proj, frame_row, pred_proj, out: Linear, lp_src, lp_ext, lamb
     return zq, lp, fused
 
 
-def beam_step(score, fused, blank=0, force_blank=False):
+def beam_step(score, fused, blank=0, force_blank=False, want_gap=False):
+    """want_gap: also returns, per utterance, the smallest difference between consecutive values among the picks and
+    the best candidate left out (inf when nothing is ranked against anything)."""
     score = _arr(score, np.float32)
     fused = _arr(fused, np.float32)
     B, W = score.shape
@@ -319,6 +336,11 @@ def beam_step(score, fused, blank=0, force_blank=False):
     par = np.empty((B, W), np.int32)
     tok = np.empty((B, W), np.int32)
     ns = np.empty((B, W), np.float32)
+    if want_gap:
+        gap = np.full(B, np.inf, np.float64)
+        lib().oq_beam_step_gap(_p(score), _p(fused), C.c_int(B), C.c_int(W), C.c_int(V), C.c_int(blank),
+                               C.c_int(1 if force_blank else 0), _p(par), _p(tok), _p(ns), _p(gap))
+        return par, tok, ns, gap
     lib().oq_beam_step(_p(score), _p(fused), C.c_int(B), C.c_int(W), C.c_int(V), C.c_int(blank),
                        C.c_int(1 if force_blank else 0), _p(par), _p(tok), _p(ns))
     return par, tok, ns
@@ -391,7 +413,9 @@ class Model:
         return m
 
 
-def decode(model: Model, enc_proj, W, max_sym, max_len=None):
+def decode(model: Model, enc_proj, W, max_sym, max_len=None, margins=False):
+    """margins: also returns (qmargin [B], smargin [B]) of oq_decode_margins: the smallest quantizer tie distance and
+    the smallest selection gap met on each utterance's way."""
     enc_proj = _arr(enc_proj, np.float32)
     T, B, J = enc_proj.shape
     if max_len is None:
@@ -400,13 +424,19 @@ def decode(model: Model, enc_proj, W, max_sym, max_len=None):
     lens = np.empty((B, W), np.int32)
     scores = np.empty((B, W), np.float32)
     cm = model.c()
+    if margins:
+        qm, sm = np.empty(B, np.float64), np.empty(B, np.float64)
+        lib().oq_decode_margins(C.byref(cm), _p(enc_proj), C.c_int(T), C.c_int(B), C.c_int(W), C.c_int(max_sym),
+                                C.c_int(max_len), _p(tokens), _p(lens), _p(scores), _p(qm), _p(sm))
+        return tokens, lens, scores, qm, sm
     lib().oq_decode(C.byref(cm), _p(enc_proj), C.c_int(T), C.c_int(B), C.c_int(W), C.c_int(max_sym), C.c_int(max_len),
                     _p(tokens), _p(lens), _p(scores))
     return tokens, lens, scores
 
 
-def decode_alsd(model: Model, enc_proj, W, u_max, max_len=None):
-    """Alignment-length synchronous search with recombination; at most u_max labels per utterance."""
+def decode_alsd(model: Model, enc_proj, W, u_max, max_len=None, margins=False):
+    """Alignment-length synchronous search with recombination; at most u_max labels per utterance.
+    margins: as in decode (oq_decode_alsd_margins)."""
     enc_proj = _arr(enc_proj, np.float32)
     T, B, J = enc_proj.shape
     if max_len is None:
@@ -415,6 +445,11 @@ def decode_alsd(model: Model, enc_proj, W, u_max, max_len=None):
     lens = np.empty((B, W), np.int32)
     scores = np.empty((B, W), np.float32)
     cm = model.c()
+    if margins:
+        qm, sm = np.empty(B, np.float64), np.empty(B, np.float64)
+        lib().oq_decode_alsd_margins(C.byref(cm), _p(enc_proj), C.c_int(T), C.c_int(B), C.c_int(W), C.c_int(u_max),
+                                     C.c_int(max_len), _p(tokens), _p(lens), _p(scores), _p(qm), _p(sm))
+        return tokens, lens, scores, qm, sm
     lib().oq_decode_alsd(C.byref(cm), _p(enc_proj), C.c_int(T), C.c_int(B), C.c_int(W), C.c_int(u_max),
                          C.c_int(max_len), _p(tokens), _p(lens), _p(scores))
     return tokens, lens, scores

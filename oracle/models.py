@@ -72,9 +72,10 @@ def encoder_from_float(m):
     return layers, proj
 
 
-def encoder_forward(layers, proj, feats, alpha_x):
+def encoder_forward(layers, proj, feats, alpha_x, utt_margin=None):
     """features [T,B,D] fp32 -> (codes of the last layer [T,B,dirs*H], e [T,B,J]).  The input quantizer has
-    the width of the first layer."""
+    the width of the first layer.  utt_margin (float64 [B], optional) is lowered to the smallest tie distance of
+    every hidden-state quantizer decision of each utterance."""
     bits = layers[0][0].bits
     _, inv_s_x = act_scale(alpha_x, bits)
     x = quant_sym(feats, inv_s_x, bits)
@@ -83,7 +84,7 @@ def encoder_forward(layers, proj, feats, alpha_x):
         H = dirs[0].H
         out = np.zeros((T, B, H * len(dirs)), np.int8)
         for d, L in enumerate(dirs):
-            lstm_layer(L, x, reverse=(d == 1), h_out=out, col_off=d * H)
+            lstm_layer(L, x, reverse=(d == 1), h_out=out, col_off=d * H, utt_margin=utt_margin)
         x = out
     e = linear(proj, x.reshape(T * B, -1)).reshape(T, B, -1)
     return x, e

@@ -84,6 +84,24 @@ void oq_quantize_sym(const float *x, int64_t n, float inv_s, int bits, int8_t *q
     for (int64_t i = 0; i < n; ++i) q[i] = oq_quant_sym(x[i], inv_s, bits);
 }
 
+/* Bookkeeping for free-running comparisons (no part of the method): how close
+ * the quantizer's decision on x came to a rounding tie.  A value computed in
+ * fp32 by another implementation differs from this file's fp64 value by a few
+ * units in the last place; when x * inv_s lies that close to k + 1/2 the two
+ * round to different codes, both within the accuracy the method has.  Returned
+ * in units of 4-bit code steps (the distance on the 8-bit grid times 7/127, so
+ * that one bound serves both widths); +inf where the clamp decides the code
+ * (no rounding involved).  Pinned by: hand values. */
+double oq_tie_distance(float x, float inv_s, int bits)
+{
+    if (bits == 0) bits = 4;
+    const double qmax = (double)((1 << (bits - 1)) - 1);
+    const double t = (double)(x * inv_s);           /* the fp32 product that is rounded */
+    if (t <= -qmax - 1.5 || t >= qmax + 0.5) return INFINITY;
+    const double frac = t - floor(t);
+    return fabs(frac - 0.5) * (7.0 / qmax);
+}
+
 /* Asymmetric LQ, Eq. 2 and Eq. 3, for b bits and boundaries alpha_-/alpha_+.
  * Not on the integer path (weights are symmetric and every activation range
  * used is +-alpha); carried as a utility.  Pinned by: alpha_- maps to 0,
@@ -230,10 +248,11 @@ static double sigm(double v) { return 1.0 / (1.0 + exp(-v)); }
  * i,f,g,o), h_real fp64 [N,H] (h before the quantizer).
  * Pinned by: zero-weight closed form, |code|<=7, hand-rolled numpy cell on
  * random small inputs, pass-through of inactive rows. */
-void oq_lstm_step(const oq_lstm_t *L, const int8_t *x, const int32_t *parent,
+static void lstm_step_core(const oq_lstm_t *L, const int8_t *x, const int32_t *parent,
                   const int8_t *h_prev, const float *c_prev, const uint8_t *active, int N,
                   int8_t *h_next, float *c_next,
-                  int32_t *accx_out, int32_t *acch_out, double *gates_out, double *h_real_out)
+                  int32_t *accx_out, int32_t *acch_out, double *gates_out, double *h_real_out,
+                  double *row_margin /* [N] or NULL: smallest oq_tie_distance among the row's H decisions */)
 {
     const int H = L->H, I = L->I, R = 4 * L->H;
     g_quant_tensor_calls += 1; /* the one quantizer at the cell output */
@@ -242,6 +261,7 @@ void oq_lstm_step(const oq_lstm_t *L, const int8_t *x, const int32_t *parent,
         int src = parent ? parent[n] : n;
         const int8_t *hp = h_prev + (int64_t)src * H;
         const float *cp = c_prev + (int64_t)src * H;
+        if (row_margin) row_margin[n] = INFINITY;
         if (active && !active[n]) {
             memcpy(h_next + (int64_t)n * H, hp, (size_t)H);
             memcpy(c_next + (int64_t)n * H, cp, (size_t)H * sizeof(float));
@@ -269,6 +289,10 @@ void oq_lstm_step(const oq_lstm_t *L, const int8_t *x, const int32_t *parent,
             double h = go * tanh(c);
             c_next[(int64_t)n * H + j] = (float)c;
             h_next[(int64_t)n * H + j] = oq_quant_sym((float)h, L->inv_s_h, L->bits);
+            if (row_margin) {
+                const double d = oq_tie_distance((float)h, L->inv_s_h, L->bits);
+                if (d < row_margin[n]) row_margin[n] = d;
+            }
             if (gates_out) {
                 double *g = gates_out + (int64_t)n * R;
                 g[j] = gi; g[H + j] = gf; g[2 * H + j] = gg; g[3 * H + j] = go;
@@ -279,6 +303,14 @@ void oq_lstm_step(const oq_lstm_t *L, const int8_t *x, const int32_t *parent,
     }
 }
 
+void oq_lstm_step(const oq_lstm_t *L, const int8_t *x, const int32_t *parent,
+                  const int8_t *h_prev, const float *c_prev, const uint8_t *active, int N,
+                  int8_t *h_next, float *c_next,
+                  int32_t *accx_out, int32_t *acch_out, double *gates_out, double *h_real_out)
+{
+    lstm_step_core(L, x, parent, h_prev, c_prev, active, N, h_next, c_next, accx_out, acch_out, gates_out, h_real_out, NULL);
+}
+
 /* One layer-direction over a whole batch of equal-length utterances.
  * x [T,B,I] codes; output codes written to h_out[t,b,col_off + j] with row
  * pitch ld_out, so that a bidirectional layer is two calls that fill the two
@@ -286,28 +318,50 @@ void oq_lstm_step(const oq_lstm_t *L, const int8_t *x, const int32_t *parent,
  * reverse!=0 walks t = T-1..0.  h0/c0 NULL mean zero (Sec. 3.4 assumes a zero
  * state before the first step).  c_all (optional) receives c_t for every t.
  * Pinned by: reverse == time-flip of forward on flipped input; T=1 == step. */
-void oq_lstm_layer(const oq_lstm_t *L, const int8_t *x, int T, int B, int reverse,
+static void lstm_layer_core(const oq_lstm_t *L, const int8_t *x, int T, int B, int reverse,
                    const int8_t *h0, const float *c0,
                    int8_t *h_out, int ld_out, int col_off,
-                   int8_t *h_last, float *c_last, float *c_all)
+                   int8_t *h_last, float *c_last, float *c_all,
+                   double *utt_margin /* [B] or NULL: lowered to the smallest oq_tie_distance of utterance b's cells */)
 {
     const int H = L->H, I = L->I;
+    double *rm = utt_margin ? (double *)malloc(sizeof(double) * (size_t)B) : NULL;
     int8_t *h = (int8_t *)calloc((size_t)B * H, 1), *hn = (int8_t *)calloc((size_t)B * H, 1);
     float *c = (float *)calloc((size_t)B * H, sizeof(float)), *cn = (float *)calloc((size_t)B * H, sizeof(float));
     if (h0) memcpy(h, h0, (size_t)B * H);
     if (c0) memcpy(c, c0, (size_t)B * H * sizeof(float));
     for (int s = 0; s < T; ++s) {
         int t = reverse ? T - 1 - s : s;
-        oq_lstm_step(L, x + (int64_t)t * B * I, NULL, h, c, NULL, B, hn, cn, NULL, NULL, NULL, NULL);
-        for (int b = 0; b < B; ++b)
+        lstm_step_core(L, x + (int64_t)t * B * I, NULL, h, c, NULL, B, hn, cn, NULL, NULL, NULL, NULL, rm);
+        for (int b = 0; b < B; ++b) {
             memcpy(h_out + ((int64_t)t * B + b) * ld_out + col_off, hn + (int64_t)b * H, (size_t)H);
+            if (rm && rm[b] < utt_margin[b]) utt_margin[b] = rm[b];
+        }
         if (c_all) memcpy(c_all + (int64_t)t * B * H, cn, (size_t)B * H * sizeof(float));
         int8_t *th = h; h = hn; hn = th;
         float *tc = c; c = cn; cn = tc;
     }
     if (h_last) memcpy(h_last, h, (size_t)B * H);
     if (c_last) memcpy(c_last, c, (size_t)B * H * sizeof(float));
-    free(h); free(hn); free(c); free(cn);
+    free(h); free(hn); free(c); free(cn); free(rm);
+}
+
+void oq_lstm_layer(const oq_lstm_t *L, const int8_t *x, int T, int B, int reverse,
+                   const int8_t *h0, const float *c0,
+                   int8_t *h_out, int ld_out, int col_off,
+                   int8_t *h_last, float *c_last, float *c_all)
+{
+    lstm_layer_core(L, x, T, B, reverse, h0, c0, h_out, ld_out, col_off, h_last, c_last, c_all, NULL);
+}
+
+/* The same, also lowering utt_margin[b] (caller-initialised, e.g. to +inf) to the smallest
+ * oq_tie_distance met by any hidden-state quantizer of utterance b. */
+void oq_lstm_layer_margin(const oq_lstm_t *L, const int8_t *x, int T, int B, int reverse,
+                          const int8_t *h0, const float *c0,
+                          int8_t *h_out, int ld_out, int col_off,
+                          int8_t *h_last, float *c_last, float *c_all, double *utt_margin)
+{
+    lstm_layer_core(L, x, T, B, reverse, h0, c0, h_out, ld_out, col_off, h_last, c_last, c_all, utt_margin);
 }
 
 /* ------------------------------------------------------------------ */
@@ -366,17 +420,29 @@ void oq_log_softmax(const float *x, int N, int V, float *lp)
  * the tanh is the measured configuration's), then the 4-bit code of z since z
  * is the input of a quantized linear layer (Sec. 3.2).  Row n uses encoder row
  * frame_row[n].  Pinned by: numpy restatement, |code| <= 7. */
-void oq_joint_z(const float *enc_proj, const int32_t *frame_row, const float *pred_proj,
-                int N, int J, float inv_s_z, int bits, int8_t *zq, double *z_real)
+static void joint_z_core(const float *enc_proj, const int32_t *frame_row, const float *pred_proj,
+                         int N, int J, float inv_s_z, int bits, int8_t *zq, double *z_real,
+                         double *row_margin /* [N] or NULL: smallest oq_tie_distance among the row's J decisions */)
 {
     for (int n = 0; n < N; ++n) {
         const float *e = enc_proj + (int64_t)frame_row[n] * J, *p = pred_proj + (int64_t)n * J;
+        if (row_margin) row_margin[n] = INFINITY;
         for (int j = 0; j < J; ++j) {
             double z = tanh((double)e[j] * (double)p[j]);
             if (z_real) z_real[(int64_t)n * J + j] = z;
             zq[(int64_t)n * J + j] = oq_quant_sym((float)z, inv_s_z, bits);
+            if (row_margin) {
+                const double d = oq_tie_distance((float)z, inv_s_z, bits);
+                if (d < row_margin[n]) row_margin[n] = d;
+            }
         }
     }
+}
+
+void oq_joint_z(const float *enc_proj, const int32_t *frame_row, const float *pred_proj,
+                int N, int J, float inv_s_z, int bits, int8_t *zq, double *z_real)
+{
+    joint_z_core(enc_proj, frame_row, pred_proj, N, J, inv_s_z, bits, zq, z_real, NULL);
 }
 
 /* Joint, second half + Eq. 1.  logits = Linear_out(zq); lp = log_softmax;
@@ -412,15 +478,24 @@ void oq_joint_out(const oq_linear_t *out, const int8_t *zq, const float *lp_src,
     free(buf);
 }
 
+static void joint_fuse_core(const float *enc_proj, const int32_t *frame_row, const float *pred_proj,
+                            const oq_linear_t *out, float inv_s_z, const float *lp_src, const float *lp_ext,
+                            float lambda_src, float lambda_ext, float rho, int N, int blank,
+                            int8_t *zq_out, float *lp_rnnt, float *fused, double *row_margin)
+{
+    int8_t *zq = zq_out ? zq_out : (int8_t *)malloc((size_t)N * out->cols);
+    joint_z_core(enc_proj, frame_row, pred_proj, N, out->cols, inv_s_z, out->bits, zq, NULL, row_margin);
+    oq_joint_out(out, zq, lp_src, lp_ext, lambda_src, lambda_ext, rho, N, blank, lp_rnnt, fused);
+    if (!zq_out) free(zq);
+}
+
 void oq_joint_fuse(const float *enc_proj, const int32_t *frame_row, const float *pred_proj,
                    const oq_linear_t *out, float inv_s_z, const float *lp_src, const float *lp_ext,
                    float lambda_src, float lambda_ext, float rho, int N, int blank,
                    int8_t *zq_out, float *lp_rnnt, float *fused)
 {
-    int8_t *zq = zq_out ? zq_out : (int8_t *)malloc((size_t)N * out->cols);
-    oq_joint_z(enc_proj, frame_row, pred_proj, N, out->cols, inv_s_z, out->bits, zq, NULL);
-    oq_joint_out(out, zq, lp_src, lp_ext, lambda_src, lambda_ext, rho, N, blank, lp_rnnt, fused);
-    if (!zq_out) free(zq);
+    joint_fuse_core(enc_proj, frame_row, pred_proj, out, inv_s_z, lp_src, lp_ext, lambda_src, lambda_ext, rho, N, blank,
+                    zq_out, lp_rnnt, fused, NULL);
 }
 
 /* ------------------------------------------------------------------ */
@@ -433,8 +508,12 @@ void oq_joint_fuse(const float *enc_proj, const int32_t *frame_row, const float 
  * force_blank != 0 restricts the candidates to k == blank.  Unfilled ranks get
  * parent = token = -1, score = -inf.
  * Pinned by: numpy lexsort restatement, tie case, -inf case. */
-void oq_beam_step(const float *score, const float *fused, int B, int W, int V, int blank,
-                  int force_blank, int32_t *parent_out, int32_t *token_out, float *score_out)
+static void beam_step_core(const float *score, const float *fused, int B, int W, int V, int blank,
+                           int force_blank, int32_t *parent_out, int32_t *token_out, float *score_out,
+                           double *utt_gap /* [B] or NULL: lowered to the smallest difference between
+                                              consecutive values among the picks and the best candidate
+                                              left out (what a perturbation of the values must exceed to
+                                              change the picks or their order) */)
 {
     for (int b = 0; b < B; ++b) {
         int nc = W * V;
@@ -459,8 +538,36 @@ void oq_beam_step(const float *score, const float *fused, int B, int W, int V, i
                 parent_out[b * W + r] = best / V; token_out[b * W + r] = best % V; score_out[b * W + r] = val[best];
             }
         }
+        if (utt_gap) {
+            float prev = INFINITY;
+            for (int r = 0; r <= W; ++r) {
+                float v = -INFINITY;
+                if (r < W) {
+                    v = score_out[b * W + r];
+                } else {   /* the best candidate that was not picked */
+                    for (int c = 0; c < nc; ++c)
+                        if (!taken[c] && val[c] > v) v = val[c];
+                }
+                if (!(v > -INFINITY)) break;
+                if (r > 0 && (double)prev - (double)v < utt_gap[b]) utt_gap[b] = (double)prev - (double)v;
+                prev = v;
+            }
+        }
         free(val); free(taken);
     }
+}
+
+void oq_beam_step(const float *score, const float *fused, int B, int W, int V, int blank,
+                  int force_blank, int32_t *parent_out, int32_t *token_out, float *score_out)
+{
+    beam_step_core(score, fused, B, W, V, blank, force_blank, parent_out, token_out, score_out, NULL);
+}
+
+/* oq_beam_step that also lowers utt_gap[b] (caller-initialised) as described at beam_step_core. */
+void oq_beam_step_gap(const float *score, const float *fused, int B, int W, int V, int blank,
+                      int force_blank, int32_t *parent_out, int32_t *token_out, float *score_out, double *utt_gap)
+{
+    beam_step_core(score, fused, B, W, V, blank, force_blank, parent_out, token_out, score_out, utt_gap);
 }
 
 /* A language model or the prediction network: embedding lookup, the symmetric
@@ -520,15 +627,20 @@ static void ns_copy(const oq_net_t *net, net_state *d, const net_state *s)
 }
 
 /* Feed one symbol: dst = advance(src, token).  dst and src must differ. */
-static void net_advance(const oq_net_t *net, const net_state *src, int token, net_state *dst)
+/* margin (optional): lowered to the smallest oq_tie_distance of the quantizers whose input is computed here
+ * (hidden states, the bottleneck's output; the embedding's quantizer sees a stored fp32 value and decides the
+ * same way in any implementation). */
+static void net_advance(const oq_net_t *net, const net_state *src, int token, net_state *dst, double *margin)
 {
     int maxw = net->E;
     for (int l = 0; l < net->L; ++l) if (net->layer[l].H > maxw) maxw = net->layer[l].H;
     int8_t *xin = (int8_t *)malloc((size_t)maxw);
     oq_quantize_sym4(net->embed + (int64_t)token * net->E, net->E, net->inv_s_e, xin);
     for (int l = 0; l < net->L; ++l) {
-        oq_lstm_step(&net->layer[l], xin, NULL, src->h[l], src->c[l], NULL, 1,
-                     dst->h[l], dst->c[l], NULL, NULL, NULL, NULL);
+        double rm = INFINITY;
+        lstm_step_core(&net->layer[l], xin, NULL, src->h[l], src->c[l], NULL, 1,
+                       dst->h[l], dst->c[l], NULL, NULL, NULL, NULL, margin ? &rm : NULL);
+        if (margin && rm < *margin) *margin = rm;
         memcpy(xin, dst->h[l], (size_t)net->layer[l].H);
     }
     if (net->has_mid) {
@@ -536,6 +648,11 @@ static void net_advance(const oq_net_t *net, const net_state *src, int token, ne
         int8_t *qm = (int8_t *)malloc((size_t)net->mid.rows);
         oq_linear(&net->mid, xin, 1, ym, NULL);
         oq_quantize_sym(ym, net->mid.rows, net->inv_s_mid, net->out.bits, qm); /* the output layer's own input quantizer */
+        if (margin)
+            for (int r = 0; r < net->mid.rows; ++r) {
+                const double d = oq_tie_distance(ym[r], net->inv_s_mid, net->out.bits);
+                if (d < *margin) *margin = d;
+            }
         oq_linear(&net->out, qm, 1, dst->y, NULL);
         free(ym); free(qm);
     } else {
@@ -552,7 +669,7 @@ void oq_net_run(const oq_net_t *net, const int32_t *tokens, int n_tok, float *y_
     net_state a, b;
     ns_alloc(net, &a); ns_alloc(net, &b);
     for (int i = 0; i < n_tok; ++i) {
-        net_advance(net, &a, tokens[i], &b);
+        net_advance(net, &a, tokens[i], &b, NULL);
         memcpy(y_all + (int64_t)i * net->out.rows, b.y, (size_t)net->out.rows * sizeof(float));
         net_state t = a; a = b; b = t;
     }
@@ -589,14 +706,14 @@ static void hyp_copy(const oq_model_t *M, hyp_t *d, const hyp_t *s)
     if (M->use_ext) ns_copy(&M->lm_ext, &d->ext, &s->ext);
 }
 /* d = s extended by `token` (all three networks advance from s's state). */
-static void hyp_extend(const oq_model_t *M, hyp_t *d, const hyp_t *s, int token, float score)
+static void hyp_extend(const oq_model_t *M, hyp_t *d, const hyp_t *s, int token, float score, double *margin)
 {
     if (d->cap < s->len + 1) { d->cap = s->len + 16; d->tok = (int32_t *)realloc(d->tok, sizeof(int32_t) * (size_t)d->cap); }
     if (s->len) memcpy(d->tok, s->tok, sizeof(int32_t) * (size_t)s->len);
     d->tok[s->len] = token; d->len = s->len + 1; d->score = score;
-    net_advance(&M->pred, &s->pred, token, &d->pred);
-    if (M->use_src) net_advance(&M->lm_src, &s->src, token, &d->src);
-    if (M->use_ext) net_advance(&M->lm_ext, &s->ext, token, &d->ext);
+    net_advance(&M->pred, &s->pred, token, &d->pred, margin);
+    if (M->use_src) net_advance(&M->lm_src, &s->src, token, &d->src, margin);
+    if (M->use_ext) net_advance(&M->lm_ext, &s->ext, token, &d->ext, margin);
 }
 
 /* Time-synchronous beam search with at most max_sym labels per frame, one
@@ -621,13 +738,17 @@ static void hyp_extend(const oq_model_t *M, hyp_t *d, const hyp_t *s, int token,
  * scores [B,W].
  * Pinned by: W=1 vs an independent greedy loop, exhaustive enumeration on a
  * tiny case, permutation of utterances, monotone scores. */
-void oq_decode(const oq_model_t *M, const float *enc_proj, int T, int B, int W, int max_sym,
-               int max_len, int32_t *tokens_out, int32_t *len_out, float *score_out)
+static void decode_core(const oq_model_t *M, const float *enc_proj, int T, int B, int W, int max_sym,
+                        int max_len, int32_t *tokens_out, int32_t *len_out, float *score_out,
+                        double *qmargin, double *smargin)
 {
     const int V = M->V, J = M->joint_out.cols;
+    const int want = qmargin != NULL && smargin != NULL;
 #pragma omp parallel for schedule(dynamic)
     for (int b = 0; b < B; ++b) {
         int nx_cap = W * (max_sym + 1);
+        double qm = INFINITY, sm = INFINITY;   /* bookkeeping only, see oq_decode_margins */
+        double *rowm = (double *)malloc(sizeof(double) * (size_t)W);
         hyp_t *beam = (hyp_t *)malloc(sizeof(hyp_t) * (size_t)W);
         hyp_t *A = (hyp_t *)malloc(sizeof(hyp_t) * (size_t)W);
         hyp_t *A2 = (hyp_t *)malloc(sizeof(hyp_t) * (size_t)W);
@@ -647,7 +768,7 @@ void oq_decode(const oq_model_t *M, const float *enc_proj, int T, int B, int W, 
         /* start hypothesis: zero state advanced on symbol 0 */
         {
             hyp_t zero; hyp_alloc(M, &zero);
-            hyp_extend(M, &beam[0], &zero, 0, 0.0f);
+            hyp_extend(M, &beam[0], &zero, 0, 0.0f, want ? &qm : NULL);
             beam[0].len = 0; /* the start symbol is not part of the label sequence */
             hyp_free(M, &zero);
         }
@@ -665,10 +786,12 @@ void oq_decode(const oq_model_t *M, const float *enc_proj, int T, int B, int W, 
                     if (M->use_src) memcpy(Ls + (int64_t)w * V, h->src.y, sizeof(float) * (size_t)V);
                     if (M->use_ext) memcpy(Le + (int64_t)w * V, h->ext.y, sizeof(float) * (size_t)V);
                 }
-                oq_joint_fuse(enc_proj, frow, P, &M->joint_out, M->inv_s_z,
-                              M->use_src ? Ls : NULL, M->use_ext ? Le : NULL,
-                              M->lambda_src, M->lambda_ext, M->rho, W, M->blank, NULL, NULL, F);
-                oq_beam_step(S, F, 1, W, V, M->blank, v == max_sym, par, tk, ns);
+                joint_fuse_core(enc_proj, frow, P, &M->joint_out, M->inv_s_z,
+                                M->use_src ? Ls : NULL, M->use_ext ? Le : NULL,
+                                M->lambda_src, M->lambda_ext, M->rho, W, M->blank, NULL, NULL, F, want ? rowm : NULL);
+                if (want)
+                    for (int w = 0; w < nA; ++w) if (rowm[w] < qm) qm = rowm[w];
+                beam_step_core(S, F, 1, W, V, M->blank, v == max_sym, par, tk, ns, want ? &sm : NULL);
                 int nA2 = 0;
                 for (int r = 0; r < W; ++r) {
                     if (par[r] < 0) break;
@@ -677,7 +800,7 @@ void oq_decode(const oq_model_t *M, const float *enc_proj, int T, int B, int W, 
                         Nx[nNx].score = ns[r];
                         ++nNx;
                     } else {
-                        hyp_extend(M, &A2[nA2], &A[par[r]], tk[r], ns[r]);
+                        hyp_extend(M, &A2[nA2], &A[par[r]], tk[r], ns[r], want ? &qm : NULL);
                         ++nA2;
                     }
                 }
@@ -697,8 +820,18 @@ void oq_decode(const oq_model_t *M, const float *enc_proj, int T, int B, int W, 
                 used[best] = 1;
                 hyp_copy(M, &beam[n_beam++], &Nx[best]);
             }
+            if (want) {   /* consecutive differences among the new beam and the best candidate left out */
+                float left = -INFINITY;
+                for (int i = 0; i < nNx; ++i) if (!used[i] && Nx[i].score > left) left = Nx[i].score;
+                for (int r = 0; r < n_beam; ++r) {
+                    const float nextv = r + 1 < n_beam ? beam[r + 1].score : left;
+                    if (nextv > -INFINITY && (double)beam[r].score - (double)nextv < sm) sm = (double)beam[r].score - (double)nextv;
+                }
+            }
             free(used);
         }
+        if (want) { qmargin[b] = qm; smargin[b] = sm; }
+        free(rowm);
         for (int w = 0; w < W; ++w) {
             int32_t *dst = tokens_out + ((int64_t)b * W + w) * max_len;
             for (int i = 0; i < max_len; ++i) dst[i] = -1;
@@ -717,6 +850,29 @@ void oq_decode(const oq_model_t *M, const float *enc_proj, int T, int B, int W, 
         free(beam); free(A); free(A2); free(Nx);
         free(S); free(F); free(P); free(Ls); free(Le); free(frow); free(par); free(tk); free(ns);
     }
+}
+
+void oq_decode(const oq_model_t *M, const float *enc_proj, int T, int B, int W, int max_sym,
+               int max_len, int32_t *tokens_out, int32_t *len_out, float *score_out)
+{
+    decode_core(M, enc_proj, T, B, W, max_sym, max_len, tokens_out, len_out, score_out, NULL, NULL);
+}
+
+/* oq_decode plus, per utterance, how far its result is from depending on the last
+ * bits of the arithmetic (bookkeeping for free-running comparisons with an fp32
+ * implementation; the search itself is unchanged):
+ *   qmargin[b]: the smallest oq_tie_distance over every quantizer decision on a
+ *     computed value (hidden states, z, bottleneck output) of a live hypothesis;
+ *   smargin[b]: the smallest difference between consecutive values in any selection
+ *     (among the picks of a round and the best candidate left out; among the new
+ *     beam of a frame and the best entry left out).  0 for an exact tie.
+ * A result is robust to perturbations below both.  Pinned by: a hand-built near-tie
+ * lowers the margin to the planted distance; margins do not change the outputs. */
+void oq_decode_margins(const oq_model_t *M, const float *enc_proj, int T, int B, int W, int max_sym,
+                       int max_len, int32_t *tokens_out, int32_t *len_out, float *score_out,
+                       double *qmargin, double *smargin)
+{
+    decode_core(M, enc_proj, T, B, W, max_sym, max_len, tokens_out, len_out, score_out, qmargin, smargin);
 }
 
 /* Alignment-length synchronous search with recombination (Sec. 2: the paper
@@ -748,15 +904,25 @@ void oq_decode(const oq_model_t *M, const float *enc_proj, int T, int B, int W, 
  * label-wise fusion terms: that is what pins this function (RNN-T forward
  * recursion in numpy).  Also pinned by: permutation of utterances, u_max = 0
  * (all-blank path only).
+ * Parity unpinned: two choices of this function are readings that neither the
+ * paper (which prints no algorithm) nor any pin fixes, because the forward-
+ * recursion pin runs without pruning: (1) the W best candidates are picked
+ * first and equal label sequences are merged afterwards, so a merge frees slots
+ * that stay empty (merging before picking would fill them with further
+ * candidates); (2) the finished list is cut to its W best at every insertion.
  * Outputs as oq_decode; ranks beyond the number of finals are empty. */
 typedef struct { int32_t *tok; int len; float score; } fin_t;
 
-void oq_decode_alsd(const oq_model_t *M, const float *enc_proj, int T, int B, int W, int u_max,
-                    int max_len, int32_t *tokens_out, int32_t *len_out, float *score_out)
+static void decode_alsd_core(const oq_model_t *M, const float *enc_proj, int T, int B, int W, int u_max,
+                             int max_len, int32_t *tokens_out, int32_t *len_out, float *score_out,
+                             double *qmargin, double *smargin)
 {
     const int V = M->V, J = M->joint_out.cols;
+    const int want = qmargin != NULL && smargin != NULL;
 #pragma omp parallel for schedule(dynamic)
     for (int b = 0; b < B; ++b) {
+        double qm = INFINITY, sm = INFINITY;   /* bookkeeping only, see oq_decode_margins */
+        double *rowm = (double *)malloc(sizeof(double) * (size_t)W);
         hyp_t *cur = (hyp_t *)malloc(sizeof(hyp_t) * (size_t)W);
         hyp_t *nxt = (hyp_t *)malloc(sizeof(hyp_t) * (size_t)W);
         for (int w = 0; w < W; ++w) { hyp_alloc(M, &cur[w]); hyp_alloc(M, &nxt[w]); }
@@ -774,7 +940,7 @@ void oq_decode_alsd(const oq_model_t *M, const float *enc_proj, int T, int B, in
         int *lead = (int *)malloc(sizeof(int) * (size_t)W);
         {
             hyp_t zero; hyp_alloc(M, &zero);
-            hyp_extend(M, &cur[0], &zero, 0, 0.0f);
+            hyp_extend(M, &cur[0], &zero, 0, 0.0f, want ? &qm : NULL);
             cur[0].len = 0;
             hyp_free(M, &zero);
         }
@@ -794,9 +960,11 @@ void oq_decode_alsd(const oq_model_t *M, const float *enc_proj, int T, int B, in
                 if (M->use_ext) memcpy(Le + (int64_t)w * V, h->ext.y, sizeof(float) * (size_t)V);
             }
             if (!alive) break;
-            oq_joint_fuse(enc_proj, frow, P, &M->joint_out, M->inv_s_z,
-                          M->use_src ? Ls : NULL, M->use_ext ? Le : NULL,
-                          M->lambda_src, M->lambda_ext, M->rho, W, M->blank, NULL, NULL, F);
+            joint_fuse_core(enc_proj, frow, P, &M->joint_out, M->inv_s_z,
+                            M->use_src ? Ls : NULL, M->use_ext ? Le : NULL,
+                            M->lambda_src, M->lambda_ext, M->rho, W, M->blank, NULL, NULL, F, want ? rowm : NULL);
+            if (want)
+                for (int w = 0; w < W; ++w) if (cur[w].score > -INFINITY && rowm[w] < qm) qm = rowm[w];
             /* finished hypotheses and excluded labels leave the candidate set */
             for (int w = 0; w < W; ++w) {
                 if (!(cur[w].score > -INFINITY)) continue;
@@ -804,6 +972,11 @@ void oq_decode_alsd(const oq_model_t *M, const float *enc_proj, int T, int B, in
                 if (t == T - 1) {
                     const float v = S[w] + F[(int64_t)w * V + M->blank];
                     F[(int64_t)w * V + M->blank] = -INFINITY;
+                    if (want)   /* how close the newcomer is to any final it is ranked against */
+                        for (int q = 0; q < nfin; ++q) {
+                            const double d = fabs((double)fin[q].score - (double)v);
+                            if (d < sm) sm = d;
+                        }
                     /* insert after every final that is at least as good (insertion order on ties) */
                     int pos = nfin;
                     while (pos > 0 && fin[pos - 1].score < v) --pos;
@@ -820,7 +993,7 @@ void oq_decode_alsd(const oq_model_t *M, const float *enc_proj, int T, int B, in
                     for (int k = 0; k < V; ++k)
                         if (k != M->blank) F[(int64_t)w * V + k] = -INFINITY;
             }
-            oq_beam_step(S, F, 1, W, V, M->blank, 0, par, tk, ns);
+            beam_step_core(S, F, 1, W, V, M->blank, 0, par, tk, ns, want ? &sm : NULL);
             /* recombination on the label sequences the picks stand for */
             for (int r = 0; r < W; ++r) {
                 lead[r] = -1;
@@ -853,7 +1026,7 @@ void oq_decode_alsd(const oq_model_t *M, const float *enc_proj, int T, int B, in
                     if (par[q] >= 0 && lead[q] == r) sum += exp((double)ns[q] - m);
                 const float sc = (float)(m + log(sum));
                 if (tk[r] == M->blank) { hyp_copy(M, &nxt[r], &cur[par[r]]); nxt[r].score = sc; }
-                else hyp_extend(M, &nxt[r], &cur[par[r]], tk[r], sc);
+                else hyp_extend(M, &nxt[r], &cur[par[r]], tk[r], sc, want ? &qm : NULL);
             }
             hyp_t *tmp = cur; cur = nxt; nxt = tmp;
         }
@@ -870,11 +1043,28 @@ void oq_decode_alsd(const oq_model_t *M, const float *enc_proj, int T, int B, in
                 score_out[b * W + w] = -INFINITY;
             }
         }
+        if (want) { qmargin[b] = qm; smargin[b] = sm; }
+        free(rowm);
         for (int q = 0; q < nfin; ++q) free(fin[q].tok);
         for (int w = 0; w < W; ++w) { hyp_free(M, &cur[w]); hyp_free(M, &nxt[w]); }
         free(cur); free(nxt); free(fin);
         free(S); free(F); free(P); free(Ls); free(Le); free(frow); free(par); free(tk); free(ns); free(lead);
     }
+}
+
+void oq_decode_alsd(const oq_model_t *M, const float *enc_proj, int T, int B, int W, int u_max,
+                    int max_len, int32_t *tokens_out, int32_t *len_out, float *score_out)
+{
+    decode_alsd_core(M, enc_proj, T, B, W, u_max, max_len, tokens_out, len_out, score_out, NULL, NULL);
+}
+
+/* oq_decode_alsd with the margins of oq_decode_margins; smargin also covers the
+ * ranking of every newly finished hypothesis against the finished list. */
+void oq_decode_alsd_margins(const oq_model_t *M, const float *enc_proj, int T, int B, int W, int u_max,
+                            int max_len, int32_t *tokens_out, int32_t *len_out, float *score_out,
+                            double *qmargin, double *smargin)
+{
+    decode_alsd_core(M, enc_proj, T, B, W, u_max, max_len, tokens_out, len_out, score_out, qmargin, smargin);
 }
 
 /* Score of one fixed alignment, for the exhaustive-search pin: `actions` is a
@@ -888,7 +1078,7 @@ float oq_score_alignment(const oq_model_t *M, const float *enc_proj, int B, int 
     const int V = M->V, J = M->joint_out.cols;
     hyp_t cur, nxt, zero;
     hyp_alloc(M, &cur); hyp_alloc(M, &nxt); hyp_alloc(M, &zero);
-    hyp_extend(M, &cur, &zero, 0, 0.0f);
+    hyp_extend(M, &cur, &zero, 0, 0.0f, NULL);
     cur.len = 0;
     float *F = (float *)malloc(sizeof(float) * (size_t)V);
     (void)J;
@@ -903,7 +1093,7 @@ float oq_score_alignment(const oq_model_t *M, const float *enc_proj, int B, int 
         if (actions[a] == M->blank) {
             ++t;
         } else {
-            hyp_extend(M, &nxt, &cur, actions[a], S);
+            hyp_extend(M, &nxt, &cur, actions[a], S, NULL);
             hyp_t tmp = cur; cur = nxt; nxt = tmp;
         }
     }

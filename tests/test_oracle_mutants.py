@@ -36,8 +36,8 @@ MUTANTS = [
     ("label reward dropped", "                f += (double)rho;\n", ""),
     ("log-softmax without the max shift restored", "lp[k] = x[k] - m - ls;", "lp[k] = x[k] - ls;"),
     ("last index wins a tie in the beam step", "if (best < 0 || val[c] > val[best]) best = c;", "if (best < 0 || val[c] >= val[best]) best = c;"),
-    ("labels allowed in the last round of a frame", "oq_beam_step(S, F, 1, W, V, M->blank, v == max_sym, par, tk, ns);",
-     "oq_beam_step(S, F, 1, W, V, M->blank, 0, par, tk, ns);"),
+    ("labels allowed in the last round of a frame", "beam_step_core(S, F, 1, W, V, M->blank, v == max_sym, par, tk, ns, want ? &sm : NULL);",
+     "beam_step_core(S, F, 1, W, V, M->blank, 0, par, tk, ns, want ? &sm : NULL);"),
     ("blank keeps the old score", "                        Nx[nNx].score = ns[r];\n", ""),
     ("linear layer bias dropped", "(double)s + (P->bias ? (double)P->bias[r] : 0.0);", "(double)s;"),
     ("a blank pick copies the wrong hypothesis", "hyp_copy(M, &Nx[nNx], &A[par[r]]);", "hyp_copy(M, &Nx[nNx], &A[r < nA ? r : 0]);"),
@@ -53,6 +53,18 @@ MUTANTS = [
      "for (int q = 0; q < net->mid.rows; ++q) qm[q] = (int8_t)(ym[q] * net->inv_s_mid);"),
     ("upper LSTM layers of a network see zero state from the layer below",
      "        memcpy(xin, dst->h[l], (size_t)net->layer[l].H);", "        memset(xin, 0, (size_t)maxw);"),
+    ("a layer's initial cell state ignored", "    if (c0) memcpy(c, c0, (size_t)B * H * sizeof(float));\n", ""),
+    ("a layer's initial hidden codes ignored", "    if (h0) memcpy(h, h0, (size_t)B * H);\n", ""),
+    ("tie distance taken on the fp64 product", "const double t = (double)(x * inv_s);", "const double t = (double)x * (double)inv_s;"),
+    ("tie distance on the 8-bit grid not scaled to 4-bit steps", "return fabs(frac - 0.5) * (7.0 / qmax);", "return fabs(frac - 0.5);"),
+    ("clamped values counted as near ties", "    if (t <= -qmax - 1.5 || t >= qmax + 0.5) return INFINITY;\n", ""),
+    ("selection gap ignores the best candidate left out", "            for (int r = 0; r <= W; ++r) {", "            for (int r = 0; r < W; ++r) {"),
+    ("margin of the start-symbol advance dropped", "hyp_extend(M, &beam[0], &zero, 0, 0.0f, want ? &qm : NULL);",
+     "hyp_extend(M, &beam[0], &zero, 0, 0.0f, NULL);"),
+    ("ALSD: margin of the start-symbol advance dropped", "hyp_extend(M, &cur[0], &zero, 0, 0.0f, want ? &qm : NULL);",
+     "hyp_extend(M, &cur[0], &zero, 0, 0.0f, NULL);"),
+    ("z decisions not counted in the margin", "for (int w = 0; w < nA; ++w) if (rowm[w] < qm) qm = rowm[w];",
+     "for (int w = 0; w < nA; ++w) if (rowm[w] < 0.0) qm = rowm[w];"),
 ]
 
 FILES = ["oracle", "tests/test_oracle_pins.py", "tests/conftest.py", "tests/golden", "paper_2206_07882_amd/synth.py",

@@ -706,3 +706,148 @@ def test_quantizer_properties_over_random_boundaries():
         assert np.all(np.abs(x[inside].astype(np.float64) - q[inside] * step) <= step / 2 * (1 + 1e-3) + 1e-7)
 
     check()
+
+
+# ------------------------------------------------------------------ initial state of a layer
+
+def test_lstm_layer_initial_state_closed_form_and_continuation():
+    # zero weights and a given c0: c_1 = f c0 + i g exactly (h0 meets zero weights), so the layer started from
+    # (h0, c0) must give c_t = f^t c0 + i g (1 - f^t)/(1 - f); and a layer run in two halves, the second started
+    # from the first's final state, must equal the layer run in one piece (any weights).
+    H, I, T, B = 5, 4, 9, 3
+    rng = np.random.default_rng(41)
+    b = rng.standard_normal(4 * H)
+    L0 = oracle.Lstm(np.zeros((4 * H, I)), np.ones(4 * H), np.zeros((4 * H, H)), np.ones(4 * H), b, 0.3)
+    x = rng.integers(-7, 8, (T, B, I)).astype(np.int8)
+    h0 = rng.integers(-7, 8, (B, H)).astype(np.int8)
+    c0 = rng.standard_normal((B, H)).astype(np.float32)
+    _, _, _, c_all = oracle.lstm_layer(L0, x, h0=h0, c0=c0, want_c_all=True)
+    b32 = b.astype(np.float32).astype(np.float64)
+    sg = lambda v: 1 / (1 + np.exp(-v))
+    i, f, g = sg(b32[:H]), sg(b32[H:2 * H]), np.tanh(b32[2 * H:3 * H])
+    for t in range(1, T + 1):
+        c = f ** t * c0.astype(np.float64) + i * g * (1 - f ** t) / (1 - f)
+        assert np.allclose(c_all[t - 1], c, rtol=3e-6, atol=2e-7)
+    L = _rand_lstm(rng, I, H)
+    for reverse in (False, True):
+        whole, hl, cl, _ = oracle.lstm_layer(L, x, reverse=reverse, h0=h0, c0=c0)
+        first = x[T - 4:] if reverse else x[:5]
+        second = x[:T - 4] if reverse else x[5:]
+        a, ha, ca, _ = oracle.lstm_layer(L, first, reverse=reverse, h0=h0, c0=c0)
+        bb, hb, cb, _ = oracle.lstm_layer(L, second, reverse=reverse, h0=ha, c0=ca)
+        joined = np.concatenate([bb, a]) if reverse else np.concatenate([a, bb])
+        assert np.array_equal(whole, joined) and np.array_equal(hl, hb) and np.array_equal(cl, cb)
+        # the initial hidden codes matter too (non-zero recurrent weights), and None means zero
+        other, _, _, _ = oracle.lstm_layer(L, x, reverse=reverse, h0=np.zeros_like(h0), c0=c0)
+        assert not np.array_equal(other, whole)
+        z1, _, _, _ = oracle.lstm_layer(L, x, reverse=reverse)
+        z2, _, _, _ = oracle.lstm_layer(L, x, reverse=reverse, h0=np.zeros_like(h0), c0=np.zeros_like(c0))
+        assert np.array_equal(z1, z2)
+
+
+# ------------------------------------------------------------------ tie and selection margins (bookkeeping)
+
+def _np_tie_distance(x, inv_s, qmax=7.0):
+    t = (np.asarray(x, np.float32) * np.float32(inv_s)).astype(np.float64)
+    d = np.abs(t - np.floor(t) - 0.5) * (7.0 / qmax)
+    return np.where((t <= -qmax - 1.5) | (t >= qmax + 0.5), np.inf, d)
+
+
+def test_tie_distance_hand_values():
+    assert oracle.tie_distance(0.5, 7.0) == 0.0                       # 3.5: a tie
+    assert oracle.tie_distance(np.float32(2.5) / np.float32(7), 7.0) < 3e-7
+    assert oracle.tie_distance(1.0, 7.0) == 0.5                       # a grid value is as far from a tie as can be
+    assert abs(oracle.tie_distance(0.3, 1.0) - 0.2) < 1e-7            # rounds to 0, 0.2 below the tie at 0.5
+    assert abs(oracle.tie_distance(-1.2, 7.0) - 0.1) < 1e-5           # -8.4: 0.1 from the tie between -8 and the clamp at -8.5
+    assert oracle.tie_distance(1.5, 7.0) == math.inf                  # 10.5: the clamp decides
+    assert oracle.tie_distance(-1.3, 7.0) == math.inf                 # -9.1
+    assert abs(oracle.tie_distance(1.071, 7.0) - 0.003) < 1e-5        # 7.497: the last tie before the clamp, at 7.5
+    assert oracle.tie_distance(0.5, 127.0, 8) == 0.0                  # 63.5
+    assert abs(oracle.tie_distance(0.5 + 0.25 / 127, 127.0, 8) - 0.25 * 7 / 127) < 1e-6   # in 4-bit code steps
+    assert oracle.tie_distance(2.0, 127.0, 8) == math.inf
+
+
+def test_layer_margin_is_the_smallest_tie_distance_of_each_utterance():
+    rng = np.random.default_rng(42)
+    I, H, T, B = 6, 8, 11, 4
+    L = _rand_lstm(rng, I, H)
+    x = rng.integers(-7, 8, (T, B, I)).astype(np.int8)
+    um = np.full(B, np.inf)
+    h_out, _, _, _ = oracle.lstm_layer(L, x, utt_margin=um)
+    plain, _, _, _ = oracle.lstm_layer(L, x)
+    assert np.array_equal(h_out, plain)
+    hp, cp = np.zeros((B, H), np.int8), np.zeros((B, H), np.float32)
+    want = np.full(B, np.inf)
+    for t in range(T):
+        hp, cp, dbg = oracle.lstm_step(L, x[t], hp, cp, debug=True)
+        want = np.minimum(want, _np_tie_distance(dbg["h_real"], 7.0).min(axis=1))
+    assert np.allclose(um, want, rtol=0, atol=1e-12) and np.all(um < 0.5) and len(set(um.tolist())) == B
+    # an already lower entry stays (the argument is lowered, not overwritten)
+    um2 = np.array([0.0, np.inf, np.inf, np.inf])
+    oracle.lstm_layer(L, x, utt_margin=um2)
+    assert um2[0] == 0.0 and np.allclose(um2[1:], want[1:], atol=1e-12)
+
+
+def test_beam_step_gap_against_a_sort():
+    rng = np.random.default_rng(43)
+    B, W, V = 5, 3, 4
+    score = rng.standard_normal((B, W)).astype(np.float32)
+    fused = rng.standard_normal((B * W, V)).astype(np.float32)
+    score[1, 1:] = -np.inf                       # 4 finite candidates: 3 picks + one left out
+    score[2, 1:] = -np.inf; fused[2 * W, 2:] = -np.inf      # 2 finite candidates: nothing left out
+    fused[3 * W, 0] = fused[3 * W, 1] = 50.0     # an exact tie among the picks
+    for force in (False, True):
+        par, tok, ns, gap = oracle.beam_step(score, fused, force_blank=force, want_gap=True)
+        p2, t2, n2 = oracle.beam_step(score, fused, force_blank=force)
+        assert np.array_equal(par, p2) and np.array_equal(tok, t2) and np.array_equal(ns, n2)
+        for b in range(B):
+            val = (score[b][:, None] + fused[b * W:(b + 1) * W]).astype(np.float32)
+            if force:
+                val[:, 1:] = -np.inf
+            v = np.sort(val[np.isfinite(val)].astype(np.float64))[::-1][:W + 1]
+            want = np.min(v[:-1] - v[1:]) if len(v) > 1 else np.inf
+            assert gap[b] == want, (force, b)
+    assert oracle.beam_step(score, fused, want_gap=True)[3][3] == 0.0
+
+
+def test_decode_margins_on_a_path_that_can_be_recomputed():
+    # margins are bookkeeping: same beams with and without them; and with one hypothesis and no labels per frame
+    # (W = 1, max_sym = 0) the path is the start hypothesis at every frame, whose quantizer decisions can be
+    # recomputed one by one: the start-symbol advance of each network and z at every frame.
+    m = _tiny_model(44)
+    rng = np.random.default_rng(45)
+    T, B, J = 6, 3, m.joint_out.cols
+    e = rng.standard_normal((T, B, J)).astype(np.float32)
+    for W, ms in ((1, 0), (3, 2)):
+        a = oracle.decode(m, e, W, ms, max_len=8)
+        bq = oracle.decode(m, e, W, ms, max_len=8, margins=True)
+        assert all(np.array_equal(x, y) for x, y in zip(a, bq[:3]))
+        c = oracle.decode_alsd(m, e, W, 2)
+        d = oracle.decode_alsd(m, e, W, 2, margins=True)
+        assert all(np.array_equal(x, y) for x, y in zip(c, d[:3]))
+        assert np.all(d[3] > 0) and np.all(d[3] < 0.5) and np.all(d[4] >= 0)
+    _, _, _, qm, sm = oracle.decode(m, e, 1, 0, max_len=1, margins=True)
+    start = np.inf
+    for net in (m.pred, m.lm_src, m.lm_ext):
+        xq = oracle.quant_sym4(net.embed[0][None], net.inv_s_e)
+        H = net.layers[0].H
+        _, _, dbg = oracle.lstm_step(net.layers[0], xq, np.zeros((1, H), np.int8), np.zeros((1, H), np.float32), debug=True)
+        start = min(start, _np_tie_distance(dbg["h_real"], 7.0).min())
+    p0 = oracle.net_run(m.pred, np.array([0], np.int32))
+    for b in range(B):
+        rows = np.array([t * B + b for t in range(T)], np.int32)
+        _, z_real = oracle.joint_z(e.reshape(T * B, J), rows, np.repeat(p0, T, axis=0), 7.0)
+        want = min(start, _np_tie_distance(z_real, 7.0).min())
+        assert abs(qm[b] - want) < 1e-12, b
+    assert np.all(np.isinf(sm))     # one candidate per selection: nothing is ranked against anything
+    # a single frame: few z decisions, so for most utterances the start-symbol advance holds the smallest distance
+    e1 = rng.standard_normal((1, 8, J)).astype(np.float32)
+    _, _, _, qm1, _ = oracle.decode(m, e1, 1, 0, max_len=1, margins=True)
+    _, _, _, qa1, _ = oracle.decode_alsd(m, e1, 1, 0, margins=True)
+    assert np.all(qm1 <= start) and (qm1 == start).sum() >= 3 and np.array_equal(qm1, qa1)
+    # a wider beam only adds decisions, and dead slots add none: the margin of utterance b does not depend on
+    # what else is in the batch
+    _, _, _, q3, s3 = oracle.decode(m, e, 3, 2, max_len=8, margins=True)
+    assert np.all(q3 <= qm)
+    _, _, _, q1, s1 = oracle.decode(m, np.ascontiguousarray(e[:, 1:2]), 3, 2, max_len=8, margins=True)
+    assert q1[0] == q3[1] and s1[0] == s3[1]
