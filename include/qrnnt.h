@@ -14,13 +14,24 @@
  *   - Pointers marked [device] must be device memory reachable from the GPU
  *     that is current on the calling thread; pointers marked [host] are host
  *     memory.  The caller owns every buffer, including workspaces; the library
- *     allocates nothing and keeps no state between calls.
+ *     allocates no device memory.  The only state it keeps between calls is what
+ *     it has learned about each device on first use (number of compute units,
+ *     how many workgroups of the persistent recurrence fit at once, kernel
+ *     attributes already set), cached per device; no call's result depends on
+ *     an earlier call.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
  *     All work is enqueued asynchronously; nothing synchronises.
  *   - Every call validates its arguments on the host before launching
  *     anything and returns a qrnnt_status; nothing throws across the boundary.
  *     Validation needs no GPU.
  *   - Activation codes travel as int8 containers holding values in [-8, 7].
+ *     A matrix of activation codes with C columns ([N, I] inputs of an LSTM
+ *     layer, [V, E] embedding tables) is stored with a row pitch of
+ *     qrnnt_act_pitch(C) = C rounded up to a multiple of 16 bytes, so that every
+ *     row starts on a 16-byte boundary; the bytes behind column C may hold
+ *     anything (they meet the zero padding of the packed weights).  Where C is a
+ *     multiple of 16, as every hidden size is, this is the plain [N, C] array.
+ *     qrnnt_quantize_act_rows writes that form from fp32 rows of any width.
  *     Weights only exist as nibble-packed blobs written by qrnnt_pack_int4.
  *   - Quantizer: q = clamp(rne(x * inv_step), -8, 7), product in fp32, ties to
  *     even; step = alpha/7 (symmetric LQ of Sec. 3.1 on a signed 4-bit grid).
@@ -99,7 +110,8 @@ typedef struct {
     float x_scale;          /* step of the input codes */
     float h_scale;          /* step of the hidden codes (FIX +-1: 1/7) */
     float h_inv_scale;      /* 7/alpha of the hidden quantizer (FIX +-1: 7) */
-    int32_t input_size, hidden_size; /* both multiples of 16 */
+    int32_t input_size, hidden_size; /* hidden_size a multiple of 16; input_size any (rows of input codes
+                                        have the pitch qrnnt_act_pitch(input_size)) */
 } qrnnt_lstm;
 
 /* ---- weights: quantize once, pack (Sec. 3.1 MAX per row + symmetric LQ; Sec. 3.2) ---- */
@@ -135,6 +147,17 @@ qrnnt_status qrnnt_quantize_act(const float *x, int64_t n, float inv_scale, int8
 /* The 8-bit form (input of the encoder's first layer, Sec. 3.2): clamp to [-128, 127]. */
 qrnnt_status qrnnt_quantize_act8(const float *x, int64_t n, float inv_scale, int8_t *q, void *stream);
 
+/* Row pitch in bytes of an activation-code matrix with `cols` columns (cols rounded up to a multiple of 16). */
+int32_t qrnnt_act_pitch(int32_t cols);
+
+/* The same quantizer for a matrix: x [device] fp32 [rows, cols] contiguous (any cols) -> q [device] int8 with a
+ * row pitch of ld_out bytes (ld_out >= cols, a multiple of 16; normally qrnnt_act_pitch(cols)); bits = 4 clamps
+ * to [-8, 7], bits = 8 to [-128, 127]; the bytes behind column cols are written as zero.  This is how features of
+ * any width (Sec. 2: 340) and embedding tables of any width (Sec. 2: "a small embedding") reach the LSTM entry
+ * points. */
+qrnnt_status qrnnt_quantize_act_rows(const float *x, int64_t rows, int32_t cols, float inv_scale, int32_t bits,
+                                     int8_t *q, int32_t ld_out, void *stream);
+
 /* ---- quantized linear layer (Sec. 3.2: weights and inputs quantized) ---- */
 
 /* y[n,r] = a_scale * row_scale[r] * sum_k w[r,k]*a[n,k] + bias[r]; with
@@ -157,7 +180,7 @@ qrnnt_status qrnnt_linear_quant(const qrnnt_qmat *w, const float *bias, float a_
 
 /* ---- LSTM: one step for a set of hypotheses (Sec. 3.2, Sec. 3.4) ---- */
 
-/* For n in [0,N): input row x_codes[x_row ? x_row[n] : n] (length I), previous
+/* For n in [0,N): input row x_codes[x_row ? x_row[n] : n] (length I, row pitch qrnnt_act_pitch(I)), previous
  * state from slot s = parent ? parent[n] : n of h_prev/c_prev ([n_slots, H]);
  *   pre = x_scale*s_wih[r]*accx + h_scale*s_whh[r]*acch + bias[r]   (fp32)
  *   i,f,o = sigmoid, g = tanh, c' = f*c + i*g, h' = o*tanh(c'),
@@ -173,7 +196,10 @@ qrnnt_status qrnnt_lstm_step(const qrnnt_lstm *L, const int8_t *x_codes, const i
 
 /* Up to 3 independent steps (e.g. the first layers of the prediction network and
  * of both LMs) in one launch, so that small problems fill the GPU together.
- * Each descriptor carries the arguments of qrnnt_lstm_step (no debug outputs).
+ * Each descriptor carries the arguments of qrnnt_lstm_step; its debug outputs are
+ * optional as there (dbg_accx is not written by a launch that takes the input part
+ * from gx_table: the table holds no integers).  A launch with a debug output runs
+ * the debug build of the kernel variant the same launch would run without one.
  * gx [device] int32 [n_x_rows, 4H] or NULL: the input projection of the rows of
  * x_codes as written by qrnnt_input_projection.  When given, the input part of
  * the step is looked up in it (row x_row ? x_row[n] : n) instead of contracted:
@@ -192,6 +218,8 @@ typedef struct {
     int8_t *h_next;  float *c_next;
     const int32_t *gx;
     const float *gx_table;
+    int32_t *dbg_accx, *dbg_acch;   /* [device] int32 [N, 4H] in source row order, or NULL */
+    float *dbg_gates;               /* [device] fp32 [N, 4H] activated i,f,g,o, or NULL */
 } qrnnt_step_desc;
 
 qrnnt_status qrnnt_lstm_step_group(const qrnnt_step_desc *steps, int32_t n_steps, void *stream);
@@ -219,18 +247,23 @@ qrnnt_status qrnnt_lstm_step_group_listed(const qrnnt_step_desc *steps, int32_t 
 
 size_t qrnnt_lstm_layer_workspace(const qrnnt_lstm *L, int32_t T, int32_t B);
 
-/* x_codes [device] [T,B,I] int8.  The input projection of all T*B frames is
+/* x_codes [device] [T,B,I] int8 (row pitch qrnnt_act_pitch(I)).  The input projection of all T*B frames is
  * one integer GEMM; the recurrence then runs t = 0..T-1 (T-1..0 if reverse).
  * Output codes go to h_out[(t*B + b)*ld_out + col_off + j], so the two
  * directions of a bidirectional layer fill the two halves of [T,B,2H] (both
  * use the FIX +-1 grid, Sec. 3.2).  h0/c0 [device] [B,H] or NULL (zero state,
  * as Sec. 3.4 assumes).  h_last/c_last [device] [B,H] or NULL.  Debug
  * [device] or NULL: dbg_accx int32 [T,B,4H] (source row order), dbg_c_all fp32
- * [T,B,H].  All utterances have length T.  For H <= 1024 (multiple of 8) and
- * B <= 128 the recurrence runs as one persistent kernel whose workgroups exchange
- * hidden codes through the workspace; its waits are bounded, and if one ever runs
- * out the int32 at workspace + workspace_bytes_needed - 256 is set to 1 and the
- * outputs are invalid (it stays 0 otherwise). */
+ * [T,B,H].  All utterances have length T.
+ * The recurrence runs as one persistent kernel (H/16 x ceil(B/16) workgroups per
+ * direction, exchanging hidden codes through the workspace) when H <= 1024 and all
+ * of those workgroups fit on the device at once (as reported by the runtime's
+ * occupancy query for an otherwise idle device); otherwise as one fused launch per
+ * time step (4-bit layers only: an 8-bit layer that cannot take the persistent path
+ * returns QRNNT_ERR_UNSUPPORTED).  The persistent kernel's waits are bounded: if one
+ * ever runs out (e.g. other work keeps part of the device busy), the int32 at
+ * workspace + qrnnt_lstm_layer_workspace(L, T, B) - 256 is set to 1 and the outputs
+ * are invalid; it is 0 after every other call. */
 qrnnt_status qrnnt_lstm_layer(const qrnnt_lstm *L, const int8_t *x_codes, int32_t T, int32_t B, int32_t reverse,
                               const int8_t *h0, const float *c0, int8_t *h_out, int32_t ld_out, int32_t col_off,
                               int8_t *h_last, float *c_last, int32_t *dbg_accx, float *dbg_c_all,
@@ -255,7 +288,10 @@ qrnnt_status qrnnt_lstm_layer_static(const qrnnt_lstm *L, const int8_t *x_codes,
 /* Both directions of a bidirectional layer in one call (zero initial state):
  * forward codes go to columns [0,H) and backward codes to [H,2H) of h_out [device]
  * [T,B,2H].  The two recurrences advance concurrently in one launch.  workspace
- * [device]: qrnnt_bilstm_layer_workspace bytes, 256-byte aligned. */
+ * [device]: qrnnt_bilstm_layer_workspace bytes, 256-byte aligned; it holds the
+ * forward direction's workspace followed by the backward direction's, so there are
+ * two bounded-wait flags: the int32 at workspace + qrnnt_lstm_layer_workspace(fwd, T, B)
+ * - 256 and the int32 at workspace + qrnnt_bilstm_layer_workspace(...) - 256. */
 size_t qrnnt_bilstm_layer_workspace(const qrnnt_lstm *fwd, const qrnnt_lstm *bwd, int32_t T, int32_t B);
 qrnnt_status qrnnt_bilstm_layer(const qrnnt_lstm *fwd, const qrnnt_lstm *bwd, const int8_t *x_codes, int32_t T,
                                 int32_t B, int8_t *h_out, void *workspace, size_t workspace_bytes, void *stream);
@@ -322,7 +358,7 @@ qrnnt_status qrnnt_beam_step(const float *score, const float *fused, int32_t B, 
  * mid_inv_scale at the width of `out`; no activation function, the paper names
  * none) and `out` then reads those codes with step mid_scale. */
 typedef struct {
-    const int8_t *embed_codes;  /* [device] [V, E] embedding rows already quantized (FIX boundary, Sec. 3.2) */
+    const int8_t *embed_codes;  /* [device] [V, E] embedding rows already quantized (FIX boundary, Sec. 3.2), row pitch qrnnt_act_pitch(E) */
     int32_t n_layers;           /* 1..QRNNT_MAX_LAYERS; layer[0].input_size = E */
     qrnnt_lstm layer[QRNNT_MAX_LAYERS];
     qrnnt_qmat out;             /* TILED, [out_rows, H_top] ([out_rows, M] behind a bottleneck) */

@@ -204,7 +204,7 @@ void advance_nets(const qrnnt_model *m, const Plan &p, int src, int dst, int n_e
             if (l == 0) {
                 // The input of layer 0 is one of V embedding rows, so its integer input
                 // projection is a table lookup (exactly the sums the contraction would give).
-                a.x = net->embed_codes;  a.ld_x = L->input_size;  a.x_row = p.token;  a.n_x_rows = n_embed_rows;
+                a.x = net->embed_codes;  a.ld_x = qr_act_pitch(L->input_size);  a.x_row = p.token;  a.n_x_rows = n_embed_rows;
                 a.gx = p.net[k].gx0;  a.ld_gx = 4 * (int64_t)H;  a.tabf = p.net[k].tab0;
             } else {
                 a.x = p.net[k].h[l - 1] + (size_t)dst * N * L->input_size;  a.ld_x = L->input_size;

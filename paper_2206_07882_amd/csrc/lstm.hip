@@ -2,7 +2,7 @@
 // with the whole cell fused behind the contraction (Sec. 3.2: integer MACs for
 // W_ih and W_hh, fp bias and cell state; Sec. 3.4: the hidden state is
 // quantized once, at the cell output).
-#include <cstdlib>
+#include <atomic>
 #include <mutex>
 #include <type_traits>
 
@@ -236,7 +236,7 @@ __global__ __launch_bounds__(256, (USE_GX && !DBG) ? 3 : 2) void lstm_step_pipe_
     int ld_n[NT], ld_s[NT], ld_x[NT], n_of[NT], src_of[NT], gx_of[NT];
     bool n_ok[NT];   // the column stands for a hypothesis (not for padding of the last block)
     int nt_valid = NT;   // this wave's column tiles from here on are padding (list mode)
-    constexpr bool HALF_OK = !DBG;   // the variants that have the narrower instances
+    constexpr bool HALF_OK = true;   // every variant has the narrower instances (the debug build of each included)
     // With a list the problem has *n_rows rows, row j standing for the hypothesis of entry j.
     //  * A workgroup takes 32*NT, 16*NT or 8*NT consecutive entries (width 0, 1, 2): the narrowest width at which the
     //    launch's column blocks still cover the list and the working workgroups do not outnumber the compute units
@@ -530,18 +530,14 @@ template <int MT, int NT, int S, bool USE_GX, bool TAB, bool DBG, bool FAST>
 void launch_pipe_f(const QrStepGroup &g, hipStream_t st)
 {
     using P = QrPipe<MT, NT, S>;
-    static bool configured = false;
+    static std::atomic<int> n_cu_of[QR_MAX_DEVICES];   // 0: not asked yet (also marks "attribute not set yet")
     auto kern = lstm_step_pipe_kernel<MT, NT, S, USE_GX, TAB, DBG, FAST>;
-    if (!configured) {
-        (void)hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, P::LDS_BYTES);
-        configured = true;
-    }
-    static int n_cu = 0;
+    const int dev = qr_current_device();
+    int n_cu = n_cu_of[dev].load(std::memory_order_relaxed);
     if (n_cu == 0) {
-        int dev = 0;
-        if (hipGetDevice(&dev) != hipSuccess ||
-            hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
-            n_cu = 1;
+        (void)hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, P::LDS_BYTES);
+        if (hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n_cu <= 0) n_cu = 1;
+        n_cu_of[dev].store(n_cu, std::memory_order_relaxed);
     }
     QrStepGroup gg = g;
     int gx = 0, max_n = 0;
@@ -556,7 +552,7 @@ void launch_pipe_f(const QrStepGroup &g, hipStream_t st)
     // Without a list the width is chosen here, by the rule the kernel applies to a list's length: the narrowest
     // share per workgroup at which the working workgroups do not outnumber the compute units.
     gg.width = 0;
-    if (!DBG && !g.rows)
+    if (!g.rows)
         for (int w = 1; w <= 2; ++w)
             if (gg.row_blocks * ((max_n + (P::BN >> w) - 1) / (P::BN >> w)) <= n_cu) gg.width = w;
     const int per = P::BN >> gg.width;
@@ -579,7 +575,11 @@ void launch_pipe(const QrStepGroup &g, hipStream_t st)
         fast = fast && a.H % (8 * MT) == 0 && a.N % P::BN == 0 && a.H % QRNNT_KCHUNK == 0 &&
                (USE_GX || a.I % QRNNT_KCHUNK == 0);
     }
-    if (dbg) launch_pipe_f<MT, NT, S, USE_GX, false, true, false>(g, st);
+    // with debug outputs: the debug build of the same variant (same body, same tile walk, same narrow instances)
+    if (dbg && USE_GX && tab && fast) launch_pipe_f<MT, NT, S, USE_GX, USE_GX, true, true>(g, st);
+    else if (dbg && USE_GX && tab) launch_pipe_f<MT, NT, S, USE_GX, USE_GX, true, false>(g, st);
+    else if (dbg && fast) launch_pipe_f<MT, NT, S, USE_GX, false, true, true>(g, st);
+    else if (dbg) launch_pipe_f<MT, NT, S, USE_GX, false, true, false>(g, st);
     else if (USE_GX && tab && fast) launch_pipe_f<MT, NT, S, USE_GX, USE_GX, false, true>(g, st);
     else if (USE_GX && tab) launch_pipe_f<MT, NT, S, USE_GX, USE_GX, false, false>(g, st);
     else if (fast) launch_pipe_f<MT, NT, S, USE_GX, false, false, true>(g, st);
@@ -673,20 +673,22 @@ void launch_gx_pipe(const qrnnt_lstm *L, const int8_t *x_codes, int M, int32_t *
     const int nkc = qr_round_up(I, QRNNT_KCHUNK) / QRNNT_KCHUNK;
     const int nbx = (n_row_tiles + 2 * MT - 1) / (2 * MT), nby = (M + P::BN - 1) / P::BN;
     dim3 grid((unsigned)(nbx * 8 * ((nby + 7) / 8)));
-    static bool configured = false;
-    if (!configured) {
+    static std::atomic<bool> configured[QR_MAX_DEVICES];
+    const int dev = qr_current_device();
+    if (!configured[dev].load(std::memory_order_relaxed)) {
         (void)hipFuncSetAttribute((const void *)gx_gemm_pipe_kernel<MT, NT, S, true, W8>,
                                   hipFuncAttributeMaxDynamicSharedMemorySize, P::LDS_BYTES);
         (void)hipFuncSetAttribute((const void *)gx_gemm_pipe_kernel<MT, NT, S, false, W8>,
                                   hipFuncAttributeMaxDynamicSharedMemorySize, P::LDS_BYTES);
-        configured = true;
+        configured[dev].store(true, std::memory_order_relaxed);
     }
+    const int64_t ld_x = qr_act_pitch(I);
     if (I % QRNNT_KCHUNK)
         gx_gemm_pipe_kernel<MT, NT, S, true, W8><<<grid, 256, P::LDS_BYTES, st>>>((const v4i *)L->w_ih.packed, nkc, n_row_tiles,
-                                                                                 x_codes, I, M, I, gx, H, dbg_accx);
+                                                                                 x_codes, ld_x, M, I, gx, H, dbg_accx);
     else
         gx_gemm_pipe_kernel<MT, NT, S, false, W8><<<grid, 256, P::LDS_BYTES, st>>>((const v4i *)L->w_ih.packed, nkc, n_row_tiles,
-                                                                                  x_codes, I, M, I, gx, H, dbg_accx);
+                                                                                  x_codes, ld_x, M, I, gx, H, dbg_accx);
 }
 
 // fp32 form of a precomputed input projection: tab[m, r'] = k * (x_scale * s_wih[r] * gx[m, r'] + bias[r]),
@@ -722,7 +724,7 @@ qrnnt_status qr_check_lstm(const qrnnt_lstm *L)
     QR_REQUIRE(qr_aligned(L->bias, 16) && qr_aligned(L->w_ih.row_scale, 16) && qr_aligned(L->w_hh.row_scale, 16),
                QRNNT_ERR_ALIGN);
     QR_REQUIRE(L->input_size > 0 && L->hidden_size > 0, QRNNT_ERR_SHAPE);
-    QR_REQUIRE(L->input_size % 16 == 0 && L->hidden_size % 16 == 0, QRNNT_ERR_SHAPE);
+    QR_REQUIRE(L->hidden_size % 16 == 0, QRNNT_ERR_SHAPE);   // any input size: its rows are stored with a pitch of qr_act_pitch
     QR_REQUIRE(L->w_ih.rows == 4 * L->hidden_size && L->w_hh.rows == 4 * L->hidden_size, QRNNT_ERR_SHAPE);
     QR_REQUIRE(L->w_ih.cols == L->input_size && L->w_hh.cols == L->hidden_size, QRNNT_ERR_SHAPE);
     QR_REQUIRE(L->x_scale > 0.0f && L->h_scale > 0.0f && L->h_inv_scale > 0.0f, QRNNT_ERR_RANGE);
@@ -794,7 +796,7 @@ static qrnnt_status make_step_args(QrStepArgs &a, const qrnnt_lstm *L, const int
     QR_REQUIRE((const void *)h_next != (const void *)h_prev && c_next != c_prev, QRNNT_ERR_RANGE);
     a = QrStepArgs{};
     qr_fill_lstm_weights(a, L);
-    a.x = x_codes;  a.ld_x = L->input_size;  a.x_row = x_row;  a.n_x_rows = n_x_rows;
+    a.x = x_codes;  a.ld_x = qr_act_pitch(L->input_size);  a.x_row = x_row;  a.n_x_rows = n_x_rows;
     a.parent = parent;  a.n_slots = n_slots;
     a.h_prev = h_prev;  a.ld_hp = L->hidden_size;  a.c_prev = c_prev;  a.active = active;
     a.h_next = h_next;  a.ld_hn = L->hidden_size;  a.c_next = c_next;
@@ -844,6 +846,7 @@ qrnnt_status step_group(const qrnnt_step_desc *steps, int32_t n_steps, const int
         QR_REQUIRE(d.gx_table == nullptr || d.gx != nullptr, QRNNT_ERR_NULL);
         QR_REQUIRE(qr_aligned(d.gx_table, 16), QRNNT_ERR_ALIGN);
         g.p[i].gx = d.gx;  g.p[i].ld_gx = 4 * (int64_t)d.L->hidden_size;  g.p[i].tabf = d.gx_table;
+        g.p[i].dbg_accx = d.dbg_accx;  g.p[i].dbg_acch = d.dbg_acch;  g.p[i].dbg_gates = d.dbg_gates;
     }
     qr_launch_lstm_step_group(g, steps[0].gx != nullptr, (hipStream_t)stream);
     return qr_launch_status();
@@ -953,8 +956,7 @@ qrnnt_status run_layer(const LayerCall *calls, int n, const int8_t *x_codes, int
                        hipStream_t st)
 {
     const int H = calls[0].L->hidden_size;
-    static const bool no_persist = getenv("QRNNT_STEPWISE_RECURRENCE") != nullptr;
-    bool persist = !no_persist && qr_rec_supported(H, B);
+    bool persist = qr_rec_supported(H, B);
     for (int d = 1; d < n; ++d) persist = persist && calls[d].L->hidden_size == H;
     bool any8 = false;
     for (int d = 0; d < n; ++d) any8 = any8 || qr_bits(&calls[d].L->w_hh) == 8;
@@ -1004,6 +1006,7 @@ qrnnt_status run_layer(const LayerCall *calls, int n, const int8_t *x_codes, int
         QrStepArgs a = {};
         qr_fill_lstm_weights(a, L);
         a.ld_gx = 4 * (int64_t)H;
+        a.n_x_rows = B;   // rows of the step's slice of gx (row indices are clamped into [0, n_x_rows))
         a.n_slots = B;
         a.N = B;
         a.ld_hn = ld_out;
@@ -1084,7 +1087,6 @@ extern "C" qrnnt_status qrnnt_bilstm_layer(const qrnnt_lstm *fwd, const qrnnt_ls
 static __device__ __align__(256) unsigned char scratch[QR_STATIC_WS_BYTES];
 
 namespace {
-constexpr int QR_MAX_DEVICES = 64;
 std::mutex scratch_mutex;
 void *scratch_ptr[QR_MAX_DEVICES];   // per device: address of `scratch` on that device (nullptr: not asked yet)
 

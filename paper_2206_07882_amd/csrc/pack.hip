@@ -19,7 +19,7 @@ extern "C" const char *qrnnt_status_str(qrnnt_status s)
     return "unknown status";
 }
 
-extern "C" uint32_t qrnnt_abi_version(void) { return 2u; }
+extern "C" uint32_t qrnnt_abi_version(void) { return 3u; }
 
 static size_t pack_bytes(int32_t rows, int32_t cols, int32_t layout, int bits)
 {
@@ -364,5 +364,36 @@ extern "C" qrnnt_status qrnnt_quantize_act(const float *x, int64_t n, float inv_
     QR_REQUIRE(qr_aligned(x, 16) && qr_aligned(q, 4), QRNNT_ERR_ALIGN);
     const int64_t n4 = (n + 3) / 4;
     quantize_kernel<<<(unsigned)((n4 + 255) / 256), 256, 0, (hipStream_t)stream>>>(x, n, inv_scale, q);
+    return qr_launch_status();
+}
+
+// rows x cols fp32 (contiguous) -> codes with a row pitch of ld_out bytes; one thread per 4 output bytes, the
+// columns behind `cols` are written as zero.
+__global__ __launch_bounds__(256) void quantize_rows_kernel(const float *__restrict__ x, int64_t rows, int cols, int ld_out,
+                                                             float inv, int bits, int8_t *__restrict__ q)
+{
+    const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int wpr = ld_out >> 2;
+    if (idx >= rows * wpr) return;
+    const int64_t r = idx / wpr;
+    const int c0 = (int)(idx - r * wpr) * 4;
+    uint32_t w = 0;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+        if (c0 + i < cols) w |= (uint32_t)(qr_quant(x[r * cols + c0 + i], inv, bits) & 0xFF) << (8 * i);
+    *(uint32_t *)(q + r * ld_out + c0) = w;
+}
+
+extern "C" int32_t qrnnt_act_pitch(int32_t cols) { return cols > 0 ? qr_act_pitch(cols) : 0; }
+
+extern "C" qrnnt_status qrnnt_quantize_act_rows(const float *x, int64_t rows, int32_t cols, float inv_scale, int32_t bits,
+                                                int8_t *q, int32_t ld_out, void *stream)
+{
+    QR_REQUIRE(x != nullptr && q != nullptr, QRNNT_ERR_NULL);
+    QR_REQUIRE(rows > 0 && cols > 0 && ld_out >= cols && ld_out % 16 == 0, QRNNT_ERR_SHAPE);
+    QR_REQUIRE(inv_scale > 0.0f && (bits == 4 || bits == 8), QRNNT_ERR_RANGE);
+    QR_REQUIRE(qr_aligned(x, 4) && qr_aligned(q, 16), QRNNT_ERR_ALIGN);
+    const int64_t n = rows * (ld_out >> 2);
+    quantize_rows_kernel<<<(unsigned)((n + 255) / 256), 256, 0, (hipStream_t)stream>>>(x, rows, cols, ld_out, inv_scale, bits, q);
     return qr_launch_status();
 }

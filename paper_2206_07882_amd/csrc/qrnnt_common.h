@@ -26,6 +26,20 @@ __host__ __device__ static inline int qr_gates_tiled_row(int cell, int gate)
 }
 static inline bool qr_aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
 
+// Row pitch in bytes of an activation-code matrix with `cols` columns: rows start on 16-byte boundaries, the
+// columns behind `cols` are padding that may hold anything (it meets the zero padding of the packed weights).
+__host__ __device__ static inline int qr_act_pitch(int cols) { return qr_round_up(cols, 16); }
+
+// What the launchers cache about a device (compute units, occupancy of a kernel, "attribute already set") is kept
+// per device, indexed by the device that is current on the calling thread.
+#define QR_MAX_DEVICES 64
+static inline int qr_current_device()
+{
+    int d = 0;
+    if (hipGetDevice(&d) != hipSuccess || d < 0 || d >= QR_MAX_DEVICES) d = 0;
+    return d;
+}
+
 #define QR_REQUIRE(cond, err) \
     do {                      \
         if (!(cond)) return (err); \

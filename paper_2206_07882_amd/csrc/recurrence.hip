@@ -22,6 +22,8 @@
 // flag is set and the workgroup leaves the loop, so the grid always drains.
 #include <hip/hip_runtime.h>
 
+#include <atomic>
+
 #include "kernels.h"
 
 namespace {
@@ -205,15 +207,18 @@ bool launch_rec_t(const QrRecGroup &g, hipStream_t st)
     const int H = g.d[0].H, B = g.d[0].B;
     dim3 grid(H / 16, (B + 15) / 16, g.n);
     // every workgroup spins on its peers: all of them must fit on the device at once
-    static int per_cu = -1, n_cu = 0;
-    if (per_cu < 0) {
-        int dev = 0;
-        hipDeviceProp_t prop;
-        if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) return false;
-        n_cu = prop.multiProcessorCount;
-        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, lstm_rec_kernel<KW>, 256, 0) != hipSuccess) per_cu = 0;
+    static std::atomic<long long> resident_of[QR_MAX_DEVICES];   // workgroups the device holds at once; 0: not asked yet
+    const int dev = qr_current_device();
+    long long resident = resident_of[dev].load(std::memory_order_relaxed);
+    if (resident == 0) {
+        int n_cu = 0, per_cu = 0;
+        if (hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return false;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, lstm_rec_kernel<KW>, 256, 0) != hipSuccess) return false;
+        resident = (long long)per_cu * n_cu;
+        if (resident <= 0) return false;
+        resident_of[dev].store(resident, std::memory_order_relaxed);
     }
-    if ((long long)grid.x * grid.y * grid.z > (long long)per_cu * n_cu) return false;
+    if ((long long)grid.x * grid.y * grid.z > resident) return false;
     lstm_rec_kernel<KW><<<grid, 256, 0, st>>>(g);
     return true;
 }

@@ -41,7 +41,7 @@ def net_from_float(f, alpha_e: float, log_softmax: bool, device="cuda:0", out_bi
     """out_bits = 8: the output layer's weights at 8 bits (Sec. 3.2, the RNN-T's linear layers); its input
     stays the top layer's hidden codes, quantized once at the cell output (Sec. 3.4)."""
     s_e, inv_e = act_scale(alpha_e)
-    embed_codes = q.quantize_act(_dev(f.embed, device), inv_e)
+    embed_codes = q.quantize_act_rows(_dev(f.embed, device), inv_e)   # [V, act_pitch(E)]
     layers = [lstm_from_float(lf, s_e if i == 0 else S_H, device) for i, lf in enumerate(f.layers)]
     out = _pack(_dev(f.out.w, device), q.LAYOUT_TILED, out_bits)
     mid = getattr(f, "mid", None)
@@ -87,6 +87,8 @@ class Encoder:
         self.proj_a_scale = S_H8 if (self.mixed and len(m.enc_layers) == 1) else S_H
         self.proj_bias = _dev(m.enc_proj.bias, device)
         self._ws: Optional[torch.Tensor] = None
+        # bounded-wait flags of the persistent recurrence, one per layer-direction, as the last forward left them
+        self._flags = torch.zeros(sum(len(d) for d in self.layers), dtype=torch.int32, device=device)
 
     def workspace(self, T: int, B: int, device) -> torch.Tensor:
         need = max(sum(q.lstm_layer_workspace(L, T, B) for L in dirs) for dirs in self.layers)
@@ -98,14 +100,29 @@ class Encoder:
         """feats [T,B,D] fp32 on the device -> (codes [T,B,dirs*H], e [T,B,J] fp32)."""
         T, B, _ = feats.shape
         ws = self.workspace(T, B, feats.device)
-        x = q.quantize_act8(feats, self.inv_s_x) if self.mixed else q.quantize_act(feats, self.inv_s_x)
+        x = q.quantize_act_rows(feats, self.inv_s_x, 8 if self.mixed else 4)   # [T, B, act_pitch(D)]
+        k = 0
         for dirs in self.layers:
             H = dirs[0].H
             out = torch.empty((T, B, H * len(dirs)), dtype=torch.int8, device=feats.device)
+            ends = []   # where each direction's workspace ends: its flag sits 256 bytes before
+            for L in dirs:
+                ends.append((ends[-1] if ends else 0) + q.lstm_layer_workspace(L, T, B))
             if len(dirs) == 2:
                 q.bilstm_layer(dirs[0], dirs[1], x, h_out=out, workspace=ws)
             else:
                 q.lstm_layer(dirs[0], x, h_out=out, col_off=0, workspace=ws)
+            for end in ends:   # the workspace is reused by the next layer: keep the flag (4 bytes, device to device)
+                self._flags[k:k + 1].copy_(ws[end - 256:end - 252].view(torch.int32))
+                k += 1
             x = out
         e = q.linear(self.proj, self.proj_bias, self.proj_a_scale, x.reshape(T * B, -1)).reshape(T, B, -1)
         return x, e
+
+    def check(self) -> None:
+        """Raises if a bounded wait of the persistent recurrence ran out in the last forward (its outputs are then
+        invalid).  One small device-to-host copy: call it outside timed regions."""
+        flags = self._flags.cpu().tolist()
+        if any(flags):
+            raise RuntimeError(f"persistent recurrence: a bounded wait ran out (flags per layer-direction: {flags}); "
+                               "was other work running on the device?")

@@ -58,7 +58,7 @@ class CModel(C.Structure):
 
 
 EXPORTS = ["qrnnt_status_str", "qrnnt_abi_version", "qrnnt_pack_int4_bytes", "qrnnt_pack_int4", "qrnnt_unpack_int4",
-           "qrnnt_pack_int8_bytes", "qrnnt_pack_int8", "qrnnt_quantize_act8",
+           "qrnnt_pack_int8_bytes", "qrnnt_pack_int8", "qrnnt_quantize_act8", "qrnnt_act_pitch", "qrnnt_quantize_act_rows",
            "qrnnt_quantize_act", "qrnnt_linear", "qrnnt_linear_quant", "qrnnt_lstm_step", "qrnnt_lstm_layer_workspace", "qrnnt_lstm_layer",
            "qrnnt_input_projection", "qrnnt_input_table", "qrnnt_lstm_step_group", "qrnnt_lstm_step_group_listed",
            "qrnnt_bilstm_layer_workspace", "qrnnt_bilstm_layer", "qrnnt_lstm_layer_static",
@@ -82,8 +82,8 @@ def load():
         lib.qrnnt_pack_int4_bytes.argtypes = [C.c_int32, C.c_int32, C.c_int32]
         lib.qrnnt_pack_int8_bytes.restype = C.c_size_t
         lib.qrnnt_pack_int8_bytes.argtypes = [C.c_int32, C.c_int32, C.c_int32]
-        if lib.qrnnt_abi_version() != 2:
-            raise RuntimeError(f"{LIB_PATH} has ABI version {lib.qrnnt_abi_version()}, this binding needs 2: rebuild")
+        if lib.qrnnt_abi_version() != 3:
+            raise RuntimeError(f"{LIB_PATH} has ABI version {lib.qrnnt_abi_version()}, this binding needs 3: rebuild")
         lib.qrnnt_lstm_layer_workspace.restype = C.c_size_t
         lib.qrnnt_lstm_layer_workspace.argtypes = [C.c_void_p, C.c_int32, C.c_int32]
         lib.qrnnt_bilstm_layer_workspace.restype = C.c_size_t
@@ -183,6 +183,21 @@ def quantize_act8(x: torch.Tensor, inv_scale: float) -> torch.Tensor:
     return q
 
 
+def act_pitch(cols: int) -> int:
+    return int(load().qrnnt_act_pitch(C.c_int32(cols)))
+
+
+def quantize_act_rows(x: torch.Tensor, inv_scale: float, bits: int = 4) -> torch.Tensor:
+    """fp32 [..., cols] -> codes [..., act_pitch(cols)] (pad bytes zero): the form every LSTM entry point reads."""
+    cols = x.shape[-1]
+    rows = x.numel() // cols
+    ld = act_pitch(cols)
+    q = torch.empty(tuple(x.shape[:-1]) + (ld,), dtype=torch.int8, device=x.device)
+    _check(load().qrnnt_quantize_act_rows(_ptr(x, torch.float32), C.c_int64(rows), C.c_int32(cols), C.c_float(inv_scale),
+                                          C.c_int32(bits), _ptr(q), C.c_int32(ld), _stream()), "qrnnt_quantize_act_rows")
+    return q
+
+
 def linear(w: QMat, bias: Optional[torch.Tensor], a_scale: float, a: torch.Tensor, log_softmax: bool = False,
            want_acc: bool = False):
     N = a.shape[0]
@@ -259,7 +274,8 @@ class CStepDesc(C.Structure):
     _fields_ = [("L", C.c_void_p), ("x_codes", C.c_void_p), ("x_row", C.c_void_p), ("n_x_rows", C.c_int32),
                 ("parent", C.c_void_p), ("h_prev", C.c_void_p), ("c_prev", C.c_void_p), ("n_slots", C.c_int32),
                 ("active", C.c_void_p), ("N", C.c_int32), ("h_next", C.c_void_p), ("c_next", C.c_void_p),
-                ("gx", C.c_void_p), ("gx_table", C.c_void_p)]
+                ("gx", C.c_void_p), ("gx_table", C.c_void_p), ("dbg_accx", C.c_void_p), ("dbg_acch", C.c_void_p),
+                ("dbg_gates", C.c_void_p)]
 
 
 class StepGroup:
@@ -267,7 +283,8 @@ class StepGroup:
 
     def __init__(self, steps):
         """steps: list of dicts with keys L, x_codes, h_prev, c_prev, h_next, c_next, N and optional x_row, parent,
-        active, gx (the input projection of the rows of x_codes, see input_projection) and gx_table (input_table)."""
+        active, gx (the input projection of the rows of x_codes, see input_projection), gx_table (input_table) and the
+        debug outputs dbg_accx / dbg_acch (int32 [N, 4H]) / dbg_gates (fp32 [N, 4H])."""
         self._keep = []
         self.n = len(steps)
         self.arr = (CStepDesc * self.n)()
@@ -278,7 +295,7 @@ class StepGroup:
             self.arr[i] = CStepDesc(C.addressof(cl), p(d["x_codes"]), p(d.get("x_row")), d["x_codes"].shape[0],
                                     p(d.get("parent")), p(d["h_prev"]), p(d["c_prev"]), d["h_prev"].shape[0],
                                     p(d.get("active")), d["N"], p(d["h_next"]), p(d["c_next"]), p(d.get("gx")),
-                                    p(d.get("gx_table")))
+                                    p(d.get("gx_table")), p(d.get("dbg_accx")), p(d.get("dbg_acch")), p(d.get("dbg_gates")))
 
     def launch(self, list=None, n_list=None):
         """list [>= N, 4] int32 and n_list [1] int32 (device): only the listed hypotheses advance

@@ -82,12 +82,9 @@ def _linear(rng, rows, cols, std=None):
                    bias=(rng.standard_normal(rows) * 0.1).astype(np.float32))
 
 
-def _net(rng, V, E, hidden, n_layers, out_rows, std=None, E_used=None, mid=None):
-    """E_used < E: an E_used-dimensional embedding zero-padded to E columns (the kernels want a
-    multiple of 16).  mid: width of a bottleneck layer between the LSTM stack and the output layer."""
+def _net(rng, V, E, hidden, n_layers, out_rows, std=None, mid=None):
+    """mid: width of a bottleneck layer between the LSTM stack and the output layer."""
     embed = (rng.standard_normal((V, E)) * 0.5).astype(np.float32)
-    if E_used is not None:
-        embed[:, E_used:] = 0.0
     layers = []
     for l in range(n_layers):
         layers.append(_lstm(rng, E if l == 0 else hidden, hidden, std, std))
@@ -126,20 +123,21 @@ def make_model(config: int, *, enc_layers: Optional[int] = None, weight_std: flo
         return m
     V, J = 46, 256
     if config == 5:
-        # The shapes of Sec. 2 (all 4-bit here): 340 input features (zero-padded to 352), prediction network
-        # and source LM 1 x 768 cells over a ~10-dimensional embedding (the parameter counts of Sec. 2 imply
-        # that size; padded to 16), external LM 2 x 2048 cells + bottleneck 256, and the fusion weights of
-        # Eq. 1 (mu = 0.7 on the external LM, lambda = 0.5 on the source LM, rho = 0.2 per label).
-        m = ModelF(name="cfg5-paper-shapes", V=V, J=J, feat_dim=352, lambda_src=0.5, lambda_ext=0.7, rho=0.2)
+        # The shapes of Sec. 2 (all 4-bit here): 340 input features, prediction network and source LM 1 x 768
+        # cells over a 10-dimensional embedding, external LM 2 x 2048 cells over a 15-dimensional embedding +
+        # bottleneck 256 (the parameter counts of Sec. 2, 2.6 M and 51.0 M, imply those embedding sizes), and
+        # the fusion weights of Eq. 1 (mu = 0.7 on the external LM, lambda = 0.5 on the source LM, rho = 0.2
+        # per label).
+        m = ModelF(name="cfg5-paper-shapes", V=V, J=J, feat_dim=340, lambda_src=0.5, lambda_ext=0.7, rho=0.2)
         nl = 6 if enc_layers is None else enc_layers
         for l in range(nl):
-            I = 352 if l == 0 else 1280
+            I = 340 if l == 0 else 1280
             m.enc_layers.append([_lstm(rng, I, 640), _lstm(rng, I, 640)])
         m.enc_proj = _linear(rng, J, 1280)
-        m.pred = _net(rng, V, 16, 768, 1, J, E_used=10)
+        m.pred = _net(rng, V, 10, 768, 1, J)
         m.joint_out = _linear(rng, V, J)
-        m.lm_src = _net(rng, V, 16, 768, 1, V, E_used=10)
-        m.lm_ext = _net(rng, V, 16, 2048, 2, V, mid=256)
+        m.lm_src = _net(rng, V, 10, 768, 1, V)
+        m.lm_ext = _net(rng, V, 15, 2048, 2, V, mid=256)
         return m
     m = ModelF(name=f"cfg{config}", V=V, J=J, feat_dim=240)
     if config in (1, 4):
@@ -164,10 +162,7 @@ def make_model(config: int, *, enc_layers: Optional[int] = None, weight_std: flo
 def features(config: int, T: int, B: int, dim: int) -> np.ndarray:
     """Acoustic features [T, B, dim] ~ N(0,1)."""
     rng = np.random.default_rng(BASE_SEED + config + 1000)
-    x = rng.standard_normal((T, B, dim)).astype(np.float32)
-    if config == 5:
-        x[:, :, 340:] = 0.0   # 340 features, zero-padded
-    return x
+    return rng.standard_normal((T, B, dim)).astype(np.float32)
 
 
 def codes(seed: int, shape, lo: int = -7, hi: int = 7) -> np.ndarray:

@@ -24,7 +24,7 @@ def test_library_exports_every_declared_symbol():
     for n in names:
         assert hasattr(lib, n), f"{n} is declared in qrnnt.h but not exported"
     assert sorted(qrnnt.EXPORTS) == names
-    assert lib.qrnnt_abi_version() == 2
+    assert lib.qrnnt_abi_version() == 3
 
 
 def test_pack_bytes_formula():

@@ -1,8 +1,8 @@
 """Configurations 2 and 3 as scripted step sequences at their full size (64 utterances x beam 16 =
 1024 hypotheses, full layer widths), driven through the per-kernel entry points of the C ABI with the
-state carried on the GPU.  Every step is checked teacher-forced on a sample of hypotheses: the oracle
+state carried on the GPU.  Every step is checked teacher-forced on every hypothesis: the oracle
 recomputes the step from the GPU's own state of the step before (hypotheses are independent), so a
-rounding tie cannot travel, and the sample keeps the oracle's work to seconds.
+rounding tie cannot travel.
 Configuration 2: prediction network + joint under a seeded emission script (blanks advance a
 hypothesis' frame, labels advance its prediction network; every step all hypotheses run the joint).
 Configuration 3: both LMs step on random labels and parents, then the joint with the fusion of Eq. 1
@@ -36,6 +36,8 @@ def _codes_close(got, ref, h_real, what):
     diff = got.astype(np.int32) - ref
     bad = np.nonzero(diff)
     assert len(bad[0]) <= max(1, got.size // 10000), what
+    if len(bad[0]) == 0:
+        return
     t = h_real[bad] * 7.0
     assert np.all(np.abs(diff[bad]) == 1) and np.all(np.abs(np.abs(t - np.floor(t)) - 0.5) < 1e-4), what
 
@@ -53,7 +55,7 @@ def test_config2_prediction_and_joint_under_an_emission_script(gpu_lib):
     enc_codes = synth.codes(901, (T_enc, B, 1280), -7, 7)
     # the script: a label (uniform over 1..45) with probability 1/3, else blank
     script = np.where(rng.random((steps, N)) < 1.0 / 3.0, rng.integers(1, V, (steps, N)), 0).astype(np.int32)
-    rows = np.sort(rng.choice(N, 40, replace=False))
+    rows = np.arange(N)                              # every hypothesis is recomputed by the oracle
     utt = (np.arange(N) // W).astype(np.int32)
 
     Gp = gmodel.net_from_float(m.pred, m.alpha_e, False, DEV)
@@ -111,7 +113,7 @@ def test_config3_dual_lm_step_fusion_and_selection(gpu_lib):
     steps = 4
     lam_src, lam_ext = 0.3, 0.5
     rng = np.random.default_rng(20220610)
-    rows = np.sort(rng.choice(N, 24, replace=False))
+    rows = np.arange(N)                              # every hypothesis is recomputed by the oracle
     nets_g = [gmodel.net_from_float(f, m.alpha_e, True, DEV) for f in (m.lm_src, m.lm_ext)]
     nets_o = [omodels.net_from_float(f, m.alpha_e, True) for f in (m.lm_src, m.lm_ext)]
     jout_g = q.pack_int4(dev(m.joint_out.w), q.LAYOUT_TILED)

@@ -340,3 +340,72 @@ def test_alsd_config0_end_to_end_matches_golden(gpu_lib, std):
         assert tok_g[int(b), int(w), :len_g[int(b), int(w)]].tolist() == [int(t) for t in labs.split()]
         n += 1
     assert n >= 6
+
+
+def test_config4_slice_encoder_through_decoder_at_full_widths(gpu_lib):
+    """The end-to-end configuration at its own parity size: 2 utterances x 50 frames through the whole network at
+    full depth and width (240 features -> 6 bidirectional layers of 640 cells -> projection -> time-synchronous
+    search at beam 16 with at most 4 labels per frame over the prediction network 768 and both LMs 2 x 1024),
+    free-running on both sides.  What may differ, and when, is decided by the oracle's margins and by nothing
+    chosen here.  Encoder: ~4 * 10^5 hidden-state decisions per utterance; an utterance none of whose decisions
+    lies within the bound of a rounding tie must come out with exactly the oracle's codes; one that has such a
+    decision may lose it either way, and a flipped code then travels through the layers above, so for it the
+    free-running codes say nothing, and every layer is checked step by step on the GPU's own inputs instead (for
+    every utterance).  The decoder then runs on the GPU's own encoder output on both sides, and every utterance
+    whose decode margins are clear of the bounds must give the oracle's beams."""
+    from paper_2206_07882_amd import model as gmodel
+    from tests.test_gpu_sweep import Q_BOUND, S_STEP, _utterance_equal
+    from tests.test_gpu_parity import assert_codes_close
+    q = gpu_lib
+    m = synth.make_model(4)
+    T, B, W, max_sym = 50, 2, 16, 4
+    feats = synth.features(4, T, B, m.feat_dim)
+    layers, proj = omodels.encoder_from_float(m)
+    enc_margin = np.full(B, np.inf)
+    x_r, e_r = omodels.encoder_forward(layers, proj, feats, m.alpha_x, utt_margin=enc_margin)
+    enc = gmodel.Encoder(m, DEV)
+    x_g, e_g = enc.forward(dev(feats))
+    enc.check()
+    xg = host(x_g)
+    agree = (xg == x_r).mean(axis=(0, 2))
+    for b in range(B):
+        if enc_margin[b] >= Q_BOUND:          # no decision of this utterance near a tie: the codes are the oracle's
+            assert np.array_equal(xg[:, b], x_r[:, b]), (b, enc_margin[b], agree[b])
+    # layer by layer, step by step, on the GPU's own inputs and previous codes
+    ws = enc.workspace(T, B, DEV)
+    x = q.quantize_act_rows(dev(feats), enc.inv_s_x)
+    assert np.array_equal(host(x)[:, :, :m.feat_dim], oracle.quant_sym(feats, enc.inv_s_x, 4))
+    for li, (dirs_g, dirs_o) in enumerate(zip(enc.layers, layers)):
+        H = dirs_g[0].H
+        out = torch.empty((T, B, 2 * H), dtype=torch.int8, device=DEV)
+        q.bilstm_layer(dirs_g[0], dirs_g[1], x, h_out=out, workspace=ws)
+        og, xin = host(out), host(x)[:, :, :dirs_o[0].I]
+        for d, (L, order) in enumerate(((dirs_o[0], range(T)), (dirs_o[1], range(T - 1, -1, -1)))):
+            hg = og[:, :, d * H:(d + 1) * H]
+            hp = np.zeros((B, H), np.int8); cp = np.zeros((B, H), np.float32)
+            for t in order:
+                hr, cr, dbg = oracle.lstm_step(L, xin[t], hp, cp, debug=True)
+                assert_codes_close(hg[t], hr, dbg["h_real"] * 7.0, f"layer {li} dir {d} t={t}", min_agree=0.999)
+                hp, cp = hg[t], cr            # GPU codes forward; cell state from the oracle's step on those codes
+        x = out
+    assert np.array_equal(host(x), xg)
+    # the projection of the GPU's own codes
+    e_own = oracle.linear(proj, xg.reshape(T * B, -1)).reshape(T, B, -1)
+    assert np.abs(host(e_g) - e_own).max() <= 1e-5 * np.abs(e_own).max() + 1e-6
+    # decoder, free-running from the GPU's encoder output on both sides
+    eg = host(e_g)
+    ref = oracle.decode(omodels.model_from_float(m), eg, W, max_sym, margins=True)
+    got = tuple(host(t) for t in gpu_lib.decode(gmodel.model_from_float(m, DEV), e_g, W, max_sym))
+    qm, sm = ref[3], ref[4]
+    s_bound = S_STEP * T * (max_sym + 1)
+    n_equal = 0
+    for b in range(B):
+        equal = _utterance_equal(got, ref[:3], b, s_bound + 1e-5)
+        n_equal += int(equal)
+        clear = qm[b] >= Q_BOUND and sm[b] >= s_bound
+        assert equal or not clear, (b, qm[b], sm[b])
+    print("config-4 slice: free-running encoder agreement", agree, "encoder margins", enc_margin, "decode margins", qm, sm,
+          "utterances with the oracle's beams:", n_equal, "of", B)
+    # whatever the margins say, a flipped code moves scores by fractions of a unit: the best hypothesis' score
+    # must be close for every utterance
+    assert np.all(np.abs(got[2][:, 0] - ref[2][:, 0]) < 0.5)

@@ -33,6 +33,8 @@ def host(t):
 def assert_codes_close(got, ref, real, what, min_agree=0.9999):
     """Codes equal except at rounding ties of `real` (= value * inv_step, fp64)."""
     got = got.astype(np.int32); ref = ref.astype(np.int32)
+    if got.size == 0:
+        return
     bad = got != ref
     frac = 1.0 - bad.mean()
     assert frac >= min_agree, f"{what}: only {frac:.6f} of codes agree"
@@ -168,7 +170,18 @@ def test_linear_quant_parity(gpu_lib, rows, cols, N):
 
 # ------------------------------------------------------------------ LSTM step
 
+_PAIRS = {}
+
+
 def _lstm_pair(q, seed, I, H, s_x, std=None):
+    """(oracle layer, GPU layer) from the same seeded float weights; built once per distinct argument set."""
+    key = (seed, I, H, float(s_x), std)
+    if key not in _PAIRS:
+        _PAIRS[key] = _make_lstm_pair(q, seed, I, H, s_x, std)
+    return _PAIRS[key]
+
+
+def _make_lstm_pair(q, seed, I, H, s_x, std=None):
     sd_i = std if std is not None else 1.0 / np.sqrt(I)
     sd_h = std if std is not None else 1.0 / np.sqrt(H)
     w_ih = synth.normal(seed, (4 * H, I), sd_i)
@@ -294,11 +307,13 @@ def test_lstm_step_group_parity(gpu_lib, N, use_gx):
         assert np.array_equal(host(d["h_next"])[~act], hn_r[~act])
 
 
-def test_lstm_step_group_full_size_sampled(gpu_lib):
+def test_lstm_step_group_full_size_all_rows(gpu_lib):
     """The two grouped launches of one decoding round exactly as the benchmark times them (64 utterances x
     beam 16 = 1024 hypotheses; prediction network 768 and both LMs' first layers 1024 fed from the per-token
-    table, then both LMs' second layers 1024 <- 1024), checked on a sample of hypotheses the oracle computes
-    one by one."""
+    table, then both LMs' second layers 1024 <- 1024), every hypothesis and every cell against the oracle.
+    Each launch runs twice: as the benchmark runs it (the production build of the kernel variant) and with the
+    debug outputs (the debug build of the same variant), whose int32 sums must be the oracle's bit for bit and
+    whose states must be the production build's bit for bit."""
     q = gpu_lib
     V, W, B = 46, 16, 64
     N = B * W
@@ -306,8 +321,7 @@ def test_lstm_step_group_full_size_sampled(gpu_lib):
     parent = synth.parent_perm(180, B, W)
     tok = synth.token_ids(181, (N,), V)
     active = (np.random.default_rng(182).random(N) < 0.9).astype(np.uint8)
-    rows = np.random.default_rng(183).choice(N, 48, replace=False)
-    act = active[rows].astype(bool)
+    act = active.astype(bool)
     for shapes, table in (([(768, 768), (256, 1024), (256, 1024)], True), ([(1024, 1024), (1024, 1024)], False)):
         steps, refs = [], []
         for i, (I, H) in enumerate(shapes):
@@ -321,18 +335,39 @@ def test_lstm_step_group_full_size_sampled(gpu_lib):
                 emb = synth.codes(191 + i, (V, I), -7, 7)
                 gx = q.input_projection(G, dev(emb))[0]
                 d.update(x_codes=dev(emb), x_row=dev(tok), gx=gx, gx_table=q.input_table(G, gx))
-                x_rows = emb[tok[rows]]
+                x_rows = emb[tok]
+                # the table's integer form: the oracle's input sums of every token, bit for bit
+                ref_tab = oracle.matmul_i32(L.w_ih, emb)
+                col = _tiled_gate_col(H)
+                for g4 in range(4):
+                    assert np.array_equal(host(gx)[:, col[g4]], ref_tab[:, g4 * H:(g4 + 1) * H])
             else:
                 x = synth.codes(194 + i, (N, I), -7, 7)
                 d.update(x_codes=dev(x))
-                x_rows = x[rows]
+                x_rows = x
             steps.append(d)
-            refs.append(oracle.lstm_step(L, x_rows, hp[parent[rows]], cp[parent[rows]], active=active[rows], debug=True))
+            refs.append(oracle.lstm_step(L, x_rows, hp[parent], cp[parent], active=active, debug=True))
         q.StepGroup(steps).launch()
+        prod = [(host(d["h_next"]).copy(), host(d["c_next"]).copy()) for d in steps]
         for d, (hn_r, cn_r, dbg_r) in zip(steps, refs):
-            assert_rel(host(d["c_next"])[rows], cn_r, "c")
-            assert_codes_close(host(d["h_next"])[rows][act], hn_r[act], (dbg_r["h_real"] * 7.0)[act], "h codes")
-            assert np.array_equal(host(d["h_next"])[rows][~act], hn_r[~act])
+            assert_rel(host(d["c_next"]), cn_r, "c")
+            assert_codes_close(host(d["h_next"])[act], hn_r[act], (dbg_r["h_real"] * 7.0)[act], "h codes")
+            assert np.array_equal(host(d["h_next"])[~act], hn_r[~act])
+        # the debug build of the same variant
+        for d in steps:
+            H = d["L"].H
+            d["h_next"] = torch.empty_like(d["h_next"]); d["c_next"] = torch.empty_like(d["c_next"])
+            d["dbg_acch"] = torch.zeros((N, 4 * H), dtype=torch.int32, device=DEV)
+            d["dbg_gates"] = torch.zeros((N, 4 * H), dtype=torch.float32, device=DEV)
+            if not table:
+                d["dbg_accx"] = torch.zeros((N, 4 * H), dtype=torch.int32, device=DEV)
+        q.StepGroup(steps).launch()
+        for d, (hn_r, cn_r, dbg_r), (hn_p, cn_p) in zip(steps, refs, prod):
+            assert np.array_equal(host(d["dbg_acch"])[act], dbg_r["acch"][act]), "acch"
+            if not table:
+                assert np.array_equal(host(d["dbg_accx"])[act], dbg_r["accx"][act]), "accx"
+            assert_rel(host(d["dbg_gates"])[act], dbg_r["gates"][act], "gates")
+            assert np.array_equal(host(d["h_next"]), hn_p) and np.array_equal(host(d["c_next"]), cn_p)
 
 
 @pytest.mark.parametrize("N,n_list", [(1024, 0), (1024, 1), (1024, 33), (1024, 64), (1024, 65), (1024, 100), (1024, 128),
@@ -341,9 +376,10 @@ def test_lstm_step_group_full_size_sampled(gpu_lib):
                                       (32, 10), (16, 16), (16, 5)])
 def test_lstm_step_group_listed(gpu_lib, N, n_list):
     """qrnnt_lstm_step_group_listed at the shapes of a decoding round (first layers from the per-token table, then
-    the LMs' second layers): the listed hypotheses, in a seeded random order, must get the oracle's step (sampled),
-    every other row of the outputs must keep what it held.  The list lengths walk through the kernel's ways of
-    splitting a list over workgroups (32, 64 or 128 entries each) and their ragged ends; entries beyond the count
+    the LMs' second layers): the listed hypotheses, in a seeded random order, must get the oracle's step (all of
+    them, every cell), every other row of the outputs must keep what it held; once as the decoder launches it and
+    once with the int32 sums of the recurrent part as a debug output, which must be the oracle's bit for bit.
+    The list lengths walk through the kernel's ways of splitting a list over workgroups (32, 64 or 128 entries each) and their ragged ends; entries beyond the count
     hold out-of-range values, which must be harmless."""
     q = gpu_lib
     V, W = 46, 16
@@ -362,10 +398,13 @@ def test_lstm_step_group_listed(gpu_lib, N, n_list):
     lst[:n_list, 1] = parent[listed]
     lst[:n_list, 2] = tok[listed]
     cnt = dev(np.array([n_list], np.int32))
-    rows = listed[:32]
+    rows = listed                                    # every listed hypothesis is checked
     act = active[rows].astype(bool)
     unlisted = np.setdiff1d(np.arange(N), listed)
-    for shapes, table in (([(768, 768), (256, 1024), (256, 1024)], True), ([(1024, 1024), (1024, 1024)], False)):
+    for shapes, table, with_dbg in (([(768, 768), (256, 1024), (256, 1024)], True, False),
+                                    ([(1024, 1024), (1024, 1024)], False, False),
+                                    ([(768, 768), (256, 1024), (256, 1024)], True, True),
+                                    ([(1024, 1024), (1024, 1024)], False, True)):
         steps, refs = [], []
         for i, (I, H) in enumerate(shapes):
             L, G = _lstm_pair(q, 290 + 10 * i + I, I, H, s_x if table else S_H)
@@ -374,6 +413,8 @@ def test_lstm_step_group_listed(gpu_lib, N, n_list):
             d = dict(L=G, parent=dev(parent), active=dev(active), h_prev=dev(hp), c_prev=dev(cp), N=N,
                      h_next=torch.full((N, H), 5, dtype=torch.int8, device=DEV),
                      c_next=torch.full((N, H), 123.0, dtype=torch.float32, device=DEV))
+            if with_dbg:   # the debug build of the variant (and of its half- and quarter-width instances)
+                d["dbg_acch"] = torch.full((N, 4 * H), -77, dtype=torch.int32, device=DEV)
             if table:
                 emb = synth.codes(291 + i, (V, I), -7, 7)
                 gx = q.input_projection(G, dev(emb))[0]
@@ -398,8 +439,9 @@ def test_lstm_step_group_listed(gpu_lib, N, n_list):
             assert_rel(cn[rows], cn_r, "c")
             assert_codes_close(hn[rows][act], hn_r[act], (dbg_r["h_real"] * 7.0)[act], "h codes")
             assert np.array_equal(hn[rows][~act], hn_r[~act])
-            if n_list > 32:            # the rest of the list: written (no sentinel left in c)
-                assert not np.any(cn[listed[32:]] == 123.0)
+            if with_dbg:               # int32 sums of the listed rows bit for bit, nothing written for the others
+                acc = host(d["dbg_acch"])
+                assert np.array_equal(acc[rows][act], dbg_r["acch"][act]) and np.all(acc[unlisted] == -77)
 
 
 def test_lstm_step_extreme_codes_no_overflow(gpu_lib):
