@@ -438,6 +438,33 @@ qrnnt_status qrnnt_decode_alsd(const qrnnt_model *m, const float *enc_proj, int3
                                int32_t u_max, int32_t max_len, int32_t *tokens_out, int32_t *len_out, float *score_out,
                                void *workspace, size_t workspace_bytes, void *stream);
 
+/* qrnnt_decode_alsd with options.  QRNNT_ALSD_REUSE: reuse of cached hypotheses (Sec. 4.1 names it as what
+ * makes the decoding time fall sub-linearly at small beams).  The states of the prediction network and of the
+ * LMs after a label sequence depend on that sequence alone; with this flag a label pick whose resulting
+ * sequence a live hypothesis of the current beam already holds takes over that hypothesis' states (the slot
+ * becomes an inactive row of the network advance, copied from that hypothesis) instead of advancing the
+ * networks from its own parent.  Results are bit for bit those of qrnnt_decode_alsd; sequences are compared
+ * by (length, 64-bit hash) as in the recombination.  The cache is the current beam: a sequence that left the
+ * beam is not remembered.  stats [device] int32[2] or NULL: the call adds the number of label picks that kept
+ * their slot to stats[0] and the number of those that reused states to stats[1] (the caller zeroes it). */
+#define QRNNT_ALSD_REUSE 1u
+qrnnt_status qrnnt_decode_alsd_ex(const qrnnt_model *m, const float *enc_proj, int32_t T, int32_t B, int32_t W,
+                                  int32_t u_max, int32_t max_len, uint32_t flags, int32_t *stats, int32_t *tokens_out,
+                                  int32_t *len_out, float *score_out, void *workspace, size_t workspace_bytes,
+                                  void *stream);
+
+/* ---- diagnostics ---- */
+
+/* Register-only issue rate of one of the matrix instructions that can carry the 4-bit x 4-bit contraction
+ * exactly (codes in [-8, 7] are exact in int8 and in fp8-E4M3, partial sums stay below 2^24; Sec. 3.1 fixes
+ * the integer grid only).  form in [0, qrnnt_diag_mfma_forms()); qrnnt_diag_mfma_form_name gives its name.
+ * Runs `iters` loop iterations of back-to-back independent instructions on two workgroups per compute unit and
+ * writes the rate in TOP/s (2 ops per multiply-accumulate) to *tops_out [host].  sink [device]: one float the
+ * kernel may write.  Unlike every other call this one waits for its own work (it times it with events). */
+int32_t qrnnt_diag_mfma_forms(void);
+const char *qrnnt_diag_mfma_form_name(int32_t form);
+qrnnt_status qrnnt_diag_mfma_rate(int32_t form, int32_t iters, float *sink, double *tops_out, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

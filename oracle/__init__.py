@@ -455,6 +455,23 @@ def decode_alsd(model: Model, enc_proj, W, u_max, max_len=None, margins=False):
     return tokens, lens, scores
 
 
+def decode_alsd_cached(model: Model, enc_proj, W, u_max, cache_mode, max_len=None):
+    """oq_decode_alsd_cached: the search with reuse of cached hypotheses (cache_mode 0 none, 1 the current beam,
+    2 every sequence ever extended).  Returns (tokens, lens, scores, requested [B], performed [B])."""
+    enc_proj = _arr(enc_proj, np.float32)
+    T, B, J = enc_proj.shape
+    if max_len is None:
+        max_len = max(1, u_max)
+    tokens = np.empty((B, W, max_len), np.int32)
+    lens = np.empty((B, W), np.int32)
+    scores = np.empty((B, W), np.float32)
+    req, done = np.zeros(B, np.int64), np.zeros(B, np.int64)
+    cm = model.c()
+    lib().oq_decode_alsd_cached(C.byref(cm), _p(enc_proj), C.c_int(T), C.c_int(B), C.c_int(W), C.c_int(u_max),
+                                C.c_int(max_len), _p(tokens), _p(lens), _p(scores), C.c_int(cache_mode), _p(req), _p(done))
+    return tokens, lens, scores, req, done
+
+
 def score_alignment(model: Model, enc_proj, b, actions):
     enc_proj = _arr(enc_proj, np.float32)
     T, B, J = enc_proj.shape

@@ -913,9 +913,28 @@ void oq_decode_margins(const oq_model_t *M, const float *enc_proj, int T, int B,
  * Outputs as oq_decode; ranks beyond the number of finals are empty. */
 typedef struct { int32_t *tok; int len; float score; } fin_t;
 
+/* Reuse of cached hypotheses (Sec. 4.1 names it as what makes the decoding time fall sub-linearly at small
+ * beams): the state of the prediction network and of the LMs after a label sequence depends on that sequence
+ * alone, so a hypothesis that reaches a sequence some other hypothesis has already reached can take over its
+ * network states instead of advancing the networks again.  The result of the search is the same bit for bit;
+ * only the number of network advances changes, which is what the counters report.
+ *   cache_mode 0: none (every label pick that keeps its slot advances the networks);
+ *   cache_mode 1: the current beam is the cache (a sequence that a live hypothesis of the beam holds);
+ *   cache_mode 2: every sequence ever extended in this utterance stays cached. */
+typedef struct { int32_t *tok; int len; hyp_t h; } cache_ent;
+
+static int same_seq(const int32_t *a, int la, const int32_t *b, int lb, int extra_b)
+{   /* is a == b followed by extra_b (extra_b < 0: b alone)? */
+    const int lbb = lb + (extra_b >= 0);
+    if (la != lbb) return 0;
+    for (int p = 0; p < la; ++p)
+        if (a[p] != (p < lb ? b[p] : extra_b)) return 0;
+    return 1;
+}
+
 static void decode_alsd_core(const oq_model_t *M, const float *enc_proj, int T, int B, int W, int u_max,
                              int max_len, int32_t *tokens_out, int32_t *len_out, float *score_out,
-                             double *qmargin, double *smargin)
+                             double *qmargin, double *smargin, int cache_mode, int64_t *requested, int64_t *performed)
 {
     const int V = M->V, J = M->joint_out.cols;
     const int want = qmargin != NULL && smargin != NULL;
@@ -927,6 +946,9 @@ static void decode_alsd_core(const oq_model_t *M, const float *enc_proj, int T, 
         hyp_t *nxt = (hyp_t *)malloc(sizeof(hyp_t) * (size_t)W);
         for (int w = 0; w < W; ++w) { hyp_alloc(M, &cur[w]); hyp_alloc(M, &nxt[w]); }
         fin_t *fin = (fin_t *)calloc((size_t)W + 1, sizeof(fin_t));
+        cache_ent *cache = NULL;
+        int n_cache = 0, cap_cache = 0;
+        int64_t n_req = 0, n_done = 0;
         int nfin = 0;
         float *S = (float *)malloc(sizeof(float) * (size_t)W);
         float *F = (float *)malloc(sizeof(float) * (size_t)W * V);
@@ -1026,7 +1048,39 @@ static void decode_alsd_core(const oq_model_t *M, const float *enc_proj, int T, 
                     if (par[q] >= 0 && lead[q] == r) sum += exp((double)ns[q] - m);
                 const float sc = (float)(m + log(sum));
                 if (tk[r] == M->blank) { hyp_copy(M, &nxt[r], &cur[par[r]]); nxt[r].score = sc; }
-                else hyp_extend(M, &nxt[r], &cur[par[r]], tk[r], sc, want ? &qm : NULL);
+                else {
+                    const hyp_t *pr = &cur[par[r]];
+                    const hyp_t *hit = NULL;
+                    ++n_req;
+                    if (cache_mode == 1) {
+                        for (int j = 0; j < W && !hit; ++j)
+                            if (cur[j].score > -INFINITY && same_seq(cur[j].tok, cur[j].len, pr->tok, pr->len, tk[r])) hit = &cur[j];
+                    } else if (cache_mode == 2) {
+                        for (int j = 0; j < n_cache && !hit; ++j)
+                            if (same_seq(cache[j].tok, cache[j].len, pr->tok, pr->len, tk[r])) hit = &cache[j].h;
+                    }
+                    if (hit) {   /* the networks' states after this sequence exist already: take them over */
+                        const hyp_t *src = hit;
+                        hyp_copy(M, &nxt[r], src);
+                        if (nxt[r].cap < pr->len + 1) { nxt[r].cap = pr->len + 16; nxt[r].tok = (int32_t *)realloc(nxt[r].tok, sizeof(int32_t) * (size_t)nxt[r].cap); }
+                        if (pr->len) memcpy(nxt[r].tok, pr->tok, sizeof(int32_t) * (size_t)pr->len);
+                        nxt[r].tok[pr->len] = tk[r];
+                        nxt[r].len = pr->len + 1;
+                        nxt[r].score = sc;
+                    } else {
+                        ++n_done;
+                        hyp_extend(M, &nxt[r], pr, tk[r], sc, want ? &qm : NULL);
+                        if (cache_mode == 2) {
+                            if (n_cache == cap_cache) { cap_cache = cap_cache ? 2 * cap_cache : 64; cache = (cache_ent *)realloc(cache, sizeof(cache_ent) * (size_t)cap_cache); }
+                            cache_ent *ce = &cache[n_cache++];
+                            ce->len = nxt[r].len;
+                            ce->tok = (int32_t *)malloc(sizeof(int32_t) * (size_t)(ce->len + 1));
+                            memcpy(ce->tok, nxt[r].tok, sizeof(int32_t) * (size_t)ce->len);
+                            hyp_alloc(M, &ce->h);
+                            hyp_copy(M, &ce->h, &nxt[r]);
+                        }
+                    }
+                }
             }
             hyp_t *tmp = cur; cur = nxt; nxt = tmp;
         }
@@ -1045,6 +1099,10 @@ static void decode_alsd_core(const oq_model_t *M, const float *enc_proj, int T, 
         }
         if (want) { qmargin[b] = qm; smargin[b] = sm; }
         free(rowm);
+        if (requested) requested[b] = n_req;
+        if (performed) performed[b] = n_done;
+        for (int j = 0; j < n_cache; ++j) { free(cache[j].tok); hyp_free(M, &cache[j].h); }
+        free(cache);
         for (int q = 0; q < nfin; ++q) free(fin[q].tok);
         for (int w = 0; w < W; ++w) { hyp_free(M, &cur[w]); hyp_free(M, &nxt[w]); }
         free(cur); free(nxt); free(fin);
@@ -1055,7 +1113,7 @@ static void decode_alsd_core(const oq_model_t *M, const float *enc_proj, int T, 
 void oq_decode_alsd(const oq_model_t *M, const float *enc_proj, int T, int B, int W, int u_max,
                     int max_len, int32_t *tokens_out, int32_t *len_out, float *score_out)
 {
-    decode_alsd_core(M, enc_proj, T, B, W, u_max, max_len, tokens_out, len_out, score_out, NULL, NULL);
+    decode_alsd_core(M, enc_proj, T, B, W, u_max, max_len, tokens_out, len_out, score_out, NULL, NULL, 0, NULL, NULL);
 }
 
 /* oq_decode_alsd with the margins of oq_decode_margins; smargin also covers the
@@ -1064,7 +1122,19 @@ void oq_decode_alsd_margins(const oq_model_t *M, const float *enc_proj, int T, i
                             int max_len, int32_t *tokens_out, int32_t *len_out, float *score_out,
                             double *qmargin, double *smargin)
 {
-    decode_alsd_core(M, enc_proj, T, B, W, u_max, max_len, tokens_out, len_out, score_out, qmargin, smargin);
+    decode_alsd_core(M, enc_proj, T, B, W, u_max, max_len, tokens_out, len_out, score_out, qmargin, smargin, 0, NULL, NULL);
+}
+
+/* oq_decode_alsd with reuse of cached hypotheses (see cache_ent above).  requested[b]: label picks of
+ * utterance b that kept their slot, i.e. network advances without a cache; performed[b]: advances actually
+ * made.  Pinned by: identical outputs in all three modes; with nothing pruned and V - 1 labels, mode 2
+ * performs exactly one advance per distinct label sequence of length 1 .. u_max. */
+void oq_decode_alsd_cached(const oq_model_t *M, const float *enc_proj, int T, int B, int W, int u_max,
+                           int max_len, int32_t *tokens_out, int32_t *len_out, float *score_out,
+                           int cache_mode, int64_t *requested, int64_t *performed)
+{
+    decode_alsd_core(M, enc_proj, T, B, W, u_max, max_len, tokens_out, len_out, score_out, NULL, NULL, cache_mode,
+                     requested, performed);
 }
 
 /* Score of one fixed alignment, for the exhaustive-search pin: `actions` is a

@@ -468,8 +468,19 @@ extern "C" qrnnt_status qrnnt_decode_alsd(const qrnnt_model *m, const float *enc
                                           int32_t u_max, int32_t max_len, int32_t *tokens_out, int32_t *len_out,
                                           float *score_out, void *workspace, size_t workspace_bytes, void *stream)
 {
+    return qrnnt_decode_alsd_ex(m, enc_proj, T, B, W, u_max, max_len, 0u, nullptr, tokens_out, len_out, score_out,
+                                workspace, workspace_bytes, stream);
+}
+
+extern "C" qrnnt_status qrnnt_decode_alsd_ex(const qrnnt_model *m, const float *enc_proj, int32_t T, int32_t B, int32_t W,
+                                             int32_t u_max, int32_t max_len, uint32_t flags, int32_t *stats,
+                                             int32_t *tokens_out, int32_t *len_out, float *score_out, void *workspace,
+                                             size_t workspace_bytes, void *stream)
+{
     qrnnt_status s = check_model(m);
     if (s != QRNNT_OK) return s;
+    QR_REQUIRE((flags & ~(uint32_t)QRNNT_ALSD_REUSE) == 0u, QRNNT_ERR_RANGE);
+    QR_REQUIRE(qr_aligned(stats, 4), QRNNT_ERR_ALIGN);
     QR_REQUIRE(enc_proj && tokens_out && len_out && score_out && workspace, QRNNT_ERR_NULL);
     QR_REQUIRE(T > 0 && B > 0 && W > 0 && max_len > 0 && u_max >= 0, QRNNT_ERR_SHAPE);
     QR_REQUIRE(W <= 64, QRNNT_ERR_UNSUPPORTED);
@@ -540,6 +551,7 @@ extern "C" qrnnt_status qrnnt_decode_alsd(const qrnnt_model *m, const float *enc
         sa.iter = i;  sa.T = T;  sa.u_max = u_max;
         sa.hash_src = ap.hash + (size_t)cur * Ns;  sa.hash_dst = ap.hash + (size_t)nxt * Ns;
         sa.fin_score = ap.fin_score;  sa.fin_node = ap.fin_node;  sa.fin_len = ap.fin_len;
+        sa.reuse = (flags & QRNNT_ALSD_REUSE) ? 1 : 0;  sa.stats = stats;
         qr_launch_joint_alsd(ja, ra, sa, st);
         if (i + 1 < ap.n_iter) advance_nets(m, p, cur, nxt, V, ra.live_next, nullptr, st);
         cur = nxt;

@@ -121,6 +121,8 @@ struct QrAlsdArgs {
     const unsigned long long *hash_src;              // [N] hash of the label sequence (recombination key, with the length)
     unsigned long long *hash_dst;
     float *fin_score;  int32_t *fin_node, *fin_len;  // [B,W] the W best finished hypotheses so far, best first
+    int reuse;                                       // a label pick whose sequence a live hypothesis of the beam holds takes over its states
+    int32_t *stats;                                  // optional [device] int32[2]: += label picks that kept their slot, += those that reused states
 };
 
 struct QrRecArgs {

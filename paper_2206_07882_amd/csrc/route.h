@@ -126,6 +126,7 @@ __device__ __forceinline__ void qr_frame_end(const QrRouteArgs &a, int b, int la
 struct QrAlsdOwn {
     int len, node;
     unsigned long long hash;
+    float score;
     float fin_score;  int fin_node, fin_len;
 };
 
@@ -133,7 +134,7 @@ __device__ __forceinline__ QrAlsdOwn qr_alsd_load_own(const QrRouteArgs &a, cons
 {
     const int own = b * a.W + (lane < a.W ? lane : 0);
     QrAlsdOwn o;
-    o.len = a.len_src[own];  o.node = a.node_src[own];  o.hash = s.hash_src[own];
+    o.len = a.len_src[own];  o.node = a.node_src[own];  o.hash = s.hash_src[own];  o.score = a.score_src[own];
     o.fin_score = s.fin_score[own];  o.fin_node = s.fin_node[own];  o.fin_len = s.fin_len[own];
     return o;
 }
@@ -180,6 +181,25 @@ __device__ __forceinline__ void qr_alsd_route(const QrRouteArgs &a, const QrAlsd
     const bool keep = found && leader == lane;
     const unsigned long long km = __ballot(keep);
     if (lane == 0 && km != 0ull && a.live_next) atomicAdd(a.live_next, 1);
+    // Reuse of cached hypotheses (Sec. 4.1): the networks' states after a label sequence depend on the sequence
+    // alone.  When a live hypothesis of the current beam already holds the sequence this label pick produces (the
+    // usual case: y + k is in the beam and y proposes k again one frame later), the new slot takes over that
+    // hypothesis' states as an inactive row of the advance instead of stepping the networks from y.
+    int reuse_slot = -1;
+    if (s.reuse) {   // uniform
+        const int o_hlo = (int)(unsigned)o.hash, o_hhi = (int)(unsigned)(o.hash >> 32);
+        for (int j = 0; j < W; ++j) {
+            const bool live_j = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(o.score), j)) > -INFINITY;
+            const bool same = live_j && __builtin_amdgcn_readlane(o.len, j) == new_len &&
+                              __builtin_amdgcn_readlane(o_hlo, j) == h_lo && __builtin_amdgcn_readlane(o_hhi, j) == h_hi;
+            if (same && keep && is_lab && reuse_slot < 0) reuse_slot = j;
+        }
+    }
+    if (s.stats) {   // uniform
+        const int n_req = (int)__popcll(__ballot(keep && is_lab)), n_hit = (int)__popcll(__ballot(reuse_slot >= 0));
+        if (lane == 0 && n_req) atomicAdd(s.stats, n_req);
+        if (lane == 0 && n_hit) atomicAdd(s.stats + 1, n_hit);
+    }
     if (in) {
         const int dst = b * W + lane;
         if (keep) {
@@ -193,9 +213,9 @@ __device__ __forceinline__ void qr_alsd_route(const QrRouteArgs &a, const QrAlsd
             a.node_dst[dst] = node;
             a.len_dst[dst] = new_len;
             s.hash_dst[dst] = new_hash;
-            a.parent_idx[dst] = src_slot;
+            a.parent_idx[dst] = reuse_slot >= 0 ? b * W + reuse_slot : src_slot;
             a.token[dst] = tok;
-            a.active[dst] = is_lab ? 1 : 0;
+            a.active[dst] = (is_lab && reuse_slot < 0) ? 1 : 0;
         } else {
             a.score_dst[dst] = -INFINITY;
             a.node_dst[dst] = 0;

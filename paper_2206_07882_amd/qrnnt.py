@@ -63,7 +63,8 @@ EXPORTS = ["qrnnt_status_str", "qrnnt_abi_version", "qrnnt_pack_int4_bytes", "qr
            "qrnnt_input_projection", "qrnnt_input_table", "qrnnt_lstm_step_group", "qrnnt_lstm_step_group_listed",
            "qrnnt_bilstm_layer_workspace", "qrnnt_bilstm_layer", "qrnnt_lstm_layer_static",
            "qrnnt_joint_fuse", "qrnnt_beam_step", "qrnnt_decode_workspace", "qrnnt_decode", "qrnnt_decode_ex",
-           "qrnnt_decode_alsd_workspace", "qrnnt_decode_alsd"]
+           "qrnnt_decode_alsd_workspace", "qrnnt_decode_alsd", "qrnnt_decode_alsd_ex",
+           "qrnnt_diag_mfma_forms", "qrnnt_diag_mfma_form_name", "qrnnt_diag_mfma_rate"]
 
 DECODE_EARLY_STOP = 1
 
@@ -92,6 +93,8 @@ def load():
         lib.qrnnt_decode_workspace.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32]
         lib.qrnnt_decode_alsd_workspace.restype = C.c_size_t
         lib.qrnnt_decode_alsd_workspace.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32]
+        lib.qrnnt_diag_mfma_form_name.restype = C.c_char_p
+        lib.qrnnt_act_pitch.restype = C.c_int32
         _lib = lib
     return _lib
 
@@ -521,9 +524,14 @@ def decode_alsd_workspace(model: Model, T: int, B: int, W: int, u_max: int) -> i
     return int(load().qrnnt_decode_alsd_workspace(C.byref(cm), T, B, W, u_max))
 
 
+ALSD_REUSE = 1
+
+
 def decode_alsd(model: Model, enc_proj: torch.Tensor, W: int, u_max: int, max_len: Optional[int] = None,
-                workspace: Optional[torch.Tensor] = None):
-    """Alignment-length synchronous search with recombination; at most u_max labels per utterance."""
+                workspace: Optional[torch.Tensor] = None, flags: int = 0, stats: Optional[torch.Tensor] = None):
+    """Alignment-length synchronous search with recombination; at most u_max labels per utterance.
+    flags = ALSD_REUSE: label picks take over the states of a live hypothesis that holds their sequence;
+    stats (int32 [2] on the device, zeroed by the caller) counts label picks and reuses."""
     T, B, J = enc_proj.shape
     dev = enc_proj.device
     if max_len is None:
@@ -537,8 +545,22 @@ def decode_alsd(model: Model, enc_proj: torch.Tensor, W: int, u_max: int, max_le
     tokens = torch.empty((B, W, max_len), dtype=torch.int32, device=dev)
     lens = torch.empty((B, W), dtype=torch.int32, device=dev)
     scores = torch.empty((B, W), dtype=torch.float32, device=dev)
-    st = load().qrnnt_decode_alsd(C.byref(cm), _ptr(enc_proj, torch.float32), C.c_int32(T), C.c_int32(B), C.c_int32(W),
-                                  C.c_int32(u_max), C.c_int32(max_len), _ptr(tokens), _ptr(lens), _ptr(scores),
-                                  _ptr(workspace), C.c_size_t(workspace.numel()), _stream())
-    _check(st, "qrnnt_decode_alsd")
+    st = load().qrnnt_decode_alsd_ex(C.byref(cm), _ptr(enc_proj, torch.float32), C.c_int32(T), C.c_int32(B), C.c_int32(W),
+                                     C.c_int32(u_max), C.c_int32(max_len), C.c_uint32(flags), _ptr(stats, torch.int32),
+                                     _ptr(tokens), _ptr(lens), _ptr(scores), _ptr(workspace),
+                                     C.c_size_t(workspace.numel()), _stream())
+    _check(st, "qrnnt_decode_alsd_ex")
     return tokens, lens, scores
+
+
+def diag_mfma_rates(iters: int = 20000, device="cuda:0"):
+    """[(name, TOP/s)] for every matrix-instruction form the library knows (qrnnt_diag_mfma_rate)."""
+    lib = load()
+    sink = torch.zeros(1, dtype=torch.float32, device=device)
+    out = []
+    for f in range(int(lib.qrnnt_diag_mfma_forms())):
+        tops = C.c_double(0.0)
+        _check(lib.qrnnt_diag_mfma_rate(C.c_int32(f), C.c_int32(iters), _ptr(sink), C.byref(tops), _stream()),
+               "qrnnt_diag_mfma_rate")
+        out.append((lib.qrnnt_diag_mfma_form_name(C.c_int32(f)).decode(), float(tops.value)))
+    return out

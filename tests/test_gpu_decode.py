@@ -409,3 +409,41 @@ def test_config4_slice_encoder_through_decoder_at_full_widths(gpu_lib):
     # whatever the margins say, a flipped code moves scores by fractions of a unit: the best hypothesis' score
     # must be close for every utterance
     assert np.all(np.abs(got[2][:, 0] - ref[2][:, 0]) < 0.5)
+
+
+@pytest.mark.parametrize("B,W,u_max,T,std", [(5, 16, 6, 10, 0.5), (3, 4, 8, 12, 0.6), (16, 64, 3, 4, 0.5), (4, 8, 5, 9, 0.4)])
+def test_alsd_reuse_of_cached_hypotheses(gpu_lib, B, W, u_max, T, std):
+    """Sec. 4.1's reuse of cached hypotheses in the alignment-length synchronous search: a label pick whose sequence
+    a live hypothesis of the beam already holds takes over its network states.  Same finished lists as without the
+    flag and as the oracle; the counters (label picks that kept their slot, reuses) are the oracle's own for the
+    same rule (its cache mode 1)."""
+    from paper_2206_07882_amd import model as gmodel
+    m = synth.make_model(0, weight_std=std)
+    m.rho = 0.1
+    e = synth.normal(460 + B + W, (T, B, m.J), 1.0)
+    from tests.test_gpu_sweep import Q_BOUND, S_STEP, _utterance_equal
+    M = omodels.model_from_float(m)
+    ref = oracle.decode_alsd_cached(M, e, W, u_max, 1)
+    marg = oracle.decode_alsd(M, e, W, u_max, margins=True)
+    G = gmodel.model_from_float(m, DEV)
+    plain = gpu_lib.decode_alsd(G, dev(e), W, u_max)
+    stats = torch.zeros(2, dtype=torch.int32, device=DEV)
+    got = gpu_lib.decode_alsd(G, dev(e), W, u_max, flags=gpu_lib.ALSD_REUSE, stats=stats)
+    for a, b in zip(plain, got):
+        assert torch.equal(a, b)              # the flag changes the work, not one bit of the result
+    # against the oracle under the rule of the free-running sweep: an utterance whose margins are clear must agree
+    got_h = tuple(host(x) for x in got)
+    s_bound = S_STEP * (T + u_max)
+    all_equal = True
+    for b in range(B):
+        equal = _utterance_equal(got_h, ref[:3], b, s_bound + 1e-5)
+        all_equal = all_equal and equal
+        assert equal or not (marg[3][b] >= Q_BOUND and marg[4][b] >= s_bound), (b, marg[3][b], marg[4][b])
+    n_req, n_hit = (int(v) for v in stats.cpu())
+    assert n_hit > 0 and abs(n_req - int(ref[3].sum())) <= 0.05 * n_req
+    if all_equal:     # same search, same rule: the same counts
+        assert n_req == int(ref[3].sum()) and n_hit == int((ref[3] - ref[4]).sum()), (n_req, n_hit, ref[3].sum(), ref[4].sum())
+    # without the flag the counters still count the picks, and no reuse
+    stats.zero_()
+    gpu_lib.decode_alsd(G, dev(e), W, u_max, stats=stats)
+    assert stats.cpu().tolist() == [n_req, 0]

@@ -63,6 +63,11 @@ MUTANTS = [
      "hyp_extend(M, &beam[0], &zero, 0, 0.0f, NULL);"),
     ("ALSD: margin of the start-symbol advance dropped", "hyp_extend(M, &cur[0], &zero, 0, 0.0f, want ? &qm : NULL);",
      "hyp_extend(M, &cur[0], &zero, 0, 0.0f, NULL);"),
+    ("cache: a hit in the beam takes the parent's own sequence for the new one",
+     "same_seq(cur[j].tok, cur[j].len, pr->tok, pr->len, tk[r])) hit = &cur[j];",
+     "same_seq(cur[j].tok, cur[j].len, pr->tok, pr->len, -1)) hit = &cur[j];"),
+    ("cache: extended sequences are never remembered", "cache_ent *ce = &cache[n_cache++];", "cache_ent *ce = &cache[n_cache]; n_cache += 0;"),
+    ("cache: sequences compared by length only", "        if (a[p] != (p < lb ? b[p] : extra_b)) return 0;\n", ""),
     ("z decisions not counted in the margin", "for (int w = 0; w < nA; ++w) if (rowm[w] < qm) qm = rowm[w];",
      "for (int w = 0; w < nA; ++w) if (rowm[w] < 0.0) qm = rowm[w];"),
 ]

@@ -851,3 +851,36 @@ def test_decode_margins_on_a_path_that_can_be_recomputed():
     assert np.all(q3 <= qm)
     _, _, _, q1, s1 = oracle.decode(m, np.ascontiguousarray(e[:, 1:2]), 3, 2, max_len=8, margins=True)
     assert q1[0] == q3[1] and s1[0] == s3[1]
+
+
+# ------------------------------------------------------------------ reuse of cached hypotheses (Sec. 4.1)
+
+def test_alsd_hypothesis_cache_changes_the_work_not_the_result():
+    # the networks' states after a label sequence depend on the sequence alone: taking them over from a cache gives
+    # the same finished lists bit for bit in every mode.  With a beam wide enough that nothing is pruned and 2 labels,
+    # every label sequence of length 1..3 is extended at some iteration, many of them again and again (from the same
+    # prefix one frame later): an unbounded cache advances the networks exactly once per distinct sequence,
+    # 2 + 4 + 8 = 14 times, whatever the number of frames.
+    m = _tiny_model(61)                      # V = 3: blank + 2 labels
+    rng = np.random.default_rng(62)
+    J = m.joint_out.cols
+    for T in (1, 2, 4):
+        e = rng.standard_normal((T, 2, J)).astype(np.float32)
+        base = oracle.decode_alsd(m, e, 48, 3)
+        outs = [oracle.decode_alsd_cached(m, e, 48, 3, mode) for mode in (0, 1, 2)]
+        for o in outs:
+            assert all(np.array_equal(a, b) for a, b in zip(o[:3], base))
+        req0, done0 = outs[0][3], outs[0][4]
+        assert np.array_equal(req0, done0)                       # no cache: every request is an advance
+        assert np.all(outs[2][4] == 14), (T, outs[2][4])         # one advance per distinct sequence
+        assert np.all(outs[1][3] == req0) and np.all(outs[2][3] == req0)
+        assert np.all(outs[1][4] <= done0) and np.all(outs[2][4] <= outs[1][4])
+        if T >= 2:
+            assert np.all(req0 > 14) and np.all(outs[1][4] < req0)   # re-proposed sequences are found in the beam
+    # a narrow beam on a longer utterance: still the same beams in every mode
+    m2 = _tiny_model(63, V=5, rho=0.1)
+    e = rng.standard_normal((9, 3, m2.joint_out.cols)).astype(np.float32)
+    base = oracle.decode_alsd(m2, e, 4, 6)
+    for mode in (0, 1, 2):
+        o = oracle.decode_alsd_cached(m2, e, 4, 6, mode)
+        assert all(np.array_equal(a, b) for a, b in zip(o[:3], base)) and np.all(o[4] <= o[3])
