@@ -177,6 +177,40 @@ def main():
         extra["alsd"] = {"rows": alsd_rows,
                          "note": "same networks and encoder output as the headline; label cap u_max per utterance; the launch "
                                  "sequence has T + u_max iterations, those after the last live hypothesis return at once"}
+        # Fig. 2(b) of the paper on this machine: decoder time of the paper's own search against the beam width
+        # (200 frames, label cap T/2), with and without the reuse of cached hypotheses, and how often a label pick
+        # found its sequence in the beam
+        sweep_a = []
+        for Wb in (1, 2, 4, 8, 16):
+            um = Ts // 2
+            wsa = torch.empty(q.decode_alsd_workspace(G, Ts, B, Wb, um), dtype=torch.uint8, device=dev)
+            ta = timed(lambda: q.decode_alsd(G, es, Wb, um, max_len=um, workspace=wsa), 1, warm=1)
+            st = torch.zeros(2, dtype=torch.int32, device=dev)
+            tr = timed(lambda: q.decode_alsd(G, es, Wb, um, max_len=um, workspace=wsa, flags=q.ALSD_REUSE), 1, warm=1)
+            q.decode_alsd(G, es, Wb, um, max_len=um, workspace=wsa, flags=q.ALSD_REUSE, stats=st)
+            n_req, n_hit = (int(v) for v in st.cpu())
+            sweep_a.append({"beam": Wb, "decoder_ms_per_1000_frames": ta * 1e3 * 1000.0 / Ts, "decoder_rtf": ta / (B * Ts * FRAME_SEC),
+                            "with_reuse_ms_per_1000_frames": tr * 1e3 * 1000.0 / Ts, "label_picks": n_req, "reused": n_hit})
+            del wsa
+        extra["alsd_beam_sweep"] = {"rows": sweep_a,
+                                    "note": "alignment-length synchronous search, label cap T/2; 'reused' = label picks whose sequence a live "
+                                            "hypothesis of the beam already held (Sec. 4.1's reuse of cached hypotheses): they become copied "
+                                            "rows of the advance; the advance is one dense launch per layer over all slots, so on this "
+                                            "machine a reused row costs what an advanced one costs"}
+        # worst case for the time-synchronous search: the blank's joint bias lowered until every pick of every round
+        # is a label, so all four advances of a frame run over full lists (the headline model picks 15, 1, 15, 1 of 16)
+        import copy
+        m_lab = copy.deepcopy(m)
+        m_lab.joint_out.bias = m_lab.joint_out.bias.copy()
+        m_lab.joint_out.bias[0] -= 8.0
+        G_lab = gmodel.model_from_float(m_lab, dev)
+        wsl = torch.empty(q.decode_workspace(G_lab, Ts, B, W, MAX_SYM), dtype=torch.uint8, device=dev)
+        tl = timed(lambda: q.decode(G_lab, es, W, MAX_SYM, max_len=Ts * MAX_SYM, workspace=wsl), 1, warm=1)
+        ll = q.decode(G_lab, es, W, MAX_SYM, max_len=Ts * MAX_SYM, workspace=wsl)[1].cpu().numpy()
+        extra["decode_all_labels"] = {"decoder_ms_per_1000_frames": tl * 1e3 * 1000.0 / Ts, "mean_labels_best_hyp_per_frame": float(ll[:, 0].mean()) / Ts,
+                                      "note": "same networks with the blank made improbable: every round's 16 picks are labels "
+                                              "(4 labels per frame), the upper bound of the decoder's time per frame"}
+        del wsl, G_lab, m_lab
         del feats, ws_dec, e, es, out
         # the same pipeline with the layer shapes of the paper's Sec. 2 (340 features, prediction network and
         # source LM 1 x 768, external LM 2 x 2048 + bottleneck 256, fusion weights 0.7 / 0.5 / 0.2), all 4-bit
@@ -274,6 +308,24 @@ def main():
             import re
             hit = re.search(r"^hbm_bytes_per_launch:\s*(\d+)", open(tr).read(), re.M)
             result["roofline"]["traffic"] = int(hit.group(1)) if hit else None
+            result["roofline"]["traffic_source"] = ("profiles/lstm_step_pipe_kernel_decode_round_hbm_traffic.txt: rocprofv3 --pmc "
+                                                    "FETCH_SIZE / WRITE_SIZE of these two launches, calibrated on a copy; a committed "
+                                                    "measurement of the same kernels, not taken in this run")
+
+        # ---- what the matrix unit itself does: register-only rates of the instruction forms that can carry the
+        # contraction exactly (codes in [-8, 7] are exact in int8 and fp8-E4M3, sums stay below 2^24)
+        rates = q.diag_mfma_rates(20000, dev)
+        best_i8 = max(t for n, t in rates if n.startswith("int8"))
+        extra["mfma_forms"] = {"rows": [{"form": n, "TOPs": t, "frac_of_published_int8_peak": t / INT8_MFMA_PEAK_TOPS} for n, t in rates],
+                               "int8_peak_at_measured_clock_TOPs": best_i8,
+                               "implied_clock_GHz": best_i8 * 1e12 / (2048.0 * 4 * 256) / 1e9,
+                               "note": "two workgroups per CU issuing independent accumulator chains, no memory traffic. The 32x32x32 int8 "
+                                       "form runs at the full rate (2048 op/clk/SIMD, which gives the clock above); the 16x16x64 int8 form, "
+                                       "the one the kernels' 16-row gate tiles use, at half of it; the fp8/fp6/fp4 16x16x128 forms reach the "
+                                       "full rate at 16 rows but need both operands as 8-bit floats (a table lookup per nibble), and no "
+                                       "float form beats int8 32x32x32 by more than 10 %: the faster unit for this path is the 32-row int8 form"}
+        result["roofline"]["peak_at_measured_clock"] = best_i8
+        result["roofline"]["frac_of_peak_at_measured_clock"] = ach / best_i8
 
         # ---- beam-16 regime (one utterance, N = 16): weight streaming, against HBM
         byt16, t16 = 0.0, 0.0
@@ -334,17 +386,22 @@ def main():
                                        "GBps": 2 * src.numel() / tc / 1e9}
         del src, dst
 
-        # ---- input-projection GEMM, encoder layers 2-6 shape: [T*B = 16000, 1280] x [1280, 2560]
+        # ---- input-projection GEMM, encoder layers 2-6 shape: [T*B, 1280] x [1280, 2560] at configuration 1's
+        # M = 16000 (32 utterances x 500 frames) and configuration 4's M = 64000 (64 x 1000: 656 MB of int32 sums,
+        # more than the 256 MB cache in front of HBM holds)
         L = enc.layers[1][0]
-        M = 16000
-        xg = torch.from_numpy(synth.codes(8, (M, L.I))).to(dev)
-        gx = torch.empty((M, 4 * L.H), dtype=torch.int32, device=dev)
-        tg = timed_graph(lambda: q.input_projection(L, xg, gx), 20)
-        gops = 2.0 * M * L.I * 4 * L.H
-        gbytes = M * L.I + 4 * L.H * L.I / 2 + M * 4 * L.H * 4
-        extra["input_projection_gemm"] = {"M": M, "K": L.I, "N": 4 * L.H, "us": tg * 1e6, "TOPs": gops / tg / 1e12,
-                                          "frac_int8_mfma": gops / tg / 1e12 / INT8_MFMA_PEAK_TOPS,
-                                          "algorithmic_bytes": gbytes, "GBps": gbytes / tg / 1e9}
+        gemm_rows = []
+        for M in (16000, 64000):
+            xg = torch.from_numpy(synth.codes(8, (M, L.I))).to(dev)
+            gx = torch.empty((M, 4 * L.H), dtype=torch.int32, device=dev)
+            tg = timed_graph(lambda: q.input_projection(L, xg, gx), 20 if M <= 16000 else 6)
+            gops = 2.0 * M * L.I * 4 * L.H
+            gbytes = M * L.I + 4 * L.H * L.I / 2 + M * 4 * L.H * 4
+            gemm_rows.append({"M": M, "K": L.I, "N": 4 * L.H, "us": tg * 1e6, "TOPs": gops / tg / 1e12,
+                              "frac_int8_mfma": gops / tg / 1e12 / INT8_MFMA_PEAK_TOPS,
+                              "algorithmic_bytes": gbytes, "GBps": gbytes / tg / 1e9})
+            del xg, gx
+        extra["input_projection_gemm"] = dict(gemm_rows[0], rows=gemm_rows)
 
         # ---- the encoder stack alone at the sizes of configuration 1: 32 utterances x 500 frames, and one utterance
         rows = []
@@ -358,6 +415,22 @@ def main():
         extra["encoder_stack"] = {"rows": rows,
                                   "note": "6 bidirectional layers + projection; us_per_layer_step = time / (6 layers x T steps): both "
                                           "directions of a layer advance in the same persistent launch, input projections included"}
+
+        # ---- what one step of the persistent recurrence costs when there is next to nothing to compute: a layer of
+        # 32 cells (two workgroups per direction that wait for each other's hidden codes every step) over 2000 steps,
+        # i.e. the exchange latency (publish -> visible -> polled) that every step of the encoder pays
+        Lt = gmodel.lstm_from_float(synth._lstm(np.random.default_rng(5), 16, 32), gmodel.S_H, dev)
+        Tf = 2000
+        xf = torch.from_numpy(synth.codes(9, (Tf, 16, 16))).to(dev)
+        wsf = torch.empty(q.lstm_layer_workspace(Lt, Tf, 16), dtype=torch.uint8, device=dev)
+        hof = torch.empty((Tf, 16, 32), dtype=torch.int8, device=dev)
+        tf_ = timed(lambda: q.lstm_layer(Lt, xf, h_out=hof, workspace=wsf), 3, warm=1)
+        assert q.layer_error_flag(wsf, wsf.numel()) == 0
+        extra["recurrence_exchange_floor"] = {"us_per_step": tf_ * 1e6 / Tf,
+                                              "note": "H = 32 (2 workgroups exchanging tagged words), B = 16, T = 2000, input projection included "
+                                                      "(0.1 % of the time): the latency floor of a recurrence step; compare "
+                                                      "encoder_stack.us_per_layer_step"}
+        del xf, wsf, hof
 
     # ---------------------------------------------------------------- CPU oracle on a bounded slice
     if not args.no_cpu and args.leg in ("all",):
@@ -389,6 +462,18 @@ def main():
         oracle.set_threads(Bc)
         extra["cpu_oracle_single_thread"] = {"value": t_1 / (10 * FRAME_SEC), "unit": "s/s", "cores": 1,
                                              "sample": f"B=1 x T=10 frames ({t_1:.1f} s)"}
+
+        # Sec. 4.1's reuse of cached hypotheses, counted by the oracle on a slice: network advances a search without
+        # a cache makes, with the current beam as the cache (what the GPU's QRNNT_ALSD_REUSE does), and with every
+        # sequence ever extended kept
+        e_c = np.ascontiguousarray(e_o[:20, :4])
+        rows_c = []
+        for Wc in (1, 4, 16):
+            r1 = oracle.decode_alsd_cached(M_o, e_c, Wc, 10, 1)
+            r2 = oracle.decode_alsd_cached(M_o, e_c, Wc, 10, 2)
+            rows_c.append({"beam": Wc, "advances_without_cache": int(r1[3].sum()), "with_beam_as_cache": int(r1[4].sum()),
+                           "with_unbounded_cache": int(r2[4].sum())})
+        extra["hypothesis_cache_oracle"] = {"rows": rows_c, "sample": "ALSD, 4 utterances x 20 frames, label cap 10, config-4 networks"}
 
     result["extra"] = extra
     if "value" not in result:
