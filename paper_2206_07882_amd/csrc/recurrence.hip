@@ -65,11 +65,16 @@ __device__ __forceinline__ void ll_store(u64 *p, u64 v)
 // word q of lane (grp, col) of K step ks holds cells 64*ks + 16*grp + 4*q .. +3 of
 // utterance 16*ug + col.
 // KW: K steps per wave (H <= 256*KW).
-template <int KW>
+// CT: 16-cell groups per workgroup (1 or 2).  A workgroup of CT = 2 owns 32 cells (8 row tiles, two per wave in the
+// epilogue) and so halves the number of workgroups of a launch: used when CT = 1 would ask for more workgroups than
+// the device has compute units (two workgroups sharing a CU take turns, and every step then waits for the slower
+// ones), e.g. 64 utterances x 640 cells x 2 directions = 320 workgroups on 256 CUs.  H must be a multiple of 16*CT.
+template <int KW, int CT>
 __global__ __launch_bounds__(256) void lstm_rec_kernel(const QrRecGroup g)
 {
-    __shared__ v4i part[4][4][64];     // [wave][row tile][lane] partial sums
-    __shared__ int8_t hc[16][16];      // [utterance][cell] codes of this step
+    constexpr int RT = 4 * CT;             // row tiles (of 4 cells x 4 gates) per workgroup
+    __shared__ v4i part[4][RT][64];    // [wave][row tile][lane] partial sums
+    __shared__ __attribute__((aligned(16))) int8_t hc[16][16 * CT]; // [utterance][cell] codes of this step (read back as 32-bit words)
     __shared__ int s_fail;
     const QrRecArgs &a = g.d[blockIdx.z];
     const int H = a.H, B = a.B, T = a.T;
@@ -80,35 +85,39 @@ __global__ __launch_bounds__(256) void lstm_rec_kernel(const QrRecGroup g)
     const v4i zero = {0, 0, 0, 0};
     const int m = (int)0xF0F0F0F0u;
 
-    // ---- stationary operands: this wave's K steps of the workgroup's 4 row tiles
-    v4i A[4][KW];
+    // ---- stationary operands: this wave's K steps of the workgroup's row tiles
+    v4i A[RT][KW];
 #pragma unroll
-    for (int rt = 0; rt < 4; ++rt)
+    for (int rt = 0; rt < RT; ++rt)
 #pragma unroll
         for (int k = 0; k < KW; ++k) {
             const int ks = wave + 4 * k;
             A[rt][k] = zero;
             if (ks < nks) {
                 if (a.w8) {   // 8-bit layer: the operand as stored, two blocks per 128-column chunk
-                    A[rt][k] = a.whh[(((size_t)(cg * 4 + rt) * a.nkc_h + (ks >> 1)) * 2 + (ks & 1)) * 64 + lane];
+                    A[rt][k] = a.whh[(((size_t)(cg * RT + rt) * a.nkc_h + (ks >> 1)) * 2 + (ks & 1)) * 64 + lane];
                 } else {
-                    const v4i p = a.whh[((size_t)(cg * 4 + rt) * a.nkc_h + (ks >> 1)) * 64 + lane];
+                    const v4i p = a.whh[((size_t)(cg * RT + rt) * a.nkc_h + (ks >> 1)) * 64 + lane];
                     A[rt][k] = (ks & 1) ? (p & m) : ((p << 4) & m);
                 }
             }
         }
-    // ---- the cell this lane finishes: row tile = wave, cell j, utterance n
-    const int j = qr_gates_cell(cg * 4 + wave, grp);   // = 16*cg + 4*grp + wave
+    // ---- the cells this lane finishes: row tiles 4*c + wave (c < CT), cell j[c], utterance n
     const int n = ug * 16 + col;
     const int nn = n < B ? n : B - 1;
-    float sx[4], sh[4], bb[4];
+    int j[CT];
+    float sx[CT][4], sh[CT][4], bb[CT][4], c[CT];
 #pragma unroll
-    for (int gt = 0; gt < 4; ++gt) {
-        sx[gt] = a.x_scale * a.s_wih[gt * H + j];
-        sh[gt] = a.h_scale * a.s_whh[gt * H + j];
-        bb[gt] = a.bias[gt * H + j];
+    for (int ct = 0; ct < CT; ++ct) {
+        j[ct] = qr_gates_cell(cg * RT + 4 * ct + wave, grp);   // = 16*(CT*cg + ct) + 4*grp + wave
+#pragma unroll
+        for (int gt = 0; gt < 4; ++gt) {
+            sx[ct][gt] = a.x_scale * a.s_wih[gt * H + j[ct]];
+            sh[ct][gt] = a.h_scale * a.s_whh[gt * H + j[ct]];
+            bb[ct][gt] = a.bias[gt * H + j[ct]];
+        }
+        c[ct] = a.c0 ? a.c0[(int64_t)nn * H + j[ct]] : 0.0f;
     }
-    float c = a.c0 ? a.c0[(int64_t)nn * H + j] : 0.0f;
     if (tid == 0) s_fail = 0;
     __syncthreads();
 
@@ -116,8 +125,13 @@ __global__ __launch_bounds__(256) void lstm_rec_kernel(const QrRecGroup g)
     const size_t xparity = (size_t)((B + 15) >> 4) * xgroup;
     for (int s = 0; s < T; ++s) {
         const int t = a.reverse ? T - 1 - s : s;
-        const v4i gxv = *(const v4i *)(a.gx + ((int64_t)t * B + nn) * 4 * H + (cg * 4 + wave) * 16 + 4 * grp);   // independent of h: first
-        v4i acc[4] = {zero, zero, zero, zero};
+        v4i gxv[CT];   // independent of h: first
+#pragma unroll
+        for (int ct = 0; ct < CT; ++ct)
+            gxv[ct] = *(const v4i *)(a.gx + ((int64_t)t * B + nn) * 4 * H + (cg * RT + 4 * ct + wave) * 16 + 4 * grp);
+        v4i acc[RT];
+#pragma unroll
+        for (int rt = 0; rt < RT; ++rt) acc[rt] = zero;
         bool failed = false;
         if (s > 0 || a.h0) {
             v4i bf[KW];
@@ -161,32 +175,36 @@ __global__ __launch_bounds__(256) void lstm_rec_kernel(const QrRecGroup g)
 #pragma unroll
             for (int k = 0; k < KW; ++k)
 #pragma unroll
-                for (int rt = 0; rt < 4; ++rt) acc[rt] = qr_mfma(A[rt][k], bf[k], acc[rt]);
+                for (int rt = 0; rt < RT; ++rt) acc[rt] = qr_mfma(A[rt][k], bf[k], acc[rt]);
         }
         if (failed && lane == 0) {
             atomicExch(a.err, 1);
             s_fail = 1;
         }
 #pragma unroll
-        for (int rt = 0; rt < 4; ++rt) part[wave][rt][lane] = acc[rt];
+        for (int rt = 0; rt < RT; ++rt) part[wave][rt][lane] = acc[rt];
         __syncthreads();
         const int fail_now = s_fail;   // written only before this barrier, read only after it: uniform
-        const v4i asum = part[0][wave][lane] + part[1][wave][lane] + part[2][wave][lane] + part[3][wave][lane];
-        const v4i ah = a.w8 ? asum : (asum >> 4);   // 4-bit operands carry a factor 16
-        float p[4];
 #pragma unroll
-        for (int gt = 0; gt < 4; ++gt) p[gt] = sx[gt] * (float)gxv[gt] + (sh[gt] * (float)ah[gt] + bb[gt]);
-        const float gi = qr_sigmoid(p[0]), gf = qr_sigmoid(p[1]), gg = qr_tanh(p[2]), go = qr_sigmoid(p[3]);
-        c = gf * c + gi * gg;
-        const float h = go * qr_tanh(c);
-        hc[col][grp * 4 + wave] = (int8_t)qr_quant(h, a.h_inv, a.w8 ? 8 : 4);
-        if (a.dbg_c_all && n < B) a.dbg_c_all[((int64_t)t * B + n) * H + j] = c;
+        for (int ct = 0; ct < CT; ++ct) {
+            const int rt = 4 * ct + wave;
+            const v4i asum = part[0][rt][lane] + part[1][rt][lane] + part[2][rt][lane] + part[3][rt][lane];
+            const v4i ah = a.w8 ? asum : (asum >> 4);   // 4-bit operands carry a factor 16
+            float p[4];
+#pragma unroll
+            for (int gt = 0; gt < 4; ++gt) p[gt] = sx[ct][gt] * (float)gxv[ct][gt] + (sh[ct][gt] * (float)ah[gt] + bb[ct][gt]);
+            const float gi = qr_sigmoid(p[0]), gf = qr_sigmoid(p[1]), gg = qr_tanh(p[2]), go = qr_sigmoid(p[3]);
+            c[ct] = gf * c[ct] + gi * gg;
+            const float h = go * qr_tanh(c[ct]);
+            hc[col][16 * ct + grp * 4 + wave] = (int8_t)qr_quant(h, a.h_inv, a.w8 ? 8 : 4);
+            if (a.dbg_c_all && n < B) a.dbg_c_all[((int64_t)t * B + n) * H + j[ct]] = c[ct];
+        }
         __syncthreads();
-        // publish: 16 utterances x 4 quads, one 8-byte word each, tagged s+1
-        if (tid < 64) {
-            const int u = tid & 15, rt = tid >> 4;
-            const int Q = cg * 4 + rt;
-            const unsigned data = *(const unsigned *)&hc[u][rt * 4];
+        // publish: 16 utterances x 4*CT quads, one 8-byte word each, tagged s+1
+        if (tid < 64 * CT) {
+            const int u = tid & 15, q = tid >> 4;       // quad q of the workgroup's 4*CT: cells 4*q .. 4*q+3 of its 16*CT
+            const int Q = cg * RT + q;                  // quad of the layer
+            const unsigned data = *(const unsigned *)&hc[u][q * 4];
             u64 *dst = a.xbuf + (size_t)(s & 1) * xparity + (size_t)ug * xgroup +
                        ((size_t)(Q >> 4) * 64 + ((Q & 15) >> 2) * 16 + u) * 4 + (Q & 3);
             ll_store(dst, ((u64)(unsigned)(s + 1) << 32) | data);
@@ -198,29 +216,48 @@ __global__ __launch_bounds__(256) void lstm_rec_kernel(const QrRecGroup g)
         }
         if (fail_now) break;
     }
-    if (a.c_last && n < B) a.c_last[(int64_t)n * H + j] = c;
+#pragma unroll
+    for (int ct = 0; ct < CT; ++ct)
+        if (a.c_last && n < B) a.c_last[(int64_t)n * H + j[ct]] = c[ct];
 }
 
+template <int KW, int CT>
+bool launch_rec_ct(const QrRecGroup &g, bool only_if_it_fits_the_cus, hipStream_t st)
+{
+    const int H = g.d[0].H, B = g.d[0].B;
+    if (H % (16 * CT) != 0) return false;
+    dim3 grid(H / (16 * CT), (B + 15) / 16, g.n);
+    // every workgroup spins on its peers: all of them must fit on the device at once
+    static std::atomic<long long> resident_of[QR_MAX_DEVICES];   // workgroups the device holds at once; 0: not asked yet
+    static std::atomic<int> n_cu_of[QR_MAX_DEVICES];
+    const int dev = qr_current_device();
+    long long resident = resident_of[dev].load(std::memory_order_relaxed);
+    int n_cu = n_cu_of[dev].load(std::memory_order_relaxed);
+    if (resident == 0) {
+        int per_cu = 0;
+        if (hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return false;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, lstm_rec_kernel<KW, CT>, 256, 0) != hipSuccess) return false;
+        resident = (long long)per_cu * n_cu;
+        if (resident <= 0 || n_cu <= 0) return false;
+        n_cu_of[dev].store(n_cu, std::memory_order_relaxed);
+        resident_of[dev].store(resident, std::memory_order_relaxed);
+    }
+    const long long wgs = (long long)grid.x * grid.y * grid.z;
+    if (wgs > resident) return false;
+    if (only_if_it_fits_the_cus && wgs > n_cu) return false;
+    lstm_rec_kernel<KW, CT><<<grid, 256, 0, st>>>(g);
+    return true;
+}
+
+// One workgroup per compute unit if either form allows it (16 cells each, else 32 cells each); otherwise whichever
+// form is resident at all, fewest workgroups sharing a CU first.
 template <int KW>
 bool launch_rec_t(const QrRecGroup &g, hipStream_t st)
 {
-    const int H = g.d[0].H, B = g.d[0].B;
-    dim3 grid(H / 16, (B + 15) / 16, g.n);
-    // every workgroup spins on its peers: all of them must fit on the device at once
-    static std::atomic<long long> resident_of[QR_MAX_DEVICES];   // workgroups the device holds at once; 0: not asked yet
-    const int dev = qr_current_device();
-    long long resident = resident_of[dev].load(std::memory_order_relaxed);
-    if (resident == 0) {
-        int n_cu = 0, per_cu = 0;
-        if (hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return false;
-        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, lstm_rec_kernel<KW>, 256, 0) != hipSuccess) return false;
-        resident = (long long)per_cu * n_cu;
-        if (resident <= 0) return false;
-        resident_of[dev].store(resident, std::memory_order_relaxed);
-    }
-    if ((long long)grid.x * grid.y * grid.z > resident) return false;
-    lstm_rec_kernel<KW><<<grid, 256, 0, st>>>(g);
-    return true;
+    if (launch_rec_ct<KW, 1>(g, true, st)) return true;
+    if (launch_rec_ct<KW, 2>(g, true, st)) return true;
+    if (launch_rec_ct<KW, 2>(g, false, st)) return true;
+    return launch_rec_ct<KW, 1>(g, false, st);
 }
 
 }  // namespace

@@ -145,7 +145,7 @@ def test_input_projection_int8_exact(gpu_lib, I, H, M):
 
 
 @pytest.mark.parametrize("T,B,I,H,reverse", [(20, 2, 32, 64, False), (7, 3, 32, 64, True), (12, 32, 352, 640, False),
-                                             (9, 17, 352, 640, True)])
+                                             (9, 17, 352, 640, True), (5, 120, 64, 640, False)])
 def test_lstm_layer_int8_parity(gpu_lib, T, B, I, H, reverse):
     """The 8-bit layer (8-bit weights, inputs and hidden state): GEMM bit-exact, then every step against one
     oracle step fed the GPU's own previous state."""

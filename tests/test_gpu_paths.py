@@ -38,12 +38,15 @@ def _teacher_forced_layer(L, x, hg, cg, reverse, h0, c0, what):
 
 @pytest.mark.parametrize("T,B,I,H,reverse,state", [(6, 3, 64, 1040, False, False), (5, 40, 64, 1040, True, True),
                                                    (4, 2, 32, 2048, False, True), (9, 5, 32, 64, False, True),
-                                                   (7, 33, 240, 640, True, True), (30, 16, 16, 32, False, False)])
+                                                   (7, 33, 240, 640, True, True), (30, 16, 16, 32, False, False),
+                                                   (5, 112, 64, 640, True, True), (4, 130, 32, 1024, False, True)])
 def test_lstm_layer_step_by_step_form_and_initial_state(gpu_lib, T, B, I, H, reverse, state):
     """H = 1040 and 2048 exceed what the persistent recurrence holds (H <= 1024), so the layer runs as one fused
     launch per time step (few utterances: the weight-streaming step kernel; 40: the tiled one, with a ragged
     row block since 1040 is not a multiple of 32); H = 64 and 640 take the persistent kernel, and so does H = 32, its
-    smallest exchange (two workgroups per direction: the shape the benchmark times as the latency floor of a step).  Both forms with a
+    smallest exchange (two workgroups per direction: the shape the benchmark times as the latency floor of a step).
+    112 and 130 utterances make more workgroups of 16 cells than the device has compute units, so the persistent kernel
+    runs in its form with 32 cells per workgroup (two row-tile groups per wave in the cell update).  Both forms with a
     given initial state (hidden codes and cell state), every step against one oracle step from the GPU's own
     previous state, final state returned."""
     q = gpu_lib
