@@ -37,6 +37,10 @@ __global__ __launch_bounds__(256) void mfma_rate_kernel(int iters, float *sink)
             if (FORM == 3 && i < 4) cf32[i] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a8, b8, cf32[i], 0, 0, 0, 0x7F7F7F7F, 0, 0x7F7F7F7F);
             if (FORM == 4) cf[i] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(a8, b8, cf[i], 2, 2, 0, 0x7F7F7F7F, 0, 0x7F7F7F7F);   // fp6 E2M3
             if (FORM == 5) cf[i] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(a8, b8, cf[i], 4, 4, 0, 0x7F7F7F7F, 0, 0x7F7F7F7F);   // fp4 E2M1
+            if (FORM == 6) {   // the contraction kernels' pattern: the two K halves of a chunk into one accumulator, back to back
+                ci[i] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a4, b4, ci[i], 0, 0, 0);
+                ci[i] = __builtin_amdgcn_mfma_i32_16x16x64_i8(b4, a4, ci[i], 0, 0, 0);
+            }
         }
     }
     float s = 0.0f;
@@ -64,6 +68,7 @@ const Form forms[] = {
     {"int8 16x16x64", 16.0 * 16 * 64, 8, launch_form<0>},   {"int8 32x32x32", 32.0 * 32 * 32, 4, launch_form<1>},
     {"fp8-E4M3 16x16x128", 16.0 * 16 * 128, 8, launch_form<2>}, {"fp8-E4M3 32x32x64", 32.0 * 32 * 64, 4, launch_form<3>},
     {"fp6-E2M3 16x16x128", 16.0 * 16 * 128, 8, launch_form<4>}, {"fp4-E2M1 16x16x128", 16.0 * 16 * 128, 8, launch_form<5>},
+    {"int8 16x16x64, dependent pairs", 16.0 * 16 * 64, 16, launch_form<6>},
 };
 constexpr int N_FORMS = (int)(sizeof(forms) / sizeof(forms[0]));
 
