@@ -319,11 +319,12 @@ def main():
         extra["mfma_forms"] = {"rows": [{"form": n, "TOPs": t, "frac_of_published_int8_peak": t / INT8_MFMA_PEAK_TOPS} for n, t in rates],
                                "int8_peak_at_measured_clock_TOPs": best_i8,
                                "implied_clock_GHz": best_i8 * 1e12 / (2048.0 * 4 * 256) / 1e9,
-                               "note": "two workgroups per CU issuing independent accumulator chains, no memory traffic. The 32x32x32 int8 "
-                                       "form runs at the full rate (2048 op/clk/SIMD, which gives the clock above); the 16x16x64 int8 form, "
-                                       "the one the kernels' 16-row gate tiles use, at half of it; the fp8/fp6/fp4 16x16x128 forms reach the "
-                                       "full rate at 16 rows but need both operands as 8-bit floats (a table lookup per nibble), and no "
-                                       "float form beats int8 32x32x32 by more than 10 %: the faster unit for this path is the 32-row int8 form"}
+                               "note": "two workgroups per CU, 8 accumulator chains per wave (4 of the 32-row forms), two instructions per "
+                                       "chain and loop iteration, no memory traffic, loop body checked to hold nothing but the matrix "
+                                       "instructions. The best int8 rate gives the clock (2048 op/clk/SIMD). The fp6 forms hold the codes "
+                                       "exactly (E2M3: -7.5..7.5 in steps of 0.5 above 4; E3M2: every integer up to 8), fp8-E4M3 too; "
+                                       "fp4-E2M1 does not (no 5 and no 7). Whether a faster unit helps the kernels is a question of "
+                                       "what binds them: see roofline.launches and the profiles' matrix-unit busy counters"}
         result["roofline"]["peak_at_measured_clock"] = best_i8
         result["roofline"]["frac_of_peak_at_measured_clock"] = ach / best_i8
 

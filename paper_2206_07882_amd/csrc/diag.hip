@@ -1,8 +1,8 @@
 // Diagnostics: issue rates of the matrix instructions that could carry the W4A4 contraction on gfx950, measured
-// in registers (no memory traffic in the loop).  Codes in [-8, 7] are exact in fp8-E4M3 and in int8, and sums of
-// up to 2048 products stay below 2^24, so every form listed here would give the same integers (Sec. 3.1 / 3.2:
-// the method only fixes the integer grid, not the unit that multiplies); which one to build on is a question of
-// rate and of operand layout.  bench.py reports these rates next to the kernels' achieved ones.
+// in registers (no memory traffic in the loop).  Codes in [-8, 7] are exact in int8, fp8-E4M3 and fp6-E3M2 (and
+// [-7, 7] in fp6-E2M3), and sums of up to 2048 products stay below 2^24, so these forms would give the same
+// integers (Sec. 3.1 / 3.2: the method only fixes the integer grid, not the unit that multiplies); fp4-E2M1 lacks
+// 5 and 7 and is listed for its rate only.  Which form to build on is a question of rate and of operand layout.  bench.py reports these rates next to the kernels' achieved ones.
 #include "qrnnt_common.h"
 
 namespace {
@@ -11,13 +11,20 @@ typedef int v8i __attribute__((ext_vector_type(8)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 typedef float v16f __attribute__((ext_vector_type(16)));
 
-// 8 independent accumulator chains of the 16 x 16 forms (4 of the 32 x 32 forms) per wave, back to back.
+// 8 accumulator chains of the 16 x 16 forms (4 of the 32 x 32 forms) per wave.  Every chain gets two instructions
+// per loop iteration (operands swapped for the second), the pattern of the contraction kernels, whose 128-column
+// chunk is two K steps into one accumulator; the compiler keeps such a loop free of register moves, so the loop
+// body is the matrix instructions and the branch (a body with one instruction per chain and iteration made it
+// shuffle the accumulators between the instructions, which halved the measured rate of the 4-pass forms).
 template <int FORM>
 __global__ __launch_bounds__(256) void mfma_rate_kernel(int iters, float *sink)
 {
     const int lane = threadIdx.x;
     const v4i a4 = {lane, lane + 1, 3, 4}, b4 = {lane * 3, 7, 1, 2};
     const v8i a8 = {lane, lane + 1, 3, 4, 5, 6, 0, 0}, b8 = {lane * 3, 7, 1, 2, 9, 8, 0, 0};
+    constexpr bool WIDE = FORM == 1 || FORM == 3;        // 32 x 32 forms: 16 accumulator registers per chain
+    constexpr bool INT = FORM <= 1;
+    constexpr int fmt = FORM == 4 ? 2 : FORM == 5 ? 3 : FORM == 6 ? 4 : 0;   // fp8-E4M3 0, fp6-E2M3 2, fp6-E3M2 3, fp4-E2M1 4
     v4i ci[8];
     v4f cf[8];
     v16i ci32[4];
@@ -30,16 +37,22 @@ __global__ __launch_bounds__(256) void mfma_rate_kernel(int iters, float *sink)
         for (int j = 0; j < 16; ++j) { ci32[i][j] = 0; cf32[i][j] = 0.0f; }
     for (int it = 0; it < iters; ++it) {
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            if (FORM == 0) ci[i] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a4, b4, ci[i], 0, 0, 0);
-            if (FORM == 1 && i < 4) ci32[i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a4, b4, ci32[i], 0, 0, 0);
-            if (FORM == 2) cf[i] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(a8, b8, cf[i], 0, 0, 0, 0x7F7F7F7F, 0, 0x7F7F7F7F);   // fp8 E4M3
-            if (FORM == 3 && i < 4) cf32[i] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a8, b8, cf32[i], 0, 0, 0, 0x7F7F7F7F, 0, 0x7F7F7F7F);
-            if (FORM == 4) cf[i] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(a8, b8, cf[i], 2, 2, 0, 0x7F7F7F7F, 0, 0x7F7F7F7F);   // fp6 E2M3
-            if (FORM == 5) cf[i] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(a8, b8, cf[i], 4, 4, 0, 0x7F7F7F7F, 0, 0x7F7F7F7F);   // fp4 E2M1
-            if (FORM == 6) {   // the contraction kernels' pattern: the two K halves of a chunk into one accumulator, back to back
+        for (int i = 0; i < (WIDE ? 4 : 8); ++i) {
+            if (INT && !WIDE) {
                 ci[i] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a4, b4, ci[i], 0, 0, 0);
                 ci[i] = __builtin_amdgcn_mfma_i32_16x16x64_i8(b4, a4, ci[i], 0, 0, 0);
+            }
+            if (INT && WIDE) {
+                ci32[i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a4, b4, ci32[i], 0, 0, 0);
+                ci32[i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(b4, a4, ci32[i], 0, 0, 0);
+            }
+            if (!INT && !WIDE) {
+                cf[i] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(a8, b8, cf[i], fmt, fmt, 0, 0x7F7F7F7F, 0, 0x7F7F7F7F);
+                cf[i] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(b8, a8, cf[i], fmt, fmt, 0, 0x7F7F7F7F, 0, 0x7F7F7F7F);
+            }
+            if (!INT && WIDE) {
+                cf32[i] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a8, b8, cf32[i], fmt, fmt, 0, 0x7F7F7F7F, 0, 0x7F7F7F7F);
+                cf32[i] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(b8, a8, cf32[i], fmt, fmt, 0, 0x7F7F7F7F, 0, 0x7F7F7F7F);
             }
         }
     }
@@ -65,10 +78,10 @@ void launch_form(int blocks, int iters, float *sink, hipStream_t st)
 }
 
 const Form forms[] = {
-    {"int8 16x16x64", 16.0 * 16 * 64, 8, launch_form<0>},   {"int8 32x32x32", 32.0 * 32 * 32, 4, launch_form<1>},
-    {"fp8-E4M3 16x16x128", 16.0 * 16 * 128, 8, launch_form<2>}, {"fp8-E4M3 32x32x64", 32.0 * 32 * 64, 4, launch_form<3>},
-    {"fp6-E2M3 16x16x128", 16.0 * 16 * 128, 8, launch_form<4>}, {"fp4-E2M1 16x16x128", 16.0 * 16 * 128, 8, launch_form<5>},
-    {"int8 16x16x64, dependent pairs", 16.0 * 16 * 64, 16, launch_form<6>},
+    {"int8 16x16x64", 16.0 * 16 * 64, 16, launch_form<0>},      {"int8 32x32x32", 32.0 * 32 * 32, 8, launch_form<1>},
+    {"fp8-E4M3 16x16x128", 16.0 * 16 * 128, 16, launch_form<2>}, {"fp8-E4M3 32x32x64", 32.0 * 32 * 64, 8, launch_form<3>},
+    {"fp6-E2M3 16x16x128", 16.0 * 16 * 128, 16, launch_form<4>}, {"fp6-E3M2 16x16x128", 16.0 * 16 * 128, 16, launch_form<5>},
+    {"fp4-E2M1 16x16x128", 16.0 * 16 * 128, 16, launch_form<6>},
 };
 constexpr int N_FORMS = (int)(sizeof(forms) / sizeof(forms[0]));
 

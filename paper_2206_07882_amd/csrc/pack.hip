@@ -363,6 +363,7 @@ extern "C" qrnnt_status qrnnt_quantize_act(const float *x, int64_t n, float inv_
     QR_REQUIRE(inv_scale > 0.0f, QRNNT_ERR_RANGE);
     QR_REQUIRE(qr_aligned(x, 16) && qr_aligned(q, 4), QRNNT_ERR_ALIGN);
     const int64_t n4 = (n + 3) / 4;
+    QR_REQUIRE(n4 <= (int64_t)INT32_MAX * 256, QRNNT_ERR_SHAPE);   // one thread per 4 elements, the grid's x limit
     quantize_kernel<<<(unsigned)((n4 + 255) / 256), 256, 0, (hipStream_t)stream>>>(x, n, inv_scale, q);
     return qr_launch_status();
 }
@@ -393,6 +394,7 @@ extern "C" qrnnt_status qrnnt_quantize_act_rows(const float *x, int64_t rows, in
     QR_REQUIRE(rows > 0 && cols > 0 && ld_out >= cols && ld_out % 16 == 0, QRNNT_ERR_SHAPE);
     QR_REQUIRE(inv_scale > 0.0f && (bits == 4 || bits == 8), QRNNT_ERR_RANGE);
     QR_REQUIRE(qr_aligned(x, 4) && qr_aligned(q, 16), QRNNT_ERR_ALIGN);
+    QR_REQUIRE(rows <= (int64_t)INT32_MAX * 256 / (ld_out >> 2), QRNNT_ERR_SHAPE);   // the grid's x limit
     const int64_t n = rows * (ld_out >> 2);
     quantize_rows_kernel<<<(unsigned)((n + 255) / 256), 256, 0, (hipStream_t)stream>>>(x, rows, cols, ld_out, inv_scale, bits, q);
     return qr_launch_status();

@@ -140,6 +140,43 @@ def test_validation_of_the_8bit_and_search_entry_points():
     assert lib.qrnnt_decode_workspace(None, 10, 2, 4, 2) == 0
 
 
+def test_validation_of_the_row_quantizer_static_layer_and_diagnostics():
+    lib = qrnnt.load()
+    P = C.c_void_p
+    # activation pitch: the next multiple of 16 bytes; non-positive widths have none
+    lib.qrnnt_act_pitch.restype = C.c_int32
+    assert [lib.qrnnt_act_pitch(c) for c in (1, 10, 15, 16, 17, 240, 340, 1280)] == [16, 16, 16, 16, 32, 240, 352, 1280]
+    assert lib.qrnnt_act_pitch(0) == 0 and lib.qrnnt_act_pitch(-3) == 0
+    # row quantizer: pointers, shape (pitch >= width and a multiple of 16), scale and width, alignment
+    qr = lambda x=P(0x1000), rows=4, cols=10, inv=1.0, bits=4, q=P(0x2000), ld=16: lib.qrnnt_quantize_act_rows(
+        x, C.c_int64(rows), cols, C.c_float(inv), bits, q, ld, None)
+    assert qr(x=None) == 1 and qr(q=None) == 1
+    assert qr(rows=0) == 2 and qr(cols=0) == 2 and qr(cols=20) == 2 and qr(ld=24) == 2
+    assert qr(inv=0.0) == 4 and qr(bits=5) == 4
+    assert qr(x=P(0x1002)) == 3 and qr(q=P(0x2004)) == 3
+    # the layer call on the library's own scratch array: same checks as qrnnt_lstm_layer, then the size limit
+    good = _lstm(w_ih=_qmat(rows=64, cols=64), w_hh=_qmat(rows=64, cols=16))
+    ls = lambda T=10, B=2, x=P(0x1000), ld=16: lib.qrnnt_lstm_layer_static(C.byref(good), x, T, B, 0, None, None,
+                                                                           P(0x2000), ld, 0, None, None, None)
+    assert ls(x=None) == 1 and ls(ld=8) == 2 and ls(T=0) == 2
+    too_long = (qrnnt.STATIC_WORKSPACE_BYTES // (2 * 64 * 4)) + 1        # the int32 input projection alone exceeds the array
+    assert lib.qrnnt_lstm_layer_workspace(C.byref(good), too_long, 2) > qrnnt.STATIC_WORKSPACE_BYTES
+    assert ls(T=too_long) == 5
+    # alignment-length synchronous search: unknown flag bits are refused before anything else is looked at
+    assert lib.qrnnt_decode_alsd_ex(None, P(0x1000), 10, 2, 4, 5, 15, C.c_uint32(2), None, P(0x2000), P(0x3000), P(0x4000),
+                                    P(0x10000), C.c_size_t(1 << 20), None) in (1, 4)
+    # matrix-instruction diagnostics: names for every form, argument checks
+    lib.qrnnt_diag_mfma_form_name.restype = C.c_char_p
+    n = lib.qrnnt_diag_mfma_forms()
+    names = [lib.qrnnt_diag_mfma_form_name(i).decode() for i in range(n)]
+    assert n >= 6 and len(set(names)) == n and names[0].startswith("int8") and lib.qrnnt_diag_mfma_form_name(n) == b""
+    tops = C.c_double(0.0)
+    dr = lambda form=0, iters=100, sink=P(0x1000), out=C.byref(tops): lib.qrnnt_diag_mfma_rate(form, iters, sink, out, None)
+    assert dr(sink=None) == 1 and dr(out=None) == 1
+    assert dr(form=n) == 4 and dr(form=-1) == 4 and dr(iters=0) == 4 and dr(iters=(1 << 22) + 1) == 4
+    assert dr(sink=P(0x1002)) == 3
+
+
 def test_product_path_does_not_reference_the_oracle():
     """The GPU package must never import or call the test oracle."""
     pkg = os.path.join(ROOT, "paper_2206_07882_amd")
