@@ -323,8 +323,11 @@ def main():
                                        "chain and loop iteration, no memory traffic, loop body checked to hold nothing but the matrix "
                                        "instructions. The best int8 rate gives the clock (2048 op/clk/SIMD). The fp6 forms hold the codes "
                                        "exactly (E2M3: -7.5..7.5 in steps of 0.5 above 4; E3M2: every integer up to 8), fp8-E4M3 too; "
-                                       "fp4-E2M1 does not (no 5 and no 7). Whether a faster unit helps the kernels is a question of "
-                                       "what binds them: see roofline.launches and the profiles' matrix-unit busy counters"}
+                                       "fp4-E2M1 does not (no 5 and no 7). The 'chunk loop' rows run the same instructions in a loop "
+                                       "shaped like the contraction kernels' 128-column chunk without its global loads (a barrier, the "
+                                       "wave's operand reads from LDS for a 64 x 64 tile, the nibble unpack where the form needs one, "
+                                       "three workgroups per CU): what the matrix unit and LDS allow together; the kernels' own "
+                                       "rates are in roofline.launches"}
         result["roofline"]["peak_at_measured_clock"] = best_i8
         result["roofline"]["frac_of_peak_at_measured_clock"] = ach / best_i8
 

@@ -459,8 +459,10 @@ qrnnt_status qrnnt_decode_alsd_ex(const qrnnt_model *m, const float *enc_proj, i
  * exactly or nearly so (codes in [-8, 7] are exact in int8, fp8-E4M3 and fp6-E3M2, [-7, 7] in fp6-E2M3; fp4-E2M1
  * is listed for its rate only; partial sums stay below 2^24; Sec. 3.1 fixes the integer grid only).
  * form in [0, qrnnt_diag_mfma_forms()); qrnnt_diag_mfma_form_name gives its name.
- * Runs `iters` loop iterations (two instructions on each of 8 accumulator chains per wave, 4 chains for the
- * 32-row forms) on two workgroups per compute unit and
+ * Runs `iters` loop iterations on two workgroups per compute unit (two instructions on each of 8 accumulator
+ * chains per wave, 4 chains for the 32-row forms; registers only), or, for the forms named "chunk loop ...", on
+ * three workgroups per compute unit a loop shaped like the contraction kernels' 128-column chunk without its
+ * global loads (barrier, LDS operand reads of a wave's 64 x 64 tile, nibble unpack, matrix instructions), and
  * writes the rate in TOP/s (2 ops per multiply-accumulate) to *tops_out [host].  sink [device]: one float the
  * kernel may write.  Unlike every other call this one waits for its own work (it times it with events). */
 int32_t qrnnt_diag_mfma_forms(void);
