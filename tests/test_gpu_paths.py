@@ -156,3 +156,17 @@ def test_encoder_reports_the_recurrence_flag(gpu_lib):
     enc._flags[2] = 1                         # what a timed-out wait in layer 1, forward direction, would leave
     with pytest.raises(RuntimeError):
         enc.check()
+
+
+def test_matrix_instruction_diagnostics(gpu_lib):
+    """qrnnt_diag_mfma_rate runs every form and reports plausible rates: positive, below twice the published fp6 / fp4
+    peak, the int8 forms within reach of their 5.0 POP/s peak, and a chunk-shaped loop (LDS operand reads, barrier)
+    never faster than the same instruction issued from registers alone."""
+    rates = dict(gpu_lib.diag_mfma_rates(2000, DEV))
+    assert len(rates) >= 9 and all(0.0 < t < 2.5e4 for t in rates.values()), rates
+    for name in ("int8 16x16x64", "int8 32x32x32"):
+        assert 2000.0 < rates[name] < 5500.0, rates
+    for name, t in rates.items():
+        if name.startswith("chunk loop"):
+            base = name.split(": ", 1)[1]
+            assert t <= 1.05 * rates[base], (name, t, rates[base])
